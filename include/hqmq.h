@@ -1,0 +1,157 @@
+/*
+ * hqmq.h - C ABI of the MI355X (gfx950) HQMQ KV-cache encode / decode library.
+ *
+ * HQMQ (Hurwitz Quaternion Multiplicative Quantization) splits every K or V head vector
+ * into 4-element chunks read as quaternions x, stores the norm r = |x| with a uniform
+ * b_r-bit quantiser against a per-token scale, and the direction u = x / r as the index of
+ * the nearest product q_p * q_s, q_p in the 24-element Hurwitz group 2T, q_s in a seeded
+ * per-(layer, head, role) codebook of S unit quaternions (paper Sec. 3, Eq. 1, Alg. 1).
+ * Chunks whose norm exceeds C times the batch median norm of their (layer, head, role) are
+ * kept verbatim in fp16 next to a one-bit flag (Sec. 3 "Median-multiplier outlier
+ * extraction").
+ *
+ * Conventions common to every entry point
+ *   - extern "C", plain pointers and sizes.  "HOST" / "DEVICE" says where a pointer lives.
+ *   - The caller owns every buffer.  The library allocates nothing, keeps no global state
+ *     besides the last HIP error code, and only enqueues work on the given HIP stream
+ *     (hipStream_t passed as void*; NULL = the default stream).  Calls return as soon as the
+ *     work is enqueued; results are valid once the stream has been synchronised.
+ *   - Return value: HQMQ_OK or a negative HQMQ_ERR_* code.  Nothing is enqueued when an
+ *     argument error is returned.  Data-dependent conditions are reported through the
+ *     device-side status word (see hqmq_encoded.status).
+ *   - One call handles one (layer, role) tensor X, fp16 [B, H, T, D] addressed through
+ *     element strides (D contiguous): "the current batch" of Alg. 1.  A row is one (b, h, t)
+ *     vector, linear row index R = (b*H + h)*T + t; chunk c of a row is elements 4c..4c+3,
+ *     element 0 being the real part; linear chunk index = R*(D/4) + c.
+ *   - This build supports D == 128 (32 chunks per row: one flag word and exactly w code
+ *     words per row).
+ */
+#ifndef HQMQ_H
+#define HQMQ_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HQMQ_OK 0
+#define HQMQ_ERR_INVALID_ARG (-1)      /* null pointer, non-positive size, misaligned pointer or stride */
+#define HQMQ_ERR_UNSUPPORTED (-2)      /* D != 128, S outside 1..512, b_r outside 1..8, C not a positive finite number */
+#define HQMQ_ERR_BUFFER_TOO_SMALL (-3) /* workspace smaller than hqmq_sizes() asks for */
+#define HQMQ_ERR_HIP (-4)              /* a HIP call failed; see hqmq_last_hip_error() */
+
+/* hqmq_params.flags */
+#define HQMQ_FLAG_NO_OUTLIERS 1u /* skip the median and the extraction: no chunk is flagged */
+
+/* bits of the device-side status word */
+#define HQMQ_STATUS_OUTLIER_OVERFLOW 1u /* more outliers than outlier_capacity: payload truncated */
+
+typedef struct hqmq_params {
+    int32_t B, H, T, D;                   /* X is fp16 [B, H, T, D], D contiguous                  */
+    int64_t stride_b, stride_h, stride_t; /* element strides of b, h, t; multiples of 4           */
+    int32_t S;                            /* secondary codebook size per (layer, head, role)       */
+    int32_t b_r;                          /* radius bits (paper: 3, 4 or 6)                        */
+    float C;                              /* outlier multiplier (paper: 3)                         */
+    uint32_t flags;                       /* HQMQ_FLAG_*                                           */
+} hqmq_params;
+
+/* Buffer sizes for a given hqmq_params, in bytes unless said otherwise. */
+typedef struct hqmq_size_info {
+    uint64_t n_rows;               /* B*H*T                                                        */
+    uint32_t index_bits;           /* w_idx = ceil(log2(24 S)) (Sec. 3: index width)               */
+    uint32_t code_bits;            /* w = w_idx + b_r: bits per chunk, and 32-bit words per row    */
+    uint64_t code_bytes;           /* n_rows * w * 4                                               */
+    uint64_t sigma_bytes;          /* n_rows * 2                                                   */
+    uint64_t flag_bytes;           /* n_rows * 4                                                   */
+    uint64_t row_off_bytes;        /* (n_rows + 1) * 4                                             */
+    uint64_t n_outliers_bytes;     /* (H + 1) * 4                                                  */
+    uint64_t status_bytes;         /* 4                                                            */
+    uint64_t outlier_capacity_max; /* chunks: no input can flag more than this                     */
+    uint64_t outlier_bytes_max;    /* outlier_capacity_max * 8                                     */
+    uint64_t workspace_bytes;      /* scratch hqmq_encode needs                                    */
+} hqmq_size_info;
+
+/* The encoded form of one tensor: a HOST struct of DEVICE pointers, all caller-owned.
+ *   codes      uint32 [n_rows][w]   chunk code = (r_q << w_idx) | k, k = p*S + s (p-major),
+ *                                   flagged chunks 0; the 32 codes of a row concatenated
+ *                                   LSB first: chunk c at bits [c*w, (c+1)*w) of the row's w
+ *                                   little-endian words                       (Alg. 1 "store")
+ *   sigma      fp16   [n_rows]      per-token scale: largest norm among the row's unflagged
+ *                                   chunks, rounded to nearest even, saturating (Sec. 3
+ *                                   "Radius quantization")
+ *   flags      uint32 [n_rows]      bit c set = chunk c of the row is an outlier
+ *   row_off    uint32 [n_rows + 1]  number of outliers in all earlier rows (exclusive prefix);
+ *                                   last entry = total
+ *   outliers   fp16   [cap][4]      the flagged chunks verbatim, ascending linear chunk index
+ *   n_outliers uint32 [H + 1]       outliers per head, then the total (true counts even on
+ *                                   overflow)
+ *   status     uint32 [1]           HQMQ_STATUS_* bits, written by hqmq_encode             */
+typedef struct hqmq_encoded {
+    uint32_t *codes;
+    uint16_t *sigma;
+    uint32_t *flags;
+    uint32_t *row_off;
+    uint16_t *outliers;
+    uint32_t *n_outliers;
+    uint32_t *status;
+} hqmq_encoded;
+
+/* Secondary codebooks (App. D "Secondary codebook initialization"): for every (layer, role,
+ * head) S i.i.d. standard-normal 4-vectors, normalised to unit length, drawn from a
+ * counter-based generator so that entry (layer, role, head, s) depends only on the seed and
+ * its linear index ((layer*2 + role)*n_kv_heads + head)*S + s.  role 0 = K, 1 = V.
+ *   sec_host  HOST, out, fp32 [n_layers][2][n_kv_heads][S][4], caller-owned.
+ * Pure host function (no GPU work).  Errors: INVALID_ARG (null pointer, non-positive size),
+ * UNSUPPORTED (24*S > 65536). */
+int32_t hqmq_build_codebooks(uint64_t seed, int32_t n_layers, int32_t n_kv_heads, int32_t S,
+                             float *sec_host);
+
+/* Sizes of the encoded buffers and of the encode workspace for `params` (HOST pointers).
+ * Errors: INVALID_ARG, UNSUPPORTED (same checks as hqmq_encode). */
+int32_t hqmq_sizes(const hqmq_params *params, hqmq_size_info *out);
+
+/* Encode one tensor (Alg. 1 "Encode" + "Outlier extraction", App. D "Encode", "Outlier
+ * extraction").  Steps, all on the GPU: squared chunk norms in fp64; exact lower median per
+ * head over the batch (radix select); flag r^2 > C^2 * median (strict); ordered compaction
+ * of the flagged chunks; per-row fp16 scale over the unflagged chunks; nearest joint codeword
+ * by exhaustive search over all S secondaries (24 primaries each, lowest index on ties);
+ * radius code r_q = clamp(rint(r * (2^b_r - 1) / sigma), 0, 2^b_r - 1); bit packing.
+ *   params            HOST.
+ *   x_dev             DEVICE, in, fp16, 8-byte aligned, addressed with params strides; finite.
+ *   sec_dev           DEVICE, in, fp32 [H][S][4]: the codebooks of THIS (layer, role).
+ *   enc               HOST struct of DEVICE pointers (see hqmq_encoded), sized per hqmq_sizes.
+ *   outlier_capacity  entries (chunks) available in enc->outliers; outlier_capacity_max always
+ *                     suffices.  If fewer, surplus outliers are dropped, status gets
+ *                     HQMQ_STATUS_OUTLIER_OVERFLOW and n_outliers / row_off still hold the true
+ *                     counts so the caller can retry.
+ *   workspace_dev     DEVICE scratch, 256-byte aligned, at least workspace_bytes; contents
+ *                     need not be preserved or initialised.
+ *   stream            hipStream_t.
+ * Two calls may run concurrently only with distinct workspaces and outputs. */
+int32_t hqmq_encode(const hqmq_params *params, const void *x_dev, const float *sec_dev,
+                    const hqmq_encoded *enc, uint64_t outlier_capacity, void *workspace_dev,
+                    uint64_t workspace_bytes, void *stream);
+
+/* Decode one tensor (Alg. 1 "Decode", App. D "Decode"): x_hat = r_hat * (q_p * q_s) with
+ * r_hat = r_q * sigma / (2^b_r - 1) and the Hamilton product taken at decode time, rounded to
+ * fp16; flagged chunks are restored from the outlier list.
+ *   params   HOST; B, H, T, D, S, b_r and the strides (of out_dev) are used.
+ *   enc      HOST struct of DEVICE pointers as produced by hqmq_encode (n_outliers and status
+ *            are not read).  Codes must hold k < 24*S.
+ *   outlier_capacity  entries available in enc->outliers; a flagged chunk whose list position
+ *            lies beyond it (an encode that overflowed) decodes to zeros.
+ *   sec_dev  DEVICE, fp32 [H][S][4], the same codebooks used to encode.
+ *   out_dev  DEVICE, out, fp16, 8-byte aligned, addressed with params strides.
+ *   stream   hipStream_t. */
+int32_t hqmq_decode(const hqmq_params *params, const hqmq_encoded *enc, uint64_t outlier_capacity,
+                    const float *sec_dev, void *out_dev, void *stream);
+
+/* hipError_t value of the last failed HIP call made by this library on the calling thread
+ * (0 if none). */
+int32_t hqmq_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HQMQ_H */

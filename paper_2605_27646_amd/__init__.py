@@ -1,0 +1,23 @@
+"""MI355X-native HQMQ KV-cache encode / decode.
+
+The product is the C-ABI library ``libhqmq.so`` (HIP kernels for gfx950, declared in
+``include/hqmq.h``); this package is its thin Python binding: the functions below have the
+library's names and only marshal arguments.  PyTorch provides device memory and streams.
+"""
+from .binding import (  # noqa: F401
+    HQMQ_FLAG_NO_OUTLIERS,
+    HQMQ_STATUS_OUTLIER_OVERFLOW,
+    EncodedBuffers,
+    HqmqError,
+    HqmqParams,
+    HqmqSizeInfo,
+    alloc_encoded,
+    alloc_workspace,
+    hqmq_build_codebooks,
+    hqmq_decode,
+    hqmq_encode,
+    hqmq_last_hip_error,
+    hqmq_sizes,
+    library_path,
+    params_for,
+)

@@ -1,0 +1,186 @@
+"""ctypes binding of libhqmq.so.  Argument marshalling only: every step of encode and decode
+runs in the library's kernels.  There is no fallback: if the library is not built, loading
+raises."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libhqmq.so")
+
+HQMQ_OK = 0
+HQMQ_FLAG_NO_OUTLIERS = 1
+HQMQ_STATUS_OUTLIER_OVERFLOW = 1
+_ERRORS = {-1: "HQMQ_ERR_INVALID_ARG", -2: "HQMQ_ERR_UNSUPPORTED", -3: "HQMQ_ERR_BUFFER_TOO_SMALL",
+           -4: "HQMQ_ERR_HIP"}
+
+
+class HqmqError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where} failed: {_ERRORS.get(code, code)}")
+
+
+class HqmqParams(C.Structure):
+    _fields_ = [("B", C.c_int32), ("H", C.c_int32), ("T", C.c_int32), ("D", C.c_int32),
+                ("stride_b", C.c_int64), ("stride_h", C.c_int64), ("stride_t", C.c_int64),
+                ("S", C.c_int32), ("b_r", C.c_int32), ("C", C.c_float), ("flags", C.c_uint32)]
+
+
+class HqmqSizeInfo(C.Structure):
+    _fields_ = [("n_rows", C.c_uint64), ("index_bits", C.c_uint32), ("code_bits", C.c_uint32),
+                ("code_bytes", C.c_uint64), ("sigma_bytes", C.c_uint64), ("flag_bytes", C.c_uint64),
+                ("row_off_bytes", C.c_uint64), ("n_outliers_bytes", C.c_uint64),
+                ("status_bytes", C.c_uint64), ("outlier_capacity_max", C.c_uint64),
+                ("outlier_bytes_max", C.c_uint64), ("workspace_bytes", C.c_uint64)]
+
+
+class _Encoded(C.Structure):
+    _fields_ = [("codes", C.c_void_p), ("sigma", C.c_void_p), ("flags", C.c_void_p),
+                ("row_off", C.c_void_p), ("outliers", C.c_void_p), ("n_outliers", C.c_void_p),
+                ("status", C.c_void_p)]
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError(
+                f"{_LIB_PATH} is missing: build it with `python -m paper_2605_27646_amd.build` "
+                "(there is no fallback path)")
+        lib = C.CDLL(_LIB_PATH)
+        lib.hqmq_build_codebooks.restype = C.c_int32
+        lib.hqmq_build_codebooks.argtypes = [C.c_uint64, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
+        lib.hqmq_sizes.restype = C.c_int32
+        lib.hqmq_sizes.argtypes = [C.POINTER(HqmqParams), C.POINTER(HqmqSizeInfo)]
+        lib.hqmq_encode.restype = C.c_int32
+        lib.hqmq_encode.argtypes = [C.POINTER(HqmqParams), C.c_void_p, C.c_void_p, C.POINTER(_Encoded),
+                                    C.c_uint64, C.c_void_p, C.c_uint64, C.c_void_p]
+        lib.hqmq_decode.restype = C.c_int32
+        lib.hqmq_decode.argtypes = [C.POINTER(HqmqParams), C.POINTER(_Encoded), C.c_uint64, C.c_void_p,
+                                    C.c_void_p, C.c_void_p]
+        lib.hqmq_last_hip_error.restype = C.c_int32
+        lib.hqmq_last_hip_error.argtypes = []
+        _lib = lib
+    return _lib
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != HQMQ_OK:
+        raise HqmqError(rc, where)
+
+
+def params_for(x: torch.Tensor, S: int, b_r: int = 6, Cmul: float = 3.0, flags: int = 0) -> HqmqParams:
+    """hqmq_params describing tensor x [B, H, T, D] (any strides with D contiguous)."""
+    if x.dim() != 4 or x.stride(3) != 1:
+        raise ValueError("x must be [B, H, T, D] with D contiguous")
+    B, H, T, D = x.shape
+    return HqmqParams(B, H, T, D, x.stride(0), x.stride(1), x.stride(2), S, b_r, Cmul, flags)
+
+
+@dataclass
+class EncodedBuffers:
+    """Caller-owned device buffers of one encoded tensor (see hqmq_encoded in hqmq.h)."""
+    codes: torch.Tensor        # int32 [n_rows, w]   (bit patterns of uint32)
+    sigma: torch.Tensor        # float16 [n_rows]
+    flags: torch.Tensor        # int32 [n_rows]
+    row_off: torch.Tensor      # int32 [n_rows + 1]
+    outliers: torch.Tensor     # float16 [capacity, 4]
+    n_outliers: torch.Tensor   # int32 [H + 1]
+    status: torch.Tensor       # int32 [1]
+
+    @property
+    def outlier_capacity(self) -> int:
+        return self.outliers.shape[0]
+
+    def as_struct(self) -> _Encoded:
+        return _Encoded(self.codes.data_ptr(), self.sigma.data_ptr(), self.flags.data_ptr(),
+                        self.row_off.data_ptr(), self.outliers.data_ptr(), self.n_outliers.data_ptr(),
+                        self.status.data_ptr())
+
+    def nbytes(self) -> int:
+        return sum(t.numel() * t.element_size() for t in
+                   (self.codes, self.sigma, self.flags, self.row_off, self.outliers, self.n_outliers, self.status))
+
+
+def hqmq_last_hip_error() -> int:
+    return int(_load().hqmq_last_hip_error())
+
+
+def hqmq_build_codebooks(seed: int, n_layers: int, n_kv_heads: int, S: int) -> torch.Tensor:
+    """fp32 [n_layers, 2, n_kv_heads, S, 4] on the host (role 0 = K, 1 = V)."""
+    if n_layers <= 0 or n_kv_heads <= 0 or S <= 0:
+        _check(-1, "hqmq_build_codebooks")
+    out = torch.empty(n_layers, 2, n_kv_heads, S, 4, dtype=torch.float32)
+    _check(_load().hqmq_build_codebooks(seed, n_layers, n_kv_heads, S, out.data_ptr()), "hqmq_build_codebooks")
+    return out
+
+
+def hqmq_sizes(params: HqmqParams) -> HqmqSizeInfo:
+    info = HqmqSizeInfo()
+    _check(_load().hqmq_sizes(C.byref(params), C.byref(info)), "hqmq_sizes")
+    return info
+
+
+def alloc_encoded(params: HqmqParams, device, outlier_capacity: int | None = None) -> EncodedBuffers:
+    """Allocate the encoded buffers with torch (memory plumbing only)."""
+    info = hqmq_sizes(params)
+    cap = int(info.outlier_capacity_max if outlier_capacity is None else outlier_capacity)
+    n = int(info.n_rows)
+    return EncodedBuffers(
+        codes=torch.empty(n, info.code_bits, dtype=torch.int32, device=device),
+        sigma=torch.empty(n, dtype=torch.float16, device=device),
+        flags=torch.empty(n, dtype=torch.int32, device=device),
+        row_off=torch.empty(n + 1, dtype=torch.int32, device=device),
+        outliers=torch.empty(max(cap, 1), 4, dtype=torch.float16, device=device)[:cap],
+        n_outliers=torch.empty(params.H + 1, dtype=torch.int32, device=device),
+        status=torch.empty(1, dtype=torch.int32, device=device),
+    )
+
+
+def alloc_workspace(params: HqmqParams, device) -> torch.Tensor:
+    info = hqmq_sizes(params)
+    return torch.empty(int(info.workspace_bytes), dtype=torch.uint8, device=device)
+
+
+def _stream_ptr(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream)
+
+
+def hqmq_encode(params: HqmqParams, x: torch.Tensor, sec: torch.Tensor, enc: EncodedBuffers,
+                workspace: torch.Tensor, stream=None) -> None:
+    """Enqueue the encode of x (fp16 device tensor described by params) against sec
+    (fp32 [H, S, 4] on the device) on `stream` (default: torch's current stream)."""
+    if x.dtype != torch.float16 or not x.is_cuda or not sec.is_cuda or sec.dtype != torch.float32:
+        raise ValueError("x must be a device fp16 tensor and sec a device fp32 tensor")
+    if not sec.is_contiguous() or tuple(sec.shape) != (params.H, params.S, 4):
+        raise ValueError("sec must be contiguous [H, S, 4]")
+    rc = _load().hqmq_encode(C.byref(params), x.data_ptr(), sec.data_ptr(), C.byref(enc.as_struct()),
+                             enc.outlier_capacity, workspace.data_ptr(), workspace.numel(),
+                             _stream_ptr(stream))
+    _check(rc, "hqmq_encode")
+
+
+def hqmq_decode(params: HqmqParams, enc: EncodedBuffers, sec: torch.Tensor, out: torch.Tensor,
+                stream=None) -> None:
+    """Enqueue the decode into `out` (fp16 device tensor with the strides params holds)."""
+    if out.dtype != torch.float16 or not out.is_cuda or not sec.is_cuda or sec.dtype != torch.float32:
+        raise ValueError("out must be a device fp16 tensor and sec a device fp32 tensor")
+    if not sec.is_contiguous() or tuple(sec.shape) != (params.H, params.S, 4):
+        raise ValueError("sec must be contiguous [H, S, 4]")
+    rc = _load().hqmq_decode(C.byref(params), C.byref(enc.as_struct()), enc.outlier_capacity,
+                             sec.data_ptr(), out.data_ptr(), _stream_ptr(stream))
+    _check(rc, "hqmq_decode")

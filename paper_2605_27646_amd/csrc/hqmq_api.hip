@@ -1,0 +1,229 @@
+// C ABI of the HQMQ library (declared in include/hqmq.h): argument validation, workspace
+// carve-up and the stream-ordered kernel sequences.  No allocation, no synchronisation.
+#include <cmath>
+#include <cstring>
+
+#include "hqmq_device.h"
+
+namespace hqmq {
+
+static thread_local int32_t g_last_hip_error = 0;
+
+static inline uint64_t align_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
+
+static int index_bits(int S)
+{
+    int j = 0;
+    while ((1ll << j) < 24ll * S)
+        ++j;
+    return j;
+}
+
+// Largest S the search kernel's LDS tables are sized for (paper sweeps S up to 192).
+constexpr int kMaxS = 512;
+
+static int32_t check_params(const hqmq_params *p)
+{
+    if (!p)
+        return HQMQ_ERR_INVALID_ARG;
+    if (p->B <= 0 || p->H <= 0 || p->T <= 0 || p->D <= 0)
+        return HQMQ_ERR_INVALID_ARG;
+    if (p->D != 4 * kChunksPerRow)
+        return HQMQ_ERR_UNSUPPORTED;
+    if (p->S < 1 || p->S > kMaxS || p->b_r < 1 || p->b_r > 8)
+        return HQMQ_ERR_UNSUPPORTED;
+    if (!(p->flags & HQMQ_FLAG_NO_OUTLIERS) && !(std::isfinite(p->C) && p->C > 0.f))
+        return HQMQ_ERR_UNSUPPORTED;
+    if (p->stride_b < 0 || p->stride_h < 0 || p->stride_t < p->D)
+        return HQMQ_ERR_INVALID_ARG;
+    if ((p->stride_b % 4) || (p->stride_h % 4) || (p->stride_t % 4))
+        return HQMQ_ERR_INVALID_ARG;
+    if ((int64_t)p->B * p->H > 65535)
+        return HQMQ_ERR_UNSUPPORTED;  // grid.y
+    const uint64_t n_rows = (uint64_t)p->B * p->H * p->T;
+    if (n_rows * kChunksPerRow >= (1ull << 32))
+        return HQMQ_ERR_UNSUPPORTED;  // 32-bit outlier offsets and ranks
+    return HQMQ_OK;
+}
+
+static Geometry make_geometry(const hqmq_params *p)
+{
+    Geometry g;
+    g.B = p->B;
+    g.H = p->H;
+    g.T = p->T;
+    g.S = p->S;
+    g.S4 = (p->S + 3) / 4;
+    g.b_r = p->b_r;
+    g.w_idx = index_bits(p->S);
+    g.w = g.w_idx + p->b_r;
+    g.sb = p->stride_b;
+    g.sh = p->stride_h;
+    g.st = p->stride_t;
+    g.s_magic = (p->S == 1) ? 0u : (uint32_t)((1ull << 32) / (uint64_t)p->S + 1ull);
+    g.n_mask_blocks_per_seg = (uint32_t)((p->T + kMaskRows - 1) / kMaskRows);
+    return g;
+}
+
+struct WorkspaceLayout {
+    uint64_t state, thr, hist, block_sum, block_pre, total;
+};
+
+static WorkspaceLayout workspace_layout(const Geometry &g)
+{
+    WorkspaceLayout l;
+    uint64_t off = 0;
+    const uint64_t n_blocks = (uint64_t)g.B * g.H * g.n_mask_blocks_per_seg;
+    l.state = off;
+    off = align_up(off + (uint64_t)g.H * sizeof(SelectState), 256);
+    l.thr = off;
+    off = align_up(off + (uint64_t)g.H * sizeof(double), 256);
+    l.hist = off;
+    off = align_up(off + (uint64_t)g.H * kHistBins * sizeof(uint32_t), 256);
+    l.block_sum = off;
+    off = align_up(off + n_blocks * sizeof(uint32_t), 256);
+    l.block_pre = off;
+    off = align_up(off + n_blocks * sizeof(uint32_t), 256);
+    l.total = off;
+    return l;
+}
+
+static bool misaligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) % a) != 0; }
+
+static int32_t check_encoded(const hqmq_encoded *e, bool need_counts)
+{
+    if (!e || !e->codes || !e->sigma || !e->flags || !e->row_off || !e->outliers)
+        return HQMQ_ERR_INVALID_ARG;
+    if (need_counts && (!e->n_outliers || !e->status))
+        return HQMQ_ERR_INVALID_ARG;
+    if (misaligned(e->codes, 4) || misaligned(e->sigma, 2) || misaligned(e->flags, 4) ||
+        misaligned(e->row_off, 4) || misaligned(e->outliers, 8))
+        return HQMQ_ERR_INVALID_ARG;
+    if (need_counts && (misaligned(e->n_outliers, 4) || misaligned(e->status, 4)))
+        return HQMQ_ERR_INVALID_ARG;
+    return HQMQ_OK;
+}
+
+static EncodedPtrs to_ptrs(const hqmq_encoded *e)
+{
+    EncodedPtrs p;
+    p.codes = e->codes;
+    p.sigma = e->sigma;
+    p.flags = e->flags;
+    p.row_off = e->row_off;
+    p.outliers = e->outliers;
+    p.n_outliers = e->n_outliers;
+    p.status = e->status;
+    return p;
+}
+
+static int32_t hip_failed(hipError_t err)
+{
+    g_last_hip_error = (int32_t)err;
+    return HQMQ_ERR_HIP;
+}
+
+}  // namespace hqmq
+
+using namespace hqmq;
+
+extern "C" int32_t hqmq_last_hip_error(void) { return g_last_hip_error; }
+
+extern "C" int32_t hqmq_sizes(const hqmq_params *params, hqmq_size_info *out)
+{
+    if (!out)
+        return HQMQ_ERR_INVALID_ARG;
+    int32_t rc = check_params(params);
+    if (rc != HQMQ_OK)
+        return rc;
+    const Geometry g = make_geometry(params);
+    std::memset(out, 0, sizeof(*out));
+    const uint64_t n_rows = (uint64_t)g.B * g.H * g.T;
+    out->n_rows = n_rows;
+    out->index_bits = (uint32_t)g.w_idx;
+    out->code_bits = (uint32_t)g.w;
+    out->code_bytes = n_rows * g.w * 4;
+    out->sigma_bytes = n_rows * 2;
+    out->flag_bytes = n_rows * 4;
+    out->row_off_bytes = (n_rows + 1) * 4;
+    out->n_outliers_bytes = ((uint64_t)g.H + 1) * 4;
+    out->status_bytes = 4;
+    // A chunk is flagged when r^2 > C^2 * median.  For C >= 1 that needs r^2 above the lower
+    // median of its head, which at most floor(n_h / 2) chunks are; for C < 1 any chunk may be.
+    const uint64_t n_h = (uint64_t)g.B * g.T * kChunksPerRow;
+    uint64_t cap = (uint64_t)g.H * n_h;
+    if (params->flags & HQMQ_FLAG_NO_OUTLIERS)
+        cap = 0;
+    else if (params->C >= 1.0f)
+        cap = (uint64_t)g.H * (n_h / 2);
+    out->outlier_capacity_max = cap;
+    out->outlier_bytes_max = cap * 8;
+    out->workspace_bytes = workspace_layout(g).total;
+    return HQMQ_OK;
+}
+
+extern "C" int32_t hqmq_encode(const hqmq_params *params, const void *x_dev, const float *sec_dev,
+                               const hqmq_encoded *enc, uint64_t outlier_capacity,
+                               void *workspace_dev, uint64_t workspace_bytes, void *stream)
+{
+    int32_t rc = check_params(params);
+    if (rc != HQMQ_OK)
+        return rc;
+    if (!x_dev || !sec_dev || !workspace_dev)
+        return HQMQ_ERR_INVALID_ARG;
+    if (misaligned(x_dev, 8) || misaligned(sec_dev, 16) || misaligned(workspace_dev, 256))
+        return HQMQ_ERR_INVALID_ARG;
+    rc = check_encoded(enc, true);
+    if (rc != HQMQ_OK)
+        return rc;
+    const Geometry g = make_geometry(params);
+    const WorkspaceLayout l = workspace_layout(g);
+    if (workspace_bytes < l.total)
+        return HQMQ_ERR_BUFFER_TOO_SMALL;
+
+    char *wsb = static_cast<char *>(workspace_dev);
+    Workspace ws;
+    ws.state = reinterpret_cast<SelectState *>(wsb + l.state);
+    ws.thr = reinterpret_cast<double *>(wsb + l.thr);
+    ws.hist = reinterpret_cast<uint32_t *>(wsb + l.hist);
+    ws.block_sum = reinterpret_cast<uint32_t *>(wsb + l.block_sum);
+    ws.block_pre = reinterpret_cast<uint32_t *>(wsb + l.block_pre);
+
+    const EncodedPtrs ep = to_ptrs(enc);
+    const _Float16 *x = static_cast<const _Float16 *>(x_dev);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool no_outliers = (params->flags & HQMQ_FLAG_NO_OUTLIERS) != 0;
+
+    hipError_t err = launch_select_median(x, g, ws, params->C, no_outliers, ep, st);
+    if (err != hipSuccess)
+        return hip_failed(err);
+    err = launch_mask_scan(x, g, ws, ep, outlier_capacity, st);
+    if (err != hipSuccess)
+        return hip_failed(err);
+    err = launch_search(x, sec_dev, g, ws, ep, outlier_capacity, st);
+    if (err != hipSuccess)
+        return hip_failed(err);
+    return HQMQ_OK;
+}
+
+extern "C" int32_t hqmq_decode(const hqmq_params *params, const hqmq_encoded *enc,
+                               uint64_t outlier_capacity, const float *sec_dev, void *out_dev,
+                               void *stream)
+{
+    int32_t rc = check_params(params);
+    if (rc != HQMQ_OK)
+        return rc;
+    if (!sec_dev || !out_dev)
+        return HQMQ_ERR_INVALID_ARG;
+    if (misaligned(out_dev, 8) || misaligned(sec_dev, 16))
+        return HQMQ_ERR_INVALID_ARG;
+    rc = check_encoded(enc, false);
+    if (rc != HQMQ_OK)
+        return rc;
+    const Geometry g = make_geometry(params);
+    hipError_t err = launch_decode(g, to_ptrs(enc), outlier_capacity, sec_dev,
+                                   static_cast<_Float16 *>(out_dev), static_cast<hipStream_t>(stream));
+    if (err != hipSuccess)
+        return hip_failed(err);
+    return HQMQ_OK;
+}

@@ -1,0 +1,97 @@
+// Internal declarations shared by the HQMQ gfx950 kernels and the host-side launch code.
+// Not part of the public ABI (that is include/hqmq.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "hqmq.h"
+
+namespace hqmq {
+
+constexpr int kChunksPerRow = 32;    // D = 128
+constexpr int kHistBins = 8192;      // widest radix digit: 13 bits
+constexpr int kHistRows = 256;       // rows of one (b, h) segment per histogram block
+constexpr int kMaskRows = 256;       // rows per mask block = granularity of the outlier scan
+constexpr int kSearchRows = 64;      // rows per search block (divides kMaskRows)
+constexpr int kDecodeRows = 128;     // rows per decode block
+constexpr int kThreads = 256;        // every kernel runs 4 wave64 per workgroup
+
+// Radix-select digits over the 63 value bits of a non-negative IEEE double, high to low.
+constexpr int kNumPasses = 5;
+__host__ __device__ constexpr int pass_bits(int p) { return p < 3 ? 13 : 12; }
+__host__ __device__ constexpr int pass_shift(int p) { return p == 0 ? 50 : p == 1 ? 37 : p == 2 ? 24 : p == 3 ? 12 : 0; }
+
+// Per-head state of the running radix select.
+struct SelectState {
+    unsigned long long prefix;  // key bits fixed so far (right aligned)
+    uint32_t rank;              // rank still to be located inside the prefix bucket
+    uint32_t pad;
+};
+
+// Shape and addressing of one tensor, passed by value to every kernel.
+struct Geometry {
+    int32_t B, H, T;
+    int32_t S;            // secondaries per head
+    int32_t S4;           // ceil(S / 4): s-blocks of the MFMA tile
+    int32_t b_r, w_idx, w;
+    int64_t sb, sh, st;   // element strides
+    uint32_t s_magic;     // k / S == mulhi(k, s_magic) for every k < 2^w_idx
+    uint32_t n_mask_blocks_per_seg;
+};
+
+// Workspace carve-up (device pointers into the caller's workspace).
+struct Workspace {
+    SelectState *state;   // [H]
+    double *thr;          // [H] outlier threshold on squared norms
+    uint32_t *hist;       // [H][kHistBins]
+    uint32_t *block_sum;  // [B*H*n_mask_blocks_per_seg]
+    uint32_t *block_pre;  // same shape, exclusive prefix
+};
+
+struct EncodedPtrs {
+    uint32_t *codes;
+    uint16_t *sigma;
+    uint32_t *flags;
+    uint32_t *row_off;
+    uint16_t *outliers;
+    uint32_t *n_outliers;
+    uint32_t *status;
+};
+
+// ---- device helpers --------------------------------------------------------------------
+
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+
+// Squared norm of a chunk in fp64, fixed order ((x0^2 + x1^2) + x2^2) + x3^2.  The products
+// of fp16 values are exact in fp64, so only the three additions round.
+__device__ __forceinline__ double chunk_norm2(const half4_t v)
+{
+    double x0 = (double)(float)v[0], x1 = (double)(float)v[1];
+    double x2 = (double)(float)v[2], x3 = (double)(float)v[3];
+    return ((x0 * x0 + x1 * x1) + x2 * x2) + x3 * x3;
+}
+
+__device__ __forceinline__ half4_t load_chunk(const _Float16 *p)
+{
+    uint2 raw = *reinterpret_cast<const uint2 *>(p);
+    return __builtin_bit_cast(half4_t, raw);
+}
+
+__device__ __forceinline__ unsigned long long key_of(double r2)
+{
+    return (unsigned long long)__double_as_longlong(r2);
+}
+
+// Launchers implemented in the kernel translation units (host side).
+hipError_t launch_select_median(const _Float16 *x, const Geometry &g, const Workspace &ws, float C,
+                                bool no_outliers, const EncodedPtrs &enc, hipStream_t stream);
+hipError_t launch_mask_scan(const _Float16 *x, const Geometry &g, const Workspace &ws,
+                            const EncodedPtrs &enc, uint64_t outlier_capacity, hipStream_t stream);
+hipError_t launch_search(const _Float16 *x, const float *sec, const Geometry &g, const Workspace &ws,
+                         const EncodedPtrs &enc, uint64_t outlier_capacity, hipStream_t stream);
+hipError_t launch_decode(const Geometry &g, const EncodedPtrs &enc, uint64_t outlier_capacity,
+                         const float *sec, _Float16 *out, hipStream_t stream);
+
+}  // namespace hqmq

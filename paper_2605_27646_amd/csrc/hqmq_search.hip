@@ -1,0 +1,309 @@
+// HQMQ encode, second half: per-row scale, nearest-codeword search, radius code, bit packing
+// and the ordered write of the outlier payload (paper Alg. 1 "Encode", App. D "Encode").
+//
+// Search formulation.  The score of codeword (p, s) is <u, P_p q_s>.  Right multiplication by
+// conj(q_s) is an isometry of R^4 up to the common factor |q_s|^2, so
+//     <u, P_p q_s> = <u conj(q_s), P_p>,
+// and for a fixed s the best primary is the 24-cell vertex nearest to v = u conj(q_s):
+//     max_p <v, P_p> = max( max_i |v_i| , (|v_0|+|v_1|+|v_2|+|v_3|)/2 )
+// (first term: the 8 axis elements +-1, +-i, +-j, +-k; second: the 16 half-integer elements).
+// The map u -> v is linear, v = A(q_s) u with a 4x4 matrix per secondary, so all S products of
+// 16 chunks are one [4S x 4] x [4 x 16] contraction with K = 4: exactly the shape of
+// v_mfma_f32_16x16x4_f32.  One MFMA gives every lane the four components of v for one
+// (chunk, secondary) pair; the closed form and the running argmax over s are a handful of VALU
+// instructions per pair.  The search stays exhaustive over all S secondaries and, through the
+// closed form, over all 24 primaries.
+//
+// Work split: a workgroup (4 wave64) owns kSearchRows rows of one (b, h) segment, so the A
+// matrices of the head sit in LDS once per workgroup.  A wave takes two rows (64 chunks, one per
+// lane) at a time and runs them as four 16-chunk MFMA column groups.
+#include "hqmq_device.h"
+
+namespace hqmq {
+
+namespace {
+
+__device__ __forceinline__ uint16_t double_to_half_rne_sat(double v)
+{
+    // v >= 0 and finite.  Round to nearest even from the full 53-bit significand (no double
+    // rounding through fp32), saturate at 65504.
+    if (!(v < 65504.0))
+        return 0x7bff;
+    unsigned long long bits = (unsigned long long)__double_as_longlong(v);
+    int e = (int)(bits >> 52) - 1023;
+    if (e < -40)
+        return 0;  // far below half of the smallest subnormal 2^-24
+    unsigned long long m = (bits & 0x000fffffffffffffull) | 0x0010000000000000ull;
+    int E = e < -14 ? -14 : e;
+    int sh = 42 + (E - e);  // 42 .. 68
+    if (sh > 63)
+        return 0;
+    unsigned long long q = m >> sh;
+    unsigned long long rem = m & ((1ull << sh) - 1ull);
+    unsigned long long half = 1ull << (sh - 1);
+    if (rem > half || (rem == half && (q & 1ull)))
+        ++q;
+    uint32_t out = ((uint32_t)(E + 14) << 10) + (uint32_t)q;
+    return out > 0x7bff ? (uint16_t)0x7bff : (uint16_t)out;
+}
+
+__device__ __forceinline__ double half_bits_to_double(uint16_t h)
+{
+    return (double)(float)__builtin_bit_cast(_Float16, h);
+}
+
+// Nearest 24-cell vertex to v in the order of the primary table: p = 0..7 are +1, -1, +i, -i,
+// +j, -j, +k, -k, p = 8 + 8 b0 + 4 b1 + 2 b2 + b3 is ((-1)^b0, (-1)^b1, (-1)^b2, (-1)^b3)/2.
+// Exact ties go to the lowest p.
+__device__ __forceinline__ int nearest_primary(float v0, float v1, float v2, float v3, float &score)
+{
+    float a0 = fabsf(v0), a1 = fabsf(v1), a2 = fabsf(v2), a3 = fabsf(v3);
+    float ax = a0;
+    int pi = (v0 < 0.f) ? 1 : 0;
+    if (a1 > ax) { ax = a1; pi = 2 + ((v1 < 0.f) ? 1 : 0); }
+    if (a2 > ax) { ax = a2; pi = 4 + ((v2 < 0.f) ? 1 : 0); }
+    if (a3 > ax) { ax = a3; pi = 6 + ((v3 < 0.f) ? 1 : 0); }
+    float hs = 0.5f * (((a0 + a1) + a2) + a3);
+    int ph = 8 + ((v0 < 0.f) ? 8 : 0) + ((v1 < 0.f) ? 4 : 0) + ((v2 < 0.f) ? 2 : 0) + ((v3 < 0.f) ? 1 : 0);
+    if (ax >= hs) {
+        score = ax;
+        return pi;
+    }
+    score = hs;
+    return ph;
+}
+
+}  // namespace
+
+// Dynamic LDS layout (floats):
+//   amat  [S4][64]      MFMA A operands: lane l of s-block sb holds A[row l%16][k l/16], row 4g+i =
+//                       component i of v for secondary 4 sb + g
+//   secl  [4*S4][4]     the head's secondaries (zero padded to a multiple of 4)
+//   ubuf  [4 waves][64][4]   unit directions of the wave's 64 chunks (for the B operands)
+//   pack  [4 waves][2][32]   row code words being assembled
+//   roff  [kSearchRows] outlier offsets of the block's rows
+__global__ __launch_bounds__(kThreads) void k_search(const _Float16 *__restrict__ x,
+                                                     const float *__restrict__ sec, Geometry g,
+                                                     Workspace ws, EncodedPtrs enc,
+                                                     uint64_t outlier_capacity)
+{
+    extern __shared__ float smem[];
+    float *amat = smem;
+    float *secl = amat + (size_t)g.S4 * 64;
+    float *ubuf = secl + (size_t)g.S4 * 16;
+    uint32_t *pack = reinterpret_cast<uint32_t *>(ubuf + 4 * 64 * 4);
+    uint32_t *roff = pack + 4 * 2 * 32;
+
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int seg = blockIdx.y, b = seg / g.H, h = seg % g.H;
+    const int t0 = blockIdx.x * kSearchRows;
+    const int64_t row0 = (int64_t)seg * g.T;  // linear index of the segment's first row
+    const float *sec_h = sec + (size_t)h * g.S * 4;
+
+    // ---- setup: secondaries and A operands into LDS ---------------------------------------
+    for (int s = tid; s < g.S4 * 4; s += kThreads) {
+        float4_t q = {0.f, 0.f, 0.f, 0.f};
+        if (s < g.S)
+            q = *reinterpret_cast<const float4_t *>(sec_h + 4 * s);
+        *reinterpret_cast<float4_t *>(secl + 4 * s) = q;
+    }
+    __syncthreads();
+    for (int idx = tid; idx < g.S4 * 64; idx += kThreads) {
+        int sb = idx >> 6, l = idx & 63;
+        int row = l & 15, k = l >> 4;
+        int gsub = row >> 2, i = row & 3;
+        const float *q = secl + 4 * (4 * sb + gsub);
+        float a = q[0], bq = q[1], c = q[2], d = q[3];
+        // v = u (x) conj(q):  v0 =  a u0 + b u1 + c u2 + d u3
+        //                     v1 = -b u0 + a u1 - d u2 + c u3
+        //                     v2 = -c u0 + d u1 + a u2 - b u3
+        //                     v3 = -d u0 - c u1 + b u2 + a u3
+        float val;
+        if (i == 0)
+            val = (k == 0) ? a : (k == 1) ? bq : (k == 2) ? c : d;
+        else if (i == 1)
+            val = (k == 0) ? -bq : (k == 1) ? a : (k == 2) ? -d : c;
+        else if (i == 2)
+            val = (k == 0) ? -c : (k == 1) ? d : (k == 2) ? a : -bq;
+        else
+            val = (k == 0) ? -d : (k == 1) ? -c : (k == 2) ? bq : a;
+        amat[idx] = val;
+    }
+
+    // ---- setup: outlier offsets of the block's rows -----------------------------------------
+    // offset(row) = prefix of the 256-row scan block + flagged chunks in its earlier rows
+    if (wv == 0) {
+        const int scan_t0 = (t0 / kMaskRows) * kMaskRows;
+        uint32_t before = 0;
+        for (int t = scan_t0 + lane; t < t0; t += 64)
+            before += __popc(enc.flags[row0 + t]);
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1)
+            before += __shfl_xor(before, d, 64);
+        before += ws.block_pre[(size_t)seg * g.n_mask_blocks_per_seg + t0 / kMaskRows];
+        const int t = t0 + lane;
+        uint32_t cnt = (t < g.T) ? __popc(enc.flags[row0 + t]) : 0;
+        uint32_t inc = cnt;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            uint32_t o = __shfl_up(inc, d, 64);
+            if (lane >= d)
+                inc += o;
+        }
+        uint32_t off = before + inc - cnt;
+        roff[lane] = off;
+        if (t < g.T)
+            enc.row_off[row0 + t] = off;
+    }
+    __syncthreads();
+
+    const double thr = ws.thr[h];
+    const double Lq = (double)((1 << g.b_r) - 1);
+    const int c = lane & 31, half_id = lane >> 5;
+    float *my_ubuf = ubuf + wv * 64 * 4;
+    uint32_t *my_pack = pack + wv * 64;
+    const _Float16 *base = x + (int64_t)b * g.sb + (int64_t)h * g.sh + 4 * c;
+
+    for (int it = 0; it < kSearchRows / 8; ++it) {
+        const int r_in_block = it * 8 + wv * 2 + half_id;
+        const int t = t0 + r_in_block;
+        const bool valid = t < g.T;
+
+        // ---- chunk, norm, flag, row scale --------------------------------------------------
+        half4_t xv = valid ? load_chunk(base + (int64_t)t * g.st) : half4_t{0, 0, 0, 0};
+        const double r2 = chunk_norm2(xv);
+        const bool flagged = valid && (r2 > thr);
+        const unsigned long long ballot = __ballot(flagged);
+        const uint32_t word = half_id ? (uint32_t)(ballot >> 32) : (uint32_t)ballot;
+
+        double rmax = flagged ? 0.0 : r2;  // max over the 32 lanes of the row
+#pragma unroll
+        for (int d = 16; d >= 1; d >>= 1) {
+            double o = __shfl_xor(rmax, d, 64);
+            rmax = o > rmax ? o : rmax;
+        }
+        const uint16_t sigma16 = double_to_half_rne_sat(sqrt(rmax));
+        const double sigma = half_bits_to_double(sigma16);
+
+        int rq = 0;
+        if (sigma != 0.0 && r2 != 0.0) {
+            double q = rint((sqrt(r2) * Lq) / sigma);
+            q = q < 0.0 ? 0.0 : (q > Lq ? Lq : q);
+            rq = (int)q;
+        }
+
+        // ---- unit direction (fp32) and its transpose into MFMA B operands --------------------
+        float u0 = 0.f, u1 = 0.f, u2 = 0.f, u3 = 0.f;
+        if (r2 != 0.0) {
+            float inv = 1.0f / sqrtf((float)r2);
+            u0 = (float)xv[0] * inv;
+            u1 = (float)xv[1] * inv;
+            u2 = (float)xv[2] * inv;
+            u3 = (float)xv[3] * inv;
+        }
+        __syncthreads();  // previous iteration's readers of ubuf / pack are done
+        *reinterpret_cast<float4_t *>(my_ubuf + 4 * lane) = float4_t{u0, u1, u2, u3};
+        if (lane < 2 * 32)
+            my_pack[lane] = 0;
+        __syncthreads();
+        float bop[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            bop[j] = my_ubuf[4 * (16 * j + (lane & 15)) + (lane >> 4)];
+
+        // ---- exhaustive search over the secondaries -------------------------------------------
+        float best[4] = {-1.f, -1.f, -1.f, -1.f};
+        int bsb[4] = {0, 0, 0, 0};
+        const float4_t zero4 = {0.f, 0.f, 0.f, 0.f};
+        for (int sb = 0; sb < g.S4; ++sb) {
+            const float aop = amat[sb * 64 + lane];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                float4_t v = __builtin_amdgcn_mfma_f32_16x16x4f32(aop, bop[j], zero4, 0, 0, 0);
+                float a0 = fabsf(v[0]), a1 = fabsf(v[1]), a2 = fabsf(v[2]), a3 = fabsf(v[3]);
+                float hs = 0.5f * (((a0 + a1) + a2) + a3);
+                float m = fmaxf(fmaxf(fmaxf(fmaxf(a0, a1), a2), a3), hs);  // two v_max3
+                if (m > best[j]) {
+                    best[j] = m;
+                    bsb[j] = sb;
+                }
+            }
+        }
+
+        // ---- reduce over the 4 lanes that share a chunk, hand the winner to the owner lane ------
+        int s_mine = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float bj = best[j];
+            int sj = 4 * bsb[j] + (lane >> 4);
+#pragma unroll
+            for (int d = 16; d <= 32; d <<= 1) {
+                float ob = __shfl_xor(bj, d, 64);
+                int os = __shfl_xor(sj, d, 64);
+                if (ob > bj || (ob == bj && os < sj)) {
+                    bj = ob;
+                    sj = os;
+                }
+            }
+            int got = __shfl(sj, lane & 15, 64);
+            if ((lane >> 4) == j)
+                s_mine = got;
+        }
+        if (s_mine >= g.S)
+            s_mine = g.S - 1;
+
+        // ---- primary for the winning secondary, code word --------------------------------------
+        uint32_t code = 0;
+        if (!flagged && r2 != 0.0) {
+            const float *q = secl + 4 * s_mine;
+            float a = q[0], bq = q[1], cq = q[2], d = q[3];
+            float v0 = fmaf(d, u3, fmaf(cq, u2, fmaf(bq, u1, a * u0)));
+            float v1 = fmaf(cq, u3, fmaf(-d, u2, fmaf(a, u1, -bq * u0)));
+            float v2 = fmaf(-bq, u3, fmaf(a, u2, fmaf(d, u1, -cq * u0)));
+            float v3 = fmaf(a, u3, fmaf(bq, u2, fmaf(-cq, u1, -d * u0)));
+            float sc;
+            int p = nearest_primary(v0, v1, v2, v3, sc);
+            uint32_t k = (uint32_t)(p * g.S + s_mine);
+            code = ((uint32_t)rq << g.w_idx) | k;
+        }
+
+        // ---- pack the row: chunk c at bits [c*w, (c+1)*w) -----------------------------------------
+        {
+            uint32_t bitpos = (uint32_t)c * g.w;
+            uint32_t d0 = bitpos >> 5, sh = bitpos & 31;
+            uint32_t *rowp = my_pack + half_id * 32;
+            if (code) {
+                atomicOr(&rowp[d0], code << sh);
+                if (sh + g.w > 32)
+                    atomicOr(&rowp[d0 + 1], code >> (32 - sh));
+            }
+        }
+        __syncthreads();
+        if (valid) {
+            const int64_t R = row0 + t;
+            if (c < g.w)
+                enc.codes[R * g.w + c] = my_pack[half_id * 32 + c];
+            if (c == 0) {
+                enc.sigma[R] = sigma16;
+            }
+            if (flagged) {
+                uint64_t pos = (uint64_t)roff[r_in_block] + __popc(word & ((1u << c) - 1u));
+                if (pos < outlier_capacity)
+                    *reinterpret_cast<uint2 *>(enc.outliers + 4 * pos) = __builtin_bit_cast(uint2, xv);
+            }
+        }
+    }
+}
+
+hipError_t launch_search(const _Float16 *x, const float *sec, const Geometry &g, const Workspace &ws,
+                         const EncodedPtrs &enc, uint64_t outlier_capacity, hipStream_t stream)
+{
+    dim3 grid((g.T + kSearchRows - 1) / kSearchRows, g.B * g.H);
+    size_t lds = ((size_t)g.S4 * 64 + (size_t)g.S4 * 16 + 4 * 64 * 4) * sizeof(float) +
+                 (4 * 2 * 32 + kSearchRows) * sizeof(uint32_t);
+    hipLaunchKernelGGL(k_search, grid, dim3(kThreads), lds, stream, x, sec, g, ws, enc,
+                       outlier_capacity);
+    return hipGetLastError();
+}
+
+}  // namespace hqmq

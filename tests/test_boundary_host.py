@@ -1,0 +1,131 @@
+"""Host-side checks of the C-ABI boundary that need no GPU: the library loads, exports every
+symbol the header declares, validates its arguments, sizes its buffers, and builds the same
+codebooks as the oracle's independent generator."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2605_27646_amd as hq
+from paper_2605_27646_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(hq.library_path()):
+        from paper_2605_27646_amd import build
+        build.build()
+    return binding._load()
+
+
+def test_library_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "hqmq.h")).read()
+    declared = set(re.findall(r"^(?:int32_t|void|uint64_t)\s+(hqmq_\w+)\s*\(", header, re.M))
+    assert declared == {"hqmq_build_codebooks", "hqmq_sizes", "hqmq_encode", "hqmq_decode", "hqmq_last_hip_error"}
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_struct_layouts_match_header():
+    assert C.sizeof(hq.HqmqParams) == 56
+    assert C.sizeof(hq.HqmqSizeInfo) == 88
+    assert C.sizeof(binding._Encoded) == 56
+
+
+def _params(**kw):
+    d = dict(B=1, H=8, T=1024, D=128, stride_b=8 * 1024 * 128, stride_h=1024 * 128, stride_t=128, S=256,
+             b_r=6, C=3.0, flags=0)
+    d.update(kw)
+    return hq.HqmqParams(**d)
+
+
+def test_sizes_of_the_headline_workload(lib):
+    info = hq.hqmq_sizes(_params(T=32768, stride_b=8 * 32768 * 128, stride_h=32768 * 128))
+    assert info.n_rows == 8 * 32768
+    assert (info.index_bits, info.code_bits) == (13, 19)           # ceil(log2(24*256)) + 6
+    assert info.code_bytes == info.n_rows * 19 * 4
+    assert info.sigma_bytes == info.n_rows * 2 and info.flag_bytes == info.n_rows * 4
+    assert info.row_off_bytes == (info.n_rows + 1) * 4 and info.n_outliers_bytes == 36
+    assert info.outlier_capacity_max == 8 * (32768 * 32 // 2)      # at most half of a head lies above its median
+    assert info.outlier_bytes_max == info.outlier_capacity_max * 8
+    assert 0 < info.workspace_bytes < 1 << 20
+    # stored bits per element agree with the accounting of Sec. 3 taken with ceil(log2(24 S))
+    stored = (info.code_bytes + info.sigma_bytes) * 8 / (info.n_rows * 128)
+    assert stored == oracle.bits_per_element(256, 6, 128, stored=True)
+    assert hq.hqmq_sizes(_params(C=0.5)).outlier_capacity_max == 8 * 1024 * 32
+    assert hq.hqmq_sizes(_params(flags=hq.HQMQ_FLAG_NO_OUTLIERS)).outlier_capacity_max == 0
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(B=0), -1), (dict(T=-3), -1), (dict(stride_t=126), -1), (dict(stride_t=64), -1), (dict(stride_h=-4), -1),
+    (dict(D=64), -2), (dict(D=130), -2), (dict(S=0), -2), (dict(S=513), -2), (dict(b_r=0), -2), (dict(b_r=9), -2),
+    (dict(C=0.0), -2), (dict(C=float("nan")), -2), (dict(C=float("inf")), -2), (dict(B=70000, H=1), -2),
+    (dict(T=1 << 27), -2),
+])
+def test_sizes_rejects_bad_params(lib, kw, code):
+    with pytest.raises(hq.HqmqError) as ei:
+        hq.hqmq_sizes(_params(**kw))
+    assert ei.value.code == code
+    info = hq.HqmqSizeInfo()
+    assert lib.hqmq_sizes(None, C.byref(info)) == -1
+    assert lib.hqmq_sizes(C.byref(_params()), None) == -1
+
+
+def test_encode_decode_reject_bad_arguments_without_touching_the_gpu(lib):
+    p = _params()
+    info = hq.hqmq_sizes(p)
+    good = binding._Encoded(0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000)
+    ws = int(info.workspace_bytes)
+    enc = lib.hqmq_encode
+    assert enc(None, 0x1000, 0x1000, C.byref(good), 0, 0x1000, ws, None) == -1
+    assert enc(C.byref(p), None, 0x1000, C.byref(good), 0, 0x1000, ws, None) == -1          # null x
+    assert enc(C.byref(p), 0x1004, 0x1000, C.byref(good), 0, 0x1000, ws, None) == -1        # misaligned x
+    assert enc(C.byref(p), 0x1000, 0x1004, C.byref(good), 0, 0x1000, ws, None) == -1        # misaligned codebook
+    assert enc(C.byref(p), 0x1000, 0x1000, None, 0, 0x1000, ws, None) == -1                 # null struct
+    assert enc(C.byref(p), 0x1000, 0x1000, C.byref(good), 0, 0x1010, ws, None) == -1        # misaligned workspace
+    assert enc(C.byref(p), 0x1000, 0x1000, C.byref(good), 0, 0x1000, ws - 1, None) == -3    # workspace too small
+    bad = binding._Encoded(0x1000, 0x1000, None, 0x1000, 0x1000, 0x1000, 0x1000)
+    assert enc(C.byref(p), 0x1000, 0x1000, C.byref(bad), 0, 0x1000, ws, None) == -1         # null member
+    bad = binding._Encoded(0x1002, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000)
+    assert enc(C.byref(p), 0x1000, 0x1000, C.byref(bad), 0, 0x1000, ws, None) == -1         # misaligned member
+    assert enc(C.byref(_params(D=64)), 0x1000, 0x1000, C.byref(good), 0, 0x1000, ws, None) == -2
+    dec = lib.hqmq_decode
+    assert dec(C.byref(p), C.byref(good), 0, None, 0x1000, None) == -1
+    assert dec(C.byref(p), C.byref(good), 0, 0x1000, 0x1004, None) == -1
+    assert dec(C.byref(p), None, 0, 0x1000, 0x1000, None) == -1
+    assert dec(C.byref(_params(S=600)), C.byref(good), 0, 0x1000, 0x1000, None) == -2
+    assert lib.hqmq_last_hip_error() == 0
+
+
+def test_build_codebooks_matches_the_oracles_generator(lib):
+    for seed in (0, 1, 7, 42, 1337):
+        mine = hq.hqmq_build_codebooks(seed, 3, 4, 48).numpy()
+        ref = oracle.build_codebooks(seed, 3, 4, 48)
+        ulp = np.abs(mine.view(np.int32).astype(np.int64) - ref.view(np.int32).astype(np.int64))
+        assert ulp.max() <= 2
+    # entry (layer, role, head, s) depends only on the seed and its linear index
+    a = hq.hqmq_build_codebooks(5, 2, 4, 16)
+    b = hq.hqmq_build_codebooks(5, 4, 4, 16)
+    assert torch.equal(a, b[:2])
+    assert np.abs(np.linalg.norm(a.numpy().astype(np.float64), axis=-1) - 1).max() < 1e-7
+    with pytest.raises(hq.HqmqError):
+        hq.hqmq_build_codebooks(0, 0, 4, 16)
+    assert lib.hqmq_build_codebooks(0, 1, 1, 4, None) == -1
+    buf = (C.c_float * 16)()
+    assert lib.hqmq_build_codebooks(0, 1, 1, 3000, buf) == -2
+
+
+def test_binding_refuses_host_tensors(lib):
+    x = torch.zeros(1, 2, 4, 128, dtype=torch.float16)
+    p = hq.params_for(x, 16)
+    assert (p.stride_b, p.stride_h, p.stride_t) == (2 * 4 * 128, 4 * 128, 128)
+    with pytest.raises(ValueError):
+        hq.hqmq_encode(p, x, torch.zeros(2, 16, 4), None, None)
+    with pytest.raises(ValueError):
+        hq.params_for(x[..., ::2], 16)

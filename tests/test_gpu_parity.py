@@ -1,0 +1,233 @@
+"""GPU parity: the HIP library (through its C ABI) against the fp64 CPU oracle, element by
+element, on seeded synthetic KV tensors.  Bit-exact on outlier masks, offsets, payload, scales
+and radius codes; codeword indices identical outside near-ties (score gap < 1e-6), which are
+counted; reconstruction within 1e-3 of the chunk norm."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2605_27646_amd as hq
+import workloads
+from gpu_util import (compare_decode, compare_encode, gpu_decode, gpu_encode, upload_encoded)
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def _bits(x: torch.Tensor) -> np.ndarray:
+    return x.contiguous().cpu().numpy().view(np.uint16)
+
+
+def _sec(seed, H, S, layer=0, role=0):
+    cb = hq.hqmq_build_codebooks(seed, layer + 1, H, S)[layer, role].contiguous()
+    return cb, cb.numpy()
+
+
+def _roundtrip(x_cpu, S, b_r=6, Cmul=3.0, seed=0, rows=None, check_decode=True, flags=0):
+    """Encode on both sides, compare; decode both encodings on both sides, compare."""
+    B, H, T, D = x_cpu.shape
+    sec_t, sec = _sec(seed, H, S)
+    xb = _bits(x_cpu)
+    e = oracle.encode(xb, sec, b_r=b_r, Cmul=Cmul, use_outliers=not (flags & hq.HQMQ_FLAG_NO_OUTLIERS),
+                      rows=rows)
+    x_dev, sec_dev = x_cpu.to(DEV), sec_t.to(DEV)
+    g = gpu_encode(x_dev, sec_dev, b_r, Cmul, flags)
+    stats = compare_encode(g, e, xb, sec)
+    if check_decode:
+        # (1) identical bytes, oracle-encoded (needs every row searched)
+        if rows is None:
+            want, r_hat = oracle.decode(e.codes, e.sigma, e.flags, e.row_off, e.outliers, sec, B, H, T, b_r, True)
+            got = gpu_decode(g.params, upload_encoded(e, DEV), sec_dev, x_dev)
+            stats["decode_rel_err_oracle_bytes"] = compare_decode(got, want, r_hat, e.flag)
+        # (2) identical bytes, GPU-encoded
+        want, r_hat = oracle.decode(g.codes, g.sigma, g.flags, g.row_off, g.outliers, sec, B, H, T, b_r, True)
+        got = gpu_decode(g.params, g.bufs, sec_dev, x_dev)
+        stats["decode_rel_err_gpu_bytes"] = compare_decode(got, want, r_hat, e.flag)
+    print(stats, flush=True)
+    return stats, e, g
+
+
+def _lognormal_tensor(B, H, T, seed, sigma_g=0.5):
+    wl = workloads.Workload("t", 100 + seed, 1, B, H, T, 128, 16, sigma_g=sigma_g)
+    return workloads.make_tensor(wl, 0, 0, "cpu")
+
+
+# ---------------------------------------------------------------------------------------
+# small shapes spanning several tiles and ragged tails
+# ---------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("B,H,T,S,b_r", [
+    (1, 1, 8, 16, 6),          # one partial block
+    (1, 2, 333, 16, 6),        # ragged: not a multiple of 2, 8, 64 or 256 rows
+    (2, 3, 77, 24, 4),         # batch > 1, S not a power of two (paper's s24_r4)
+    (1, 8, 1024, 16, 6),       # the Tiny config shape
+    (1, 2, 515, 64, 3),        # several scan blocks per segment, b_r = 3
+    (1, 1, 130, 5, 6),         # S not a multiple of 4 (padded MFMA rows)
+    (1, 1, 64, 1, 6),          # S = 1: the codebook is a rotated 24-cell
+    (1, 1, 96, 192, 6),        # paper's s192_r6
+    (1, 1, 70, 256, 6),        # S of the headline workload
+    (1, 1, 40, 512, 8),        # largest supported S and b_r
+])
+def test_encode_decode_parity_small(B, H, T, S, b_r):
+    print(f"case B={B} H={H} T={T} S={S} b_r={b_r}", flush=True)
+    x = _lognormal_tensor(B, H, T, seed=T + S, sigma_g=1.0)
+    stats, e, g = _roundtrip(x, S, b_r)
+    assert stats["outliers"] > 0 or T < 16
+
+
+def test_tiny_config_full():
+    wl = workloads.WORKLOADS["tiny"]
+    for role in (0, 1):
+        print(f"tiny role={role}", flush=True)
+        x = workloads.make_tensor(wl, 0, role, "cpu")
+        sec_t = hq.hqmq_build_codebooks(0, 1, wl.H, wl.S)[0, role].contiguous()
+        sec = sec_t.numpy()
+        xb = _bits(x)
+        e = oracle.encode(xb, sec, b_r=wl.b_r, Cmul=wl.C)
+        g = gpu_encode(x.to(DEV), sec_t.to(DEV), wl.b_r, wl.C)
+        stats = compare_encode(g, e, xb, sec)
+        print(stats, flush=True)
+        assert 0.003 < stats["outliers"] / e.flag.size < 0.03
+
+
+@pytest.mark.parametrize("name", ["mistral7b_outlier", "qwen25_7b_heavy", "llama3_70b_128k"])
+def test_outlier_heavy_laws_reduced_length(name):
+    """The hot-channel / heavy-tailed / wide-lognormal value laws at a reduced sequence length
+    (the full-size shapes are covered by the sampled test below)."""
+    wl = workloads.WORKLOADS[name].with_T(700 if name != "mistral7b_outlier" else 200)
+    print(f"law {name} T={wl.T}", flush=True)
+    x = workloads.make_tensor(wl, 0, 0, "cpu")
+    stats, e, g = _roundtrip(x, wl.S, wl.b_r)
+    assert stats["outliers"] / e.flag.size > 0.01
+
+
+# ---------------------------------------------------------------------------------------
+# full-size tensor in the launch configuration the bench times
+# ---------------------------------------------------------------------------------------
+
+def test_llama3_8b_32k_layer_sampled():
+    """One full [1, 8, 32768, 128] tensor with S = 256: everything that is O(n) in the oracle
+    (norms, medians, masks, offsets, payload, scales) is compared on all rows; the exhaustive
+    search on a sample of token rows (first, last, seeded random) of every head."""
+    wl = workloads.WORKLOADS["llama3_8b_32k"]
+    x = workloads.make_tensor(wl, 3, 0, "cpu")
+    rows = workloads.sample_rows(wl, 48, 48, 160, seed=1).numpy()
+    print(f"llama3 8b 32k layer 3 K: searching {int(rows.sum())} of {rows.size} rows on the CPU", flush=True)
+    stats, e, g = _roundtrip(x, wl.S, wl.b_r, rows=rows, check_decode=True)
+    assert 0.005 < stats["outliers"] / e.flag.size < 0.03
+    assert stats["near_ties"] < 1e-3 * stats["chunks"]
+
+
+# ---------------------------------------------------------------------------------------
+# degenerate inputs and the boundary's data-dependent behaviour
+# ---------------------------------------------------------------------------------------
+
+def test_single_token_row():
+    x = _lognormal_tensor(1, 2, 1, seed=5)
+    _roundtrip(x, 16)
+
+
+def test_all_zero_and_constant_tensors():
+    z = torch.zeros(1, 2, 40, 128, dtype=torch.float16)
+    stats, e, g = _roundtrip(z, 16)
+    assert stats["outliers"] == 0 and not g.codes.any() and not g.sigma.any()
+    c = torch.full((1, 2, 40, 128), 0.5, dtype=torch.float16)
+    stats, e, g = _roundtrip(c, 16)
+    assert stats["outliers"] == 0                      # equal norms: nothing exceeds 3x the median
+    half = torch.zeros(1, 1, 64, 128, dtype=torch.float16)
+    half[:, :, :, :40] = 1.0                            # median norm 0: every non-zero chunk is flagged
+    stats, e, g = _roundtrip(half, 16)
+    assert stats["outliers"] == 64 * 10
+
+
+def test_exact_tie_structured_input():
+    """Chunks like (a, a, 0, 0) sit on the boundary between several codewords when the
+    secondary is the identity; whichever the GPU picks must score as the oracle's best."""
+    x = torch.zeros(1, 1, 16, 128, dtype=torch.float16)
+    x[..., 0::4] = 1.0
+    x[..., 1::4] = 1.0
+    sec = np.array([[[1, 0, 0, 0]]], np.float32)
+    xb = _bits(x)
+    e = oracle.encode(xb, sec)
+    g = gpu_encode(x.to(DEV), torch.from_numpy(sec).to(DEV))
+    stats = compare_encode(g, e, xb, sec)
+    k, _ = oracle.unpack_rows(g.codes, 1, 6)
+    assert (k == 0).all()                               # lowest index of the six tied vertices
+    assert stats["near_ties"] == 16 * 32
+
+
+def test_extreme_magnitudes():
+    x = _lognormal_tensor(1, 2, 64, seed=9).float()
+    x[0, 0, :8] *= 6e-6                                 # subnormal fp16 territory
+    x[0, 1, :8] = x[0, 1, :8].sign() * 65504.0          # largest finite halves: sigma saturates
+    x[0, 1, 8:16] *= 3000.0
+    _roundtrip(x.clamp(-65504, 65504).half(), 16)
+
+
+def test_no_outliers_flag():
+    x = _lognormal_tensor(1, 2, 100, seed=11, sigma_g=1.5)
+    stats, e, g = _roundtrip(x, 16, flags=hq.HQMQ_FLAG_NO_OUTLIERS)
+    assert stats["outliers"] == 0 and not g.flags.any()
+
+
+def test_other_multiplier():
+    x = _lognormal_tensor(1, 2, 128, seed=12)
+    stats, _, _ = _roundtrip(x, 16, Cmul=1.5)
+    assert stats["outliers"] > 100
+
+
+def test_outlier_overflow_reports_true_counts():
+    x = _lognormal_tensor(1, 2, 256, seed=13, sigma_g=1.0)
+    sec_t, sec = _sec(0, 2, 16)
+    xb = _bits(x)
+    e = oracle.encode(xb, sec)
+    total = int(e.n_out[-1])
+    assert total > 10
+    g = gpu_encode(x.to(DEV), sec_t.to(DEV), outlier_capacity=total // 2)
+    assert g.status & hq.HQMQ_STATUS_OUTLIER_OVERFLOW
+    assert np.array_equal(g.n_out, e.n_out) and np.array_equal(g.row_off, e.row_off)
+    assert np.array_equal(g.outliers, e.outliers[: total // 2])       # the prefix that fits is right
+    # decoding the truncated encoding stays in bounds: dropped outliers come back as zeros
+    out = gpu_decode(g.params, g.bufs, sec_t.to(DEV), x.to(DEV)).reshape(-1, 32, 4)
+    fl = e.flag.astype(bool)
+    pos = np.cumsum(fl.reshape(-1)).reshape(fl.shape) - 1
+    assert not out[fl & (pos >= total // 2)].any()
+    exact = gpu_encode(x.to(DEV), sec_t.to(DEV), outlier_capacity=total)
+    assert exact.status == 0 and np.array_equal(exact.outliers, e.outliers)
+
+
+def test_strided_input_and_output():
+    """A cache stored [B, T, H, D] passes unchanged through the strides."""
+    B, H, T = 2, 3, 50
+    x = _lognormal_tensor(B, H, T, seed=14)
+    sec_t, sec = _sec(0, H, 16)
+    e = oracle.encode(_bits(x), sec)
+    x_bthd = x.permute(0, 2, 1, 3).contiguous().to(DEV)           # memory order [B, T, H, D]
+    view = x_bthd.permute(0, 2, 1, 3)                               # logical [B, H, T, D]
+    assert not view.is_contiguous()
+    g = gpu_encode(view, sec_t.to(DEV))
+    compare_encode(g, e, _bits(x), sec)
+    out = torch.zeros_like(x_bthd).permute(0, 2, 1, 3)
+    hq.hqmq_decode(hq.params_for(out, 16), g.bufs, sec_t.to(DEV), out)
+    torch.cuda.synchronize()
+    want, r_hat = oracle.decode(g.codes, g.sigma, g.flags, g.row_off, g.outliers, sec, B, H, T, 6, True)
+    compare_decode(out.contiguous().cpu().numpy().view(np.uint16), want, r_hat, e.flag)
+
+
+def test_deterministic_bytes():
+    x = _lognormal_tensor(1, 4, 300, seed=15).to(DEV)
+    sec_t, _ = _sec(0, 4, 64)
+    a = gpu_encode(x, sec_t.to(DEV))
+    b = gpu_encode(x, sec_t.to(DEV))
+    for f in ("codes", "sigma", "flags", "row_off", "n_out", "outliers"):
+        assert np.array_equal(getattr(a, f), getattr(b, f)), f
+
+
+def test_codebooks_of_library_and_oracle_agree():
+    for seed in (0, 1, 7, 42, 1337):
+        lib = hq.hqmq_build_codebooks(seed, 2, 4, 64).numpy()
+        ora = oracle.build_codebooks(seed, 2, 4, 64)
+        ulp = np.abs(lib.view(np.int32).astype(np.int64) - ora.view(np.int32).astype(np.int64))
+        assert ulp.max() <= 2
