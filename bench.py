@@ -1,0 +1,206 @@
+#!/usr/bin/env python3
+"""HQMQ encode / decode throughput on one MI355X.
+
+A step is one pass of the whole hot path over the workload: every (layer, role) tensor is
+encoded (median select, mask, scan, search + quantise + pack) and then decoded, inputs and
+outputs resident in HBM.  Prints ONE JSON line: whole-path elems/s, the encode / decode
+split, the roofline position of the dominant kernel (the MFMA search) and of the decode
+kernel, measured with HIP events on the launch stream, and the CPU oracle timed on a bounded
+sample of the same workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--layers N]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "HQMQ encode/decode elems/sec at 1 GPU; % of fp32-compute (enc) / HBM (dec) roofline"
+PEAK_FP32_TFLOPS = 157.3     # MI355X dense fp32 matrix (and packed vector) peak
+PEAK_HBM_GBS = 8000.0        # MI355X HBM3E peak
+
+
+def search_flops_per_chunk(S: int) -> float:
+    """Flops the implemented search formulation spends per chunk: per secondary one 4x4
+    matrix-vector product on the MFMA unit (16 FMA = 32 flop) and the closed-form nearest
+    24-cell vertex on the VALU (3 adds + 1 multiply); S rounded up to the MFMA tile of 4."""
+    s4 = (S + 3) // 4 * 4
+    return 36.0 * s4
+
+
+def decode_bytes_per_chunk(w: int, p_out: float) -> float:
+    """Algorithmic HBM bytes of decode per chunk: w bits of code, 1 flag bit, 1/32 of a 2-byte
+    scale and of a 4-byte offset, 8 bytes of payload for a flagged chunk; 8 bytes written."""
+    return w / 8.0 + 1.0 / 8.0 + 2.0 / 32.0 + 4.0 / 32.0 + 8.0 * p_out + 8.0
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="llama3_8b_32k")
+    ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = the workload's)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py measures the single-GPU HQMQ path; the units of work (layer, kv head, role) are "
+              "independent, so more GPUs only replicate it. Run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2605_27646_amd as hq
+    import workloads
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    wl = workloads.WORKLOADS[args.workload]
+    layers = args.layers or wl.layers
+    tensors = [(l, r) for l in range(layers) for r in (0, 1)]
+
+    # ---- resident inputs, codebooks, encoded buffers, outputs --------------------------------
+    sec_all = hq.hqmq_build_codebooks(0, layers, wl.H, wl.S).to(dev)
+    xs, encs, outs = [], [], []
+    params = None
+    for (l, r) in tensors:
+        x = workloads.make_tensor(wl, l, r, dev)
+        params = hq.params_for(x, wl.S, wl.b_r, wl.C)
+        xs.append(x)
+        encs.append(hq.alloc_encoded(params, dev))
+        outs.append(torch.empty_like(x))
+    ws = hq.alloc_workspace(params, dev)
+    info = hq.hqmq_sizes(params)
+    torch.cuda.synchronize()
+
+    n_t = len(tensors)
+    elems_per_step = wl.elems_per_tensor * n_t
+    chunks_per_tensor = wl.elems_per_tensor // 4
+
+    def new_events(n):
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(n)]
+        for e in evs:
+            e.record()          # creates the underlying hipEvent_t
+        return evs
+
+    def run_step(ev_enc=None, ev_dec=None):
+        for i, (l, r) in enumerate(tensors):
+            pe = ev_enc[4 * i: 4 * i + 4] if ev_enc is not None else [None] * 4
+            hq.hqmq_encode_timed(params, xs[i], sec_all[l, r], encs[i], ws, pe)
+        if ev_dec is not None:
+            ev_dec[0].record()
+        for i, (l, r) in enumerate(tensors):
+            hq.hqmq_decode(params, encs[i], sec_all[l, r], outs[i])
+            if ev_dec is not None:
+                ev_dec[1 + i].record()
+
+    for _ in range(args.warmup):
+        run_step()
+    torch.cuda.synchronize()
+
+    ev_enc = [new_events(4 * n_t) for _ in range(args.steps)]
+    ev_dec = [new_events(1 + n_t) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        run_step(ev_enc[k], ev_dec[k])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+
+    # ---- per-phase device times from the events ----------------------------------------------
+    t_sel = t_mask = t_search = t_enc = t_dec = 0.0
+    for k in range(args.steps):
+        for i in range(n_t):
+            e0, e1, e2, e3 = ev_enc[k][4 * i: 4 * i + 4]
+            t_sel += e0.elapsed_time(e1)
+            t_mask += e1.elapsed_time(e2)
+            t_search += e2.elapsed_time(e3)
+            t_enc += e0.elapsed_time(e3)
+        t_dec += ev_dec[k][0].elapsed_time(ev_dec[k][n_t])
+    launches = args.steps * n_t
+    search_ms = t_search / launches
+    decode_ms = t_dec / launches
+    enc_ms_step = t_enc / args.steps
+    dec_ms_step = t_dec / args.steps
+
+    # outlier fraction actually seen (drives the decode byte count)
+    n_out = sum(int(e.n_outliers[-1].item()) for e in encs)
+    p_out = n_out / (chunks_per_tensor * n_t)
+    status = max(int(e.status.item()) for e in encs)
+
+    flops_launch = search_flops_per_chunk(wl.S) * chunks_per_tensor
+    search_tflops = flops_launch / (search_ms * 1e-3) / 1e12
+    dec_bytes_launch = decode_bytes_per_chunk(info.code_bits, p_out) * chunks_per_tensor
+    dec_gbs = dec_bytes_launch / (decode_ms * 1e-3) / 1e9
+
+    result = {
+        "metric": METRIC,
+        "value": elems_per_step / (ms_per_step * 1e-3),
+        "unit": "elems/s (one encode + one decode of every element)",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "layers": layers, "B": wl.B, "kv_heads": wl.H, "T": wl.T, "D": wl.D,
+                   "S": wl.S, "b_r": wl.b_r, "C": wl.C, "tensors_per_step": n_t,
+                   "elems_per_step": elems_per_step},
+        "encode_elems_per_s": elems_per_step / (enc_ms_step * 1e-3),
+        "decode_elems_per_s": elems_per_step / (dec_ms_step * 1e-3),
+        "encode_ms_per_step": enc_ms_step,
+        "decode_ms_per_step": dec_ms_step,
+        "encode_phase_ms_per_tensor": {"median_select": t_sel / launches, "mask_scan": t_mask / launches,
+                                       "search_quantise_pack": search_ms},
+        "codeword_scores_per_s": 24.0 * wl.S * chunks_per_tensor / (search_ms * 1e-3),
+        "outlier_fraction": p_out,
+        "status_bits": status,
+        "bits_per_element_stored": (encs[0].nbytes() - encs[0].outliers.numel() * 2 + 8 * n_out / n_t) * 8
+        / wl.elems_per_tensor,
+        "roofline": {"kernel": "k_search", "bound": "mfma", "achieved": search_tflops, "peak": PEAK_FP32_TFLOPS,
+                     "unit": "TFLOP/s", "frac": search_tflops / PEAK_FP32_TFLOPS, "traffic": None,
+                     "flops_per_chunk": search_flops_per_chunk(wl.S), "formulation": "W_min (36 S flop/chunk)",
+                     "avg_launch_ms": search_ms},
+        "roofline_decode": {"kernel": "k_decode", "bound": "hbm", "achieved": dec_gbs, "peak": PEAK_HBM_GBS,
+                            "unit": "GB/s", "frac": dec_gbs / PEAK_HBM_GBS, "traffic": None,
+                            "bytes_per_chunk": decode_bytes_per_chunk(info.code_bits, p_out),
+                            "avg_launch_ms": decode_ms},
+    }
+
+    # ---- the oracle on the host cores, bounded sample of the same workload --------------------
+    if not args.no_cpu_baseline:
+        import oracle
+        Ts = min(args.cpu_sample_tokens, wl.T)
+        xs_cpu = xs[0][:, :, :Ts].contiguous().cpu().numpy().view(np.uint16)
+        sec = sec_all[0, 0].cpu().numpy()
+        threads = oracle.max_threads()
+        c0 = time.perf_counter()
+        e = oracle.encode(xs_cpu, sec, b_r=wl.b_r, Cmul=wl.C)
+        c1 = time.perf_counter()
+        oracle.decode(e.codes, e.sigma, e.flags, e.row_off, e.outliers, sec, wl.B, wl.H, Ts, wl.b_r)
+        c2 = time.perf_counter()
+        result["cpu_baseline"] = {
+            "value": xs_cpu.size / (c2 - c0), "unit": "elems/s (one encode + one decode of every element)",
+            "cores": threads, "kind": "oracle",
+            "sample": f"layer 0 K, first {Ts} token rows of all {wl.H} heads ({xs_cpu.size} elems), S={wl.S}",
+            "encode_s": c1 - c0, "decode_s": c2 - c1,
+            "encode_elems_per_s": xs_cpu.size / (c1 - c0), "decode_elems_per_s": xs_cpu.size / (c2 - c1)}
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

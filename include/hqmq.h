@@ -84,6 +84,7 @@ typedef struct hqmq_size_info {
  *   row_off    uint32 [n_rows + 1]  number of outliers in all earlier rows (exclusive prefix);
  *                                   last entry = total
  *   outliers   fp16   [cap][4]      the flagged chunks verbatim, ascending linear chunk index
+ *                                   (may be NULL when the capacity passed is 0)
  *   n_outliers uint32 [H + 1]       outliers per head, then the total (true counts even on
  *                                   overflow)
  *   status     uint32 [1]           HQMQ_STATUS_* bits, written by hqmq_encode             */
@@ -132,6 +133,15 @@ int32_t hqmq_sizes(const hqmq_params *params, hqmq_size_info *out);
 int32_t hqmq_encode(const hqmq_params *params, const void *x_dev, const float *sec_dev,
                     const hqmq_encoded *enc, uint64_t outlier_capacity, void *workspace_dev,
                     uint64_t workspace_bytes, void *stream);
+
+/* hqmq_encode with measurement marks (the per-kernel figures of the paper's latency tables,
+ * App. E / Sec. 4.10, are quoted per call; this gives the same split for the encode phases).
+ * phase_events: HOST array of 4 caller-created hipEvent_t (any entry, or the array, may be
+ * NULL), recorded on `stream`: [0] before the first kernel, [1] after the median select,
+ * [2] after mask + scan, [3] after the search kernel.  Otherwise identical to hqmq_encode. */
+int32_t hqmq_encode_timed(const hqmq_params *params, const void *x_dev, const float *sec_dev,
+                          const hqmq_encoded *enc, uint64_t outlier_capacity, void *workspace_dev,
+                          uint64_t workspace_bytes, void *stream, void *const *phase_events);
 
 /* Decode one tensor (Alg. 1 "Decode", App. D "Decode"): x_hat = r_hat * (q_p * q_s) with
  * r_hat = r_q * sigma / (2^b_r - 1) and the Hamilton product taken at decode time, rounded to

@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     hqmq_build_codebooks,
     hqmq_decode,
     hqmq_encode,
+    hqmq_encode_timed,
     hqmq_last_hip_error,
     hqmq_sizes,
     library_path,

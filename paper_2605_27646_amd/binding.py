@@ -67,6 +67,8 @@ def _load():
         lib.hqmq_encode.restype = C.c_int32
         lib.hqmq_encode.argtypes = [C.POINTER(HqmqParams), C.c_void_p, C.c_void_p, C.POINTER(_Encoded),
                                     C.c_uint64, C.c_void_p, C.c_uint64, C.c_void_p]
+        lib.hqmq_encode_timed.restype = C.c_int32
+        lib.hqmq_encode_timed.argtypes = lib.hqmq_encode.argtypes + [C.POINTER(C.c_void_p)]
         lib.hqmq_decode.restype = C.c_int32
         lib.hqmq_decode.argtypes = [C.POINTER(HqmqParams), C.POINTER(_Encoded), C.c_uint64, C.c_void_p,
                                     C.c_void_p, C.c_void_p]
@@ -172,6 +174,17 @@ def hqmq_encode(params: HqmqParams, x: torch.Tensor, sec: torch.Tensor, enc: Enc
                              enc.outlier_capacity, workspace.data_ptr(), workspace.numel(),
                              _stream_ptr(stream))
     _check(rc, "hqmq_encode")
+
+
+def hqmq_encode_timed(params: HqmqParams, x: torch.Tensor, sec: torch.Tensor, enc: EncodedBuffers,
+                      workspace: torch.Tensor, phase_events, stream=None) -> None:
+    """hqmq_encode that also records up to four torch.cuda.Event (already created, i.e.
+    recorded once) around its phases; entries may be None."""
+    handles = (C.c_void_p * 4)(*[None if e is None else e.cuda_event for e in phase_events])
+    rc = _load().hqmq_encode_timed(C.byref(params), x.data_ptr(), sec.data_ptr(), C.byref(enc.as_struct()),
+                                   enc.outlier_capacity, workspace.data_ptr(), workspace.numel(),
+                                   _stream_ptr(stream), handles)
+    _check(rc, "hqmq_encode_timed")
 
 
 def hqmq_decode(params: HqmqParams, enc: EncodedBuffers, sec: torch.Tensor, out: torch.Tensor,

@@ -90,10 +90,12 @@ static WorkspaceLayout workspace_layout(const Geometry &g)
 
 static bool misaligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) % a) != 0; }
 
-static int32_t check_encoded(const hqmq_encoded *e, bool need_counts)
+static int32_t check_encoded(const hqmq_encoded *e, bool need_counts, uint64_t outlier_capacity)
 {
-    if (!e || !e->codes || !e->sigma || !e->flags || !e->row_off || !e->outliers)
+    if (!e || !e->codes || !e->sigma || !e->flags || !e->row_off)
         return HQMQ_ERR_INVALID_ARG;
+    if (outlier_capacity > 0 && !e->outliers)
+        return HQMQ_ERR_INVALID_ARG;  // an empty list needs no storage
     if (need_counts && (!e->n_outliers || !e->status))
         return HQMQ_ERR_INVALID_ARG;
     if (misaligned(e->codes, 4) || misaligned(e->sigma, 2) || misaligned(e->flags, 4) ||
@@ -162,9 +164,9 @@ extern "C" int32_t hqmq_sizes(const hqmq_params *params, hqmq_size_info *out)
     return HQMQ_OK;
 }
 
-extern "C" int32_t hqmq_encode(const hqmq_params *params, const void *x_dev, const float *sec_dev,
-                               const hqmq_encoded *enc, uint64_t outlier_capacity,
-                               void *workspace_dev, uint64_t workspace_bytes, void *stream)
+static int32_t encode_impl(const hqmq_params *params, const void *x_dev, const float *sec_dev,
+                           const hqmq_encoded *enc, uint64_t outlier_capacity, void *workspace_dev,
+                           uint64_t workspace_bytes, void *stream, void *const *phase_events)
 {
     int32_t rc = check_params(params);
     if (rc != HQMQ_OK)
@@ -173,7 +175,7 @@ extern "C" int32_t hqmq_encode(const hqmq_params *params, const void *x_dev, con
         return HQMQ_ERR_INVALID_ARG;
     if (misaligned(x_dev, 8) || misaligned(sec_dev, 16) || misaligned(workspace_dev, 256))
         return HQMQ_ERR_INVALID_ARG;
-    rc = check_encoded(enc, true);
+    rc = check_encoded(enc, true, outlier_capacity);
     if (rc != HQMQ_OK)
         return rc;
     const Geometry g = make_geometry(params);
@@ -194,16 +196,47 @@ extern "C" int32_t hqmq_encode(const hqmq_params *params, const void *x_dev, con
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool no_outliers = (params->flags & HQMQ_FLAG_NO_OUTLIERS) != 0;
 
-    hipError_t err = launch_select_median(x, g, ws, params->C, no_outliers, ep, st);
+    auto mark = [&](int i) -> hipError_t {
+        if (phase_events && phase_events[i])
+            return hipEventRecord(static_cast<hipEvent_t>(phase_events[i]), st);
+        return hipSuccess;
+    };
+    hipError_t err = mark(0);
+    if (err != hipSuccess)
+        return hip_failed(err);
+    err = launch_select_median(x, g, ws, params->C, no_outliers, ep, st);
+    if (err == hipSuccess)
+        err = mark(1);
     if (err != hipSuccess)
         return hip_failed(err);
     err = launch_mask_scan(x, g, ws, ep, outlier_capacity, st);
+    if (err == hipSuccess)
+        err = mark(2);
     if (err != hipSuccess)
         return hip_failed(err);
     err = launch_search(x, sec_dev, g, ws, ep, outlier_capacity, st);
+    if (err == hipSuccess)
+        err = mark(3);
     if (err != hipSuccess)
         return hip_failed(err);
     return HQMQ_OK;
+}
+
+extern "C" int32_t hqmq_encode(const hqmq_params *params, const void *x_dev, const float *sec_dev,
+                               const hqmq_encoded *enc, uint64_t outlier_capacity,
+                               void *workspace_dev, uint64_t workspace_bytes, void *stream)
+{
+    return encode_impl(params, x_dev, sec_dev, enc, outlier_capacity, workspace_dev, workspace_bytes,
+                       stream, nullptr);
+}
+
+extern "C" int32_t hqmq_encode_timed(const hqmq_params *params, const void *x_dev,
+                                     const float *sec_dev, const hqmq_encoded *enc,
+                                     uint64_t outlier_capacity, void *workspace_dev,
+                                     uint64_t workspace_bytes, void *stream, void *const *phase_events)
+{
+    return encode_impl(params, x_dev, sec_dev, enc, outlier_capacity, workspace_dev, workspace_bytes,
+                       stream, phase_events);
 }
 
 extern "C" int32_t hqmq_decode(const hqmq_params *params, const hqmq_encoded *enc,
@@ -217,7 +250,7 @@ extern "C" int32_t hqmq_decode(const hqmq_params *params, const hqmq_encoded *en
         return HQMQ_ERR_INVALID_ARG;
     if (misaligned(out_dev, 8) || misaligned(sec_dev, 16))
         return HQMQ_ERR_INVALID_ARG;
-    rc = check_encoded(enc, false);
+    rc = check_encoded(enc, false, outlier_capacity);
     if (rc != HQMQ_OK)
         return rc;
     const Geometry g = make_geometry(params);
