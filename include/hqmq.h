@@ -49,7 +49,7 @@ extern "C" {
 
 typedef struct hqmq_params {
     int32_t B, H, T, D;                   /* X is fp16 [B, H, T, D], D contiguous                  */
-    int64_t stride_b, stride_h, stride_t; /* element strides of b, h, t; multiples of 4           */
+    int64_t stride_b, stride_h, stride_t; /* element strides of b, h, t; multiples of 8           */
     int32_t S;                            /* secondary codebook size per (layer, head, role)       */
     int32_t b_r;                          /* radius bits (paper: 3, 4 or 6)                        */
     float C;                              /* outlier multiplier (paper: 3)                         */
@@ -119,7 +119,7 @@ int32_t hqmq_sizes(const hqmq_params *params, hqmq_size_info *out);
  * by exhaustive search over all S secondaries (24 primaries each, lowest index on ties);
  * radius code r_q = clamp(rint(r * (2^b_r - 1) / sigma), 0, 2^b_r - 1); bit packing.
  *   params            HOST.
- *   x_dev             DEVICE, in, fp16, 8-byte aligned, addressed with params strides; finite.
+ *   x_dev             DEVICE, in, fp16, 16-byte aligned, addressed with params strides; finite.
  *   sec_dev           DEVICE, in, fp32 [H][S][4]: the codebooks of THIS (layer, role).
  *   enc               HOST struct of DEVICE pointers (see hqmq_encoded), sized per hqmq_sizes.
  *   outlier_capacity  entries (chunks) available in enc->outliers; outlier_capacity_max always
@@ -152,7 +152,7 @@ int32_t hqmq_encode_timed(const hqmq_params *params, const void *x_dev, const fl
  *   outlier_capacity  entries available in enc->outliers; a flagged chunk whose list position
  *            lies beyond it (an encode that overflowed) decodes to zeros.
  *   sec_dev  DEVICE, fp32 [H][S][4], the same codebooks used to encode.
- *   out_dev  DEVICE, out, fp16, 8-byte aligned, addressed with params strides.
+ *   out_dev  DEVICE, out, fp16, 16-byte aligned, addressed with params strides.
  *   stream   hipStream_t. */
 int32_t hqmq_decode(const hqmq_params *params, const hqmq_encoded *enc, uint64_t outlier_capacity,
                     const float *sec_dev, void *out_dev, void *stream);

@@ -36,7 +36,7 @@ static int32_t check_params(const hqmq_params *p)
         return HQMQ_ERR_UNSUPPORTED;
     if (p->stride_b < 0 || p->stride_h < 0 || p->stride_t < p->D)
         return HQMQ_ERR_INVALID_ARG;
-    if ((p->stride_b % 4) || (p->stride_h % 4) || (p->stride_t % 4))
+    if ((p->stride_b % 8) || (p->stride_h % 8) || (p->stride_t % 8))
         return HQMQ_ERR_INVALID_ARG;
     if ((int64_t)p->B * p->H > 65535)
         return HQMQ_ERR_UNSUPPORTED;  // grid.y
@@ -60,7 +60,12 @@ static Geometry make_geometry(const hqmq_params *p)
     g.sb = p->stride_b;
     g.sh = p->stride_h;
     g.st = p->stride_t;
-    g.s_magic = (p->S == 1) ? 0u : (uint32_t)((1ull << 32) / (uint64_t)p->S + 1ull);
+    g.inv_S = (1.0f / (float)p->S) * (1.0f + 0x1.0p-18f);
+    g.inv_L = 1.0f / (float)((1 << p->b_r) - 1);
+    g.log2_S = -1;
+    for (int j = 0; j < 16; ++j)
+        if ((1 << j) == p->S)
+            g.log2_S = j;
     g.n_mask_blocks_per_seg = (uint32_t)((p->T + kMaskRows - 1) / kMaskRows);
     return g;
 }
@@ -173,7 +178,7 @@ static int32_t encode_impl(const hqmq_params *params, const void *x_dev, const f
         return rc;
     if (!x_dev || !sec_dev || !workspace_dev)
         return HQMQ_ERR_INVALID_ARG;
-    if (misaligned(x_dev, 8) || misaligned(sec_dev, 16) || misaligned(workspace_dev, 256))
+    if (misaligned(x_dev, 16) || misaligned(sec_dev, 16) || misaligned(workspace_dev, 256))
         return HQMQ_ERR_INVALID_ARG;
     rc = check_encoded(enc, true, outlier_capacity);
     if (rc != HQMQ_OK)
@@ -248,7 +253,7 @@ extern "C" int32_t hqmq_decode(const hqmq_params *params, const hqmq_encoded *en
         return rc;
     if (!sec_dev || !out_dev)
         return HQMQ_ERR_INVALID_ARG;
-    if (misaligned(out_dev, 8) || misaligned(sec_dev, 16))
+    if (misaligned(out_dev, 16) || misaligned(sec_dev, 16))
         return HQMQ_ERR_INVALID_ARG;
     rc = check_encoded(enc, false, outlier_capacity);
     if (rc != HQMQ_OK)

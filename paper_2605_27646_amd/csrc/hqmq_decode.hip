@@ -2,96 +2,254 @@
 // r_hat = r_q * sigma / (2^b_r - 1); flagged chunks are restored verbatim from the outlier list.
 //
 // HBM-bound: per chunk it reads w/8 bytes of code (+ 1/8 flag, 1/16 scale, 1/8 offset) and
-// writes 8 bytes of fp16.  One lane per chunk, two rows per wave, so a wave's store is 512
-// contiguous bytes.  The head's secondaries sit in LDS; the primary is never looked up: P_p is
-// rebuilt from the bits of p (a signed axis or a sign pattern times 1/2) and multiplied out.
+// writes 8 bytes of fp16.  The kernel is shaped like a streaming copy:
+//   * small one-shot workgroups (4 wave64, 64 rows, ~14 KiB of LDS) launched in row order: the
+//     hardware dispatcher hands the next rows to whichever CU frees up, so the set of rows in
+//     flight is a compact window moving front to back through the tensor (good DRAM page
+//     locality, no tail from a static partition), and 8 workgroups per CU overlap one another's
+//     load latency;
+//   * a wave takes 16 consecutive rows: their code words, flag words, scales and outlier offsets
+//     arrive with a few fully coalesced loads and are re-distributed through LDS; every lane then
+//     owns two adjacent chunks of a row, i.e. one 16-byte store per lane and 1 KiB contiguous per
+//     wave store;
+//   * the head's S secondaries (S*16 bytes) and the 24 primaries sit in LDS; the Hamilton product
+//     is taken per chunk (16 FMA), which keeps the workgroup small enough to be one-shot;
+//   * the outlier payloads of a wave's rows are one contiguous window of the list: requested with
+//     one coalesced load as soon as the offsets are known and parked in LDS for the flagged lanes.
 #include "hqmq_device.h"
 
 namespace hqmq {
 
-__global__ __launch_bounds__(kThreads) void k_decode(Geometry g, EncodedPtrs enc,
-                                                     uint64_t outlier_capacity,
-                                                     const float *__restrict__ sec,
-                                                     _Float16 *__restrict__ out)
+namespace {
+
+constexpr int kDecThreads = 256;
+constexpr int kDecWaves = kDecThreads / 64;
+constexpr int kStageRows = 16;                      // rows per wave
+constexpr int kDecRows = kStageRows * kDecWaves;    // rows per workgroup
+constexpr int kSubs = kStageRows / 4;               // a wave stores 4 rows at a time
+constexpr int kMaxW = 24;                           // w_idx <= 14 (S <= 512), b_r <= 8  ->  w <= 22
+constexpr int kStageWords = kStageRows * kMaxW + 2; // + 2 words of padding for the 3-word window
+constexpr int kPaySlots = 64;                       // outlier payloads of a wave's 16 rows kept in LDS
+constexpr int kStagePerWave = kStageWords + 3 * kStageRows + 2 * kPaySlots;
+constexpr int kLoadsPerLane = (kStageRows * kMaxW + 63) / 64;  // 6 code words per lane
+
+}  // namespace
+
+// grid = (ceil(T / 64), B*H), block = 256.
+// dynamic LDS: secl [S][4] f32 | prim [48][4] f32 | staging [4 waves][kStagePerWave] u32
+template <bool kPow2>
+__global__ __launch_bounds__(kDecThreads) void k_decode(Geometry g, EncodedPtrs enc,
+                                                        uint64_t outlier_capacity,
+                                                        const float *__restrict__ sec,
+                                                        _Float16 *__restrict__ out)
 {
-    extern __shared__ float secl[];  // [S][4]
-    const int tid = threadIdx.x;
+    extern __shared__ float lds[];
+    float *secl = lds;
+    float *prim = lds + (size_t)g.S * 4;
+    uint32_t *stage_all = reinterpret_cast<uint32_t *>(prim + 48 * 4);
+
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int seg = blockIdx.y, b = seg / g.H, h = seg % g.H;
-    const float *sec_h = sec + (size_t)h * g.S * 4;
-    for (int s = tid; s < g.S; s += kThreads)
-        *reinterpret_cast<float4_t *>(secl + 4 * s) = *reinterpret_cast<const float4_t *>(sec_h + 4 * s);
-    __syncthreads();
-
-    const int c = tid & 31, sub = tid >> 5;
-    const int t0 = blockIdx.x * kDecodeRows;
-    const int t1 = min(g.T, t0 + kDecodeRows);
-    const int64_t row0 = (int64_t)seg * g.T;
-    _Float16 *obase = out + (int64_t)b * g.sb + (int64_t)h * g.sh + 4 * c;
-
+    const int cp = lane & 15, rsub = lane >> 4;  // chunk pair in the row, row in the group of 4
+    const int tg = blockIdx.x * kDecRows + wv * kStageRows;  // first row of this wave
+    const int nrows = min(kStageRows, g.T - tg);              // <= 0: nothing to do for this wave
+    const int64_t R0 = (int64_t)seg * g.T + tg;
     const uint32_t w = g.w, w_idx = g.w_idx;
-    const uint32_t bitpos = (uint32_t)c * w;
-    const uint32_t d0 = bitpos >> 5, sh = bitpos & 31;
-    const uint32_t d1 = (d0 + 1 < w) ? d0 + 1 : d0;
-    const uint32_t code_mask = (1u << w) - 1u, idx_mask = (1u << w_idx) - 1u;
-    const float inv_L = 1.0f / (float)((1 << g.b_r) - 1);
 
-    for (int t = t0 + sub; t < t1; t += 8) {
-        const int64_t R = row0 + t;
-        const uint32_t *cw = enc.codes + R * w;
-        const uint32_t lo = cw[d0], hi = cw[d1];
-        const uint32_t word = enc.flags[R];
-        const float sigma = (float)__builtin_bit_cast(_Float16, enc.sigma[R]);
-        half4_t o;
-        if ((word >> c) & 1u) {
-            uint64_t pos = (uint64_t)enc.row_off[R] + __popc(word & ((1u << c) - 1u));
-            uint2 raw = make_uint2(0u, 0u);
-            if (pos < outlier_capacity)
-                raw = *reinterpret_cast<const uint2 *>(enc.outliers + 4 * pos);
-            o = __builtin_bit_cast(half4_t, raw);
-        } else {
-            const uint32_t code = __builtin_amdgcn_alignbit(hi, lo, sh) & code_mask;
-            const uint32_t k = code & idx_mask, rq = code >> w_idx;
-            const uint32_t p = (g.S == 1) ? k : __umulhi(k, g.s_magic);
-            const uint32_t s = k - p * (uint32_t)g.S;
-            const float4_t q = *reinterpret_cast<const float4_t *>(secl + 4 * s);
-            // P_p from the bits of p
-            float P0, P1, P2, P3;
-            if (p < 8) {
-                const float sg = (p & 1u) ? -1.f : 1.f;
-                const uint32_t ax = p >> 1;
-                P0 = ax == 0 ? sg : 0.f;
-                P1 = ax == 1 ? sg : 0.f;
-                P2 = ax == 2 ? sg : 0.f;
-                P3 = ax == 3 ? sg : 0.f;
-            } else {
-                const uint32_t bt = p - 8;
-                P0 = (bt & 8u) ? -0.5f : 0.5f;
-                P1 = (bt & 4u) ? -0.5f : 0.5f;
-                P2 = (bt & 2u) ? -0.5f : 0.5f;
-                P3 = (bt & 1u) ? -0.5f : 0.5f;
-            }
-            // Hamilton product P (x) q
-            const float c0 = P0 * q[0] - P1 * q[1] - P2 * q[2] - P3 * q[3];
-            const float c1 = P0 * q[1] + P1 * q[0] + P2 * q[3] - P3 * q[2];
-            const float c2 = P0 * q[2] - P1 * q[3] + P2 * q[0] + P3 * q[1];
-            const float c3 = P0 * q[3] + P1 * q[2] - P2 * q[1] + P3 * q[0];
-            const float rh = ((float)rq * sigma) * inv_L;
-            const float lim = 65504.f;
-            o[0] = (_Float16)fminf(fmaxf(rh * c0, -lim), lim);
-            o[1] = (_Float16)fminf(fmaxf(rh * c1, -lim), lim);
-            o[2] = (_Float16)fminf(fmaxf(rh * c2, -lim), lim);
-            o[3] = (_Float16)fminf(fmaxf(rh * c3, -lim), lim);
+    // ---- the wave's encoded rows: coalesced loads, in flight while the tables are set up --------
+    uint32_t cwreg[kLoadsPerLane];
+    uint32_t fw = 0, sg = 0, ro = 0;
+#pragma unroll
+    for (int j = 0; j < kLoadsPerLane; ++j)
+        cwreg[j] = 0;
+    if (nrows > 0) {
+        const uint32_t *cw = enc.codes + R0 * w;
+        const int ncw = nrows * (int)w;
+#pragma unroll
+        for (int j = 0; j < kLoadsPerLane; ++j)
+            if (lane + 64 * j < ncw)
+                cwreg[j] = cw[lane + 64 * j];
+        if (lane < nrows) {
+            fw = enc.flags[R0 + lane];
+            sg = enc.sigma[R0 + lane];
+            ro = enc.row_off[R0 + lane];
         }
-        *reinterpret_cast<uint2 *>(obase + (int64_t)t * g.st) = __builtin_bit_cast(uint2, o);
     }
+
+    // ---- tables: the head's secondaries and the 24 primaries (zero rows up to 47: a code can
+    // hold p up to 47, k < 2^w_idx < 48 S; encode never produces p > 23) -------------------------
+    const float *sec_h = sec + (size_t)h * g.S * 4;
+    for (int s = tid; s < g.S; s += kDecThreads)
+        *reinterpret_cast<float4_t *>(secl + 4 * s) = *reinterpret_cast<const float4_t *>(sec_h + 4 * s);
+    if (tid < 48 * 4) {
+        const int p = tid >> 2, i = tid & 3;
+        float v = 0.f;
+        if (p < 8)
+            v = ((p >> 1) == i) ? ((p & 1) ? -1.f : 1.f) : 0.f;
+        else if (p < 24)
+            v = (((p - 8) >> (3 - i)) & 1) ? -0.5f : 0.5f;
+        prim[tid] = v;
+    }
+
+    uint32_t *stage = stage_all + wv * kStagePerWave;
+    uint32_t *st_flags = stage + kStageWords;
+    uint32_t *st_sigma = st_flags + kStageRows;
+    uint32_t *st_roff = st_sigma + kStageRows;
+#pragma unroll
+    for (int j = 0; j < kLoadsPerLane; ++j)
+        stage[lane + 64 * j] = cwreg[j];
+    if (lane < 2)
+        stage[kStageWords - 2 + lane] = 0;  // padding read by the last row's 3-word window
+    if (lane < kStageRows) {
+        st_flags[lane] = fw;
+        st_sigma[lane] = sg;
+        st_roff[lane] = ro;
+    }
+    __syncthreads();
+    if (nrows <= 0)
+        return;
+
+    // ---- outlier payloads of the wave's rows: one contiguous window of the list, requested now
+    // (its offsets have just arrived) and consumed after the arithmetic below --------------------
+    uint2 *st_pay = reinterpret_cast<uint2 *>(st_roff + kStageRows);
+    const uint32_t pay_base = st_roff[0];
+    const uint32_t pay_n = st_roff[nrows - 1] + __popc(st_flags[nrows - 1]) - pay_base;  // wave-uniform
+    // The load is unconditional (a conditional one would be waited for on the spot): lanes past the
+    // window, or beyond the list's capacity, re-read a neighbour's entry, and a wave without
+    // outliers reads 8 harmless bytes of the offset array instead of a possibly absent list.
+    const bool has_pay = pay_n > 0 && (uint64_t)pay_base < outlier_capacity;
+    const uint64_t pay_last = has_pay ? min((uint64_t)pay_n, outlier_capacity - pay_base) - 1u : 0u;
+    const uint2 *pay_src = has_pay ? reinterpret_cast<const uint2 *>(enc.outliers) + pay_base
+                                   : reinterpret_cast<const uint2 *>(enc.row_off);
+    const uint2 pay_mine = pay_src[min((uint64_t)lane, pay_last)];
+
+    const uint32_t bitpos = (uint32_t)(2 * cp) * w;
+    const uint32_t i0 = bitpos >> 5, sh0 = bitpos & 31;
+    const uint32_t sh1 = sh0 + w;  // second chunk, relative to word i0 (may exceed 32)
+    const bool second_in_low = sh1 < 32;
+    const uint32_t code_mask = (1u << w) - 1u, idx_mask = (1u << w_idx) - 1u;
+    const float inv_L = g.inv_L;
+    _Float16 *obase = out + (int64_t)b * g.sb + (int64_t)h * g.sh + (int64_t)tg * g.st + 8 * cp;
+
+    // ---- phase 1: codes and flags of the lane's 8 chunks ----------------------------------------------
+    struct Sub {
+        uint32_t code0, code1, fl, pos;
+        float sigma;
+    };
+    auto phase1 = [&](int sub) {
+        Sub o;
+        const int r = 4 * sub + rsub;
+        const uint32_t *rw = stage + r * w + i0;
+        const uint32_t d0 = rw[0], d1 = rw[1], d2 = rw[2];
+        const uint32_t word = st_flags[r];
+        o.sigma = (float)__builtin_bit_cast(_Float16, (uint16_t)st_sigma[r]);
+        o.code0 = __builtin_amdgcn_alignbit(d1, d0, sh0) & code_mask;
+        // second chunk: starts sh1 = sh0 + w bits into word i0; the funnel shift takes its amount
+        // modulo 32, so the same amount serves both windows and the choice is a plain select
+        const uint32_t lo_win = __builtin_amdgcn_alignbit(d1, d0, sh1);
+        const uint32_t hi_win = __builtin_amdgcn_alignbit(d2, d1, sh1);
+        o.code1 = (second_in_low ? lo_win : hi_win) & code_mask;
+        o.fl = (r < nrows) ? ((word >> (2 * cp)) & 3u) : 0u;
+        o.pos = st_roff[r] + __popc(word & ((1u << (2 * cp)) - 1u)) - pay_base;  // slot of the first flagged
+        return o;
+    };
+    auto decode_chunk = [&](uint32_t code, float sol) {
+        const uint32_t k = code & idx_mask, rq = code >> w_idx;
+        uint32_t p, s;
+        if (kPow2) {
+            p = k >> g.log2_S;
+            s = k & ((uint32_t)g.S - 1u);
+        } else {
+            // p = k / S by a biased reciprocal, exact for k < 48 S (see Geometry::inv_S)
+            p = (uint32_t)((float)k * g.inv_S);
+            s = k - __umul24(p, (uint32_t)g.S);
+        }
+        const float4_t P = *reinterpret_cast<const float4_t *>(prim + 4 * p);
+        const float4_t q = *reinterpret_cast<const float4_t *>(secl + 4 * s);
+        const float rh = (float)rq * sol;
+        const float R0 = rh * P[0], R1 = rh * P[1], R2 = rh * P[2], R3 = rh * P[3];
+        // Hamilton product (r_hat P) (x) q
+        float4_t y;
+        y[0] = fmaf(-R3, q[3], fmaf(-R2, q[2], fmaf(-R1, q[1], R0 * q[0])));
+        y[1] = fmaf(-R3, q[2], fmaf(R2, q[3], fmaf(R1, q[0], R0 * q[1])));
+        y[2] = fmaf(R3, q[1], fmaf(R2, q[0], fmaf(-R1, q[3], R0 * q[2])));
+        y[3] = fmaf(R3, q[0], fmaf(-R2, q[1], fmaf(R1, q[2], R0 * q[3])));
+        return y;
+    };
+    auto to_half4 = [&](float4_t y) {
+        half4_t hv;
+        hv[0] = (_Float16)y[0];
+        hv[1] = (_Float16)y[1];
+        hv[2] = (_Float16)y[2];
+        hv[3] = (_Float16)y[3];
+        return __builtin_bit_cast(uint2, hv);
+    };
+    // payload of list slot `slot` of this wave's window (LDS), or straight from memory beyond it
+    auto fetch_payload = [&](uint32_t slot) {
+        uint2 v = make_uint2(0u, 0u);
+        if (slot < (uint32_t)kPaySlots) {
+            if ((uint64_t)pay_base + slot < outlier_capacity)
+                v = st_pay[slot];
+        } else {
+            const uint64_t pos = (uint64_t)pay_base + slot;
+            if (pos < outlier_capacity)
+                v = *reinterpret_cast<const uint2 *>(enc.outliers + 4 * pos);
+        }
+        return v;
+    };
+    // ---- phase 2: decode, merge, store ---------------------------------------------------------------
+    auto phase2 = [&](int sub, const Sub &in) {
+        const int r = 4 * sub + rsub;
+        const float sol = in.sigma * inv_L;
+        float4_t ya = decode_chunk(in.code0, sol), yb = decode_chunk(in.code1, sol);
+        // A product r_hat * c_i can only leave the fp16 range when the row's scale is within a
+        // factor |c_i| of the largest half; |c_i| <= |q_s| < 2 for any codebook of (near) unit
+        // quaternions, so only such rows take the saturating conversion.
+        if (in.sigma >= 32752.f) {
+            const float lim = 65504.f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                ya[i] = __builtin_amdgcn_fmed3f(ya[i], -lim, lim);
+                yb[i] = __builtin_amdgcn_fmed3f(yb[i], -lim, lim);
+            }
+        }
+        uint2 oa = to_half4(ya), ob = to_half4(yb);
+        if (in.fl) {
+            uint32_t slot = in.pos;
+            if (in.fl & 1u) {
+                oa = fetch_payload(slot);
+                ++slot;
+            }
+            if (in.fl & 2u)
+                ob = fetch_payload(slot);
+        }
+        if (r < nrows)
+            *reinterpret_cast<uint4 *>(obase + (int64_t)r * g.st) = make_uint4(oa.x, oa.y, ob.x, ob.y);
+    };
+    static_assert(kSubs == 4, "the straight-line code below is written for 4 row groups per wave");
+    const Sub s0 = phase1(0), s1 = phase1(1), s2 = phase1(2), s3 = phase1(3);
+    // the window lands in LDS only now: every lane's loads above and below are already issued
+    if (pay_n > 0) {
+        st_pay[lane] = pay_mine;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+    phase2(0, s0);
+    phase2(1, s1);
+    phase2(2, s2);
+    phase2(3, s3);
 }
 
 hipError_t launch_decode(const Geometry &g, const EncodedPtrs &enc, uint64_t outlier_capacity,
                          const float *sec, _Float16 *out, hipStream_t stream)
 {
-    dim3 grid((g.T + kDecodeRows - 1) / kDecodeRows, g.B * g.H);
-    size_t lds = (size_t)g.S * 4 * sizeof(float);
-    hipLaunchKernelGGL(k_decode, grid, dim3(kThreads), lds, stream, g, enc, outlier_capacity, sec, out);
+    const size_t lds = ((size_t)g.S * 4 + 48 * 4) * sizeof(float) + (size_t)kDecWaves * kStagePerWave * 4;
+    dim3 grid((unsigned)((g.T + kDecRows - 1) / kDecRows), (unsigned)(g.B * g.H));
+    if ((g.S & (g.S - 1)) == 0)
+        hipLaunchKernelGGL(k_decode<true>, grid, dim3(kDecThreads), lds, stream, g, enc, outlier_capacity, sec, out);
+    else
+        hipLaunchKernelGGL(k_decode<false>, grid, dim3(kDecThreads), lds, stream, g, enc, outlier_capacity, sec, out);
     return hipGetLastError();
 }
 

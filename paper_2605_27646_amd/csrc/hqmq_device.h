@@ -36,7 +36,9 @@ struct Geometry {
     int32_t S4;           // ceil(S / 4): s-blocks of the MFMA tile
     int32_t b_r, w_idx, w;
     int64_t sb, sh, st;   // element strides
-    uint32_t s_magic;     // k / S == mulhi(k, s_magic) for every k < 2^w_idx
+    float inv_L;          // 1 / (2^b_r - 1)
+    int32_t log2_S;       // log2(S) when S is a power of two, else -1
+    float inv_S;          // (1/S)(1 + 2^-18): uint(float(k) * inv_S) == k / S for every k < 48 S, S <= 512
     uint32_t n_mask_blocks_per_seg;
 };
 

@@ -63,7 +63,7 @@ def test_sizes_of_the_headline_workload(lib):
 
 
 @pytest.mark.parametrize("kw,code", [
-    (dict(B=0), -1), (dict(T=-3), -1), (dict(stride_t=126), -1), (dict(stride_t=64), -1), (dict(stride_h=-4), -1),
+    (dict(B=0), -1), (dict(T=-3), -1), (dict(stride_t=132), -1), (dict(stride_t=64), -1), (dict(stride_h=-8), -1),
     (dict(D=64), -2), (dict(D=130), -2), (dict(S=0), -2), (dict(S=513), -2), (dict(b_r=0), -2), (dict(b_r=9), -2),
     (dict(C=0.0), -2), (dict(C=float("nan")), -2), (dict(C=float("inf")), -2), (dict(B=70000, H=1), -2),
     (dict(T=1 << 27), -2),
@@ -85,7 +85,7 @@ def test_encode_decode_reject_bad_arguments_without_touching_the_gpu(lib):
     enc = lib.hqmq_encode
     assert enc(None, 0x1000, 0x1000, C.byref(good), 0, 0x1000, ws, None) == -1
     assert enc(C.byref(p), None, 0x1000, C.byref(good), 0, 0x1000, ws, None) == -1          # null x
-    assert enc(C.byref(p), 0x1004, 0x1000, C.byref(good), 0, 0x1000, ws, None) == -1        # misaligned x
+    assert enc(C.byref(p), 0x1008, 0x1000, C.byref(good), 0, 0x1000, ws, None) == -1        # misaligned x
     assert enc(C.byref(p), 0x1000, 0x1004, C.byref(good), 0, 0x1000, ws, None) == -1        # misaligned codebook
     assert enc(C.byref(p), 0x1000, 0x1000, None, 0, 0x1000, ws, None) == -1                 # null struct
     assert enc(C.byref(p), 0x1000, 0x1000, C.byref(good), 0, 0x1010, ws, None) == -1        # misaligned workspace
@@ -97,7 +97,7 @@ def test_encode_decode_reject_bad_arguments_without_touching_the_gpu(lib):
     assert enc(C.byref(_params(D=64)), 0x1000, 0x1000, C.byref(good), 0, 0x1000, ws, None) == -2
     dec = lib.hqmq_decode
     assert dec(C.byref(p), C.byref(good), 0, None, 0x1000, None) == -1
-    assert dec(C.byref(p), C.byref(good), 0, 0x1000, 0x1004, None) == -1
+    assert dec(C.byref(p), C.byref(good), 0, 0x1000, 0x1008, None) == -1
     assert dec(C.byref(p), None, 0, 0x1000, 0x1000, None) == -1
     assert dec(C.byref(_params(S=600)), C.byref(good), 0, 0x1000, 0x1000, None) == -2
     assert lib.hqmq_last_hip_error() == 0
