@@ -53,7 +53,7 @@ static Geometry make_geometry(const hqmq_params *p)
     g.H = p->H;
     g.T = p->T;
     g.S = p->S;
-    g.S4 = (p->S + 3) / 4;
+    g.S16 = (p->S + 15) / 16;
     g.b_r = p->b_r;
     g.w_idx = index_bits(p->S);
     g.w = g.w_idx + p->b_r;

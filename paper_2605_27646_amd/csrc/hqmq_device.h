@@ -33,7 +33,7 @@ struct SelectState {
 struct Geometry {
     int32_t B, H, T;
     int32_t S;            // secondaries per head
-    int32_t S4;           // ceil(S / 4): s-blocks of the MFMA tile
+    int32_t S16;          // ceil(S / 16): groups of 16 secondaries (4 MFMA s-blocks) of the search loop
     int32_t b_r, w_idx, w;
     int64_t sb, sh, st;   // element strides
     float inv_L;          // 1 / (2^b_r - 1)

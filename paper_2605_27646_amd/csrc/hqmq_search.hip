@@ -14,6 +14,13 @@
 // instructions per pair.  The search stays exhaustive over all S secondaries and, through the
 // closed form, over all 24 primaries.
 //
+// On gfx950 the fp32 MFMA and the VALU do not run concurrently on a SIMD (measured: their times
+// add), so the inner loop is costed as 32 cycles of MFMA plus 4 cycles per VALU instruction for
+// every 64 (chunk, secondary) pairs, and the VALU count per pair is what is minimised: the
+// running argmax is kept per group of 16 secondaries (4 per lane) with v_max3 chains, one
+// compare-and-select per group, and the winner inside the winning group is found afterwards by
+// re-scoring its 4 candidates once per chunk.
+//
 // Work split: a workgroup (4 wave64) owns kSearchRows rows of one (b, h) segment, so the A
 // matrices of the head sit in LDS once per workgroup.  A wave takes two rows (64 chunks, one per
 // lane) at a time and runs them as four 16-chunk MFMA column groups.
@@ -22,6 +29,15 @@
 namespace hqmq {
 
 namespace {
+
+__device__ __forceinline__ void wave_lds_sync()
+{
+    // LDS serves the instructions of one wave in order; this only stops the compiler from moving
+    // LDS accesses of other lanes' data across the point.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
 
 __device__ __forceinline__ uint16_t double_to_half_rne_sat(double v)
 {
@@ -76,9 +92,9 @@ __device__ __forceinline__ int nearest_primary(float v0, float v1, float v2, flo
 }  // namespace
 
 // Dynamic LDS layout (floats):
-//   amat  [S4][64]      MFMA A operands: lane l of s-block sb holds A[row l%16][k l/16], row 4g+i =
+//   amat  [4*S16][64]   MFMA A operands: lane l of s-block sb holds A[row l%16][k l/16], row 4g+i =
 //                       component i of v for secondary 4 sb + g
-//   secl  [4*S4][4]     the head's secondaries (zero padded to a multiple of 4)
+//   secl  [16*S16][4]   the head's secondaries (zero padded to a multiple of 16)
 //   ubuf  [4 waves][64][4]   unit directions of the wave's 64 chunks (for the B operands)
 //   pack  [4 waves][2][32]   row code words being assembled
 //   roff  [kSearchRows] outlier offsets of the block's rows
@@ -89,8 +105,8 @@ __global__ __launch_bounds__(kThreads) void k_search(const _Float16 *__restrict_
 {
     extern __shared__ float smem[];
     float *amat = smem;
-    float *secl = amat + (size_t)g.S4 * 64;
-    float *ubuf = secl + (size_t)g.S4 * 16;
+    float *secl = amat + (size_t)g.S16 * 4 * 64;
+    float *ubuf = secl + (size_t)g.S16 * 16 * 4;
     uint32_t *pack = reinterpret_cast<uint32_t *>(ubuf + 4 * 64 * 4);
     uint32_t *roff = pack + 4 * 2 * 32;
 
@@ -101,14 +117,14 @@ __global__ __launch_bounds__(kThreads) void k_search(const _Float16 *__restrict_
     const float *sec_h = sec + (size_t)h * g.S * 4;
 
     // ---- setup: secondaries and A operands into LDS ---------------------------------------
-    for (int s = tid; s < g.S4 * 4; s += kThreads) {
+    for (int s = tid; s < g.S16 * 16; s += kThreads) {
         float4_t q = {0.f, 0.f, 0.f, 0.f};
         if (s < g.S)
             q = *reinterpret_cast<const float4_t *>(sec_h + 4 * s);
         *reinterpret_cast<float4_t *>(secl + 4 * s) = q;
     }
     __syncthreads();
-    for (int idx = tid; idx < g.S4 * 64; idx += kThreads) {
+    for (int idx = tid; idx < g.S16 * 4 * 64; idx += kThreads) {
         int sb = idx >> 6, l = idx & 63;
         int row = l & 15, k = l >> 4;
         int gsub = row >> 2, i = row & 3;
@@ -201,70 +217,99 @@ __global__ __launch_bounds__(kThreads) void k_search(const _Float16 *__restrict_
             u2 = (float)xv[2] * inv;
             u3 = (float)xv[3] * inv;
         }
-        __syncthreads();  // previous iteration's readers of ubuf / pack are done
+        wave_lds_sync();  // this wave's reads of ubuf / pack from the previous iteration are done
         *reinterpret_cast<float4_t *>(my_ubuf + 4 * lane) = float4_t{u0, u1, u2, u3};
-        if (lane < 2 * 32)
-            my_pack[lane] = 0;
-        __syncthreads();
+        my_pack[lane] = 0;
+        wave_lds_sync();
         float bop[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j)
             bop[j] = my_ubuf[4 * (16 * j + (lane & 15)) + (lane >> 4)];
 
         // ---- exhaustive search over the secondaries -------------------------------------------
+        // best[j] / bgrp[j]: running maximum of the closed-form score and the group of 16
+        // secondaries (4 of them on this lane: s = 16 grp + 4 t + lane/16) that reached it.
         float best[4] = {-1.f, -1.f, -1.f, -1.f};
-        int bsb[4] = {0, 0, 0, 0};
+        int bgrp[4] = {0, 0, 0, 0};
         const float4_t zero4 = {0.f, 0.f, 0.f, 0.f};
-        for (int sb = 0; sb < g.S4; ++sb) {
-            const float aop = amat[sb * 64 + lane];
+        for (int grp = 0; grp < g.S16; ++grp) {
+            // Over the group's 4 secondaries: GA = largest |v_i| (best axis element), GH = largest
+            // |v_0|+|v_1|+|v_2|+|v_3| (twice the best half-integer element); the group's score is
+            // max(GA, GH / 2), taken once per group.
+            float GA[4] = {0.f, 0.f, 0.f, 0.f}, GH[4] = {0.f, 0.f, 0.f, 0.f};
+            const float *arow = amat + (size_t)grp * 4 * 64 + lane;
+#pragma unroll
+            for (int tp = 0; tp < 2; ++tp) {
+                const float aA = arow[(2 * tp) * 64], aB = arow[(2 * tp + 1) * 64];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float4_t vA = __builtin_amdgcn_mfma_f32_16x16x4f32(aA, bop[j], zero4, 0, 0, 0);
+                    const float4_t vB = __builtin_amdgcn_mfma_f32_16x16x4f32(aB, bop[j], zero4, 0, 0, 0);
+                    const float a0 = fabsf(vA[0]), a1 = fabsf(vA[1]), a2 = fabsf(vA[2]), a3 = fabsf(vA[3]);
+                    const float b0 = fabsf(vB[0]), b1 = fabsf(vB[1]), b2 = fabsf(vB[2]), b3 = fabsf(vB[3]);
+                    const float hA = ((a0 + a1) + a2) + a3;
+                    const float hB = ((b0 + b1) + b2) + b3;
+                    float ga = fmaxf(fmaxf(GA[j], a0), a1);  // v_max3 each
+                    ga = fmaxf(fmaxf(ga, a2), a3);
+                    ga = fmaxf(fmaxf(ga, b0), b1);
+                    GA[j] = fmaxf(fmaxf(ga, b2), b3);
+                    GH[j] = fmaxf(fmaxf(GH[j], hA), hB);
+                }
+            }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                float4_t v = __builtin_amdgcn_mfma_f32_16x16x4f32(aop, bop[j], zero4, 0, 0, 0);
-                float a0 = fabsf(v[0]), a1 = fabsf(v[1]), a2 = fabsf(v[2]), a3 = fabsf(v[3]);
-                float hs = 0.5f * (((a0 + a1) + a2) + a3);
-                float m = fmaxf(fmaxf(fmaxf(fmaxf(a0, a1), a2), a3), hs);  // two v_max3
-                if (m > best[j]) {
-                    best[j] = m;
-                    bsb[j] = sb;
+                const float M = fmaxf(GA[j], 0.5f * GH[j]);
+                if (M > best[j]) {
+                    best[j] = M;
+                    bgrp[j] = grp;
                 }
             }
         }
 
         // ---- reduce over the 4 lanes that share a chunk, hand the winner to the owner lane ------
-        int s_mine = 0;
+        // key = 16 grp + lane/16: the first of the 4 candidates s = key + 4 t of the winning lane
+        int key_mine = 0;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             float bj = best[j];
-            int sj = 4 * bsb[j] + (lane >> 4);
+            int kj = 16 * bgrp[j] + (lane >> 4);
 #pragma unroll
             for (int d = 16; d <= 32; d <<= 1) {
                 float ob = __shfl_xor(bj, d, 64);
-                int os = __shfl_xor(sj, d, 64);
-                if (ob > bj || (ob == bj && os < sj)) {
+                int ok = __shfl_xor(kj, d, 64);
+                if (ob > bj || (ob == bj && ok < kj)) {
                     bj = ob;
-                    sj = os;
+                    kj = ok;
                 }
             }
-            int got = __shfl(sj, lane & 15, 64);
+            int got = __shfl(kj, lane & 15, 64);
             if ((lane >> 4) == j)
-                s_mine = got;
+                key_mine = got;
         }
-        if (s_mine >= g.S)
-            s_mine = g.S - 1;
 
-        // ---- primary for the winning secondary, code word --------------------------------------
+        // ---- re-score the 4 candidates of the winning group: secondary, primary, code word -------
         uint32_t code = 0;
         if (!flagged && r2 != 0.0) {
-            const float *q = secl + 4 * s_mine;
-            float a = q[0], bq = q[1], cq = q[2], d = q[3];
-            float v0 = fmaf(d, u3, fmaf(cq, u2, fmaf(bq, u1, a * u0)));
-            float v1 = fmaf(cq, u3, fmaf(-d, u2, fmaf(a, u1, -bq * u0)));
-            float v2 = fmaf(-bq, u3, fmaf(a, u2, fmaf(d, u1, -cq * u0)));
-            float v3 = fmaf(a, u3, fmaf(bq, u2, fmaf(-cq, u1, -d * u0)));
-            float sc;
-            int p = nearest_primary(v0, v1, v2, v3, sc);
-            uint32_t k = (uint32_t)(p * g.S + s_mine);
-            code = ((uint32_t)rq << g.w_idx) | k;
+            float bsc = -1.f;
+            uint32_t bk = 0;
+#pragma unroll
+            for (int tt = 0; tt < 4; ++tt) {
+                const int sc_idx = key_mine + 4 * tt;  // < 16 S16: inside the padded table
+                const float *q = secl + 4 * sc_idx;
+                const float a = q[0], bq = q[1], cq = q[2], d = q[3];
+                const float v0 = fmaf(d, u3, fmaf(cq, u2, fmaf(bq, u1, a * u0)));
+                const float v1 = fmaf(cq, u3, fmaf(-d, u2, fmaf(a, u1, -bq * u0)));
+                const float v2 = fmaf(-bq, u3, fmaf(a, u2, fmaf(d, u1, -cq * u0)));
+                const float v3 = fmaf(a, u3, fmaf(bq, u2, fmaf(-cq, u1, -d * u0)));
+                float sc;
+                const int p = nearest_primary(v0, v1, v2, v3, sc);
+                const uint32_t k = (uint32_t)(p * g.S + sc_idx);
+                if (sc_idx < g.S && (sc > bsc || (sc == bsc && k < bk))) {
+                    bsc = sc;
+                    bk = k;
+                }
+            }
+            code = ((uint32_t)rq << g.w_idx) | bk;
         }
 
         // ---- pack the row: chunk c at bits [c*w, (c+1)*w) -----------------------------------------
@@ -278,7 +323,7 @@ __global__ __launch_bounds__(kThreads) void k_search(const _Float16 *__restrict_
                     atomicOr(&rowp[d0 + 1], code >> (32 - sh));
             }
         }
-        __syncthreads();
+        wave_lds_sync();
         if (valid) {
             const int64_t R = row0 + t;
             if (c < g.w)
@@ -299,7 +344,7 @@ hipError_t launch_search(const _Float16 *x, const float *sec, const Geometry &g,
                          const EncodedPtrs &enc, uint64_t outlier_capacity, hipStream_t stream)
 {
     dim3 grid((g.T + kSearchRows - 1) / kSearchRows, g.B * g.H);
-    size_t lds = ((size_t)g.S4 * 64 + (size_t)g.S4 * 16 + 4 * 64 * 4) * sizeof(float) +
+    size_t lds = ((size_t)g.S16 * 4 * 64 + (size_t)g.S16 * 16 * 4 + 4 * 64 * 4) * sizeof(float) +
                  (4 * 2 * 32 + kSearchRows) * sizeof(uint32_t);
     hipLaunchKernelGGL(k_search, grid, dim3(kThreads), lds, stream, x, sec, g, ws, enc,
                        outlier_capacity);
