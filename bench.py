@@ -2,7 +2,7 @@
 """HQMQ encode / decode throughput on one MI355X.
 
 A step is one pass of the whole hot path over the workload: every (layer, role) tensor is
-encoded (median select, mask, scan, search + quantise + pack) and then decoded, inputs and
+encoded (median select, search + quantise + pack, outlier scan + gather) and then decoded, inputs and
 outputs resident in HBM.  Prints ONE JSON line: whole-path elems/s, the encode / decode
 split, the roofline position of the dominant kernel (the MFMA search) and of the decode
 kernel, measured with HIP events on the launch stream, and the CPU oracle timed on a bounded
@@ -30,9 +30,9 @@ PEAK_HBM_GBS = 8000.0        # MI355X HBM3E peak
 def search_flops_per_chunk(S: int) -> float:
     """Flops the implemented search formulation spends per chunk: per secondary one 4x4
     matrix-vector product on the MFMA unit (16 FMA = 32 flop) and the closed-form nearest
-    24-cell vertex on the VALU (3 adds + 1 multiply); S rounded up to the MFMA tile of 4."""
-    s4 = (S + 3) // 4 * 4
-    return 36.0 * s4
+    24-cell vertex on the VALU (3 adds + 1 multiply); S rounded up to the loop's group of 16."""
+    s16 = (S + 15) // 16 * 16
+    return 36.0 * s16
 
 
 def decode_bytes_per_chunk(w: int, p_out: float) -> float:
@@ -118,13 +118,13 @@ def main() -> int:
     ms_per_step = wall * 1e3 / args.steps
 
     # ---- per-phase device times from the events ----------------------------------------------
-    t_sel = t_mask = t_search = t_enc = t_dec = 0.0
+    t_sel = t_list = t_search = t_enc = t_dec = 0.0
     for k in range(args.steps):
         for i in range(n_t):
             e0, e1, e2, e3 = ev_enc[k][4 * i: 4 * i + 4]
             t_sel += e0.elapsed_time(e1)
-            t_mask += e1.elapsed_time(e2)
-            t_search += e2.elapsed_time(e3)
+            t_search += e1.elapsed_time(e2)
+            t_list += e2.elapsed_time(e3)
             t_enc += e0.elapsed_time(e3)
         t_dec += ev_dec[k][0].elapsed_time(ev_dec[k][n_t])
     launches = args.steps * n_t
@@ -163,8 +163,8 @@ def main() -> int:
         "decode_elems_per_s": elems_per_step / (dec_ms_step * 1e-3),
         "encode_ms_per_step": enc_ms_step,
         "decode_ms_per_step": dec_ms_step,
-        "encode_phase_ms_per_tensor": {"median_select": t_sel / launches, "mask_scan": t_mask / launches,
-                                       "search_quantise_pack": search_ms},
+        "encode_phase_ms_per_tensor": {"median_select": t_sel / launches, "search_quantise_pack": search_ms,
+                                       "outlier_scan_gather": t_list / launches},
         "codeword_scores_per_s": 24.0 * wl.S * chunks_per_tensor / (search_ms * 1e-3),
         "outlier_fraction": p_out,
         "status_bits": status,

@@ -138,7 +138,8 @@ int32_t hqmq_encode(const hqmq_params *params, const void *x_dev, const float *s
  * App. E / Sec. 4.10, are quoted per call; this gives the same split for the encode phases).
  * phase_events: HOST array of 4 caller-created hipEvent_t (any entry, or the array, may be
  * NULL), recorded on `stream`: [0] before the first kernel, [1] after the median select,
- * [2] after mask + scan, [3] after the search kernel.  Otherwise identical to hqmq_encode. */
+ * [2] after the search kernel (flags, scales, codes), [3] after the outlier list (scan and
+ * payload gather).  Otherwise identical to hqmq_encode. */
 int32_t hqmq_encode_timed(const hqmq_params *params, const void *x_dev, const float *sec_dev,
                           const hqmq_encoded *enc, uint64_t outlier_capacity, void *workspace_dev,
                           uint64_t workspace_bytes, void *stream, void *const *phase_events);

@@ -66,29 +66,32 @@ static Geometry make_geometry(const hqmq_params *p)
     for (int j = 0; j < 16; ++j)
         if ((1 << j) == p->S)
             g.log2_S = j;
-    g.n_mask_blocks_per_seg = (uint32_t)((p->T + kMaskRows - 1) / kMaskRows);
+    g.n_search_blocks_per_seg = (uint32_t)((p->T + kSearchRows - 1) / kSearchRows);
     return g;
 }
 
 struct WorkspaceLayout {
-    uint64_t state, thr, hist, block_sum, block_pre, total;
+    uint64_t state, thr, hist0, hist1, cand_count, cand, block_sum, block_pre, total;
 };
 
 static WorkspaceLayout workspace_layout(const Geometry &g)
 {
     WorkspaceLayout l;
     uint64_t off = 0;
-    const uint64_t n_blocks = (uint64_t)g.B * g.H * g.n_mask_blocks_per_seg;
-    l.state = off;
-    off = align_up(off + (uint64_t)g.H * sizeof(SelectState), 256);
-    l.thr = off;
-    off = align_up(off + (uint64_t)g.H * sizeof(double), 256);
-    l.hist = off;
-    off = align_up(off + (uint64_t)g.H * kHistBins * sizeof(uint32_t), 256);
-    l.block_sum = off;
-    off = align_up(off + n_blocks * sizeof(uint32_t), 256);
-    l.block_pre = off;
-    off = align_up(off + n_blocks * sizeof(uint32_t), 256);
+    const uint64_t n_blocks = (uint64_t)g.B * g.H * g.n_search_blocks_per_seg;
+    auto take = [&](uint64_t bytes) {
+        const uint64_t at = off;
+        off = align_up(off + bytes, 256);
+        return at;
+    };
+    l.state = take((uint64_t)g.H * sizeof(SelectState));
+    l.thr = take((uint64_t)g.H * sizeof(double));
+    l.hist0 = take((uint64_t)g.H * kBins0 * sizeof(uint32_t));
+    l.hist1 = take((uint64_t)g.H * kBins1 * sizeof(uint32_t));
+    l.cand_count = take((uint64_t)g.H * sizeof(uint32_t));
+    l.cand = take((uint64_t)g.H * kCandCap * sizeof(unsigned long long));
+    l.block_sum = take(n_blocks * sizeof(uint32_t));
+    l.block_pre = take(n_blocks * sizeof(uint32_t));
     l.total = off;
     return l;
 }
@@ -192,7 +195,10 @@ static int32_t encode_impl(const hqmq_params *params, const void *x_dev, const f
     Workspace ws;
     ws.state = reinterpret_cast<SelectState *>(wsb + l.state);
     ws.thr = reinterpret_cast<double *>(wsb + l.thr);
-    ws.hist = reinterpret_cast<uint32_t *>(wsb + l.hist);
+    ws.hist0 = reinterpret_cast<uint32_t *>(wsb + l.hist0);
+    ws.hist1 = reinterpret_cast<uint32_t *>(wsb + l.hist1);
+    ws.cand_count = reinterpret_cast<uint32_t *>(wsb + l.cand_count);
+    ws.cand = reinterpret_cast<unsigned long long *>(wsb + l.cand);
     ws.block_sum = reinterpret_cast<uint32_t *>(wsb + l.block_sum);
     ws.block_pre = reinterpret_cast<uint32_t *>(wsb + l.block_pre);
 
@@ -214,12 +220,12 @@ static int32_t encode_impl(const hqmq_params *params, const void *x_dev, const f
         err = mark(1);
     if (err != hipSuccess)
         return hip_failed(err);
-    err = launch_mask_scan(x, g, ws, ep, outlier_capacity, st);
+    err = launch_search(x, sec_dev, g, ws, ep, st);
     if (err == hipSuccess)
         err = mark(2);
     if (err != hipSuccess)
         return hip_failed(err);
-    err = launch_search(x, sec_dev, g, ws, ep, outlier_capacity, st);
+    err = launch_outlier_list(x, g, ws, ep, outlier_capacity, st);
     if (err == hipSuccess)
         err = mark(3);
     if (err != hipSuccess)

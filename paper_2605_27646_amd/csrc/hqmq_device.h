@@ -10,17 +10,16 @@
 namespace hqmq {
 
 constexpr int kChunksPerRow = 32;    // D = 128
-constexpr int kHistBins = 8192;      // widest radix digit: 13 bits
-constexpr int kHistRows = 256;       // rows of one (b, h) segment per histogram block
-constexpr int kMaskRows = 256;       // rows per mask block = granularity of the outlier scan
-constexpr int kSearchRows = 64;      // rows per search block (divides kMaskRows)
-constexpr int kDecodeRows = 128;     // rows per decode block
-constexpr int kThreads = 256;        // every kernel runs 4 wave64 per workgroup
+constexpr int kSearchRows = 64;      // rows per search workgroup = granularity of the outlier scan
+constexpr int kThreads = 256;        // default workgroup: 4 wave64
 
-// Radix-select digits over the 63 value bits of a non-negative IEEE double, high to low.
-constexpr int kNumPasses = 5;
-__host__ __device__ constexpr int pass_bits(int p) { return p < 3 ? 13 : 12; }
-__host__ __device__ constexpr int pass_shift(int p) { return p == 0 ? 50 : p == 1 ? 37 : p == 2 ? 24 : p == 3 ? 12 : 0; }
+// Radix select over the 63 value bits of a non-negative IEEE double: two histogram digits from
+// the top, then a candidate list for the keys sharing those 23 bits.
+constexpr int kBits0 = 13, kShift0 = 50, kBins0 = 1 << kBits0;  // bits 62..50
+constexpr int kBits1 = 10, kShift1 = 40, kBins1 = 1 << kBits1;  // bits 49..40
+constexpr int kCandCap = 16384;      // candidate keys kept per head
+constexpr int kSelectThreads = 1024; // workgroup of the select sweeps
+constexpr int kSelectRows = 1024;    // rows of one (b, h) segment per select workgroup
 
 // Per-head state of the running radix select.
 struct SelectState {
@@ -39,16 +38,19 @@ struct Geometry {
     float inv_L;          // 1 / (2^b_r - 1)
     int32_t log2_S;       // log2(S) when S is a power of two, else -1
     float inv_S;          // (1/S)(1 + 2^-18): uint(float(k) * inv_S) == k / S for every k < 48 S, S <= 512
-    uint32_t n_mask_blocks_per_seg;
+    uint32_t n_search_blocks_per_seg;  // ceil(T / kSearchRows)
 };
 
 // Workspace carve-up (device pointers into the caller's workspace).
 struct Workspace {
-    SelectState *state;   // [H]
-    double *thr;          // [H] outlier threshold on squared norms
-    uint32_t *hist;       // [H][kHistBins]
-    uint32_t *block_sum;  // [B*H*n_mask_blocks_per_seg]
-    uint32_t *block_pre;  // same shape, exclusive prefix
+    SelectState *state;            // [H]
+    double *thr;                   // [H] outlier threshold on squared norms
+    uint32_t *hist0;               // [H][kBins0]
+    uint32_t *hist1;               // [H][kBins1]
+    uint32_t *cand_count;          // [H] keys in the candidate bucket (may exceed kCandCap)
+    unsigned long long *cand;      // [H][kCandCap]
+    uint32_t *block_sum;           // [B*H*n_search_blocks_per_seg] outliers per search workgroup
+    uint32_t *block_pre;           // same shape, exclusive prefix
 };
 
 struct EncodedPtrs {
@@ -89,10 +91,10 @@ __device__ __forceinline__ unsigned long long key_of(double r2)
 // Launchers implemented in the kernel translation units (host side).
 hipError_t launch_select_median(const _Float16 *x, const Geometry &g, const Workspace &ws, float C,
                                 bool no_outliers, const EncodedPtrs &enc, hipStream_t stream);
-hipError_t launch_mask_scan(const _Float16 *x, const Geometry &g, const Workspace &ws,
-                            const EncodedPtrs &enc, uint64_t outlier_capacity, hipStream_t stream);
 hipError_t launch_search(const _Float16 *x, const float *sec, const Geometry &g, const Workspace &ws,
-                         const EncodedPtrs &enc, uint64_t outlier_capacity, hipStream_t stream);
+                         const EncodedPtrs &enc, hipStream_t stream);
+hipError_t launch_outlier_list(const _Float16 *x, const Geometry &g, const Workspace &ws,
+                               const EncodedPtrs &enc, uint64_t outlier_capacity, hipStream_t stream);
 hipError_t launch_decode(const Geometry &g, const EncodedPtrs &enc, uint64_t outlier_capacity,
                          const float *sec, _Float16 *out, hipStream_t stream);
 

@@ -1,36 +1,95 @@
 // Med3x outlier extraction, first half: the exact per-head median of the squared chunk norms
-// and the outlier mask (paper Sec. 3 "Median-multiplier outlier extraction", Alg. 1 "Outlier
-// extraction").
+// (paper Sec. 3 "Median-multiplier outlier extraction", Alg. 1 "Outlier extraction").
 //
 // The median is the lower median (element (n-1)/2 of the sorted norms) of all B*T*32 chunks of
 // a head.  Non-negative IEEE doubles order like their bit patterns read as unsigned integers,
 // so the median is found by a most-significant-digit radix select on the 63 value bits of r^2:
-// each pass histograms one digit of the keys that still match the digits fixed so far, a tiny
-// kernel picks the digit bucket holding the wanted rank.  Nothing is sorted and no float
-// arithmetic is involved after r^2 itself, so the result is the exact order statistic.
-//
-// All passes are HBM-bound sweeps over the fp16 tensor (8 B per chunk); r^2 is recomputed in
-// registers each time, which costs less than storing and reloading 8-byte keys.
+//   pass 0  histogram of bits 62..50 (sign-free exponent + 2 mantissa bits), all keys
+//   pass 1  histogram of bits 49..40 of the keys in the bucket that holds the wanted rank
+//   collect the few keys that share the 23 bits fixed so far go to a candidate list
+//   finish  one workgroup per head selects the wanted rank among the candidates (radix select on
+//           the low 40 bits) and writes the outlier threshold C^2 * median.
+// Nothing is sorted and no float arithmetic is involved after r^2 itself, so the result is the
+// exact order statistic.  Each pass recomputes r^2 in registers from the fp16 tensor (8 B per
+// chunk, HBM-bound); the bucket choice of the previous pass is re-derived by every workgroup
+// from the (L2-resident) histogram instead of costing a kernel launch of its own.
+// If a head has more keys in the candidate bucket than the list holds (many equal norms: a
+// constant or coarsely quantised tensor), the finishing workgroup falls back to radix-selecting
+// the low bits over the head's raw rows itself: slow, exact, and only for such inputs.
 #include "hqmq_device.h"
 
 namespace hqmq {
 
+namespace {
+
+constexpr unsigned long long kKeyMask = 0x7fffffffffffffffull;
+
+// Exclusive scan position of `rank` in a histogram: returns the bin holding the rank-th key
+// (0-based) and how many keys lie in earlier bins.  Called by every thread of the block with the
+// same arguments; `hist` may be global memory.  kBins is a multiple of the block size.
+template <int kBins, int kBlock>
+__device__ __forceinline__ void pick_bin(const uint32_t *hist, uint32_t rank, uint32_t *scratch /* LDS, kBlock + 2 */,
+                                         uint32_t &bin_out, uint32_t &before_out)
+{
+    constexpr int kPer = kBins / kBlock;
+    static_assert(kBins % kBlock == 0 && kBlock % 64 == 0, "bins must tile the block");
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    uint32_t local[kPer];
+    uint32_t sum = 0;
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+        local[i] = hist[tid * kPer + i];
+        sum += local[i];
+    }
+    // inclusive scan over the block: shuffle scan inside each wave, then wave totals through LDS
+    uint32_t inc = sum;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        uint32_t o = __shfl_up(inc, d, 64);
+        if (lane >= d)
+            inc += o;
+    }
+    if (lane == 63)
+        scratch[wv] = inc;
+    __syncthreads();
+    uint32_t wave_before = 0;
+    for (int k = 0; k < kBlock / 64; ++k)
+        if (k < wv)
+            wave_before += scratch[k];
+    uint32_t before = wave_before + inc - sum;
+    if (rank >= before && rank < before + sum) {
+        bool found = false;
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            if (!found && rank < before + local[i]) {
+                scratch[kBlock] = tid * kPer + i;
+                scratch[kBlock + 1] = before;
+                found = true;
+            }
+            if (!found)
+                before += local[i];
+        }
+    }
+    __syncthreads();
+    bin_out = scratch[kBlock];
+    before_out = scratch[kBlock + 1];
+    __syncthreads();
+}
+
+}  // namespace
+
 // ---------------------------------------------------------------------------------------
 // reset of the per-call scratch state
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void k_init(Geometry g, Workspace ws, EncodedPtrs enc,
-                                                   uint32_t n_hist, uint32_t n_blocks)
+__global__ __launch_bounds__(kThreads) void k_init(Geometry g, Workspace ws, EncodedPtrs enc)
 {
-    uint32_t i = blockIdx.x * kThreads + threadIdx.x;
-    if (i < n_hist)
-        ws.hist[i] = 0;
-    if (i < n_blocks)
-        ws.block_sum[i] = 0;
+    const uint32_t i = blockIdx.x * kThreads + threadIdx.x;
+    if (i < (uint32_t)g.H * kBins0)
+        ws.hist0[i] = 0;
+    if (i < (uint32_t)g.H * kBins1)
+        ws.hist1[i] = 0;
     if (i < (uint32_t)g.H) {
-        uint64_t n_h = (uint64_t)g.B * g.T * kChunksPerRow;
-        ws.state[i].prefix = 0;
-        ws.state[i].rank = (uint32_t)((n_h - 1) / 2);
-        ws.state[i].pad = 0;
+        ws.cand_count[i] = 0;
         ws.thr[i] = __longlong_as_double(0x7ff0000000000000LL);  // +inf: nothing is flagged
     }
     if (i <= (uint32_t)g.H)
@@ -40,170 +99,157 @@ __global__ __launch_bounds__(kThreads) void k_init(Geometry g, Workspace ws, Enc
 }
 
 // ---------------------------------------------------------------------------------------
-// one radix pass: histogram digit `pass` of the keys matching the current prefix
-// grid = (ceil(T / kHistRows), B*H); one lane per chunk, 8 rows per block iteration
+// sweeps.  grid = (ceil(T / kSelectRows), B*H), 1024 threads: one lane per chunk, 32 rows per
+// block iteration, four independent 8-byte loads in flight per lane.
+//   MODE 0: histogram of digit 0            MODE 1: pick digit 0, histogram of digit 1
+//   MODE 2: pick digits 0 and 1, append the keys of the chosen bucket to the candidate list
 // ---------------------------------------------------------------------------------------
-template <int PASS>
-__global__ __launch_bounds__(kThreads) void k_hist(const _Float16 *__restrict__ x, Geometry g,
-                                                   Workspace ws)
+template <int MODE>
+__global__ __launch_bounds__(kSelectThreads) void k_select_sweep(const _Float16 *__restrict__ x, Geometry g,
+                                                                 Workspace ws)
 {
-    constexpr int kBits = pass_bits(PASS);
-    constexpr int kShift = pass_shift(PASS);
-    constexpr int kBins = 1 << kBits;
-    __shared__ uint32_t lh[kBins];
+    constexpr int kLdsBins = MODE == 0 ? kBins0 : kBins1;
+    __shared__ uint32_t lh[MODE == 2 ? 1 : kLdsBins];
+    __shared__ uint32_t scratch[kSelectThreads + 2];
 
     const int seg = blockIdx.y, b = seg / g.H, h = seg % g.H;
-    for (int i = threadIdx.x; i < kBins; i += kThreads)
-        lh[i] = 0;
-    __syncthreads();
+    const uint32_t rank0 = (uint32_t)(((uint64_t)g.B * g.T * kChunksPerRow - 1) / 2);
+    uint32_t bin0 = 0, before0 = 0, bin1 = 0, before1 = 0;
+    if (MODE >= 1)
+        pick_bin<kBins0, kSelectThreads>(ws.hist0 + (size_t)h * kBins0, rank0, scratch, bin0, before0);
+    if (MODE == 2) {
+        pick_bin<kBins1, kSelectThreads>(ws.hist1 + (size_t)h * kBins1, rank0 - before0, scratch, bin1, before1);
+        if (blockIdx.x == 0 && b == 0 && threadIdx.x == 0) {
+            ws.state[h].prefix = ((unsigned long long)bin0 << kBits1) | bin1;
+            ws.state[h].rank = rank0 - before0 - before1;
+        }
+    }
+    if (MODE != 2) {
+        for (int i = threadIdx.x; i < kLdsBins; i += kSelectThreads)
+            lh[i] = 0;
+        __syncthreads();
+    }
+    const unsigned long long prefix = MODE == 1 ? (unsigned long long)bin0
+                                                : (((unsigned long long)bin0 << kBits1) | bin1);
 
-    const unsigned long long prefix = (PASS == 0) ? 0ull : ws.state[h].prefix;
-    const int c = threadIdx.x & 31, sub = threadIdx.x >> 5;
-    const int t0 = blockIdx.x * kHistRows;
-    const int t1 = min(g.T, t0 + kHistRows);
+    const int c = threadIdx.x & 31, sub = threadIdx.x >> 5;  // 32 rows per iteration
+    const int t0 = blockIdx.x * kSelectRows;
+    const int t1 = min(g.T, t0 + kSelectRows);
     const _Float16 *base = x + (int64_t)b * g.sb + (int64_t)h * g.sh + 4 * c;
+    unsigned long long *cand = ws.cand + (size_t)h * kCandCap;
 
-    for (int t = t0 + sub; t < t1; t += 32) {
-        // four independent 8-byte loads in flight per lane
+    for (int tb = t0; tb < t1; tb += 128) {  // uniform over the block
         half4_t v[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            int tt = t + 8 * u;
+            const int tt = tb + sub + 32 * u;
             v[u] = (tt < t1) ? load_chunk(base + (int64_t)tt * g.st) : half4_t{0, 0, 0, 0};
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            if (t + 8 * u < t1) {
-                unsigned long long key = key_of(chunk_norm2(v[u])) & 0x7fffffffffffffffull;
-                if (PASS == 0 || (key >> (kShift + kBits)) == prefix)
-                    atomicAdd(&lh[(uint32_t)(key >> kShift) & (kBins - 1)], 1u);
+            const bool in = (tb + sub + 32 * u) < t1;
+            const unsigned long long key = key_of(chunk_norm2(v[u])) & kKeyMask;
+            if (MODE == 0) {
+                if (in)
+                    atomicAdd(&lh[(uint32_t)(key >> kShift0)], 1u);
+            } else if (MODE == 1) {
+                if (in && (key >> kShift0) == prefix)
+                    atomicAdd(&lh[(uint32_t)(key >> kShift1) & (kBins1 - 1)], 1u);
+            } else {
+                // one counter update per wave: ballot, leader adds, lanes take consecutive slots
+                const bool hit = in && (key >> kShift1) == prefix;
+                const unsigned long long m = __ballot(hit);
+                if (m) {
+                    uint32_t basepos = 0;
+                    const int leader = __ffsll((long long)m) - 1;
+                    if ((int)(threadIdx.x & 63) == leader)
+                        basepos = atomicAdd(&ws.cand_count[h], (uint32_t)__popcll(m));
+                    basepos = __shfl(basepos, leader, 64);
+                    if (hit) {
+                        const uint32_t pos = basepos + __popcll(m & ((1ull << (threadIdx.x & 63)) - 1ull));
+                        if (pos < (uint32_t)kCandCap)
+                            cand[pos] = key;
+                    }
+                }
             }
         }
     }
-    __syncthreads();
-    uint32_t *gh = ws.hist + (size_t)h * kHistBins;
-    for (int i = threadIdx.x; i < kBins; i += kThreads) {
-        uint32_t n = lh[i];
-        if (n)
-            atomicAdd(&gh[i], n);
+    if (MODE != 2) {
+        __syncthreads();
+        uint32_t *gh = MODE == 0 ? ws.hist0 + (size_t)h * kBins0 : ws.hist1 + (size_t)h * kBins1;
+        for (int i = threadIdx.x; i < kLdsBins; i += kSelectThreads) {
+            const uint32_t n = lh[i];
+            if (n)
+                atomicAdd(&gh[i], n);
+        }
     }
 }
 
 // ---------------------------------------------------------------------------------------
-// pick the bucket that holds the wanted rank; one block per head.
-// After the last pass the prefix is the full key: the median's bit pattern.
+// finish: one workgroup per head.  Radix-selects the low kShift1 = 40 bits (4 digits of 10 bits)
+// among the keys whose top 23 bits equal the chosen prefix: from the candidate list when it holds
+// them all, otherwise from the head's raw rows.  Writes thr[h] = fl(fl(C*C) * median).
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void k_pick(Geometry g, Workspace ws, int pass, float C)
+__global__ __launch_bounds__(kSelectThreads) void k_select_finish(const _Float16 *__restrict__ x, Geometry g,
+                                                                  Workspace ws, float C)
 {
+    __shared__ uint32_t lh[kBins1];
+    __shared__ uint32_t scratch[kSelectThreads + 2];
     const int h = blockIdx.x;
-    const int bits = pass_bits(pass);
-    const int bins = 1 << bits;
-    const int per = bins / kThreads;  // 32 or 16 consecutive bins per thread
-    uint32_t *gh = ws.hist + (size_t)h * kHistBins;
-    __shared__ uint32_t part[kThreads];
-    __shared__ uint32_t sel_bin, sel_before;
+    const unsigned long long prefix = ws.state[h].prefix;  // top 23 bits, right aligned
+    uint32_t rank = ws.state[h].rank;
+    const uint32_t n_cand = ws.cand_count[h];
+    const bool from_list = n_cand <= (uint32_t)kCandCap;
+    const unsigned long long *cand = ws.cand + (size_t)h * kCandCap;
 
-    uint32_t local[32];
-    uint32_t sum = 0;
-#pragma unroll
-    for (int i = 0; i < 32; ++i) {
-        local[i] = (i < per) ? gh[threadIdx.x * per + i] : 0u;
-        sum += local[i];
-    }
-    part[threadIdx.x] = sum;
-    __syncthreads();
-    // exclusive prefix of the per-thread sums (256 values: a serial scan by one thread is
-    // cheap next to the sweeps around it)
-    if (threadIdx.x == 0) {
-        uint32_t run = 0;
-        for (int i = 0; i < kThreads; ++i) {
-            uint32_t v = part[i];
-            part[i] = run;
-            run += v;
-        }
-    }
-    __syncthreads();
-    const uint32_t rank = ws.state[h].rank;
-    uint32_t before = part[threadIdx.x];
-    if (rank >= before && rank < before + sum) {
-        bool found = false;
-#pragma unroll
-        for (int i = 0; i < 32; ++i) {
-            if (!found && rank < before + local[i]) {
-                sel_bin = threadIdx.x * per + i;
-                sel_before = before;
-                found = true;
+    unsigned long long low = 0;  // low-bit digits fixed so far, right aligned
+    int fixed = 0;               // number of low-part bits fixed (from the top of the 40)
+    for (int pass = 0; pass < 4; ++pass) {
+        for (int i = threadIdx.x; i < kBins1; i += kSelectThreads)
+            lh[i] = 0;
+        __syncthreads();
+        const int shift = kShift1 - 10 * (pass + 1);  // 30, 20, 10, 0
+        const unsigned long long want = (prefix << fixed) | low;  // compare key >> (shift + 10)
+        if (from_list) {
+            for (uint32_t i = threadIdx.x; i < n_cand; i += kSelectThreads) {
+                const unsigned long long key = cand[i];
+                if ((key >> (shift + 10)) == want)
+                    atomicAdd(&lh[(uint32_t)(key >> shift) & (kBins1 - 1)], 1u);
             }
-            if (!found)
-                before += local[i];
+        } else {
+            // rare path: sweep the head's rows (every batch entry), one lane per chunk
+            const int c = threadIdx.x & 31, sub = threadIdx.x >> 5;
+            for (int b = 0; b < g.B; ++b) {
+                const _Float16 *base = x + (int64_t)b * g.sb + (int64_t)h * g.sh + 4 * c;
+                for (int t = sub; t < g.T; t += kSelectThreads / 32) {
+                    const unsigned long long key = key_of(chunk_norm2(load_chunk(base + (int64_t)t * g.st))) & kKeyMask;
+                    if ((key >> (shift + 10)) == want)
+                        atomicAdd(&lh[(uint32_t)(key >> shift) & (kBins1 - 1)], 1u);
+                }
+            }
         }
+        __syncthreads();
+        uint32_t bin, before;
+        pick_bin<kBins1, kSelectThreads>(lh, rank, scratch, bin, before);
+        rank -= before;
+        low = (low << 10) | bin;
+        fixed += 10;
     }
-    __syncthreads();
-    for (int i = 0; i < per; ++i)
-        gh[threadIdx.x * per + i] = 0;  // ready for the next pass
     if (threadIdx.x == 0) {
-        unsigned long long prefix = (ws.state[h].prefix << bits) | sel_bin;
-        ws.state[h].prefix = prefix;
-        ws.state[h].rank = rank - sel_before;
-        if (pass == kNumPasses - 1) {
-            // threshold on squares: fl(fl(C*C) * median), C widened from fp32
-            double c = (double)C;
-            double c2 = c * c;
-            ws.thr[h] = c2 * __longlong_as_double((long long)prefix);
-        }
+        const unsigned long long median_bits = (prefix << kShift1) | low;
+        // threshold on squares: fl(fl(C*C) * median), C widened from fp32
+        const double c = (double)C;
+        const double c2 = c * c;
+        ws.thr[h] = c2 * __longlong_as_double((long long)median_bits);
     }
 }
 
 // ---------------------------------------------------------------------------------------
-// outlier mask: one flag word per row, the outlier count of every block of kMaskRows rows
-// and the per-head totals.  grid = (ceil(T / kMaskRows), B*H)
-// ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void k_mask(const _Float16 *__restrict__ x, Geometry g,
-                                                   Workspace ws, EncodedPtrs enc)
-{
-    const int seg = blockIdx.y, b = seg / g.H, h = seg % g.H;
-    const double thr = ws.thr[h];
-    const int c = threadIdx.x & 31, sub = threadIdx.x >> 5;
-    const int t0 = blockIdx.x * kMaskRows;
-    const int t1 = min(g.T, t0 + kMaskRows);
-    const _Float16 *base = x + (int64_t)b * g.sb + (int64_t)h * g.sh + 4 * c;
-    const int64_t row0 = (int64_t)seg * g.T;
-    uint32_t count = 0;  // per wave (uniform)
-
-    // tb is uniform over the block, so every lane reaches every ballot
-    for (int tb = t0; tb < t1; tb += 32) {
-        half4_t v[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            int tt = tb + sub + 8 * u;
-            v[u] = (tt < t1) ? load_chunk(base + (int64_t)tt * g.st) : half4_t{0, 0, 0, 0};
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            int tt = tb + sub + 8 * u;
-            bool flag = (tt < t1) && (chunk_norm2(v[u]) > thr);
-            unsigned long long ballot = __ballot(flag);
-            uint32_t word = (threadIdx.x & 32) ? (uint32_t)(ballot >> 32) : (uint32_t)ballot;
-            if (c == 0 && tt < t1)
-                enc.flags[row0 + tt] = word;
-            count += __popcll(ballot);
-        }
-    }
-    __shared__ uint32_t wave_count[kThreads / 64];
-    if ((threadIdx.x & 63) == 0)
-        wave_count[threadIdx.x >> 6] = count;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        uint32_t total = wave_count[0] + wave_count[1] + wave_count[2] + wave_count[3];
-        ws.block_sum[(size_t)seg * g.n_mask_blocks_per_seg + blockIdx.x] = total;
-        if (total)
-            atomicAdd(&enc.n_outliers[h], total);
-    }
-}
-
-// ---------------------------------------------------------------------------------------
-// exclusive scan of the block sums (linear row order), totals and overflow status.
-// One block; the number of entries is n_rows / 256, a few thousand at most per tensor.
+// outlier bookkeeping after the search kernel has written the flag words, the per-row offsets
+// local to its 64-row workgroup and the workgroup totals:
+//   k_scan    exclusive scan of the workgroup totals (linear row order), per-head totals, status
+//   k_gather  adds the workgroup prefix to every row offset and copies the flagged chunks into
+//             the outlier list in ascending linear chunk order
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void k_scan(Geometry g, Workspace ws, EncodedPtrs enc,
                                                uint32_t n_blocks, uint64_t n_rows,
@@ -212,13 +258,13 @@ __global__ __launch_bounds__(1024) void k_scan(Geometry g, Workspace ws, Encoded
     __shared__ uint32_t wave_tot[16];
     __shared__ uint32_t carry_s;
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const uint32_t blocks_per_seg = g.n_search_blocks_per_seg;
     if (threadIdx.x == 0)
         carry_s = 0;
     __syncthreads();
     for (uint32_t start = 0; start < n_blocks; start += 1024) {
-        uint32_t i = start + threadIdx.x;
-        uint32_t v = (i < n_blocks) ? ws.block_sum[i] : 0;
-        // inclusive scan inside the wave
+        const uint32_t i = start + threadIdx.x;
+        const uint32_t v = (i < n_blocks) ? ws.block_sum[i] : 0;
         uint32_t inc = v;
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) {
@@ -231,12 +277,12 @@ __global__ __launch_bounds__(1024) void k_scan(Geometry g, Workspace ws, Encoded
         __syncthreads();
         uint32_t wave_before = 0, all = 0;
         for (int k = 0; k < 16; ++k) {
-            uint32_t wt = wave_tot[k];
+            const uint32_t wt = wave_tot[k];
             if (k < wv)
                 wave_before += wt;
             all += wt;
         }
-        uint32_t carry = carry_s;
+        const uint32_t carry = carry_s;
         if (i < n_blocks)
             ws.block_pre[i] = carry + wave_before + inc - v;
         __syncthreads();
@@ -244,12 +290,49 @@ __global__ __launch_bounds__(1024) void k_scan(Geometry g, Workspace ws, Encoded
             carry_s = carry + all;
         __syncthreads();
     }
+    const uint32_t total = carry_s;
+    // per-head totals from the prefix array: a head's workgroups are contiguous inside each batch
+    // entry's segment (the block's own global writes are visible to it after the barriers above)
+    for (uint32_t h = threadIdx.x; h < (uint32_t)g.H; h += 1024) {
+        uint32_t sum = 0;
+        for (uint32_t b = 0; b < (uint32_t)g.B; ++b) {
+            const uint32_t first = (b * (uint32_t)g.H + h) * blocks_per_seg, last = first + blocks_per_seg;
+            const uint32_t hi = (last < n_blocks) ? ws.block_pre[last] : total;
+            sum += hi - ws.block_pre[first];
+        }
+        enc.n_outliers[h] = sum;
+    }
     if (threadIdx.x == 0) {
-        uint32_t total = carry_s;
         enc.n_outliers[g.H] = total;
         enc.row_off[n_rows] = total;
         if ((uint64_t)total > outlier_capacity)
             enc.status[0] = HQMQ_STATUS_OUTLIER_OVERFLOW;
+    }
+}
+
+// grid = (ceil(T / 256), B*H), one thread per row
+__global__ __launch_bounds__(kThreads) void k_gather(const _Float16 *__restrict__ x, Geometry g,
+                                                     Workspace ws, EncodedPtrs enc,
+                                                     uint64_t outlier_capacity)
+{
+    const int seg = blockIdx.y, b = seg / g.H, h = seg % g.H;
+    const int t = blockIdx.x * kThreads + threadIdx.x;
+    if (t >= g.T)
+        return;
+    const int64_t R = (int64_t)seg * g.T + t;
+    uint32_t word = enc.flags[R];
+    const uint32_t off = enc.row_off[R] + ws.block_pre[(size_t)seg * g.n_search_blocks_per_seg + t / kSearchRows];
+    enc.row_off[R] = off;
+    if (!word)
+        return;
+    const _Float16 *row = x + (int64_t)b * g.sb + (int64_t)h * g.sh + (int64_t)t * g.st;
+    uint64_t pos = off;
+    while (word) {
+        const int c = __ffs((int)word) - 1;
+        word &= word - 1;
+        if (pos < outlier_capacity)
+            *reinterpret_cast<uint2 *>(enc.outliers + 4 * pos) = *reinterpret_cast<const uint2 *>(row + 4 * c);
+        ++pos;
     }
 }
 
@@ -259,38 +342,26 @@ __global__ __launch_bounds__(1024) void k_scan(Geometry g, Workspace ws, Encoded
 hipError_t launch_select_median(const _Float16 *x, const Geometry &g, const Workspace &ws, float C,
                                 bool no_outliers, const EncodedPtrs &enc, hipStream_t stream)
 {
-    const uint32_t n_hist = (uint32_t)g.H * kHistBins;
-    const uint32_t n_blocks = (uint32_t)g.B * g.H * g.n_mask_blocks_per_seg;
-    uint32_t n_init = n_hist > n_blocks ? n_hist : n_blocks;
-    if (n_init < (uint32_t)g.H + 1)
-        n_init = g.H + 1;
-    hipLaunchKernelGGL(k_init, dim3((n_init + kThreads - 1) / kThreads), dim3(kThreads), 0, stream, g,
-                       ws, enc, n_hist, n_blocks);
+    uint32_t n_init = (uint32_t)g.H * kBins0;
+    hipLaunchKernelGGL(k_init, dim3((n_init + kThreads - 1) / kThreads), dim3(kThreads), 0, stream, g, ws, enc);
     if (!no_outliers) {
-        dim3 grid((g.T + kHistRows - 1) / kHistRows, g.B * g.H);
-        hipLaunchKernelGGL(k_hist<0>, grid, dim3(kThreads), 0, stream, x, g, ws);
-        hipLaunchKernelGGL(k_pick, dim3(g.H), dim3(kThreads), 0, stream, g, ws, 0, C);
-        hipLaunchKernelGGL(k_hist<1>, grid, dim3(kThreads), 0, stream, x, g, ws);
-        hipLaunchKernelGGL(k_pick, dim3(g.H), dim3(kThreads), 0, stream, g, ws, 1, C);
-        hipLaunchKernelGGL(k_hist<2>, grid, dim3(kThreads), 0, stream, x, g, ws);
-        hipLaunchKernelGGL(k_pick, dim3(g.H), dim3(kThreads), 0, stream, g, ws, 2, C);
-        hipLaunchKernelGGL(k_hist<3>, grid, dim3(kThreads), 0, stream, x, g, ws);
-        hipLaunchKernelGGL(k_pick, dim3(g.H), dim3(kThreads), 0, stream, g, ws, 3, C);
-        hipLaunchKernelGGL(k_hist<4>, grid, dim3(kThreads), 0, stream, x, g, ws);
-        hipLaunchKernelGGL(k_pick, dim3(g.H), dim3(kThreads), 0, stream, g, ws, 4, C);
+        dim3 grid((g.T + kSelectRows - 1) / kSelectRows, g.B * g.H);
+        hipLaunchKernelGGL(k_select_sweep<0>, grid, dim3(kSelectThreads), 0, stream, x, g, ws);
+        hipLaunchKernelGGL(k_select_sweep<1>, grid, dim3(kSelectThreads), 0, stream, x, g, ws);
+        hipLaunchKernelGGL(k_select_sweep<2>, grid, dim3(kSelectThreads), 0, stream, x, g, ws);
+        hipLaunchKernelGGL(k_select_finish, dim3(g.H), dim3(kSelectThreads), 0, stream, x, g, ws, C);
     }
     return hipGetLastError();
 }
 
-hipError_t launch_mask_scan(const _Float16 *x, const Geometry &g, const Workspace &ws,
-                            const EncodedPtrs &enc, uint64_t outlier_capacity, hipStream_t stream)
+hipError_t launch_outlier_list(const _Float16 *x, const Geometry &g, const Workspace &ws,
+                               const EncodedPtrs &enc, uint64_t outlier_capacity, hipStream_t stream)
 {
-    dim3 grid(g.n_mask_blocks_per_seg, g.B * g.H);
-    hipLaunchKernelGGL(k_mask, grid, dim3(kThreads), 0, stream, x, g, ws, enc);
-    const uint32_t n_blocks = (uint32_t)g.B * g.H * g.n_mask_blocks_per_seg;
+    const uint32_t n_blocks = (uint32_t)g.B * g.H * g.n_search_blocks_per_seg;
     const uint64_t n_rows = (uint64_t)g.B * g.H * g.T;
-    hipLaunchKernelGGL(k_scan, dim3(1), dim3(1024), 0, stream, g, ws, enc, n_blocks, n_rows,
-                       outlier_capacity);
+    hipLaunchKernelGGL(k_scan, dim3(1), dim3(1024), 0, stream, g, ws, enc, n_blocks, n_rows, outlier_capacity);
+    dim3 grid((g.T + kThreads - 1) / kThreads, g.B * g.H);
+    hipLaunchKernelGGL(k_gather, grid, dim3(kThreads), 0, stream, x, g, ws, enc, outlier_capacity);
     return hipGetLastError();
 }
 

@@ -1,5 +1,5 @@
-// HQMQ encode, second half: per-row scale, nearest-codeword search, radius code, bit packing
-// and the ordered write of the outlier payload (paper Alg. 1 "Encode", App. D "Encode").
+// HQMQ encode, second half: outlier flags, per-row scale, nearest-codeword search, radius code and
+// bit packing (paper Alg. 1 "Encode", App. D "Encode").
 //
 // Search formulation.  The score of codeword (p, s) is <u, P_p q_s>.  Right multiplication by
 // conj(q_s) is an isometry of R^4 up to the common factor |q_s|^2, so
@@ -97,18 +97,17 @@ __device__ __forceinline__ int nearest_primary(float v0, float v1, float v2, flo
 //   secl  [16*S16][4]   the head's secondaries (zero padded to a multiple of 16)
 //   ubuf  [4 waves][64][4]   unit directions of the wave's 64 chunks (for the B operands)
 //   pack  [4 waves][2][32]   row code words being assembled
-//   roff  [kSearchRows] outlier offsets of the block's rows
+//   rcnt  [kSearchRows] outliers per row of the workgroup
 __global__ __launch_bounds__(kThreads) void k_search(const _Float16 *__restrict__ x,
                                                      const float *__restrict__ sec, Geometry g,
-                                                     Workspace ws, EncodedPtrs enc,
-                                                     uint64_t outlier_capacity)
+                                                     Workspace ws, EncodedPtrs enc)
 {
     extern __shared__ float smem[];
     float *amat = smem;
     float *secl = amat + (size_t)g.S16 * 4 * 64;
     float *ubuf = secl + (size_t)g.S16 * 16 * 4;
     uint32_t *pack = reinterpret_cast<uint32_t *>(ubuf + 4 * 64 * 4);
-    uint32_t *roff = pack + 4 * 2 * 32;
+    uint32_t *rcnt = pack + 4 * 2 * 32;
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int seg = blockIdx.y, b = seg / g.H, h = seg % g.H;
@@ -146,31 +145,6 @@ __global__ __launch_bounds__(kThreads) void k_search(const _Float16 *__restrict_
         amat[idx] = val;
     }
 
-    // ---- setup: outlier offsets of the block's rows -----------------------------------------
-    // offset(row) = prefix of the 256-row scan block + flagged chunks in its earlier rows
-    if (wv == 0) {
-        const int scan_t0 = (t0 / kMaskRows) * kMaskRows;
-        uint32_t before = 0;
-        for (int t = scan_t0 + lane; t < t0; t += 64)
-            before += __popc(enc.flags[row0 + t]);
-#pragma unroll
-        for (int d = 32; d >= 1; d >>= 1)
-            before += __shfl_xor(before, d, 64);
-        before += ws.block_pre[(size_t)seg * g.n_mask_blocks_per_seg + t0 / kMaskRows];
-        const int t = t0 + lane;
-        uint32_t cnt = (t < g.T) ? __popc(enc.flags[row0 + t]) : 0;
-        uint32_t inc = cnt;
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            uint32_t o = __shfl_up(inc, d, 64);
-            if (lane >= d)
-                inc += o;
-        }
-        uint32_t off = before + inc - cnt;
-        roff[lane] = off;
-        if (t < g.T)
-            enc.row_off[row0 + t] = off;
-    }
     __syncthreads();
 
     const double thr = ws.thr[h];
@@ -330,24 +304,39 @@ __global__ __launch_bounds__(kThreads) void k_search(const _Float16 *__restrict_
                 enc.codes[R * g.w + c] = my_pack[half_id * 32 + c];
             if (c == 0) {
                 enc.sigma[R] = sigma16;
-            }
-            if (flagged) {
-                uint64_t pos = (uint64_t)roff[r_in_block] + __popc(word & ((1u << c) - 1u));
-                if (pos < outlier_capacity)
-                    *reinterpret_cast<uint2 *>(enc.outliers + 4 * pos) = __builtin_bit_cast(uint2, xv);
+                enc.flags[R] = word;
             }
         }
+        if (c == 0)
+            rcnt[r_in_block] = valid ? __popc(word) : 0;
+    }
+
+    // ---- outlier offsets local to the workgroup and its total; the global prefix is added by the
+    // scan / gather kernels that follow --------------------------------------------------------------
+    __syncthreads();
+    if (wv == 0) {
+        const uint32_t cnt = rcnt[lane];
+        uint32_t inc = cnt;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            uint32_t o = __shfl_up(inc, d, 64);
+            if (lane >= d)
+                inc += o;
+        }
+        if (t0 + lane < g.T)
+            enc.row_off[row0 + t0 + lane] = inc - cnt;
+        if (lane == 63)
+            ws.block_sum[(size_t)seg * g.n_search_blocks_per_seg + blockIdx.x] = inc;
     }
 }
 
 hipError_t launch_search(const _Float16 *x, const float *sec, const Geometry &g, const Workspace &ws,
-                         const EncodedPtrs &enc, uint64_t outlier_capacity, hipStream_t stream)
+                         const EncodedPtrs &enc, hipStream_t stream)
 {
     dim3 grid((g.T + kSearchRows - 1) / kSearchRows, g.B * g.H);
     size_t lds = ((size_t)g.S16 * 4 * 64 + (size_t)g.S16 * 16 * 4 + 4 * 64 * 4) * sizeof(float) +
                  (4 * 2 * 32 + kSearchRows) * sizeof(uint32_t);
-    hipLaunchKernelGGL(k_search, grid, dim3(kThreads), lds, stream, x, sec, g, ws, enc,
-                       outlier_capacity);
+    hipLaunchKernelGGL(k_search, grid, dim3(kThreads), lds, stream, x, sec, g, ws, enc);
     return hipGetLastError();
 }
 

@@ -142,6 +142,18 @@ def test_all_zero_and_constant_tensors():
     assert stats["outliers"] == 64 * 10
 
 
+def test_median_with_many_equal_norms():
+    """More equal chunk norms than the select kernel's candidate list holds (16384 per head):
+    the exact median must still come out (slow path that re-reads the head's rows)."""
+    x = torch.ones(1, 2, 1100, 128, dtype=torch.float16)             # 35200 chunks of norm 2 per head
+    x[0, 0, :300] = 3.0                                               # head 0: 9600 larger ...
+    x[0, 0, 300:320, :64] = 40.0                                      # ... and a few outliers
+    x[0, 1, ::2] = 2.0                                                # head 1: two values, half each
+    x[0, 1, 7, 4:8] = 9.0
+    stats, e, g = _roundtrip(x, 16)
+    assert stats["outliers"] == 20 * 16 + 1
+
+
 def test_exact_tie_structured_input():
     """Chunks like (a, a, 0, 0) sit on the boundary between several codewords when the
     secondary is the identity; whichever the GPU picks must score as the oracle's best."""
