@@ -26,6 +26,10 @@ METRIC = "HQMQ encode/decode elems/sec at 1 GPU; % of fp32-compute (enc) / HBM (
 PEAK_FP32_TFLOPS = 157.3     # MI355X dense fp32 matrix (and packed vector) peak
 PEAK_HBM_GBS = 8000.0        # MI355X HBM3E peak
 
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs, each scaled
+# by a plain copy of known size in the same run); figures and commands in profiles/hbm_traffic_*.txt
+MEASURED_TRAFFIC_BYTES = {"llama3_8b_32k": {"k_search": 90.2e6, "k_decode": 91.5e6}}
+
 
 def search_flops_per_chunk(S: int) -> float:
     """Flops the implemented search formulation spends per chunk: per secondary one 4x4
@@ -50,6 +54,9 @@ def main() -> int:
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain elementwise copy of one tensor (known bytes) so that a profiler's "
+                         "HBM counters can be scaled against it")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py measures the single-GPU HQMQ path; the units of work (layer, kv head, role) are "
@@ -171,14 +178,23 @@ def main() -> int:
         "bits_per_element_stored": (encs[0].nbytes() - encs[0].outliers.numel() * 2 + 8 * n_out / n_t) * 8
         / wl.elems_per_tensor,
         "roofline": {"kernel": "k_search", "bound": "mfma", "achieved": search_tflops, "peak": PEAK_FP32_TFLOPS,
-                     "unit": "TFLOP/s", "frac": search_tflops / PEAK_FP32_TFLOPS, "traffic": None,
+                     "unit": "TFLOP/s", "frac": search_tflops / PEAK_FP32_TFLOPS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name, {}).get("k_search"),
                      "flops_per_chunk": search_flops_per_chunk(wl.S), "formulation": "W_min (36 S flop/chunk)",
                      "avg_launch_ms": search_ms},
         "roofline_decode": {"kernel": "k_decode", "bound": "hbm", "achieved": dec_gbs, "peak": PEAK_HBM_GBS,
-                            "unit": "GB/s", "frac": dec_gbs / PEAK_HBM_GBS, "traffic": None,
+                            "unit": "GB/s", "frac": dec_gbs / PEAK_HBM_GBS,
+                            "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name, {}).get("k_decode"),
                             "bytes_per_chunk": decode_bytes_per_chunk(info.code_bits, p_out),
                             "avg_launch_ms": decode_ms},
     }
+
+    if args.calibrate_copy:
+        # torch's elementwise kernel reads and writes exactly one tensor's bytes
+        for _ in range(3):
+            torch.add(xs[0], 0, out=outs[0])
+        torch.cuda.synchronize()
+        result["calibration_copy_bytes_each_way"] = xs[0].numel() * 2
 
     # ---- the oracle on the host cores, bounded sample of the same workload --------------------
     if not args.no_cpu_baseline:
