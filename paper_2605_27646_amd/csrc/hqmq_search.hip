@@ -175,17 +175,33 @@ __global__ __launch_bounds__(kThreads) void k_search(const _Float16 *__restrict_
         const uint16_t sigma16 = double_to_half_rne_sat(sqrt(rmax));
         const double sigma = half_bits_to_double(sigma16);
 
+        // Radius code r_q = clamp(rint(sqrt(r2) * L / sigma), 0, L), defined in fp64.  An fp32
+        // evaluation (relative error < 1e-6, i.e. < 3e-4 absolute at L = 255) rounds the same way
+        // unless it lands within 1e-3 of a rounding boundary; only then is the fp64 recipe run
+        // (about one wave in eight takes that branch).
         int rq = 0;
-        if (sigma != 0.0 && r2 != 0.0) {
-            double q = rint((sqrt(r2) * Lq) / sigma);
-            q = q < 0.0 ? 0.0 : (q > Lq ? Lq : q);
-            rq = (int)q;
+        const float r2f = (float)r2;
+        const float r_f = sqrtf(r2f);
+        const float sigma_f = (float)__builtin_bit_cast(_Float16, sigma16);
+        bool exact_needed = false;
+        if (sigma16 != 0 && r2 != 0.0) {
+            const float qf = fminf(r_f * (float)Lq / sigma_f, (float)Lq);
+            const float fr = qf - floorf(qf);
+            exact_needed = fabsf(fr - 0.5f) < 1e-3f;
+            rq = (int)rintf(qf);
+        }
+        if (__any(exact_needed)) {
+            if (exact_needed) {
+                double q = rint((sqrt(r2) * Lq) / sigma);
+                q = q < 0.0 ? 0.0 : (q > Lq ? Lq : q);
+                rq = (int)q;
+            }
         }
 
         // ---- unit direction (fp32) and its transpose into MFMA B operands --------------------
         float u0 = 0.f, u1 = 0.f, u2 = 0.f, u3 = 0.f;
         if (r2 != 0.0) {
-            float inv = 1.0f / sqrtf((float)r2);
+            float inv = 1.0f / r_f;
             u0 = (float)xv[0] * inv;
             u1 = (float)xv[1] * inv;
             u2 = (float)xv[2] * inv;
@@ -265,7 +281,8 @@ __global__ __launch_bounds__(kThreads) void k_search(const _Float16 *__restrict_
         uint32_t code = 0;
         if (!flagged && r2 != 0.0) {
             float bsc = -1.f;
-            uint32_t bk = 0;
+            float w0 = 0.f, w1 = 0.f, w2 = 0.f, w3 = 0.f;
+            int bs = key_mine;
 #pragma unroll
             for (int tt = 0; tt < 4; ++tt) {
                 const int sc_idx = key_mine + 4 * tt;  // < 16 S16: inside the padded table
@@ -275,15 +292,17 @@ __global__ __launch_bounds__(kThreads) void k_search(const _Float16 *__restrict_
                 const float v1 = fmaf(cq, u3, fmaf(-d, u2, fmaf(a, u1, -bq * u0)));
                 const float v2 = fmaf(-bq, u3, fmaf(a, u2, fmaf(d, u1, -cq * u0)));
                 const float v3 = fmaf(a, u3, fmaf(bq, u2, fmaf(-cq, u1, -d * u0)));
-                float sc;
-                const int p = nearest_primary(v0, v1, v2, v3, sc);
-                const uint32_t k = (uint32_t)(p * g.S + sc_idx);
-                if (sc_idx < g.S && (sc > bsc || (sc == bsc && k < bk))) {
+                const float a0 = fabsf(v0), a1 = fabsf(v1), a2 = fabsf(v2), a3 = fabsf(v3);
+                const float sc = fmaxf(fmaxf(fmaxf(a0, a1), fmaxf(a2, a3)), 0.5f * (((a0 + a1) + a2) + a3));
+                if (sc_idx < g.S && sc > bsc) {  // strict: the lowest s wins a tie
                     bsc = sc;
-                    bk = k;
+                    bs = sc_idx;
+                    w0 = v0, w1 = v1, w2 = v2, w3 = v3;
                 }
             }
-            code = ((uint32_t)rq << g.w_idx) | bk;
+            float sc;
+            const int p = nearest_primary(w0, w1, w2, w3, sc);
+            code = ((uint32_t)rq << g.w_idx) | (uint32_t)(p * g.S + bs);
         }
 
         // ---- pack the row: chunk c at bits [c*w, (c+1)*w) -----------------------------------------
