@@ -87,9 +87,9 @@ def main() -> int:
         outs.append(torch.empty_like(x))
     ws = hq.alloc_workspace(params, dev)
     info = hq.hqmq_sizes(params)
+    n_t = len(tensors)
     torch.cuda.synchronize()
 
-    n_t = len(tensors)
     elems_per_step = wl.elems_per_tensor * n_t
     chunks_per_tensor = wl.elems_per_tensor // 4
 
@@ -99,23 +99,26 @@ def main() -> int:
             e.record()          # creates the underlying hipEvent_t
         return evs
 
+    # decode of the whole cache: one batched call (up to 32 tensors per launch)
+    dec_batch = hq.DecodeBatch(params, encs, [sec_all[l, r] for (l, r) in tensors], outs)
+    dec_launches_per_step = (n_t + 31) // 32
+
     def run_step(ev_enc=None, ev_dec=None):
         for i, (l, r) in enumerate(tensors):
             pe = ev_enc[4 * i: 4 * i + 4] if ev_enc is not None else [None] * 4
             hq.hqmq_encode_timed(params, xs[i], sec_all[l, r], encs[i], ws, pe)
         if ev_dec is not None:
             ev_dec[0].record()
-        for i, (l, r) in enumerate(tensors):
-            hq.hqmq_decode(params, encs[i], sec_all[l, r], outs[i])
-            if ev_dec is not None:
-                ev_dec[1 + i].record()
+        hq.hqmq_decode_batch(dec_batch)
+        if ev_dec is not None:
+            ev_dec[1].record()
 
     for _ in range(args.warmup):
         run_step()
     torch.cuda.synchronize()
 
     ev_enc = [new_events(4 * n_t) for _ in range(args.steps)]
-    ev_dec = [new_events(1 + n_t) for _ in range(args.steps)]
+    ev_dec = [new_events(2) for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(args.steps):
@@ -133,10 +136,11 @@ def main() -> int:
             t_search += e1.elapsed_time(e2)
             t_list += e2.elapsed_time(e3)
             t_enc += e0.elapsed_time(e3)
-        t_dec += ev_dec[k][0].elapsed_time(ev_dec[k][n_t])
+        t_dec += ev_dec[k][0].elapsed_time(ev_dec[k][1])
     launches = args.steps * n_t
     search_ms = t_search / launches
-    decode_ms = t_dec / launches
+    decode_ms = t_dec / (args.steps * dec_launches_per_step)   # average k_decode launch
+    tensors_per_dec_launch = n_t / dec_launches_per_step
     enc_ms_step = t_enc / args.steps
     dec_ms_step = t_dec / args.steps
 
@@ -147,7 +151,7 @@ def main() -> int:
 
     flops_launch = search_flops_per_chunk(wl.S) * chunks_per_tensor
     search_tflops = flops_launch / (search_ms * 1e-3) / 1e12
-    dec_bytes_launch = decode_bytes_per_chunk(info.code_bits, p_out) * chunks_per_tensor
+    dec_bytes_launch = decode_bytes_per_chunk(info.code_bits, p_out) * chunks_per_tensor * tensors_per_dec_launch
     dec_gbs = dec_bytes_launch / (decode_ms * 1e-3) / 1e9
 
     result = {
@@ -184,7 +188,9 @@ def main() -> int:
                      "avg_launch_ms": search_ms},
         "roofline_decode": {"kernel": "k_decode", "bound": "hbm", "achieved": dec_gbs, "peak": PEAK_HBM_GBS,
                             "unit": "GB/s", "frac": dec_gbs / PEAK_HBM_GBS,
-                            "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name, {}).get("k_decode"),
+                            "traffic": (MEASURED_TRAFFIC_BYTES[wl.name]["k_decode"] * tensors_per_dec_launch
+                                        if wl.name in MEASURED_TRAFFIC_BYTES else None),
+                            "tensors_per_launch": tensors_per_dec_launch,
                             "bytes_per_chunk": decode_bytes_per_chunk(info.code_bits, p_out),
                             "avg_launch_ms": decode_ms},
     }

@@ -158,6 +158,17 @@ int32_t hqmq_encode_timed(const hqmq_params *params, const void *x_dev, const fl
 int32_t hqmq_decode(const hqmq_params *params, const hqmq_encoded *enc, uint64_t outlier_capacity,
                     const float *sec_dev, void *out_dev, void *stream);
 
+/* Decode n_tensors tensors of ONE shape (the same params: e.g. the K and V caches of every layer)
+ * with as few launches as possible: up to 32 tensors share a launch, which keeps the GPU streaming
+ * across tensor boundaries (the paper's deployment setting decodes the whole cache, Sec. 4.10
+ * "Memory and latency").  Semantics per tensor are exactly hqmq_decode's.
+ *   enc, outlier_capacity, sec_dev, out_dev   HOST arrays of n_tensors entries; sec_dev[i] and
+ *            out_dev[i] are DEVICE pointers, enc[i] a struct of DEVICE pointers.
+ * Errors: as hqmq_decode; INVALID_ARG also for n_tensors <= 0 or a null array. */
+int32_t hqmq_decode_batch(const hqmq_params *params, int32_t n_tensors, const hqmq_encoded *enc,
+                          const uint64_t *outlier_capacity, const float *const *sec_dev,
+                          void *const *out_dev, void *stream);
+
 /* hipError_t value of the last failed HIP call made by this library on the calling thread
  * (0 if none). */
 int32_t hqmq_last_hip_error(void);

@@ -7,6 +7,7 @@ library's names and only marshal arguments.  PyTorch provides device memory and 
 from .binding import (  # noqa: F401
     HQMQ_FLAG_NO_OUTLIERS,
     HQMQ_STATUS_OUTLIER_OVERFLOW,
+    DecodeBatch,
     EncodedBuffers,
     HqmqError,
     HqmqParams,
@@ -15,6 +16,7 @@ from .binding import (  # noqa: F401
     alloc_workspace,
     hqmq_build_codebooks,
     hqmq_decode,
+    hqmq_decode_batch,
     hqmq_encode,
     hqmq_encode_timed,
     hqmq_last_hip_error,

@@ -72,6 +72,10 @@ def _load():
         lib.hqmq_decode.restype = C.c_int32
         lib.hqmq_decode.argtypes = [C.POINTER(HqmqParams), C.POINTER(_Encoded), C.c_uint64, C.c_void_p,
                                     C.c_void_p, C.c_void_p]
+        lib.hqmq_decode_batch.restype = C.c_int32
+        lib.hqmq_decode_batch.argtypes = [C.POINTER(HqmqParams), C.c_int32, C.POINTER(_Encoded),
+                                          C.POINTER(C.c_uint64), C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
+                                          C.c_void_p]
         lib.hqmq_last_hip_error.restype = C.c_int32
         lib.hqmq_last_hip_error.argtypes = []
         _lib = lib
@@ -197,3 +201,34 @@ def hqmq_decode(params: HqmqParams, enc: EncodedBuffers, sec: torch.Tensor, out:
     rc = _load().hqmq_decode(C.byref(params), C.byref(enc.as_struct()), enc.outlier_capacity,
                              sec.data_ptr(), out.data_ptr(), _stream_ptr(stream))
     _check(rc, "hqmq_decode")
+
+
+class DecodeBatch:
+    """Marshalled argument arrays of hqmq_decode_batch, built once and reusable across calls
+    (the tensors' buffers must stay alive and in place)."""
+
+    def __init__(self, params: HqmqParams, encs, secs, outs):
+        n = len(encs)
+        if not (n == len(secs) == len(outs)) or n == 0:
+            raise ValueError("encs, secs and outs must be non-empty lists of equal length")
+        for sec, out in zip(secs, outs):
+            if out.dtype != torch.float16 or not out.is_cuda or not sec.is_cuda or sec.dtype != torch.float32:
+                raise ValueError("outs must be device fp16 tensors and secs device fp32 tensors")
+            if not sec.is_contiguous() or tuple(sec.shape) != (params.H, params.S, 4):
+                raise ValueError("every sec must be contiguous [H, S, 4]")
+            if (out.stride(0), out.stride(1), out.stride(2)) != (params.stride_b, params.stride_h, params.stride_t):
+                raise ValueError("every out must have the strides params holds")
+        self.params = params
+        self.n = n
+        self.keep = (list(encs), list(secs), list(outs))
+        self.enc = (_Encoded * n)(*[e.as_struct() for e in encs])
+        self.cap = (C.c_uint64 * n)(*[e.outlier_capacity for e in encs])
+        self.sec = (C.c_void_p * n)(*[t.data_ptr() for t in secs])
+        self.out = (C.c_void_p * n)(*[t.data_ptr() for t in outs])
+
+
+def hqmq_decode_batch(batch: DecodeBatch, stream=None) -> None:
+    """Enqueue the decode of every tensor of the batch (one shape) on `stream`."""
+    rc = _load().hqmq_decode_batch(C.byref(batch.params), batch.n, batch.enc, batch.cap, batch.sec, batch.out,
+                                   _stream_ptr(stream))
+    _check(rc, "hqmq_decode_batch")

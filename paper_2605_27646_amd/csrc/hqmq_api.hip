@@ -250,24 +250,56 @@ extern "C" int32_t hqmq_encode_timed(const hqmq_params *params, const void *x_de
                        stream, phase_events);
 }
 
-extern "C" int32_t hqmq_decode(const hqmq_params *params, const hqmq_encoded *enc,
-                               uint64_t outlier_capacity, const float *sec_dev, void *out_dev,
-                               void *stream)
+static int32_t decode_impl(const hqmq_params *params, int32_t n_tensors, const hqmq_encoded *enc,
+                           const uint64_t *outlier_capacity, const float *const *sec_dev,
+                           void *const *out_dev, void *stream)
 {
     int32_t rc = check_params(params);
     if (rc != HQMQ_OK)
         return rc;
-    if (!sec_dev || !out_dev)
+    if (n_tensors <= 0 || !enc || !outlier_capacity || !sec_dev || !out_dev)
         return HQMQ_ERR_INVALID_ARG;
-    if (misaligned(out_dev, 16) || misaligned(sec_dev, 16))
-        return HQMQ_ERR_INVALID_ARG;
-    rc = check_encoded(enc, false, outlier_capacity);
-    if (rc != HQMQ_OK)
-        return rc;
+    for (int32_t i = 0; i < n_tensors; ++i) {
+        if (!sec_dev[i] || !out_dev[i] || misaligned(out_dev[i], 16) || misaligned(sec_dev[i], 16))
+            return HQMQ_ERR_INVALID_ARG;
+        rc = check_encoded(&enc[i], false, outlier_capacity[i]);
+        if (rc != HQMQ_OK)
+            return rc;
+    }
     const Geometry g = make_geometry(params);
-    hipError_t err = launch_decode(g, to_ptrs(enc), outlier_capacity, sec_dev,
-                                   static_cast<_Float16 *>(out_dev), static_cast<hipStream_t>(stream));
-    if (err != hipSuccess)
-        return hip_failed(err);
+    for (int32_t first = 0; first < n_tensors; first += kMaxDecodeBatch) {
+        const int n = (n_tensors - first < kMaxDecodeBatch) ? n_tensors - first : kMaxDecodeBatch;
+        DecodeBatch batch;
+        std::memset(&batch, 0, sizeof(batch));
+        for (int i = 0; i < n; ++i) {
+            const hqmq_encoded &e = enc[first + i];
+            DecodeTensor &t = batch.t[i];
+            t.codes = e.codes;
+            t.sigma = e.sigma;
+            t.flags = e.flags;
+            t.row_off = e.row_off;
+            t.outliers = e.outliers;
+            t.sec = sec_dev[first + i];
+            t.out = static_cast<_Float16 *>(out_dev[first + i]);
+            t.outlier_capacity = outlier_capacity[first + i];
+        }
+        hipError_t err = launch_decode(g, batch, n, static_cast<hipStream_t>(stream));
+        if (err != hipSuccess)
+            return hip_failed(err);
+    }
     return HQMQ_OK;
+}
+
+extern "C" int32_t hqmq_decode(const hqmq_params *params, const hqmq_encoded *enc,
+                               uint64_t outlier_capacity, const float *sec_dev, void *out_dev,
+                               void *stream)
+{
+    return decode_impl(params, 1, enc, &outlier_capacity, &sec_dev, &out_dev, stream);
+}
+
+extern "C" int32_t hqmq_decode_batch(const hqmq_params *params, int32_t n_tensors,
+                                     const hqmq_encoded *enc, const uint64_t *outlier_capacity,
+                                     const float *const *sec_dev, void *const *out_dev, void *stream)
+{
+    return decode_impl(params, n_tensors, enc, outlier_capacity, sec_dev, out_dev, stream);
 }

@@ -35,18 +35,29 @@ constexpr int kLoadsPerLane = (kStageRows * kMaxW + 63) / 64;  // 6 code words p
 
 }  // namespace
 
-// grid = (ceil(T / 64), B*H), block = 256.
-// dynamic LDS: secl [S][4] f32 | prim [48][4] f32 | staging [4 waves][kStagePerWave] u32
+// grid = (ceil(T / 64), B*H, tensors), block = 256.
+// dynamic LDS: prim [48][4] f32 | staging [4 waves][kStagePerWave] u32 | secl [S][4] f32
+// (the tables with compile-time sizes first, so that their LDS addresses are immediates)
+// blockIdx.z selects the tensor of a batch (all of one shape); the descriptors travel as kernel
+// arguments, so a batch needs no device-side table.
 template <bool kPow2>
-__global__ __launch_bounds__(kDecThreads) void k_decode(Geometry g, EncodedPtrs enc,
-                                                        uint64_t outlier_capacity,
-                                                        const float *__restrict__ sec,
-                                                        _Float16 *__restrict__ out)
+__global__ __launch_bounds__(kDecThreads) void k_decode(Geometry g, DecodeBatch batch)
 {
+    const DecodeTensor &dt = batch.t[blockIdx.z];
+    EncodedPtrs enc;
+    enc.codes = dt.codes;
+    enc.sigma = dt.sigma;
+    enc.flags = dt.flags;
+    enc.row_off = dt.row_off;
+    enc.outliers = dt.outliers;
+    const uint64_t outlier_capacity = dt.outlier_capacity;
+    const float *__restrict__ sec = dt.sec;
+    _Float16 *__restrict__ out = dt.out;
+
     extern __shared__ float lds[];
-    float *secl = lds;
-    float *prim = lds + (size_t)g.S * 4;
+    float *prim = lds;
     uint32_t *stage_all = reinterpret_cast<uint32_t *>(prim + 48 * 4);
+    float *secl = reinterpret_cast<float *>(stage_all + kDecWaves * kStagePerWave);
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int seg = blockIdx.y, b = seg / g.H, h = seg % g.H;
@@ -122,6 +133,8 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(Geometry g, EncodedPtrs 
     const uint2 *pay_src = has_pay ? reinterpret_cast<const uint2 *>(enc.outliers) + pay_base
                                    : reinterpret_cast<const uint2 *>(enc.row_off);
     const uint2 pay_mine = pay_src[min((uint64_t)lane, pay_last)];
+    // wave-uniform: the whole window fits the LDS slots and the list's capacity
+    const bool window_ok = pay_n <= (uint32_t)kPaySlots && (uint64_t)pay_base + pay_n <= outlier_capacity;
 
     const uint32_t bitpos = (uint32_t)(2 * cp) * w;
     const uint32_t i0 = bitpos >> 5, sh0 = bitpos & 31;
@@ -154,18 +167,21 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(Geometry g, EncodedPtrs 
         return o;
     };
     auto decode_chunk = [&](uint32_t code, float sol) {
-        const uint32_t k = code & idx_mask, rq = code >> w_idx;
-        uint32_t p, s;
+        const uint32_t rq = code >> w_idx;
+        uint32_t p_off, s_off;  // byte offsets of P_p and q_s in their LDS tables
         if (kPow2) {
-            p = k >> g.log2_S;
-            s = k & ((uint32_t)g.S - 1u);
+            // code = r_q : p : s as bit fields; p has 5 bits (24 S <= 2^w_idx < 48 S)
+            p_off = ((code >> g.log2_S) & 31u) << 4;
+            s_off = (code << 4) & (((uint32_t)g.S - 1u) << 4);
         } else {
             // p = k / S by a biased reciprocal, exact for k < 48 S (see Geometry::inv_S)
-            p = (uint32_t)((float)k * g.inv_S);
-            s = k - __umul24(p, (uint32_t)g.S);
+            const uint32_t k = code & idx_mask;
+            const uint32_t p = (uint32_t)((float)k * g.inv_S);
+            p_off = p << 4;
+            s_off = (k - __umul24(p, (uint32_t)g.S)) << 4;
         }
-        const float4_t P = *reinterpret_cast<const float4_t *>(prim + 4 * p);
-        const float4_t q = *reinterpret_cast<const float4_t *>(secl + 4 * s);
+        const float4_t P = *reinterpret_cast<const float4_t *>(reinterpret_cast<const char *>(prim) + p_off);
+        const float4_t q = *reinterpret_cast<const float4_t *>(reinterpret_cast<const char *>(secl) + s_off);
         const float rh = (float)rq * sol;
         const float R0 = rh * P[0], R1 = rh * P[1], R2 = rh * P[2], R3 = rh * P[3];
         // Hamilton product (r_hat P) (x) q
@@ -197,9 +213,8 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(Geometry g, EncodedPtrs 
         }
         return v;
     };
-    // ---- phase 2: decode, merge, store ---------------------------------------------------------------
-    auto phase2 = [&](int sub, const Sub &in) {
-        const int r = 4 * sub + rsub;
+    // ---- phase 2: decode every chunk (all arithmetic, while the payload window is still in flight) ----
+    auto phase2 = [&](const Sub &in) {
         const float sol = in.sigma * inv_L;
         float4_t ya = decode_chunk(in.code0, sol), yb = decode_chunk(in.code1, sol);
         // A product r_hat * c_i can only leave the fp16 range when the row's scale is within a
@@ -213,43 +228,65 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(Geometry g, EncodedPtrs 
                 yb[i] = __builtin_amdgcn_fmed3f(yb[i], -lim, lim);
             }
         }
-        uint2 oa = to_half4(ya), ob = to_half4(yb);
-        if (in.fl) {
+        const uint2 oa = to_half4(ya), ob = to_half4(yb);
+        return make_uint4(oa.x, oa.y, ob.x, ob.y);
+    };
+    // ---- phase 3: flagged chunks take their payload; store ---------------------------------------------
+    auto phase3 = [&](int sub, const Sub &in, uint4 o) {
+        const int r = 4 * sub + rsub;
+        if (window_ok) {
+            // every flagged chunk of the wave has its payload in the LDS window: read and select
+            // without branching (unflagged lanes read a clamped slot and discard it)
+            const uint32_t slot_b = in.pos + (in.fl & 1u);
+            const uint2 pa = st_pay[min(in.pos, (uint32_t)kPaySlots - 1u)];
+            const uint2 pb = st_pay[min(slot_b, (uint32_t)kPaySlots - 1u)];
+            if (in.fl & 1u) {
+                o.x = pa.x;
+                o.y = pa.y;
+            }
+            if (in.fl & 2u) {
+                o.z = pb.x;
+                o.w = pb.y;
+            }
+        } else if (in.fl) {
             uint32_t slot = in.pos;
             if (in.fl & 1u) {
-                oa = fetch_payload(slot);
+                const uint2 v = fetch_payload(slot);
+                o.x = v.x;
+                o.y = v.y;
                 ++slot;
             }
-            if (in.fl & 2u)
-                ob = fetch_payload(slot);
+            if (in.fl & 2u) {
+                const uint2 v = fetch_payload(slot);
+                o.z = v.x;
+                o.w = v.y;
+            }
         }
         if (r < nrows)
-            *reinterpret_cast<uint4 *>(obase + (int64_t)r * g.st) = make_uint4(oa.x, oa.y, ob.x, ob.y);
+            *reinterpret_cast<uint4 *>(obase + (int64_t)r * g.st) = o;
     };
     static_assert(kSubs == 4, "the straight-line code below is written for 4 row groups per wave");
     const Sub s0 = phase1(0), s1 = phase1(1), s2 = phase1(2), s3 = phase1(3);
-    // the window lands in LDS only now: every lane's loads above and below are already issued
-    if (pay_n > 0) {
-        st_pay[lane] = pay_mine;
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    }
-    phase2(0, s0);
-    phase2(1, s1);
-    phase2(2, s2);
-    phase2(3, s3);
+    const uint4 o0 = phase2(s0), o1 = phase2(s1), o2 = phase2(s2), o3 = phase2(s3);
+    // the window lands in LDS only now, after all the arithmetic that does not need it
+    st_pay[lane] = pay_mine;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    phase3(0, s0, o0);
+    phase3(1, s1, o1);
+    phase3(2, s2, o2);
+    phase3(3, s3, o3);
 }
 
-hipError_t launch_decode(const Geometry &g, const EncodedPtrs &enc, uint64_t outlier_capacity,
-                         const float *sec, _Float16 *out, hipStream_t stream)
+hipError_t launch_decode(const Geometry &g, const DecodeBatch &batch, int n_tensors, hipStream_t stream)
 {
     const size_t lds = ((size_t)g.S * 4 + 48 * 4) * sizeof(float) + (size_t)kDecWaves * kStagePerWave * 4;
-    dim3 grid((unsigned)((g.T + kDecRows - 1) / kDecRows), (unsigned)(g.B * g.H));
+    dim3 grid((unsigned)((g.T + kDecRows - 1) / kDecRows), (unsigned)(g.B * g.H), (unsigned)n_tensors);
     if ((g.S & (g.S - 1)) == 0)
-        hipLaunchKernelGGL(k_decode<true>, grid, dim3(kDecThreads), lds, stream, g, enc, outlier_capacity, sec, out);
+        hipLaunchKernelGGL(k_decode<true>, grid, dim3(kDecThreads), lds, stream, g, batch);
     else
-        hipLaunchKernelGGL(k_decode<false>, grid, dim3(kDecThreads), lds, stream, g, enc, outlier_capacity, sec, out);
+        hipLaunchKernelGGL(k_decode<false>, grid, dim3(kDecThreads), lds, stream, g, batch);
     return hipGetLastError();
 }
 

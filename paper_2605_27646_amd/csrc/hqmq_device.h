@@ -63,6 +63,22 @@ struct EncodedPtrs {
     uint32_t *status;
 };
 
+// One tensor of a decode batch and the batch itself (passed by value as kernel arguments).
+struct DecodeTensor {
+    uint32_t *codes;
+    uint16_t *sigma;
+    uint32_t *flags;
+    uint32_t *row_off;
+    uint16_t *outliers;
+    const float *sec;
+    _Float16 *out;
+    uint64_t outlier_capacity;
+};
+constexpr int kMaxDecodeBatch = 32;  // 32 * 64 B of descriptors stay well inside the 4 KiB of kernel arguments
+struct DecodeBatch {
+    DecodeTensor t[kMaxDecodeBatch];
+};
+
 // ---- device helpers --------------------------------------------------------------------
 
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
@@ -95,7 +111,6 @@ hipError_t launch_search(const _Float16 *x, const float *sec, const Geometry &g,
                          const EncodedPtrs &enc, hipStream_t stream);
 hipError_t launch_outlier_list(const _Float16 *x, const Geometry &g, const Workspace &ws,
                                const EncodedPtrs &enc, uint64_t outlier_capacity, hipStream_t stream);
-hipError_t launch_decode(const Geometry &g, const EncodedPtrs &enc, uint64_t outlier_capacity,
-                         const float *sec, _Float16 *out, hipStream_t stream);
+hipError_t launch_decode(const Geometry &g, const DecodeBatch &batch, int n_tensors, hipStream_t stream);
 
 }  // namespace hqmq

@@ -27,7 +27,7 @@ def lib():
 def test_library_exports_every_declared_symbol(lib):
     header = open(os.path.join(ROOT, "include", "hqmq.h")).read()
     declared = set(re.findall(r"^(?:int32_t|void|uint64_t)\s+(hqmq_\w+)\s*\(", header, re.M))
-    assert declared == {"hqmq_build_codebooks", "hqmq_sizes", "hqmq_encode", "hqmq_encode_timed", "hqmq_decode", "hqmq_last_hip_error"}
+    assert declared == {"hqmq_build_codebooks", "hqmq_sizes", "hqmq_encode", "hqmq_encode_timed", "hqmq_decode", "hqmq_decode_batch", "hqmq_last_hip_error"}
     for name in declared:
         assert hasattr(lib, name), name
 
@@ -100,6 +100,16 @@ def test_encode_decode_reject_bad_arguments_without_touching_the_gpu(lib):
     assert dec(C.byref(p), C.byref(good), 0, 0x1000, 0x1008, None) == -1
     assert dec(C.byref(p), None, 0, 0x1000, 0x1000, None) == -1
     assert dec(C.byref(_params(S=600)), C.byref(good), 0, 0x1000, 0x1000, None) == -2
+    db = lib.hqmq_decode_batch
+    encs = (binding._Encoded * 2)(good, good)
+    caps = (C.c_uint64 * 2)(0, 0)
+    ptrs = (C.c_void_p * 2)(0x1000, 0x1000)
+    bad_ptrs = (C.c_void_p * 2)(0x1000, 0x1008)
+    assert db(C.byref(p), 0, encs, caps, ptrs, ptrs, None) == -1                              # empty batch
+    assert db(C.byref(p), 2, None, caps, ptrs, ptrs, None) == -1
+    assert db(C.byref(p), 2, encs, None, ptrs, ptrs, None) == -1
+    assert db(C.byref(p), 2, encs, caps, ptrs, bad_ptrs, None) == -1                          # second out misaligned
+    assert db(C.byref(_params(b_r=0)), 2, encs, caps, ptrs, ptrs, None) == -2
     assert lib.hqmq_last_hip_error() == 0
 
 

@@ -228,6 +228,29 @@ def test_strided_input_and_output():
     compare_decode(out.contiguous().cpu().numpy().view(np.uint16), want, r_hat, e.flag)
 
 
+def test_decode_batch_equals_single_decodes():
+    """One launch for many tensors of a shape must give each tensor exactly hqmq_decode's bytes
+    (40 tensors: more than one launch's worth of descriptors)."""
+    B, H, T, S = 1, 2, 70, 16
+    n = 40
+    cb = hq.hqmq_build_codebooks(3, n, H, S)
+    xs, encs, secs, singles = [], [], [], []
+    for i in range(n):
+        x = _lognormal_tensor(B, H, T, seed=200 + i, sigma_g=1.0).to(DEV)
+        sec = cb[i, i % 2].contiguous().to(DEV)
+        g = gpu_encode(x, sec)
+        xs.append(x)
+        encs.append(g.bufs)
+        secs.append(sec)
+        singles.append(gpu_decode(g.params, g.bufs, sec, x))
+    params = hq.params_for(xs[0], S)
+    outs = [torch.full_like(x, float("nan")) for x in xs]
+    hq.hqmq_decode_batch(hq.DecodeBatch(params, encs, secs, outs))
+    torch.cuda.synchronize()
+    for i in range(n):
+        assert np.array_equal(outs[i].cpu().numpy().view(np.uint16), singles[i]), i
+
+
 def test_deterministic_bytes():
     x = _lognormal_tensor(1, 4, 300, seed=15).to(DEV)
     sec_t, _ = _sec(0, 4, 64)
