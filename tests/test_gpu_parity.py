@@ -120,6 +120,30 @@ def test_llama3_8b_32k_layer_sampled():
     assert stats["near_ties"] < 1e-3 * stats["chunks"]
 
 
+@pytest.mark.parametrize("name,layer,role", [
+    ("mistral7b_outlier", 5, 0),     # [4, 8, 8192, 128], S = 64: batch > 1, hot channels (about 10 % outliers)
+    ("qwen25_7b_heavy", 2, 0),       # [1, 4, 32768, 128], S = 256: hot channels + heavy-tailed spikes
+    ("llama3_70b_128k", 7, 1),       # [1, 8, 131072, 128], S = 256: 256 MiB per tensor, four times the rows
+])
+def test_other_workloads_full_size_sampled(name, layer, role):
+    """One full-size tensor of each remaining workload, as the library is launched on it: the O(n)
+    results on every row, the search on a sample of token rows of every (batch, head)."""
+    wl = workloads.WORKLOADS[name]
+    x = workloads.make_tensor(wl, layer, role, "cpu")
+    rows = workloads.sample_rows(wl, 16, 16, 64, seed=2).numpy()
+    print(f"{name} layer {layer} role {role}: searching {int(rows.sum())} of {rows.size} rows on the CPU", flush=True)
+    stats, e, g = _roundtrip(x, wl.S, wl.b_r, rows=rows, check_decode=(name != "llama3_70b_128k"))
+    assert stats["near_ties"] < 1e-3 * stats["chunks"]
+    if name == "llama3_70b_128k":
+        # decode parity on the sampled rows only (the full 33.5 M-chunk comparison is done for the
+        # smaller shapes): both decoders on the GPU-encoded bytes
+        want, r_hat = oracle.decode(g.codes, g.sigma, g.flags, g.row_off, g.outliers, _sec(0, wl.H, wl.S)[1],
+                                    wl.B, wl.H, wl.T, wl.b_r, True)
+        got = gpu_decode(g.params, g.bufs, _sec(0, wl.H, wl.S)[0].to(DEV), x.to(DEV))
+        sel = np.flatnonzero(rows)
+        compare_decode(got.reshape(-1, 128)[sel], want.reshape(-1, 128)[sel], r_hat[sel], e.flag[sel])
+
+
 # ---------------------------------------------------------------------------------------
 # degenerate inputs and the boundary's data-dependent behaviour
 # ---------------------------------------------------------------------------------------
