@@ -97,6 +97,12 @@ def _declare(L):
     L.hqo_unpack_row.argtypes = [_u32p, C.c_int, _u32p]
     L.hqo_pack_rows.restype = None
     L.hqo_pack_rows.argtypes = [_i32p, _i32p, _u8p, C.c_int64, C.c_int, C.c_int, _u32p]
+    L.hqo_decode64.restype = None
+    L.hqo_decode64.argtypes = [_u32p, _u16p, _u32p, _u32p, _u16p, _f32p, C.c_int, C.c_int,
+                               C.c_int, C.c_int, C.c_int, _u16p, C.c_void_p, _f64p]
+    L.hqo_attend.restype = None
+    L.hqo_attend.argtypes = [_u16p, _f64p, _f64p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                             C.c_double, _u16p, _f64p]
     L.hqo_decode.restype = None
     L.hqo_decode.argtypes = [_u32p, _u16p, _u32p, _u32p, _u16p, _f32p, C.c_int, C.c_int,
                              C.c_int, C.c_int, C.c_int, _u16p, C.c_void_p]
@@ -340,6 +346,39 @@ def decode(codes, sigma, flags, row_off, outliers, sec, B, H, T, b_r, want_r_hat
     if want_r_hat:
         return out, r_hat.reshape(n_rows, NC)
     return out
+
+
+def decode64(codes, sigma, flags, row_off, outliers, sec, B, H, T, b_r) -> np.ndarray:
+    """Reconstruction before the final fp16 rounding, fp64 [B, H, T, 128] (outliers widened)."""
+    sec = np.ascontiguousarray(sec, np.float32)
+    S = sec.shape[1]
+    n_rows = B * H * T
+    out16 = np.zeros(n_rows * NC * 4, np.uint16)
+    out64 = np.zeros(n_rows * NC * 4)
+    outliers = np.ascontiguousarray(outliers, np.uint16).reshape(-1)
+    if outliers.size == 0:
+        outliers = np.zeros(4, np.uint16)
+    lib().hqo_decode64(np.ascontiguousarray(codes, np.uint32).reshape(-1),
+                       np.ascontiguousarray(sigma, np.uint16), np.ascontiguousarray(flags, np.uint32),
+                       np.ascontiguousarray(row_off, np.uint32), outliers, sec.reshape(-1),
+                       B, H, T, S, b_r, out16, None, out64)
+    return out64.reshape(B, H, T, NC * 4)
+
+
+def attend(q_bits: np.ndarray, K64: np.ndarray, V64: np.ndarray, scale: float):
+    """Single-query attention (one token per sequence) over a reconstructed cache.
+    q_bits: fp16 bit patterns [B, Hq, D]; K64, V64: fp64 [B, H, T, D]; returns (fp16 bits, fp64)."""
+    q_bits = np.ascontiguousarray(q_bits, np.uint16)
+    K64 = np.ascontiguousarray(K64, np.float64)
+    V64 = np.ascontiguousarray(V64, np.float64)
+    B, Hq, D = q_bits.shape
+    _, H, T, _ = K64.shape
+    assert Hq % H == 0 and K64.shape == V64.shape and K64.shape[0] == B and K64.shape[3] == D
+    out16 = np.zeros((B, Hq, D), np.uint16)
+    out64 = np.zeros((B, Hq, D))
+    lib().hqo_attend(q_bits.reshape(-1), K64.reshape(-1), V64.reshape(-1), B, Hq, H, T, D, float(scale),
+                     out16.reshape(-1), out64.reshape(-1))
+    return out16, out64
 
 
 # --------------------------------------------------------------------------------------

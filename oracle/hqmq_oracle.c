@@ -17,6 +17,8 @@
  *                                              extraction", Alg. 1, App. D "Outlier extraction"
  *   - decode ................................. Alg. 1 (decode), App. D "Decode"
  *   - secondary codebook initialisation ...... App. D "Secondary codebook initialization"
+ *   - single-query attention over the
+ *     reconstructed K and V .................. App. F (fused attention: softmax(Q K^T scale) V)
  *
  * Where the paper leaves a choice open (median of an even count, tie-break, rounding,
  * bit layout, ...) the reading taken is stated at the function that needs it.
@@ -480,11 +482,25 @@ void hqo_pack_rows(const int32_t *k, const int32_t *rq, const uint8_t *flag, int
  * Decode:  x_hat = r_hat * (P[p] (x) sec[s]),  r_hat = r_q * sigma / L,  rounded to fp16
  * (ties to even, saturating); flagged chunks take their stored fp16 payload verbatim, the
  * j-th flagged chunk of a row sitting at payload[row_off[row] + j].
- * Also returns r_hat per chunk (fp64, 0 for flagged chunks) for tolerance checks.
+ * Also returns r_hat per chunk (fp64, 0 for flagged chunks) for tolerance checks, and, when
+ * out64 is given, the reconstruction before the final fp16 rounding (flagged chunks: their
+ * fp16 payload widened).
  * ---------------------------------------------------------------------------------- */
+void hqo_decode64(const uint32_t *codes, const uint16_t *sigma16, const uint32_t *flag_words,
+                  const uint32_t *row_off, const uint16_t *payload, const float *sec_all, int B,
+                  int H, int T, int S, int b_r, uint16_t *out, double *r_hat, double *out64);
+
 void hqo_decode(const uint32_t *codes, const uint16_t *sigma16, const uint32_t *flag_words,
                 const uint32_t *row_off, const uint16_t *payload, const float *sec_all, int B,
                 int H, int T, int S, int b_r, uint16_t *out /* [rows][128] */, double *r_hat)
+{
+    hqo_decode64(codes, sigma16, flag_words, row_off, payload, sec_all, B, H, T, S, b_r, out, r_hat, 0);
+}
+
+void hqo_decode64(const uint32_t *codes, const uint16_t *sigma16, const uint32_t *flag_words,
+                const uint32_t *row_off, const uint16_t *payload, const float *sec_all, int B,
+                  int H, int T, int S, int b_r, uint16_t *out /* [rows][128] */, double *r_hat,
+                  double *out64 /* [rows][128] or NULL */)
 {
     int w_idx = hqo_index_bits(S), w = w_idx + b_r;
     double L = (double)((1 << b_r) - 1);
@@ -500,6 +516,9 @@ void hqo_decode(const uint32_t *codes, const uint16_t *sigma16, const uint32_t *
             int64_t chunk = row * HQO_NC + c;
             if ((flag_words[row] >> c) & 1u) {
                 memcpy(out + 4 * chunk, payload + 4 * next, 4 * sizeof(uint16_t));
+                if (out64)
+                    for (int i = 0; i < 4; ++i)
+                        out64[4 * chunk + i] = hqo_half_to_double(payload[4 * next + i]);
                 ++next;
                 if (r_hat)
                     r_hat[chunk] = 0.0;
@@ -510,10 +529,60 @@ void hqo_decode(const uint32_t *codes, const uint16_t *sigma16, const uint32_t *
             double rh = ((double)q * sigma) / L;
             double cw[4];
             hqo_codeword(sec, S, kk, cw);
-            for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < 4; ++i) {
                 out[4 * chunk + i] = hqo_double_to_half(rh * cw[i]);
+                if (out64)
+                    out64[4 * chunk + i] = rh * cw[i];
+            }
             if (r_hat)
                 r_hat[chunk] = rh;
         }
     }
+}
+
+/* ------------------------------------------------------------------------------------
+ * Single-query attention over a reconstructed cache (the paper's fused HQMQ-attention kernel,
+ * App. F: S = Q K^T scale, O = softmax(S) V with K and V decoded inside the loop; here for one
+ * query token per sequence, the decode step of generation).  q: fp16 [B][Hq][D]; K, V: fp64
+ * [B][H][T][D] as returned by hqo_decode64 (reconstruction before fp16 rounding, outliers as
+ * stored); query head hq reads kv head hq / (Hq / H) (grouped-query attention).  Plain softmax
+ * with the row maximum subtracted, everything in fp64; out16 = result rounded to fp16.
+ * ---------------------------------------------------------------------------------- */
+void hqo_attend(const uint16_t *q, const double *K, const double *V, int B, int Hq, int H, int T,
+                int D, double scale, uint16_t *out16, double *out64)
+{
+    int G = Hq / H;
+    double *p = (double *)malloc((size_t)T * sizeof(double));
+    for (int b = 0; b < B; ++b)
+        for (int hq = 0; hq < Hq; ++hq) {
+            int h = hq / G;
+            const double *Kh = K + ((int64_t)b * H + h) * T * D;
+            const double *Vh = V + ((int64_t)b * H + h) * T * D;
+            const uint16_t *qv = q + ((int64_t)b * Hq + hq) * D;
+            double m = -INFINITY;
+            for (int t = 0; t < T; ++t) {
+                double s = 0.0;
+                for (int d = 0; d < D; ++d)
+                    s += hqo_half_to_double(qv[d]) * Kh[(int64_t)t * D + d];
+                p[t] = scale * s;
+                if (p[t] > m)
+                    m = p[t];
+            }
+            double l = 0.0;
+            for (int t = 0; t < T; ++t) {
+                p[t] = exp(p[t] - m);
+                l += p[t];
+            }
+            for (int d = 0; d < D; ++d) {
+                double o = 0.0;
+                for (int t = 0; t < T; ++t)
+                    o += p[t] * Vh[(int64_t)t * D + d];
+                o /= l;
+                int64_t at = ((int64_t)b * Hq + hq) * D + d;
+                if (out64)
+                    out64[at] = o;
+                out16[at] = hqo_double_to_half(o);
+            }
+        }
+    free(p);
 }

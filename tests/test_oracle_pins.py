@@ -547,6 +547,58 @@ def test_reconstruction_error_matches_angular_error():
 
 
 # ---------------------------------------------------------------------------------------
+# single-query attention over the reconstructed cache
+# ---------------------------------------------------------------------------------------
+
+def test_attend_matches_numpy_softmax_einsum_with_gqa():
+    from scipy.special import softmax
+    rng = np.random.default_rng(50)
+    B, Hq, H, T, D = 2, 6, 2, 37, 128
+    q = rng.standard_normal((B, Hq, D)).astype(np.float16)
+    K = rng.standard_normal((B, H, T, D))
+    V = rng.standard_normal((B, H, T, D))
+    scale = 1 / math.sqrt(D)
+    o16, o64 = oracle.attend(q.view(np.uint16), K, V, scale)
+    kv = np.repeat(np.arange(H), Hq // H)                       # query head -> kv head (grouped)
+    s = np.einsum("bqd,bqtd->bqt", q.astype(np.float64), K[:, kv]) * scale
+    want = np.einsum("bqt,bqtd->bqd", softmax(s, axis=-1), V[:, kv])
+    assert np.allclose(o64, want, rtol=0, atol=1e-13)
+    assert np.array_equal(o16, o64.astype(np.float16).view(np.uint16))      # numpy's RNE cast
+
+
+def test_attend_invariants():
+    rng = np.random.default_rng(51)
+    B, Hq, H, T, D = 1, 4, 1, 50, 128
+    q = rng.standard_normal((B, Hq, D)).astype(np.float16).view(np.uint16)
+    K = rng.standard_normal((B, H, T, D))
+    V = rng.standard_normal((B, H, T, D))
+    _, o = oracle.attend(q, K, V, 0.1)
+    # a convex combination of the value rows
+    assert (o <= V.max(2) + 1e-12).all() and (o >= V.min(2) - 1e-12).all()
+    # permuting the tokens changes nothing; zero scale gives the plain mean
+    perm = rng.permutation(T)
+    _, o2 = oracle.attend(q, K[:, :, perm], V[:, :, perm], 0.1)
+    assert np.allclose(o, o2, atol=1e-13)
+    _, o3 = oracle.attend(q, K, V, 0.0)
+    assert np.allclose(o3, np.broadcast_to(V.mean(2), o3.shape), atol=1e-13)
+    # a key aligned with the query and a huge scale picks that token's value
+    K2 = K.copy()
+    K2[0, 0, 7] = 50 * q.view(np.float16).astype(np.float64)[0, 2]
+    _, o4 = oracle.attend(q, K2, V, 5.0)
+    assert np.allclose(o4[0, 2], V[0, 0, 7], atol=1e-9)
+
+
+def test_decode64_rounds_to_decode():
+    rng = np.random.default_rng(52)
+    x = f16(rng.standard_normal((1, 2, 16, 128)) * np.exp(rng.normal(0, 1.2, (1, 2, 16, 128))))
+    e, sec = _encode_small(x, S=16)
+    d16 = oracle.decode(e.codes, e.sigma, e.flags, e.row_off, e.outliers, sec, 1, 2, 16, 6)
+    d64 = oracle.decode64(e.codes, e.sigma, e.flags, e.row_off, e.outliers, sec, 1, 2, 16, 6)
+    assert e.n_out[-1] > 0
+    assert np.array_equal(d64.astype(np.float16).view(np.uint16), d16)      # numpy's RNE cast
+
+
+# ---------------------------------------------------------------------------------------
 # numbers the paper prints
 # ---------------------------------------------------------------------------------------
 
