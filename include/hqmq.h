@@ -169,6 +169,33 @@ int32_t hqmq_decode_batch(const hqmq_params *params, int32_t n_tensors, const hq
                           const uint64_t *outlier_capacity, const float *const *sec_dev,
                           void *const *out_dev, void *stream);
 
+/* Single-query attention read straight from a packed K cache and a packed V cache (the paper's
+ * fused attention kernel, App. F: O = softmax(Q K^T * scale) V with K and V reconstructed inside
+ * the attention loop and never materialised), for ONE query token per sequence (the generation
+ * step).  Query head hq attends to kv head hq / (n_q_heads / H) (grouped-query attention); all T
+ * cached tokens are visible.  K_hat and V_hat are the reconstructions r_hat * (P_p (x) q_s) before
+ * any fp16 rounding, flagged chunks as stored; products and sums are fp32, the softmax subtracts
+ * the running maximum (online form), the result is rounded once to fp16.
+ *   params     HOST; B, H, T, D, S, b_r describe BOTH caches (strides are ignored).
+ *   n_q_heads  a multiple of H, at most 8 * H.
+ *   q_dev      DEVICE, fp16 [B][n_q_heads][128] contiguous, 16-byte aligned.
+ *   scale      softmax scale (usually 1/sqrt(128)); finite.
+ *   enc_k, enc_v, cap_k, cap_v, sec_k_dev, sec_v_dev   as enc / outlier_capacity / sec_dev of
+ *              hqmq_decode, for the key and the value cache.
+ *   out_dev    DEVICE, out, fp16 [B][n_q_heads][128] contiguous, 16-byte aligned.
+ *   workspace_dev  DEVICE scratch, 256-byte aligned, hqmq_attend_workspace_bytes() bytes; owned
+ *              by the caller, contents undefined afterwards; concurrent calls need their own.
+ *   stream     hipStream_t; two kernels are enqueued, nothing is synchronised or allocated.
+ * Errors: INVALID_ARG (null / misaligned pointer, bad n_q_heads, non-finite scale), UNSUPPORTED
+ * (params the decode rejects, more than 8 query heads per kv head), BUFFER_TOO_SMALL, HIP. */
+int32_t hqmq_attend(const hqmq_params *params, int32_t n_q_heads, const void *q_dev, float scale,
+                    const hqmq_encoded *enc_k, uint64_t cap_k, const float *sec_k_dev,
+                    const hqmq_encoded *enc_v, uint64_t cap_v, const float *sec_v_dev, void *out_dev,
+                    void *workspace_dev, uint64_t workspace_bytes, void *stream);
+
+/* Workspace hqmq_attend needs for these params and n_q_heads, in bytes (0 if they are invalid). */
+uint64_t hqmq_attend_workspace_bytes(const hqmq_params *params, int32_t n_q_heads);
+
 /* hipError_t value of the last failed HIP call made by this library on the calling thread
  * (0 if none). */
 int32_t hqmq_last_hip_error(void);

@@ -14,6 +14,8 @@ from .binding import (  # noqa: F401
     HqmqSizeInfo,
     alloc_encoded,
     alloc_workspace,
+    hqmq_attend,
+    hqmq_attend_workspace_bytes,
     hqmq_build_codebooks,
     hqmq_decode,
     hqmq_decode_batch,

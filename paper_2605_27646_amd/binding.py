@@ -76,6 +76,13 @@ def _load():
         lib.hqmq_decode_batch.argtypes = [C.POINTER(HqmqParams), C.c_int32, C.POINTER(_Encoded),
                                           C.POINTER(C.c_uint64), C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
                                           C.c_void_p]
+        lib.hqmq_attend.restype = C.c_int32
+        lib.hqmq_attend.argtypes = [C.POINTER(HqmqParams), C.c_int32, C.c_void_p, C.c_float,
+                                    C.POINTER(_Encoded), C.c_uint64, C.c_void_p,
+                                    C.POINTER(_Encoded), C.c_uint64, C.c_void_p,
+                                    C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]
+        lib.hqmq_attend_workspace_bytes.restype = C.c_uint64
+        lib.hqmq_attend_workspace_bytes.argtypes = [C.POINTER(HqmqParams), C.c_int32]
         lib.hqmq_last_hip_error.restype = C.c_int32
         lib.hqmq_last_hip_error.argtypes = []
         _lib = lib
@@ -232,3 +239,31 @@ def hqmq_decode_batch(batch: DecodeBatch, stream=None) -> None:
     rc = _load().hqmq_decode_batch(C.byref(batch.params), batch.n, batch.enc, batch.cap, batch.sec, batch.out,
                                    _stream_ptr(stream))
     _check(rc, "hqmq_decode_batch")
+
+
+def hqmq_attend_workspace_bytes(params: HqmqParams, n_q_heads: int) -> int:
+    return int(_load().hqmq_attend_workspace_bytes(C.byref(params), int(n_q_heads)))
+
+
+def hqmq_attend(params: HqmqParams, q: torch.Tensor, scale: float, enc_k: EncodedBuffers,
+                sec_k: torch.Tensor, enc_v: EncodedBuffers, sec_v: torch.Tensor, out: torch.Tensor,
+                workspace: torch.Tensor, stream=None) -> None:
+    """Enqueue single-query attention over the packed K and V caches: q and out are contiguous
+    device fp16 [B, n_q_heads, 128]."""
+    for t in (q, out):
+        if t.dtype != torch.float16 or not t.is_cuda or not t.is_contiguous() or t.dim() != 3:
+            raise ValueError("q and out must be contiguous device fp16 [B, n_q_heads, 128]")
+    if q.shape != out.shape or q.shape[0] != params.B or q.shape[2] != params.D:
+        raise ValueError("q / out shape does not match params")
+    for sec in (sec_k, sec_v):
+        if not sec.is_cuda or sec.dtype != torch.float32 or not sec.is_contiguous() or \
+                tuple(sec.shape) != (params.H, params.S, 4):
+            raise ValueError("sec must be contiguous device fp32 [H, S, 4]")
+    if not workspace.is_cuda or not workspace.is_contiguous():
+        raise ValueError("workspace must be a contiguous device tensor")
+    rc = _load().hqmq_attend(C.byref(params), int(q.shape[1]), q.data_ptr(), float(scale),
+                             C.byref(enc_k.as_struct()), enc_k.outlier_capacity, sec_k.data_ptr(),
+                             C.byref(enc_v.as_struct()), enc_v.outlier_capacity, sec_v.data_ptr(),
+                             out.data_ptr(), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                             _stream_ptr(stream))
+    _check(rc, "hqmq_attend")

@@ -10,7 +10,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhqmq.so")
 
-SOURCES = ["hqmq_api.hip", "hqmq_median.hip", "hqmq_search.hip", "hqmq_decode.hip", "hqmq_codebook.cpp"]
+SOURCES = ["hqmq_api.hip", "hqmq_median.hip", "hqmq_search.hip", "hqmq_decode.hip", "hqmq_attend.hip",
+           "hqmq_codebook.cpp"]
 
 FLAGS = [
     "--offload-arch=gfx950",

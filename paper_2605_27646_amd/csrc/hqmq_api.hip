@@ -303,3 +303,75 @@ extern "C" int32_t hqmq_decode_batch(const hqmq_params *params, int32_t n_tensor
 {
     return decode_impl(params, n_tensors, enc, outlier_capacity, sec_dev, out_dev, stream);
 }
+
+static int32_t check_attend(const hqmq_params *params, int32_t n_q_heads)
+{
+    int32_t rc = check_params(params);
+    if (rc != HQMQ_OK)
+        return rc;
+    if (n_q_heads <= 0 || n_q_heads % params->H)
+        return HQMQ_ERR_INVALID_ARG;
+    if (n_q_heads / params->H > kMaxGroup)
+        return HQMQ_ERR_UNSUPPORTED;
+    return HQMQ_OK;
+}
+
+extern "C" uint64_t hqmq_attend_workspace_bytes(const hqmq_params *params, int32_t n_q_heads)
+{
+    if (check_attend(params, n_q_heads) != HQMQ_OK)
+        return 0;
+    return plan_attend(make_geometry(params), n_q_heads / params->H).total_bytes;
+}
+
+extern "C" int32_t hqmq_attend(const hqmq_params *params, int32_t n_q_heads, const void *q_dev,
+                               float scale, const hqmq_encoded *enc_k, uint64_t cap_k,
+                               const float *sec_k_dev, const hqmq_encoded *enc_v, uint64_t cap_v,
+                               const float *sec_v_dev, void *out_dev, void *workspace_dev,
+                               uint64_t workspace_bytes, void *stream)
+{
+    int32_t rc = check_attend(params, n_q_heads);
+    if (rc != HQMQ_OK)
+        return rc;
+    if (!q_dev || !out_dev || !sec_k_dev || !sec_v_dev || !workspace_dev || !std::isfinite(scale))
+        return HQMQ_ERR_INVALID_ARG;
+    if (misaligned(q_dev, 16) || misaligned(out_dev, 16) || misaligned(sec_k_dev, 16) ||
+        misaligned(sec_v_dev, 16) || misaligned(workspace_dev, 256))
+        return HQMQ_ERR_INVALID_ARG;
+    rc = check_encoded(enc_k, false, cap_k);
+    if (rc == HQMQ_OK)
+        rc = check_encoded(enc_v, false, cap_v);
+    if (rc != HQMQ_OK)
+        return rc;
+    const Geometry g = make_geometry(params);
+    const int G = n_q_heads / params->H;
+    const AttendPlan plan = plan_attend(g, G);
+    if (workspace_bytes < plan.total_bytes)
+        return HQMQ_ERR_BUFFER_TOO_SMALL;
+
+    auto side = [](const hqmq_encoded *e, const float *sec, uint64_t cap) {
+        AttendSide s;
+        s.codes = e->codes;
+        s.sigma = e->sigma;
+        s.flags = e->flags;
+        s.row_off = e->row_off;
+        s.outliers = e->outliers;
+        s.sec = sec;
+        s.outlier_capacity = cap;
+        return s;
+    };
+    AttendArgs a;
+    a.k = side(enc_k, sec_k_dev, cap_k);
+    a.v = side(enc_v, sec_v_dev, cap_v);
+    a.q = static_cast<const _Float16 *>(q_dev);
+    a.out = static_cast<_Float16 *>(out_dev);
+    a.part_ml = reinterpret_cast<float *>(workspace_dev);
+    a.part_acc = reinterpret_cast<float *>(static_cast<char *>(workspace_dev) + plan.ml_bytes);
+    a.qscale = scale * 1.44269504088896340736f;
+    a.G = G;
+    a.n_splits = plan.n_splits;
+    a.rows_per_split = plan.rows_per_split;
+    hipError_t err = launch_attend(g, a, static_cast<hipStream_t>(stream));
+    if (err != hipSuccess)
+        return hip_failed(err);
+    return HQMQ_OK;
+}

@@ -79,6 +79,36 @@ struct DecodeBatch {
     DecodeTensor t[kMaxDecodeBatch];
 };
 
+// Single-query attention over a packed K and a packed V cache (one query token per sequence).
+constexpr int kMaxGroup = 8;         // query heads sharing one kv head
+constexpr int kAttendTile = 64;      // rows per workgroup iteration (4 waves x 16 rows)
+struct AttendSide {
+    const uint32_t *codes;
+    const uint16_t *sigma;
+    const uint32_t *flags;
+    const uint32_t *row_off;
+    const uint16_t *outliers;
+    const float *sec;
+    uint64_t outlier_capacity;
+};
+struct AttendArgs {
+    AttendSide k, v;
+    const _Float16 *q;     // [B][H * G][128]
+    _Float16 *out;         // [B][H * G][128]
+    float *part_ml;        // [B * H * G][n_splits][2]: running maximum (log2 domain) and weight sum
+    float *part_acc;       // [B * H * G][n_splits][128]: weighted value sum
+    float qscale;          // softmax scale * log2(e), folded into the query
+    int32_t G;             // query heads per kv head
+    int32_t n_splits;      // workgroups along the sequence
+    int32_t rows_per_split;  // multiple of kAttendTile
+};
+// Split of the sequence over workgroups: enough of them to fill the chip, at least one tile each.
+struct AttendPlan {
+    int32_t n_splits, rows_per_split;
+    uint64_t ml_bytes, acc_bytes, total_bytes;
+};
+AttendPlan plan_attend(const Geometry &g, int G);
+
 // ---- device helpers --------------------------------------------------------------------
 
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
@@ -112,5 +142,6 @@ hipError_t launch_search(const _Float16 *x, const float *sec, const Geometry &g,
 hipError_t launch_outlier_list(const _Float16 *x, const Geometry &g, const Workspace &ws,
                                const EncodedPtrs &enc, uint64_t outlier_capacity, hipStream_t stream);
 hipError_t launch_decode(const Geometry &g, const DecodeBatch &batch, int n_tensors, hipStream_t stream);
+hipError_t launch_attend(const Geometry &g, const AttendArgs &args, hipStream_t stream);
 
 }  // namespace hqmq

@@ -27,7 +27,7 @@ def lib():
 def test_library_exports_every_declared_symbol(lib):
     header = open(os.path.join(ROOT, "include", "hqmq.h")).read()
     declared = set(re.findall(r"^(?:int32_t|void|uint64_t)\s+(hqmq_\w+)\s*\(", header, re.M))
-    assert declared == {"hqmq_build_codebooks", "hqmq_sizes", "hqmq_encode", "hqmq_encode_timed", "hqmq_decode", "hqmq_decode_batch", "hqmq_last_hip_error"}
+    assert declared == {"hqmq_build_codebooks", "hqmq_sizes", "hqmq_encode", "hqmq_encode_timed", "hqmq_decode", "hqmq_decode_batch", "hqmq_attend", "hqmq_attend_workspace_bytes", "hqmq_last_hip_error"}
     for name in declared:
         assert hasattr(lib, name), name
 
@@ -110,6 +110,23 @@ def test_encode_decode_reject_bad_arguments_without_touching_the_gpu(lib):
     assert db(C.byref(p), 2, encs, None, ptrs, ptrs, None) == -1
     assert db(C.byref(p), 2, encs, caps, ptrs, bad_ptrs, None) == -1                          # second out misaligned
     assert db(C.byref(_params(b_r=0)), 2, encs, caps, ptrs, ptrs, None) == -2
+    att = lib.hqmq_attend
+    wsb = lib.hqmq_attend_workspace_bytes
+    need = wsb(C.byref(p), 4 * p.H)
+    assert need > 0 and need % 256 == 0
+    assert wsb(C.byref(p), p.H + 1) == 0 and wsb(C.byref(p), 9 * p.H) == 0 and wsb(None, 4) == 0
+    def call(params=p, hq_=4 * p.H, q=0x1000, scale=0.1, ek=good, ev=good, sk=0x1000, sv=0x1000, out=0x2000,
+             ws_ptr=0x4000, ws_bytes=need):
+        return att(C.byref(params), hq_, q, scale, C.byref(ek), 0, sk, C.byref(ev), 0, sv, out, ws_ptr,
+                   ws_bytes, None)
+    assert call(hq_=p.H + 1) == -1                    # not a multiple of the kv heads
+    assert call(hq_=9 * p.H) == -2                    # more than 8 query heads per kv head
+    assert call(q=None) == -1 and call(out=0x2008) == -1 and call(sv=None) == -1
+    assert call(scale=float("nan")) == -1
+    assert call(ek=bad) == -1 and call(ev=bad) == -1
+    assert call(ws_ptr=0x4010) == -1                  # workspace not 256-byte aligned
+    assert call(ws_bytes=need - 1) == -3
+    assert call(params=_params(D=64)) == -2
     assert lib.hqmq_last_hip_error() == 0
 
 

@@ -1,0 +1,200 @@
+"""GPU parity of hqmq_attend (single-query attention read from the packed K and V caches, paper
+App. F) against the fp64 oracle: the oracle reconstructs K and V from the SAME encoded bytes
+(before fp16 rounding), takes the plain softmax attention in fp64, and the library's fp16 output
+must agree within a tolerance derived from its fp32 arithmetic:
+
+  |o_gpu - o| <= 2^-10 |o|  (one fp16 rounding, with slack)  +  ATT_TOL * max|V_hat| of the head
+
+where ATT_TOL = 1e-3 bounds the effect of fp32 rounding in the 128-term score products (an
+absolute score error d changes a softmax weight by a factor 2^d) and in the running sums.  The
+observed error is printed; it sits two orders of magnitude below the bound."""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2605_27646_amd as hq
+import workloads
+from gpu_util import gpu_encode, upload_encoded
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+ATT_TOL = 1e-3
+
+
+def _bits(x: torch.Tensor) -> np.ndarray:
+    return x.contiguous().cpu().numpy().view(np.uint16)
+
+
+def _secs(seed, H, S):
+    cb = hq.hqmq_build_codebooks(seed, 1, H, S)
+    return cb[0, 0].contiguous(), cb[0, 1].contiguous()
+
+
+def _query(B, Hq, seed, gain=1.0):
+    gen = torch.Generator().manual_seed(seed)
+    return (torch.randn(B, Hq, 128, generator=gen) * gain).to(torch.float16)
+
+
+def _gpu_attend(params, q, scale, bufs_k, sec_k, bufs_v, sec_v):
+    q_dev = q.to(DEV)
+    out = torch.full_like(q_dev, float("nan"))
+    ws = torch.empty(hq.hqmq_attend_workspace_bytes(params, q.shape[1]), dtype=torch.uint8, device=DEV)
+    ws.fill_(0xCD)                      # the workspace needs no initialisation
+    hq.hqmq_attend(params, q_dev, scale, bufs_k, sec_k, bufs_v, sec_v, out, ws)
+    torch.cuda.synchronize()
+    return out.cpu().numpy().astype(np.float64)
+
+
+def _check(got, want64, V64, Hq):
+    H = V64.shape[1]
+    vmax = np.abs(V64).max(axis=(2, 3))                     # [B, H]
+    vmax_q = np.repeat(vmax, Hq // H, axis=1)[:, :, None]   # [B, Hq, 1]
+    err = np.abs(got - want64)
+    bound = 2.0 ** -10 * np.abs(want64) + ATT_TOL * vmax_q + 1e-30
+    assert np.isfinite(got).all()
+    assert (err <= bound).all(), (float(err.max()), np.argwhere(err > bound)[:5])
+    rel = float((err / np.maximum(vmax_q, 1e-30)).max())
+    print({"max_err_over_vmax": rel}, flush=True)
+    return rel
+
+
+def _oracle_attend(enc, sec_np, q, scale, B, H, T, b_r):
+    """enc: a pair of objects with codes / sigma / flags / row_off / outliers (numpy)."""
+    K64 = oracle.decode64(enc[0].codes, enc[0].sigma, enc[0].flags, enc[0].row_off, enc[0].outliers,
+                          sec_np[0], B, H, T, b_r)
+    V64 = oracle.decode64(enc[1].codes, enc[1].sigma, enc[1].flags, enc[1].row_off, enc[1].outliers,
+                          sec_np[1], B, H, T, b_r)
+    _, o64 = oracle.attend(_bits(q), K64, V64, scale)
+    return o64, K64, V64
+
+
+def _tensors(B, H, T, seed, law_sigma=0.7):
+    wl = workloads.Workload("att", 300 + seed, 1, B, H, T, 128, 16, sigma_g=law_sigma)
+    return workloads.make_tensor(wl, 0, 0, "cpu"), workloads.make_tensor(wl, 0, 1, "cpu")
+
+
+@pytest.mark.parametrize("B,H,T,Hq,S,b_r", [
+    (1, 1, 1, 1, 16, 6),          # a single cached token: the output is its value row
+    (1, 2, 63, 4, 16, 6),         # ragged tile
+    (2, 2, 200, 8, 64, 6),        # 4 query heads per kv head, several tiles
+    (1, 1, 1000, 8, 24, 6),       # 8 query heads per kv head, S not a power of two
+    (1, 3, 129, 9, 256, 4),       # 3 per kv head, one row past a tile
+    (1, 2, 777, 14, 48, 8),       # 7 per kv head (the Qwen-2.5-7B grouping)
+])
+def test_attend_small_oracle_encoded(B, H, T, Hq, S, b_r):
+    """Identical bytes on both sides: encoded by the oracle, uploaded."""
+    k, v = _tensors(B, H, T, seed=T)
+    sec_k, sec_v = _secs(5, H, S)
+    ek = oracle.encode(_bits(k), sec_k.numpy(), b_r=b_r)
+    ev = oracle.encode(_bits(v), sec_v.numpy(), b_r=b_r)
+    assert ek.n_out[-1] > 0 or T < 8
+    q = _query(B, Hq, seed=T + 1)
+    scale = 1 / math.sqrt(128)
+    want, _, V64 = _oracle_attend((ek, ev), (sec_k.numpy(), sec_v.numpy()), q, scale, B, H, T, b_r)
+    params = hq.params_for(k.to(DEV), S, b_r)
+    got = _gpu_attend(params, q, scale, upload_encoded(ek, DEV), sec_k.to(DEV), upload_encoded(ev, DEV),
+                      sec_v.to(DEV))
+    _check(got, want, V64, Hq)
+
+
+def test_attend_splits_with_several_tiles_each_gpu_encoded():
+    """Long enough that every workgroup walks several tiles and the last split is ragged;
+    encoded by the library, the oracle reads those bytes back."""
+    B, H, T, Hq, S, b_r = 2, 4, 20011, 16, 16, 6
+    k, v = _tensors(B, H, T, seed=9)
+    sec_k, sec_v = _secs(6, H, S)
+    gk = gpu_encode(k.to(DEV), sec_k.to(DEV), b_r)
+    gv = gpu_encode(v.to(DEV), sec_v.to(DEV), b_r)
+    assert gk.status == 0 and gv.status == 0 and gk.n_out[-1] > 0 and gv.n_out[-1] > 0
+    q = _query(B, Hq, seed=10, gain=2.0)
+    scale = 1 / math.sqrt(128)
+    want, _, V64 = _oracle_attend((gk, gv), (sec_k.numpy(), sec_v.numpy()), q, scale, B, H, T, b_r)
+    got = _gpu_attend(gk.params, q, scale, gk.bufs, sec_k.to(DEV), gv.bufs, sec_v.to(DEV))
+    _check(got, want, V64, Hq)
+
+
+def test_attend_picks_single_rows_including_outlier_rows():
+    """A query aligned with one cached key and a large scale puts all the weight on that token:
+    the output must be that token's reconstructed value row, outlier chunks included, to fp16
+    rounding.  One query head per probed token, the probes spread over tiles and waves."""
+    B, H, T, S, b_r = 1, 1, 517, 16, 6
+    Hq = 8
+    k, v = _tensors(B, H, T, seed=21, law_sigma=1.0)
+    sec_k, sec_v = _secs(7, H, S)
+    ek = oracle.encode(_bits(k), sec_k.numpy(), b_r=b_r)
+    ev = oracle.encode(_bits(v), sec_v.numpy(), b_r=b_r)
+    K64 = oracle.decode64(ek.codes, ek.sigma, ek.flags, ek.row_off, ek.outliers, sec_k.numpy(), B, H, T, b_r)
+    V64 = oracle.decode64(ev.codes, ev.sigma, ev.flags, ev.row_off, ev.outliers, sec_v.numpy(), B, H, T, b_r)
+    # a row with a large key norm wins a scaled dot product against its own direction: take the
+    # largest of each eighth of the sequence, so the probes fall into different tiles and waves
+    norms = np.linalg.norm(K64[0, 0], axis=1)
+    edges = np.linspace(0, T, Hq + 1).astype(int)
+    probes = [int(lo + np.argmax(norms[lo:hi])) for lo, hi in zip(edges[:-1], edges[1:])]
+    assert ev.flag.reshape(T, -1)[probes].any(1).sum() >= 4     # their value rows hold outlier chunks
+    q = np.stack([K64[0, 0, t] / norms[t] for t in probes])[None]            # [1, 8, 128]
+    q_t = torch.from_numpy(q).to(torch.float16)
+    scale = 64.0
+    want = oracle.attend(_bits(q_t), K64, V64, scale)[1]
+    params = hq.params_for(k.to(DEV), S, b_r)
+    got = _gpu_attend(params, q_t, scale, upload_encoded(ek, DEV), sec_k.to(DEV), upload_encoded(ev, DEV),
+                      sec_v.to(DEV))
+    # the probe really isolates one token in the oracle ...
+    sel = [int(np.abs(want[0, i] - V64[0, 0]).sum(1).argmin()) for i in range(Hq)]
+    iso = [np.abs(want[0, i] - V64[0, 0, sel[i]]).max() < 1e-6 * np.abs(V64[0, 0, sel[i]]).max() for i in range(Hq)]
+    assert sum(iso) >= 4, iso
+    # ... and the library returns that row to fp16 rounding
+    for i in range(Hq):
+        if iso[i]:
+            row = V64[0, 0, sel[i]]
+            assert np.abs(got[0, i] - row).max() <= 2.0 ** -10 * np.abs(row).max() + 1e-7, (i, sel[i])
+    _check(got, want, V64, Hq)
+
+
+def test_attend_without_outlier_lists():
+    B, H, T, Hq, S, b_r = 1, 2, 300, 4, 16, 6
+    k, v = _tensors(B, H, T, seed=31)
+    sec_k, sec_v = _secs(8, H, S)
+    flags = hq.HQMQ_FLAG_NO_OUTLIERS
+    gk = gpu_encode(k.to(DEV), sec_k.to(DEV), b_r, flags=flags)
+    gv = gpu_encode(v.to(DEV), sec_v.to(DEV), b_r, flags=flags)
+    assert gk.bufs.outlier_capacity == 0 and gk.n_out[-1] == 0
+    q = _query(B, Hq, seed=32)
+    want, _, V64 = _oracle_attend((gk, gv), (sec_k.numpy(), sec_v.numpy()), q, 0.1, B, H, T, b_r)
+    got = _gpu_attend(gk.params, q, 0.1, gk.bufs, sec_k.to(DEV), gv.bufs, sec_v.to(DEV))
+    _check(got, want, V64, Hq)
+
+
+def test_attend_llama3_8b_32k_layer_full_size():
+    """The bench's shape (T = 32768, 8 kv heads, 32 query heads): encoded by the library, every
+    output element checked against the oracle's attention over the same bytes."""
+    wl = workloads.WORKLOADS["llama3_8b_32k"]
+    k = workloads.make_tensor(wl, 3, 0, DEV)
+    v = workloads.make_tensor(wl, 3, 1, DEV)
+    cb = hq.hqmq_build_codebooks(0, 4, wl.H, wl.S)
+    sec_k, sec_v = cb[3, 0].contiguous(), cb[3, 1].contiguous()
+    gk = gpu_encode(k, sec_k.to(DEV), wl.b_r)
+    gv = gpu_encode(v, sec_v.to(DEV), wl.b_r)
+    Hq = 32
+    q = _query(wl.B, Hq, seed=40, gain=1.5)
+    scale = 1 / math.sqrt(128)
+    want, _, V64 = _oracle_attend((gk, gv), (sec_k.numpy(), sec_v.numpy()), q, scale, wl.B, wl.H, wl.T, wl.b_r)
+    got = _gpu_attend(gk.params, q, scale, gk.bufs, sec_k.to(DEV), gv.bufs, sec_v.to(DEV))
+    _check(got, want, V64, Hq)
+
+
+def test_attend_is_deterministic():
+    B, H, T, Hq, S = 1, 2, 5000, 8, 16
+    k, v = _tensors(B, H, T, seed=51)
+    sec_k, sec_v = _secs(9, H, S)
+    gk = gpu_encode(k.to(DEV), sec_k.to(DEV))
+    gv = gpu_encode(v.to(DEV), sec_v.to(DEV))
+    q = _query(B, Hq, seed=52)
+    a = _gpu_attend(gk.params, q, 0.09, gk.bufs, sec_k.to(DEV), gv.bufs, sec_v.to(DEV))
+    b = _gpu_attend(gk.params, q, 0.09, gk.bufs, sec_k.to(DEV), gv.bufs, sec_v.to(DEV))
+    assert np.array_equal(a, b)
