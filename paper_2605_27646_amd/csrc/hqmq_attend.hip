@@ -15,6 +15,8 @@
 //     rescale per group of 4 rows; each 16-lane group keeps its own running maximum / sum /
 //     weighted value sum, merged across groups, waves and finally splits (second kernel);
 //   * flagged chunks take their stored fp16 payload, from the wave's window of the outlier list.
+#include <type_traits>
+
 #include "hqmq_device.h"
 
 namespace hqmq {
@@ -31,6 +33,10 @@ constexpr int kPaySlots = 64;                       // outlier payloads of a wav
 constexpr int kSideWords = kStageWords + 3 * kStageRows + 2 * kPaySlots;  // one side (K or V) of one wave
 constexpr int kLoadsPerLane = (kStageRows * kMaxW + 63) / 64;
 constexpr float kNegBig = -1.0e30f;                 // "no row seen yet" (finite, so differences stay finite)
+#ifndef HQMQ_ATTEND_TARGET_BLOCKS
+#define HQMQ_ATTEND_TARGET_BLOCKS 2048
+#endif
+constexpr int kAttendTargetBlocks = HQMQ_ATTEND_TARGET_BLOCKS;  // workgroups to aim for across the chip
 constexpr int kRedStride = 2 + 128;                 // one partial state: maximum, sum, 128 weighted values
 
 static_assert(kAttendTile == kAttWaves * kStageRows, "tile = rows of all waves");
@@ -88,6 +94,22 @@ __device__ __forceinline__ void stage_tile(const TileRegs &t, uint32_t *stage, i
     }
 }
 
+// Sum over the 16 lanes of a row (quad swaps, then the two mirror patterns: after each step the
+// partial sums are uniform over a block twice as large, so a mirror pairs the right blocks).
+template <int kCtrl>
+__device__ __forceinline__ float dpp_move(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), kCtrl, 0xf, 0xf, true));
+}
+__device__ __forceinline__ float row16_sum(float v)
+{
+    v += dpp_move<0xB1>(v);   // quad_perm [1, 0, 3, 2]
+    v += dpp_move<0x4E>(v);   // quad_perm [2, 3, 0, 1]
+    v += dpp_move<0x141>(v);  // row_half_mirror
+    v += dpp_move<0x140>(v);  // row_mirror
+    return v;
+}
+
 // m, l, acc <- merge of two partial softmax states (log2 domain)
 template <int N>
 __device__ __forceinline__ void merge_state(float &m, float &l, float (&acc)[N], float m2, float l2,
@@ -117,7 +139,8 @@ __global__ __launch_bounds__(kAttThreads) void k_attend_partial(Geometry g, Atte
     float *sec_k = q_l + G * 128;
     float *sec_v = sec_k + 4 * g.S;
 
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, and known to be
     const int seg = blockIdx.y, b = seg / g.H, h = seg % g.H;
     const int split = blockIdx.x;
     const int cp = lane & 15, rsub = lane >> 4;
@@ -175,184 +198,216 @@ __global__ __launch_bounds__(kAttThreads) void k_attend_partial(Geometry g, Atte
     const uint32_t code_mask = (1u << w) - 1u, idx_mask = (1u << w_idx) - 1u;
     const float inv_L = g.inv_L;
 
+    // Outlier payloads of a wave's 16 rows: one contiguous window of the list.  Opened from the
+    // tile's registers (offset of the first row, offset + count of the last) half a tile ahead.
+    struct Window {
+        uint32_t base;
+        bool ok;     // the whole window fits the LDS slots and the list's capacity
+        uint2 mine;  // this lane's entry of the window, on its way to LDS
+    };
+    auto open_window = [&](const AttendSide &s, const TileRegs &t, int nrows) {
+        Window wd;
+        wd.base = 0;
+        wd.ok = true;
+        wd.mine = make_uint2(0u, 0u);
+        if (nrows > 0) {
+            const int last_row = nrows - 1;
+            wd.base = (uint32_t)__builtin_amdgcn_readlane((int)t.ro, 0);
+            const uint32_t ro_l = (uint32_t)__builtin_amdgcn_readlane((int)t.ro, last_row);
+            const uint32_t fw_l = (uint32_t)__builtin_amdgcn_readlane((int)t.fw, last_row);
+            const uint32_t pay_n = ro_l + __popc(fw_l) - wd.base;
+            // unconditional load: lanes past the window (or the list's capacity) re-read a neighbour's
+            // entry; a wave without outliers reads 8 harmless bytes of the offset array
+            const bool has_pay = pay_n > 0 && (uint64_t)wd.base < s.outlier_capacity;
+            const uint64_t last = has_pay ? min((uint64_t)pay_n, s.outlier_capacity - wd.base) - 1u : 0u;
+            const uint2 *src = has_pay ? reinterpret_cast<const uint2 *>(s.outliers) + wd.base
+                                       : reinterpret_cast<const uint2 *>(s.row_off);
+            wd.mine = src[min((uint64_t)lane, last)];
+            wd.ok = pay_n <= (uint32_t)kPaySlots && (uint64_t)wd.base + pay_n <= s.outlier_capacity;
+        }
+        return wd;
+    };
+
+    // ---- reconstruction of the lane's two chunks of row 4 sub + rsub --------------------------------
+    auto decode_chunk = [&](uint32_t code, float sol, const float *secl, float *y) {
+        const uint32_t rq = code >> w_idx;
+        uint32_t p_off, s_off;
+        if (kPow2) {
+            p_off = ((code >> g.log2_S) & 31u) << 4;
+            s_off = (code << 4) & (((uint32_t)g.S - 1u) << 4);
+        } else {
+            const uint32_t k = code & idx_mask;
+            const uint32_t p = (uint32_t)((float)k * g.inv_S);  // exact for k < 48 S
+            p_off = p << 4;
+            s_off = (k - __umul24(p, (uint32_t)g.S)) << 4;
+        }
+        const float4_t P = *reinterpret_cast<const float4_t *>(reinterpret_cast<const char *>(prim) + p_off);
+        const float4_t q = *reinterpret_cast<const float4_t *>(reinterpret_cast<const char *>(secl) + s_off);
+        const float rh = (float)rq * sol;
+        const float R0 = rh * P[0], R1 = rh * P[1], R2 = rh * P[2], R3 = rh * P[3];
+        y[0] = fmaf(-R3, q[3], fmaf(-R2, q[2], fmaf(-R1, q[1], R0 * q[0])));
+        y[1] = fmaf(-R3, q[2], fmaf(R2, q[3], fmaf(R1, q[0], R0 * q[1])));
+        y[2] = fmaf(R3, q[1], fmaf(R2, q[0], fmaf(-R1, q[3], R0 * q[2])));
+        y[3] = fmaf(R3, q[0], fmaf(-R2, q[1], fmaf(R1, q[2], R0 * q[3])));
+    };
+    // the 8 values of the lane's chunk pair: reconstruction, flagged chunks replaced by their payload
+    // (kFast: the wave's whole payload window sits in LDS, so the patch is branch-free; the other
+    // form serves windows beyond the LDS slots or the list's capacity.  The choice is made per tile,
+    // outside the loop over row groups, which keeps each group's code straight-line.)
+    auto row_values = [&](auto fast_tag, const AttendSide &s, const uint32_t *stage, const float *secl,
+                          uint32_t base, int sub, int nrows, float *y) {
+        constexpr bool kFast = decltype(fast_tag)::value;
+        const int r = 4 * sub + rsub;
+        const uint32_t *rw = stage + r * w + i0;
+        const uint32_t d0 = rw[0], d1 = rw[1], d2 = rw[2];
+        const uint32_t word = stage[kStageWords + r];
+        const float sigma = (float)__builtin_bit_cast(_Float16, (uint16_t)stage[kStageWords + kStageRows + r]);
+        const uint32_t code0 = __builtin_amdgcn_alignbit(d1, d0, sh0) & code_mask;
+        const uint32_t lo_win = __builtin_amdgcn_alignbit(d1, d0, sh1);
+        const uint32_t hi_win = __builtin_amdgcn_alignbit(d2, d1, sh1);
+        const uint32_t code1 = (second_in_low ? lo_win : hi_win) & code_mask;
+        const uint32_t fl = (r < nrows) ? ((word >> (2 * cp)) & 3u) : 0u;
+        const uint32_t pos = stage[kStageWords + 2 * kStageRows + r] + __popc(word & ((1u << (2 * cp)) - 1u)) - base;
+        const float sol = sigma * inv_L;
+        decode_chunk(code0, sol, secl, y);
+        decode_chunk(code1, sol, secl, y + 4);
+        const uint2 *st_pay = reinterpret_cast<const uint2 *>(stage + kStageWords + 3 * kStageRows);
+        uint2 pa = make_uint2(0u, 0u), pb = make_uint2(0u, 0u);
+        if (kFast) {
+            pa = st_pay[min(pos, (uint32_t)kPaySlots - 1u)];
+            pb = st_pay[min(pos + (fl & 1u), (uint32_t)kPaySlots - 1u)];
+        } else {
+            // per chunk, still without branches: from LDS, from memory beyond the slots (the load is
+            // unconditional, its index clamped into the list), zeros beyond the list's capacity
+            const bool any = s.outlier_capacity > 0;
+            const uint2 *src = any ? reinterpret_cast<const uint2 *>(s.outliers)
+                                   : reinterpret_cast<const uint2 *>(s.row_off);
+            const uint64_t last = any ? s.outlier_capacity - 1u : 0u;
+            auto fetch = [&](uint32_t slot) {
+                const uint64_t at = (uint64_t)base + slot;
+                const uint2 far = src[min(at, last)];
+                const uint2 near = st_pay[min(slot, (uint32_t)kPaySlots - 1u)];
+                uint2 v = (slot < (uint32_t)kPaySlots) ? near : far;
+                if (at >= s.outlier_capacity)
+                    v = make_uint2(0u, 0u);
+                return v;
+            };
+            pa = fetch(pos);
+            pb = fetch(pos + (fl & 1u));
+        }
+        const half4_t ha = __builtin_bit_cast(half4_t, pa), hb = __builtin_bit_cast(half4_t, pb);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            y[i] = (fl & 1u) ? (float)ha[i] : y[i];
+            y[4 + i] = (fl & 2u) ? (float)hb[i] : y[4 + i];
+        }
+    };
+
+    int nrows = min(kStageRows, row_end - (row_begin + wv * kStageRows));
+    Window wk = open_window(a.k, tk, nrows), wvw = open_window(a.v, tv, nrows);
+
     for (int t0 = row_begin; t0 < row_end; t0 += kAttendTile) {
-        const int tg = t0 + wv * kStageRows;
-        const int nrows = min(kStageRows, row_end - tg);  // <= 0: this wave has no rows in the tile
+        // ---- this tile's rows and payload windows into LDS; the next tile's rows requested -----------
         stage_tile(tk, stage_k, lane);
         stage_tile(tv, stage_v, lane);
+        reinterpret_cast<uint2 *>(stage_k + kStageWords + 3 * kStageRows)[lane] = wk.mine;
+        reinterpret_cast<uint2 *>(stage_v + kStageWords + 3 * kStageRows)[lane] = wvw.mine;
         wave_lds_sync();
-
-        // ---- payload windows of the wave's rows (K and V), then the next tile's encoded rows ---------
-        struct Window {
-            uint32_t base;
-            bool ok;
-            uint2 mine;
-        };
-        auto open_window = [&](const AttendSide &s, const uint32_t *stage) {
-            Window wd;
-            wd.base = 0;
-            wd.ok = true;
-            wd.mine = make_uint2(0u, 0u);
-            if (nrows > 0) {
-                const uint32_t *st_flags = stage + kStageWords, *st_roff = stage + kStageWords + 2 * kStageRows;
-                wd.base = st_roff[0];
-                const uint32_t pay_n = st_roff[nrows - 1] + __popc(st_flags[nrows - 1]) - wd.base;
-                // unconditional load: lanes past the window (or the list's capacity) re-read a neighbour's
-                // entry; a wave without outliers reads 8 harmless bytes of the offset array
-                const bool has_pay = pay_n > 0 && (uint64_t)wd.base < s.outlier_capacity;
-                const uint64_t last = has_pay ? min((uint64_t)pay_n, s.outlier_capacity - wd.base) - 1u : 0u;
-                const uint2 *src = has_pay ? reinterpret_cast<const uint2 *>(s.outliers) + wd.base
-                                           : reinterpret_cast<const uint2 *>(s.row_off);
-                wd.mine = src[min((uint64_t)lane, last)];
-                wd.ok = pay_n <= (uint32_t)kPaySlots && (uint64_t)wd.base + pay_n <= s.outlier_capacity;
-            }
-            return wd;
-        };
-        const Window wk = open_window(a.k, stage_k), wvw = open_window(a.v, stage_v);
-        if (t0 + kAttendTile < row_end) {
-            const int tgn = tg + kAttendTile;
-            const int nn = min(kStageRows, row_end - tgn);
+        const uint32_t base_k = wk.base, base_v = wvw.base;
+        const bool ok_k = wk.ok, ok_v = wvw.ok;
+        const bool more = t0 + kAttendTile < row_end;
+        const int tgn = t0 + kAttendTile + wv * kStageRows;
+        const int nn = more ? min(kStageRows, row_end - tgn) : 0;
+        if (more) {
             const int64_t R0n = (int64_t)seg * g.T + tgn;
             load_tile(tk, a.k, R0n, nn, w, lane);
             load_tile(tv, a.v, R0n, nn, w, lane);
         }
-        if (nrows <= 0)
-            continue;
 
-        // ---- reconstruction of the lane's two chunks of row 4 sub + rsub --------------------------------
-        auto decode_chunk = [&](uint32_t code, float sol, const float *secl, float *y) {
-            const uint32_t rq = code >> w_idx;
-            uint32_t p_off, s_off;
-            if (kPow2) {
-                p_off = ((code >> g.log2_S) & 31u) << 4;
-                s_off = (code << 4) & (((uint32_t)g.S - 1u) << 4);
-            } else {
-                const uint32_t k = code & idx_mask;
-                const uint32_t p = (uint32_t)((float)k * g.inv_S);  // exact for k < 48 S
-                p_off = p << 4;
-                s_off = (k - __umul24(p, (uint32_t)g.S)) << 4;
-            }
-            const float4_t P = *reinterpret_cast<const float4_t *>(reinterpret_cast<const char *>(prim) + p_off);
-            const float4_t q = *reinterpret_cast<const float4_t *>(reinterpret_cast<const char *>(secl) + s_off);
-            const float rh = (float)rq * sol;
-            const float R0 = rh * P[0], R1 = rh * P[1], R2 = rh * P[2], R3 = rh * P[3];
-            y[0] = fmaf(-R3, q[3], fmaf(-R2, q[2], fmaf(-R1, q[1], R0 * q[0])));
-            y[1] = fmaf(-R3, q[2], fmaf(R2, q[3], fmaf(R1, q[0], R0 * q[1])));
-            y[2] = fmaf(R3, q[1], fmaf(R2, q[0], fmaf(-R1, q[3], R0 * q[2])));
-            y[3] = fmaf(R3, q[0], fmaf(-R2, q[1], fmaf(R1, q[2], R0 * q[3])));
-        };
-        auto decode_pair = [&](const uint32_t *stage, const float *secl, uint32_t base, int sub, float *y,
-                               uint32_t &fl, uint32_t &pos) {
-            const int r = 4 * sub + rsub;
-            const uint32_t *rw = stage + r * w + i0;
-            const uint32_t d0 = rw[0], d1 = rw[1], d2 = rw[2];
-            const uint32_t word = stage[kStageWords + r];
-            const float sigma = (float)__builtin_bit_cast(_Float16, (uint16_t)stage[kStageWords + kStageRows + r]);
-            const uint32_t code0 = __builtin_amdgcn_alignbit(d1, d0, sh0) & code_mask;
-            const uint32_t lo_win = __builtin_amdgcn_alignbit(d1, d0, sh1);
-            const uint32_t hi_win = __builtin_amdgcn_alignbit(d2, d1, sh1);
-            const uint32_t code1 = (second_in_low ? lo_win : hi_win) & code_mask;
-            fl = (r < nrows) ? ((word >> (2 * cp)) & 3u) : 0u;
-            pos = stage[kStageWords + 2 * kStageRows + r] + __popc(word & ((1u << (2 * cp)) - 1u)) - base;
-            const float sol = sigma * inv_L;
-            decode_chunk(code0, sol, secl, y);
-            decode_chunk(code1, sol, secl, y + 4);
-        };
-        // flagged chunks: the stored fp16 values replace the reconstruction
-        auto patch = [&](const AttendSide &s, const uint32_t *stage, const Window &wd, uint32_t fl, uint32_t pos,
-                         float *y) {
-            const uint2 *st_pay = reinterpret_cast<const uint2 *>(stage + kStageWords + 3 * kStageRows);
-            uint2 pa = make_uint2(0u, 0u), pb = make_uint2(0u, 0u);
-            if (wd.ok) {
-                pa = st_pay[min(pos, (uint32_t)kPaySlots - 1u)];
-                pb = st_pay[min(pos + (fl & 1u), (uint32_t)kPaySlots - 1u)];
-            } else if (fl) {
-                // window larger than the LDS slots, or a list shorter than the offsets say: per chunk
-                auto fetch = [&](uint32_t slot) {
-                    uint2 v = make_uint2(0u, 0u);
-                    const uint64_t at = (uint64_t)wd.base + slot;
-                    if (at < s.outlier_capacity)
-                        v = (slot < (uint32_t)kPaySlots) ? st_pay[slot]
-                                                         : *reinterpret_cast<const uint2 *>(s.outliers + 4 * at);
-                    return v;
-                };
-                pa = fetch(pos);
-                pb = fetch(pos + (fl & 1u));
-            }
-            const half4_t ha = __builtin_bit_cast(half4_t, pa), hb = __builtin_bit_cast(half4_t, pb);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                y[i] = (fl & 1u) ? (float)ha[i] : y[i];
-                y[4 + i] = (fl & 2u) ? (float)hb[i] : y[4 + i];
-            }
-        };
-
-        float kx[kSubs][8];
-        uint32_t kfl[kSubs], kpos[kSubs];
-#pragma unroll
-        for (int sub = 0; sub < kSubs; ++sub)
-            decode_pair(stage_k, sec_k, wk.base, sub, kx[sub], kfl[sub], kpos[sub]);
-        // the payload windows land in LDS only now, after the arithmetic that does not need them
-        reinterpret_cast<uint2 *>(stage_k + kStageWords + 3 * kStageRows)[lane] = wk.mine;
-        reinterpret_cast<uint2 *>(stage_v + kStageWords + 3 * kStageRows)[lane] = wvw.mine;
-        wave_lds_sync();
-#pragma unroll
-        for (int sub = 0; sub < kSubs; ++sub)
-            patch(a.k, stage_k, wk, kfl[sub], kpos[sub], kx[sub]);
-
-        // ---- scores of 4 rows x G heads, softmax update --------------------------------------------------
+        // ---- scores of 4 rows x G heads -------------------------------------------------------------------
         float pw[G][kSubs];
-#pragma unroll
-        for (int gq = 0; gq < G; ++gq) {
-            const float4_t qa = *reinterpret_cast<const float4_t *>(q_l + gq * 128 + 8 * cp);
-            const float4_t qb = *reinterpret_cast<const float4_t *>(q_l + gq * 128 + 8 * cp + 4);
-            float sc[kSubs];
+        auto scores = [&](auto fast_tag) {
 #pragma unroll
             for (int sub = 0; sub < kSubs; ++sub) {
-                const float *y = kx[sub];
-                float s = qa[0] * y[0];
-                s = fmaf(qa[1], y[1], s);
-                s = fmaf(qa[2], y[2], s);
-                s = fmaf(qa[3], y[3], s);
-                s = fmaf(qb[0], y[4], s);
-                s = fmaf(qb[1], y[5], s);
-                s = fmaf(qb[2], y[6], s);
-                s = fmaf(qb[3], y[7], s);
-                s += __shfl_xor(s, 1);
-                s += __shfl_xor(s, 2);
-                s += __shfl_xor(s, 4);
-                s += __shfl_xor(s, 8);
-                sc[sub] = (4 * sub + rsub < nrows) ? s : kNegBig;
-            }
-            const float mn = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])), m[gq]);
-            const float corr = __builtin_amdgcn_exp2f(m[gq] - mn);
-            float psum = 0.f;
+                // the query is re-read from LDS for every row group (an opaque offset keeps the
+                // compiler from parking all 8 G values in registers)
+                int q_off = 8 * cp;
+                asm volatile("" : "+v"(q_off));
+                float y[8];
+                row_values(fast_tag, a.k, stage_k, sec_k, base_k, sub, nrows, y);
 #pragma unroll
-            for (int sub = 0; sub < kSubs; ++sub) {
-                const float e = __builtin_amdgcn_exp2f(sc[sub] - mn);
-                pw[gq][sub] = (4 * sub + rsub < nrows) ? e : 0.f;
-                psum += pw[gq][sub];
+                for (int gq = 0; gq < G; ++gq) {
+                    const float4_t qa = *reinterpret_cast<const float4_t *>(q_l + gq * 128 + q_off);
+                    const float4_t qb = *reinterpret_cast<const float4_t *>(q_l + gq * 128 + q_off + 4);
+                    float s = qa[0] * y[0];
+                    s = fmaf(qa[1], y[1], s);
+                    s = fmaf(qa[2], y[2], s);
+                    s = fmaf(qa[3], y[3], s);
+                    s = fmaf(qb[0], y[4], s);
+                    s = fmaf(qb[1], y[5], s);
+                    s = fmaf(qb[2], y[6], s);
+                    s = fmaf(qb[3], y[7], s);
+                    pw[gq][sub] = row16_sum(s);
+                }
+                // keep the four row groups apart: interleaving them only lengthens live ranges
+                //SB __builtin_amdgcn_sched_barrier(0);
             }
-            l[gq] = l[gq] * corr + psum;
+        };
+        if (nrows > 0) {
+            if (ok_k)
+                scores(std::true_type{});
+            else
+                scores(std::false_type{});
+            // ---- softmax update, one rescale per 4 rows ---------------------------------------------------
 #pragma unroll
-            for (int i = 0; i < 8; ++i)
-                acc[gq][i] *= corr;
-            m[gq] = mn;
+            for (int gq = 0; gq < G; ++gq) {
+                float mn = m[gq];
+#pragma unroll
+                for (int sub = 0; sub < kSubs; ++sub)
+                    mn = fmaxf(mn, (4 * sub + rsub < nrows) ? pw[gq][sub] : kNegBig);
+                const float corr = __builtin_amdgcn_exp2f(m[gq] - mn);
+                float psum = 0.f;
+#pragma unroll
+                for (int sub = 0; sub < kSubs; ++sub) {
+                    const float e = __builtin_amdgcn_exp2f(pw[gq][sub] - mn);
+                    pw[gq][sub] = (4 * sub + rsub < nrows) ? e : 0.f;
+                    psum += pw[gq][sub];
+                }
+                l[gq] = l[gq] * corr + psum;
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    acc[gq][i] *= corr;
+                m[gq] = mn;
+            }
+        }
+
+        // ---- the next tile's payload windows (its offsets have arrived by now) ---------------------------
+        if (more) {
+            wk = open_window(a.k, tk, nn);
+            wvw = open_window(a.v, tv, nn);
         }
 
         // ---- weighted values ----------------------------------------------------------------------------
+        auto weighted_values = [&](auto fast_tag) {
 #pragma unroll
-        for (int sub = 0; sub < kSubs; ++sub) {
-            float vx[8];
-            uint32_t vfl, vpos;
-            decode_pair(stage_v, sec_v, wvw.base, sub, vx, vfl, vpos);
-            patch(a.v, stage_v, wvw, vfl, vpos, vx);
+            for (int sub = 0; sub < kSubs; ++sub) {
+                float vx[8];
+                row_values(fast_tag, a.v, stage_v, sec_v, base_v, sub, nrows, vx);
 #pragma unroll
-            for (int gq = 0; gq < G; ++gq)
+                for (int gq = 0; gq < G; ++gq)
 #pragma unroll
-                for (int i = 0; i < 8; ++i)
-                    acc[gq][i] = fmaf(pw[gq][sub], vx[i], acc[gq][i]);
+                    for (int i = 0; i < 8; ++i)
+                        acc[gq][i] = fmaf(pw[gq][sub], vx[i], acc[gq][i]);
+                //SB __builtin_amdgcn_sched_barrier(0);
+            }
+        };
+        if (nrows > 0) {
+            if (ok_v)
+                weighted_values(std::true_type{});
+            else
+                weighted_values(std::false_type{});
         }
+        nrows = nn;
     }
 
     // ---- merge: the 4 row groups of a wave (lanes l, l^16, l^32, l^48), then the 4 waves -----------------
@@ -407,42 +462,72 @@ __global__ __launch_bounds__(kAttThreads) void k_attend_partial(Geometry g, Atte
     }
 }
 
-// grid = B * H * G (one workgroup per query head), block = 256: wave wq folds splits wq, wq + 4, ...,
-// a lane holding two of the 128 dimensions; the four waves meet in LDS.
+// grid = (B * H * G, 8): workgroup (head, y) produces 16 of the head's 128 output dimensions.
+// First the global maximum and the weight 2^(m_s - M) of every split (kept in LDS), then plain
+// weighted sums with independent loads: thread (j, i) adds the splits j, j + 16, ... for dimension i.
+constexpr int kMergeDims = 16;
+constexpr int kMergeWays = kAttThreads / kMergeDims;
 __global__ __launch_bounds__(kAttThreads) void k_attend_merge(AttendArgs a)
 {
-    __shared__ float red[kAttWaves][kRedStride];
+    extern __shared__ float wts[];  // [n_splits] weights, then [kMergeWays][kMergeDims + 1] partial sums
+    __shared__ float red[kAttWaves];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const size_t head = blockIdx.x;
-    const float *ml = a.part_ml + head * a.n_splits * 2;
-    const float *pa = a.part_acc + head * a.n_splits * 128;
-    float m = kNegBig, l = 0.f, o[2] = {0.f, 0.f};
-    for (int s = wv; s < a.n_splits; s += kAttWaves) {
-        const float2 st = *reinterpret_cast<const float2 *>(ml + 2 * s);
-        const float2 av = *reinterpret_cast<const float2 *>(pa + (size_t)s * 128 + 2 * lane);
-        const float a2[2] = {av.x, av.y};
-        merge_state(m, l, o, st.x, st.y, a2);
-    }
-    if (lane == 0) {
-        red[wv][0] = m;
-        red[wv][1] = l;
-    }
-    red[wv][2 + 2 * lane] = o[0];
-    red[wv][2 + 2 * lane + 1] = o[1];
+    const int d0 = blockIdx.y * kMergeDims;
+    const int n = a.n_splits;
+    const float2 *ml = reinterpret_cast<const float2 *>(a.part_ml) + head * n;
+    const float *pa = a.part_acc + head * n * 128;
+
+    float mx = kNegBig;
+    for (int s = tid; s < n; s += kAttThreads)
+        mx = fmaxf(mx, ml[s].x);
+#pragma unroll
+    for (int step = 32; step >= 1; step >>= 1)
+        mx = fmaxf(mx, __shfl_xor(mx, step));
+    if (lane == 0)
+        red[wv] = mx;
     __syncthreads();
-    if (tid < 128) {
-        float mm = kNegBig;
+    mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    __syncthreads();
+    float lsum = 0.f;
+    for (int s = tid; s < n; s += kAttThreads) {
+        const float2 st = ml[s];
+        const float wgt = __builtin_amdgcn_exp2f(st.x - mx);
+        wts[s] = wgt;
+        lsum = fmaf(st.y, wgt, lsum);
+    }
 #pragma unroll
-        for (int wq = 0; wq < kAttWaves; ++wq)
-            mm = fmaxf(mm, red[wq][0]);
-        float ll = 0.f, oo = 0.f;
+    for (int step = 32; step >= 1; step >>= 1)
+        lsum += __shfl_xor(lsum, step);
+    if (lane == 0)
+        red[wv] = lsum;
+    __syncthreads();
+    lsum = (red[0] + red[1]) + (red[2] + red[3]);
+
+    const int i = tid % kMergeDims, j = tid / kMergeDims;
+    float o = 0.f;
+    int s = j;
+    for (; s + 3 * kMergeWays < n; s += 4 * kMergeWays) {  // four loads in flight
+        const float v0 = pa[(size_t)s * 128 + d0 + i];
+        const float v1 = pa[(size_t)(s + kMergeWays) * 128 + d0 + i];
+        const float v2 = pa[(size_t)(s + 2 * kMergeWays) * 128 + d0 + i];
+        const float v3 = pa[(size_t)(s + 3 * kMergeWays) * 128 + d0 + i];
+        o = fmaf(v0, wts[s], o);
+        o = fmaf(v1, wts[s + kMergeWays], o);
+        o = fmaf(v2, wts[s + 2 * kMergeWays], o);
+        o = fmaf(v3, wts[s + 3 * kMergeWays], o);
+    }
+    for (; s < n; s += kMergeWays)
+        o = fmaf(pa[(size_t)s * 128 + d0 + i], wts[s], o);
+    float *sums = wts + n;
+    sums[j * (kMergeDims + 1) + i] = o;
+    __syncthreads();
+    if (tid < kMergeDims) {
+        float tot = 0.f;
 #pragma unroll
-        for (int wq = 0; wq < kAttWaves; ++wq) {
-            const float c = __builtin_amdgcn_exp2f(red[wq][0] - mm);
-            ll = fmaf(red[wq][1], c, ll);
-            oo = fmaf(red[wq][2 + tid], c, oo);
-        }
-        a.out[head * 128 + tid] = (_Float16)(oo / ll);
+        for (int jj = 0; jj < kMergeWays; ++jj)
+            tot += sums[jj * (kMergeDims + 1) + tid];
+        a.out[head * 128 + d0 + tid] = (_Float16)(tot / lsum);
     }
 }
 
@@ -451,7 +536,7 @@ AttendPlan plan_attend(const Geometry &g, int G)
     AttendPlan p;
     const int64_t n_tiles = ((int64_t)g.T + kAttendTile - 1) / kAttendTile;
     const int64_t segs = (int64_t)g.B * g.H;
-    int64_t want = (2048 + segs - 1) / segs;  // about 8 workgroups per compute unit
+    int64_t want = (kAttendTargetBlocks + segs - 1) / segs;
     if (want > n_tiles)
         want = n_tiles;
     if (want < 1)
@@ -500,7 +585,9 @@ hipError_t launch_attend(const Geometry &g, const AttendArgs &a, hipStream_t str
     hipError_t err = hipGetLastError();
     if (err != hipSuccess)
         return err;
-    hipLaunchKernelGGL(k_attend_merge, dim3((unsigned)(g.B * g.H * a.G)), dim3(kAttThreads), 0, stream, a);
+    const size_t merge_lds = ((size_t)a.n_splits + kMergeWays * (kMergeDims + 1)) * sizeof(float);
+    hipLaunchKernelGGL(k_attend_merge, dim3((unsigned)(g.B * g.H * a.G), 128 / kMergeDims), dim3(kAttThreads),
+                       merge_lds, stream, a);
     return hipGetLastError();
 }
 
