@@ -173,11 +173,12 @@ int32_t hqmq_decode_batch(const hqmq_params *params, int32_t n_tensors, const hq
  * fused attention kernel, App. F: O = softmax(Q K^T * scale) V with K and V reconstructed inside
  * the attention loop and never materialised), for ONE query token per sequence (the generation
  * step).  Query head hq attends to kv head hq / (n_q_heads / H) (grouped-query attention); all T
- * cached tokens are visible.  K_hat and V_hat are the reconstructions r_hat * (P_p (x) q_s) before
- * any fp16 rounding, flagged chunks as stored; products and sums are fp32, the softmax subtracts
- * the running maximum (online form), the result is rounded once to fp16.
+ * cached tokens are visible.  K_hat and V_hat are exactly the fp16 tensors hqmq_decode would
+ * return; their products with Q and with the softmax weights are accumulated in fp32 (the
+ * weights enter with about 22 significant bits), the softmax subtracts the running maximum
+ * (online form), and the result is rounded once to fp16.
  *   params     HOST; B, H, T, D, S, b_r describe BOTH caches (strides are ignored).
- *   n_q_heads  a multiple of H, at most 8 * H.
+ *   n_q_heads  a multiple of H, at most 16 * H.
  *   q_dev      DEVICE, fp16 [B][n_q_heads][128] contiguous, 16-byte aligned.
  *   scale      softmax scale (usually 1/sqrt(128)); finite.
  *   enc_k, enc_v, cap_k, cap_v, sec_k_dev, sec_v_dev   as enc / outlier_capacity / sec_dev of
@@ -187,7 +188,7 @@ int32_t hqmq_decode_batch(const hqmq_params *params, int32_t n_tensors, const hq
  *              by the caller, contents undefined afterwards; concurrent calls need their own.
  *   stream     hipStream_t; two kernels are enqueued, nothing is synchronised or allocated.
  * Errors: INVALID_ARG (null / misaligned pointer, bad n_q_heads, non-finite scale), UNSUPPORTED
- * (params the decode rejects, more than 8 query heads per kv head), BUFFER_TOO_SMALL, HIP. */
+ * (params the decode rejects, more than 16 query heads per kv head), BUFFER_TOO_SMALL, HIP. */
 int32_t hqmq_attend(const hqmq_params *params, int32_t n_q_heads, const void *q_dev, float scale,
                     const hqmq_encoded *enc_k, uint64_t cap_k, const float *sec_k_dev,
                     const hqmq_encoded *enc_v, uint64_t cap_v, const float *sec_v_dev, void *out_dev,

@@ -1,20 +1,28 @@
 // Single-query attention straight from the packed cache (paper App. F, the fused attention
-// kernel: O = softmax(Q K^T scale) V with K and V decoded inside the attention loop and never
-// written out in fp16).  This is the generation step's shape: one query token per sequence, G
-// query heads sharing each kv head.
+// kernel: O = softmax(Q K^T scale) V with K and V decoded inside the attention loop, handed to the
+// matrix cores as fp16 tiles and never written out).  This is the generation step's shape: one
+// query token per sequence, G query heads sharing each kv head.
 //
-// Bound by the decode arithmetic and the packed bytes: per cached token it reads 2 * (4 w + 10)
-// bytes plus the outlier payloads, where plain fp16 attention reads 512.  Shape:
+// Bound by the decode arithmetic: per cached token it reads 2 * (4 w + 10) bytes plus the outlier
+// payloads, where plain fp16 attention reads 512.  Shape:
 //   * split-K over the sequence: workgroup (split, b * H + h) walks its rows in tiles of 64, a wave
-//     takes 16 rows of a tile; the encoded rows of K and of V arrive with coalesced loads that are
-//     issued one tile ahead and re-distributed through LDS exactly as in the stand-alone decode;
-//   * a lane owns two adjacent chunks (8 of the 128 dimensions) of four of the wave's rows: the
-//     query-key products are partial sums over those 8 dimensions, completed across the 16 lanes
-//     of a row with a butterfly; every reconstructed K or V chunk serves all G query heads;
-//   * online softmax in the log2 domain (the scale and log2 e are folded into the query), one
-//     rescale per group of 4 rows; each 16-lane group keeps its own running maximum / sum /
-//     weighted value sum, merged across groups, waves and finally splits (second kernel);
-//   * flagged chunks take their stored fp16 payload, from the wave's window of the outlier list.
+//     takes 16 rows of a tile; the encoded rows of K and of V arrive with coalesced loads issued one
+//     tile ahead and are re-distributed through LDS as in the stand-alone decode;
+//   * both products run on v_mfma_f32_16x16x16_f16, and the lane-to-chunk assignment of each decode
+//     is the operand layout of its product, so no value crosses lanes:
+//       scores  S[row][head]  = K_hat[16 rows x 128] * Q^T : lane (row = l % 16, j = l / 16) decodes
+//               chunks 4 m + j, m = 0..7, i.e. exactly the four k-values it owes to product m;
+//       values  O[head][dim] += P^T[head x 16 rows] * V_hat : lane (n = l % 16, j) decodes chunks
+//               n and n + 16 of rows 4 j .. 4 j + 3; a 4 x 4 (row x component) block, regrouped by
+//               component with byte permutes, feeds four products whose output column n stands for
+//               dimension 4 n + e (+ 64 for the upper chunk);
+//     the scores of product one land as lane (head = l % 16, rows 4 j .. 4 j + 3), which is the
+//     layout product two wants for P^T;
+//   * online softmax in the log2 domain, fp32; the weights enter the second product as an fp16
+//     pair (high part + remainder), so they carry about 22 bits; the accumulators are rescaled only
+//     when a tile raises a head's running maximum;
+//   * a flagged chunk takes its stored fp16 payload from the wave's window of the outlier list.
+// The work per cached token does not depend on G (up to 16 heads ride in one product).
 #include <type_traits>
 
 #include "hqmq_device.h"
@@ -26,22 +34,20 @@ namespace {
 constexpr int kAttThreads = 256;
 constexpr int kAttWaves = kAttThreads / 64;
 constexpr int kStageRows = 16;                      // rows per wave and tile
-constexpr int kSubs = kStageRows / 4;               // a wave handles 4 rows at a time
 constexpr int kMaxW = 24;                           // w <= 22
-constexpr int kStageWords = kStageRows * kMaxW + 2; // + 2 words of padding for the 3-word window
+constexpr int kStageWords = kStageRows * kMaxW + 4; // + padding: a 2-word window may start at the last word
 constexpr int kPaySlots = 64;                       // outlier payloads of a wave's 16 rows kept in LDS
 constexpr int kSideWords = kStageWords + 3 * kStageRows + 2 * kPaySlots;  // one side (K or V) of one wave
 constexpr int kLoadsPerLane = (kStageRows * kMaxW + 63) / 64;
 constexpr float kNegBig = -1.0e30f;                 // "no row seen yet" (finite, so differences stay finite)
-#ifndef HQMQ_ATTEND_TARGET_BLOCKS
-#define HQMQ_ATTEND_TARGET_BLOCKS 2048
-#endif
-constexpr int kAttendTargetBlocks = HQMQ_ATTEND_TARGET_BLOCKS;  // workgroups to aim for across the chip
 constexpr int kRedStride = 2 + 128;                 // one partial state: maximum, sum, 128 weighted values
+constexpr int kAttendTargetBlocks = 512;            // two resident workgroups per compute unit
+constexpr uint32_t kHalfOfMaxHalf = 0x77ffu;        // 32752 = 65504 / 2 as fp16 bits
 
 static_assert(kAttendTile == kAttWaves * kStageRows, "tile = rows of all waves");
-static_assert(kAttWaves * kMaxGroup * kRedStride <= kAttWaves * 2 * kSideWords,
-              "the end-of-workgroup reduction re-uses the staging area");
+static_assert(kStageWords % 4 == 0 && kSideWords % 4 == 0, "16-byte LDS reads of the per-row words");
+
+typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ void wave_lds_sync()
 {
@@ -80,13 +86,15 @@ __device__ __forceinline__ void load_tile(TileRegs &t, const AttendSide &s, int6
     }
 }
 
+// LDS image of one side: code words [16 rows][w] | padding | flag words [16] | scales [16] |
+// offsets [16] | payload window [64] x 8 bytes
 __device__ __forceinline__ void stage_tile(const TileRegs &t, uint32_t *stage, int lane)
 {
 #pragma unroll
     for (int j = 0; j < kLoadsPerLane; ++j)
         stage[lane + 64 * j] = t.cw[j];
-    if (lane < 2)
-        stage[kStageWords - 2 + lane] = 0;
+    if (lane < 4)
+        stage[kStageWords - 4 + lane] = 0;
     if (lane < kStageRows) {
         stage[kStageWords + lane] = t.fw;
         stage[kStageWords + kStageRows + lane] = t.sg;
@@ -94,56 +102,41 @@ __device__ __forceinline__ void stage_tile(const TileRegs &t, uint32_t *stage, i
     }
 }
 
-// Sum over the 16 lanes of a row (quad swaps, then the two mirror patterns: after each step the
-// partial sums are uniform over a block twice as large, so a mirror pairs the right blocks).
-template <int kCtrl>
-__device__ __forceinline__ float dpp_move(float v)
+__device__ __forceinline__ uint32_t pack_half2(float lo, float hi)
 {
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), kCtrl, 0xf, 0xf, true));
-}
-__device__ __forceinline__ float row16_sum(float v)
-{
-    v += dpp_move<0xB1>(v);   // quad_perm [1, 0, 3, 2]
-    v += dpp_move<0x4E>(v);   // quad_perm [2, 3, 0, 1]
-    v += dpp_move<0x141>(v);  // row_half_mirror
-    v += dpp_move<0x140>(v);  // row_mirror
-    return v;
+    typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+    half2_t v;
+    v[0] = (_Float16)lo;
+    v[1] = (_Float16)hi;
+    return __builtin_bit_cast(uint32_t, v);
 }
 
-// m, l, acc <- merge of two partial softmax states (log2 domain)
-template <int N>
-__device__ __forceinline__ void merge_state(float &m, float &l, float (&acc)[N], float m2, float l2,
-                                            const float (&acc2)[N])
+__device__ __forceinline__ float4_t mfma16(uint2 a, uint2 b, float4_t c)
 {
-    const float mn = fmaxf(m, m2);
-    const float c1 = __builtin_amdgcn_exp2f(m - mn), c2 = __builtin_amdgcn_exp2f(m2 - mn);
-    l = l * c1 + l2 * c2;
-#pragma unroll
-    for (int i = 0; i < N; ++i)
-        acc[i] = acc[i] * c1 + acc2[i] * c2;
-    m = mn;
+    return __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(half4_t, a), __builtin_bit_cast(half4_t, b), c,
+                                                 0, 0, 0);
 }
 
 }  // namespace
 
 // grid = (n_splits, B*H), block = 256.
-// dynamic LDS: prim [48][4] f32 | staging [4 waves][K, V][kSideWords] u32 | q [G][128] f32 |
-//              secondaries of K [S][4] f32 | secondaries of V [S][4] f32
-template <bool kPow2, int G>
-__global__ __launch_bounds__(kAttThreads) void k_attend_partial(Geometry g, AttendArgs a)
+// dynamic LDS: prim [48][4] f32 | max(staging [4 waves][K, V][kSideWords] u32, merge buffer
+//              [4 waves][G][130] f32) | secondaries of K [S][4] f32 | secondaries of V [S][4] f32
+template <bool kPow2>
+__global__ __launch_bounds__(kAttThreads) void k_attend_partial(Geometry g, AttendArgs a, int stage_floats)
 {
     extern __shared__ float lds[];
     float *prim = lds;
     uint32_t *stage_all = reinterpret_cast<uint32_t *>(prim + 48 * 4);
-    float *q_l = reinterpret_cast<float *>(stage_all + kAttWaves * 2 * kSideWords);
-    float *sec_k = q_l + G * 128;
+    float *sec_k = reinterpret_cast<float *>(stage_all) + stage_floats;
     float *sec_v = sec_k + 4 * g.S;
 
     const int tid = threadIdx.x, lane = tid & 63;
-    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, and known to be
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int seg = blockIdx.y, b = seg / g.H, h = seg % g.H;
     const int split = blockIdx.x;
-    const int cp = lane & 15, rsub = lane >> 4;
+    const int n16 = lane & 15, j4 = lane >> 4;
+    const int G = a.G;
     const uint32_t w = g.w, w_idx = g.w_idx;
     const int row_begin = split * a.rows_per_split;
     const int row_end = min(g.T, row_begin + a.rows_per_split);
@@ -153,12 +146,21 @@ __global__ __launch_bounds__(kAttThreads) void k_attend_partial(Geometry g, Atte
 
     // ---- first tile on its way while the tables are set up ----------------------------------------------
     TileRegs tk, tv;
+    int nrows = min(kStageRows, row_end - (row_begin + wv * kStageRows));
     {
-        const int tg = row_begin + wv * kStageRows;
-        const int nrows = min(kStageRows, row_end - tg);
-        const int64_t R0 = (int64_t)seg * g.T + tg;
+        const int64_t R0 = (int64_t)seg * g.T + row_begin + wv * kStageRows;
         load_tile(tk, a.k, R0, nrows, w, lane);
         load_tile(tv, a.v, R0, nrows, w, lane);
+    }
+    // Q^T as the B operand of the score products: lane (head n16, j4) holds q[head][16 m + 4 j4 + 0..3]
+    uint2 qb[8];
+    {
+        const _Float16 *qh = a.q + (((size_t)b * g.H + h) * G + min(n16, G - 1)) * 128 + 4 * j4;
+#pragma unroll
+        for (int m = 0; m < 8; ++m) {
+            const uint2 v = *reinterpret_cast<const uint2 *>(qh + 16 * m);
+            qb[m] = (n16 < G) ? v : make_uint2(0u, 0u);
+        }
     }
     {
         const float *sk = a.k.sec + (size_t)h * g.S * 4, *sv = a.v.sec + (size_t)h * g.S * 4;
@@ -175,26 +177,20 @@ __global__ __launch_bounds__(kAttThreads) void k_attend_partial(Geometry g, Atte
                 v = (((p - 8) >> (3 - i)) & 1) ? -0.5f : 0.5f;
             prim[tid] = v;
         }
-        const _Float16 *qh = a.q + ((size_t)b * g.H + h) * G * 128;  // the G query heads of this kv head
-        for (int i = tid; i < G * 128; i += kAttThreads)
-            q_l[i] = (float)qh[i] * a.qscale;
     }
     __syncthreads();
 
-    float m[G], l[G], acc[G][8];
+    // running state of head n16 (m_run is the same in all four j4 groups; l_run holds this lane's
+    // rows only and is summed over j4 at the end)
+    float m_run = kNegBig, l_run = 0.f;
+    // [upper chunk u][component e]: element i = head 4 j4 + i, output column n16 = dimension 64 u + 4 n16 + e
+    float4_t acc[2][4];
 #pragma unroll
-    for (int gq = 0; gq < G; ++gq) {
-        m[gq] = kNegBig;
-        l[gq] = 0.f;
+    for (int u = 0; u < 2; ++u)
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
-            acc[gq][i] = 0.f;
-    }
+        for (int e = 0; e < 4; ++e)
+            acc[u][e] = float4_t{0.f, 0.f, 0.f, 0.f};
 
-    const uint32_t bitpos = (uint32_t)(2 * cp) * w;
-    const uint32_t i0 = bitpos >> 5, sh0 = bitpos & 31;
-    const uint32_t sh1 = sh0 + w;
-    const bool second_in_low = sh1 < 32;
     const uint32_t code_mask = (1u << w) - 1u, idx_mask = (1u << w_idx) - 1u;
     const float inv_L = g.inv_L;
 
@@ -205,13 +201,13 @@ __global__ __launch_bounds__(kAttThreads) void k_attend_partial(Geometry g, Atte
         bool ok;     // the whole window fits the LDS slots and the list's capacity
         uint2 mine;  // this lane's entry of the window, on its way to LDS
     };
-    auto open_window = [&](const AttendSide &s, const TileRegs &t, int nrows) {
+    auto open_window = [&](const AttendSide &s, const TileRegs &t, int nr) {
         Window wd;
         wd.base = 0;
         wd.ok = true;
         wd.mine = make_uint2(0u, 0u);
-        if (nrows > 0) {
-            const int last_row = nrows - 1;
+        if (nr > 0) {
+            const int last_row = nr - 1;
             wd.base = (uint32_t)__builtin_amdgcn_readlane((int)t.ro, 0);
             const uint32_t ro_l = (uint32_t)__builtin_amdgcn_readlane((int)t.ro, last_row);
             const uint32_t fw_l = (uint32_t)__builtin_amdgcn_readlane((int)t.fw, last_row);
@@ -228,8 +224,17 @@ __global__ __launch_bounds__(kAttThreads) void k_attend_partial(Geometry g, Atte
         return wd;
     };
 
-    // ---- reconstruction of the lane's two chunks of row 4 sub + rsub --------------------------------
-    auto decode_chunk = [&](uint32_t code, float sol, const float *secl, float *y) {
+    // One chunk of `row` as the library's decode returns it: four fp16 values (two dwords).
+    // kFast: the wave's whole payload window sits in LDS and no scale of the tile can overflow fp16,
+    // so there is neither a far load nor a clamp.  The choice is made per tile and side.
+    auto chunk_half4 = [&](auto fast_tag, const AttendSide &s, const uint32_t *stage, const float *secl,
+                           uint32_t base, int row, uint32_t c, uint32_t word, uint32_t roff, float sol,
+                           bool row_valid) {
+        constexpr bool kFast = decltype(fast_tag)::value;
+        const uint32_t bitpos = c * w;
+        const uint32_t *rw = stage + row * w + (bitpos >> 5);
+        const uint32_t d0 = rw[0], d1 = rw[1];
+        const uint32_t code = __builtin_amdgcn_alignbit(d1, d0, bitpos & 31u) & code_mask;
         const uint32_t rq = code >> w_idx;
         uint32_t p_off, s_off;
         if (kPow2) {
@@ -245,65 +250,42 @@ __global__ __launch_bounds__(kAttThreads) void k_attend_partial(Geometry g, Atte
         const float4_t q = *reinterpret_cast<const float4_t *>(reinterpret_cast<const char *>(secl) + s_off);
         const float rh = (float)rq * sol;
         const float R0 = rh * P[0], R1 = rh * P[1], R2 = rh * P[2], R3 = rh * P[3];
-        y[0] = fmaf(-R3, q[3], fmaf(-R2, q[2], fmaf(-R1, q[1], R0 * q[0])));
-        y[1] = fmaf(-R3, q[2], fmaf(R2, q[3], fmaf(R1, q[0], R0 * q[1])));
-        y[2] = fmaf(R3, q[1], fmaf(R2, q[0], fmaf(-R1, q[3], R0 * q[2])));
-        y[3] = fmaf(R3, q[0], fmaf(-R2, q[1], fmaf(R1, q[2], R0 * q[3])));
-    };
-    // the 8 values of the lane's chunk pair: reconstruction, flagged chunks replaced by their payload
-    // (kFast: the wave's whole payload window sits in LDS, so the patch is branch-free; the other
-    // form serves windows beyond the LDS slots or the list's capacity.  The choice is made per tile,
-    // outside the loop over row groups, which keeps each group's code straight-line.)
-    auto row_values = [&](auto fast_tag, const AttendSide &s, const uint32_t *stage, const float *secl,
-                          uint32_t base, int sub, int nrows, float *y) {
-        constexpr bool kFast = decltype(fast_tag)::value;
-        const int r = 4 * sub + rsub;
-        const uint32_t *rw = stage + r * w + i0;
-        const uint32_t d0 = rw[0], d1 = rw[1], d2 = rw[2];
-        const uint32_t word = stage[kStageWords + r];
-        const float sigma = (float)__builtin_bit_cast(_Float16, (uint16_t)stage[kStageWords + kStageRows + r]);
-        const uint32_t code0 = __builtin_amdgcn_alignbit(d1, d0, sh0) & code_mask;
-        const uint32_t lo_win = __builtin_amdgcn_alignbit(d1, d0, sh1);
-        const uint32_t hi_win = __builtin_amdgcn_alignbit(d2, d1, sh1);
-        const uint32_t code1 = (second_in_low ? lo_win : hi_win) & code_mask;
-        const uint32_t fl = (r < nrows) ? ((word >> (2 * cp)) & 3u) : 0u;
-        const uint32_t pos = stage[kStageWords + 2 * kStageRows + r] + __popc(word & ((1u << (2 * cp)) - 1u)) - base;
-        const float sol = sigma * inv_L;
-        decode_chunk(code0, sol, secl, y);
-        decode_chunk(code1, sol, secl, y + 4);
+        float y0 = fmaf(-R3, q[3], fmaf(-R2, q[2], fmaf(-R1, q[1], R0 * q[0])));
+        float y1 = fmaf(-R3, q[2], fmaf(R2, q[3], fmaf(R1, q[0], R0 * q[1])));
+        float y2 = fmaf(R3, q[1], fmaf(R2, q[0], fmaf(-R1, q[3], R0 * q[2])));
+        float y3 = fmaf(R3, q[0], fmaf(-R2, q[1], fmaf(R1, q[2], R0 * q[3])));
+        if (!kFast) {
+            const float lim = 65504.f;  // the decode saturates instead of overflowing to infinity
+            y0 = __builtin_amdgcn_fmed3f(y0, -lim, lim);
+            y1 = __builtin_amdgcn_fmed3f(y1, -lim, lim);
+            y2 = __builtin_amdgcn_fmed3f(y2, -lim, lim);
+            y3 = __builtin_amdgcn_fmed3f(y3, -lim, lim);
+        }
+        uint2 out = make_uint2(pack_half2(y0, y1), pack_half2(y2, y3));
+        // flagged: the stored payload replaces the reconstruction
+        const bool fl = row_valid && ((word >> c) & 1u);
+        const uint32_t pos = roff + __popc(word & ((1u << c) - 1u)) - base;
         const uint2 *st_pay = reinterpret_cast<const uint2 *>(stage + kStageWords + 3 * kStageRows);
-        uint2 pa = make_uint2(0u, 0u), pb = make_uint2(0u, 0u);
-        if (kFast) {
-            pa = st_pay[min(pos, (uint32_t)kPaySlots - 1u)];
-            pb = st_pay[min(pos + (fl & 1u), (uint32_t)kPaySlots - 1u)];
-        } else {
-            // per chunk, still without branches: from LDS, from memory beyond the slots (the load is
-            // unconditional, its index clamped into the list), zeros beyond the list's capacity
+        uint2 pay = st_pay[min(pos, (uint32_t)kPaySlots - 1u)];
+        if (!kFast) {
+            // still without branches: from memory beyond the LDS slots (unconditional load, index
+            // clamped into the list), zeros beyond the list's capacity
             const bool any = s.outlier_capacity > 0;
             const uint2 *src = any ? reinterpret_cast<const uint2 *>(s.outliers)
                                    : reinterpret_cast<const uint2 *>(s.row_off);
             const uint64_t last = any ? s.outlier_capacity - 1u : 0u;
-            auto fetch = [&](uint32_t slot) {
-                const uint64_t at = (uint64_t)base + slot;
-                const uint2 far = src[min(at, last)];
-                const uint2 near = st_pay[min(slot, (uint32_t)kPaySlots - 1u)];
-                uint2 v = (slot < (uint32_t)kPaySlots) ? near : far;
-                if (at >= s.outlier_capacity)
-                    v = make_uint2(0u, 0u);
-                return v;
-            };
-            pa = fetch(pos);
-            pb = fetch(pos + (fl & 1u));
+            const uint64_t at = (uint64_t)base + pos;
+            const uint2 far = src[min(at, last)];
+            if (pos >= (uint32_t)kPaySlots)
+                pay = far;
+            if (at >= s.outlier_capacity)
+                pay = make_uint2(0u, 0u);
         }
-        const half4_t ha = __builtin_bit_cast(half4_t, pa), hb = __builtin_bit_cast(half4_t, pb);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            y[i] = (fl & 1u) ? (float)ha[i] : y[i];
-            y[4 + i] = (fl & 2u) ? (float)hb[i] : y[4 + i];
-        }
+        out.x = fl ? pay.x : out.x;
+        out.y = fl ? pay.y : out.y;
+        return out;
     };
 
-    int nrows = min(kStageRows, row_end - (row_begin + wv * kStageRows));
     Window wk = open_window(a.k, tk, nrows), wvw = open_window(a.v, tv, nrows);
 
     for (int t0 = row_begin; t0 < row_end; t0 += kAttendTile) {
@@ -314,7 +296,10 @@ __global__ __launch_bounds__(kAttThreads) void k_attend_partial(Geometry g, Atte
         reinterpret_cast<uint2 *>(stage_v + kStageWords + 3 * kStageRows)[lane] = wvw.mine;
         wave_lds_sync();
         const uint32_t base_k = wk.base, base_v = wvw.base;
-        const bool ok_k = wk.ok, ok_v = wvw.ok;
+        // a product r_hat * c_i can leave the fp16 range only when the row's scale is within a factor
+        // |c_i| < 2 of the largest half
+        const bool big_k = __any(tk.sg >= kHalfOfMaxHalf) != 0, big_v = __any(tv.sg >= kHalfOfMaxHalf) != 0;
+        const bool fast_k = wk.ok && !big_k, fast_v = wvw.ok && !big_v;
         const bool more = t0 + kAttendTile < row_end;
         const int tgn = t0 + kAttendTile + wv * kStageRows;
         const int nn = more ? min(kStageRows, row_end - tgn) : 0;
@@ -324,60 +309,73 @@ __global__ __launch_bounds__(kAttThreads) void k_attend_partial(Geometry g, Atte
             load_tile(tv, a.v, R0n, nn, w, lane);
         }
 
-        // ---- scores of 4 rows x G heads -------------------------------------------------------------------
-        float pw[G][kSubs];
-        auto scores = [&](auto fast_tag) {
-#pragma unroll
-            for (int sub = 0; sub < kSubs; ++sub) {
-                // the query is re-read from LDS for every row group (an opaque offset keeps the
-                // compiler from parking all 8 G values in registers)
-                int q_off = 8 * cp;
-                asm volatile("" : "+v"(q_off));
-                float y[8];
-                row_values(fast_tag, a.k, stage_k, sec_k, base_k, sub, nrows, y);
-#pragma unroll
-                for (int gq = 0; gq < G; ++gq) {
-                    const float4_t qa = *reinterpret_cast<const float4_t *>(q_l + gq * 128 + q_off);
-                    const float4_t qb = *reinterpret_cast<const float4_t *>(q_l + gq * 128 + q_off + 4);
-                    float s = qa[0] * y[0];
-                    s = fmaf(qa[1], y[1], s);
-                    s = fmaf(qa[2], y[2], s);
-                    s = fmaf(qa[3], y[3], s);
-                    s = fmaf(qb[0], y[4], s);
-                    s = fmaf(qb[1], y[5], s);
-                    s = fmaf(qb[2], y[6], s);
-                    s = fmaf(qb[3], y[7], s);
-                    pw[gq][sub] = row16_sum(s);
-                }
-                // keep the four row groups apart: interleaving them only lengthens live ranges
-                //SB __builtin_amdgcn_sched_barrier(0);
-            }
-        };
+        uint2 p_hi = make_uint2(0u, 0u), p_lo = make_uint2(0u, 0u);
         if (nrows > 0) {
-            if (ok_k)
+            // ---- scores: lane (row n16, j4) supplies chunks 4 m + j4 ------------------------------------
+            float4_t sc = float4_t{0.f, 0.f, 0.f, 0.f};
+            auto scores = [&](auto fast_tag) {
+                const uint32_t word = stage_k[kStageWords + n16];
+                const float sigma =
+                    (float)__builtin_bit_cast(_Float16, (uint16_t)stage_k[kStageWords + kStageRows + n16]);
+                const uint32_t roff = stage_k[kStageWords + 2 * kStageRows + n16];
+                const float sol = sigma * inv_L;
+                const bool valid = n16 < nrows;
+#pragma unroll
+                for (int m = 0; m < 8; ++m) {
+                    const uint2 kh = chunk_half4(fast_tag, a.k, stage_k, sec_k, base_k, n16,
+                                                 (uint32_t)(4 * m + j4), word, roff, sol, valid);
+                    sc = mfma16(kh, qb[m], sc);
+                    if (m & 1)  // two chunks in flight are enough to cover the LDS latency
+                        __builtin_amdgcn_sched_barrier(0);
+                }
+            };
+            if (fast_k)
                 scores(std::true_type{});
             else
                 scores(std::false_type{});
-            // ---- softmax update, one rescale per 4 rows ---------------------------------------------------
+
+            // ---- softmax update: lane (head n16, j4) holds the scores of rows 4 j4 + i --------------------
+            float s4[4];
+            float mx = kNegBig;
 #pragma unroll
-            for (int gq = 0; gq < G; ++gq) {
-                float mn = m[gq];
+            for (int i = 0; i < 4; ++i) {
+                s4[i] = (4 * j4 + i < nrows) ? sc[i] * a.qscale : kNegBig;
+                mx = fmaxf(mx, s4[i]);
+            }
+            mx = fmaxf(mx, __shfl_xor(mx, 16));
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float mn = fmaxf(m_run, mx);
+            if (__any(mn > m_run)) {
+                // some head's maximum rose: rescale.  The accumulators of this lane belong to heads
+                // 4 j4 + i, whose factors live in lanes 4 j4 + i.
+                const float corr = __builtin_amdgcn_exp2f(m_run - mn);
+                l_run *= corr;
 #pragma unroll
-                for (int sub = 0; sub < kSubs; ++sub)
-                    mn = fmaxf(mn, (4 * sub + rsub < nrows) ? pw[gq][sub] : kNegBig);
-                const float corr = __builtin_amdgcn_exp2f(m[gq] - mn);
-                float psum = 0.f;
+                for (int i = 0; i < 4; ++i) {
+                    const float ci = __shfl(corr, 4 * j4 + i);
 #pragma unroll
-                for (int sub = 0; sub < kSubs; ++sub) {
-                    const float e = __builtin_amdgcn_exp2f(pw[gq][sub] - mn);
-                    pw[gq][sub] = (4 * sub + rsub < nrows) ? e : 0.f;
-                    psum += pw[gq][sub];
+                    for (int u = 0; u < 2; ++u)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            acc[u][e][i] *= ci;
                 }
-                l[gq] = l[gq] * corr + psum;
+                m_run = mn;
+            }
+            float pw[4], ph[4];
 #pragma unroll
-                for (int i = 0; i < 8; ++i)
-                    acc[gq][i] *= corr;
-                m[gq] = mn;
+            for (int i = 0; i < 4; ++i) {
+                const float e = __builtin_amdgcn_exp2f(s4[i] - m_run);
+                pw[i] = (4 * j4 + i < nrows) ? e : 0.f;
+                l_run += pw[i];
+            }
+            // P^T as the A operand of the value products, split into an fp16 pair
+            p_hi = make_uint2(pack_half2(pw[0], pw[1]), pack_half2(pw[2], pw[3]));
+            {
+                const half4_t hv = __builtin_bit_cast(half4_t, p_hi);
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    ph[i] = pw[i] - (float)hv[i];
+                p_lo = make_uint2(pack_half2(ph[0], ph[1]), pack_half2(ph[2], ph[3]));
             }
         }
 
@@ -387,22 +385,44 @@ __global__ __launch_bounds__(kAttThreads) void k_attend_partial(Geometry g, Atte
             wvw = open_window(a.v, tv, nn);
         }
 
-        // ---- weighted values ----------------------------------------------------------------------------
-        auto weighted_values = [&](auto fast_tag) {
-#pragma unroll
-            for (int sub = 0; sub < kSubs; ++sub) {
-                float vx[8];
-                row_values(fast_tag, a.v, stage_v, sec_v, base_v, sub, nrows, vx);
-#pragma unroll
-                for (int gq = 0; gq < G; ++gq)
-#pragma unroll
-                    for (int i = 0; i < 8; ++i)
-                        acc[gq][i] = fmaf(pw[gq][sub], vx[i], acc[gq][i]);
-                //SB __builtin_amdgcn_sched_barrier(0);
-            }
-        };
+        // ---- weighted values: lane (n16, j4) supplies chunks n16 and n16 + 16 of rows 4 j4 + i -----------
         if (nrows > 0) {
-            if (ok_v)
+            auto weighted_values = [&](auto fast_tag) {
+                const uint4v word4 = *reinterpret_cast<const uint4v *>(stage_v + kStageWords + 4 * j4);
+                const uint4v sig4 = *reinterpret_cast<const uint4v *>(stage_v + kStageWords + kStageRows + 4 * j4);
+                const uint4v roff4 =
+                    *reinterpret_cast<const uint4v *>(stage_v + kStageWords + 2 * kStageRows + 4 * j4);
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    uint2 vh[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const float sigma = (float)__builtin_bit_cast(_Float16, (uint16_t)sig4[i]);
+                        vh[i] = chunk_half4(fast_tag, a.v, stage_v, sec_v, base_v, 4 * j4 + i,
+                                            (uint32_t)(n16 + 16 * u), word4[i], roff4[i], sigma * inv_L,
+                                            4 * j4 + i < nrows);
+                        if (i & 1)
+                            __builtin_amdgcn_sched_barrier(0);
+                    }
+                    // regroup the 4 x 4 block by component: operand e = (rows 0..3 of component e)
+                    const uint32_t lo_sel = 0x05040100u, hi_sel = 0x07060302u;  // low / high halves of (b, a)
+                    uint2 be[4];
+                    be[0] = make_uint2(__builtin_amdgcn_perm(vh[1].x, vh[0].x, lo_sel),
+                                       __builtin_amdgcn_perm(vh[3].x, vh[2].x, lo_sel));
+                    be[1] = make_uint2(__builtin_amdgcn_perm(vh[1].x, vh[0].x, hi_sel),
+                                       __builtin_amdgcn_perm(vh[3].x, vh[2].x, hi_sel));
+                    be[2] = make_uint2(__builtin_amdgcn_perm(vh[1].y, vh[0].y, lo_sel),
+                                       __builtin_amdgcn_perm(vh[3].y, vh[2].y, lo_sel));
+                    be[3] = make_uint2(__builtin_amdgcn_perm(vh[1].y, vh[0].y, hi_sel),
+                                       __builtin_amdgcn_perm(vh[3].y, vh[2].y, hi_sel));
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        acc[u][e] = mfma16(p_hi, be[e], acc[u][e]);
+                        acc[u][e] = mfma16(p_lo, be[e], acc[u][e]);
+                    }
+                }
+            };
+            if (fast_v)
                 weighted_values(std::true_type{});
             else
                 weighted_values(std::false_type{});
@@ -410,32 +430,25 @@ __global__ __launch_bounds__(kAttThreads) void k_attend_partial(Geometry g, Atte
         nrows = nn;
     }
 
-    // ---- merge: the 4 row groups of a wave (lanes l, l^16, l^32, l^48), then the 4 waves -----------------
-#pragma unroll
-    for (int gq = 0; gq < G; ++gq) {
-#pragma unroll
-        for (int step = 16; step <= 32; step <<= 1) {
-            const float m2 = __shfl_xor(m[gq], step), l2 = __shfl_xor(l[gq], step);
-            float a2[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i)
-                a2[i] = __shfl_xor(acc[gq][i], step);
-            merge_state(m[gq], l[gq], acc[gq], m2, l2, a2);
-        }
-    }
+    // ---- merge: the row groups of a wave (sum of l_run over j4), then the 4 waves -----------------------
+    l_run += __shfl_xor(l_run, 16);
+    l_run += __shfl_xor(l_run, 32);
     __syncthreads();  // every wave is done with its staging area
     float *red = reinterpret_cast<float *>(stage_all);
-    if (rsub == 0) {
+    if (j4 == 0 && n16 < G) {
+        red[(wv * G + n16) * kRedStride + 0] = m_run;
+        red[(wv * G + n16) * kRedStride + 1] = l_run;
+    }
 #pragma unroll
-        for (int gq = 0; gq < G; ++gq) {
-            float *dst = red + (wv * G + gq) * kRedStride;
-            if (cp == 0) {
-                dst[0] = m[gq];
-                dst[1] = l[gq];
+    for (int i = 0; i < 4; ++i) {
+        const int head = 4 * j4 + i;
+        if (head < G) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                float *dst = red + (wv * G + head) * kRedStride + 2 + 64 * u + 4 * n16;
+                *reinterpret_cast<float2 *>(dst) = make_float2(acc[u][0][i], acc[u][1][i]);
+                *reinterpret_cast<float2 *>(dst + 2) = make_float2(acc[u][2][i], acc[u][3][i]);
             }
-#pragma unroll
-            for (int i = 0; i < 8; ++i)
-                dst[2 + 8 * cp + i] = acc[gq][i];
         }
     }
     __syncthreads();
@@ -551,37 +564,21 @@ AttendPlan plan_attend(const Geometry &g, int G)
     return p;
 }
 
-template <bool kPow2, int G>
-static void launch_partial(const Geometry &g, const AttendArgs &a, size_t lds, hipStream_t stream)
-{
-    dim3 grid((unsigned)a.n_splits, (unsigned)(g.B * g.H));
-    hipLaunchKernelGGL((k_attend_partial<kPow2, G>), grid, dim3(kAttThreads), lds, stream, g, a);
-}
-
-template <bool kPow2>
-static bool launch_partial_g(const Geometry &g, const AttendArgs &a, size_t lds, hipStream_t stream)
-{
-    switch (a.G) {
-    case 1: launch_partial<kPow2, 1>(g, a, lds, stream); return true;
-    case 2: launch_partial<kPow2, 2>(g, a, lds, stream); return true;
-    case 3: launch_partial<kPow2, 3>(g, a, lds, stream); return true;
-    case 4: launch_partial<kPow2, 4>(g, a, lds, stream); return true;
-    case 5: launch_partial<kPow2, 5>(g, a, lds, stream); return true;
-    case 6: launch_partial<kPow2, 6>(g, a, lds, stream); return true;
-    case 7: launch_partial<kPow2, 7>(g, a, lds, stream); return true;
-    case 8: launch_partial<kPow2, 8>(g, a, lds, stream); return true;
-    default: return false;
-    }
-}
-
 hipError_t launch_attend(const Geometry &g, const AttendArgs &a, hipStream_t stream)
 {
-    const size_t lds = (size_t)(48 * 4 + a.G * 128 + 8 * g.S) * sizeof(float) +
-                       (size_t)kAttWaves * 2 * kSideWords * sizeof(uint32_t);
-    const bool ok = ((g.S & (g.S - 1)) == 0) ? launch_partial_g<true>(g, a, lds, stream)
-                                             : launch_partial_g<false>(g, a, lds, stream);
-    if (!ok)
+    if (a.G < 1 || a.G > kMaxGroup)
         return hipErrorInvalidValue;
+    // the staging area doubles as the end-of-workgroup merge buffer
+    int stage_floats = kAttWaves * 2 * kSideWords;
+    if (stage_floats < kAttWaves * a.G * kRedStride)
+        stage_floats = kAttWaves * a.G * kRedStride;
+    stage_floats = (stage_floats + 3) / 4 * 4;
+    const size_t lds = (size_t)(48 * 4 + stage_floats + 8 * g.S) * sizeof(float);
+    dim3 grid((unsigned)a.n_splits, (unsigned)(g.B * g.H));
+    if ((g.S & (g.S - 1)) == 0)
+        hipLaunchKernelGGL(k_attend_partial<true>, grid, dim3(kAttThreads), lds, stream, g, a, stage_floats);
+    else
+        hipLaunchKernelGGL(k_attend_partial<false>, grid, dim3(kAttThreads), lds, stream, g, a, stage_floats);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess)
         return err;

@@ -80,7 +80,7 @@ struct DecodeBatch {
 };
 
 // Single-query attention over a packed K and a packed V cache (one query token per sequence).
-constexpr int kMaxGroup = 8;         // query heads sharing one kv head
+constexpr int kMaxGroup = 16;        // query heads sharing one kv head (columns of one matrix-core product)
 constexpr int kAttendTile = 64;      // rows per workgroup iteration (4 waves x 16 rows)
 struct AttendSide {
     const uint32_t *codes;

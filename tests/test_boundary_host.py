@@ -114,13 +114,13 @@ def test_encode_decode_reject_bad_arguments_without_touching_the_gpu(lib):
     wsb = lib.hqmq_attend_workspace_bytes
     need = wsb(C.byref(p), 4 * p.H)
     assert need > 0 and need % 256 == 0
-    assert wsb(C.byref(p), p.H + 1) == 0 and wsb(C.byref(p), 9 * p.H) == 0 and wsb(None, 4) == 0
+    assert wsb(C.byref(p), p.H + 1) == 0 and wsb(C.byref(p), 17 * p.H) == 0 and wsb(None, 4) == 0
     def call(params=p, hq_=4 * p.H, q=0x1000, scale=0.1, ek=good, ev=good, sk=0x1000, sv=0x1000, out=0x2000,
              ws_ptr=0x4000, ws_bytes=need):
         return att(C.byref(params), hq_, q, scale, C.byref(ek), 0, sk, C.byref(ev), 0, sv, out, ws_ptr,
                    ws_bytes, None)
     assert call(hq_=p.H + 1) == -1                    # not a multiple of the kv heads
-    assert call(hq_=9 * p.H) == -2                    # more than 8 query heads per kv head
+    assert call(hq_=17 * p.H) == -2                   # more than 16 query heads per kv head
     assert call(q=None) == -1 and call(out=0x2008) == -1 and call(sv=None) == -1
     assert call(scale=float("nan")) == -1
     assert call(ek=bad) == -1 and call(ev=bad) == -1

@@ -1,13 +1,13 @@
 """GPU parity of hqmq_attend (single-query attention read from the packed K and V caches, paper
-App. F) against the fp64 oracle: the oracle reconstructs K and V from the SAME encoded bytes
-(before fp16 rounding), takes the plain softmax attention in fp64, and the library's fp16 output
-must agree within a tolerance derived from its fp32 arithmetic:
+App. F) against the fp64 oracle: the oracle decodes K and V from the SAME encoded bytes to fp16
+(its own decode), takes the plain softmax attention over them in fp64, and the library's fp16
+output must agree within a tolerance derived from its fp32 arithmetic:
 
   |o_gpu - o| <= 2^-10 |o|  (one fp16 rounding, with slack)  +  ATT_TOL * max|V_hat| of the head
 
-where ATT_TOL = 1e-3 bounds the effect of fp32 rounding in the 128-term score products (an
-absolute score error d changes a softmax weight by a factor 2^d) and in the running sums.  The
-observed error is printed; it sits two orders of magnitude below the bound."""
+where ATT_TOL = 1e-4 covers fp32 rounding in the 128-term score sums (an absolute score error d
+changes a softmax weight by a factor 2^d; |d| <~ 1e-5 for scores of a few tens), the ~2^-22
+relative error of the weights and the fp32 running sums.  The observed error is printed."""
 from __future__ import annotations
 
 import math
@@ -24,7 +24,7 @@ from gpu_util import gpu_encode, upload_encoded
 pytestmark = pytest.mark.gpu
 
 DEV = "cuda:0"
-ATT_TOL = 1e-3
+ATT_TOL = 1e-4
 
 
 def _bits(x: torch.Tensor) -> np.ndarray:
@@ -64,12 +64,16 @@ def _check(got, want64, V64, Hq):
     return rel
 
 
+def _decoded(e, sec_np, B, H, T, b_r):
+    """The oracle's fp16 decode of an encoded tensor, widened to fp64 [B, H, T, 128]."""
+    bits = oracle.decode(e.codes, e.sigma, e.flags, e.row_off, e.outliers, sec_np, B, H, T, b_r)
+    return bits.view(np.float16).astype(np.float64).reshape(B, H, T, 128)
+
+
 def _oracle_attend(enc, sec_np, q, scale, B, H, T, b_r):
     """enc: a pair of objects with codes / sigma / flags / row_off / outliers (numpy)."""
-    K64 = oracle.decode64(enc[0].codes, enc[0].sigma, enc[0].flags, enc[0].row_off, enc[0].outliers,
-                          sec_np[0], B, H, T, b_r)
-    V64 = oracle.decode64(enc[1].codes, enc[1].sigma, enc[1].flags, enc[1].row_off, enc[1].outliers,
-                          sec_np[1], B, H, T, b_r)
+    K64 = _decoded(enc[0], sec_np[0], B, H, T, b_r)
+    V64 = _decoded(enc[1], sec_np[1], B, H, T, b_r)
     _, o64 = oracle.attend(_bits(q), K64, V64, scale)
     return o64, K64, V64
 
@@ -84,6 +88,7 @@ def _tensors(B, H, T, seed, law_sigma=0.7):
     (1, 2, 63, 4, 16, 6),         # ragged tile
     (2, 2, 200, 8, 64, 6),        # 4 query heads per kv head, several tiles
     (1, 1, 1000, 8, 24, 6),       # 8 query heads per kv head, S not a power of two
+    (1, 1, 90, 16, 16, 6),        # 16 per kv head: every column of the product in use
     (1, 3, 129, 9, 256, 4),       # 3 per kv head, one row past a tile
     (1, 2, 777, 14, 48, 8),       # 7 per kv head (the Qwen-2.5-7B grouping)
 ])
@@ -129,8 +134,8 @@ def test_attend_picks_single_rows_including_outlier_rows():
     sec_k, sec_v = _secs(7, H, S)
     ek = oracle.encode(_bits(k), sec_k.numpy(), b_r=b_r)
     ev = oracle.encode(_bits(v), sec_v.numpy(), b_r=b_r)
-    K64 = oracle.decode64(ek.codes, ek.sigma, ek.flags, ek.row_off, ek.outliers, sec_k.numpy(), B, H, T, b_r)
-    V64 = oracle.decode64(ev.codes, ev.sigma, ev.flags, ev.row_off, ev.outliers, sec_v.numpy(), B, H, T, b_r)
+    K64 = _decoded(ek, sec_k.numpy(), B, H, T, b_r)
+    V64 = _decoded(ev, sec_v.numpy(), B, H, T, b_r)
     # a row with a large key norm wins a scaled dot product against its own direction: take the
     # largest of each eighth of the sequence, so the probes fall into different tiles and waves
     norms = np.linalg.norm(K64[0, 0], axis=1)
