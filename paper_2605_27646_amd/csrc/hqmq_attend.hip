@@ -36,7 +36,7 @@ constexpr int kAttWaves = kAttThreads / 64;
 constexpr int kStageRows = 16;                      // rows per wave and tile
 constexpr int kMaxW = 24;                           // w <= 22
 constexpr int kStageWords = kStageRows * kMaxW + 4; // + padding: a 2-word window may start at the last word
-constexpr int kPaySlots = 64;                       // outlier payloads of a wave's 16 rows kept in LDS
+constexpr int kPaySlots = 128;                      // outlier payloads of a wave's 16 rows kept in LDS
 constexpr int kSideWords = kStageWords + 3 * kStageRows + 2 * kPaySlots;  // one side (K or V) of one wave
 constexpr int kLoadsPerLane = (kStageRows * kMaxW + 63) / 64;
 constexpr float kNegBig = -1.0e30f;                 // "no row seen yet" (finite, so differences stay finite)
@@ -123,7 +123,7 @@ __device__ __forceinline__ float4_t mfma16(uint2 a, uint2 b, float4_t c)
 // dynamic LDS: prim [48][4] f32 | max(staging [4 waves][K, V][kSideWords] u32, merge buffer
 //              [4 waves][G][130] f32) | secondaries of K [S][4] f32 | secondaries of V [S][4] f32
 template <bool kPow2>
-__global__ __launch_bounds__(kAttThreads) void k_attend_partial(Geometry g, AttendArgs a, int stage_floats)
+__global__ __launch_bounds__(kAttThreads, 2) void k_attend_partial(Geometry g, AttendArgs a, int stage_floats)
 {
     extern __shared__ float lds[];
     float *prim = lds;
@@ -136,6 +136,7 @@ __global__ __launch_bounds__(kAttThreads) void k_attend_partial(Geometry g, Atte
     const int seg = blockIdx.y, b = seg / g.H, h = seg % g.H;
     const int split = blockIdx.x;
     const int n16 = lane & 15, j4 = lane >> 4;
+    const int n16_ = n16, j4_ = j4;
     const int G = a.G;
     const uint32_t w = g.w, w_idx = g.w_idx;
     const int row_begin = split * a.rows_per_split;
@@ -194,48 +195,71 @@ __global__ __launch_bounds__(kAttThreads) void k_attend_partial(Geometry g, Atte
     const uint32_t code_mask = (1u << w) - 1u, idx_mask = (1u << w_idx) - 1u;
     const float inv_L = g.inv_L;
 
-    // Outlier payloads of a wave's 16 rows: one contiguous window of the list.  Opened from the
-    // tile's registers (offset of the first row, offset + count of the last) half a tile ahead.
+    // Outlier payloads of a wave's 16 rows: one contiguous window of the list, its first 128 entries
+    // copied to LDS (zeros for entries beyond the list's capacity).  The first 64 are requested half
+    // a tile ahead, from the tile's registers (offset of the first row, offset + count of the last);
+    // the next 64 (rare) are copied when the tile is staged; a still larger window (more than a
+    // quarter of the chunks flagged) sends the tile down the careful path, which reads the list.
     struct Window {
-        uint32_t base;
-        bool ok;     // the whole window fits the LDS slots and the list's capacity
-        uint2 mine;  // this lane's entry of the window, on its way to LDS
+        uint32_t base, n;
+        uint2 mine;  // entry `lane` of the window, on its way to LDS
     };
     auto open_window = [&](const AttendSide &s, const TileRegs &t, int nr) {
         Window wd;
         wd.base = 0;
-        wd.ok = true;
+        wd.n = 0;
         wd.mine = make_uint2(0u, 0u);
         if (nr > 0) {
             const int last_row = nr - 1;
             wd.base = (uint32_t)__builtin_amdgcn_readlane((int)t.ro, 0);
             const uint32_t ro_l = (uint32_t)__builtin_amdgcn_readlane((int)t.ro, last_row);
             const uint32_t fw_l = (uint32_t)__builtin_amdgcn_readlane((int)t.fw, last_row);
-            const uint32_t pay_n = ro_l + __popc(fw_l) - wd.base;
-            // unconditional load: lanes past the window (or the list's capacity) re-read a neighbour's
-            // entry; a wave without outliers reads 8 harmless bytes of the offset array
-            const bool has_pay = pay_n > 0 && (uint64_t)wd.base < s.outlier_capacity;
-            const uint64_t last = has_pay ? min((uint64_t)pay_n, s.outlier_capacity - wd.base) - 1u : 0u;
+            wd.n = ro_l + __popc(fw_l) - wd.base;
+            // unconditional load (a conditional one would be waited for on the spot): lanes past the
+            // window or the list's capacity re-read a neighbour's entry; a wave without outliers reads
+            // 8 harmless bytes of the offset array
+            const bool has_pay = wd.n > 0 && (uint64_t)wd.base < s.outlier_capacity;
+            const uint64_t last = has_pay ? min((uint64_t)wd.n, s.outlier_capacity - wd.base) - 1u : 0u;
             const uint2 *src = has_pay ? reinterpret_cast<const uint2 *>(s.outliers) + wd.base
                                        : reinterpret_cast<const uint2 *>(s.row_off);
             wd.mine = src[min((uint64_t)lane, last)];
-            wd.ok = pay_n <= (uint32_t)kPaySlots && (uint64_t)wd.base + pay_n <= s.outlier_capacity;
+            if (!has_pay || (uint64_t)lane > last)
+                wd.mine = make_uint2(0u, 0u);
         }
         return wd;
     };
+    auto stage_window = [&](const AttendSide &s, const Window &wd, uint32_t *stage) {
+        uint2 *st_pay = reinterpret_cast<uint2 *>(stage + kStageWords + 3 * kStageRows);
+        st_pay[lane] = wd.mine;
+        if (wd.n > 64u) {  // wave-uniform and rare: more than 64 outliers in 16 rows
+            for (uint32_t k = 64u + lane; k < min(wd.n, (uint32_t)kPaySlots); k += 64u) {
+                const uint64_t at = (uint64_t)wd.base + k;
+                st_pay[k] = at < s.outlier_capacity ? reinterpret_cast<const uint2 *>(s.outliers)[at]
+                                                    : make_uint2(0u, 0u);
+            }
+        }
+    };
 
-    // One chunk of `row` as the library's decode returns it: four fp16 values (two dwords).
-    // kFast: the wave's whole payload window sits in LDS and no scale of the tile can overflow fp16,
-    // so there is neither a far load nor a clamp.  The choice is made per tile and side.
-    auto chunk_half4 = [&](auto fast_tag, const AttendSide &s, const uint32_t *stage, const float *secl,
-                           uint32_t base, int row, uint32_t c, uint32_t word, uint32_t roff, float sol,
-                           bool row_valid) {
-        constexpr bool kFast = decltype(fast_tag)::value;
+    // One chunk of `row` as the library's decode returns it (four fp16 values, two dwords), in three
+    // steps so that the LDS round trips of neighbouring chunks overlap: the code, then the table
+    // entries and the payload slot it selects, then the arithmetic.
+    // kFast: the wave's whole payload window sits in LDS and no scale of the tile can push a product
+    // beyond the fp16 range, so there is neither a far load nor a clamp.  The choice is made per
+    // tile and side.
+    auto read_code = [&](const uint32_t *stage, int row, uint32_t c) {
         const uint32_t bitpos = c * w;
         const uint32_t *rw = stage + row * w + (bitpos >> 5);
         const uint32_t d0 = rw[0], d1 = rw[1];
-        const uint32_t code = __builtin_amdgcn_alignbit(d1, d0, bitpos & 31u) & code_mask;
-        const uint32_t rq = code >> w_idx;
+        return __builtin_amdgcn_alignbit(d1, d0, bitpos & 31u) & code_mask;
+    };
+    struct Fetched {
+        float4_t P, q;
+        uint2 pay;
+        uint32_t pos;
+    };
+    auto fetch = [&](const uint32_t *stage, const float *secl, uint32_t base, uint32_t code, uint32_t c,
+                     uint32_t word, uint32_t roff) {
+        Fetched f;
         uint32_t p_off, s_off;
         if (kPow2) {
             p_off = ((code >> g.log2_S) & 31u) << 4;
@@ -246,9 +270,19 @@ __global__ __launch_bounds__(kAttThreads) void k_attend_partial(Geometry g, Atte
             p_off = p << 4;
             s_off = (k - __umul24(p, (uint32_t)g.S)) << 4;
         }
-        const float4_t P = *reinterpret_cast<const float4_t *>(reinterpret_cast<const char *>(prim) + p_off);
-        const float4_t q = *reinterpret_cast<const float4_t *>(reinterpret_cast<const char *>(secl) + s_off);
-        const float rh = (float)rq * sol;
+        f.P = *reinterpret_cast<const float4_t *>(reinterpret_cast<const char *>(prim) + p_off);
+        f.q = *reinterpret_cast<const float4_t *>(reinterpret_cast<const char *>(secl) + s_off);
+        // list slot of this chunk if it is flagged (any in-range slot otherwise: the value is unused)
+        f.pos = roff + __popc(word & ((1u << c) - 1u)) - base;
+        const uint2 *st_pay = reinterpret_cast<const uint2 *>(stage + kStageWords + 3 * kStageRows);
+        f.pay = st_pay[min(f.pos, (uint32_t)kPaySlots - 1u)];
+        return f;
+    };
+    auto finish = [&](auto fast_tag, const AttendSide &s, uint32_t base, const Fetched &f, uint32_t code,
+                      uint32_t c, uint32_t word, float sol, bool row_valid) {
+        constexpr bool kFast = decltype(fast_tag)::value;
+        const float rh = (float)(code >> w_idx) * sol;
+        const float4_t P = f.P, q = f.q;
         const float R0 = rh * P[0], R1 = rh * P[1], R2 = rh * P[2], R3 = rh * P[3];
         float y0 = fmaf(-R3, q[3], fmaf(-R2, q[2], fmaf(-R1, q[1], R0 * q[0])));
         float y1 = fmaf(-R3, q[2], fmaf(R2, q[3], fmaf(R1, q[0], R0 * q[1])));
@@ -264,22 +298,18 @@ __global__ __launch_bounds__(kAttThreads) void k_attend_partial(Geometry g, Atte
         uint2 out = make_uint2(pack_half2(y0, y1), pack_half2(y2, y3));
         // flagged: the stored payload replaces the reconstruction
         const bool fl = row_valid && ((word >> c) & 1u);
-        const uint32_t pos = roff + __popc(word & ((1u << c) - 1u)) - base;
-        const uint2 *st_pay = reinterpret_cast<const uint2 *>(stage + kStageWords + 3 * kStageRows);
-        uint2 pay = st_pay[min(pos, (uint32_t)kPaySlots - 1u)];
+        uint2 pay = f.pay;
         if (!kFast) {
-            // still without branches: from memory beyond the LDS slots (unconditional load, index
-            // clamped into the list), zeros beyond the list's capacity
+            // beyond the LDS slots: straight from the list (unconditional load, index clamped into
+            // the list), zeros beyond the list's capacity
             const bool any = s.outlier_capacity > 0;
             const uint2 *src = any ? reinterpret_cast<const uint2 *>(s.outliers)
                                    : reinterpret_cast<const uint2 *>(s.row_off);
             const uint64_t last = any ? s.outlier_capacity - 1u : 0u;
-            const uint64_t at = (uint64_t)base + pos;
+            const uint64_t at = (uint64_t)base + f.pos;
             const uint2 far = src[min(at, last)];
-            if (pos >= (uint32_t)kPaySlots)
-                pay = far;
-            if (at >= s.outlier_capacity)
-                pay = make_uint2(0u, 0u);
+            if (f.pos >= (uint32_t)kPaySlots)
+                pay = at < s.outlier_capacity ? far : make_uint2(0u, 0u);
         }
         out.x = fl ? pay.x : out.x;
         out.y = fl ? pay.y : out.y;
@@ -292,14 +322,14 @@ __global__ __launch_bounds__(kAttThreads) void k_attend_partial(Geometry g, Atte
         // ---- this tile's rows and payload windows into LDS; the next tile's rows requested -----------
         stage_tile(tk, stage_k, lane);
         stage_tile(tv, stage_v, lane);
-        reinterpret_cast<uint2 *>(stage_k + kStageWords + 3 * kStageRows)[lane] = wk.mine;
-        reinterpret_cast<uint2 *>(stage_v + kStageWords + 3 * kStageRows)[lane] = wvw.mine;
+        stage_window(a.k, wk, stage_k);
+        stage_window(a.v, wvw, stage_v);
         wave_lds_sync();
         const uint32_t base_k = wk.base, base_v = wvw.base;
         // a product r_hat * c_i can leave the fp16 range only when the row's scale is within a factor
         // |c_i| < 2 of the largest half
         const bool big_k = __any(tk.sg >= kHalfOfMaxHalf) != 0, big_v = __any(tv.sg >= kHalfOfMaxHalf) != 0;
-        const bool fast_k = wk.ok && !big_k, fast_v = wvw.ok && !big_v;
+        const bool fast_k = !big_k && wk.n <= (uint32_t)kPaySlots, fast_v = !big_v && wvw.n <= (uint32_t)kPaySlots;
         const bool more = t0 + kAttendTile < row_end;
         const int tgn = t0 + kAttendTile + wv * kStageRows;
         const int nn = more ? min(kStageRows, row_end - tgn) : 0;
@@ -314,19 +344,32 @@ __global__ __launch_bounds__(kAttThreads) void k_attend_partial(Geometry g, Atte
             // ---- scores: lane (row n16, j4) supplies chunks 4 m + j4 ------------------------------------
             float4_t sc = float4_t{0.f, 0.f, 0.f, 0.f};
             auto scores = [&](auto fast_tag) {
+                // The careful form is rare: its lane indices are made opaque so that the compiler does
+                // not hoist a second set of per-lane address constants out of the tile loop, which
+                // would cost the common form its registers.
+                int n16 = n16_, j4 = j4_;
+                if (!decltype(fast_tag)::value)
+                    asm volatile("" : "+v"(n16), "+v"(j4));
                 const uint32_t word = stage_k[kStageWords + n16];
                 const float sigma =
                     (float)__builtin_bit_cast(_Float16, (uint16_t)stage_k[kStageWords + kStageRows + n16]);
                 const uint32_t roff = stage_k[kStageWords + 2 * kStageRows + n16];
                 const float sol = sigma * inv_L;
                 const bool valid = n16 < nrows;
+                uint32_t code[8];
+#pragma unroll
+                for (int m = 0; m < 8; ++m)
+                    code[m] = read_code(stage_k, n16, (uint32_t)(4 * m + j4));
+                Fetched cur = fetch(stage_k, sec_k, base_k, code[0], (uint32_t)j4, word, roff);
 #pragma unroll
                 for (int m = 0; m < 8; ++m) {
-                    const uint2 kh = chunk_half4(fast_tag, a.k, stage_k, sec_k, base_k, n16,
-                                                 (uint32_t)(4 * m + j4), word, roff, sol, valid);
+                    Fetched nxt = cur;
+                    if (m + 1 < 8)
+                        nxt = fetch(stage_k, sec_k, base_k, code[m + 1], (uint32_t)(4 * (m + 1) + j4), word, roff);
+                    const uint2 kh = finish(fast_tag, a.k, base_k, cur, code[m], (uint32_t)(4 * m + j4), word, sol, valid);
                     sc = mfma16(kh, qb[m], sc);
-                    if (m & 1)  // two chunks in flight are enough to cover the LDS latency
-                        __builtin_amdgcn_sched_barrier(0);
+                    cur = nxt;
+                    __builtin_amdgcn_sched_barrier(0);  // keep the one-chunk-ahead order
                 }
             };
             if (fast_k)
@@ -388,21 +431,36 @@ __global__ __launch_bounds__(kAttThreads) void k_attend_partial(Geometry g, Atte
         // ---- weighted values: lane (n16, j4) supplies chunks n16 and n16 + 16 of rows 4 j4 + i -----------
         if (nrows > 0) {
             auto weighted_values = [&](auto fast_tag) {
+                int n16 = n16_, j4 = j4_;
+                if (!decltype(fast_tag)::value)
+                    asm volatile("" : "+v"(n16), "+v"(j4));
                 const uint4v word4 = *reinterpret_cast<const uint4v *>(stage_v + kStageWords + 4 * j4);
                 const uint4v sig4 = *reinterpret_cast<const uint4v *>(stage_v + kStageWords + kStageRows + 4 * j4);
                 const uint4v roff4 =
                     *reinterpret_cast<const uint4v *>(stage_v + kStageWords + 2 * kStageRows + 4 * j4);
+                uint32_t code[8];
+                float sol[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    sol[i] = (float)__builtin_bit_cast(_Float16, (uint16_t)sig4[i]) * inv_L;
+                    code[i] = read_code(stage_v, 4 * j4 + i, (uint32_t)n16);
+                    code[4 + i] = read_code(stage_v, 4 * j4 + i, (uint32_t)(n16 + 16));
+                }
+                Fetched cur = fetch(stage_v, sec_v, base_v, code[0], (uint32_t)n16, word4[0], roff4[0]);
 #pragma unroll
                 for (int u = 0; u < 2; ++u) {
                     uint2 vh[4];
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        const float sigma = (float)__builtin_bit_cast(_Float16, (uint16_t)sig4[i]);
-                        vh[i] = chunk_half4(fast_tag, a.v, stage_v, sec_v, base_v, 4 * j4 + i,
-                                            (uint32_t)(n16 + 16 * u), word4[i], roff4[i], sigma * inv_L,
-                                            4 * j4 + i < nrows);
-                        if (i & 1)
-                            __builtin_amdgcn_sched_barrier(0);
+                        const int at = 4 * u + i, nx = at + 1;
+                        Fetched nxt = cur;
+                        if (nx < 8)
+                            nxt = fetch(stage_v, sec_v, base_v, code[nx], (uint32_t)(n16 + 16 * (nx >> 2)),
+                                        word4[nx & 3], roff4[nx & 3]);
+                        vh[i] = finish(fast_tag, a.v, base_v, cur, code[at], (uint32_t)(n16 + 16 * u), word4[i],
+                                       sol[i], 4 * j4 + i < nrows);
+                        cur = nxt;
+                        __builtin_amdgcn_sched_barrier(0);
                     }
                     // regroup the 4 x 4 block by component: operand e = (rows 0..3 of component e)
                     const uint32_t lo_sel = 0x05040100u, hi_sel = 0x07060302u;  // low / high halves of (b, a)

@@ -175,6 +175,72 @@ def test_attend_without_outlier_lists():
     _check(got, want, V64, Hq)
 
 
+def _spiky(B, H, T, seed, rows, big=5.0, small=0.01):
+    """Small Gaussian rows with a band of large rows: every chunk of the band is an outlier."""
+    gen = torch.Generator().manual_seed(seed)
+    x = torch.randn(B, H, T, 128, generator=gen) * small
+    x[:, :, rows[0]:rows[1]] = torch.randn(B, H, rows[1] - rows[0], 128, generator=gen) * big
+    return x.to(torch.float16)
+
+
+def test_attend_windows_larger_than_the_lds_slots():
+    """16-row groups whose outlier window exceeds the slots kept in LDS (here: whole rows flagged)."""
+    B, H, T, Hq, S, b_r = 1, 2, 200, 4, 16, 6
+    k, v = _spiky(B, H, T, 61, (40, 60)), _spiky(B, H, T, 62, (35, 57))
+    sec_k, sec_v = _secs(10, H, S)
+    ek = oracle.encode(_bits(k), sec_k.numpy(), b_r=b_r)
+    ev = oracle.encode(_bits(v), sec_v.numpy(), b_r=b_r)
+    per_row = ek.flag.reshape(B * H, T, -1).sum(-1)
+    assert per_row[:, 40:60].min() == 32 and per_row[0, 32:48].sum() > 128
+    q = _query(B, Hq, seed=63, gain=3.0)
+    want, _, V64 = _oracle_attend((ek, ev), (sec_k.numpy(), sec_v.numpy()), q, 0.3, B, H, T, b_r)
+    params = hq.params_for(k.to(DEV), S, b_r)
+    got = _gpu_attend(params, q, 0.3, upload_encoded(ek, DEV), sec_k.to(DEV), upload_encoded(ev, DEV),
+                      sec_v.to(DEV))
+    _check(got, want, V64, Hq)
+
+
+def test_attend_with_truncated_outlier_lists():
+    """An encode that overflowed its lists: the dropped outliers count as zeros, as in the decode."""
+    B, H, T, Hq, S, b_r = 1, 2, 300, 4, 16, 6
+    k, v = _tensors(B, H, T, seed=71, law_sigma=1.0)
+    sec_k, sec_v = _secs(11, H, S)
+    full_k = gpu_encode(k.to(DEV), sec_k.to(DEV), b_r)
+    full_v = gpu_encode(v.to(DEV), sec_v.to(DEV), b_r)
+    nk, nv = int(full_k.n_out[-1]), int(full_v.n_out[-1])
+    gk = gpu_encode(k.to(DEV), sec_k.to(DEV), b_r, outlier_capacity=nk // 2)
+    gv = gpu_encode(v.to(DEV), sec_v.to(DEV), b_r, outlier_capacity=nv // 3)
+    assert gk.status & hq.HQMQ_STATUS_OUTLIER_OVERFLOW and gv.status & hq.HQMQ_STATUS_OUTLIER_OVERFLOW
+
+    class Padded:                                   # the kept prefix, zeros for what was dropped
+        def __init__(self, g, total):
+            self.codes, self.sigma, self.flags, self.row_off = g.codes, g.sigma, g.flags, g.row_off
+            self.outliers = np.zeros((total, 4), np.uint16)
+            self.outliers[: g.outliers.shape[0]] = g.outliers
+    q = _query(B, Hq, seed=72)
+    want, _, V64 = _oracle_attend((Padded(gk, nk), Padded(gv, nv)), (sec_k.numpy(), sec_v.numpy()), q, 0.09,
+                                  B, H, T, b_r)
+    got = _gpu_attend(gk.params, q, 0.09, gk.bufs, sec_k.to(DEV), gv.bufs, sec_v.to(DEV))
+    _check(got, want, V64, Hq)
+
+
+def test_attend_scales_near_the_fp16_maximum():
+    """Rows whose scale is close to 65504: the tile takes the saturating conversion."""
+    B, H, T, Hq, S, b_r = 1, 1, 100, 2, 16, 6
+    gen = torch.Generator().manual_seed(81)
+    k = (torch.randn(B, H, T, 128, generator=gen) * 12000).clamp(-65504, 65504).to(torch.float16)
+    v = (torch.randn(B, H, T, 128, generator=gen) * 12000).clamp(-65504, 65504).to(torch.float16)
+    sec_k, sec_v = _secs(12, H, S)
+    flags = hq.HQMQ_FLAG_NO_OUTLIERS
+    gk = gpu_encode(k.to(DEV), sec_k.to(DEV), b_r, flags=flags)
+    gv = gpu_encode(v.to(DEV), sec_v.to(DEV), b_r, flags=flags)
+    assert (gk.sigma.view(np.float16).astype(np.float64) >= 32752).any()
+    q = _query(B, Hq, seed=82)
+    want, _, V64 = _oracle_attend((gk, gv), (sec_k.numpy(), sec_v.numpy()), q, 1e-5, B, H, T, b_r)
+    got = _gpu_attend(gk.params, q, 1e-5, gk.bufs, sec_k.to(DEV), gv.bufs, sec_v.to(DEV))
+    _check(got, want, V64, Hq)
+
+
 def test_attend_llama3_8b_32k_layer_full_size():
     """The bench's shape (T = 32768, 8 kv heads, 32 query heads): encoded by the library, every
     output element checked against the oracle's attention over the same bytes."""
