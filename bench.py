@@ -53,6 +53,8 @@ def main() -> int:
     ap.add_argument("--workload", default="llama3_8b_32k")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--q-heads-per-kv", type=int, default=4,
+                    help="query heads per kv head of the fused-attention extra (0 = skip it)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain elementwise copy of one tensor (known bytes) so that a profiler's "
@@ -194,6 +196,39 @@ def main() -> int:
                             "bytes_per_chunk": decode_bytes_per_chunk(info.code_bits, p_out),
                             "avg_launch_ms": decode_ms},
     }
+
+    # ---- extra, outside the timed step: one generation step's attention read from the packed cache
+    # (one hqmq_attend per layer over that layer's encoded K and V) ------------------------------
+    if args.q_heads_per_kv > 0:
+        import math
+        G = args.q_heads_per_kv
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(1234)
+        q = torch.randn(wl.B, wl.H * G, wl.D, device=dev, generator=gen).to(torch.float16)
+        o = torch.empty_like(q)
+        aws = torch.empty(hq.hqmq_attend_workspace_bytes(params, wl.H * G), dtype=torch.uint8, device=dev)
+        scale = 1.0 / math.sqrt(wl.D)
+
+        def attend_all():
+            for l in range(layers):
+                hq.hqmq_attend(params, q, scale, encs[2 * l], sec_all[l, 0], encs[2 * l + 1], sec_all[l, 1], o, aws)
+        attend_all()
+        torch.cuda.synchronize()
+        ea, eb = new_events(2)
+        reps = 5
+        ea.record()
+        for _ in range(reps):
+            attend_all()
+        eb.record()
+        torch.cuda.synchronize()
+        us_layer = ea.elapsed_time(eb) * 1e3 / (reps * layers)
+        packed = 2 * info.n_rows * (4 * info.code_bits + 10) + 8.0 * n_out / layers
+        result["attend"] = {
+            "what": "single-query attention read from the packed K and V of one layer (hqmq_attend)",
+            "q_heads_per_kv_head": G, "us_per_layer": us_layer,
+            "cached_tokens_per_s": wl.B * wl.T / (us_layer * 1e-6),
+            "packed_bytes_per_layer": packed, "packed_GBs": packed / (us_layer * 1e-6) / 1e9,
+            "fp16_cache_bytes_per_layer": 2 * info.n_rows * wl.D * 2}
 
     if args.calibrate_copy:
         # torch's elementwise kernel reads and writes exactly one tensor's bytes

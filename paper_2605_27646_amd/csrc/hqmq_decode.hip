@@ -59,7 +59,9 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(Geometry g, DecodeBatch 
     uint32_t *stage_all = reinterpret_cast<uint32_t *>(prim + 48 * 4);
     float *secl = reinterpret_cast<float *>(stage_all + kDecWaves * kStagePerWave);
 
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, and known to be: row
+    // addresses become scalar bases with per-lane offsets
     const int seg = blockIdx.y, b = seg / g.H, h = seg % g.H;
     const int cp = lane & 15, rsub = lane >> 4;  // chunk pair in the row, row in the group of 4
     const int tg = blockIdx.x * kDecRows + wv * kStageRows;  // first row of this wave

@@ -109,7 +109,8 @@ __global__ __launch_bounds__(kThreads) void k_search(const _Float16 *__restrict_
     uint32_t *pack = reinterpret_cast<uint32_t *>(ubuf + 4 * 64 * 4);
     uint32_t *rcnt = pack + 4 * 2 * 32;
 
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, and known to be
     const int seg = blockIdx.y, b = seg / g.H, h = seg % g.H;
     const int t0 = blockIdx.x * kSearchRows;
     const int64_t row0 = (int64_t)seg * g.T;  // linear index of the segment's first row
