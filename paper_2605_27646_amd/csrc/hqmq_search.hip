@@ -229,23 +229,36 @@ __global__ __launch_bounds__(kThreads) void k_search(const _Float16 *__restrict_
             // max(GA, GH / 2), taken once per group.
             float GA[4] = {0.f, 0.f, 0.f, 0.f}, GH[4] = {0.f, 0.f, 0.f, 0.f};
             const float *arow = amat + (size_t)grp * 4 * 64 + lane;
+            float aop[4];
 #pragma unroll
-            for (int tp = 0; tp < 2; ++tp) {
-                const float aA = arow[(2 * tp) * 64], aB = arow[(2 * tp + 1) * 64];
+            for (int t = 0; t < 4; ++t)
+                aop[t] = arow[t * 64];
+            // 8 pairs of products (secondaries 2 tp, 2 tp + 1 of the group x chunk group j).  The
+            // products of pair k + 1 are issued before the arithmetic on pair k: MFMA and VALU do not
+            // overlap on this SIMD, but a VALU instruction right behind the MFMA it depends on idles
+            // for the depth of the matrix pipeline.
+            float4_t vA = __builtin_amdgcn_mfma_f32_16x16x4f32(aop[0], bop[0], zero4, 0, 0, 0);
+            float4_t vB = __builtin_amdgcn_mfma_f32_16x16x4f32(aop[1], bop[0], zero4, 0, 0, 0);
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const float4_t vA = __builtin_amdgcn_mfma_f32_16x16x4f32(aA, bop[j], zero4, 0, 0, 0);
-                    const float4_t vB = __builtin_amdgcn_mfma_f32_16x16x4f32(aB, bop[j], zero4, 0, 0, 0);
-                    const float a0 = fabsf(vA[0]), a1 = fabsf(vA[1]), a2 = fabsf(vA[2]), a3 = fabsf(vA[3]);
-                    const float b0 = fabsf(vB[0]), b1 = fabsf(vB[1]), b2 = fabsf(vB[2]), b3 = fabsf(vB[3]);
-                    const float hA = ((a0 + a1) + a2) + a3;
-                    const float hB = ((b0 + b1) + b2) + b3;
-                    float ga = fmaxf(fmaxf(GA[j], a0), a1);  // v_max3 each
-                    ga = fmaxf(fmaxf(ga, a2), a3);
-                    ga = fmaxf(fmaxf(ga, b0), b1);
-                    GA[j] = fmaxf(fmaxf(ga, b2), b3);
-                    GH[j] = fmaxf(fmaxf(GH[j], hA), hB);
+            for (int k = 0; k < 8; ++k) {
+                const int j = k & 3;
+                const float4_t cA = vA, cB = vB;
+                if (k + 1 < 8) {
+                    const int tn = (k + 1) >> 2, jn = (k + 1) & 3;
+                    vA = __builtin_amdgcn_mfma_f32_16x16x4f32(aop[2 * tn], bop[jn], zero4, 0, 0, 0);
+                    vB = __builtin_amdgcn_mfma_f32_16x16x4f32(aop[2 * tn + 1], bop[jn], zero4, 0, 0, 0);
                 }
+                __builtin_amdgcn_sched_barrier(0);  // products first, then the arithmetic on the older pair
+                const float a0 = fabsf(cA[0]), a1 = fabsf(cA[1]), a2 = fabsf(cA[2]), a3 = fabsf(cA[3]);
+                const float b0 = fabsf(cB[0]), b1 = fabsf(cB[1]), b2 = fabsf(cB[2]), b3 = fabsf(cB[3]);
+                const float hA = ((a0 + a1) + a2) + a3;
+                const float hB = ((b0 + b1) + b2) + b3;
+                float ga = fmaxf(fmaxf(GA[j], a0), a1);  // v_max3 each
+                ga = fmaxf(fmaxf(ga, a2), a3);
+                ga = fmaxf(fmaxf(ga, b0), b1);
+                GA[j] = fmaxf(fmaxf(ga, b2), b3);
+                GH[j] = fmaxf(fmaxf(GH[j], hA), hB);
+                __builtin_amdgcn_sched_barrier(0);
             }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
