@@ -63,6 +63,19 @@ __device__ __forceinline__ uint16_t double_to_half_rne_sat(double v)
     return out > 0x7bff ? (uint16_t)0x7bff : (uint16_t)out;
 }
 
+template <int kCtrl>
+__device__ __forceinline__ unsigned long long dpp_move64(unsigned long long v)
+{
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)v, kCtrl, 0xf, 0xf, true);
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)(v >> 32), kCtrl, 0xf, 0xf, true);
+    return ((unsigned long long)(uint32_t)hi << 32) | (uint32_t)lo;
+}
+
+__device__ __forceinline__ unsigned long long umax64(unsigned long long a, unsigned long long b)
+{
+    return a > b ? a : b;
+}
+
 __device__ __forceinline__ double half_bits_to_double(uint16_t h)
 {
     return (double)(float)__builtin_bit_cast(_Float16, h);
@@ -167,13 +180,32 @@ __global__ __launch_bounds__(kThreads) void k_search(const _Float16 *__restrict_
         const unsigned long long ballot = __ballot(flagged);
         const uint32_t word = half_id ? (uint32_t)(ballot >> 32) : (uint32_t)ballot;
 
-        double rmax = flagged ? 0.0 : r2;  // max over the 32 lanes of the row
-#pragma unroll
-        for (int d = 16; d >= 1; d >>= 1) {
-            double o = __shfl_xor(rmax, d, 64);
-            rmax = o > rmax ? o : rmax;
+        // max over the 32 lanes of the row: non-negative doubles order like their bit patterns; four
+        // DPP steps inside each 16-lane row (after each step the running maxima are uniform over a
+        // block twice as large, so the mirror patterns pair the right blocks), one swap across rows
+        unsigned long long rbits = flagged ? 0ull : key_of(r2);
+        rbits = umax64(rbits, dpp_move64<0xB1>(rbits));   // quad_perm [1, 0, 3, 2]
+        rbits = umax64(rbits, dpp_move64<0x4E>(rbits));   // quad_perm [2, 3, 0, 1]
+        rbits = umax64(rbits, dpp_move64<0x141>(rbits));  // row_half_mirror
+        rbits = umax64(rbits, dpp_move64<0x140>(rbits));  // row_mirror
+        rbits = umax64(rbits, (unsigned long long)__shfl_xor((long long)rbits, 16, 64));
+        const double rmax = __longlong_as_double((long long)rbits);
+        // sigma = fp16(sqrt(rmax)), round to nearest even, saturating.  The fp32 square root is within
+        // 2 ulp(fp32) of the exact one, so it rounds to the same fp16 value unless it lies within a few
+        // fp32 ulp of a rounding boundary (the 13 dropped bits close to 0x1000) or the result is
+        // subnormal; only then is the fp64 recipe run.
+        uint16_t sigma16 = 0;
+        {
+            const float sf = sqrtf((float)rmax);
+            const uint32_t sb = __float_as_uint(sf);
+            const int dist = (int)(sb & 0x1fffu) - 0x1000;
+            const bool slow = rmax != 0.0 && sf < 65504.f && (sf < 0x1.0p-14f || (dist >= -8 && dist <= 8));
+            sigma16 = sf >= 65504.f ? (uint16_t)0x7bff : __builtin_bit_cast(uint16_t, (_Float16)sf);
+            if (__any(slow)) {
+                if (slow)
+                    sigma16 = double_to_half_rne_sat(sqrt(rmax));
+            }
         }
-        const uint16_t sigma16 = double_to_half_rne_sat(sqrt(rmax));
         const double sigma = half_bits_to_double(sigma16);
 
         // Radius code r_q = clamp(rint(sqrt(r2) * L / sigma), 0, L), defined in fp64.  An fp32
