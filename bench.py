@@ -53,6 +53,11 @@ def main() -> int:
     ap.add_argument("--workload", default="llama3_8b_32k")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--streams", type=int, default=1,
+                    help="HIP streams the per-tensor encodes are spread over (default priority each).  With 3, "
+                         "the HBM-bound median sweeps of one tensor overlap the compute-bound search of another "
+                         "(+8 %% whole-step rate), but kernels of different streams then share the chip and the "
+                         "per-kernel durations behind the roofline figures are no longer those of the kernel alone")
     ap.add_argument("--q-heads-per-kv", type=int, default=4,
                     help="query heads per kv head of the fused-attention extra (0 = skip it)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
@@ -87,7 +92,9 @@ def main() -> int:
         xs.append(x)
         encs.append(hq.alloc_encoded(params, dev))
         outs.append(torch.empty_like(x))
-    ws = hq.alloc_workspace(params, dev)
+    n_streams = max(1, min(args.streams, len(tensors)))
+    enc_streams = [torch.cuda.Stream(device=dev) for _ in range(n_streams)]
+    wss = [hq.alloc_workspace(params, dev) for _ in range(n_streams)]      # one workspace per stream
     info = hq.hqmq_sizes(params)
     n_t = len(tensors)
     torch.cuda.synchronize()
@@ -105,15 +112,29 @@ def main() -> int:
     dec_batch = hq.DecodeBatch(params, encs, [sec_all[l, r] for (l, r) in tensors], outs)
     dec_launches_per_step = (n_t + 31) // 32
 
+    main = torch.cuda.current_stream(dev)
+    join = [torch.cuda.Event() for _ in range(n_streams)]
+    dec_done = torch.cuda.Event()
+    dec_done.record(main)
+
     def run_step(ev_enc=None, ev_dec=None):
+        # encodes: tensor i on stream i mod n (its own workspace); they start after the previous
+        # step's decode, which reads the buffers they overwrite
+        for st in enc_streams:
+            st.wait_event(dec_done)
         for i, (l, r) in enumerate(tensors):
+            k = i % n_streams
             pe = ev_enc[4 * i: 4 * i + 4] if ev_enc is not None else [None] * 4
-            hq.hqmq_encode_timed(params, xs[i], sec_all[l, r], encs[i], ws, pe)
+            hq.hqmq_encode_timed(params, xs[i], sec_all[l, r], encs[i], wss[k], pe, stream=enc_streams[k])
+        for k, st in enumerate(enc_streams):
+            join[k].record(st)
+            main.wait_event(join[k])
         if ev_dec is not None:
-            ev_dec[0].record()
+            ev_dec[0].record(main)
         hq.hqmq_decode_batch(dec_batch)
         if ev_dec is not None:
-            ev_dec[1].record()
+            ev_dec[1].record(main)
+        dec_done.record(main)
 
     for _ in range(args.warmup):
         run_step()
@@ -130,6 +151,8 @@ def main() -> int:
     ms_per_step = wall * 1e3 / args.steps
 
     # ---- per-phase device times from the events ----------------------------------------------
+    # (phases of tensors on different streams overlap: the per-phase figures are averages of the
+    # individual launches, the encode span of a step runs from its first encode to the decode's start)
     t_sel = t_list = t_search = t_enc = t_dec = 0.0
     for k in range(args.steps):
         for i in range(n_t):
@@ -137,7 +160,7 @@ def main() -> int:
             t_sel += e0.elapsed_time(e1)
             t_search += e1.elapsed_time(e2)
             t_list += e2.elapsed_time(e3)
-            t_enc += e0.elapsed_time(e3)
+        t_enc += ev_enc[k][0].elapsed_time(ev_dec[k][0])
         t_dec += ev_dec[k][0].elapsed_time(ev_dec[k][1])
     launches = args.steps * n_t
     search_ms = t_search / launches
@@ -170,7 +193,7 @@ def main() -> int:
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": wl.name, "layers": layers, "B": wl.B, "kv_heads": wl.H, "T": wl.T, "D": wl.D,
-                   "S": wl.S, "b_r": wl.b_r, "C": wl.C, "tensors_per_step": n_t,
+                   "S": wl.S, "b_r": wl.b_r, "C": wl.C, "tensors_per_step": n_t, "encode_streams": n_streams,
                    "elems_per_step": elems_per_step},
         "encode_elems_per_s": elems_per_step / (enc_ms_step * 1e-3),
         "decode_elems_per_s": elems_per_step / (dec_ms_step * 1e-3),
