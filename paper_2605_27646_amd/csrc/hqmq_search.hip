@@ -209,18 +209,19 @@ __global__ __launch_bounds__(kThreads) void k_search(const _Float16 *__restrict_
         const double sigma = half_bits_to_double(sigma16);
 
         // Radius code r_q = clamp(rint(sqrt(r2) * L / sigma), 0, L), defined in fp64.  An fp32
-        // evaluation (relative error < 1e-6, i.e. < 3e-4 absolute at L = 255) rounds the same way
-        // unless it lands within 1e-3 of a rounding boundary; only then is the fp64 recipe run
-        // (about one wave in eight takes that branch).
+        // evaluation with the hardware's 1-ulp square root and reciprocal is off by at most
+        // 6e-7 * L (five roundings of <= 1.2e-7 each); it rounds the same way unless it lands within
+        // that distance of a rounding boundary, and only then is the fp64 recipe run (about one wave
+        // in two hundred at L = 63).
         int rq = 0;
         const float r2f = (float)r2;
-        const float r_f = sqrtf(r2f);
+        const float r_f = __builtin_amdgcn_sqrtf(r2f);
         const float sigma_f = (float)__builtin_bit_cast(_Float16, sigma16);
         bool exact_needed = false;
         if (sigma16 != 0 && r2 != 0.0) {
-            const float qf = fminf(r_f * (float)Lq / sigma_f, (float)Lq);
+            const float qf = fminf(r_f * (float)Lq * __builtin_amdgcn_rcpf(sigma_f), (float)Lq);
             const float fr = qf - floorf(qf);
-            exact_needed = fabsf(fr - 0.5f) < 1e-3f;
+            exact_needed = fabsf(fr - 0.5f) < 6e-7f * (float)Lq + 1e-6f;
             rq = (int)rintf(qf);
         }
         if (__any(exact_needed)) {
@@ -234,7 +235,7 @@ __global__ __launch_bounds__(kThreads) void k_search(const _Float16 *__restrict_
         // ---- unit direction (fp32) and its transpose into MFMA B operands --------------------
         float u0 = 0.f, u1 = 0.f, u2 = 0.f, u3 = 0.f;
         if (r2 != 0.0) {
-            float inv = 1.0f / r_f;
+            const float inv = __builtin_amdgcn_rcpf(r_f);
             u0 = (float)xv[0] * inv;
             u1 = (float)xv[1] * inv;
             u2 = (float)xv[2] * inv;
@@ -311,12 +312,12 @@ __global__ __launch_bounds__(kThreads) void k_search(const _Float16 *__restrict_
             int kj = 16 * bgrp[j] + (lane >> 4);
 #pragma unroll
             for (int d = 16; d <= 32; d <<= 1) {
-                float ob = __shfl_xor(bj, d, 64);
-                int ok = __shfl_xor(kj, d, 64);
-                if (ob > bj || (ob == bj && ok < kj)) {
-                    bj = ob;
-                    kj = ok;
-                }
+                const float ob = __shfl_xor(bj, d, 64);
+                const int ok = __shfl_xor(kj, d, 64);
+                // selects, not branches: the larger score, the lower key on equal scores
+                const bool take = (ob > bj) | ((ob == bj) & (ok < kj));
+                bj = take ? ob : bj;
+                kj = take ? ok : kj;
             }
             int got = __shfl(kj, lane & 15, 64);
             if ((lane >> 4) == j)
@@ -340,11 +341,13 @@ __global__ __launch_bounds__(kThreads) void k_search(const _Float16 *__restrict_
                 const float v3 = fmaf(a, u3, fmaf(bq, u2, fmaf(-cq, u1, -d * u0)));
                 const float a0 = fabsf(v0), a1 = fabsf(v1), a2 = fabsf(v2), a3 = fabsf(v3);
                 const float sc = fmaxf(fmaxf(fmaxf(a0, a1), fmaxf(a2, a3)), 0.5f * (((a0 + a1) + a2) + a3));
-                if (sc_idx < g.S && sc > bsc) {  // strict: the lowest s wins a tie
-                    bsc = sc;
-                    bs = sc_idx;
-                    w0 = v0, w1 = v1, w2 = v2, w3 = v3;
-                }
+                const bool take = (sc_idx < g.S) & (sc > bsc);  // strict: the lowest s wins a tie
+                bsc = take ? sc : bsc;
+                bs = take ? sc_idx : bs;
+                w0 = take ? v0 : w0;
+                w1 = take ? v1 : w1;
+                w2 = take ? v2 : w2;
+                w3 = take ? v3 : w3;
             }
             float sc;
             const int p = nearest_primary(w0, w1, w2, w3, sc);
