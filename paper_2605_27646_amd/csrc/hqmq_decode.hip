@@ -264,8 +264,11 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(Geometry g, DecodeBatch 
                 o.w = v.y;
             }
         }
-        if (r < nrows)
-            *reinterpret_cast<uint4 *>(obase + (int64_t)r * g.st) = o;
+        if (r < nrows) {
+            typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+            const u32x4 ov = {o.x, o.y, o.z, o.w};
+            __builtin_nontemporal_store(ov, reinterpret_cast<u32x4 *>(obase + (int64_t)r * g.st));
+        }
     };
     static_assert(kSubs == 4, "the straight-line code below is written for 4 row groups per wave");
     const Sub s0 = phase1(0), s1 = phase1(1), s2 = phase1(2), s3 = phase1(3);
