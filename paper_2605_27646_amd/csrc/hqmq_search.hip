@@ -63,6 +63,30 @@ __device__ __forceinline__ uint16_t double_to_half_rne_sat(double v)
     return out > 0x7bff ? (uint16_t)0x7bff : (uint16_t)out;
 }
 
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+constexpr float kOperandScale = 1024.f;
+
+// x = h + l + m to 33 bits, each part an fp16
+struct Parts {
+    _Float16 h, l, m;
+};
+__device__ __forceinline__ Parts split3(float x)
+{
+    Parts p;
+    p.h = (_Float16)x;
+    float r = x - (float)p.h;
+    p.l = (_Float16)r;
+    r -= (float)p.l;
+    p.m = (_Float16)r;
+    return p;
+}
+__device__ __forceinline__ uint32_t pack2(_Float16 lo, _Float16 hi)
+{
+    typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+    const half2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, v);
+}
+
 template <int kCtrl>
 __device__ __forceinline__ unsigned long long dpp_move64(unsigned long long v)
 {
@@ -104,21 +128,28 @@ __device__ __forceinline__ int nearest_primary(float v0, float v1, float v2, flo
 
 }  // namespace
 
-// Dynamic LDS layout (floats):
-//   amat  [4*S16][64]   MFMA A operands: lane l of s-block sb holds A[row l%16][k l/16], row 4g+i =
-//                       component i of v for secondary 4 sb + g
-//   secl  [16*S16][4]   the head's secondaries (zero padded to a multiple of 16)
-//   ubuf  [4 waves][64][4]   unit directions of the wave's 64 chunks (for the B operands)
-//   pack  [4 waves][2][32]   row code words being assembled
-//   rcnt  [kSearchRows] outliers per row of the workgroup
+// The K = 4 contraction v = A(q_s) u runs on v_mfma_f32_16x16x32_f16, which issues in half the time
+// of the fp32 shape: every fp32 factor is split into three fp16 parts (h + l + m carries 33 bits; both
+// operands are scaled by 2^10 first so that the small parts stay normal), lane group k of the
+// product holds the parts of its one factor in its 8 slots, A as [h h l l h m l m], B as
+// [h l h l m h m l], and the eight fp16 x fp16 products (exact in fp32) add up to the fp32-accurate
+// a * u inside the matrix core.  The scores come out scaled by 2^20, which no comparison notices.
+//
+// Dynamic LDS layout:
+//   amat  [4*S16][64] x 16 B   MFMA A operands: lane l of s-block sb holds the parts of
+//                              A[row l%16][k l/16], row 4g+i = component i of v for secondary 4 sb + g
+//   secl  [16*S16][4] f32      the head's secondaries (zero padded to a multiple of 16)
+//   ubuf  [4 waves][64][4] x 8 B   parts (h, l, m, 0) of the unit directions of the wave's 64 chunks
+//   pack  [4 waves][2][32] u32 row code words being assembled
+//   rcnt  [kSearchRows] u32    outliers per row of the workgroup
 __global__ __launch_bounds__(kThreads) void k_search(const _Float16 *__restrict__ x,
                                                      const float *__restrict__ sec, Geometry g,
                                                      Workspace ws, EncodedPtrs enc)
 {
     extern __shared__ float smem[];
-    float *amat = smem;
-    float *secl = amat + (size_t)g.S16 * 4 * 64;
-    float *ubuf = secl + (size_t)g.S16 * 16 * 4;
+    uint4 *amat = reinterpret_cast<uint4 *>(smem);
+    float *secl = reinterpret_cast<float *>(amat + (size_t)g.S16 * 4 * 64);
+    uint2 *ubuf = reinterpret_cast<uint2 *>(secl + (size_t)g.S16 * 16 * 4);
     uint32_t *pack = reinterpret_cast<uint32_t *>(ubuf + 4 * 64 * 4);
     uint32_t *rcnt = pack + 4 * 2 * 32;
 
@@ -156,7 +187,8 @@ __global__ __launch_bounds__(kThreads) void k_search(const _Float16 *__restrict_
             val = (k == 0) ? -c : (k == 1) ? d : (k == 2) ? a : -bq;
         else
             val = (k == 0) ? -d : (k == 1) ? -c : (k == 2) ? bq : a;
-        amat[idx] = val;
+        const Parts pa = split3(val * kOperandScale);
+        amat[idx] = make_uint4(pack2(pa.h, pa.h), pack2(pa.l, pa.l), pack2(pa.h, pa.m), pack2(pa.l, pa.m));
     }
 
     __syncthreads();
@@ -164,7 +196,7 @@ __global__ __launch_bounds__(kThreads) void k_search(const _Float16 *__restrict_
     const double thr = ws.thr[h];
     const double Lq = (double)((1 << g.b_r) - 1);
     const int c = lane & 31, half_id = lane >> 5;
-    float *my_ubuf = ubuf + wv * 64 * 4;
+    uint2 *my_ubuf = ubuf + wv * 64 * 4;
     uint32_t *my_pack = pack + wv * 64;
     const _Float16 *base = x + (int64_t)b * g.sb + (int64_t)h * g.sh + 4 * c;
 
@@ -242,13 +274,24 @@ __global__ __launch_bounds__(kThreads) void k_search(const _Float16 *__restrict_
             u3 = (float)xv[3] * inv;
         }
         wave_lds_sync();  // this wave's reads of ubuf / pack from the previous iteration are done
-        *reinterpret_cast<float4_t *>(my_ubuf + 4 * lane) = float4_t{u0, u1, u2, u3};
+        {
+            const Parts p0 = split3(u0 * kOperandScale), p1 = split3(u1 * kOperandScale);
+            const Parts p2 = split3(u2 * kOperandScale), p3 = split3(u3 * kOperandScale);
+            uint4 *dst = reinterpret_cast<uint4 *>(my_ubuf + 4 * lane);
+            dst[0] = make_uint4(pack2(p0.h, p0.l), pack2(p0.m, (_Float16)0.f), pack2(p1.h, p1.l), pack2(p1.m, (_Float16)0.f));
+            dst[1] = make_uint4(pack2(p2.h, p2.l), pack2(p2.m, (_Float16)0.f), pack2(p3.h, p3.l), pack2(p3.m, (_Float16)0.f));
+        }
         my_pack[lane] = 0;
         wave_lds_sync();
-        float bop[4];
+        // B operand of chunk group j: lane (col l % 16, k l / 16) holds the parts of u_k of chunk 16 j + col
+        half8_t bop[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            bop[j] = my_ubuf[4 * (16 * j + (lane & 15)) + (lane >> 4)];
+        for (int j = 0; j < 4; ++j) {
+            const uint2 e = my_ubuf[4 * (16 * j + (lane & 15)) + (lane >> 4)];  // (h, l), (m, 0)
+            const uint32_t mh = __builtin_amdgcn_perm(e.x, e.y, 0x05040100u);   // (m, h)
+            const uint32_t ml = __builtin_amdgcn_perm(e.x, e.y, 0x07060100u);   // (m, l)
+            bop[j] = __builtin_bit_cast(half8_t, make_uint4(e.x, e.x, mh, ml));
+        }
 
         // ---- exhaustive search over the secondaries -------------------------------------------
         // best[j] / bgrp[j]: running maximum of the closed-form score and the group of 16
@@ -261,25 +304,25 @@ __global__ __launch_bounds__(kThreads) void k_search(const _Float16 *__restrict_
             // |v_0|+|v_1|+|v_2|+|v_3| (twice the best half-integer element); the group's score is
             // max(GA, GH / 2), taken once per group.
             float GA[4] = {0.f, 0.f, 0.f, 0.f}, GH[4] = {0.f, 0.f, 0.f, 0.f};
-            const float *arow = amat + (size_t)grp * 4 * 64 + lane;
-            float aop[4];
+            const uint4 *arow = amat + (size_t)grp * 4 * 64 + lane;
+            half8_t aop[4];
 #pragma unroll
             for (int t = 0; t < 4; ++t)
-                aop[t] = arow[t * 64];
+                aop[t] = __builtin_bit_cast(half8_t, arow[t * 64]);
             // 8 pairs of products (secondaries 2 tp, 2 tp + 1 of the group x chunk group j).  The
             // products of pair k + 1 are issued before the arithmetic on pair k: MFMA and VALU do not
             // overlap on this SIMD, but a VALU instruction right behind the MFMA it depends on idles
             // for the depth of the matrix pipeline.
-            float4_t vA = __builtin_amdgcn_mfma_f32_16x16x4f32(aop[0], bop[0], zero4, 0, 0, 0);
-            float4_t vB = __builtin_amdgcn_mfma_f32_16x16x4f32(aop[1], bop[0], zero4, 0, 0, 0);
+            float4_t vA = __builtin_amdgcn_mfma_f32_16x16x32_f16(aop[0], bop[0], zero4, 0, 0, 0);
+            float4_t vB = __builtin_amdgcn_mfma_f32_16x16x32_f16(aop[1], bop[0], zero4, 0, 0, 0);
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
                 const int j = k & 3;
                 const float4_t cA = vA, cB = vB;
                 if (k + 1 < 8) {
                     const int tn = (k + 1) >> 2, jn = (k + 1) & 3;
-                    vA = __builtin_amdgcn_mfma_f32_16x16x4f32(aop[2 * tn], bop[jn], zero4, 0, 0, 0);
-                    vB = __builtin_amdgcn_mfma_f32_16x16x4f32(aop[2 * tn + 1], bop[jn], zero4, 0, 0, 0);
+                    vA = __builtin_amdgcn_mfma_f32_16x16x32_f16(aop[2 * tn], bop[jn], zero4, 0, 0, 0);
+                    vB = __builtin_amdgcn_mfma_f32_16x16x32_f16(aop[2 * tn + 1], bop[jn], zero4, 0, 0, 0);
                 }
                 __builtin_amdgcn_sched_barrier(0);  // products first, then the arithmetic on the older pair
                 const float a0 = fabsf(cA[0]), a1 = fabsf(cA[1]), a2 = fabsf(cA[2]), a3 = fabsf(cA[3]);
@@ -402,8 +445,13 @@ hipError_t launch_search(const _Float16 *x, const float *sec, const Geometry &g,
                          const EncodedPtrs &enc, hipStream_t stream)
 {
     dim3 grid((g.T + kSearchRows - 1) / kSearchRows, g.B * g.H);
-    size_t lds = ((size_t)g.S16 * 4 * 64 + (size_t)g.S16 * 16 * 4 + 4 * 64 * 4) * sizeof(float) +
-                 (4 * 2 * 32 + kSearchRows) * sizeof(uint32_t);
+    const size_t lds = (size_t)g.S16 * 4 * 64 * sizeof(uint4) + (size_t)g.S16 * 16 * 4 * sizeof(float) +
+                       4 * 64 * 4 * sizeof(uint2) + (4 * 2 * 32 + kSearchRows) * sizeof(uint32_t);
+    // more than the 64 KiB a kernel gets by default once S > 208
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(k_search),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (attr != hipSuccess)
+        return attr;
     hipLaunchKernelGGL(k_search, grid, dim3(kThreads), lds, stream, x, sec, g, ws, enc);
     return hipGetLastError();
 }
