@@ -54,11 +54,6 @@ def main() -> int:
     ap.add_argument("--workload", default="llama3_8b_32k")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--streams", type=int, default=1,
-                    help="HIP streams the per-tensor encodes are spread over (default priority each).  With 3, "
-                         "the HBM-bound median sweeps of one tensor overlap the compute-bound search of another "
-                         "(+8 %% whole-step rate), but kernels of different streams then share the chip and the "
-                         "per-kernel durations behind the roofline figures are no longer those of the kernel alone")
     ap.add_argument("--q-heads-per-kv", type=int, default=4,
                     help="query heads per kv head of the fused-attention extra (0 = skip it)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
@@ -93,9 +88,6 @@ def main() -> int:
         xs.append(x)
         encs.append(hq.alloc_encoded(params, dev))
         outs.append(torch.empty_like(x))
-    n_streams = max(1, min(args.streams, len(tensors)))
-    enc_streams = [torch.cuda.Stream(device=dev) for _ in range(n_streams)]
-    wss = [hq.alloc_workspace(params, dev) for _ in range(n_streams)]      # one workspace per stream
     info = hq.hqmq_sizes(params)
     n_t = len(tensors)
     torch.cuda.synchronize()
@@ -113,35 +105,29 @@ def main() -> int:
     dec_batch = hq.DecodeBatch(params, encs, [sec_all[l, r] for (l, r) in tensors], outs)
     dec_launches_per_step = (n_t + 31) // 32
 
-    main = torch.cuda.current_stream(dev)
-    join = [torch.cuda.Event() for _ in range(n_streams)]
-    dec_done = torch.cuda.Event()
-    dec_done.record(main)
+    # encode of the whole cache: batched calls of up to 32 tensors (one launch group each), so that the
+    # phase events bracket single launches
+    GROUP = 32
+    secs = [sec_all[l, r] for (l, r) in tensors]
+    ws = hq.alloc_batch_workspace(params, min(n_t, GROUP), dev)
+    enc_batches = [hq.EncodeBatch(params, xs[i:i + GROUP], secs[i:i + GROUP], encs[i:i + GROUP], ws)
+                   for i in range(0, n_t, GROUP)]
+    n_groups = len(enc_batches)
 
     def run_step(ev_enc=None, ev_dec=None):
-        # encodes: tensor i on stream i mod n (its own workspace); they start after the previous
-        # step's decode, which reads the buffers they overwrite
-        for st in enc_streams:
-            st.wait_event(dec_done)
-        for i, (l, r) in enumerate(tensors):
-            k = i % n_streams
-            pe = ev_enc[4 * i: 4 * i + 4] if ev_enc is not None else [None] * 4
-            hq.hqmq_encode_timed(params, xs[i], sec_all[l, r], encs[i], wss[k], pe, stream=enc_streams[k])
-        for k, st in enumerate(enc_streams):
-            join[k].record(st)
-            main.wait_event(join[k])
+        for gi, eb in enumerate(enc_batches):
+            hq.hqmq_encode_batch(eb, ev_enc[4 * gi: 4 * gi + 4] if ev_enc is not None else None)
         if ev_dec is not None:
-            ev_dec[0].record(main)
+            ev_dec[0].record()
         hq.hqmq_decode_batch(dec_batch)
         if ev_dec is not None:
-            ev_dec[1].record(main)
-        dec_done.record(main)
+            ev_dec[1].record()
 
     for _ in range(args.warmup):
         run_step()
     torch.cuda.synchronize()
 
-    ev_enc = [new_events(4 * n_t) for _ in range(args.steps)]
+    ev_enc = [new_events(4 * n_groups) for _ in range(args.steps)]
     ev_dec = [new_events(2) for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -152,18 +138,17 @@ def main() -> int:
     ms_per_step = wall * 1e3 / args.steps
 
     # ---- per-phase device times from the events ----------------------------------------------
-    # (phases of tensors on different streams overlap: the per-phase figures are averages of the
-    # individual launches, the encode span of a step runs from its first encode to the decode's start)
     t_sel = t_list = t_search = t_enc = t_dec = 0.0
     for k in range(args.steps):
-        for i in range(n_t):
-            e0, e1, e2, e3 = ev_enc[k][4 * i: 4 * i + 4]
+        for gi in range(n_groups):
+            e0, e1, e2, e3 = ev_enc[k][4 * gi: 4 * gi + 4]
             t_sel += e0.elapsed_time(e1)
             t_search += e1.elapsed_time(e2)
             t_list += e2.elapsed_time(e3)
         t_enc += ev_enc[k][0].elapsed_time(ev_dec[k][0])
         t_dec += ev_dec[k][0].elapsed_time(ev_dec[k][1])
-    launches = args.steps * n_t
+    launches = args.steps * n_groups                 # k_search launches in the timed region
+    tensors_per_enc_launch = n_t / n_groups
     search_ms = t_search / launches
     decode_ms = t_dec / (args.steps * dec_launches_per_step)   # average k_decode launch
     tensors_per_dec_launch = n_t / dec_launches_per_step
@@ -176,7 +161,7 @@ def main() -> int:
     status = max(int(e.status.item()) for e in encs)
 
     S16 = (wl.S + 15) // 16
-    flops_launch = search_flops_per_chunk(wl.S) * chunks_per_tensor
+    flops_launch = search_flops_per_chunk(wl.S) * chunks_per_tensor * tensors_per_enc_launch
     search_tflops = flops_launch / (search_ms * 1e-3) / 1e12
     dec_bytes_launch = decode_bytes_per_chunk(info.code_bits, p_out) * chunks_per_tensor * tensors_per_dec_launch
     dec_gbs = dec_bytes_launch / (decode_ms * 1e-3) / 1e9
@@ -195,15 +180,16 @@ def main() -> int:
         "dtype": "f32 (search contraction: fp32 factors as 3-part fp16 splits on the matrix cores, fp32 accumulate)",
         "data": "synthetic",
         "config": {"workload": wl.name, "layers": layers, "B": wl.B, "kv_heads": wl.H, "T": wl.T, "D": wl.D,
-                   "S": wl.S, "b_r": wl.b_r, "C": wl.C, "tensors_per_step": n_t, "encode_streams": n_streams,
+                   "S": wl.S, "b_r": wl.b_r, "C": wl.C, "tensors_per_step": n_t,
                    "elems_per_step": elems_per_step},
         "encode_elems_per_s": elems_per_step / (enc_ms_step * 1e-3),
         "decode_elems_per_s": elems_per_step / (dec_ms_step * 1e-3),
         "encode_ms_per_step": enc_ms_step,
         "decode_ms_per_step": dec_ms_step,
-        "encode_phase_ms_per_tensor": {"median_select": t_sel / launches, "search_quantise_pack": search_ms,
-                                       "outlier_scan_gather": t_list / launches},
-        "codeword_scores_per_s": 24.0 * wl.S * chunks_per_tensor / (search_ms * 1e-3),
+        "encode_phase_ms_per_tensor": {"median_select": t_sel / launches / tensors_per_enc_launch,
+                                       "search_quantise_pack": search_ms / tensors_per_enc_launch,
+                                       "outlier_scan_gather": t_list / launches / tensors_per_enc_launch},
+        "codeword_scores_per_s": 24.0 * wl.S * chunks_per_tensor * tensors_per_enc_launch / (search_ms * 1e-3),
         "outlier_fraction": p_out,
         "status_bits": status,
         "bits_per_element_stored": (encs[0].nbytes() - encs[0].outliers.numel() * 2 + 8 * n_out / n_t) * 8
@@ -214,14 +200,17 @@ def main() -> int:
         # "executed" prices those instructions against their own peak.
         "roofline": {"kernel": "k_search", "bound": "mfma", "achieved": search_tflops, "peak": PEAK_FP32_TFLOPS,
                      "unit": "TFLOP/s", "frac": search_tflops / PEAK_FP32_TFLOPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name, {}).get("k_search"),
+                     "traffic": (MEASURED_TRAFFIC_BYTES[wl.name]["k_search"] * tensors_per_enc_launch
+                                 if wl.name in MEASURED_TRAFFIC_BYTES else None),
+                     "tensors_per_launch": tensors_per_enc_launch,
                      "flops_per_chunk": search_flops_per_chunk(wl.S), "formulation": "W_min (36 S flop/chunk)",
                      "avg_launch_ms": search_ms,
                      "executed": {"instruction": "v_mfma_f32_16x16x32_f16", "flops_per_chunk": 256.0 * S16 * 16,
-                                  "achieved": 256.0 * S16 * 16 * chunks_per_tensor / (search_ms * 1e-3) / 1e12,
+                                  "achieved": 256.0 * S16 * 16 * chunks_per_tensor * tensors_per_enc_launch
+                                  / (search_ms * 1e-3) / 1e12,
                                   "peak": PEAK_F16_TFLOPS, "unit": "TFLOP/s",
-                                  "frac": 256.0 * S16 * 16 * chunks_per_tensor / (search_ms * 1e-3) / 1e12
-                                  / PEAK_F16_TFLOPS}},
+                                  "frac": 256.0 * S16 * 16 * chunks_per_tensor * tensors_per_enc_launch
+                                  / (search_ms * 1e-3) / 1e12 / PEAK_F16_TFLOPS}},
         "roofline_decode": {"kernel": "k_decode", "bound": "hbm", "achieved": dec_gbs, "peak": PEAK_HBM_GBS,
                             "unit": "GB/s", "frac": dec_gbs / PEAK_HBM_GBS,
                             "traffic": (MEASURED_TRAFFIC_BYTES[wl.name]["k_decode"] * tensors_per_dec_launch

@@ -158,6 +158,24 @@ int32_t hqmq_encode_timed(const hqmq_params *params, const void *x_dev, const fl
 int32_t hqmq_decode(const hqmq_params *params, const hqmq_encoded *enc, uint64_t outlier_capacity,
                     const float *sec_dev, void *out_dev, void *stream);
 
+/* Encode n_tensors tensors of ONE shape (the same params: e.g. the K and V of every layer of the
+ * current batch, Alg. 1 applied per (layer, role)) with as few launches as possible: up to 32
+ * tensors share each kernel launch, which removes the launch gaps and small-kernel tails of the
+ * per-tensor sequence.  Semantics per tensor are exactly hqmq_encode's.
+ *   x_dev, sec_dev, enc, outlier_capacity   HOST arrays of n_tensors entries (device pointers /
+ *            structs of device pointers); the tensors must not overlap.
+ *   workspace_dev   DEVICE scratch, 256-byte aligned, min(n_tensors, 32) * workspace_bytes(of
+ *            hqmq_sizes) bytes: one slice per tensor of a launch group.
+ *   phase_events    NULL, or 4 hipEvent_t as in hqmq_encode_timed (entries may be NULL): [0] is
+ *            recorded before the first launch, [1..3] after the select / search / outlier-list
+ *            phase of EVERY group of 32 tensors, so with more than 32 tensors they hold the times
+ *            of the last group; time groups of at most 32 with one call each.
+ * Errors: as hqmq_encode; INVALID_ARG also for n_tensors <= 0 or a null array. */
+int32_t hqmq_encode_batch(const hqmq_params *params, int32_t n_tensors, const void *const *x_dev,
+                          const float *const *sec_dev, const hqmq_encoded *enc,
+                          const uint64_t *outlier_capacity, void *workspace_dev,
+                          uint64_t workspace_bytes, void *stream, void *const *phase_events);
+
 /* Decode n_tensors tensors of ONE shape (the same params: e.g. the K and V caches of every layer)
  * with as few launches as possible: up to 32 tensors share a launch, which keeps the GPU streaming
  * across tensor boundaries (the paper's deployment setting decodes the whole cache, Sec. 4.10

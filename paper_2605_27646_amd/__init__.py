@@ -8,10 +8,12 @@ from .binding import (  # noqa: F401
     HQMQ_FLAG_NO_OUTLIERS,
     HQMQ_STATUS_OUTLIER_OVERFLOW,
     DecodeBatch,
+    EncodeBatch,
     EncodedBuffers,
     HqmqError,
     HqmqParams,
     HqmqSizeInfo,
+    alloc_batch_workspace,
     alloc_encoded,
     alloc_workspace,
     hqmq_attend,
@@ -20,6 +22,7 @@ from .binding import (  # noqa: F401
     hqmq_decode,
     hqmq_decode_batch,
     hqmq_encode,
+    hqmq_encode_batch,
     hqmq_encode_timed,
     hqmq_last_hip_error,
     hqmq_sizes,

@@ -69,6 +69,10 @@ def _load():
                                     C.c_uint64, C.c_void_p, C.c_uint64, C.c_void_p]
         lib.hqmq_encode_timed.restype = C.c_int32
         lib.hqmq_encode_timed.argtypes = lib.hqmq_encode.argtypes + [C.POINTER(C.c_void_p)]
+        lib.hqmq_encode_batch.restype = C.c_int32
+        lib.hqmq_encode_batch.argtypes = [C.POINTER(HqmqParams), C.c_int32, C.POINTER(C.c_void_p),
+                                          C.POINTER(C.c_void_p), C.POINTER(_Encoded), C.POINTER(C.c_uint64),
+                                          C.c_void_p, C.c_uint64, C.c_void_p, C.POINTER(C.c_void_p)]
         lib.hqmq_decode.restype = C.c_int32
         lib.hqmq_decode.argtypes = [C.POINTER(HqmqParams), C.POINTER(_Encoded), C.c_uint64, C.c_void_p,
                                     C.c_void_p, C.c_void_p]
@@ -208,6 +212,52 @@ def hqmq_decode(params: HqmqParams, enc: EncodedBuffers, sec: torch.Tensor, out:
     rc = _load().hqmq_decode(C.byref(params), C.byref(enc.as_struct()), enc.outlier_capacity,
                              sec.data_ptr(), out.data_ptr(), _stream_ptr(stream))
     _check(rc, "hqmq_decode")
+
+
+class EncodeBatch:
+    """Marshalled argument arrays of hqmq_encode_batch, built once and reusable across calls (the
+    tensors' buffers must stay alive and in place).  `workspace` holds min(n, 32) slices of
+    hqmq_sizes().workspace_bytes."""
+
+    def __init__(self, params: HqmqParams, xs, secs, encs, workspace: torch.Tensor):
+        n = len(xs)
+        if not (n == len(secs) == len(encs)) or n == 0:
+            raise ValueError("xs, secs and encs must be non-empty lists of equal length")
+        for x, sec in zip(xs, secs):
+            if x.dtype != torch.float16 or not x.is_cuda or not sec.is_cuda or sec.dtype != torch.float32:
+                raise ValueError("xs must be device fp16 tensors and secs device fp32 tensors")
+            if not sec.is_contiguous() or tuple(sec.shape) != (params.H, params.S, 4):
+                raise ValueError("every sec must be contiguous [H, S, 4]")
+            if (x.stride(0), x.stride(1), x.stride(2)) != (params.stride_b, params.stride_h, params.stride_t) or \
+                    x.stride(3) != 1:
+                raise ValueError("every x must have the strides params holds")
+        if not workspace.is_cuda or not workspace.is_contiguous():
+            raise ValueError("workspace must be a contiguous device tensor")
+        self.params = params
+        self.n = n
+        self.keep = (list(xs), list(secs), list(encs), workspace)
+        self.x = (C.c_void_p * n)(*[t.data_ptr() for t in xs])
+        self.sec = (C.c_void_p * n)(*[t.data_ptr() for t in secs])
+        self.enc = (_Encoded * n)(*[e.as_struct() for e in encs])
+        self.cap = (C.c_uint64 * n)(*[e.outlier_capacity for e in encs])
+        self.workspace = workspace
+
+
+def alloc_batch_workspace(params: HqmqParams, n_tensors: int, device) -> torch.Tensor:
+    per = int(hqmq_sizes(params).workspace_bytes)
+    return torch.empty(per * min(int(n_tensors), 32), dtype=torch.uint8, device=device)
+
+
+def hqmq_encode_batch(batch: EncodeBatch, phase_events=None, stream=None) -> None:
+    """Enqueue the encode of every tensor of the batch (up to 32 per kernel launch).  phase_events:
+    None or four torch.cuda.Event (already recorded once), see hqmq_encode_timed."""
+    handles = None
+    if phase_events is not None:
+        handles = (C.c_void_p * 4)(*[None if e is None else e.cuda_event for e in phase_events])
+    ws = batch.workspace
+    rc = _load().hqmq_encode_batch(C.byref(batch.params), batch.n, batch.x, batch.sec, batch.enc, batch.cap,
+                                   ws.data_ptr(), ws.numel() * ws.element_size(), _stream_ptr(stream), handles)
+    _check(rc, "hqmq_encode_batch")
 
 
 class DecodeBatch:

@@ -172,64 +172,88 @@ extern "C" int32_t hqmq_sizes(const hqmq_params *params, hqmq_size_info *out)
     return HQMQ_OK;
 }
 
-static int32_t encode_impl(const hqmq_params *params, const void *x_dev, const float *sec_dev,
-                           const hqmq_encoded *enc, uint64_t outlier_capacity, void *workspace_dev,
-                           uint64_t workspace_bytes, void *stream, void *const *phase_events)
+static WorkspaceOffsets workspace_offsets(const WorkspaceLayout &l)
+{
+    WorkspaceOffsets o;
+    o.state = (uint32_t)l.state;
+    o.thr = (uint32_t)l.thr;
+    o.hist0 = (uint32_t)l.hist0;
+    o.hist1 = (uint32_t)l.hist1;
+    o.cand_count = (uint32_t)l.cand_count;
+    o.cand = (uint32_t)l.cand;
+    o.block_sum = (uint32_t)l.block_sum;
+    o.block_pre = (uint32_t)l.block_pre;
+    return o;
+}
+
+// Encode n_tensors tensors of one shape: up to kMaxEncodeBatch of them share each kernel launch
+// (select -> search -> outlier list per group); a group's tensor i uses slice i of the workspace.
+static int32_t encode_impl(const hqmq_params *params, int32_t n_tensors, const void *const *x_dev,
+                           const float *const *sec_dev, const hqmq_encoded *enc,
+                           const uint64_t *outlier_capacity, void *workspace_dev, uint64_t workspace_bytes,
+                           void *stream, void *const *phase_events)
 {
     int32_t rc = check_params(params);
     if (rc != HQMQ_OK)
         return rc;
-    if (!x_dev || !sec_dev || !workspace_dev)
+    if (n_tensors <= 0 || !x_dev || !sec_dev || !enc || !outlier_capacity || !workspace_dev)
         return HQMQ_ERR_INVALID_ARG;
-    if (misaligned(x_dev, 16) || misaligned(sec_dev, 16) || misaligned(workspace_dev, 256))
+    if (misaligned(workspace_dev, 256))
         return HQMQ_ERR_INVALID_ARG;
-    rc = check_encoded(enc, true, outlier_capacity);
-    if (rc != HQMQ_OK)
-        return rc;
+    for (int32_t i = 0; i < n_tensors; ++i) {
+        if (!x_dev[i] || !sec_dev[i] || misaligned(x_dev[i], 16) || misaligned(sec_dev[i], 16))
+            return HQMQ_ERR_INVALID_ARG;
+        rc = check_encoded(&enc[i], true, outlier_capacity[i]);
+        if (rc != HQMQ_OK)
+            return rc;
+    }
     const Geometry g = make_geometry(params);
     const WorkspaceLayout l = workspace_layout(g);
-    if (workspace_bytes < l.total)
+    const int group = n_tensors < kMaxEncodeBatch ? n_tensors : kMaxEncodeBatch;
+    if (workspace_bytes < l.total * (uint64_t)group)
         return HQMQ_ERR_BUFFER_TOO_SMALL;
+    if (l.total >= (1ull << 32))
+        return HQMQ_ERR_UNSUPPORTED;  // 32-bit offsets inside a slice
+    const WorkspaceOffsets wo = workspace_offsets(l);
 
-    char *wsb = static_cast<char *>(workspace_dev);
-    Workspace ws;
-    ws.state = reinterpret_cast<SelectState *>(wsb + l.state);
-    ws.thr = reinterpret_cast<double *>(wsb + l.thr);
-    ws.hist0 = reinterpret_cast<uint32_t *>(wsb + l.hist0);
-    ws.hist1 = reinterpret_cast<uint32_t *>(wsb + l.hist1);
-    ws.cand_count = reinterpret_cast<uint32_t *>(wsb + l.cand_count);
-    ws.cand = reinterpret_cast<unsigned long long *>(wsb + l.cand);
-    ws.block_sum = reinterpret_cast<uint32_t *>(wsb + l.block_sum);
-    ws.block_pre = reinterpret_cast<uint32_t *>(wsb + l.block_pre);
-
-    const EncodedPtrs ep = to_ptrs(enc);
-    const _Float16 *x = static_cast<const _Float16 *>(x_dev);
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool no_outliers = (params->flags & HQMQ_FLAG_NO_OUTLIERS) != 0;
-
     auto mark = [&](int i) -> hipError_t {
         if (phase_events && phase_events[i])
             return hipEventRecord(static_cast<hipEvent_t>(phase_events[i]), st);
         return hipSuccess;
     };
-    hipError_t err = mark(0);
-    if (err != hipSuccess)
-        return hip_failed(err);
-    err = launch_select_median(x, g, ws, params->C, no_outliers, ep, st);
-    if (err == hipSuccess)
-        err = mark(1);
-    if (err != hipSuccess)
-        return hip_failed(err);
-    err = launch_search(x, sec_dev, g, ws, ep, st);
-    if (err == hipSuccess)
-        err = mark(2);
-    if (err != hipSuccess)
-        return hip_failed(err);
-    err = launch_outlier_list(x, g, ws, ep, outlier_capacity, st);
-    if (err == hipSuccess)
-        err = mark(3);
-    if (err != hipSuccess)
-        return hip_failed(err);
+    for (int32_t first = 0; first < n_tensors; first += kMaxEncodeBatch) {
+        const int n = (n_tensors - first < kMaxEncodeBatch) ? n_tensors - first : kMaxEncodeBatch;
+        EncodeBatch batch;
+        std::memset(&batch, 0, sizeof(batch));
+        for (int i = 0; i < n; ++i) {
+            EncodeTensor &t = batch.t[i];
+            t.x = static_cast<const _Float16 *>(x_dev[first + i]);
+            t.sec = sec_dev[first + i];
+            t.enc = to_ptrs(&enc[first + i]);
+            t.ws = static_cast<char *>(workspace_dev) + l.total * (uint64_t)i;
+            t.outlier_capacity = outlier_capacity[first + i];
+        }
+        hipError_t err = first == 0 ? mark(0) : hipSuccess;
+        if (err != hipSuccess)
+            return hip_failed(err);
+        err = launch_select_median(g, wo, batch, n, params->C, no_outliers, st);
+        if (err == hipSuccess)
+            err = mark(1);
+        if (err != hipSuccess)
+            return hip_failed(err);
+        err = launch_search(g, wo, batch, n, st);
+        if (err == hipSuccess)
+            err = mark(2);
+        if (err != hipSuccess)
+            return hip_failed(err);
+        err = launch_outlier_list(g, wo, batch, n, st);
+        if (err == hipSuccess)
+            err = mark(3);
+        if (err != hipSuccess)
+            return hip_failed(err);
+    }
     return HQMQ_OK;
 }
 
@@ -237,7 +261,7 @@ extern "C" int32_t hqmq_encode(const hqmq_params *params, const void *x_dev, con
                                const hqmq_encoded *enc, uint64_t outlier_capacity,
                                void *workspace_dev, uint64_t workspace_bytes, void *stream)
 {
-    return encode_impl(params, x_dev, sec_dev, enc, outlier_capacity, workspace_dev, workspace_bytes,
+    return encode_impl(params, 1, &x_dev, &sec_dev, enc, &outlier_capacity, workspace_dev, workspace_bytes,
                        stream, nullptr);
 }
 
@@ -246,7 +270,16 @@ extern "C" int32_t hqmq_encode_timed(const hqmq_params *params, const void *x_de
                                      uint64_t outlier_capacity, void *workspace_dev,
                                      uint64_t workspace_bytes, void *stream, void *const *phase_events)
 {
-    return encode_impl(params, x_dev, sec_dev, enc, outlier_capacity, workspace_dev, workspace_bytes,
+    return encode_impl(params, 1, &x_dev, &sec_dev, enc, &outlier_capacity, workspace_dev, workspace_bytes,
+                       stream, phase_events);
+}
+
+extern "C" int32_t hqmq_encode_batch(const hqmq_params *params, int32_t n_tensors, const void *const *x_dev,
+                                     const float *const *sec_dev, const hqmq_encoded *enc,
+                                     const uint64_t *outlier_capacity, void *workspace_dev,
+                                     uint64_t workspace_bytes, void *stream, void *const *phase_events)
+{
+    return encode_impl(params, n_tensors, x_dev, sec_dev, enc, outlier_capacity, workspace_dev, workspace_bytes,
                        stream, phase_events);
 }
 

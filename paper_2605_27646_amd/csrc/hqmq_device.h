@@ -63,6 +63,39 @@ struct EncodedPtrs {
     uint32_t *status;
 };
 
+// Byte offsets of the workspace parts inside one tensor's slice (same for every tensor of a shape).
+struct WorkspaceOffsets {
+    uint32_t state, thr, hist0, hist1, cand_count, cand, block_sum, block_pre;
+};
+
+// One tensor of an encode batch and the batch itself (passed by value as kernel arguments; every
+// encode kernel takes blockIdx.z as the tensor index).
+struct EncodeTensor {
+    const _Float16 *x;
+    const float *sec;
+    EncodedPtrs enc;
+    char *ws;                  // this tensor's slice of the workspace
+    uint64_t outlier_capacity;
+};
+constexpr int kMaxEncodeBatch = 32;  // 32 * 88 B of descriptors stay inside the 4 KiB of kernel arguments
+struct EncodeBatch {
+    EncodeTensor t[kMaxEncodeBatch];
+};
+
+__device__ __forceinline__ Workspace carve_workspace(char *base, const WorkspaceOffsets &o)
+{
+    Workspace ws;
+    ws.state = reinterpret_cast<SelectState *>(base + o.state);
+    ws.thr = reinterpret_cast<double *>(base + o.thr);
+    ws.hist0 = reinterpret_cast<uint32_t *>(base + o.hist0);
+    ws.hist1 = reinterpret_cast<uint32_t *>(base + o.hist1);
+    ws.cand_count = reinterpret_cast<uint32_t *>(base + o.cand_count);
+    ws.cand = reinterpret_cast<unsigned long long *>(base + o.cand);
+    ws.block_sum = reinterpret_cast<uint32_t *>(base + o.block_sum);
+    ws.block_pre = reinterpret_cast<uint32_t *>(base + o.block_pre);
+    return ws;
+}
+
 // One tensor of a decode batch and the batch itself (passed by value as kernel arguments).
 struct DecodeTensor {
     uint32_t *codes;
@@ -135,12 +168,12 @@ __device__ __forceinline__ unsigned long long key_of(double r2)
 }
 
 // Launchers implemented in the kernel translation units (host side).
-hipError_t launch_select_median(const _Float16 *x, const Geometry &g, const Workspace &ws, float C,
-                                bool no_outliers, const EncodedPtrs &enc, hipStream_t stream);
-hipError_t launch_search(const _Float16 *x, const float *sec, const Geometry &g, const Workspace &ws,
-                         const EncodedPtrs &enc, hipStream_t stream);
-hipError_t launch_outlier_list(const _Float16 *x, const Geometry &g, const Workspace &ws,
-                               const EncodedPtrs &enc, uint64_t outlier_capacity, hipStream_t stream);
+hipError_t launch_select_median(const Geometry &g, const WorkspaceOffsets &wo, const EncodeBatch &batch, int n_tensors,
+                                float C, bool no_outliers, hipStream_t stream);
+hipError_t launch_search(const Geometry &g, const WorkspaceOffsets &wo, const EncodeBatch &batch, int n_tensors,
+                         hipStream_t stream);
+hipError_t launch_outlier_list(const Geometry &g, const WorkspaceOffsets &wo, const EncodeBatch &batch, int n_tensors,
+                               hipStream_t stream);
 hipError_t launch_decode(const Geometry &g, const DecodeBatch &batch, int n_tensors, hipStream_t stream);
 hipError_t launch_attend(const Geometry &g, const AttendArgs &args, hipStream_t stream);
 

@@ -81,8 +81,11 @@ __device__ __forceinline__ void pick_bin(const uint32_t *hist, uint32_t rank, ui
 // ---------------------------------------------------------------------------------------
 // reset of the per-call scratch state
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void k_init(Geometry g, Workspace ws, EncodedPtrs enc)
+__global__ __launch_bounds__(kThreads) void k_init(Geometry g, WorkspaceOffsets wo, EncodeBatch batch)
 {
+    const EncodeTensor &tn = batch.t[blockIdx.z];
+    const Workspace ws = carve_workspace(tn.ws, wo);
+    const EncodedPtrs enc = tn.enc;
     const uint32_t i = blockIdx.x * kThreads + threadIdx.x;
     if (i < (uint32_t)g.H * kBins0)
         ws.hist0[i] = 0;
@@ -105,9 +108,11 @@ __global__ __launch_bounds__(kThreads) void k_init(Geometry g, Workspace ws, Enc
 //   MODE 2: pick digits 0 and 1, append the keys of the chosen bucket to the candidate list
 // ---------------------------------------------------------------------------------------
 template <int MODE>
-__global__ __launch_bounds__(kSelectThreads) void k_select_sweep(const _Float16 *__restrict__ x, Geometry g,
-                                                                 Workspace ws)
+__global__ __launch_bounds__(kSelectThreads) void k_select_sweep(Geometry g, WorkspaceOffsets wo, EncodeBatch batch)
 {
+    const EncodeTensor &tn = batch.t[blockIdx.z];
+    const Workspace ws = carve_workspace(tn.ws, wo);
+    const _Float16 *__restrict__ x = tn.x;
     constexpr int kLdsBins = MODE == 0 ? kBins0 : kBins1;
     __shared__ uint32_t lh[MODE == 2 ? 1 : kLdsBins];
     __shared__ uint32_t scratch[kSelectThreads + 2];
@@ -190,9 +195,12 @@ __global__ __launch_bounds__(kSelectThreads) void k_select_sweep(const _Float16 
 // among the keys whose top 23 bits equal the chosen prefix: from the candidate list when it holds
 // them all, otherwise from the head's raw rows.  Writes thr[h] = fl(fl(C*C) * median).
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kSelectThreads) void k_select_finish(const _Float16 *__restrict__ x, Geometry g,
-                                                                  Workspace ws, float C)
+__global__ __launch_bounds__(kSelectThreads) void k_select_finish(Geometry g, WorkspaceOffsets wo, EncodeBatch batch,
+                                                                  float C)
 {
+    const EncodeTensor &tn = batch.t[blockIdx.z];
+    const Workspace ws = carve_workspace(tn.ws, wo);
+    const _Float16 *__restrict__ x = tn.x;
     __shared__ uint32_t lh[kBins1];
     __shared__ uint32_t scratch[kSelectThreads + 2];
     const int h = blockIdx.x;
@@ -251,10 +259,13 @@ __global__ __launch_bounds__(kSelectThreads) void k_select_finish(const _Float16
 //   k_gather  adds the workgroup prefix to every row offset and copies the flagged chunks into
 //             the outlier list in ascending linear chunk order
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(1024) void k_scan(Geometry g, Workspace ws, EncodedPtrs enc,
-                                               uint32_t n_blocks, uint64_t n_rows,
-                                               uint64_t outlier_capacity)
+__global__ __launch_bounds__(1024) void k_scan(Geometry g, WorkspaceOffsets wo, EncodeBatch batch,
+                                               uint32_t n_blocks, uint64_t n_rows)
 {
+    const EncodeTensor &tn = batch.t[blockIdx.z];
+    const Workspace ws = carve_workspace(tn.ws, wo);
+    const EncodedPtrs enc = tn.enc;
+    const uint64_t outlier_capacity = tn.outlier_capacity;
     __shared__ uint32_t wave_tot[16];
     __shared__ uint32_t carry_s;
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
@@ -311,10 +322,13 @@ __global__ __launch_bounds__(1024) void k_scan(Geometry g, Workspace ws, Encoded
 }
 
 // grid = (ceil(T / 256), B*H), one thread per row
-__global__ __launch_bounds__(kThreads) void k_gather(const _Float16 *__restrict__ x, Geometry g,
-                                                     Workspace ws, EncodedPtrs enc,
-                                                     uint64_t outlier_capacity)
+__global__ __launch_bounds__(kThreads) void k_gather(Geometry g, WorkspaceOffsets wo, EncodeBatch batch)
 {
+    const EncodeTensor &tn = batch.t[blockIdx.z];
+    const Workspace ws = carve_workspace(tn.ws, wo);
+    const EncodedPtrs enc = tn.enc;
+    const uint64_t outlier_capacity = tn.outlier_capacity;
+    const _Float16 *__restrict__ x = tn.x;
     const int seg = blockIdx.y, b = seg / g.H, h = seg % g.H;
     const int t = blockIdx.x * kThreads + threadIdx.x;
     if (t >= g.T)
@@ -339,29 +353,31 @@ __global__ __launch_bounds__(kThreads) void k_gather(const _Float16 *__restrict_
 // ---------------------------------------------------------------------------------------
 // host-side launch sequences
 // ---------------------------------------------------------------------------------------
-hipError_t launch_select_median(const _Float16 *x, const Geometry &g, const Workspace &ws, float C,
-                                bool no_outliers, const EncodedPtrs &enc, hipStream_t stream)
+hipError_t launch_select_median(const Geometry &g, const WorkspaceOffsets &wo, const EncodeBatch &batch, int n_tensors,
+                                float C, bool no_outliers, hipStream_t stream)
 {
+    const unsigned n = (unsigned)n_tensors;
     uint32_t n_init = (uint32_t)g.H * kBins0;
-    hipLaunchKernelGGL(k_init, dim3((n_init + kThreads - 1) / kThreads), dim3(kThreads), 0, stream, g, ws, enc);
+    hipLaunchKernelGGL(k_init, dim3((n_init + kThreads - 1) / kThreads, 1, n), dim3(kThreads), 0, stream, g, wo, batch);
     if (!no_outliers) {
-        dim3 grid((g.T + kSelectRows - 1) / kSelectRows, g.B * g.H);
-        hipLaunchKernelGGL(k_select_sweep<0>, grid, dim3(kSelectThreads), 0, stream, x, g, ws);
-        hipLaunchKernelGGL(k_select_sweep<1>, grid, dim3(kSelectThreads), 0, stream, x, g, ws);
-        hipLaunchKernelGGL(k_select_sweep<2>, grid, dim3(kSelectThreads), 0, stream, x, g, ws);
-        hipLaunchKernelGGL(k_select_finish, dim3(g.H), dim3(kSelectThreads), 0, stream, x, g, ws, C);
+        dim3 grid((g.T + kSelectRows - 1) / kSelectRows, g.B * g.H, n);
+        hipLaunchKernelGGL(k_select_sweep<0>, grid, dim3(kSelectThreads), 0, stream, g, wo, batch);
+        hipLaunchKernelGGL(k_select_sweep<1>, grid, dim3(kSelectThreads), 0, stream, g, wo, batch);
+        hipLaunchKernelGGL(k_select_sweep<2>, grid, dim3(kSelectThreads), 0, stream, g, wo, batch);
+        hipLaunchKernelGGL(k_select_finish, dim3(g.H, 1, n), dim3(kSelectThreads), 0, stream, g, wo, batch, C);
     }
     return hipGetLastError();
 }
 
-hipError_t launch_outlier_list(const _Float16 *x, const Geometry &g, const Workspace &ws,
-                               const EncodedPtrs &enc, uint64_t outlier_capacity, hipStream_t stream)
+hipError_t launch_outlier_list(const Geometry &g, const WorkspaceOffsets &wo, const EncodeBatch &batch, int n_tensors,
+                               hipStream_t stream)
 {
+    const unsigned n = (unsigned)n_tensors;
     const uint32_t n_blocks = (uint32_t)g.B * g.H * g.n_search_blocks_per_seg;
     const uint64_t n_rows = (uint64_t)g.B * g.H * g.T;
-    hipLaunchKernelGGL(k_scan, dim3(1), dim3(1024), 0, stream, g, ws, enc, n_blocks, n_rows, outlier_capacity);
-    dim3 grid((g.T + kThreads - 1) / kThreads, g.B * g.H);
-    hipLaunchKernelGGL(k_gather, grid, dim3(kThreads), 0, stream, x, g, ws, enc, outlier_capacity);
+    hipLaunchKernelGGL(k_scan, dim3(1, 1, n), dim3(1024), 0, stream, g, wo, batch, n_blocks, n_rows);
+    dim3 grid((g.T + kThreads - 1) / kThreads, g.B * g.H, n);
+    hipLaunchKernelGGL(k_gather, grid, dim3(kThreads), 0, stream, g, wo, batch);
     return hipGetLastError();
 }
 

@@ -142,10 +142,13 @@ __device__ __forceinline__ int nearest_primary(float v0, float v1, float v2, flo
 //   ubuf  [4 waves][64][4] x 8 B   parts (h, l, m, 0) of the unit directions of the wave's 64 chunks
 //   pack  [4 waves][2][32] u32 row code words being assembled
 //   rcnt  [kSearchRows] u32    outliers per row of the workgroup
-__global__ __launch_bounds__(kThreads) void k_search(const _Float16 *__restrict__ x,
-                                                     const float *__restrict__ sec, Geometry g,
-                                                     Workspace ws, EncodedPtrs enc)
+__global__ __launch_bounds__(kThreads) void k_search(Geometry g, WorkspaceOffsets wo, EncodeBatch batch)
 {
+    const EncodeTensor &tn = batch.t[blockIdx.z];
+    const Workspace ws = carve_workspace(tn.ws, wo);
+    const EncodedPtrs enc = tn.enc;
+    const _Float16 *__restrict__ x = tn.x;
+    const float *__restrict__ sec = tn.sec;
     extern __shared__ float smem[];
     uint4 *amat = reinterpret_cast<uint4 *>(smem);
     float *secl = reinterpret_cast<float *>(amat + (size_t)g.S16 * 4 * 64);
@@ -441,10 +444,10 @@ __global__ __launch_bounds__(kThreads) void k_search(const _Float16 *__restrict_
     }
 }
 
-hipError_t launch_search(const _Float16 *x, const float *sec, const Geometry &g, const Workspace &ws,
-                         const EncodedPtrs &enc, hipStream_t stream)
+hipError_t launch_search(const Geometry &g, const WorkspaceOffsets &wo, const EncodeBatch &batch, int n_tensors,
+                         hipStream_t stream)
 {
-    dim3 grid((g.T + kSearchRows - 1) / kSearchRows, g.B * g.H);
+    dim3 grid((g.T + kSearchRows - 1) / kSearchRows, g.B * g.H, (unsigned)n_tensors);
     const size_t lds = (size_t)g.S16 * 4 * 64 * sizeof(uint4) + (size_t)g.S16 * 16 * 4 * sizeof(float) +
                        4 * 64 * 4 * sizeof(uint2) + (4 * 2 * 32 + kSearchRows) * sizeof(uint32_t);
     // more than the 64 KiB a kernel gets by default once S > 208
@@ -452,7 +455,7 @@ hipError_t launch_search(const _Float16 *x, const float *sec, const Geometry &g,
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (attr != hipSuccess)
         return attr;
-    hipLaunchKernelGGL(k_search, grid, dim3(kThreads), lds, stream, x, sec, g, ws, enc);
+    hipLaunchKernelGGL(k_search, grid, dim3(kThreads), lds, stream, g, wo, batch);
     return hipGetLastError();
 }
 

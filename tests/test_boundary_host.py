@@ -27,7 +27,7 @@ def lib():
 def test_library_exports_every_declared_symbol(lib):
     header = open(os.path.join(ROOT, "include", "hqmq.h")).read()
     declared = set(re.findall(r"^(?:int32_t|void|uint64_t)\s+(hqmq_\w+)\s*\(", header, re.M))
-    assert declared == {"hqmq_build_codebooks", "hqmq_sizes", "hqmq_encode", "hqmq_encode_timed", "hqmq_decode", "hqmq_decode_batch", "hqmq_attend", "hqmq_attend_workspace_bytes", "hqmq_last_hip_error"}
+    assert declared == {"hqmq_build_codebooks", "hqmq_sizes", "hqmq_encode", "hqmq_encode_timed", "hqmq_encode_batch", "hqmq_decode", "hqmq_decode_batch", "hqmq_attend", "hqmq_attend_workspace_bytes", "hqmq_last_hip_error"}
     for name in declared:
         assert hasattr(lib, name), name
 
@@ -110,6 +110,13 @@ def test_encode_decode_reject_bad_arguments_without_touching_the_gpu(lib):
     assert db(C.byref(p), 2, encs, None, ptrs, ptrs, None) == -1
     assert db(C.byref(p), 2, encs, caps, ptrs, bad_ptrs, None) == -1                          # second out misaligned
     assert db(C.byref(_params(b_r=0)), 2, encs, caps, ptrs, ptrs, None) == -2
+    eb = lib.hqmq_encode_batch
+    ws2 = 2 * ws
+    assert eb(C.byref(p), 0, ptrs, ptrs, encs, caps, 0x1000, ws2, None, None) == -1                # empty batch
+    assert eb(C.byref(p), 2, None, ptrs, encs, caps, 0x1000, ws2, None, None) == -1
+    assert eb(C.byref(p), 2, ptrs, bad_ptrs, encs, caps, 0x1000, ws2, None, None) == -1            # second sec misaligned
+    assert eb(C.byref(p), 2, ptrs, ptrs, encs, caps, 0x1000, ws2 - 1, None, None) == -3            # one slice per tensor
+    assert eb(C.byref(p), 2, ptrs, ptrs, encs, caps, 0x1010, ws2, None, None) == -1                # workspace alignment
     att = lib.hqmq_attend
     wsb = lib.hqmq_attend_workspace_bytes
     need = wsb(C.byref(p), 4 * p.H)

@@ -275,6 +275,38 @@ def test_decode_batch_equals_single_decodes():
         assert np.array_equal(outs[i].cpu().numpy().view(np.uint16), singles[i]), i
 
 
+def test_encode_batch_equals_single_encodes():
+    """One launch group for many tensors of a shape must give each tensor exactly hqmq_encode's bytes
+    (40 tensors: two groups; the second re-uses the workspace slices of the first)."""
+    B, H, T, S = 2, 2, 131, 16
+    n = 40
+    cb = hq.hqmq_build_codebooks(4, n, H, S)
+    xs, secs, singles = [], [], []
+    for i in range(n):
+        x = _lognormal_tensor(B, H, T, seed=300 + i, sigma_g=0.4 + 0.02 * i).to(DEV)
+        sec = cb[i, i % 2].contiguous().to(DEV)
+        xs.append(x)
+        secs.append(sec)
+        singles.append(gpu_encode(x, sec))
+    params = hq.params_for(xs[0], S)
+    encs = [hq.alloc_encoded(params, DEV) for _ in range(n)]
+    for e in encs:
+        e.codes.fill_(-1)
+    ws = hq.alloc_batch_workspace(params, n, DEV)
+    ws.fill_(0xAB)
+    hq.hqmq_encode_batch(hq.EncodeBatch(params, xs, secs, encs, ws))
+    torch.cuda.synchronize()
+    for i in range(n):
+        g = singles[i]
+        total = int(g.n_out[-1])
+        assert total > 0
+        assert torch.equal(encs[i].codes, g.bufs.codes), i
+        assert torch.equal(encs[i].sigma.view(torch.int16), g.bufs.sigma.view(torch.int16)), i
+        assert torch.equal(encs[i].flags, g.bufs.flags) and torch.equal(encs[i].row_off, g.bufs.row_off), i
+        assert torch.equal(encs[i].n_outliers, g.bufs.n_outliers) and int(encs[i].status[0]) == 0, i
+        assert torch.equal(encs[i].outliers[:total].view(torch.int16), g.bufs.outliers[:total].view(torch.int16)), i
+
+
 def test_deterministic_bytes():
     x = _lognormal_tensor(1, 4, 300, seed=15).to(DEV)
     sec_t, _ = _sec(0, 4, 64)
