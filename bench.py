@@ -29,7 +29,7 @@ PEAK_HBM_GBS = 8000.0        # MI355X HBM3E peak
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs, each scaled
 # by a plain copy of known size in the same run); figures and commands in profiles/hbm_traffic_*.txt
-MEASURED_TRAFFIC_BYTES = {"llama3_8b_32k": {"k_search": 90.2e6, "k_decode": 91.5e6}}
+MEASURED_TRAFFIC_BYTES = {"llama3_8b_32k": {"k_search": 90.1e6, "k_decode": 91.4e6}}
 
 
 def search_flops_per_chunk(S: int) -> float:
