@@ -350,24 +350,31 @@ __global__ __launch_bounds__(kThreads) void k_search(Geometry g, WorkspaceOffset
         }
 
         // ---- reduce over the 4 lanes that share a chunk, hand the winner to the owner lane ------
-        // key = 16 grp + lane/16: the first of the 4 candidates s = key + 4 t of the winning lane
-        int key_mine = 0;
+        // key = 16 grp + lane/16: the first of the 4 candidates s = key + 4 t of the winning lane.
+        // Chunk 16 j + col was scored by lanes col, col + 16, col + 32, col + 48 (slot j of each) and
+        // is owned by lane 16 j + col: the (score, key) pairs go through LDS (the operand buffer is
+        // free by now), the owner reads its four and keeps the larger score, the lower key on equal ones.
+        int key_mine;
+        {
+            uint2 *red = my_ubuf;  // [4 slots][64 lanes]
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            float bj = best[j];
-            int kj = 16 * bgrp[j] + (lane >> 4);
+            for (int j = 0; j < 4; ++j)
+                red[j * 64 + lane] = make_uint2(__float_as_uint(best[j]), (uint32_t)(16 * bgrp[j] + (lane >> 4)));
+            wave_lds_sync();
+            const uint2 *mine = red + (lane >> 4) * 64 + (lane & 15);
+            uint2 e = mine[0];
+            float bj = __uint_as_float(e.x);
+            int kj = (int)e.y;
 #pragma unroll
-            for (int d = 16; d <= 32; d <<= 1) {
-                const float ob = __shfl_xor(bj, d, 64);
-                const int ok = __shfl_xor(kj, d, 64);
-                // selects, not branches: the larger score, the lower key on equal scores
+            for (int m = 1; m < 4; ++m) {
+                e = mine[16 * m];
+                const float ob = __uint_as_float(e.x);
+                const int ok = (int)e.y;
                 const bool take = (ob > bj) | ((ob == bj) & (ok < kj));
                 bj = take ? ob : bj;
                 kj = take ? ok : kj;
             }
-            int got = __shfl(kj, lane & 15, 64);
-            if ((lane >> 4) == j)
-                key_mine = got;
+            key_mine = kj;
         }
 
         // ---- re-score the 4 candidates of the winning group: secondary, primary, code word -------
