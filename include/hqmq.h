@@ -158,6 +158,30 @@ int32_t hqmq_encode_timed(const hqmq_params *params, const void *x_dev, const fl
 int32_t hqmq_decode(const hqmq_params *params, const hqmq_encoded *enc, uint64_t outlier_capacity,
                     const float *sec_dev, void *out_dev, void *stream);
 
+/* Incremental encode: as hqmq_encode, for the few token rows a generation step appends, with the
+ * outlier thresholds SUPPLIED by the caller instead of taken from the call's own median (the
+ * median over the 32 B T chunks of a one-token tensor means nothing; Sec. 3 "Median-multiplier
+ * outlier extraction" leaves a running estimate for short contexts to the implementation).
+ *   thr_dev  DEVICE, fp64 [H]: a chunk of head h is flagged iff its squared norm r^2 > thr_dev[h]
+ *            (for the paper's rule with a running median estimate r_med: thr = (C r_med)^2; to
+ *            freeze the prefill's thresholds pass what hqmq_thresholds returned).  params->C is
+ *            not used; HQMQ_FLAG_NO_OUTLIERS is rejected (INVALID_ARG).
+ * Everything else (buffers, sizes from hqmq_sizes for THIS small shape, ordering of the outlier
+ * list, errors) is as in hqmq_encode; the encoded rows form a tensor of their own. */
+int32_t hqmq_encode_given_thresholds(const hqmq_params *params, const void *x_dev, const float *sec_dev,
+                                     const double *thr_dev, const hqmq_encoded *enc,
+                                     uint64_t outlier_capacity, void *workspace_dev,
+                                     uint64_t workspace_bytes, void *stream);
+
+/* The thresholds on squared chunk norms, fp64 [H], that the last encode using this workspace
+ * applied (fl(fl(C C) median(r^2)) per head, Sec. 3; +infinity with HQMQ_FLAG_NO_OUTLIERS): a
+ * stream-ordered device-to-device copy of H doubles, e.g. to seed or update a caller's running
+ * estimate.  slice: 0 for hqmq_encode; for hqmq_encode_batch the index of the tensor within its
+ * launch group of 32.  Errors: INVALID_ARG (null / misaligned pointer, slice outside 0..31),
+ * UNSUPPORTED (params), HIP. */
+int32_t hqmq_thresholds(const hqmq_params *params, const void *workspace_dev, int32_t slice,
+                        double *thr_out_dev, void *stream);
+
 /* Encode n_tensors tensors of ONE shape (the same params: e.g. the K and V of every layer of the
  * current batch, Alg. 1 applied per (layer, role)) with as few launches as possible: up to 32
  * tensors share each kernel launch, which removes the launch gaps and small-kernel tails of the

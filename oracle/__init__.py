@@ -262,11 +262,12 @@ class Encoded:
 
 
 def encode(x_bits: np.ndarray, sec: np.ndarray, b_r: int = 6, Cmul: float = 3.0,
-           use_outliers: bool = True, rows=None) -> Encoded:
+           use_outliers: bool = True, rows=None, thresholds=None) -> Encoded:
     """Encode one fp16 tensor [B, H, T, 128] (uint16 bit patterns) against the secondary
     codebooks sec [H, S, 4] (fp32) of its (layer, role).  `rows`: optional boolean mask or
     index list of the rows whose (expensive) search is run; the O(n) steps always cover the
-    whole tensor."""
+    whole tensor.  `thresholds`: fp64 [H] on squared norms, supplied instead of the batch's
+    own C^2 * median (the incremental setting: a chunk is flagged iff r^2 > thresholds[h])."""
     L = lib()
     x_bits = np.ascontiguousarray(x_bits, np.uint16)
     B, H, T, D = x_bits.shape
@@ -284,7 +285,11 @@ def encode(x_bits: np.ndarray, sec: np.ndarray, b_r: int = 6, Cmul: float = 3.0,
     m2 = np.zeros(H)
     L.hqo_head_medians(r2, B, H, T, NC, m2)
     flag = np.zeros(n_chunks, np.uint8)
-    L.hqo_flags(r2, m2, float(Cmul), int(bool(use_outliers)), B, H, T, NC, flag)
+    if thresholds is None:
+        L.hqo_flags(r2, m2, float(Cmul), int(bool(use_outliers)), B, H, T, NC, flag)
+    else:
+        # the flag rule compares against fl(fl(C C) m): with C = 1 that is m itself
+        L.hqo_flags(r2, np.ascontiguousarray(thresholds, np.float64), 1.0, 1, B, H, T, NC, flag)
 
     flags = np.zeros(n_rows, np.uint32)
     row_off = np.zeros(n_rows + 1, np.uint32)

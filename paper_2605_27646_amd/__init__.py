@@ -23,9 +23,11 @@ from .binding import (  # noqa: F401
     hqmq_decode_batch,
     hqmq_encode,
     hqmq_encode_batch,
+    hqmq_encode_given_thresholds,
     hqmq_encode_timed,
     hqmq_last_hip_error,
     hqmq_sizes,
+    hqmq_thresholds,
     library_path,
     params_for,
 )

@@ -69,6 +69,12 @@ def _load():
                                     C.c_uint64, C.c_void_p, C.c_uint64, C.c_void_p]
         lib.hqmq_encode_timed.restype = C.c_int32
         lib.hqmq_encode_timed.argtypes = lib.hqmq_encode.argtypes + [C.POINTER(C.c_void_p)]
+        lib.hqmq_encode_given_thresholds.restype = C.c_int32
+        lib.hqmq_encode_given_thresholds.argtypes = [C.POINTER(HqmqParams), C.c_void_p, C.c_void_p, C.c_void_p,
+                                                     C.POINTER(_Encoded), C.c_uint64, C.c_void_p, C.c_uint64,
+                                                     C.c_void_p]
+        lib.hqmq_thresholds.restype = C.c_int32
+        lib.hqmq_thresholds.argtypes = [C.POINTER(HqmqParams), C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
         lib.hqmq_encode_batch.restype = C.c_int32
         lib.hqmq_encode_batch.argtypes = [C.POINTER(HqmqParams), C.c_int32, C.POINTER(C.c_void_p),
                                           C.POINTER(C.c_void_p), C.POINTER(_Encoded), C.POINTER(C.c_uint64),
@@ -212,6 +218,29 @@ def hqmq_decode(params: HqmqParams, enc: EncodedBuffers, sec: torch.Tensor, out:
     rc = _load().hqmq_decode(C.byref(params), C.byref(enc.as_struct()), enc.outlier_capacity,
                              sec.data_ptr(), out.data_ptr(), _stream_ptr(stream))
     _check(rc, "hqmq_decode")
+
+
+def hqmq_encode_given_thresholds(params: HqmqParams, x: torch.Tensor, sec: torch.Tensor, thr: torch.Tensor,
+                                 enc: EncodedBuffers, workspace: torch.Tensor, stream=None) -> None:
+    """hqmq_encode with the caller's thresholds on squared chunk norms (device fp64 [H])."""
+    if x.dtype != torch.float16 or not x.is_cuda or not sec.is_cuda or sec.dtype != torch.float32:
+        raise ValueError("x must be a device fp16 tensor and sec a device fp32 tensor")
+    if not thr.is_cuda or thr.dtype != torch.float64 or not thr.is_contiguous() or thr.numel() != params.H:
+        raise ValueError("thr must be a contiguous device fp64 tensor of H entries")
+    rc = _load().hqmq_encode_given_thresholds(C.byref(params), x.data_ptr(), sec.data_ptr(), thr.data_ptr(),
+                                              C.byref(enc.as_struct()), enc.outlier_capacity,
+                                              workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                              _stream_ptr(stream))
+    _check(rc, "hqmq_encode_given_thresholds")
+
+
+def hqmq_thresholds(params: HqmqParams, workspace: torch.Tensor, slice_index: int = 0, stream=None) -> torch.Tensor:
+    """Device fp64 [H]: the thresholds the last encode on this workspace (slice) applied."""
+    out = torch.empty(params.H, dtype=torch.float64, device=workspace.device)
+    rc = _load().hqmq_thresholds(C.byref(params), workspace.data_ptr(), int(slice_index), out.data_ptr(),
+                                 _stream_ptr(stream))
+    _check(rc, "hqmq_thresholds")
+    return out
 
 
 class EncodeBatch:

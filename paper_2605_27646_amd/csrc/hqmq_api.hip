@@ -191,7 +191,7 @@ static WorkspaceOffsets workspace_offsets(const WorkspaceLayout &l)
 static int32_t encode_impl(const hqmq_params *params, int32_t n_tensors, const void *const *x_dev,
                            const float *const *sec_dev, const hqmq_encoded *enc,
                            const uint64_t *outlier_capacity, void *workspace_dev, uint64_t workspace_bytes,
-                           void *stream, void *const *phase_events)
+                           void *stream, void *const *phase_events, const double *thr_given = nullptr)
 {
     int32_t rc = check_params(params);
     if (rc != HQMQ_OK)
@@ -218,6 +218,8 @@ static int32_t encode_impl(const hqmq_params *params, int32_t n_tensors, const v
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool no_outliers = (params->flags & HQMQ_FLAG_NO_OUTLIERS) != 0;
+    if (thr_given && (no_outliers || n_tensors != 1 || misaligned(thr_given, 8)))
+        return HQMQ_ERR_INVALID_ARG;
     auto mark = [&](int i) -> hipError_t {
         if (phase_events && phase_events[i])
             return hipEventRecord(static_cast<hipEvent_t>(phase_events[i]), st);
@@ -234,11 +236,12 @@ static int32_t encode_impl(const hqmq_params *params, int32_t n_tensors, const v
             t.enc = to_ptrs(&enc[first + i]);
             t.ws = static_cast<char *>(workspace_dev) + l.total * (uint64_t)i;
             t.outlier_capacity = outlier_capacity[first + i];
+            t.thr_given = thr_given;
         }
         hipError_t err = first == 0 ? mark(0) : hipSuccess;
         if (err != hipSuccess)
             return hip_failed(err);
-        err = launch_select_median(g, wo, batch, n, params->C, no_outliers, st);
+        err = launch_select_median(g, wo, batch, n, params->C, no_outliers || thr_given != nullptr, st);
         if (err == hipSuccess)
             err = mark(1);
         if (err != hipSuccess)
@@ -272,6 +275,42 @@ extern "C" int32_t hqmq_encode_timed(const hqmq_params *params, const void *x_de
 {
     return encode_impl(params, 1, &x_dev, &sec_dev, enc, &outlier_capacity, workspace_dev, workspace_bytes,
                        stream, phase_events);
+}
+
+extern "C" int32_t hqmq_encode_given_thresholds(const hqmq_params *params, const void *x_dev,
+                                                const float *sec_dev, const double *thr_dev,
+                                                const hqmq_encoded *enc, uint64_t outlier_capacity,
+                                                void *workspace_dev, uint64_t workspace_bytes, void *stream)
+{
+    if (!thr_dev)
+        return HQMQ_ERR_INVALID_ARG;
+    // the multiplier is not used: the thresholds are final
+    hqmq_params p;
+    if (!params)
+        return HQMQ_ERR_INVALID_ARG;
+    p = *params;
+    if (!(p.flags & HQMQ_FLAG_NO_OUTLIERS))
+        p.C = 1.0f;
+    return encode_impl(&p, 1, &x_dev, &sec_dev, enc, &outlier_capacity, workspace_dev, workspace_bytes, stream,
+                       nullptr, thr_dev);
+}
+
+extern "C" int32_t hqmq_thresholds(const hqmq_params *params, const void *workspace_dev, int32_t slice,
+                                   double *thr_out_dev, void *stream)
+{
+    int32_t rc = check_params(params);
+    if (rc != HQMQ_OK)
+        return rc;
+    if (!workspace_dev || !thr_out_dev || slice < 0 || slice >= kMaxEncodeBatch ||
+        misaligned(workspace_dev, 256) || misaligned(thr_out_dev, 8))
+        return HQMQ_ERR_INVALID_ARG;
+    const WorkspaceLayout l = workspace_layout(make_geometry(params));
+    const char *src = static_cast<const char *>(workspace_dev) + l.total * (uint64_t)slice + l.thr;
+    hipError_t err = hipMemcpyAsync(thr_out_dev, src, (size_t)params->H * sizeof(double), hipMemcpyDeviceToDevice,
+                                    static_cast<hipStream_t>(stream));
+    if (err != hipSuccess)
+        return hip_failed(err);
+    return HQMQ_OK;
 }
 
 extern "C" int32_t hqmq_encode_batch(const hqmq_params *params, int32_t n_tensors, const void *const *x_dev,

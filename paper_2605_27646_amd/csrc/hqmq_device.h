@@ -76,8 +76,9 @@ struct EncodeTensor {
     EncodedPtrs enc;
     char *ws;                  // this tensor's slice of the workspace
     uint64_t outlier_capacity;
+    const double *thr_given;   // caller's thresholds on squared norms [H], or null: take the median's
 };
-constexpr int kMaxEncodeBatch = 32;  // 32 * 88 B of descriptors stay inside the 4 KiB of kernel arguments
+constexpr int kMaxEncodeBatch = 32;  // 32 * 96 B of descriptors stay inside the 4 KiB of kernel arguments
 struct EncodeBatch {
     EncodeTensor t[kMaxEncodeBatch];
 };
@@ -169,7 +170,7 @@ __device__ __forceinline__ unsigned long long key_of(double r2)
 
 // Launchers implemented in the kernel translation units (host side).
 hipError_t launch_select_median(const Geometry &g, const WorkspaceOffsets &wo, const EncodeBatch &batch, int n_tensors,
-                                float C, bool no_outliers, hipStream_t stream);
+                                float C, bool skip_select, hipStream_t stream);
 hipError_t launch_search(const Geometry &g, const WorkspaceOffsets &wo, const EncodeBatch &batch, int n_tensors,
                          hipStream_t stream);
 hipError_t launch_outlier_list(const Geometry &g, const WorkspaceOffsets &wo, const EncodeBatch &batch, int n_tensors,

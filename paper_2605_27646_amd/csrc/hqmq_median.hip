@@ -93,7 +93,8 @@ __global__ __launch_bounds__(kThreads) void k_init(Geometry g, WorkspaceOffsets 
         ws.hist1[i] = 0;
     if (i < (uint32_t)g.H) {
         ws.cand_count[i] = 0;
-        ws.thr[i] = __longlong_as_double(0x7ff0000000000000LL);  // +inf: nothing is flagged
+        // +inf: nothing is flagged (replaced by the select, unless the caller supplies the thresholds)
+        ws.thr[i] = tn.thr_given ? tn.thr_given[i] : __longlong_as_double(0x7ff0000000000000LL);
     }
     if (i <= (uint32_t)g.H)
         enc.n_outliers[i] = 0;
@@ -354,12 +355,12 @@ __global__ __launch_bounds__(kThreads) void k_gather(Geometry g, WorkspaceOffset
 // host-side launch sequences
 // ---------------------------------------------------------------------------------------
 hipError_t launch_select_median(const Geometry &g, const WorkspaceOffsets &wo, const EncodeBatch &batch, int n_tensors,
-                                float C, bool no_outliers, hipStream_t stream)
+                                float C, bool skip_select, hipStream_t stream)
 {
     const unsigned n = (unsigned)n_tensors;
     uint32_t n_init = (uint32_t)g.H * kBins0;
     hipLaunchKernelGGL(k_init, dim3((n_init + kThreads - 1) / kThreads, 1, n), dim3(kThreads), 0, stream, g, wo, batch);
-    if (!no_outliers) {
+    if (!skip_select) {
         dim3 grid((g.T + kSelectRows - 1) / kSelectRows, g.B * g.H, n);
         hipLaunchKernelGGL(k_select_sweep<0>, grid, dim3(kSelectThreads), 0, stream, g, wo, batch);
         hipLaunchKernelGGL(k_select_sweep<1>, grid, dim3(kSelectThreads), 0, stream, g, wo, batch);

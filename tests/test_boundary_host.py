@@ -27,7 +27,7 @@ def lib():
 def test_library_exports_every_declared_symbol(lib):
     header = open(os.path.join(ROOT, "include", "hqmq.h")).read()
     declared = set(re.findall(r"^(?:int32_t|void|uint64_t)\s+(hqmq_\w+)\s*\(", header, re.M))
-    assert declared == {"hqmq_build_codebooks", "hqmq_sizes", "hqmq_encode", "hqmq_encode_timed", "hqmq_encode_batch", "hqmq_decode", "hqmq_decode_batch", "hqmq_attend", "hqmq_attend_workspace_bytes", "hqmq_last_hip_error"}
+    assert declared == {"hqmq_build_codebooks", "hqmq_sizes", "hqmq_encode", "hqmq_encode_timed", "hqmq_encode_batch", "hqmq_encode_given_thresholds", "hqmq_thresholds", "hqmq_decode", "hqmq_decode_batch", "hqmq_attend", "hqmq_attend_workspace_bytes", "hqmq_last_hip_error"}
     for name in declared:
         assert hasattr(lib, name), name
 
@@ -117,6 +117,16 @@ def test_encode_decode_reject_bad_arguments_without_touching_the_gpu(lib):
     assert eb(C.byref(p), 2, ptrs, bad_ptrs, encs, caps, 0x1000, ws2, None, None) == -1            # second sec misaligned
     assert eb(C.byref(p), 2, ptrs, ptrs, encs, caps, 0x1000, ws2 - 1, None, None) == -3            # one slice per tensor
     assert eb(C.byref(p), 2, ptrs, ptrs, encs, caps, 0x1010, ws2, None, None) == -1                # workspace alignment
+    eg = lib.hqmq_encode_given_thresholds
+    assert eg(C.byref(p), 0x1000, 0x1000, None, C.byref(good), 0, 0x1000, ws, None) == -1          # no thresholds
+    assert eg(C.byref(p), 0x1000, 0x1000, 0x1004, C.byref(good), 0, 0x1000, ws, None) == -1        # misaligned
+    assert eg(C.byref(_params(flags=hq.HQMQ_FLAG_NO_OUTLIERS)), 0x1000, 0x1000, 0x1000, C.byref(good), 0, 0x1000,
+              ws, None) == -1
+    assert eg(C.byref(p), None, 0x1000, 0x1000, C.byref(good), 0, 0x1000, ws, None) == -1
+    th = lib.hqmq_thresholds
+    assert th(C.byref(p), None, 0, 0x1000, None) == -1 and th(C.byref(p), 0x1000, 0, None, None) == -1
+    assert th(C.byref(p), 0x1000, 32, 0x1000, None) == -1 and th(C.byref(p), 0x1000, -1, 0x1000, None) == -1
+    assert th(C.byref(_params(D=64)), 0x1000, 0, 0x1000, None) == -2
     att = lib.hqmq_attend
     wsb = lib.hqmq_attend_workspace_bytes
     need = wsb(C.byref(p), 4 * p.H)

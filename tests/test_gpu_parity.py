@@ -307,6 +307,77 @@ def test_encode_batch_equals_single_encodes():
         assert torch.equal(encs[i].outliers[:total].view(torch.int16), g.bufs.outliers[:total].view(torch.int16)), i
 
 
+def test_thresholds_are_exported_and_can_be_supplied():
+    """hqmq_thresholds returns fl(fl(C C) median) per head, bit for bit; feeding those thresholds to
+    hqmq_encode_given_thresholds reproduces the plain encode's bytes."""
+    B, H, T, S = 2, 4, 257, 16
+    x = _lognormal_tensor(B, H, T, seed=41, sigma_g=0.8)
+    sec_t, sec = _sec(2, H, S)
+    e = oracle.encode(_bits(x), sec)
+    x_dev, sec_dev = x.to(DEV), sec_t.to(DEV)
+    params = hq.params_for(x_dev, S)
+    bufs = hq.alloc_encoded(params, DEV)
+    ws = hq.alloc_workspace(params, DEV)
+    hq.hqmq_encode(params, x_dev, sec_dev, bufs, ws)
+    thr = hq.hqmq_thresholds(params, ws)
+    torch.cuda.synchronize()
+    c = float(np.float32(3.0))
+    want = (c * c) * e.m2
+    assert np.array_equal(thr.cpu().numpy().view(np.uint64), want.view(np.uint64))
+    again = hq.alloc_encoded(params, DEV)
+    ws.fill_(0x5A)
+    hq.hqmq_encode_given_thresholds(params, x_dev, sec_dev, thr, again, ws)
+    torch.cuda.synchronize()
+    total = int(bufs.n_outliers[-1])
+    assert total == int(e.n_out[-1]) > 0
+    for a, b in ((again.codes, bufs.codes), (again.flags, bufs.flags), (again.row_off, bufs.row_off),
+                 (again.n_outliers, bufs.n_outliers), (again.sigma.view(torch.int16), bufs.sigma.view(torch.int16)),
+                 (again.outliers[:total].view(torch.int16), bufs.outliers[:total].view(torch.int16))):
+        assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("T_new", [1, 3])
+def test_incremental_encode_of_appended_tokens(T_new):
+    """The generation-step setting: a few new token rows per sequence, encoded against thresholds
+    frozen from the prefill (here: of a 300-token tensor of the same law).  Parity with the oracle run
+    on the same rows with the same thresholds; the decode round trip on those bytes."""
+    B, H, S, b_r = 2, 4, 16, 6
+    big = _lognormal_tensor(B, H, 300, seed=51, sigma_g=0.9)
+    sec_t, sec = _sec(3, H, S)
+    sec_dev = sec_t.to(DEV)
+    pb = hq.params_for(big.to(DEV), S, b_r)
+    wsb = hq.alloc_workspace(pb, DEV)
+    hq.hqmq_encode(pb, big.to(DEV), sec_dev, hq.alloc_encoded(pb, DEV), wsb)
+    thr = hq.hqmq_thresholds(pb, wsb)
+    torch.cuda.synchronize()
+
+    new = _lognormal_tensor(B, H, 40, seed=52, sigma_g=0.9)[:, :, :T_new].contiguous() * 1.5   # a few spill over
+    new = new.to(torch.float16)
+    xb = _bits(new)
+    e = oracle.encode(xb, sec, b_r=b_r, thresholds=thr.cpu().numpy())
+    x_dev = new.to(DEV)
+    params = hq.params_for(x_dev, S, b_r)
+    n_chunks = B * H * T_new * 32
+    bufs = hq.alloc_encoded(params, DEV, outlier_capacity=n_chunks)      # any chunk may be flagged here
+    ws = hq.alloc_workspace(params, DEV)
+    ws.fill_(0xAB)
+    hq.hqmq_encode_given_thresholds(params, x_dev, sec_dev, thr, bufs, ws)
+    torch.cuda.synchronize()
+    n_out = bufs.n_outliers.cpu().numpy().view(np.uint32)
+    total = int(n_out[-1])
+    from gpu_util import GpuEncoded
+    g = GpuEncoded(params, bufs, bufs.codes.cpu().numpy().view(np.uint32), bufs.sigma.cpu().numpy().view(np.uint16),
+                   bufs.flags.cpu().numpy().view(np.uint32), bufs.row_off.cpu().numpy().view(np.uint32), n_out,
+                   bufs.outliers[:total].cpu().numpy().view(np.uint16).reshape(total, 4),
+                   int(bufs.status.cpu().numpy().view(np.uint32)[0]))
+    stats = compare_encode(g, e, xb, sec)
+    want, r_hat = oracle.decode(g.codes, g.sigma, g.flags, g.row_off, g.outliers, sec, B, H, T_new, b_r, True)
+    got = gpu_decode(params, bufs, sec_dev, x_dev)
+    stats["decode_rel_err"] = compare_decode(got, want, r_hat, e.flag)
+    print(stats, flush=True)
+    assert 0 < stats["outliers"] < n_chunks
+
+
 def test_deterministic_bytes():
     x = _lognormal_tensor(1, 4, 300, seed=15).to(DEV)
     sec_t, _ = _sec(0, 4, 64)
