@@ -167,11 +167,22 @@ int32_t hqmq_decode(const hqmq_params *params, const hqmq_encoded *enc, uint64_t
  *            freeze the prefill's thresholds pass what hqmq_thresholds returned).  params->C is
  *            not used; HQMQ_FLAG_NO_OUTLIERS is rejected (INVALID_ARG).
  * Everything else (buffers, sizes from hqmq_sizes for THIS small shape, ordering of the outlier
- * list, errors) is as in hqmq_encode; the encoded rows form a tensor of their own. */
+ * list, errors) is as in hqmq_encode; the encoded rows form a tensor of their own.  One bound of
+ * hqmq_sizes does not carry over: with arbitrary thresholds every chunk may be flagged, so a list
+ * that can never overflow needs n_rows * 32 entries (an overflow is reported in status as usual). */
 int32_t hqmq_encode_given_thresholds(const hqmq_params *params, const void *x_dev, const float *sec_dev,
                                      const double *thr_dev, const hqmq_encoded *enc,
                                      uint64_t outlier_capacity, void *workspace_dev,
                                      uint64_t workspace_bytes, void *stream);
+
+/* hqmq_encode_given_thresholds for n_tensors tensors of one shape in one call (e.g. the new K and
+ * V rows of every layer of a generation step): up to 32 tensors per kernel launch, arguments as in
+ * hqmq_encode_batch plus thr_dev, a HOST array of n_tensors DEVICE pointers to fp64 [H]. */
+int32_t hqmq_encode_batch_given_thresholds(const hqmq_params *params, int32_t n_tensors,
+                                           const void *const *x_dev, const float *const *sec_dev,
+                                           const double *const *thr_dev, const hqmq_encoded *enc,
+                                           const uint64_t *outlier_capacity, void *workspace_dev,
+                                           uint64_t workspace_bytes, void *stream);
 
 /* The thresholds on squared chunk norms, fp64 [H], that the last encode using this workspace
  * applied (fl(fl(C C) median(r^2)) per head, Sec. 3; +infinity with HQMQ_FLAG_NO_OUTLIERS): a

@@ -23,6 +23,7 @@ from .binding import (  # noqa: F401
     hqmq_decode_batch,
     hqmq_encode,
     hqmq_encode_batch,
+    hqmq_encode_batch_given_thresholds,
     hqmq_encode_given_thresholds,
     hqmq_encode_timed,
     hqmq_last_hip_error,

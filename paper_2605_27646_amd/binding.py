@@ -73,6 +73,11 @@ def _load():
         lib.hqmq_encode_given_thresholds.argtypes = [C.POINTER(HqmqParams), C.c_void_p, C.c_void_p, C.c_void_p,
                                                      C.POINTER(_Encoded), C.c_uint64, C.c_void_p, C.c_uint64,
                                                      C.c_void_p]
+        lib.hqmq_encode_batch_given_thresholds.restype = C.c_int32
+        lib.hqmq_encode_batch_given_thresholds.argtypes = [C.POINTER(HqmqParams), C.c_int32, C.POINTER(C.c_void_p),
+                                                           C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
+                                                           C.POINTER(_Encoded), C.POINTER(C.c_uint64), C.c_void_p,
+                                                           C.c_uint64, C.c_void_p]
         lib.hqmq_thresholds.restype = C.c_int32
         lib.hqmq_thresholds.argtypes = [C.POINTER(HqmqParams), C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
         lib.hqmq_encode_batch.restype = C.c_int32
@@ -270,6 +275,21 @@ class EncodeBatch:
         self.enc = (_Encoded * n)(*[e.as_struct() for e in encs])
         self.cap = (C.c_uint64 * n)(*[e.outlier_capacity for e in encs])
         self.workspace = workspace
+
+
+def hqmq_encode_batch_given_thresholds(batch: "EncodeBatch", thrs, stream=None) -> None:
+    """hqmq_encode_batch with one caller-supplied threshold vector (device fp64 [H]) per tensor."""
+    if len(thrs) != batch.n:
+        raise ValueError("one threshold tensor per batch entry")
+    for t in thrs:
+        if not t.is_cuda or t.dtype != torch.float64 or not t.is_contiguous() or t.numel() != batch.params.H:
+            raise ValueError("thresholds must be contiguous device fp64 tensors of H entries")
+    ptrs = (C.c_void_p * batch.n)(*[t.data_ptr() for t in thrs])
+    ws = batch.workspace
+    rc = _load().hqmq_encode_batch_given_thresholds(C.byref(batch.params), batch.n, batch.x, batch.sec, ptrs,
+                                                    batch.enc, batch.cap, ws.data_ptr(),
+                                                    ws.numel() * ws.element_size(), _stream_ptr(stream))
+    _check(rc, "hqmq_encode_batch_given_thresholds")
 
 
 def alloc_batch_workspace(params: HqmqParams, n_tensors: int, device) -> torch.Tensor:

@@ -191,7 +191,7 @@ static WorkspaceOffsets workspace_offsets(const WorkspaceLayout &l)
 static int32_t encode_impl(const hqmq_params *params, int32_t n_tensors, const void *const *x_dev,
                            const float *const *sec_dev, const hqmq_encoded *enc,
                            const uint64_t *outlier_capacity, void *workspace_dev, uint64_t workspace_bytes,
-                           void *stream, void *const *phase_events, const double *thr_given = nullptr)
+                           void *stream, void *const *phase_events, const double *const *thr_given = nullptr)
 {
     int32_t rc = check_params(params);
     if (rc != HQMQ_OK)
@@ -218,8 +218,13 @@ static int32_t encode_impl(const hqmq_params *params, int32_t n_tensors, const v
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool no_outliers = (params->flags & HQMQ_FLAG_NO_OUTLIERS) != 0;
-    if (thr_given && (no_outliers || n_tensors != 1 || misaligned(thr_given, 8)))
-        return HQMQ_ERR_INVALID_ARG;
+    if (thr_given) {
+        if (no_outliers)
+            return HQMQ_ERR_INVALID_ARG;
+        for (int32_t i = 0; i < n_tensors; ++i)
+            if (!thr_given[i] || misaligned(thr_given[i], 8))
+                return HQMQ_ERR_INVALID_ARG;
+    }
     auto mark = [&](int i) -> hipError_t {
         if (phase_events && phase_events[i])
             return hipEventRecord(static_cast<hipEvent_t>(phase_events[i]), st);
@@ -236,7 +241,7 @@ static int32_t encode_impl(const hqmq_params *params, int32_t n_tensors, const v
             t.enc = to_ptrs(&enc[first + i]);
             t.ws = static_cast<char *>(workspace_dev) + l.total * (uint64_t)i;
             t.outlier_capacity = outlier_capacity[first + i];
-            t.thr_given = thr_given;
+            t.thr_given = thr_given ? thr_given[first + i] : nullptr;
         }
         hipError_t err = first == 0 ? mark(0) : hipSuccess;
         if (err != hipSuccess)
@@ -277,22 +282,46 @@ extern "C" int32_t hqmq_encode_timed(const hqmq_params *params, const void *x_de
                        stream, phase_events);
 }
 
+// the multiplier is not used when the thresholds are final
+static int32_t params_for_given_thresholds(const hqmq_params *params, hqmq_params *out)
+{
+    if (!params)
+        return HQMQ_ERR_INVALID_ARG;
+    *out = *params;
+    if (!(out->flags & HQMQ_FLAG_NO_OUTLIERS))
+        out->C = 1.0f;
+    return HQMQ_OK;
+}
+
 extern "C" int32_t hqmq_encode_given_thresholds(const hqmq_params *params, const void *x_dev,
                                                 const float *sec_dev, const double *thr_dev,
                                                 const hqmq_encoded *enc, uint64_t outlier_capacity,
                                                 void *workspace_dev, uint64_t workspace_bytes, void *stream)
 {
+    hqmq_params p;
+    int32_t rc = params_for_given_thresholds(params, &p);
+    if (rc != HQMQ_OK)
+        return rc;
     if (!thr_dev)
         return HQMQ_ERR_INVALID_ARG;
-    // the multiplier is not used: the thresholds are final
-    hqmq_params p;
-    if (!params)
-        return HQMQ_ERR_INVALID_ARG;
-    p = *params;
-    if (!(p.flags & HQMQ_FLAG_NO_OUTLIERS))
-        p.C = 1.0f;
     return encode_impl(&p, 1, &x_dev, &sec_dev, enc, &outlier_capacity, workspace_dev, workspace_bytes, stream,
-                       nullptr, thr_dev);
+                       nullptr, &thr_dev);
+}
+
+extern "C" int32_t hqmq_encode_batch_given_thresholds(const hqmq_params *params, int32_t n_tensors,
+                                                      const void *const *x_dev, const float *const *sec_dev,
+                                                      const double *const *thr_dev, const hqmq_encoded *enc,
+                                                      const uint64_t *outlier_capacity, void *workspace_dev,
+                                                      uint64_t workspace_bytes, void *stream)
+{
+    hqmq_params p;
+    int32_t rc = params_for_given_thresholds(params, &p);
+    if (rc != HQMQ_OK)
+        return rc;
+    if (!thr_dev)
+        return HQMQ_ERR_INVALID_ARG;
+    return encode_impl(&p, n_tensors, x_dev, sec_dev, enc, outlier_capacity, workspace_dev, workspace_bytes,
+                       stream, nullptr, thr_dev);
 }
 
 extern "C" int32_t hqmq_thresholds(const hqmq_params *params, const void *workspace_dev, int32_t slice,

@@ -207,6 +207,11 @@ __global__ __launch_bounds__(kThreads) void k_search(Geometry g, WorkspaceOffset
         const int r_in_block = it * 8 + wv * 2 + half_id;
         const int t = t0 + r_in_block;
         const bool valid = t < g.T;
+        if (t0 + it * 8 + wv * 2 >= g.T) {  // wave-uniform: both rows of this iteration lie past the end
+            if (c == 0)
+                rcnt[r_in_block] = 0;
+            continue;
+        }
 
         // ---- chunk, norm, flag, row scale --------------------------------------------------
         half4_t xv = valid ? load_chunk(base + (int64_t)t * g.st) : half4_t{0, 0, 0, 0};

@@ -27,7 +27,7 @@ def lib():
 def test_library_exports_every_declared_symbol(lib):
     header = open(os.path.join(ROOT, "include", "hqmq.h")).read()
     declared = set(re.findall(r"^(?:int32_t|void|uint64_t)\s+(hqmq_\w+)\s*\(", header, re.M))
-    assert declared == {"hqmq_build_codebooks", "hqmq_sizes", "hqmq_encode", "hqmq_encode_timed", "hqmq_encode_batch", "hqmq_encode_given_thresholds", "hqmq_thresholds", "hqmq_decode", "hqmq_decode_batch", "hqmq_attend", "hqmq_attend_workspace_bytes", "hqmq_last_hip_error"}
+    assert declared == {"hqmq_build_codebooks", "hqmq_sizes", "hqmq_encode", "hqmq_encode_timed", "hqmq_encode_batch", "hqmq_encode_given_thresholds", "hqmq_encode_batch_given_thresholds", "hqmq_thresholds", "hqmq_decode", "hqmq_decode_batch", "hqmq_attend", "hqmq_attend_workspace_bytes", "hqmq_last_hip_error"}
     for name in declared:
         assert hasattr(lib, name), name
 
@@ -123,6 +123,10 @@ def test_encode_decode_reject_bad_arguments_without_touching_the_gpu(lib):
     assert eg(C.byref(_params(flags=hq.HQMQ_FLAG_NO_OUTLIERS)), 0x1000, 0x1000, 0x1000, C.byref(good), 0, 0x1000,
               ws, None) == -1
     assert eg(C.byref(p), None, 0x1000, 0x1000, C.byref(good), 0, 0x1000, ws, None) == -1
+    ebg = lib.hqmq_encode_batch_given_thresholds
+    assert ebg(C.byref(p), 2, ptrs, ptrs, None, encs, caps, 0x1000, ws2, None) == -1
+    assert ebg(C.byref(p), 2, ptrs, ptrs, (C.c_void_p * 2)(0x1000, None), encs, caps, 0x1000, ws2, None) == -1
+    assert ebg(C.byref(p), 2, ptrs, ptrs, ptrs, encs, caps, 0x1000, ws2 - 1, None) == -3
     th = lib.hqmq_thresholds
     assert th(C.byref(p), None, 0, 0x1000, None) == -1 and th(C.byref(p), 0x1000, 0, None, None) == -1
     assert th(C.byref(p), 0x1000, 32, 0x1000, None) == -1 and th(C.byref(p), 0x1000, -1, 0x1000, None) == -1

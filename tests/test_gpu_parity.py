@@ -378,6 +378,31 @@ def test_incremental_encode_of_appended_tokens(T_new):
     assert 0 < stats["outliers"] < n_chunks
 
 
+def test_batched_incremental_encode_equals_single_calls():
+    B, H, S, T_new, n = 2, 4, 16, 2, 5
+    cb = hq.hqmq_build_codebooks(6, n, H, S)
+    xs, secs, thrs, singles = [], [], [], []
+    for i in range(n):
+        x = (_lognormal_tensor(B, H, 8, seed=400 + i, sigma_g=0.8)[:, :, :T_new].contiguous()).to(DEV)
+        sec = cb[i, 0].contiguous().to(DEV)
+        thr = torch.full((H,), 4.0 + i, dtype=torch.float64, device=DEV)
+        params = hq.params_for(x, S)
+        bufs = hq.alloc_encoded(params, DEV, outlier_capacity=B * H * T_new * 32)
+        hq.hqmq_encode_given_thresholds(params, x, sec, thr, bufs, hq.alloc_workspace(params, DEV))
+        xs.append(x), secs.append(sec), thrs.append(thr), singles.append(bufs)
+    encs = [hq.alloc_encoded(params, DEV, outlier_capacity=B * H * T_new * 32) for _ in range(n)]
+    batch = hq.EncodeBatch(params, xs, secs, encs, hq.alloc_batch_workspace(params, n, DEV))
+    hq.hqmq_encode_batch_given_thresholds(batch, thrs)
+    torch.cuda.synchronize()
+    for a, b in zip(encs, singles):
+        total = int(b.n_outliers[-1])
+        assert total > 0
+        assert torch.equal(a.codes, b.codes) and torch.equal(a.flags, b.flags) and torch.equal(a.row_off, b.row_off)
+        assert torch.equal(a.n_outliers, b.n_outliers)
+        assert torch.equal(a.sigma.view(torch.int16), b.sigma.view(torch.int16))
+        assert torch.equal(a.outliers[:total].view(torch.int16), b.outliers[:total].view(torch.int16))
+
+
 def test_deterministic_bytes():
     x = _lognormal_tensor(1, 4, 300, seed=15).to(DEV)
     sec_t, _ = _sec(0, 4, 64)
