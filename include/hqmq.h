@@ -120,7 +120,9 @@ int32_t hqmq_sizes(const hqmq_params *params, hqmq_size_info *out);
  * radius code r_q = clamp(rint(r * (2^b_r - 1) / sigma), 0, 2^b_r - 1); bit packing.
  *   params            HOST.
  *   x_dev             DEVICE, in, fp16, 16-byte aligned, addressed with params strides; finite.
- *   sec_dev           DEVICE, in, fp32 [H][S][4]: the codebooks of THIS (layer, role).
+ *   sec_dev           DEVICE, in, fp32 [H][S][4]: the codebooks of THIS (layer, role); unit
+ *                     quaternions (what hqmq_build_codebooks makes).  Components must stay below
+ *                     32 in magnitude (they pass through fp16 parts scaled by 2^10).
  *   enc               HOST struct of DEVICE pointers (see hqmq_encoded), sized per hqmq_sizes.
  *   outlier_capacity  entries (chunks) available in enc->outliers; outlier_capacity_max always
  *                     suffices.  If fewer, surplus outliers are dropped, status gets
