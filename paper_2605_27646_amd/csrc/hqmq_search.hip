@@ -8,15 +8,15 @@
 //     max_p <v, P_p> = max( max_i |v_i| , (|v_0|+|v_1|+|v_2|+|v_3|)/2 )
 // (first term: the 8 axis elements +-1, +-i, +-j, +-k; second: the 16 half-integer elements).
 // The map u -> v is linear, v = A(q_s) u with a 4x4 matrix per secondary, so all S products of
-// 16 chunks are one [4S x 4] x [4 x 16] contraction with K = 4: exactly the shape of
-// v_mfma_f32_16x16x4_f32.  One MFMA gives every lane the four components of v for one
-// (chunk, secondary) pair; the closed form and the running argmax over s are a handful of VALU
-// instructions per pair.  The search stays exhaustive over all S secondaries and, through the
-// closed form, over all 24 primaries.
+// 16 chunks are one [4S x 4] x [4 x 16] contraction with K = 4 on the matrix cores (how it is fed
+// to them is described at the kernel).  One MFMA gives every lane the four components of v for
+// one (chunk, secondary) pair; the closed form and the running argmax over s are a handful of
+// VALU instructions per pair.  The search stays exhaustive over all S secondaries and, through
+// the closed form, over all 24 primaries.
 //
-// On gfx950 the fp32 MFMA and the VALU do not run concurrently on a SIMD (measured: their times
-// add), so the inner loop is costed as 32 cycles of MFMA plus 4 cycles per VALU instruction for
-// every 64 (chunk, secondary) pairs, and the VALU count per pair is what is minimised: the
+// On gfx950 MFMA and VALU instructions do not run concurrently on a SIMD (measured: their times
+// add), so the inner loop is costed as 17 cycles of MFMA plus 3 to 4 cycles per VALU instruction
+// for every 64 (chunk, secondary) pairs, and the VALU count per pair is what is minimised: the
 // running argmax is kept per group of 16 secondaries (4 per lane) with v_max3 chains, one
 // compare-and-select per group, and the winner inside the winning group is found afterwards by
 // re-scoring its 4 candidates once per chunk.
