@@ -77,6 +77,27 @@ def test_encode_decode_parity_small(B, H, T, S, b_r):
     assert stats["outliers"] > 0 or T < 16
 
 
+def _random_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        B = int(rng.integers(1, 4))
+        H = int(rng.integers(1, 5))
+        T = int(rng.integers(1, 160))
+        S = int(rng.choice([1, 2, 3, 7, 16, 24, 33, 48, 64, 80]))
+        b_r = int(rng.integers(1, 9))
+        out.append((B, H, T, S, b_r))
+    return out
+
+
+@pytest.mark.parametrize("B,H,T,S,b_r", _random_shapes(14, seed=2024))
+def test_encode_decode_parity_random_shapes(B, H, T, S, b_r):
+    """Seeded random small shapes: every combination of batch, heads, ragged lengths, codebook sizes
+    that are neither powers of two nor multiples of 16, and all radius widths."""
+    x = _lognormal_tensor(B, H, T, seed=1000 + 7 * T + S, sigma_g=0.3 + 0.1 * b_r)
+    _roundtrip(x, S, b_r=b_r, seed=S)
+
+
 def test_tiny_config_full():
     wl = workloads.WORKLOADS["tiny"]
     for role in (0, 1):
