@@ -462,11 +462,20 @@ hipError_t launch_search(const Geometry &g, const WorkspaceOffsets &wo, const En
     dim3 grid((g.T + kSearchRows - 1) / kSearchRows, g.B * g.H, (unsigned)n_tensors);
     const size_t lds = (size_t)g.S16 * 4 * 64 * sizeof(uint4) + (size_t)g.S16 * 16 * 4 * sizeof(float) +
                        4 * 64 * 4 * sizeof(uint2) + (4 * 2 * 32 + kSearchRows) * sizeof(uint32_t);
-    // more than the 64 KiB a kernel gets by default once S > 208
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(k_search),
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (attr != hipSuccess)
-        return attr;
+    // more than the 64 KiB a kernel gets by default once S > 208: raise the kernel's limit, once per device
+    static bool raised[64] = {};
+    int device = 0;
+    hipError_t err = hipGetDevice(&device);
+    if (err != hipSuccess)
+        return err;
+    if (device < 0 || device >= 64 || !raised[device]) {
+        err = hipFuncSetAttribute(reinterpret_cast<const void *>(k_search),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (err != hipSuccess)
+            return err;
+        if (device >= 0 && device < 64)
+            raised[device] = true;
+    }
     hipLaunchKernelGGL(k_search, grid, dim3(kThreads), lds, stream, g, wo, batch);
     return hipGetLastError();
 }
