@@ -259,6 +259,23 @@ def test_attend_llama3_8b_32k_layer_full_size():
     _check(got, want, V64, Hq)
 
 
+def test_attend_128k_tokens_one_query_head_per_kv_head():
+    """The longest workload shape (T = 131072, 8 kv heads), G = 1: 32 tiles per split."""
+    wl = workloads.WORKLOADS["llama3_70b_128k"]
+    k = workloads.make_tensor(wl, 1, 0, DEV)
+    v = workloads.make_tensor(wl, 1, 1, DEV)
+    cb = hq.hqmq_build_codebooks(0, 2, wl.H, wl.S)
+    sec_k, sec_v = cb[1, 0].contiguous(), cb[1, 1].contiguous()
+    gk = gpu_encode(k, sec_k.to(DEV), wl.b_r)
+    gv = gpu_encode(v, sec_v.to(DEV), wl.b_r)
+    del k, v
+    q = _query(wl.B, wl.H, seed=90, gain=2.0)
+    scale = 1 / math.sqrt(128)
+    want, _, V64 = _oracle_attend((gk, gv), (sec_k.numpy(), sec_v.numpy()), q, scale, wl.B, wl.H, wl.T, wl.b_r)
+    got = _gpu_attend(gk.params, q, scale, gk.bufs, sec_k.to(DEV), gv.bufs, sec_v.to(DEV))
+    _check(got, want, V64, wl.H)
+
+
 def test_attend_is_deterministic():
     B, H, T, Hq, S = 1, 2, 5000, 8, 16
     k, v = _tensors(B, H, T, seed=51)
