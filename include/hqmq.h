@@ -233,7 +233,10 @@ int32_t hqmq_decode_batch(const hqmq_params *params, int32_t n_tensors, const hq
  * weights enter with about 22 significant bits), the softmax subtracts the running maximum
  * (online form), and the result is rounded once to fp16.
  *   params     HOST; B, H, T, D, S, b_r describe BOTH caches (strides are ignored).
- *   n_q_heads  a multiple of H, at most 16 * H.
+ *   n_q_heads  a multiple of H, at most 16 * H.  Several query tokens that all see the whole cache
+ *              (a few speculative or chunked decode positions) can ride along as extra query
+ *              heads of their kv head: lay q out as [B][H][tokens * heads_per_kv][128] and pass
+ *              n_q_heads = H * tokens * heads_per_kv <= 16 * H.
  *   q_dev      DEVICE, fp16 [B][n_q_heads][128] contiguous, 16-byte aligned.
  *   scale      softmax scale (usually 1/sqrt(128)); finite.
  *   enc_k, enc_v, cap_k, cap_v, sec_k_dev, sec_v_dev   as enc / outlier_capacity / sec_dev of
