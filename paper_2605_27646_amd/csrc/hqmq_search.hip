@@ -139,11 +139,15 @@ __device__ __forceinline__ int nearest_primary(float v0, float v1, float v2, flo
 //   amat  [4*S16][64] x 16 B   MFMA A operands: lane l of s-block sb holds the parts of
 //                              A[row l%16][k l/16], row 4g+i = component i of v for secondary 4 sb + g
 //   secl  [16*S16][4] f32      the head's secondaries (zero padded to a multiple of 16)
-//   ubuf  [4 waves][64][4] x 8 B   parts (h, l, m, 0) of the unit directions of the wave's 64 chunks
-//   pack  [4 waves][2][32] u32 row code words being assembled
+//   ubuf  [kWaves][64][4] x 8 B   parts (h, l, m, 0) of the unit directions of the wave's 64 chunks
+//   pack  [kWaves][2][32] u32 row code words being assembled
 //   rcnt  [kSearchRows] u32    outliers per row of the workgroup
-__global__ __launch_bounds__(kThreads) void k_search(Geometry g, WorkspaceOffsets wo, EncodeBatch batch)
+// kWaves: 4, or 8 when the A operands are so large (S > 256) that only one workgroup fits a CU: twice
+// the waves then share them and keep two waves on every SIMD.
+template <int kWaves>
+__global__ __launch_bounds__(64 * kWaves) void k_search(Geometry g, WorkspaceOffsets wo, EncodeBatch batch)
 {
+    constexpr int kThreadsS = 64 * kWaves;
     const EncodeTensor &tn = batch.t[blockIdx.z];
     const Workspace ws = carve_workspace(tn.ws, wo);
     const EncodedPtrs enc = tn.enc;
@@ -153,8 +157,8 @@ __global__ __launch_bounds__(kThreads) void k_search(Geometry g, WorkspaceOffset
     uint4 *amat = reinterpret_cast<uint4 *>(smem);
     float *secl = reinterpret_cast<float *>(amat + (size_t)g.S16 * 4 * 64);
     uint2 *ubuf = reinterpret_cast<uint2 *>(secl + (size_t)g.S16 * 16 * 4);
-    uint32_t *pack = reinterpret_cast<uint32_t *>(ubuf + 4 * 64 * 4);
-    uint32_t *rcnt = pack + 4 * 2 * 32;
+    uint32_t *pack = reinterpret_cast<uint32_t *>(ubuf + kWaves * 64 * 4);
+    uint32_t *rcnt = pack + kWaves * 2 * 32;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, and known to be
@@ -164,14 +168,14 @@ __global__ __launch_bounds__(kThreads) void k_search(Geometry g, WorkspaceOffset
     const float *sec_h = sec + (size_t)h * g.S * 4;
 
     // ---- setup: secondaries and A operands into LDS ---------------------------------------
-    for (int s = tid; s < g.S16 * 16; s += kThreads) {
+    for (int s = tid; s < g.S16 * 16; s += kThreadsS) {
         float4_t q = {0.f, 0.f, 0.f, 0.f};
         if (s < g.S)
             q = *reinterpret_cast<const float4_t *>(sec_h + 4 * s);
         *reinterpret_cast<float4_t *>(secl + 4 * s) = q;
     }
     __syncthreads();
-    for (int idx = tid; idx < g.S16 * 4 * 64; idx += kThreads) {
+    for (int idx = tid; idx < g.S16 * 4 * 64; idx += kThreadsS) {
         int sb = idx >> 6, l = idx & 63;
         int row = l & 15, k = l >> 4;
         int gsub = row >> 2, i = row & 3;
@@ -203,11 +207,11 @@ __global__ __launch_bounds__(kThreads) void k_search(Geometry g, WorkspaceOffset
     uint32_t *my_pack = pack + wv * 64;
     const _Float16 *base = x + (int64_t)b * g.sb + (int64_t)h * g.sh + 4 * c;
 
-    for (int it = 0; it < kSearchRows / 8; ++it) {
-        const int r_in_block = it * 8 + wv * 2 + half_id;
+    for (int it = 0; it < kSearchRows / (2 * kWaves); ++it) {
+        const int r_in_block = it * 2 * kWaves + wv * 2 + half_id;
         const int t = t0 + r_in_block;
         const bool valid = t < g.T;
-        if (t0 + it * 8 + wv * 2 >= g.T) {  // wave-uniform: both rows of this iteration lie past the end
+        if (t0 + it * 2 * kWaves + wv * 2 >= g.T) {  // wave-uniform: both rows of this iteration lie past the end
             if (c == 0)
                 rcnt[r_in_block] = 0;
             continue;
@@ -460,8 +464,9 @@ hipError_t launch_search(const Geometry &g, const WorkspaceOffsets &wo, const En
                          hipStream_t stream)
 {
     dim3 grid((g.T + kSearchRows - 1) / kSearchRows, g.B * g.H, (unsigned)n_tensors);
+    const int waves = g.S16 > 16 ? 8 : 4;
     const size_t lds = (size_t)g.S16 * 4 * 64 * sizeof(uint4) + (size_t)g.S16 * 16 * 4 * sizeof(float) +
-                       4 * 64 * 4 * sizeof(uint2) + (4 * 2 * 32 + kSearchRows) * sizeof(uint32_t);
+                       (size_t)waves * 64 * 4 * sizeof(uint2) + ((size_t)waves * 2 * 32 + kSearchRows) * sizeof(uint32_t);
     // more than the 64 KiB a kernel gets by default once S > 208: raise the kernel's limit, once per device
     static bool raised[64] = {};
     int device = 0;
@@ -469,14 +474,20 @@ hipError_t launch_search(const Geometry &g, const WorkspaceOffsets &wo, const En
     if (err != hipSuccess)
         return err;
     if (device < 0 || device >= 64 || !raised[device]) {
-        err = hipFuncSetAttribute(reinterpret_cast<const void *>(k_search),
+        err = hipFuncSetAttribute(reinterpret_cast<const void *>(k_search<4>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (err == hipSuccess)
+            err = hipFuncSetAttribute(reinterpret_cast<const void *>(k_search<8>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (err != hipSuccess)
             return err;
         if (device >= 0 && device < 64)
             raised[device] = true;
     }
-    hipLaunchKernelGGL(k_search, grid, dim3(kThreads), lds, stream, g, wo, batch);
+    if (waves == 8)
+        hipLaunchKernelGGL(k_search<8>, grid, dim3(512), lds, stream, g, wo, batch);
+    else
+        hipLaunchKernelGGL(k_search<4>, grid, dim3(256), lds, stream, g, wo, batch);
     return hipGetLastError();
 }
 
