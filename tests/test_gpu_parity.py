@@ -141,6 +141,55 @@ def test_llama3_8b_32k_layer_sampled():
     assert stats["near_ties"] < 1e-3 * stats["chunks"]
 
 
+def test_llama3_8b_32k_in_the_bench_launch_configuration():
+    """The launches bench.py times: 32 full-size tensors per hqmq_encode_batch / hqmq_decode_batch
+    launch.  One of them (slot 21 = layer 10, V) is checked against the oracle like the single-tensor
+    test above (O(n) steps on all rows, the search on sampled rows, decode of the GPU's bytes); every
+    tensor of the launch must carry its own, not a neighbour's, data: slot 4 is compared with a
+    single-tensor encode of the same input."""
+    wl = workloads.WORKLOADS["llama3_8b_32k"]
+    n = 32
+    cb = hq.hqmq_build_codebooks(0, n // 2, wl.H, wl.S)
+    slot = 21
+    x_cpu = workloads.make_tensor(wl, slot // 2, slot % 2, "cpu")
+    xs, secs = [], []
+    for i in range(n):
+        xs.append(x_cpu.to(DEV) if i == slot else workloads.make_tensor(wl, i // 2, i % 2, DEV))
+        secs.append(cb[i // 2, i % 2].contiguous().to(DEV))
+    params = hq.params_for(xs[0], wl.S, wl.b_r, wl.C)
+    encs = [hq.alloc_encoded(params, DEV) for _ in range(n)]
+    ws = hq.alloc_batch_workspace(params, n, DEV)
+    ws.fill_(0xAB)
+    hq.hqmq_encode_batch(hq.EncodeBatch(params, xs, secs, encs, ws))
+    outs = [torch.full_like(x, float("nan")) for x in xs]
+    hq.hqmq_decode_batch(hq.DecodeBatch(params, encs, secs, outs))
+    torch.cuda.synchronize()
+
+    # slot 4 against a single-tensor call
+    single = gpu_encode(xs[4], secs[4], wl.b_r, wl.C)
+    assert torch.equal(encs[4].codes, single.bufs.codes) and torch.equal(encs[4].flags, single.bufs.flags)
+    assert torch.equal(encs[4].row_off, single.bufs.row_off) and torch.equal(encs[4].n_outliers, single.bufs.n_outliers)
+    assert np.array_equal(outs[4].cpu().numpy().view(np.uint16), gpu_decode(params, single.bufs, secs[4], xs[4]))
+
+    # slot 21 against the oracle
+    from gpu_util import GpuEncoded
+    b = encs[slot]
+    n_out = b.n_outliers.cpu().numpy().view(np.uint32)
+    total = int(n_out[-1])
+    g = GpuEncoded(params, b, b.codes.cpu().numpy().view(np.uint32), b.sigma.cpu().numpy().view(np.uint16),
+                   b.flags.cpu().numpy().view(np.uint32), b.row_off.cpu().numpy().view(np.uint32), n_out,
+                   b.outliers[:total].cpu().numpy().view(np.uint16).reshape(total, 4),
+                   int(b.status.cpu().numpy().view(np.uint32)[0]))
+    sec = cb[slot // 2, slot % 2].numpy()
+    xb = _bits(x_cpu)
+    rows = workloads.sample_rows(wl, 32, 32, 96, seed=5).numpy()
+    e = oracle.encode(xb, sec, b_r=wl.b_r, Cmul=wl.C, rows=rows)
+    stats = compare_encode(g, e, xb, sec)
+    want, r_hat = oracle.decode(g.codes, g.sigma, g.flags, g.row_off, g.outliers, sec, wl.B, wl.H, wl.T, wl.b_r, True)
+    stats["decode_rel_err"] = compare_decode(outs[slot].cpu().numpy().view(np.uint16), want, r_hat, e.flag)
+    print(stats, flush=True)
+
+
 @pytest.mark.parametrize("name,layer,role", [
     ("mistral7b_outlier", 5, 0),     # [4, 8, 8192, 128], S = 64: batch > 1, hot channels (about 10 % outliers)
     ("qwen25_7b_heavy", 2, 0),       # [1, 4, 32768, 128], S = 256: hot channels + heavy-tailed spikes
