@@ -71,7 +71,7 @@ static Geometry make_geometry(const hqmq_params *p)
 }
 
 struct WorkspaceLayout {
-    uint64_t state, thr, hist0, hist1, cand_count, cand, block_sum, block_pre, total;
+    uint64_t state, thr, hist0, hist1, cand_count, cand, block_sum, block_pre, aop, total;
 };
 
 static WorkspaceLayout workspace_layout(const Geometry &g)
@@ -92,6 +92,7 @@ static WorkspaceLayout workspace_layout(const Geometry &g)
     l.cand = take((uint64_t)g.H * kCandCap * sizeof(unsigned long long));
     l.block_sum = take(n_blocks * sizeof(uint32_t));
     l.block_pre = take(n_blocks * sizeof(uint32_t));
+    l.aop = take((uint64_t)g.H * g.S16 * 4 * 64 * 16);
     l.total = off;
     return l;
 }
@@ -183,6 +184,7 @@ static WorkspaceOffsets workspace_offsets(const WorkspaceLayout &l)
     o.cand = (uint32_t)l.cand;
     o.block_sum = (uint32_t)l.block_sum;
     o.block_pre = (uint32_t)l.block_pre;
+    o.aop = (uint32_t)l.aop;
     return o;
 }
 

@@ -51,6 +51,7 @@ struct Workspace {
     unsigned long long *cand;      // [H][kCandCap]
     uint32_t *block_sum;           // [B*H*n_search_blocks_per_seg] outliers per search workgroup
     uint32_t *block_pre;           // same shape, exclusive prefix
+    uint4 *aop;                    // [H][4 * S16][64] MFMA A operands of the search, built once per call
 };
 
 struct EncodedPtrs {
@@ -65,7 +66,7 @@ struct EncodedPtrs {
 
 // Byte offsets of the workspace parts inside one tensor's slice (same for every tensor of a shape).
 struct WorkspaceOffsets {
-    uint32_t state, thr, hist0, hist1, cand_count, cand, block_sum, block_pre;
+    uint32_t state, thr, hist0, hist1, cand_count, cand, block_sum, block_pre, aop;
 };
 
 // One tensor of an encode batch and the batch itself (passed by value as kernel arguments; every
@@ -94,6 +95,7 @@ __device__ __forceinline__ Workspace carve_workspace(char *base, const Workspace
     ws.cand = reinterpret_cast<unsigned long long *>(base + o.cand);
     ws.block_sum = reinterpret_cast<uint32_t *>(base + o.block_sum);
     ws.block_pre = reinterpret_cast<uint32_t *>(base + o.block_pre);
+    ws.aop = reinterpret_cast<uint4 *>(base + o.aop);
     return ws;
 }
 

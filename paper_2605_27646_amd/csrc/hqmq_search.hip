@@ -138,10 +138,52 @@ __device__ __forceinline__ int nearest_primary(float v0, float v1, float v2, flo
 // Dynamic LDS layout:
 //   amat  [4*S16][64] x 16 B   MFMA A operands: lane l of s-block sb holds the parts of
 //                              A[row l%16][k l/16], row 4g+i = component i of v for secondary 4 sb + g
+//                              (copied from the table k_prepare_operands built for the head)
 //   secl  [16*S16][4] f32      the head's secondaries (zero padded to a multiple of 16)
 //   ubuf  [kWaves][64][4] x 8 B   parts (h, l, m, 0) of the unit directions of the wave's 64 chunks
 //   pack  [kWaves][2][32] u32 row code words being assembled
 //   rcnt  [kSearchRows] u32    outliers per row of the workgroup
+// The search's MFMA A operands of every head, built once per call into the workspace (the workgroups
+// of the search then only copy their head's table into LDS).  grid = (ceil(4 S16 64 / 256), H, tensors).
+__global__ __launch_bounds__(kThreads) void k_prepare_operands(Geometry g, WorkspaceOffsets wo, EncodeBatch batch)
+{
+    const EncodeTensor &tn = batch.t[blockIdx.z];
+    const Workspace ws = carve_workspace(tn.ws, wo);
+    const int h = blockIdx.y;
+    const float *sec_h = tn.sec + (size_t)h * g.S * 4;
+    uint4 *dst = ws.aop + (size_t)h * g.S16 * 4 * 64;
+    {
+        const int idx = blockIdx.x * kThreads + threadIdx.x;
+        if (idx >= g.S16 * 4 * 64)
+            return;
+        int sb = idx >> 6, l = idx & 63;
+        int row = l & 15, k = l >> 4;
+        int gsub = row >> 2, i = row & 3;
+        const int sidx = 4 * sb + gsub;
+        float a = 0.f, bq = 0.f, c = 0.f, d = 0.f;  // zero rows pad S up to a multiple of 16
+        if (sidx < g.S) {
+            const float *q = sec_h + 4 * sidx;
+            a = q[0], bq = q[1], c = q[2], d = q[3];
+        }
+        // v = u (x) conj(q):  v0 =  a u0 + b u1 + c u2 + d u3
+        //                     v1 = -b u0 + a u1 - d u2 + c u3
+        //                     v2 = -c u0 + d u1 + a u2 - b u3
+        //                     v3 = -d u0 - c u1 + b u2 + a u3
+        float val;
+        if (i == 0)
+            val = (k == 0) ? a : (k == 1) ? bq : (k == 2) ? c : d;
+        else if (i == 1)
+            val = (k == 0) ? -bq : (k == 1) ? a : (k == 2) ? -d : c;
+        else if (i == 2)
+            val = (k == 0) ? -c : (k == 1) ? d : (k == 2) ? a : -bq;
+        else
+            val = (k == 0) ? -d : (k == 1) ? -c : (k == 2) ? bq : a;
+        const Parts pa = split3(val * kOperandScale);
+        dst[idx] = make_uint4(pack2(pa.h, pa.h), pack2(pa.l, pa.l), pack2(pa.h, pa.m), pack2(pa.l, pa.m));
+    }
+
+}
+
 // kWaves: 4, or 8 when the A operands are so large (S > 256) that only one workgroup fits a CU: twice
 // the waves then share them and keep two waves on every SIMD.
 template <int kWaves>
@@ -174,28 +216,10 @@ __global__ __launch_bounds__(64 * kWaves) void k_search(Geometry g, WorkspaceOff
             q = *reinterpret_cast<const float4_t *>(sec_h + 4 * s);
         *reinterpret_cast<float4_t *>(secl + 4 * s) = q;
     }
-    __syncthreads();
-    for (int idx = tid; idx < g.S16 * 4 * 64; idx += kThreadsS) {
-        int sb = idx >> 6, l = idx & 63;
-        int row = l & 15, k = l >> 4;
-        int gsub = row >> 2, i = row & 3;
-        const float *q = secl + 4 * (4 * sb + gsub);
-        float a = q[0], bq = q[1], c = q[2], d = q[3];
-        // v = u (x) conj(q):  v0 =  a u0 + b u1 + c u2 + d u3
-        //                     v1 = -b u0 + a u1 - d u2 + c u3
-        //                     v2 = -c u0 + d u1 + a u2 - b u3
-        //                     v3 = -d u0 - c u1 + b u2 + a u3
-        float val;
-        if (i == 0)
-            val = (k == 0) ? a : (k == 1) ? bq : (k == 2) ? c : d;
-        else if (i == 1)
-            val = (k == 0) ? -bq : (k == 1) ? a : (k == 2) ? -d : c;
-        else if (i == 2)
-            val = (k == 0) ? -c : (k == 1) ? d : (k == 2) ? a : -bq;
-        else
-            val = (k == 0) ? -d : (k == 1) ? -c : (k == 2) ? bq : a;
-        const Parts pa = split3(val * kOperandScale);
-        amat[idx] = make_uint4(pack2(pa.h, pa.h), pack2(pa.l, pa.l), pack2(pa.h, pa.m), pack2(pa.l, pa.m));
+    {
+        const uint4 *src = ws.aop + (size_t)h * g.S16 * 4 * 64;
+        for (int idx = tid; idx < g.S16 * 4 * 64; idx += kThreadsS)
+            amat[idx] = src[idx];
     }
 
     __syncthreads();
@@ -484,6 +508,8 @@ hipError_t launch_search(const Geometry &g, const WorkspaceOffsets &wo, const En
         if (device >= 0 && device < 64)
             raised[device] = true;
     }
+    hipLaunchKernelGGL(k_prepare_operands, dim3((g.S16 * 4 * 64 + kThreads - 1) / kThreads, g.H, (unsigned)n_tensors),
+                       dim3(kThreads), 0, stream, g, wo, batch);
     if (waves == 8)
         hipLaunchKernelGGL(k_search<8>, grid, dim3(512), lds, stream, g, wo, batch);
     else
