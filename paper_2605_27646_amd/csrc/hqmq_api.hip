@@ -66,7 +66,8 @@ static Geometry make_geometry(const hqmq_params *p)
     for (int j = 0; j < 16; ++j)
         if ((1 << j) == p->S)
             g.log2_S = j;
-    g.n_search_blocks_per_seg = (uint32_t)((p->T + kSearchRows - 1) / kSearchRows);
+    g.search_rows = p->T >= kSearchRowsSwitch ? kSearchRowsLarge : kSearchRowsSmall;
+    g.n_search_blocks_per_seg = (uint32_t)((p->T + g.search_rows - 1) / g.search_rows);
     return g;
 }
 

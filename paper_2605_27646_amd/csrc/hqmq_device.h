@@ -10,7 +10,9 @@
 namespace hqmq {
 
 constexpr int kChunksPerRow = 32;    // D = 128
-constexpr int kSearchRows = 64;      // rows per search workgroup = granularity of the outlier scan
+constexpr int kSearchRowsSmall = 64;   // rows per search workgroup = granularity of the outlier scan:
+constexpr int kSearchRowsLarge = 256;  // 64 for short segments (more workgroups), 256 from 2048 rows on
+constexpr int kSearchRowsSwitch = 2048;
 constexpr int kThreads = 256;        // default workgroup: 4 wave64
 
 // Radix select over the 63 value bits of a non-negative IEEE double: two histogram digits from
@@ -38,7 +40,8 @@ struct Geometry {
     float inv_L;          // 1 / (2^b_r - 1)
     int32_t log2_S;       // log2(S) when S is a power of two, else -1
     float inv_S;          // (1/S)(1 + 2^-18): uint(float(k) * inv_S) == k / S for every k < 48 S, S <= 512
-    uint32_t n_search_blocks_per_seg;  // ceil(T / kSearchRows)
+    int32_t search_rows;               // rows per search workgroup (kSearchRowsSmall or kSearchRowsLarge)
+    uint32_t n_search_blocks_per_seg;  // ceil(T / search_rows)
 };
 
 // Workspace carve-up (device pointers into the caller's workspace).

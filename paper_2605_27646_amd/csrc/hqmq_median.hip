@@ -336,7 +336,7 @@ __global__ __launch_bounds__(kThreads) void k_gather(Geometry g, WorkspaceOffset
         return;
     const int64_t R = (int64_t)seg * g.T + t;
     uint32_t word = enc.flags[R];
-    const uint32_t off = enc.row_off[R] + ws.block_pre[(size_t)seg * g.n_search_blocks_per_seg + t / kSearchRows];
+    const uint32_t off = enc.row_off[R] + ws.block_pre[(size_t)seg * g.n_search_blocks_per_seg + t / g.search_rows];
     enc.row_off[R] = off;
     if (!word)
         return;

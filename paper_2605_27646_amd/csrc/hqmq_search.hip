@@ -21,7 +21,7 @@
 // compare-and-select per group, and the winner inside the winning group is found afterwards by
 // re-scoring its 4 candidates once per chunk.
 //
-// Work split: a workgroup (4 wave64) owns kSearchRows rows of one (b, h) segment, so the A
+// Work split: a workgroup (4 wave64) owns 64 or 256 rows of one (b, h) segment, so the A
 // matrices of the head sit in LDS once per workgroup.  A wave takes two rows (64 chunks, one per
 // lane) at a time and runs them as four 16-chunk MFMA column groups.
 #include "hqmq_device.h"
@@ -142,7 +142,7 @@ __device__ __forceinline__ int nearest_primary(float v0, float v1, float v2, flo
 //   secl  [16*S16][4] f32      the head's secondaries (zero padded to a multiple of 16)
 //   ubuf  [kWaves][64][4] x 8 B   parts (h, l, m, 0) of the unit directions of the wave's 64 chunks
 //   pack  [kWaves][2][32] u32 row code words being assembled
-//   rcnt  [kSearchRows] u32    outliers per row of the workgroup
+//   rcnt  [search_rows] u32    outliers per row of the workgroup
 // The search's MFMA A operands of every head, built once per call into the workspace (the workgroups
 // of the search then only copy their head's table into LDS).  grid = (ceil(4 S16 64 / 256), H, tensors).
 __global__ __launch_bounds__(kThreads) void k_prepare_operands(Geometry g, WorkspaceOffsets wo, EncodeBatch batch)
@@ -186,7 +186,7 @@ __global__ __launch_bounds__(kThreads) void k_prepare_operands(Geometry g, Works
 
 // kWaves: 4, or 8 when the A operands are so large (S > 256) that only one workgroup fits a CU: twice
 // the waves then share them and keep two waves on every SIMD.
-template <int kWaves>
+template <int kWaves, int kRows>
 __global__ __launch_bounds__(64 * kWaves) void k_search(Geometry g, WorkspaceOffsets wo, EncodeBatch batch)
 {
     constexpr int kThreadsS = 64 * kWaves;
@@ -205,7 +205,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_search(Geometry g, WorkspaceOff
     const int tid = threadIdx.x, lane = tid & 63;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, and known to be
     const int seg = blockIdx.y, b = seg / g.H, h = seg % g.H;
-    const int t0 = blockIdx.x * kSearchRows;
+    const int t0 = blockIdx.x * kRows;
     const int64_t row0 = (int64_t)seg * g.T;  // linear index of the segment's first row
     const float *sec_h = sec + (size_t)h * g.S * 4;
 
@@ -231,7 +231,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_search(Geometry g, WorkspaceOff
     uint32_t *my_pack = pack + wv * 64;
     const _Float16 *base = x + (int64_t)b * g.sb + (int64_t)h * g.sh + 4 * c;
 
-    for (int it = 0; it < kSearchRows / (2 * kWaves); ++it) {
+    for (int it = 0; it < kRows / (2 * kWaves); ++it) {
         const int r_in_block = it * 2 * kWaves + wv * 2 + half_id;
         const int t = t0 + r_in_block;
         const bool valid = t < g.T;
@@ -469,28 +469,34 @@ __global__ __launch_bounds__(64 * kWaves) void k_search(Geometry g, WorkspaceOff
     // scan / gather kernels that follow --------------------------------------------------------------
     __syncthreads();
     if (wv == 0) {
-        const uint32_t cnt = rcnt[lane];
-        uint32_t inc = cnt;
+        uint32_t carry = 0;
 #pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            uint32_t o = __shfl_up(inc, d, 64);
-            if (lane >= d)
-                inc += o;
+        for (int part = 0; part < kRows / 64; ++part) {
+            const int r = 64 * part + lane;
+            const uint32_t cnt = rcnt[r];
+            uint32_t inc = cnt;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                uint32_t o = __shfl_up(inc, d, 64);
+                if (lane >= d)
+                    inc += o;
+            }
+            if (t0 + r < g.T)
+                enc.row_off[row0 + t0 + r] = carry + inc - cnt;
+            carry += __shfl(inc, 63, 64);
         }
-        if (t0 + lane < g.T)
-            enc.row_off[row0 + t0 + lane] = inc - cnt;
-        if (lane == 63)
-            ws.block_sum[(size_t)seg * g.n_search_blocks_per_seg + blockIdx.x] = inc;
+        if (lane == 0)
+            ws.block_sum[(size_t)seg * g.n_search_blocks_per_seg + blockIdx.x] = carry;
     }
 }
 
 hipError_t launch_search(const Geometry &g, const WorkspaceOffsets &wo, const EncodeBatch &batch, int n_tensors,
                          hipStream_t stream)
 {
-    dim3 grid((g.T + kSearchRows - 1) / kSearchRows, g.B * g.H, (unsigned)n_tensors);
+    dim3 grid((g.T + g.search_rows - 1) / g.search_rows, g.B * g.H, (unsigned)n_tensors);
     const int waves = g.S16 > 16 ? 8 : 4;
     const size_t lds = (size_t)g.S16 * 4 * 64 * sizeof(uint4) + (size_t)g.S16 * 16 * 4 * sizeof(float) +
-                       (size_t)waves * 64 * 4 * sizeof(uint2) + ((size_t)waves * 2 * 32 + kSearchRows) * sizeof(uint32_t);
+                       (size_t)waves * 64 * 4 * sizeof(uint2) + ((size_t)waves * 2 * 32 + (size_t)g.search_rows) * sizeof(uint32_t);
     // more than the 64 KiB a kernel gets by default once S > 208: raise the kernel's limit, once per device
     static bool raised[64] = {};
     int device = 0;
@@ -498,11 +504,12 @@ hipError_t launch_search(const Geometry &g, const WorkspaceOffsets &wo, const En
     if (err != hipSuccess)
         return err;
     if (device < 0 || device >= 64 || !raised[device]) {
-        err = hipFuncSetAttribute(reinterpret_cast<const void *>(k_search<4>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (err == hipSuccess)
-            err = hipFuncSetAttribute(reinterpret_cast<const void *>(k_search<8>),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        const void *variants[4] = {reinterpret_cast<const void *>(k_search<4, kSearchRowsSmall>),
+                                   reinterpret_cast<const void *>(k_search<4, kSearchRowsLarge>),
+                                   reinterpret_cast<const void *>(k_search<8, kSearchRowsSmall>),
+                                   reinterpret_cast<const void *>(k_search<8, kSearchRowsLarge>)};
+        for (int i = 0; i < 4 && err == hipSuccess; ++i)
+            err = hipFuncSetAttribute(variants[i], hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (err != hipSuccess)
             return err;
         if (device >= 0 && device < 64)
@@ -510,10 +517,15 @@ hipError_t launch_search(const Geometry &g, const WorkspaceOffsets &wo, const En
     }
     hipLaunchKernelGGL(k_prepare_operands, dim3((g.S16 * 4 * 64 + kThreads - 1) / kThreads, g.H, (unsigned)n_tensors),
                        dim3(kThreads), 0, stream, g, wo, batch);
-    if (waves == 8)
-        hipLaunchKernelGGL(k_search<8>, grid, dim3(512), lds, stream, g, wo, batch);
+    const bool large = g.search_rows == kSearchRowsLarge;
+    if (waves == 8 && large)
+        hipLaunchKernelGGL((k_search<8, kSearchRowsLarge>), grid, dim3(512), lds, stream, g, wo, batch);
+    else if (waves == 8)
+        hipLaunchKernelGGL((k_search<8, kSearchRowsSmall>), grid, dim3(512), lds, stream, g, wo, batch);
+    else if (large)
+        hipLaunchKernelGGL((k_search<4, kSearchRowsLarge>), grid, dim3(256), lds, stream, g, wo, batch);
     else
-        hipLaunchKernelGGL(k_search<4>, grid, dim3(256), lds, stream, g, wo, batch);
+        hipLaunchKernelGGL((k_search<4, kSearchRowsSmall>), grid, dim3(256), lds, stream, g, wo, batch);
     return hipGetLastError();
 }
 
