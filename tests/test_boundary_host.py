@@ -177,3 +177,14 @@ def test_binding_refuses_host_tensors(lib):
         hq.hqmq_encode(p, x, torch.zeros(2, 16, 4), None, None)
     with pytest.raises(ValueError):
         hq.params_for(x[..., ::2], 16)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The measured path is single-GPU: bench.py --gpus N > 1 must say so and exit non-zero
+    (checked before anything touches a GPU)."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True,
+                       text=True, timeout=120)
+    assert r.returncode != 0
+    assert "single-GPU" in r.stderr and r.stdout.strip() == ""
