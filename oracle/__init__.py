@@ -20,7 +20,21 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "hqmq_oracle.c")
 _LIB = os.path.join(_HERE, "libhqmq_oracle.so")
 
-NC = 32  # chunks per packed row (D = 128)
+NC = 32  # most chunks a packed row may have (head dimension 128)
+
+
+def chunks_per_row(D: int) -> int:
+    """Quaternion chunks of a head vector of D elements: ceil(D / 4); a head dimension that is not
+    a multiple of 4 is zero-padded to the next one (App. "Padding wrapper for d_h not divisible by 4")."""
+    nc = (int(D) + 3) // 4
+    if not 1 <= nc <= NC:
+        raise ValueError("the oracle packs rows of 1..128 elements")
+    return nc
+
+
+def row_words(D: int, w: int) -> int:
+    """32-bit words of one packed row: ceil(chunks * w / 32)."""
+    return (chunks_per_row(D) * w + 31) // 32
 
 
 def build(force: bool = False) -> str:
@@ -75,10 +89,10 @@ def _declare(L):
     L.hqo_flags.argtypes = [_f64p, _f64p, C.c_float, C.c_int, C.c_int, C.c_int, C.c_int,
                             C.c_int, _u8p]
     L.hqo_extract_outliers.restype = C.c_int64
-    L.hqo_extract_outliers.argtypes = [_u16p, _u8p, C.c_int, C.c_int, C.c_int, _u32p, _u32p,
+    L.hqo_extract_outliers.argtypes = [_u16p, _u8p, C.c_int, C.c_int, C.c_int, C.c_int, _u32p, _u32p,
                                        _u32p, _u16p, C.c_int64]
     L.hqo_row_sigma.restype = None
-    L.hqo_row_sigma.argtypes = [_f64p, _u8p, C.c_int64, _u16p]
+    L.hqo_row_sigma.argtypes = [_f64p, _u8p, C.c_int64, C.c_int, _u16p]
     L.hqo_score.restype = C.c_double
     L.hqo_score.argtypes = [_u16p, _f32p, C.c_int, C.c_int]
     L.hqo_search_chunk.restype = None
@@ -89,23 +103,23 @@ def _declare(L):
     L.hqo_index_bits.restype = C.c_int
     L.hqo_index_bits.argtypes = [C.c_int]
     L.hqo_search_rows.restype = None
-    L.hqo_search_rows.argtypes = [_u16p, _u8p, _u16p, _f32p, C.c_int, C.c_int, C.c_int,
+    L.hqo_search_rows.argtypes = [_u16p, _u8p, _u16p, _f32p, C.c_int, C.c_int, C.c_int, C.c_int,
                                   C.c_int, C.c_int, C.c_void_p, _i32p, _f64p, _f64p, _i32p]
     L.hqo_pack_row.restype = None
-    L.hqo_pack_row.argtypes = [_u32p, C.c_int, _u32p]
+    L.hqo_pack_row.argtypes = [_u32p, C.c_int, C.c_int, _u32p]
     L.hqo_unpack_row.restype = None
-    L.hqo_unpack_row.argtypes = [_u32p, C.c_int, _u32p]
+    L.hqo_unpack_row.argtypes = [_u32p, C.c_int, C.c_int, _u32p]
     L.hqo_pack_rows.restype = None
-    L.hqo_pack_rows.argtypes = [_i32p, _i32p, _u8p, C.c_int64, C.c_int, C.c_int, _u32p]
+    L.hqo_pack_rows.argtypes = [_i32p, _i32p, _u8p, C.c_int64, C.c_int, C.c_int, C.c_int, _u32p]
     L.hqo_decode64.restype = None
     L.hqo_decode64.argtypes = [_u32p, _u16p, _u32p, _u32p, _u16p, _f32p, C.c_int, C.c_int,
-                               C.c_int, C.c_int, C.c_int, _u16p, C.c_void_p, _f64p]
+                               C.c_int, C.c_int, C.c_int, C.c_int, _u16p, C.c_void_p, _f64p]
     L.hqo_attend.restype = None
     L.hqo_attend.argtypes = [_u16p, _f64p, _f64p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                              C.c_double, _u16p, _f64p]
     L.hqo_decode.restype = None
     L.hqo_decode.argtypes = [_u32p, _u16p, _u32p, _u32p, _u16p, _f32p, C.c_int, C.c_int,
-                             C.c_int, C.c_int, C.c_int, _u16p, C.c_void_p]
+                             C.c_int, C.c_int, C.c_int, C.c_int, _u16p, C.c_void_p]
 
 
 # --------------------------------------------------------------------------------------
@@ -205,28 +219,30 @@ def radius_code(r2: float, sigma16: int, b_r: int) -> int:
 
 
 def pack_row(code32, w: int) -> np.ndarray:
+    """Pack the codes of one row (as many chunks as code32 has entries, at most 32)."""
     code32 = np.ascontiguousarray(code32, np.uint32)
-    words = np.zeros(w, np.uint32)
-    lib().hqo_pack_row(code32, w, words)
+    nc = code32.size
+    words = np.zeros((nc * w + 31) // 32, np.uint32)
+    lib().hqo_pack_row(code32, nc, w, words)
     return words
 
 
-def unpack_row(words, w: int) -> np.ndarray:
+def unpack_row(words, w: int, nc: int = NC) -> np.ndarray:
     words = np.ascontiguousarray(words, np.uint32)
-    code32 = np.zeros(NC, np.uint32)
-    lib().hqo_unpack_row(words, w, code32)
+    code32 = np.zeros(nc, np.uint32)
+    lib().hqo_unpack_row(words, nc, w, code32)
     return code32
 
 
-def unpack_rows(codes: np.ndarray, S: int, b_r: int):
-    """codes [rows][w] -> (k [rows][32], r_q [rows][32]) with the oracle's bit layout."""
+def unpack_rows(codes: np.ndarray, S: int, b_r: int, nc: int = NC):
+    """codes [rows][row_words] -> (k [rows][nc], r_q [rows][nc]) with the oracle's bit layout."""
     w_idx = index_bits(S)
     w = w_idx + b_r
-    codes = np.ascontiguousarray(codes, np.uint32).reshape(-1, w)
-    k = np.zeros((codes.shape[0], NC), np.int64)
-    rq = np.zeros((codes.shape[0], NC), np.int64)
+    codes = np.ascontiguousarray(codes, np.uint32).reshape(-1, (nc * w + 31) // 32)
+    k = np.zeros((codes.shape[0], nc), np.int64)
+    rq = np.zeros((codes.shape[0], nc), np.int64)
     for i in range(codes.shape[0]):
-        c = unpack_row(codes[i], w).astype(np.int64)
+        c = unpack_row(codes[i], w, nc).astype(np.int64)
         k[i] = c & ((1 << w_idx) - 1)
         rq[i] = c >> w_idx
     return k, rq
@@ -245,64 +261,68 @@ class Encoded:
     D: int
     S: int
     b_r: int
-    r2: np.ndarray          # [rows, 32] fp64 squared norms
+    r2: np.ndarray          # [rows, Nc] fp64 squared norms (Nc = ceil(D / 4) chunks per row)
     m2: np.ndarray          # [H] lower median of r2 per head
-    flag: np.ndarray        # [rows, 32] uint8
+    flag: np.ndarray        # [rows, Nc] uint8
     flags: np.ndarray       # [rows] uint32 flag words
     row_off: np.ndarray     # [rows + 1] uint32
     n_out: np.ndarray       # [H + 1] uint32
     outliers: np.ndarray    # [n_out[H], 4] uint16 (fp16 bit patterns)
     sigma: np.ndarray       # [rows] uint16 (fp16 bit patterns)
-    k: np.ndarray           # [rows, 32] int32, -1 where flagged / not searched
-    rq: np.ndarray          # [rows, 32] int32, -1 where flagged / not searched
-    best: np.ndarray        # [rows, 32] fp64 best score
-    second: np.ndarray      # [rows, 32] fp64 runner-up score
-    codes: np.ndarray       # [rows, w] uint32
+    k: np.ndarray           # [rows, Nc] int32, -1 where flagged / not searched
+    rq: np.ndarray          # [rows, Nc] int32, -1 where flagged / not searched
+    best: np.ndarray        # [rows, Nc] fp64 best score
+    second: np.ndarray      # [rows, Nc] fp64 runner-up score
+    codes: np.ndarray       # [rows, ceil(Nc w / 32)] uint32
     searched: np.ndarray    # [rows] bool
 
 
 def encode(x_bits: np.ndarray, sec: np.ndarray, b_r: int = 6, Cmul: float = 3.0,
            use_outliers: bool = True, rows=None, thresholds=None) -> Encoded:
-    """Encode one fp16 tensor [B, H, T, 128] (uint16 bit patterns) against the secondary
-    codebooks sec [H, S, 4] (fp32) of its (layer, role).  `rows`: optional boolean mask or
+    """Encode one fp16 tensor [B, H, T, D] (uint16 bit patterns), D <= 128, against the secondary
+    codebooks sec [H, S, 4] (fp32) of its (layer, role).  A D that is not a multiple of 4 is
+    zero-padded to the next one first (App. "Padding wrapper for d_h not divisible by 4").  `rows`: optional boolean mask or
     index list of the rows whose (expensive) search is run; the O(n) steps always cover the
     whole tensor.  `thresholds`: fp64 [H] on squared norms, supplied instead of the batch's
     own C^2 * median (the incremental setting: a chunk is flagged iff r^2 > thresholds[h])."""
     L = lib()
     x_bits = np.ascontiguousarray(x_bits, np.uint16)
     B, H, T, D = x_bits.shape
-    if D != 4 * NC:
-        raise ValueError("the packed-row oracle is written for D = 128")
+    nc = chunks_per_row(D)
+    if D != 4 * nc:
+        padded = np.zeros((B, H, T, 4 * nc), np.uint16)  # +0.0 in the missing elements
+        padded[..., :D] = x_bits
+        x_bits = padded
     sec = np.ascontiguousarray(sec, np.float32)
     assert sec.shape[0] == H and sec.shape[2] == 4
     S = sec.shape[1]
     n_rows = B * H * T
-    n_chunks = n_rows * NC
+    n_chunks = n_rows * nc
     flat = x_bits.reshape(-1)
 
     r2 = np.zeros(n_chunks)
     L.hqo_norm2(flat, n_chunks, r2)
     m2 = np.zeros(H)
-    L.hqo_head_medians(r2, B, H, T, NC, m2)
+    L.hqo_head_medians(r2, B, H, T, nc, m2)
     flag = np.zeros(n_chunks, np.uint8)
     if thresholds is None:
-        L.hqo_flags(r2, m2, float(Cmul), int(bool(use_outliers)), B, H, T, NC, flag)
+        L.hqo_flags(r2, m2, float(Cmul), int(bool(use_outliers)), B, H, T, nc, flag)
     else:
         # the flag rule compares against fl(fl(C C) m): with C = 1 that is m itself
-        L.hqo_flags(r2, np.ascontiguousarray(thresholds, np.float64), 1.0, 1, B, H, T, NC, flag)
+        L.hqo_flags(r2, np.ascontiguousarray(thresholds, np.float64), 1.0, 1, B, H, T, nc, flag)
 
     flags = np.zeros(n_rows, np.uint32)
     row_off = np.zeros(n_rows + 1, np.uint32)
     n_out = np.zeros(H + 1, np.uint32)
     cap = int(flag.sum())
     payload = np.zeros((max(cap, 1), 4), np.uint16)
-    total = L.hqo_extract_outliers(flat, flag, B, H, T, flags, row_off, n_out,
+    total = L.hqo_extract_outliers(flat, flag, B, H, T, nc, flags, row_off, n_out,
                                    payload.reshape(-1), cap)
     assert total == cap
     payload = payload[:cap]
 
     sigma = np.zeros(n_rows, np.uint16)
-    L.hqo_row_sigma(r2, flag, n_rows, sigma)
+    L.hqo_row_sigma(r2, flag, n_rows, nc, sigma)
 
     if rows is None:
         sel = None
@@ -319,26 +339,28 @@ def encode(x_bits: np.ndarray, sec: np.ndarray, b_r: int = 6, Cmul: float = 3.0,
     rq = np.zeros(n_chunks, np.int32)
     best = np.zeros(n_chunks)
     second = np.zeros(n_chunks)
-    L.hqo_search_rows(flat, flag, sigma, sec.reshape(-1), B, H, T, S, b_r,
+    L.hqo_search_rows(flat, flag, sigma, sec.reshape(-1), B, H, T, nc, S, b_r,
                       None if sel is None else sel.ctypes.data, k, best, second, rq)
 
     w = index_bits(S) + b_r
-    codes = np.zeros((n_rows, w), np.uint32)
-    L.hqo_pack_rows(k, rq, flag, n_rows, S, b_r, codes.reshape(-1))
+    codes = np.zeros((n_rows, (nc * w + 31) // 32), np.uint32)
+    L.hqo_pack_rows(k, rq, flag, n_rows, nc, S, b_r, codes.reshape(-1))
 
-    return Encoded(B, H, T, D, S, b_r, r2.reshape(n_rows, NC), m2, flag.reshape(n_rows, NC),
-                   flags, row_off, n_out, payload, sigma, k.reshape(n_rows, NC),
-                   rq.reshape(n_rows, NC), best.reshape(n_rows, NC),
-                   second.reshape(n_rows, NC), codes, searched)
+    return Encoded(B, H, T, D, S, b_r, r2.reshape(n_rows, nc), m2, flag.reshape(n_rows, nc),
+                   flags, row_off, n_out, payload, sigma, k.reshape(n_rows, nc),
+                   rq.reshape(n_rows, nc), best.reshape(n_rows, nc),
+                   second.reshape(n_rows, nc), codes, searched)
 
 
-def decode(codes, sigma, flags, row_off, outliers, sec, B, H, T, b_r, want_r_hat=False):
-    """Decode to fp16 bit patterns [B, H, T, 128]; optionally also r_hat [rows, 32]."""
+def decode(codes, sigma, flags, row_off, outliers, sec, B, H, T, b_r, want_r_hat=False, D=4 * NC):
+    """Decode to fp16 bit patterns [B, H, T, D] (the padding elements of a D that is not a multiple
+    of 4 are cut off again); optionally also r_hat [rows, ceil(D / 4)]."""
     sec = np.ascontiguousarray(sec, np.float32)
     S = sec.shape[1]
     n_rows = B * H * T
-    out = np.zeros(n_rows * NC * 4, np.uint16)
-    r_hat = np.zeros(n_rows * NC) if want_r_hat else None
+    nc = chunks_per_row(D)
+    out = np.zeros(n_rows * nc * 4, np.uint16)
+    r_hat = np.zeros(n_rows * nc) if want_r_hat else None
     outliers = np.ascontiguousarray(outliers, np.uint16).reshape(-1)
     if outliers.size == 0:
         outliers = np.zeros(4, np.uint16)
@@ -346,28 +368,29 @@ def decode(codes, sigma, flags, row_off, outliers, sec, B, H, T, b_r, want_r_hat
                      np.ascontiguousarray(sigma, np.uint16),
                      np.ascontiguousarray(flags, np.uint32),
                      np.ascontiguousarray(row_off, np.uint32), outliers, sec.reshape(-1),
-                     B, H, T, S, b_r, out, None if r_hat is None else r_hat.ctypes.data)
-    out = out.reshape(B, H, T, NC * 4)
+                     B, H, T, nc, S, b_r, out, None if r_hat is None else r_hat.ctypes.data)
+    out = np.ascontiguousarray(out.reshape(B, H, T, nc * 4)[..., :D])
     if want_r_hat:
-        return out, r_hat.reshape(n_rows, NC)
+        return out, r_hat.reshape(n_rows, nc)
     return out
 
 
-def decode64(codes, sigma, flags, row_off, outliers, sec, B, H, T, b_r) -> np.ndarray:
-    """Reconstruction before the final fp16 rounding, fp64 [B, H, T, 128] (outliers widened)."""
+def decode64(codes, sigma, flags, row_off, outliers, sec, B, H, T, b_r, D=4 * NC) -> np.ndarray:
+    """Reconstruction before the final fp16 rounding, fp64 [B, H, T, D] (outliers widened)."""
     sec = np.ascontiguousarray(sec, np.float32)
     S = sec.shape[1]
     n_rows = B * H * T
-    out16 = np.zeros(n_rows * NC * 4, np.uint16)
-    out64 = np.zeros(n_rows * NC * 4)
+    nc = chunks_per_row(D)
+    out16 = np.zeros(n_rows * nc * 4, np.uint16)
+    out64 = np.zeros(n_rows * nc * 4)
     outliers = np.ascontiguousarray(outliers, np.uint16).reshape(-1)
     if outliers.size == 0:
         outliers = np.zeros(4, np.uint16)
     lib().hqo_decode64(np.ascontiguousarray(codes, np.uint32).reshape(-1),
                        np.ascontiguousarray(sigma, np.uint16), np.ascontiguousarray(flags, np.uint32),
                        np.ascontiguousarray(row_off, np.uint32), outliers, sec.reshape(-1),
-                       B, H, T, S, b_r, out16, None, out64)
-    return out64.reshape(B, H, T, NC * 4)
+                       B, H, T, nc, S, b_r, out16, None, out64)
+    return np.ascontiguousarray(out64.reshape(B, H, T, nc * 4)[..., :D])
 
 
 def attend(q_bits: np.ndarray, K64: np.ndarray, V64: np.ndarray, scale: float):
@@ -399,3 +422,9 @@ def bits_per_element(S: int, b_r: int, d_h: int = 128, p: float | None = None,
     if p is not None:
         b = (1.0 - p) * b + 16.0 * p + 1.0 / 4.0
     return b
+
+
+def padding_overhead(d_h: int) -> float:
+    """Relative storage overhead of zero-padding a head of d_h elements to whole chunks:
+    ceil(d_h / 4) * 4 / d_h - 1 (App. "Padding wrapper for d_h not divisible by 4")."""
+    return chunks_per_row(d_h) * 4.0 / d_h - 1.0

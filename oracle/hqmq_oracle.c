@@ -29,16 +29,19 @@
  * compiled with -ffp-contract=off so the compiler cannot fuse or reorder it.
  *
  * Tensor layout: X is fp16 (passed as uint16 bit patterns) of logical shape
- * [B, H, T, D], D contiguous, D == 128 wherever rows are packed (32 chunks per row).
+ * [B, H, T, 4*Nc], last axis contiguous, 1 <= Nc <= 32 chunks per row (head dimensions 64,
+ * 96 and 128 of the paper's models give Nc = 16, 24, 32; a head dimension that is not a
+ * multiple of 4 is zero-padded to the next one by the caller and cut back after decode:
+ * App. "Padding wrapper for d_h not divisible by 4").
  * A "row" is one (b, h, t) vector; its linear index is (b*H + h)*T + t; chunk c of a row
- * is elements 4c .. 4c+3 and its linear chunk index is row*Nc + c, Nc = D/4.
+ * is elements 4c .. 4c+3 and its linear chunk index is row*Nc + c.
  */
 #include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
 
-#define HQO_NC 32 /* chunks per row wherever a row is packed (D = 128) */
+#define HQO_NC_MAX 32 /* most chunks a row may have (head dimension 128) */
 
 /* ------------------------------------------------------------------------------------
  * fp16 <-> fp64
@@ -265,7 +268,7 @@ void hqo_flags(const double *r2, const double *m2, float C, int use_outliers, in
  * prefix count per row (row_off has n_rows+1 entries), and the count per head
  * (n_out[0..H-1]) plus the total (n_out[H]).  Returns the total; writes at most `cap`
  * payload entries. */
-int64_t hqo_extract_outliers(const uint16_t *x, const uint8_t *flag, int B, int H, int T,
+int64_t hqo_extract_outliers(const uint16_t *x, const uint8_t *flag, int B, int H, int T, int Nc,
                              uint32_t *flag_words, uint32_t *row_off, uint32_t *n_out,
                              uint16_t *payload, int64_t cap)
 {
@@ -276,8 +279,8 @@ int64_t hqo_extract_outliers(const uint16_t *x, const uint8_t *flag, int B, int 
         int h = (int)((row / T) % H);
         uint32_t word = 0;
         row_off[row] = (uint32_t)count;
-        for (int c = 0; c < HQO_NC; ++c) {
-            int64_t chunk = row * HQO_NC + c;
+        for (int c = 0; c < Nc; ++c) {
+            int64_t chunk = row * Nc + c;
             if (flag[chunk]) {
                 word |= (uint32_t)1 << c;
                 if (count < cap)
@@ -296,12 +299,12 @@ int64_t hqo_extract_outliers(const uint16_t *x, const uint8_t *flag, int B, int 
 /* Per-row radius scale: the largest norm among the row's unflagged chunks ("per-token-max
  * scale", one fp16 per (b, h, t)), rounded to fp16 ties-to-even, saturating.  Outliers
  * are excluded because they are stored separately and would otherwise set the scale. */
-void hqo_row_sigma(const double *r2, const uint8_t *flag, int64_t n_rows, uint16_t *sigma16)
+void hqo_row_sigma(const double *r2, const uint8_t *flag, int64_t n_rows, int Nc, uint16_t *sigma16)
 {
     for (int64_t row = 0; row < n_rows; ++row) {
         double smax = 0.0;
-        for (int c = 0; c < HQO_NC; ++c) {
-            int64_t chunk = row * HQO_NC + c;
+        for (int c = 0; c < Nc; ++c) {
+            int64_t chunk = row * Nc + c;
             if (!flag[chunk]) {
                 double r = sqrt(r2[chunk]);
                 if (r > smax)
@@ -403,7 +406,7 @@ int hqo_index_bits(int S)
  * left at 0 for them.  The loop over rows is independent per row and is the only thing
  * parallelised (a plain parallel-for) so the oracle finishes in reasonable time. */
 void hqo_search_rows(const uint16_t *x, const uint8_t *flag, const uint16_t *sigma16,
-                     const float *sec_all /* [H][S][4] */, int B, int H, int T, int S, int b_r,
+                     const float *sec_all /* [H][S][4] */, int B, int H, int T, int Nc, int S, int b_r,
                      const uint8_t *sel, int32_t *k, double *best, double *second,
                      int32_t *rq)
 {
@@ -412,8 +415,8 @@ void hqo_search_rows(const uint16_t *x, const uint8_t *flag, const uint16_t *sig
     for (int64_t row = 0; row < n_rows; ++row) {
         int h = (int)((row / T) % H);
         const float *sec = sec_all + (int64_t)h * S * 4;
-        for (int c = 0; c < HQO_NC; ++c) {
-            int64_t chunk = row * HQO_NC + c;
+        for (int c = 0; c < Nc; ++c) {
+            int64_t chunk = row * Nc + c;
             k[chunk] = -1;
             rq[chunk] = -1;
             best[chunk] = 0.0;
@@ -430,15 +433,21 @@ void hqo_search_rows(const uint16_t *x, const uint8_t *flag, const uint16_t *sig
 
 /* ------------------------------------------------------------------------------------
  * Code words and their packing.  code = (r_q << w_idx) | k, width w = w_idx + b_r; a
- * flagged chunk carries code 0.  The 32 codes of a row are concatenated LSB first: chunk
- * c occupies bits [c*w, (c+1)*w) of the row's w little-endian 32-bit words.
+ * flagged chunk carries code 0.  The Nc codes of a row are concatenated LSB first: chunk
+ * c occupies bits [c*w, (c+1)*w) of the row's ceil(Nc*w/32) little-endian 32-bit words
+ * (w words when Nc = 32); the unused high bits of the last word are zero.
  * ---------------------------------------------------------------------------------- */
 
-void hqo_pack_row(const uint32_t *code32 /* [32] */, int w, uint32_t *words /* [w] */)
+int hqo_row_words(int Nc, int w)
 {
-    for (int i = 0; i < w; ++i)
+    return (Nc * w + 31) / 32;
+}
+
+void hqo_pack_row(const uint32_t *code32 /* [Nc] */, int Nc, int w, uint32_t *words /* [row_words] */)
+{
+    for (int i = 0; i < hqo_row_words(Nc, w); ++i)
         words[i] = 0;
-    for (int c = 0; c < HQO_NC; ++c)
+    for (int c = 0; c < Nc; ++c)
         for (int bit = 0; bit < w; ++bit)
             if ((code32[c] >> bit) & 1u) {
                 int pos = c * w + bit;
@@ -446,9 +455,9 @@ void hqo_pack_row(const uint32_t *code32 /* [32] */, int w, uint32_t *words /* [
             }
 }
 
-void hqo_unpack_row(const uint32_t *words /* [w] */, int w, uint32_t *code32 /* [32] */)
+void hqo_unpack_row(const uint32_t *words /* [row_words] */, int Nc, int w, uint32_t *code32 /* [Nc] */)
 {
-    for (int c = 0; c < HQO_NC; ++c) {
+    for (int c = 0; c < Nc; ++c) {
         uint32_t v = 0;
         for (int bit = 0; bit < w; ++bit) {
             int pos = c * w + bit;
@@ -461,20 +470,21 @@ void hqo_unpack_row(const uint32_t *words /* [w] */, int w, uint32_t *code32 /* 
 
 /* Pack rows whose k / r_q are known (k >= 0 or flagged); rows with an unflagged k < 0
  * (not searched) are written as zeros. */
-void hqo_pack_rows(const int32_t *k, const int32_t *rq, const uint8_t *flag, int64_t n_rows,
-                   int S, int b_r, uint32_t *codes /* [n_rows][w] */)
+void hqo_pack_rows(const int32_t *k, const int32_t *rq, const uint8_t *flag, int64_t n_rows, int Nc,
+                   int S, int b_r, uint32_t *codes /* [n_rows][row_words] */)
 {
     int w_idx = hqo_index_bits(S), w = w_idx + b_r;
+    int rw = hqo_row_words(Nc, w);
     for (int64_t row = 0; row < n_rows; ++row) {
-        uint32_t code32[HQO_NC];
-        for (int c = 0; c < HQO_NC; ++c) {
-            int64_t chunk = row * HQO_NC + c;
+        uint32_t code32[HQO_NC_MAX];
+        for (int c = 0; c < Nc; ++c) {
+            int64_t chunk = row * Nc + c;
             if (flag[chunk] || k[chunk] < 0)
                 code32[c] = 0;
             else
                 code32[c] = ((uint32_t)rq[chunk] << w_idx) | (uint32_t)k[chunk];
         }
-        hqo_pack_row(code32, w, codes + row * w);
+        hqo_pack_row(code32, Nc, w, codes + row * rw);
     }
 }
 
@@ -488,32 +498,33 @@ void hqo_pack_rows(const int32_t *k, const int32_t *rq, const uint8_t *flag, int
  * ---------------------------------------------------------------------------------- */
 void hqo_decode64(const uint32_t *codes, const uint16_t *sigma16, const uint32_t *flag_words,
                   const uint32_t *row_off, const uint16_t *payload, const float *sec_all, int B,
-                  int H, int T, int S, int b_r, uint16_t *out, double *r_hat, double *out64);
+                  int H, int T, int Nc, int S, int b_r, uint16_t *out, double *r_hat, double *out64);
 
 void hqo_decode(const uint32_t *codes, const uint16_t *sigma16, const uint32_t *flag_words,
                 const uint32_t *row_off, const uint16_t *payload, const float *sec_all, int B,
-                int H, int T, int S, int b_r, uint16_t *out /* [rows][128] */, double *r_hat)
+                int H, int T, int Nc, int S, int b_r, uint16_t *out /* [rows][4 Nc] */, double *r_hat)
 {
-    hqo_decode64(codes, sigma16, flag_words, row_off, payload, sec_all, B, H, T, S, b_r, out, r_hat, 0);
+    hqo_decode64(codes, sigma16, flag_words, row_off, payload, sec_all, B, H, T, Nc, S, b_r, out, r_hat, 0);
 }
 
 void hqo_decode64(const uint32_t *codes, const uint16_t *sigma16, const uint32_t *flag_words,
                 const uint32_t *row_off, const uint16_t *payload, const float *sec_all, int B,
-                  int H, int T, int S, int b_r, uint16_t *out /* [rows][128] */, double *r_hat,
-                  double *out64 /* [rows][128] or NULL */)
+                  int H, int T, int Nc, int S, int b_r, uint16_t *out /* [rows][4 Nc] */, double *r_hat,
+                  double *out64 /* [rows][4 Nc] or NULL */)
 {
     int w_idx = hqo_index_bits(S), w = w_idx + b_r;
+    int rw = hqo_row_words(Nc, w);
     double L = (double)((1 << b_r) - 1);
     int64_t n_rows = (int64_t)B * H * T;
     for (int64_t row = 0; row < n_rows; ++row) {
         int h = (int)((row / T) % H);
         const float *sec = sec_all + (int64_t)h * S * 4;
-        uint32_t code32[HQO_NC];
-        hqo_unpack_row(codes + row * w, w, code32);
+        uint32_t code32[HQO_NC_MAX];
+        hqo_unpack_row(codes + row * rw, Nc, w, code32);
         double sigma = hqo_half_to_double(sigma16[row]);
         int64_t next = row_off[row];
-        for (int c = 0; c < HQO_NC; ++c) {
-            int64_t chunk = row * HQO_NC + c;
+        for (int c = 0; c < Nc; ++c) {
+            int64_t chunk = row * Nc + c;
             if ((flag_words[row] >> c) & 1u) {
                 memcpy(out + 4 * chunk, payload + 4 * next, 4 * sizeof(uint16_t));
                 if (out64)

@@ -631,3 +631,101 @@ def test_memory_table_and_headlines():
     assert oracle.bits_per_element(256, 6, 128, p=0.02) == pytest.approx(
         0.98 * oracle.bits_per_element(256, 6, 128) + 0.32 + 0.25)
     assert oracle.bits_per_element(256, 6, 128, stored=True) == (13 + 6) / 4 + 0.125
+
+
+# ---------------------------------------------------------------------------------------
+# head dimensions other than 128: rows of 1..32 chunks, and the padding wrapper
+# ---------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("nc", [1, 5, 11, 16, 24, 31, 32])
+@pytest.mark.parametrize("w", [10, 13, 17, 22])
+def test_pack_row_any_chunk_count_against_big_integer(nc, w):
+    """The packed row read as one little-endian integer is sum(code_c << (c w))."""
+    rng = np.random.default_rng(100 * nc + w)
+    code = rng.integers(0, 1 << w, nc, dtype=np.uint64).astype(np.uint32)
+    words = oracle.pack_row(code, w)
+    assert words.size == -(-nc * w // 32)
+    big = sum(int(c) << (i * w) for i, c in enumerate(code))
+    want = [(big >> (32 * i)) & 0xFFFFFFFF for i in range(words.size)]
+    assert [int(v) for v in words] == want
+    assert np.array_equal(oracle.unpack_row(words, w, nc), code)
+
+
+def _embed(x_bits, D_to):
+    out = np.zeros(x_bits.shape[:-1] + (D_to,), np.uint16)
+    out[..., : x_bits.shape[-1]] = x_bits
+    return out
+
+
+@pytest.mark.parametrize("D", [64, 96, 45, 4])
+@pytest.mark.parametrize("with_thresholds", [False, True])
+def test_short_heads_equal_the_zero_padded_128_wide_tensor(D, with_thresholds):
+    """Zero chunks have no direction, no radius and are never flagged, so a head of D < 128
+    elements must encode exactly like the same rows padded with zeros to 128, chunk by chunk
+    (thresholds supplied, or extraction off, so that the padding does not move the median)."""
+    rng = np.random.default_rng(D)
+    B, H, T, S, b_r = 2, 2, 5, 24, 4
+    x = (rng.standard_normal((B, H, T, D)) * np.exp(rng.normal(0, 1.0, (B, H, T, D)))).astype(np.float16)
+    x[0, 0, 1] = 0  # a zero row
+    xb = x.view(np.uint16)
+    sec = oracle.build_codebooks(7, 1, H, S)[0, 0]
+    thr = np.array([2.0, 0.7]) if with_thresholds else None
+    kw = dict(b_r=b_r, thresholds=thr) if with_thresholds else dict(b_r=b_r, use_outliers=False)
+    e = oracle.encode(xb, sec, **kw)
+    full = oracle.encode(_embed(xb, 128), sec, **kw)
+    nc = oracle.chunks_per_row(D)
+    assert e.k.shape == (B * H * T, nc) and e.codes.shape[1] == oracle.row_words(D, oracle.index_bits(S) + b_r)
+    assert np.array_equal(e.k, full.k[:, :nc]) and np.array_equal(e.rq, full.rq[:, :nc])
+    assert np.array_equal(e.flag, full.flag[:, :nc]) and not full.flag[:, nc:].any()
+    assert np.array_equal(e.sigma, full.sigma) and np.array_equal(e.flags, full.flags)
+    assert np.array_equal(e.row_off, full.row_off) and np.array_equal(e.n_out, full.n_out)
+    assert np.array_equal(e.outliers, full.outliers)
+    if with_thresholds:
+        assert e.flag.any()
+    k2, rq2 = oracle.unpack_rows(e.codes, S, b_r, nc)
+    keep = e.flag == 0
+    assert np.array_equal(k2[keep], e.k[keep]) and np.array_equal(rq2[keep], e.rq[keep])
+    assert not k2[~keep].any() and not rq2[~keep].any()
+    out = oracle.decode(e.codes, e.sigma, e.flags, e.row_off, e.outliers, sec, B, H, T, b_r, D=D)
+    out_full = oracle.decode(full.codes, full.sigma, full.flags, full.row_off, full.outliers, sec, B, H, T, b_r)
+    assert out.shape == (B, H, T, D)
+    assert np.array_equal(out, out_full[..., :D])
+    # what lies beyond D decodes to zeros in the padded tensor (code 0 with r_q = 0)
+    assert not (out_full[..., 4 * nc:] & 0x7FFF).any()
+
+
+@pytest.mark.parametrize("D", [64, 96, 45])
+def test_median_of_short_heads_against_numpy_sort(D):
+    rng = np.random.default_rng(5 + D)
+    B, H, T = 2, 3, 7
+    x = rng.standard_normal((B, H, T, D)).astype(np.float16)
+    sec = oracle.build_codebooks(0, 1, H, 4)[0, 0]
+    e = oracle.encode(x.view(np.uint16), sec, b_r=3, rows=np.zeros(B * H * T, bool))
+    nc = oracle.chunks_per_row(D)
+    xp = np.zeros((B, H, T, 4 * nc)); xp[..., :D] = x.astype(np.float64)
+    r2 = (xp.reshape(B, H, T, nc, 4) ** 2).sum(-1)
+    for h in range(H):
+        v = np.sort(r2[:, h].reshape(-1))
+        assert e.m2[h] == pytest.approx(v[(v.size - 1) // 2], rel=1e-15)
+        want_flag = r2[:, h] > 9.0 * e.m2[h]
+        got = e.flag.reshape(B, H, T, nc)[:, h].astype(bool)
+        assert np.array_equal(got, want_flag)
+
+
+def test_padding_overhead_printed_example():
+    for line in open(os.path.join(GOLDEN, "padding_overhead.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        d_h, padded, pct = line.split()
+        assert 4 * oracle.chunks_per_row(int(d_h)) == int(padded)
+        assert round(100 * oracle.padding_overhead(int(d_h)), 1) == float(pct)
+    for d in (64, 96, 128):  # the paper's models need no padding
+        assert oracle.padding_overhead(d) == 0.0
+
+
+def test_scale_term_of_the_bit_accounting_follows_the_head_dimension():
+    # b = (log2(24 S) + b_r) / 4 + 16 / d_h: only the last term depends on d_h
+    for S, b_r in ((24, 3), (192, 4)):
+        b128 = oracle.bits_per_element(S, b_r, 128)
+        assert oracle.bits_per_element(S, b_r, 64) - b128 == pytest.approx(16 / 64 - 16 / 128)
+        assert oracle.bits_per_element(S, b_r, 96) - b128 == pytest.approx(16 / 96 - 16 / 128)
