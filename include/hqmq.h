@@ -22,9 +22,15 @@
  *   - One call handles one (layer, role) tensor X, fp16 [B, H, T, D] addressed through
  *     element strides (D contiguous): "the current batch" of Alg. 1.  A row is one (b, h, t)
  *     vector, linear row index R = (b*H + h)*T + t; chunk c of a row is elements 4c..4c+3,
- *     element 0 being the real part; linear chunk index = R*(D/4) + c.
- *   - This build supports D == 128 (32 chunks per row: one flag word and exactly w code
- *     words per row).
+ *     element 0 being the real part; linear chunk index = R*n_c + c, n_c = ceil(D/4).
+ *   - Head dimensions 1 <= D <= 128 (the paper's models have 64, 96 and 128): a row has
+ *     n_c <= 32 chunks, one flag word and ceil(n_c*w/32) code words (exactly w at D = 128).  A
+ *     D that is not a multiple of 4 is handled as the paper's padding wrapper does (App.
+ *     "Padding wrapper for d_h not divisible by 4"): the last chunk is completed with zeros on
+ *     encode and the surplus elements are not written on decode; nothing past D is touched.
+ *     D = 128 is the tuned path and wants strides that are multiples of 8; other D take any
+ *     strides (multiples of 4 and a D that is one keep every chunk one aligned 8-byte access).
+ *     hqmq_attend is written for D = 128 only.
  */
 #ifndef HQMQ_H
 #define HQMQ_H
@@ -37,7 +43,7 @@ extern "C" {
 
 #define HQMQ_OK 0
 #define HQMQ_ERR_INVALID_ARG (-1)      /* null pointer, non-positive size, misaligned pointer or stride */
-#define HQMQ_ERR_UNSUPPORTED (-2)      /* D != 128, S outside 1..512, b_r outside 1..8, C not a positive finite number */
+#define HQMQ_ERR_UNSUPPORTED (-2)      /* D > 128 (hqmq_attend: D != 128), S outside 1..512, b_r outside 1..8, C not a positive finite number */
 #define HQMQ_ERR_BUFFER_TOO_SMALL (-3) /* workspace smaller than hqmq_sizes() asks for */
 #define HQMQ_ERR_HIP (-4)              /* a HIP call failed; see hqmq_last_hip_error() */
 
@@ -49,7 +55,7 @@ extern "C" {
 
 typedef struct hqmq_params {
     int32_t B, H, T, D;                   /* X is fp16 [B, H, T, D], D contiguous                  */
-    int64_t stride_b, stride_h, stride_t; /* element strides of b, h, t; multiples of 8           */
+    int64_t stride_b, stride_h, stride_t; /* element strides of b, h, t; multiples of 8 at D = 128 */
     int32_t S;                            /* secondary codebook size per (layer, head, role)       */
     int32_t b_r;                          /* radius bits (paper: 3, 4 or 6)                        */
     float C;                              /* outlier multiplier (paper: 3)                         */
@@ -60,8 +66,8 @@ typedef struct hqmq_params {
 typedef struct hqmq_size_info {
     uint64_t n_rows;               /* B*H*T                                                        */
     uint32_t index_bits;           /* w_idx = ceil(log2(24 S)) (Sec. 3: index width)               */
-    uint32_t code_bits;            /* w = w_idx + b_r: bits per chunk, and 32-bit words per row    */
-    uint64_t code_bytes;           /* n_rows * w * 4                                               */
+    uint32_t code_bits;            /* w = w_idx + b_r: bits per chunk                              */
+    uint64_t code_bytes;           /* n_rows * code_words_per_row * 4                              */
     uint64_t sigma_bytes;          /* n_rows * 2                                                   */
     uint64_t flag_bytes;           /* n_rows * 4                                                   */
     uint64_t row_off_bytes;        /* (n_rows + 1) * 4                                             */
@@ -70,13 +76,17 @@ typedef struct hqmq_size_info {
     uint64_t outlier_capacity_max; /* chunks: no input can flag more than this                     */
     uint64_t outlier_bytes_max;    /* outlier_capacity_max * 8                                     */
     uint64_t workspace_bytes;      /* scratch hqmq_encode needs                                    */
+    uint32_t chunks_per_row;       /* n_c = ceil(D / 4)                                            */
+    uint32_t code_words_per_row;   /* ceil(n_c * w / 32): w at D = 128                             */
 } hqmq_size_info;
 
 /* The encoded form of one tensor: a HOST struct of DEVICE pointers, all caller-owned.
- *   codes      uint32 [n_rows][w]   chunk code = (r_q << w_idx) | k, k = p*S + s (p-major),
- *                                   flagged chunks 0; the 32 codes of a row concatenated
- *                                   LSB first: chunk c at bits [c*w, (c+1)*w) of the row's w
- *                                   little-endian words                       (Alg. 1 "store")
+ *   codes      uint32 [n_rows][code_words_per_row]
+ *                                   chunk code = (r_q << w_idx) | k, k = p*S + s (p-major),
+ *                                   flagged chunks 0; the n_c codes of a row concatenated
+ *                                   LSB first: chunk c at bits [c*w, (c+1)*w) of the row's
+ *                                   little-endian words, unused high bits of the last word 0
+ *                                                                             (Alg. 1 "store")
  *   sigma      fp16   [n_rows]      per-token scale: largest norm among the row's unflagged
  *                                   chunks, rounded to nearest even, saturating (Sec. 3
  *                                   "Radius quantization")
@@ -171,7 +181,7 @@ int32_t hqmq_decode(const hqmq_params *params, const hqmq_encoded *enc, uint64_t
  * Everything else (buffers, sizes from hqmq_sizes for THIS small shape, ordering of the outlier
  * list, errors) is as in hqmq_encode; the encoded rows form a tensor of their own.  One bound of
  * hqmq_sizes does not carry over: with arbitrary thresholds every chunk may be flagged, so a list
- * that can never overflow needs n_rows * 32 entries (an overflow is reported in status as usual). */
+ * that can never overflow needs n_rows * chunks_per_row entries (an overflow is reported in status as usual). */
 int32_t hqmq_encode_given_thresholds(const hqmq_params *params, const void *x_dev, const float *sec_dev,
                                      const double *thr_dev, const hqmq_encoded *enc,
                                      uint64_t outlier_capacity, void *workspace_dev,

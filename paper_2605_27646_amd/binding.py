@@ -36,7 +36,8 @@ class HqmqSizeInfo(C.Structure):
                 ("code_bytes", C.c_uint64), ("sigma_bytes", C.c_uint64), ("flag_bytes", C.c_uint64),
                 ("row_off_bytes", C.c_uint64), ("n_outliers_bytes", C.c_uint64),
                 ("status_bytes", C.c_uint64), ("outlier_capacity_max", C.c_uint64),
-                ("outlier_bytes_max", C.c_uint64), ("workspace_bytes", C.c_uint64)]
+                ("outlier_bytes_max", C.c_uint64), ("workspace_bytes", C.c_uint64),
+                ("chunks_per_row", C.c_uint32), ("code_words_per_row", C.c_uint32)]
 
 
 class _Encoded(C.Structure):
@@ -167,7 +168,7 @@ def alloc_encoded(params: HqmqParams, device, outlier_capacity: int | None = Non
     cap = int(info.outlier_capacity_max if outlier_capacity is None else outlier_capacity)
     n = int(info.n_rows)
     return EncodedBuffers(
-        codes=torch.empty(n, info.code_bits, dtype=torch.int32, device=device),
+        codes=torch.empty(n, info.code_words_per_row, dtype=torch.int32, device=device),
         sigma=torch.empty(n, dtype=torch.float16, device=device),
         flags=torch.empty(n, dtype=torch.int32, device=device),
         row_off=torch.empty(n + 1, dtype=torch.int32, device=device),

@@ -28,7 +28,7 @@ static int32_t check_params(const hqmq_params *p)
         return HQMQ_ERR_INVALID_ARG;
     if (p->B <= 0 || p->H <= 0 || p->T <= 0 || p->D <= 0)
         return HQMQ_ERR_INVALID_ARG;
-    if (p->D != 4 * kChunksPerRow)
+    if (p->D > 4 * kChunksPerRow)
         return HQMQ_ERR_UNSUPPORTED;
     if (p->S < 1 || p->S > kMaxS || p->b_r < 1 || p->b_r > 8)
         return HQMQ_ERR_UNSUPPORTED;
@@ -36,7 +36,8 @@ static int32_t check_params(const hqmq_params *p)
         return HQMQ_ERR_UNSUPPORTED;
     if (p->stride_b < 0 || p->stride_h < 0 || p->stride_t < p->D)
         return HQMQ_ERR_INVALID_ARG;
-    if ((p->stride_b % 8) || (p->stride_h % 8) || (p->stride_t % 8))
+    // D = 128 runs the kernels written for full rows: 16-byte accesses, every row aligned to them
+    if (p->D == 4 * kChunksPerRow && ((p->stride_b % 8) || (p->stride_h % 8) || (p->stride_t % 8)))
         return HQMQ_ERR_INVALID_ARG;
     if ((int64_t)p->B * p->H > 65535)
         return HQMQ_ERR_UNSUPPORTED;  // grid.y
@@ -52,11 +53,15 @@ static Geometry make_geometry(const hqmq_params *p)
     g.B = p->B;
     g.H = p->H;
     g.T = p->T;
+    g.D = p->D;
+    g.n_c = (p->D + 3) / 4;
+    g.vec_ok = (p->D % 4 == 0 && p->stride_b % 4 == 0 && p->stride_h % 4 == 0 && p->stride_t % 4 == 0) ? 1 : 0;
     g.S = p->S;
     g.S16 = (p->S + 15) / 16;
     g.b_r = p->b_r;
     g.w_idx = index_bits(p->S);
     g.w = g.w_idx + p->b_r;
+    g.row_words = (g.n_c * g.w + 31) / 32;
     g.sb = p->stride_b;
     g.sh = p->stride_h;
     g.st = p->stride_t;
@@ -154,7 +159,9 @@ extern "C" int32_t hqmq_sizes(const hqmq_params *params, hqmq_size_info *out)
     out->n_rows = n_rows;
     out->index_bits = (uint32_t)g.w_idx;
     out->code_bits = (uint32_t)g.w;
-    out->code_bytes = n_rows * g.w * 4;
+    out->code_words_per_row = (uint32_t)g.row_words;
+    out->chunks_per_row = (uint32_t)g.n_c;
+    out->code_bytes = n_rows * (uint64_t)g.row_words * 4;
     out->sigma_bytes = n_rows * 2;
     out->flag_bytes = n_rows * 4;
     out->row_off_bytes = (n_rows + 1) * 4;
@@ -162,7 +169,7 @@ extern "C" int32_t hqmq_sizes(const hqmq_params *params, hqmq_size_info *out)
     out->status_bytes = 4;
     // A chunk is flagged when r^2 > C^2 * median.  For C >= 1 that needs r^2 above the lower
     // median of its head, which at most floor(n_h / 2) chunks are; for C < 1 any chunk may be.
-    const uint64_t n_h = (uint64_t)g.B * g.T * kChunksPerRow;
+    const uint64_t n_h = (uint64_t)g.B * g.T * g.n_c;
     uint64_t cap = (uint64_t)g.H * n_h;
     if (params->flags & HQMQ_FLAG_NO_OUTLIERS)
         cap = 0;
@@ -415,6 +422,8 @@ static int32_t check_attend(const hqmq_params *params, int32_t n_q_heads)
         return rc;
     if (n_q_heads <= 0 || n_q_heads % params->H)
         return HQMQ_ERR_INVALID_ARG;
+    if (params->D != 4 * kChunksPerRow)
+        return HQMQ_ERR_UNSUPPORTED;  // the attention kernel is written for 128-element heads
     if (n_q_heads / params->H > kMaxGroup)
         return HQMQ_ERR_UNSUPPORTED;
     return HQMQ_OK;

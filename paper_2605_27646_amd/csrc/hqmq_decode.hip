@@ -284,10 +284,117 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(Geometry g, DecodeBatch 
     phase3(3, s3, o3);
 }
 
+// Decode for head dimensions other than 128 (rows of n_c = ceil(D / 4) <= 32 chunks, ceil(n_c w / 32)
+// code words each): the plain mapping, one lane per chunk slot, a 32-lane slot per row, the lanes
+// past the row's chunks idle.  Same arithmetic as k_decode; the elements of a last partial chunk that
+// lie past D are not written (the truncation of the paper's App. "Padding wrapper for d_h not
+// divisible by 4").
+// grid = (ceil(T / 64), B*H, tensors), block = 256: 8 rows per pass, 8 passes.
+// dynamic LDS: prim [48][4] f32 | secl [S][4] f32
+template <bool kPow2>
+__global__ __launch_bounds__(kDecThreads) void k_decode_rows(Geometry g, DecodeBatch batch)
+{
+    const DecodeTensor &dt = batch.t[blockIdx.z];
+    const uint64_t outlier_capacity = dt.outlier_capacity;
+    _Float16 *__restrict__ out = dt.out;
+
+    extern __shared__ float lds[];
+    float *prim = lds;
+    float *secl = prim + 48 * 4;
+
+    const int tid = threadIdx.x;
+    const int seg = blockIdx.y, b = seg / g.H, h = seg % g.H;
+    const float *sec_h = dt.sec + (size_t)h * g.S * 4;
+    for (int s = tid; s < g.S; s += kDecThreads)
+        *reinterpret_cast<float4_t *>(secl + 4 * s) = *reinterpret_cast<const float4_t *>(sec_h + 4 * s);
+    if (tid < 48 * 4) {
+        const int p = tid >> 2, i = tid & 3;
+        float v = 0.f;
+        if (p < 8)
+            v = ((p >> 1) == i) ? ((p & 1) ? -1.f : 1.f) : 0.f;
+        else if (p < 24)
+            v = (((p - 8) >> (3 - i)) & 1) ? -0.5f : 0.5f;
+        prim[tid] = v;
+    }
+    __syncthreads();
+
+    const int c = tid & 31, rsub = tid >> 5;
+    if (c >= g.n_c)
+        return;
+    const uint32_t w = g.w, w_idx = g.w_idx;
+    const uint32_t bitpos = (uint32_t)c * w, i0 = bitpos >> 5, sh = bitpos & 31;
+    const uint32_t code_mask = (1u << w) - 1u, idx_mask = (1u << w_idx) - 1u;
+    for (int pass = 0; pass < kDecRows / 8; ++pass) {
+        const int t = blockIdx.x * kDecRows + pass * 8 + rsub;
+        if (t >= g.T)
+            break;  // later passes lie further past the end
+        const int64_t R = (int64_t)seg * g.T + t;
+        const uint32_t *words = dt.codes + R * g.row_words;
+        const uint32_t d0 = words[i0];
+        const uint32_t d1 = (i0 + 1 < (uint32_t)g.row_words) ? words[i0 + 1] : 0u;
+        const uint32_t code = __builtin_amdgcn_alignbit(d1, d0, sh) & code_mask;
+        const uint32_t word = dt.flags[R];
+        half4_t hv;
+        if ((word >> c) & 1u) {
+            const uint64_t pos = (uint64_t)dt.row_off[R] + __popc(word & ((1u << c) - 1u));
+            uint2 v = make_uint2(0u, 0u);
+            if (pos < outlier_capacity)
+                v = *reinterpret_cast<const uint2 *>(dt.outliers + 4 * pos);
+            hv = __builtin_bit_cast(half4_t, v);
+        } else {
+            const float sigma = (float)__builtin_bit_cast(_Float16, dt.sigma[R]);
+            const uint32_t rq = code >> w_idx;
+            uint32_t p, sidx;
+            if (kPow2) {
+                p = (code >> g.log2_S) & 31u;
+                sidx = code & ((uint32_t)g.S - 1u);
+            } else {
+                const uint32_t k = code & idx_mask;
+                p = (uint32_t)((float)k * g.inv_S);  // k / S, exact for k < 48 S (see Geometry::inv_S)
+                sidx = k - __umul24(p, (uint32_t)g.S);
+            }
+            const float4_t P = *reinterpret_cast<const float4_t *>(prim + 4 * p);
+            const float4_t q = *reinterpret_cast<const float4_t *>(secl + 4 * sidx);
+            const float rh = (float)rq * (sigma * g.inv_L);
+            const float R0 = rh * P[0], R1 = rh * P[1], R2 = rh * P[2], R3 = rh * P[3];
+            float4_t y;  // Hamilton product (r_hat P) (x) q
+            y[0] = fmaf(-R3, q[3], fmaf(-R2, q[2], fmaf(-R1, q[1], R0 * q[0])));
+            y[1] = fmaf(-R3, q[2], fmaf(R2, q[3], fmaf(R1, q[0], R0 * q[1])));
+            y[2] = fmaf(R3, q[1], fmaf(R2, q[0], fmaf(-R1, q[3], R0 * q[2])));
+            y[3] = fmaf(R3, q[0], fmaf(-R2, q[1], fmaf(R1, q[2], R0 * q[3])));
+            if (sigma >= 32752.f) {  // only such rows can leave the fp16 range: saturate
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    y[i] = __builtin_amdgcn_fmed3f(y[i], -65504.f, 65504.f);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                hv[i] = (_Float16)y[i];
+        }
+        _Float16 *dst = out + (int64_t)b * g.sb + (int64_t)h * g.sh + (int64_t)t * g.st + 4 * c;
+        if (g.vec_ok) {
+            *reinterpret_cast<uint2 *>(dst) = __builtin_bit_cast(uint2, hv);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (4 * c + e < g.D)
+                    dst[e] = hv[e];
+        }
+    }
+}
+
 hipError_t launch_decode(const Geometry &g, const DecodeBatch &batch, int n_tensors, hipStream_t stream)
 {
     const size_t lds = ((size_t)g.S * 4 + 48 * 4) * sizeof(float) + (size_t)kDecWaves * kStagePerWave * 4;
     dim3 grid((unsigned)((g.T + kDecRows - 1) / kDecRows), (unsigned)(g.B * g.H), (unsigned)n_tensors);
+    if (g.D != 4 * kChunksPerRow) {
+        const size_t lds_rows = ((size_t)g.S * 4 + 48 * 4) * sizeof(float);
+        if ((g.S & (g.S - 1)) == 0)
+            hipLaunchKernelGGL(k_decode_rows<true>, grid, dim3(kDecThreads), lds_rows, stream, g, batch);
+        else
+            hipLaunchKernelGGL(k_decode_rows<false>, grid, dim3(kDecThreads), lds_rows, stream, g, batch);
+        return hipGetLastError();
+    }
     if ((g.S & (g.S - 1)) == 0)
         hipLaunchKernelGGL(k_decode<true>, grid, dim3(kDecThreads), lds, stream, g, batch);
     else

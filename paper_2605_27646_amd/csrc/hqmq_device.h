@@ -9,7 +9,7 @@
 
 namespace hqmq {
 
-constexpr int kChunksPerRow = 32;    // D = 128
+constexpr int kChunksPerRow = 32;    // chunks of a row of D = 128 elements, and the most a row may have
 constexpr int kSearchRowsSmall = 64;   // rows per search workgroup = granularity of the outlier scan:
 constexpr int kSearchRowsLarge = 256;  // 64 for short segments (more workgroups), 256 from 2048 rows on
 constexpr int kSearchRowsSwitch = 2048;
@@ -33,6 +33,10 @@ struct SelectState {
 // Shape and addressing of one tensor, passed by value to every kernel.
 struct Geometry {
     int32_t B, H, T;
+    int32_t D;            // elements per row (head dimension), 1..128
+    int32_t n_c;          // ceil(D / 4): chunks per row; a last partial chunk is zero-padded
+    int32_t row_words;    // ceil(n_c * w / 32): 32-bit words of one packed row (w when D = 128)
+    int32_t vec_ok;       // D and the strides are multiples of 4: every chunk is one aligned 8-byte access
     int32_t S;            // secondaries per head
     int32_t S16;          // ceil(S / 16): groups of 16 secondaries (4 MFMA s-blocks) of the search loop
     int32_t b_r, w_idx, w;
@@ -166,6 +170,29 @@ __device__ __forceinline__ half4_t load_chunk(const _Float16 *p)
 {
     uint2 raw = *reinterpret_cast<const uint2 *>(p);
     return __builtin_bit_cast(half4_t, raw);
+}
+
+// Chunk c of the row starting at `row`, for any head dimension.  kFull (D = 128, strides that keep
+// every chunk 8-byte aligned) is the plain vector load.  Otherwise lanes past the row's chunks, and
+// the elements past D inside the last chunk, read as +0: the zero padding of a head whose dimension
+// is not a multiple of 4 (paper App. "Padding wrapper for d_h not divisible by 4").
+template <bool kFull>
+__device__ __forceinline__ half4_t load_row_chunk(const _Float16 *row, int c, const Geometry &g)
+{
+    if (kFull)
+        return load_chunk(row + 4 * c);
+    half4_t v = {0, 0, 0, 0};
+    if (c < g.n_c) {
+        if (g.vec_ok) {
+            v = load_chunk(row + 4 * c);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (4 * c + e < g.D)
+                    v[e] = row[4 * c + e];
+        }
+    }
+    return v;
 }
 
 __device__ __forceinline__ unsigned long long key_of(double r2)

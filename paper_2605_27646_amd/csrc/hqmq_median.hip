@@ -1,8 +1,8 @@
 // Med3x outlier extraction, first half: the exact per-head median of the squared chunk norms
 // (paper Sec. 3 "Median-multiplier outlier extraction", Alg. 1 "Outlier extraction").
 //
-// The median is the lower median (element (n-1)/2 of the sorted norms) of all B*T*32 chunks of
-// a head.  Non-negative IEEE doubles order like their bit patterns read as unsigned integers,
+// The median is the lower median (element (n-1)/2 of the sorted norms) of all B*T*ceil(D/4) chunks
+// of a head.  Non-negative IEEE doubles order like their bit patterns read as unsigned integers,
 // so the median is found by a most-significant-digit radix select on the 63 value bits of r^2:
 //   pass 0  histogram of bits 62..50 (sign-free exponent + 2 mantissa bits), all keys
 //   pass 1  histogram of bits 49..40 of the keys in the bucket that holds the wanted rank
@@ -108,7 +108,9 @@ __global__ __launch_bounds__(kThreads) void k_init(Geometry g, WorkspaceOffsets 
 //   MODE 0: histogram of digit 0            MODE 1: pick digit 0, histogram of digit 1
 //   MODE 2: pick digits 0 and 1, append the keys of the chosen bucket to the candidate list
 // ---------------------------------------------------------------------------------------
-template <int MODE>
+// kFull: D = 128 (every lane of a 32-lane row slot holds a chunk); otherwise lanes past the row's
+// chunks are idle and the loads go through the general path.
+template <int MODE, bool kFull>
 __global__ __launch_bounds__(kSelectThreads) void k_select_sweep(Geometry g, WorkspaceOffsets wo, EncodeBatch batch)
 {
     const EncodeTensor &tn = batch.t[blockIdx.z];
@@ -119,7 +121,7 @@ __global__ __launch_bounds__(kSelectThreads) void k_select_sweep(Geometry g, Wor
     __shared__ uint32_t scratch[kSelectThreads + 2];
 
     const int seg = blockIdx.y, b = seg / g.H, h = seg % g.H;
-    const uint32_t rank0 = (uint32_t)(((uint64_t)g.B * g.T * kChunksPerRow - 1) / 2);
+    const uint32_t rank0 = (uint32_t)(((uint64_t)g.B * g.T * g.n_c - 1) / 2);
     uint32_t bin0 = 0, before0 = 0, bin1 = 0, before1 = 0;
     if (MODE >= 1)
         pick_bin<kBins0, kSelectThreads>(ws.hist0 + (size_t)h * kBins0, rank0, scratch, bin0, before0);
@@ -141,7 +143,8 @@ __global__ __launch_bounds__(kSelectThreads) void k_select_sweep(Geometry g, Wor
     const int c = threadIdx.x & 31, sub = threadIdx.x >> 5;  // 32 rows per iteration
     const int t0 = blockIdx.x * kSelectRows;
     const int t1 = min(g.T, t0 + kSelectRows);
-    const _Float16 *base = x + (int64_t)b * g.sb + (int64_t)h * g.sh + 4 * c;
+    const _Float16 *base = x + (int64_t)b * g.sb + (int64_t)h * g.sh;
+    const bool active = kFull || c < g.n_c;
     unsigned long long *cand = ws.cand + (size_t)h * kCandCap;
 
     for (int tb = t0; tb < t1; tb += 128) {  // uniform over the block
@@ -149,11 +152,11 @@ __global__ __launch_bounds__(kSelectThreads) void k_select_sweep(Geometry g, Wor
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int tt = tb + sub + 32 * u;
-            v[u] = (tt < t1) ? load_chunk(base + (int64_t)tt * g.st) : half4_t{0, 0, 0, 0};
+            v[u] = (tt < t1) ? load_row_chunk<kFull>(base + (int64_t)tt * g.st, c, g) : half4_t{0, 0, 0, 0};
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const bool in = (tb + sub + 32 * u) < t1;
+            const bool in = active && (tb + sub + 32 * u) < t1;
             const unsigned long long key = key_of(chunk_norm2(v[u])) & kKeyMask;
             if (MODE == 0) {
                 if (in)
@@ -196,6 +199,7 @@ __global__ __launch_bounds__(kSelectThreads) void k_select_sweep(Geometry g, Wor
 // among the keys whose top 23 bits equal the chosen prefix: from the candidate list when it holds
 // them all, otherwise from the head's raw rows.  Writes thr[h] = fl(fl(C*C) * median).
 // ---------------------------------------------------------------------------------------
+template <bool kFull>
 __global__ __launch_bounds__(kSelectThreads) void k_select_finish(Geometry g, WorkspaceOffsets wo, EncodeBatch batch,
                                                                   float C)
 {
@@ -229,10 +233,11 @@ __global__ __launch_bounds__(kSelectThreads) void k_select_finish(Geometry g, Wo
             // rare path: sweep the head's rows (every batch entry), one lane per chunk
             const int c = threadIdx.x & 31, sub = threadIdx.x >> 5;
             for (int b = 0; b < g.B; ++b) {
-                const _Float16 *base = x + (int64_t)b * g.sb + (int64_t)h * g.sh + 4 * c;
+                const _Float16 *base = x + (int64_t)b * g.sb + (int64_t)h * g.sh;
                 for (int t = sub; t < g.T; t += kSelectThreads / 32) {
-                    const unsigned long long key = key_of(chunk_norm2(load_chunk(base + (int64_t)t * g.st))) & kKeyMask;
-                    if ((key >> (shift + 10)) == want)
+                    const unsigned long long key =
+                        key_of(chunk_norm2(load_row_chunk<kFull>(base + (int64_t)t * g.st, c, g))) & kKeyMask;
+                    if ((kFull || c < g.n_c) && (key >> (shift + 10)) == want)
                         atomicAdd(&lh[(uint32_t)(key >> shift) & (kBins1 - 1)], 1u);
                 }
             }
@@ -323,6 +328,7 @@ __global__ __launch_bounds__(1024) void k_scan(Geometry g, WorkspaceOffsets wo, 
 }
 
 // grid = (ceil(T / 256), B*H), one thread per row
+template <bool kFull>
 __global__ __launch_bounds__(kThreads) void k_gather(Geometry g, WorkspaceOffsets wo, EncodeBatch batch)
 {
     const EncodeTensor &tn = batch.t[blockIdx.z];
@@ -346,7 +352,8 @@ __global__ __launch_bounds__(kThreads) void k_gather(Geometry g, WorkspaceOffset
         const int c = __ffs((int)word) - 1;
         word &= word - 1;
         if (pos < outlier_capacity)
-            *reinterpret_cast<uint2 *>(enc.outliers + 4 * pos) = *reinterpret_cast<const uint2 *>(row + 4 * c);
+            *reinterpret_cast<uint2 *>(enc.outliers + 4 * pos) =
+                __builtin_bit_cast(uint2, load_row_chunk<kFull>(row, c, g));
         ++pos;
     }
 }
@@ -362,10 +369,17 @@ hipError_t launch_select_median(const Geometry &g, const WorkspaceOffsets &wo, c
     hipLaunchKernelGGL(k_init, dim3((n_init + kThreads - 1) / kThreads, 1, n), dim3(kThreads), 0, stream, g, wo, batch);
     if (!skip_select) {
         dim3 grid((g.T + kSelectRows - 1) / kSelectRows, g.B * g.H, n);
-        hipLaunchKernelGGL(k_select_sweep<0>, grid, dim3(kSelectThreads), 0, stream, g, wo, batch);
-        hipLaunchKernelGGL(k_select_sweep<1>, grid, dim3(kSelectThreads), 0, stream, g, wo, batch);
-        hipLaunchKernelGGL(k_select_sweep<2>, grid, dim3(kSelectThreads), 0, stream, g, wo, batch);
-        hipLaunchKernelGGL(k_select_finish, dim3(g.H, 1, n), dim3(kSelectThreads), 0, stream, g, wo, batch, C);
+        if (g.D == 4 * kChunksPerRow) {
+            hipLaunchKernelGGL((k_select_sweep<0, true>), grid, dim3(kSelectThreads), 0, stream, g, wo, batch);
+            hipLaunchKernelGGL((k_select_sweep<1, true>), grid, dim3(kSelectThreads), 0, stream, g, wo, batch);
+            hipLaunchKernelGGL((k_select_sweep<2, true>), grid, dim3(kSelectThreads), 0, stream, g, wo, batch);
+            hipLaunchKernelGGL(k_select_finish<true>, dim3(g.H, 1, n), dim3(kSelectThreads), 0, stream, g, wo, batch, C);
+        } else {
+            hipLaunchKernelGGL((k_select_sweep<0, false>), grid, dim3(kSelectThreads), 0, stream, g, wo, batch);
+            hipLaunchKernelGGL((k_select_sweep<1, false>), grid, dim3(kSelectThreads), 0, stream, g, wo, batch);
+            hipLaunchKernelGGL((k_select_sweep<2, false>), grid, dim3(kSelectThreads), 0, stream, g, wo, batch);
+            hipLaunchKernelGGL(k_select_finish<false>, dim3(g.H, 1, n), dim3(kSelectThreads), 0, stream, g, wo, batch, C);
+        }
     }
     return hipGetLastError();
 }
@@ -378,7 +392,10 @@ hipError_t launch_outlier_list(const Geometry &g, const WorkspaceOffsets &wo, co
     const uint64_t n_rows = (uint64_t)g.B * g.H * g.T;
     hipLaunchKernelGGL(k_scan, dim3(1, 1, n), dim3(1024), 0, stream, g, wo, batch, n_blocks, n_rows);
     dim3 grid((g.T + kThreads - 1) / kThreads, g.B * g.H, n);
-    hipLaunchKernelGGL(k_gather, grid, dim3(kThreads), 0, stream, g, wo, batch);
+    if (g.D == 4 * kChunksPerRow)
+        hipLaunchKernelGGL(k_gather<true>, grid, dim3(kThreads), 0, stream, g, wo, batch);
+    else
+        hipLaunchKernelGGL(k_gather<false>, grid, dim3(kThreads), 0, stream, g, wo, batch);
     return hipGetLastError();
 }
 

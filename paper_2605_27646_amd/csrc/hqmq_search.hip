@@ -186,7 +186,10 @@ __global__ __launch_bounds__(kThreads) void k_prepare_operands(Geometry g, Works
 
 // kWaves: 4, or 8 when the A operands are so large (S > 256) that only one workgroup fits a CU: twice
 // the waves then share them and keep two waves on every SIMD.
-template <int kWaves, int kRows>
+// kFull: D = 128, every lane of a 32-lane row slot holds a chunk.  Otherwise a row has g.n_c <= 32
+// chunks: the lanes past them carry a zero chunk (no flag, code 0, no part in the row's scale) and
+// only the row's ceil(n_c w / 32) code words are stored.
+template <int kWaves, int kRows, bool kFull>
 __global__ __launch_bounds__(64 * kWaves) void k_search(Geometry g, WorkspaceOffsets wo, EncodeBatch batch)
 {
     constexpr int kThreadsS = 64 * kWaves;
@@ -229,7 +232,8 @@ __global__ __launch_bounds__(64 * kWaves) void k_search(Geometry g, WorkspaceOff
     const int c = lane & 31, half_id = lane >> 5;
     uint2 *my_ubuf = ubuf + wv * 64 * 4;
     uint32_t *my_pack = pack + wv * 64;
-    const _Float16 *base = x + (int64_t)b * g.sb + (int64_t)h * g.sh + 4 * c;
+    const _Float16 *base = x + (int64_t)b * g.sb + (int64_t)h * g.sh;
+    const int row_words = kFull ? g.w : g.row_words;
 
     for (int it = 0; it < kRows / (2 * kWaves); ++it) {
         const int r_in_block = it * 2 * kWaves + wv * 2 + half_id;
@@ -242,9 +246,9 @@ __global__ __launch_bounds__(64 * kWaves) void k_search(Geometry g, WorkspaceOff
         }
 
         // ---- chunk, norm, flag, row scale --------------------------------------------------
-        half4_t xv = valid ? load_chunk(base + (int64_t)t * g.st) : half4_t{0, 0, 0, 0};
+        half4_t xv = valid ? load_row_chunk<kFull>(base + (int64_t)t * g.st, c, g) : half4_t{0, 0, 0, 0};
         const double r2 = chunk_norm2(xv);
-        const bool flagged = valid && (r2 > thr);
+        const bool flagged = valid && (kFull || c < g.n_c) && (r2 > thr);
         const unsigned long long ballot = __ballot(flagged);
         const uint32_t word = half_id ? (uint32_t)(ballot >> 32) : (uint32_t)ballot;
 
@@ -454,8 +458,8 @@ __global__ __launch_bounds__(64 * kWaves) void k_search(Geometry g, WorkspaceOff
         wave_lds_sync();
         if (valid) {
             const int64_t R = row0 + t;
-            if (c < g.w)
-                enc.codes[R * g.w + c] = my_pack[half_id * 32 + c];
+            if (c < row_words)
+                enc.codes[R * row_words + c] = my_pack[half_id * 32 + c];
             if (c == 0) {
                 enc.sigma[R] = sigma16;
                 enc.flags[R] = word;
@@ -504,11 +508,15 @@ hipError_t launch_search(const Geometry &g, const WorkspaceOffsets &wo, const En
     if (err != hipSuccess)
         return err;
     if (device < 0 || device >= 64 || !raised[device]) {
-        const void *variants[4] = {reinterpret_cast<const void *>(k_search<4, kSearchRowsSmall>),
-                                   reinterpret_cast<const void *>(k_search<4, kSearchRowsLarge>),
-                                   reinterpret_cast<const void *>(k_search<8, kSearchRowsSmall>),
-                                   reinterpret_cast<const void *>(k_search<8, kSearchRowsLarge>)};
-        for (int i = 0; i < 4 && err == hipSuccess; ++i)
+        const void *variants[8] = {reinterpret_cast<const void *>(k_search<4, kSearchRowsSmall, true>),
+                                   reinterpret_cast<const void *>(k_search<4, kSearchRowsLarge, true>),
+                                   reinterpret_cast<const void *>(k_search<8, kSearchRowsSmall, true>),
+                                   reinterpret_cast<const void *>(k_search<8, kSearchRowsLarge, true>),
+                                   reinterpret_cast<const void *>(k_search<4, kSearchRowsSmall, false>),
+                                   reinterpret_cast<const void *>(k_search<4, kSearchRowsLarge, false>),
+                                   reinterpret_cast<const void *>(k_search<8, kSearchRowsSmall, false>),
+                                   reinterpret_cast<const void *>(k_search<8, kSearchRowsLarge, false>)};
+        for (int i = 0; i < 8 && err == hipSuccess; ++i)
             err = hipFuncSetAttribute(variants[i], hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (err != hipSuccess)
             return err;
@@ -518,14 +526,29 @@ hipError_t launch_search(const Geometry &g, const WorkspaceOffsets &wo, const En
     hipLaunchKernelGGL(k_prepare_operands, dim3((g.S16 * 4 * 64 + kThreads - 1) / kThreads, g.H, (unsigned)n_tensors),
                        dim3(kThreads), 0, stream, g, wo, batch);
     const bool large = g.search_rows == kSearchRowsLarge;
-    if (waves == 8 && large)
-        hipLaunchKernelGGL((k_search<8, kSearchRowsLarge>), grid, dim3(512), lds, stream, g, wo, batch);
-    else if (waves == 8)
-        hipLaunchKernelGGL((k_search<8, kSearchRowsSmall>), grid, dim3(512), lds, stream, g, wo, batch);
-    else if (large)
-        hipLaunchKernelGGL((k_search<4, kSearchRowsLarge>), grid, dim3(256), lds, stream, g, wo, batch);
-    else
-        hipLaunchKernelGGL((k_search<4, kSearchRowsSmall>), grid, dim3(256), lds, stream, g, wo, batch);
+    const bool full = g.D == 4 * kChunksPerRow;
+#define HQMQ_LAUNCH_SEARCH(W, R, F) \
+    hipLaunchKernelGGL((k_search<W, R, F>), grid, dim3(64 * W), lds, stream, g, wo, batch)
+    if (full) {
+        if (waves == 8 && large)
+            HQMQ_LAUNCH_SEARCH(8, kSearchRowsLarge, true);
+        else if (waves == 8)
+            HQMQ_LAUNCH_SEARCH(8, kSearchRowsSmall, true);
+        else if (large)
+            HQMQ_LAUNCH_SEARCH(4, kSearchRowsLarge, true);
+        else
+            HQMQ_LAUNCH_SEARCH(4, kSearchRowsSmall, true);
+    } else {
+        if (waves == 8 && large)
+            HQMQ_LAUNCH_SEARCH(8, kSearchRowsLarge, false);
+        else if (waves == 8)
+            HQMQ_LAUNCH_SEARCH(8, kSearchRowsSmall, false);
+        else if (large)
+            HQMQ_LAUNCH_SEARCH(4, kSearchRowsLarge, false);
+        else
+            HQMQ_LAUNCH_SEARCH(4, kSearchRowsSmall, false);
+    }
+#undef HQMQ_LAUNCH_SEARCH
     return hipGetLastError();
 }
 

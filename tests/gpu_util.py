@@ -72,6 +72,17 @@ def upload_encoded(e: oracle.Encoded, device) -> hq.EncodedBuffers:
         n_outliers=i32(e.n_out), status=torch.zeros(1, dtype=torch.int32, device=device))
 
 
+def chunked(bits: np.ndarray, nc: int) -> np.ndarray:
+    """[..., D] fp16 bit patterns -> [rows, nc, 4], a last partial chunk completed with +0."""
+    D = bits.shape[-1]
+    flat = bits.reshape(-1, D)
+    if D != 4 * nc:
+        pad = np.zeros((flat.shape[0], 4 * nc), np.uint16)
+        pad[:, :D] = flat
+        flat = pad
+    return flat.reshape(-1, nc, 4)
+
+
 def compare_encode(g: GpuEncoded, e: oracle.Encoded, x_bits: np.ndarray, sec: np.ndarray) -> dict:
     """Bit-exact parity on masks, offsets, counts, payload, scales and radius codes; codeword
     indices identical wherever the oracle's score gap is >= NEAR_TIE, and within NEAR_TIE of
@@ -83,7 +94,9 @@ def compare_encode(g: GpuEncoded, e: oracle.Encoded, x_bits: np.ndarray, sec: np
     assert np.array_equal(g.outliers, e.outliers), "outlier payload differs"
     assert np.array_equal(g.sigma, e.sigma), "per-row scales differ"
     rows = np.flatnonzero(e.searched)
-    k_gpu, rq_gpu = oracle.unpack_rows(g.codes[rows], e.S, e.b_r)
+    nc = e.r2.shape[1]
+    assert g.codes.shape == e.codes.shape
+    k_gpu, rq_gpu = oracle.unpack_rows(g.codes[rows], e.S, e.b_r, nc)
     ok = e.flag[rows] == 0
     # flagged chunks carry code 0
     assert (k_gpu[~ok] == 0).all() and (rq_gpu[~ok] == 0).all()
@@ -94,7 +107,7 @@ def compare_encode(g: GpuEncoded, e: oracle.Encoded, x_bits: np.ndarray, sec: np
     assert not (diff & (gap >= NEAR_TIE)).any(), "codeword index differs where the gap is >= 1e-6"
     # near ties: the GPU's pick must score within NEAR_TIE of the oracle's best
     rr, cc = np.nonzero(diff)
-    chunks = x_bits.reshape(-1, oracle.NC, 4)
+    chunks = chunked(x_bits, nc)
     H, T = e.H, e.T
     for r, c in zip(rr, cc):
         row = rows[r]
@@ -111,8 +124,9 @@ def compare_encode(g: GpuEncoded, e: oracle.Encoded, x_bits: np.ndarray, sec: np
 def compare_decode(out_gpu: np.ndarray, out_or: np.ndarray, r_hat: np.ndarray, flag: np.ndarray):
     """Reconstruction within RECON_TOL of the chunk norm (r_hat: the decoded norm; fp16
     rounding of a component is at most 2^-11 of it); flagged chunks bit-exact."""
-    a = out_gpu.reshape(-1, oracle.NC, 4)
-    b = out_or.reshape(-1, oracle.NC, 4)
+    nc = flag.shape[-1]
+    a = chunked(out_gpu, nc)
+    b = chunked(out_or, nc)
     fl = flag.astype(bool)
     assert np.array_equal(a[fl], b[fl]), "restored outliers differ"
     af = a.view(np.float16).astype(np.float64)

@@ -34,7 +34,7 @@ def test_library_exports_every_declared_symbol(lib):
 
 def test_struct_layouts_match_header():
     assert C.sizeof(hq.HqmqParams) == 56
-    assert C.sizeof(hq.HqmqSizeInfo) == 88
+    assert C.sizeof(hq.HqmqSizeInfo) == 96
     assert C.sizeof(binding._Encoded) == 56
 
 
@@ -62,9 +62,31 @@ def test_sizes_of_the_headline_workload(lib):
     assert hq.hqmq_sizes(_params(flags=hq.HQMQ_FLAG_NO_OUTLIERS)).outlier_capacity_max == 0
 
 
+@pytest.mark.parametrize("D,S,b_r", [(64, 192, 4), (96, 192, 4), (96, 24, 3), (45, 48, 4), (4, 16, 6), (1, 1, 1),
+                                     (128, 192, 6)])
+def test_sizes_of_other_head_dimensions(lib, D, S, b_r):
+    """Rows of ceil(D / 4) chunks packed into ceil(chunks * w / 32) words; any strides are accepted."""
+    B, H, T = 2, 4, 100
+    pitch = D + 3 if D != 128 else 128
+    info = hq.hqmq_sizes(_params(B=B, H=H, T=T, D=D, S=S, b_r=b_r, stride_t=pitch, stride_h=T * pitch,
+                                 stride_b=H * T * pitch))
+    nc = -(-D // 4)
+    w = oracle.index_bits(S) + b_r
+    assert (info.chunks_per_row, info.code_bits, info.code_words_per_row) == (nc, w, -(-nc * w // 32))
+    assert info.code_words_per_row == oracle.row_words(D, w)
+    assert info.code_bytes == B * H * T * info.code_words_per_row * 4
+    assert info.outlier_capacity_max == H * (B * T * nc // 2)
+    # stored code + scale bits per element: the accounting of Sec. 3 with the index width rounded up
+    # to whole bits, the padding of App. "Padding wrapper" and the row rounded up to whole words
+    stored = (info.code_bytes + info.sigma_bytes) * 8 / (info.n_rows * D)
+    ideal = oracle.bits_per_element(S, b_r, D, stored=True)
+    padded = (ideal - 16 / D) * (1 + oracle.padding_overhead(D)) + 16 / D
+    assert padded <= stored < padded + 32 / D
+
+
 @pytest.mark.parametrize("kw,code", [
     (dict(B=0), -1), (dict(T=-3), -1), (dict(stride_t=132), -1), (dict(stride_t=64), -1), (dict(stride_h=-8), -1),
-    (dict(D=64), -2), (dict(D=130), -2), (dict(S=0), -2), (dict(S=513), -2), (dict(b_r=0), -2), (dict(b_r=9), -2),
+    (dict(D=132, stride_t=136), -2), (dict(D=130), -2), (dict(D=0), -1), (dict(D=96, stride_t=64), -1), (dict(S=0), -2), (dict(S=513), -2), (dict(b_r=0), -2), (dict(b_r=9), -2),
     (dict(C=0.0), -2), (dict(C=float("nan")), -2), (dict(C=float("inf")), -2), (dict(B=70000, H=1), -2),
     (dict(T=1 << 27), -2),
 ])
@@ -94,7 +116,7 @@ def test_encode_decode_reject_bad_arguments_without_touching_the_gpu(lib):
     assert enc(C.byref(p), 0x1000, 0x1000, C.byref(bad), 0, 0x1000, ws, None) == -1         # null member
     bad = binding._Encoded(0x1002, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000)
     assert enc(C.byref(p), 0x1000, 0x1000, C.byref(bad), 0, 0x1000, ws, None) == -1         # misaligned member
-    assert enc(C.byref(_params(D=64)), 0x1000, 0x1000, C.byref(good), 0, 0x1000, ws, None) == -2
+    assert enc(C.byref(_params(D=132, stride_t=136)), 0x1000, 0x1000, C.byref(good), 0, 0x1000, ws, None) == -2
     dec = lib.hqmq_decode
     assert dec(C.byref(p), C.byref(good), 0, None, 0x1000, None) == -1
     assert dec(C.byref(p), C.byref(good), 0, 0x1000, 0x1008, None) == -1
@@ -130,7 +152,7 @@ def test_encode_decode_reject_bad_arguments_without_touching_the_gpu(lib):
     th = lib.hqmq_thresholds
     assert th(C.byref(p), None, 0, 0x1000, None) == -1 and th(C.byref(p), 0x1000, 0, None, None) == -1
     assert th(C.byref(p), 0x1000, 32, 0x1000, None) == -1 and th(C.byref(p), 0x1000, -1, 0x1000, None) == -1
-    assert th(C.byref(_params(D=64)), 0x1000, 0, 0x1000, None) == -2
+    assert th(C.byref(_params(D=132, stride_t=136)), 0x1000, 0, 0x1000, None) == -2
     att = lib.hqmq_attend
     wsb = lib.hqmq_attend_workspace_bytes
     need = wsb(C.byref(p), 4 * p.H)
@@ -147,7 +169,8 @@ def test_encode_decode_reject_bad_arguments_without_touching_the_gpu(lib):
     assert call(ek=bad) == -1 and call(ev=bad) == -1
     assert call(ws_ptr=0x4010) == -1                  # workspace not 256-byte aligned
     assert call(ws_bytes=need - 1) == -3
-    assert call(params=_params(D=64)) == -2
+    assert call(params=_params(D=64)) == -2          # the attention kernel takes 128-element heads only
+    assert wsb(C.byref(_params(D=64)), 4 * p.H) == 0
     assert lib.hqmq_last_hip_error() == 0
 
 

@@ -38,19 +38,19 @@ def _roundtrip(x_cpu, S, b_r=6, Cmul=3.0, seed=0, rows=None, check_decode=True, 
     if check_decode:
         # (1) identical bytes, oracle-encoded (needs every row searched)
         if rows is None:
-            want, r_hat = oracle.decode(e.codes, e.sigma, e.flags, e.row_off, e.outliers, sec, B, H, T, b_r, True)
+            want, r_hat = oracle.decode(e.codes, e.sigma, e.flags, e.row_off, e.outliers, sec, B, H, T, b_r, True, D=D)
             got = gpu_decode(g.params, upload_encoded(e, DEV), sec_dev, x_dev)
             stats["decode_rel_err_oracle_bytes"] = compare_decode(got, want, r_hat, e.flag)
         # (2) identical bytes, GPU-encoded
-        want, r_hat = oracle.decode(g.codes, g.sigma, g.flags, g.row_off, g.outliers, sec, B, H, T, b_r, True)
+        want, r_hat = oracle.decode(g.codes, g.sigma, g.flags, g.row_off, g.outliers, sec, B, H, T, b_r, True, D=D)
         got = gpu_decode(g.params, g.bufs, sec_dev, x_dev)
         stats["decode_rel_err_gpu_bytes"] = compare_decode(got, want, r_hat, e.flag)
     print(stats, flush=True)
     return stats, e, g
 
 
-def _lognormal_tensor(B, H, T, seed, sigma_g=0.5):
-    wl = workloads.Workload("t", 100 + seed, 1, B, H, T, 128, 16, sigma_g=sigma_g)
+def _lognormal_tensor(B, H, T, seed, sigma_g=0.5, D=128):
+    wl = workloads.Workload("t", 100 + seed, 1, B, H, T, D, 16, sigma_g=sigma_g)
     return workloads.make_tensor(wl, 0, 0, "cpu")
 
 
@@ -191,6 +191,8 @@ def test_llama3_8b_32k_in_the_bench_launch_configuration():
 
 
 @pytest.mark.parametrize("name,layer,role", [
+    ("mha32_d96_8k", 3, 0),          # [1, 32, 8192, 96], S = 192, b_r = 4: 24 chunks per row
+    ("gqa8_d64_32k", 1, 0),          # [1, 8, 32768, 64], S = 192, b_r = 4: 16 chunks per row, hot channels
     ("mistral7b_outlier", 5, 0),     # [4, 8, 8192, 128], S = 64: batch > 1, hot channels (about 10 % outliers)
     ("qwen25_7b_heavy", 2, 0),       # [1, 4, 32768, 128], S = 256: hot channels + heavy-tailed spikes
     ("llama3_70b_128k", 7, 1),       # [1, 8, 131072, 128], S = 256: 256 MiB per tensor, four times the rows
@@ -212,6 +214,99 @@ def test_other_workloads_full_size_sampled(name, layer, role):
         got = gpu_decode(g.params, g.bufs, _sec(0, wl.H, wl.S)[0].to(DEV), x.to(DEV))
         sel = np.flatnonzero(rows)
         compare_decode(got.reshape(-1, 128)[sel], want.reshape(-1, 128)[sel], r_hat[sel], e.flag[sel])
+
+
+# ---------------------------------------------------------------------------------------
+# head dimensions other than 128 (the paper's models: 64, 96, 128; anything else through zero padding)
+# ---------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("D,B,H,T,S,b_r", [
+    (64, 1, 2, 333, 16, 6),      # 16 chunks per row, ragged length
+    (64, 2, 3, 77, 24, 4),       # the paper's s24_r4
+    (96, 1, 2, 515, 192, 4),     # 24 chunks per row, the paper's s192_r4; several scan blocks
+    (96, 2, 1, 64, 48, 3),
+    (32, 1, 4, 130, 5, 6),
+    (4, 1, 1, 300, 16, 6),       # one chunk per row
+    (45, 1, 2, 200, 24, 4),      # the paper's padding example: 12 chunks, the last one holds 1 element
+    (1, 1, 1, 70, 16, 6),        # one element per row
+    (100, 2, 2, 90, 33, 5),      # multiple of 4, strides not multiples of 8
+    (126, 1, 1, 130, 256, 6),    # 32 chunks like the full row, but through the general path
+    (124, 1, 3, 2100, 64, 6),    # 31 chunks; long enough for the 256-row search workgroups
+])
+def test_other_head_dimensions_small(D, B, H, T, S, b_r):
+    print(f"case D={D} B={B} H={H} T={T} S={S} b_r={b_r}", flush=True)
+    x = _lognormal_tensor(B, H, T, seed=D + T, sigma_g=1.0, D=D)
+    stats, e, g = _roundtrip(x, S, b_r)
+    info = hq.hqmq_sizes(g.params)
+    nc = -(-D // 4)
+    assert info.chunks_per_row == nc and info.code_words_per_row == -(-nc * info.code_bits // 32)
+    assert stats["outliers"] > 0
+
+
+@pytest.mark.parametrize("D,pitch", [(45, 53), (96, 104), (64, 64 + 8), (3, 4)])
+def test_other_head_dimensions_touch_nothing_past_the_row(D, pitch):
+    """Rows stored with a pitch larger than D: encode must not read, and decode must not write, the
+    elements between D and the pitch (encode: the gap holds huge values that would change every
+    median, scale and flag; decode: the gap keeps its sentinel)."""
+    B, H, T, S, b_r = 2, 2, 61, 24, 4
+    x = _lognormal_tensor(B, H, T, seed=D, sigma_g=1.0, D=D)
+    sec_t, sec = _sec(1, H, S)
+    e = oracle.encode(_bits(x), sec, b_r=b_r)
+    wide = torch.full((B, H, T, pitch), 60000.0, dtype=torch.float16, device=DEV)
+    wide[..., :D] = x.to(DEV)
+    view = wide[..., :D]
+    assert view.stride(2) == pitch
+    g = gpu_encode(view, sec_t.to(DEV), b_r)
+    compare_encode(g, e, _bits(x), sec)
+    out_wide = torch.full((B, H, T, pitch), -7.0, dtype=torch.float16, device=DEV)
+    out = out_wide[..., :D]
+    hq.hqmq_decode(hq.params_for(out, S, b_r), g.bufs, sec_t.to(DEV), out)
+    torch.cuda.synchronize()
+    assert bool((out_wide[..., D:] == -7.0).all())
+    want, r_hat = oracle.decode(g.codes, g.sigma, g.flags, g.row_off, g.outliers, sec, B, H, T, b_r, True, D=D)
+    compare_decode(out.contiguous().cpu().numpy().view(np.uint16), want, r_hat, e.flag)
+
+
+def test_other_head_dimensions_batched_and_incremental():
+    """D = 96: a batch of tensors in one launch equals the single calls, and appended token rows
+    encode against thresholds taken from the prefill."""
+    B, H, T, S, b_r, D, n = 1, 3, 140, 48, 4, 96, 3
+    sec_t, sec = _sec(2, H, S)
+    sec_dev = sec_t.to(DEV)
+    xs = [_lognormal_tensor(B, H, T, seed=300 + i, sigma_g=0.8, D=D) for i in range(n)]
+    xd = [x.to(DEV) for x in xs]
+    params = hq.params_for(xd[0], S, b_r)
+    encs = [hq.alloc_encoded(params, DEV) for _ in range(n)]
+    ws = hq.alloc_batch_workspace(params, n, DEV)
+    hq.hqmq_encode_batch(hq.EncodeBatch(params, xd, [sec_dev] * n, encs, ws))
+    thr = hq.hqmq_thresholds(params, ws, 1)
+    torch.cuda.synchronize()
+    for i in range(n):
+        e = oracle.encode(_bits(xs[i]), sec, b_r=b_r)
+        bufs = encs[i]
+        n_out = bufs.n_outliers.cpu().numpy().view(np.uint32)
+        total = int(n_out[-1])
+        from gpu_util import GpuEncoded
+        g = GpuEncoded(params, bufs, bufs.codes.cpu().numpy().view(np.uint32), bufs.sigma.cpu().numpy().view(np.uint16),
+                       bufs.flags.cpu().numpy().view(np.uint32), bufs.row_off.cpu().numpy().view(np.uint32), n_out,
+                       bufs.outliers[:total].cpu().numpy().view(np.uint16).reshape(total, 4),
+                       int(bufs.status.cpu().numpy().view(np.uint32)[0]))
+        compare_encode(g, e, _bits(xs[i]), sec)
+        if i == 1:
+            assert np.array_equal(thr.cpu().numpy(), 9.0 * e.m2)
+    new = (_lognormal_tensor(B, H, 2, seed=400, sigma_g=0.8, D=D) * 1.7).to(torch.float16)
+    e = oracle.encode(_bits(new), sec, b_r=b_r, thresholds=thr.cpu().numpy())
+    p2 = hq.params_for(new.to(DEV), S, b_r)
+    bufs = hq.alloc_encoded(p2, DEV, outlier_capacity=B * H * 2 * 24)
+    hq.hqmq_encode_given_thresholds(p2, new.to(DEV), sec_dev, thr, bufs, hq.alloc_workspace(p2, DEV))
+    torch.cuda.synchronize()
+    n_out = bufs.n_outliers.cpu().numpy().view(np.uint32)
+    total = int(n_out[-1])
+    g = GpuEncoded(p2, bufs, bufs.codes.cpu().numpy().view(np.uint32), bufs.sigma.cpu().numpy().view(np.uint16),
+                   bufs.flags.cpu().numpy().view(np.uint32), bufs.row_off.cpu().numpy().view(np.uint32), n_out,
+                   bufs.outliers[:total].cpu().numpy().view(np.uint16).reshape(total, 4),
+                   int(bufs.status.cpu().numpy().view(np.uint32)[0]))
+    compare_encode(g, e, _bits(new), sec)
 
 
 # ---------------------------------------------------------------------------------------

@@ -63,6 +63,11 @@ WORKLOADS = {
     "qwen25_7b_heavy": Workload("qwen25_7b_heavy", 4, 28, 1, 4, 32768, 128, 256, law="heavy",
                                 hot=3, hot_scale=100.0, spike_prob=1e-3, spike_scale=10.0),
     "llama3_70b_128k": Workload("llama3_70b_128k", 5, 80, 1, 8, 131072, 128, 256, sigma_g=0.75),
+    # the two other head dimensions of the paper's models, at the paper's own codebook sizes
+    # (S = 192, b_r = 4): 96 (a full multi-head model with 32 kv heads) and 64 (8 kv heads)
+    "mha32_d96_8k": Workload("mha32_d96_8k", 6, 32, 1, 32, 8192, 96, 192, b_r=4),
+    "gqa8_d64_32k": Workload("gqa8_d64_32k", 7, 24, 1, 8, 32768, 64, 192, b_r=4, law="hot_channels",
+                             hot=2, hot_scale=20.0),
 }
 
 
