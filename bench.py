@@ -40,10 +40,12 @@ def search_flops_per_chunk(S: int) -> float:
     return 36.0 * s16
 
 
-def decode_bytes_per_chunk(w: int, p_out: float) -> float:
-    """Algorithmic HBM bytes of decode per chunk: w bits of code, 1 flag bit, 1/32 of a 2-byte
-    scale and of a 4-byte offset, 8 bytes of payload for a flagged chunk; 8 bytes written."""
-    return w / 8.0 + 1.0 / 8.0 + 2.0 / 32.0 + 4.0 / 32.0 + 8.0 * p_out + 8.0
+def decode_bytes_per_chunk(w: int, p_out: float, chunks_per_row: int = 32, words_per_row: int | None = None) -> float:
+    """Algorithmic HBM bytes of decode per chunk: the row's code words (w bits per chunk at 32 chunks
+    per row), flag word, 2-byte scale and 4-byte offset shared by the row's chunks, 8 bytes of
+    payload for a flagged chunk; 8 bytes written."""
+    words = w if words_per_row is None else words_per_row
+    return (4.0 * words + 4.0 + 2.0 + 4.0) / chunks_per_row + 8.0 * p_out + 8.0
 
 
 def main() -> int:
@@ -93,7 +95,7 @@ def main() -> int:
     torch.cuda.synchronize()
 
     elems_per_step = wl.elems_per_tensor * n_t
-    chunks_per_tensor = wl.elems_per_tensor // 4
+    chunks_per_tensor = wl.B * wl.H * wl.T * ((wl.D + 3) // 4)
 
     def new_events(n):
         evs = [torch.cuda.Event(enable_timing=True) for _ in range(n)]
@@ -163,7 +165,8 @@ def main() -> int:
     S16 = (wl.S + 15) // 16
     flops_launch = search_flops_per_chunk(wl.S) * chunks_per_tensor * tensors_per_enc_launch
     search_tflops = flops_launch / (search_ms * 1e-3) / 1e12
-    dec_bytes_launch = decode_bytes_per_chunk(info.code_bits, p_out) * chunks_per_tensor * tensors_per_dec_launch
+    dec_bytes_chunk = decode_bytes_per_chunk(info.code_bits, p_out, info.chunks_per_row, info.code_words_per_row)
+    dec_bytes_launch = dec_bytes_chunk * chunks_per_tensor * tensors_per_dec_launch
     dec_gbs = dec_bytes_launch / (decode_ms * 1e-3) / 1e9
 
     result = {
@@ -211,18 +214,18 @@ def main() -> int:
                                   "peak": PEAK_F16_TFLOPS, "unit": "TFLOP/s",
                                   "frac": 256.0 * S16 * 16 * chunks_per_tensor * tensors_per_enc_launch
                                   / (search_ms * 1e-3) / 1e12 / PEAK_F16_TFLOPS}},
-        "roofline_decode": {"kernel": "k_decode", "bound": "hbm", "achieved": dec_gbs, "peak": PEAK_HBM_GBS,
+        "roofline_decode": {"kernel": "k_decode" if wl.D == 128 else "k_decode_rows", "bound": "hbm", "achieved": dec_gbs, "peak": PEAK_HBM_GBS,
                             "unit": "GB/s", "frac": dec_gbs / PEAK_HBM_GBS,
                             "traffic": (MEASURED_TRAFFIC_BYTES[wl.name]["k_decode"] * tensors_per_dec_launch
                                         if wl.name in MEASURED_TRAFFIC_BYTES else None),
                             "tensors_per_launch": tensors_per_dec_launch,
-                            "bytes_per_chunk": decode_bytes_per_chunk(info.code_bits, p_out),
+                            "bytes_per_chunk": dec_bytes_chunk,
                             "avg_launch_ms": decode_ms},
     }
 
     # ---- extra, outside the timed step: one generation step's attention read from the packed cache
     # (one hqmq_attend per layer over that layer's encoded K and V) ------------------------------
-    if args.q_heads_per_kv > 0:
+    if args.q_heads_per_kv > 0 and wl.D == 128:   # the attention kernel takes 128-element heads
         import math
         G = args.q_heads_per_kv
         gen = torch.Generator(device=dev)
@@ -270,7 +273,7 @@ def main() -> int:
         c0 = time.perf_counter()
         e = oracle.encode(xs_cpu, sec, b_r=wl.b_r, Cmul=wl.C)
         c1 = time.perf_counter()
-        oracle.decode(e.codes, e.sigma, e.flags, e.row_off, e.outliers, sec, wl.B, wl.H, Ts, wl.b_r)
+        oracle.decode(e.codes, e.sigma, e.flags, e.row_off, e.outliers, sec, wl.B, wl.H, Ts, wl.b_r, D=wl.D)
         c2 = time.perf_counter()
         result["cpu_baseline"] = {
             "value": xs_cpu.size / (c2 - c0), "unit": "elems/s (one encode + one decode of every element)",

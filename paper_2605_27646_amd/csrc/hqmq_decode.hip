@@ -11,7 +11,8 @@
 //   * a wave takes 16 consecutive rows: their code words, flag words, scales and outlier offsets
 //     arrive with a few fully coalesced loads and are re-distributed through LDS; every lane then
 //     owns two adjacent chunks of a row, i.e. one 16-byte store per lane and 1 KiB contiguous per
-//     wave store;
+//     wave store (rows of 128 elements: 16 such pairs per row, 4 rows per wave store; rows of 96 or
+//     64 elements have 12 or 8 pairs and the wave's 16 rows take 3 or 2 stores);
 //   * the head's S secondaries (S*16 bytes) and the 24 primaries sit in LDS; the Hamilton product
 //     is taken per chunk (16 FMA), which keeps the workgroup small enough to be one-shot;
 //   * the outlier payloads of a wave's rows are one contiguous window of the list: requested with
@@ -26,7 +27,6 @@ constexpr int kDecThreads = 256;
 constexpr int kDecWaves = kDecThreads / 64;
 constexpr int kStageRows = 16;                      // rows per wave
 constexpr int kDecRows = kStageRows * kDecWaves;    // rows per workgroup
-constexpr int kSubs = kStageRows / 4;               // a wave stores 4 rows at a time
 constexpr int kMaxW = 24;                           // w_idx <= 14 (S <= 512), b_r <= 8  ->  w <= 22
 constexpr int kStageWords = kStageRows * kMaxW + 2; // + 2 words of padding for the 3-word window
 constexpr int kPaySlots = 64;                       // outlier payloads of a wave's 16 rows kept in LDS
@@ -40,9 +40,12 @@ constexpr int kLoadsPerLane = (kStageRows * kMaxW + 63) / 64;  // 6 code words p
 // (the tables with compile-time sizes first, so that their LDS addresses are immediates)
 // blockIdx.z selects the tensor of a batch (all of one shape); the descriptors travel as kernel
 // arguments, so a batch needs no device-side table.
-template <bool kPow2>
+// kPairs: chunk pairs (8 elements) per row: 16, 12 or 8 for D = 128, 96, 64.
+template <bool kPow2, int kPairs>
 __global__ __launch_bounds__(kDecThreads) void k_decode(Geometry g, DecodeBatch batch)
 {
+    static_assert((kStageRows * kPairs) % 64 == 0, "a wave's rows must fill whole 64-lane stores");
+    constexpr int kSubs = kStageRows * kPairs / 64;  // stores of 64 lanes x 16 bytes per wave
     const DecodeTensor &dt = batch.t[blockIdx.z];
     EncodedPtrs enc;
     enc.codes = dt.codes;
@@ -63,11 +66,11 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(Geometry g, DecodeBatch 
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, and known to be: row
     // addresses become scalar bases with per-lane offsets
     const int seg = blockIdx.y, b = seg / g.H, h = seg % g.H;
-    const int cp = lane & 15, rsub = lane >> 4;  // chunk pair in the row, row in the group of 4
     const int tg = blockIdx.x * kDecRows + wv * kStageRows;  // first row of this wave
     const int nrows = min(kStageRows, g.T - tg);              // <= 0: nothing to do for this wave
     const int64_t R0 = (int64_t)seg * g.T + tg;
     const uint32_t w = g.w, w_idx = g.w_idx;
+    const uint32_t rw_words = kPairs == 16 ? w : (uint32_t)g.row_words;  // code words per row
 
     // ---- the wave's encoded rows: coalesced loads, in flight while the tables are set up --------
     uint32_t cwreg[kLoadsPerLane];
@@ -76,8 +79,8 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(Geometry g, DecodeBatch 
     for (int j = 0; j < kLoadsPerLane; ++j)
         cwreg[j] = 0;
     if (nrows > 0) {
-        const uint32_t *cw = enc.codes + R0 * w;
-        const int ncw = nrows * (int)w;
+        const uint32_t *cw = enc.codes + R0 * rw_words;
+        const int ncw = nrows * (int)rw_words;
 #pragma unroll
         for (int j = 0; j < kLoadsPerLane; ++j)
             if (lane + 64 * j < ncw)
@@ -138,23 +141,27 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(Geometry g, DecodeBatch 
     // wave-uniform: the whole window fits the LDS slots and the list's capacity
     const bool window_ok = pay_n <= (uint32_t)kPaySlots && (uint64_t)pay_base + pay_n <= outlier_capacity;
 
-    const uint32_t bitpos = (uint32_t)(2 * cp) * w;
-    const uint32_t i0 = bitpos >> 5, sh0 = bitpos & 31;
-    const uint32_t sh1 = sh0 + w;  // second chunk, relative to word i0 (may exceed 32)
-    const bool second_in_low = sh1 < 32;
     const uint32_t code_mask = (1u << w) - 1u, idx_mask = (1u << w_idx) - 1u;
     const float inv_L = g.inv_L;
-    _Float16 *obase = out + (int64_t)b * g.sb + (int64_t)h * g.sh + (int64_t)tg * g.st + 8 * cp;
+    _Float16 *obase = out + (int64_t)b * g.sb + (int64_t)h * g.sh + (int64_t)tg * g.st;
 
     // ---- phase 1: codes and flags of the lane's 8 chunks ----------------------------------------------
     struct Sub {
         uint32_t code0, code1, fl, pos;
         float sigma;
     };
+    // pair slot 64 sub + lane of the wave: row r of the 16, chunk pair cp of the row (compile-time
+    // divisor; for 16 pairs per row r = 4 sub + lane / 16 and cp = lane % 16 for every sub)
+    auto row_of = [&](int sub) { return (int)((64u * (uint32_t)sub + (uint32_t)lane) / (uint32_t)kPairs); };
+    auto pair_of = [&](int sub) { return (int)((64u * (uint32_t)sub + (uint32_t)lane) % (uint32_t)kPairs); };
     auto phase1 = [&](int sub) {
         Sub o;
-        const int r = 4 * sub + rsub;
-        const uint32_t *rw = stage + r * w + i0;
+        const int r = row_of(sub), cp = pair_of(sub);
+        const uint32_t bitpos = (uint32_t)(2 * cp) * w;
+        const uint32_t i0 = bitpos >> 5, sh0 = bitpos & 31;
+        const uint32_t sh1 = sh0 + w;  // second chunk, relative to word i0 (may exceed 32)
+        const bool second_in_low = sh1 < 32;
+        const uint32_t *rw = stage + r * rw_words + i0;
         const uint32_t d0 = rw[0], d1 = rw[1], d2 = rw[2];
         const uint32_t word = st_flags[r];
         o.sigma = (float)__builtin_bit_cast(_Float16, (uint16_t)st_sigma[r]);
@@ -235,7 +242,7 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(Geometry g, DecodeBatch 
     };
     // ---- phase 3: flagged chunks take their payload; store ---------------------------------------------
     auto phase3 = [&](int sub, const Sub &in, uint4 o) {
-        const int r = 4 * sub + rsub;
+        const int r = row_of(sub), cp = pair_of(sub);
         if (window_ok) {
             // every flagged chunk of the wave has its payload in the LDS window: read and select
             // without branching (unflagged lanes read a clamped slot and discard it)
@@ -267,21 +274,25 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(Geometry g, DecodeBatch 
         if (r < nrows) {
             typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
             const u32x4 ov = {o.x, o.y, o.z, o.w};
-            __builtin_nontemporal_store(ov, reinterpret_cast<u32x4 *>(obase + (int64_t)r * g.st));
+            __builtin_nontemporal_store(ov, reinterpret_cast<u32x4 *>(obase + (int64_t)r * g.st + 8 * cp));
         }
     };
-    static_assert(kSubs == 4, "the straight-line code below is written for 4 row groups per wave");
-    const Sub s0 = phase1(0), s1 = phase1(1), s2 = phase1(2), s3 = phase1(3);
-    const uint4 o0 = phase2(s0), o1 = phase2(s1), o2 = phase2(s2), o3 = phase2(s3);
+    Sub sv[kSubs];
+    uint4 ov[kSubs];
+#pragma unroll
+    for (int i = 0; i < kSubs; ++i)
+        sv[i] = phase1(i);
+#pragma unroll
+    for (int i = 0; i < kSubs; ++i)
+        ov[i] = phase2(sv[i]);
     // the window lands in LDS only now, after all the arithmetic that does not need it
     st_pay[lane] = pay_mine;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    phase3(0, s0, o0);
-    phase3(1, s1, o1);
-    phase3(2, s2, o2);
-    phase3(3, s3, o3);
+#pragma unroll
+    for (int i = 0; i < kSubs; ++i)
+        phase3(i, sv[i], ov[i]);
 }
 
 // Decode for head dimensions other than 128 (rows of n_c = ceil(D / 4) <= 32 chunks, ceil(n_c w / 32)
@@ -387,6 +398,23 @@ hipError_t launch_decode(const Geometry &g, const DecodeBatch &batch, int n_tens
 {
     const size_t lds = ((size_t)g.S * 4 + 48 * 4) * sizeof(float) + (size_t)kDecWaves * kStagePerWave * 4;
     dim3 grid((unsigned)((g.T + kDecRows - 1) / kDecRows), (unsigned)(g.B * g.H), (unsigned)n_tensors);
+    // rows of 128, 96 or 64 elements whose strides keep every 16-byte store aligned take the tuned kernel
+    const bool aligned16 = g.sb % 8 == 0 && g.sh % 8 == 0 && g.st % 8 == 0;
+    const bool pow2 = (g.S & (g.S - 1)) == 0;
+    if (aligned16 && (g.D == 96 || g.D == 64)) {
+        if (g.D == 96) {
+            if (pow2)
+                hipLaunchKernelGGL((k_decode<true, 12>), grid, dim3(kDecThreads), lds, stream, g, batch);
+            else
+                hipLaunchKernelGGL((k_decode<false, 12>), grid, dim3(kDecThreads), lds, stream, g, batch);
+        } else {
+            if (pow2)
+                hipLaunchKernelGGL((k_decode<true, 8>), grid, dim3(kDecThreads), lds, stream, g, batch);
+            else
+                hipLaunchKernelGGL((k_decode<false, 8>), grid, dim3(kDecThreads), lds, stream, g, batch);
+        }
+        return hipGetLastError();
+    }
     if (g.D != 4 * kChunksPerRow) {
         const size_t lds_rows = ((size_t)g.S * 4 + 48 * 4) * sizeof(float);
         if ((g.S & (g.S - 1)) == 0)
@@ -395,10 +423,10 @@ hipError_t launch_decode(const Geometry &g, const DecodeBatch &batch, int n_tens
             hipLaunchKernelGGL(k_decode_rows<false>, grid, dim3(kDecThreads), lds_rows, stream, g, batch);
         return hipGetLastError();
     }
-    if ((g.S & (g.S - 1)) == 0)
-        hipLaunchKernelGGL(k_decode<true>, grid, dim3(kDecThreads), lds, stream, g, batch);
+    if (pow2)
+        hipLaunchKernelGGL((k_decode<true, 16>), grid, dim3(kDecThreads), lds, stream, g, batch);
     else
-        hipLaunchKernelGGL(k_decode<false>, grid, dim3(kDecThreads), lds, stream, g, batch);
+        hipLaunchKernelGGL((k_decode<false, 16>), grid, dim3(kDecThreads), lds, stream, g, batch);
     return hipGetLastError();
 }
 
