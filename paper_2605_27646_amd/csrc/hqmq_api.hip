@@ -71,7 +71,8 @@ static Geometry make_geometry(const hqmq_params *p)
     for (int j = 0; j < 16; ++j)
         if ((1 << j) == p->S)
             g.log2_S = j;
-    g.search_rows = p->T >= kSearchRowsSwitch ? kSearchRowsLarge : kSearchRowsSmall;
+    // rows of other lengths than 128 elements go through the search kernel that owns 64 rows per workgroup
+    g.search_rows = (p->T >= kSearchRowsSwitch && p->D == 4 * kChunksPerRow) ? kSearchRowsLarge : kSearchRowsSmall;
     g.n_search_blocks_per_seg = (uint32_t)((p->T + g.search_rows - 1) / g.search_rows);
     return g;
 }

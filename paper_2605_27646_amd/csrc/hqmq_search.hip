@@ -22,8 +22,10 @@
 // re-scoring its 4 candidates once per chunk.
 //
 // Work split: a workgroup (4 wave64) owns 64 or 256 rows of one (b, h) segment, so the A
-// matrices of the head sit in LDS once per workgroup.  A wave takes two rows (64 chunks, one per
-// lane) at a time and runs them as four 16-chunk MFMA column groups.
+// matrices of the head sit in LDS once per workgroup.  A wave takes 64 chunks, one per lane, at a
+// time and runs them as four 16-chunk MFMA column groups: two whole rows of 128 elements in
+// k_search, 64 consecutive chunks of the workgroup's flattened rows in k_search_flat (any other
+// head dimension).  The per-chunk steps (scale, radius code, direction search) are shared.
 #include "hqmq_device.h"
 
 namespace hqmq {
@@ -126,6 +128,212 @@ __device__ __forceinline__ int nearest_primary(float v0, float v1, float v2, flo
     return ph;
 }
 
+
+// sigma = fp16(sqrt(rmax)), round to nearest even, saturating.  The fp32 square root is within
+// 2 ulp(fp32) of the exact one, so it rounds to the same fp16 value unless it lies within a few
+// fp32 ulp of a rounding boundary (the 13 dropped bits close to 0x1000) or the result is
+// subnormal; only then is the fp64 recipe run.
+__device__ __forceinline__ uint16_t sigma_of_row_max(double rmax)
+{
+    const float sf = sqrtf((float)rmax);
+    const uint32_t sb = __float_as_uint(sf);
+    const int dist = (int)(sb & 0x1fffu) - 0x1000;
+    const bool slow = rmax != 0.0 && sf < 65504.f && (sf < 0x1.0p-14f || (dist >= -8 && dist <= 8));
+    uint16_t sigma16 = sf >= 65504.f ? (uint16_t)0x7bff : __builtin_bit_cast(uint16_t, (_Float16)sf);
+    if (__any(slow)) {
+        if (slow)
+            sigma16 = double_to_half_rne_sat(sqrt(rmax));
+    }
+    return sigma16;
+}
+
+// Radius code r_q = clamp(rint(sqrt(r2) * L / sigma), 0, L), defined in fp64.  An fp32
+// evaluation with the hardware's 1-ulp square root (r_f) and reciprocal is off by at most
+// 6e-7 * L (five roundings of <= 1.2e-7 each); it rounds the same way unless it lands within
+// that distance of a rounding boundary, and only then is the fp64 recipe run (about one wave
+// in two hundred at L = 63).
+__device__ __forceinline__ int radius_code(double r2, float r_f, uint16_t sigma16, double Lq)
+{
+    int rq = 0;
+    const float sigma_f = (float)__builtin_bit_cast(_Float16, sigma16);
+    bool exact_needed = false;
+    if (sigma16 != 0 && r2 != 0.0) {
+        const float qf = fminf(r_f * (float)Lq * __builtin_amdgcn_rcpf(sigma_f), (float)Lq);
+        const float fr = qf - floorf(qf);
+        exact_needed = fabsf(fr - 0.5f) < 6e-7f * (float)Lq + 1e-6f;
+        rq = (int)rintf(qf);
+    }
+    if (__any(exact_needed)) {
+        if (exact_needed) {
+            const double sigma = half_bits_to_double(sigma16);
+            double q = rint((sqrt(r2) * Lq) / sigma);
+            q = q < 0.0 ? 0.0 : (q > Lq ? Lq : q);
+            rq = (int)q;
+        }
+    }
+    return rq;
+}
+
+// Unit direction of a chunk in fp32 (zeros for a zero chunk).
+struct Direction {
+    float u0, u1, u2, u3;
+};
+__device__ __forceinline__ Direction unit_direction(const half4_t xv, double r2, float r_f)
+{
+    Direction d = {0.f, 0.f, 0.f, 0.f};
+    if (r2 != 0.0) {
+        const float inv = __builtin_amdgcn_rcpf(r_f);
+        d.u0 = (float)xv[0] * inv;
+        d.u1 = (float)xv[1] * inv;
+        d.u2 = (float)xv[2] * inv;
+        d.u3 = (float)xv[3] * inv;
+    }
+    return d;
+}
+
+// Exhaustive nearest-codeword search for the wave's 64 chunks (one per lane, direction u): returns
+// the chunk's code word (rq << w_idx) | k with k = p S + s of the best joint codeword; 0 for a
+// flagged chunk (also to be passed for a lane without a chunk) and for a zero chunk (r2 == 0).
+// Called by all 64 lanes.
+// my_ubuf: the wave's [64][4] x 8 B operand buffer; amat / secl: the head's A operands and
+// secondaries in LDS.
+__device__ __forceinline__ uint32_t search_codeword(const Geometry &g, int lane, const Direction u, bool flagged,
+                                                    double r2, int rq,
+                                                    uint2 *my_ubuf, const uint4 *amat, const float *secl)
+{
+    const float u0 = u.u0, u1 = u.u1, u2 = u.u2, u3 = u.u3;
+    wave_lds_sync();  // this wave's reads of ubuf / pack from the previous iteration are done
+    {
+        const Parts p0 = split3(u0 * kOperandScale), p1 = split3(u1 * kOperandScale);
+        const Parts p2 = split3(u2 * kOperandScale), p3 = split3(u3 * kOperandScale);
+        uint4 *dst = reinterpret_cast<uint4 *>(my_ubuf + 4 * lane);
+        dst[0] = make_uint4(pack2(p0.h, p0.l), pack2(p0.m, (_Float16)0.f), pack2(p1.h, p1.l), pack2(p1.m, (_Float16)0.f));
+        dst[1] = make_uint4(pack2(p2.h, p2.l), pack2(p2.m, (_Float16)0.f), pack2(p3.h, p3.l), pack2(p3.m, (_Float16)0.f));
+    }
+    wave_lds_sync();
+    // B operand of chunk group j: lane (col l % 16, k l / 16) holds the parts of u_k of chunk 16 j + col
+    half8_t bop[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint2 e = my_ubuf[4 * (16 * j + (lane & 15)) + (lane >> 4)];  // (h, l), (m, 0)
+        const uint32_t mh = __builtin_amdgcn_perm(e.x, e.y, 0x05040100u);   // (m, h)
+        const uint32_t ml = __builtin_amdgcn_perm(e.x, e.y, 0x07060100u);   // (m, l)
+        bop[j] = __builtin_bit_cast(half8_t, make_uint4(e.x, e.x, mh, ml));
+    }
+
+    // ---- exhaustive search over the secondaries -------------------------------------------
+    // best[j] / bkey[j]: running maximum of the closed-form score and 16 x the group of 16
+    // secondaries (4 of them on this lane: s = 16 grp + 4 t + lane/16) that reached it.
+    float best[4] = {-1.f, -1.f, -1.f, -1.f};
+    int bkey[4] = {0, 0, 0, 0};
+    const float4_t zero4 = {0.f, 0.f, 0.f, 0.f};
+    for (int grp = 0; grp < g.S16; ++grp) {
+        // Over the group's 4 secondaries: GA = largest |v_i| (best axis element), GH = largest
+        // |v_0|+|v_1|+|v_2|+|v_3| (twice the best half-integer element); the group's score is
+        // max(GA, GH / 2), taken once per group.
+        float GA[4] = {0.f, 0.f, 0.f, 0.f}, GH[4] = {0.f, 0.f, 0.f, 0.f};
+        const uint4 *arow = amat + (size_t)grp * 4 * 64 + lane;
+        half8_t aop[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+            aop[t] = __builtin_bit_cast(half8_t, arow[t * 64]);
+        // 8 pairs of products (secondaries 2 tp, 2 tp + 1 of the group x chunk group j).  The
+        // products of pair k + 1 are issued before the arithmetic on pair k: MFMA and VALU do not
+        // overlap on this SIMD, but a VALU instruction right behind the MFMA it depends on idles
+        // for the depth of the matrix pipeline.
+        float4_t vA = __builtin_amdgcn_mfma_f32_16x16x32_f16(aop[0], bop[0], zero4, 0, 0, 0);
+        float4_t vB = __builtin_amdgcn_mfma_f32_16x16x32_f16(aop[1], bop[0], zero4, 0, 0, 0);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int j = k & 3;
+            const float4_t cA = vA, cB = vB;
+            if (k + 1 < 8) {
+                const int tn = (k + 1) >> 2, jn = (k + 1) & 3;
+                vA = __builtin_amdgcn_mfma_f32_16x16x32_f16(aop[2 * tn], bop[jn], zero4, 0, 0, 0);
+                vB = __builtin_amdgcn_mfma_f32_16x16x32_f16(aop[2 * tn + 1], bop[jn], zero4, 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);  // products first, then the arithmetic on the older pair
+            const float a0 = fabsf(cA[0]), a1 = fabsf(cA[1]), a2 = fabsf(cA[2]), a3 = fabsf(cA[3]);
+            const float b0 = fabsf(cB[0]), b1 = fabsf(cB[1]), b2 = fabsf(cB[2]), b3 = fabsf(cB[3]);
+            const float hA = ((a0 + a1) + a2) + a3;
+            const float hB = ((b0 + b1) + b2) + b3;
+            float ga = fmaxf(fmaxf(GA[j], a0), a1);  // v_max3 each
+            ga = fmaxf(fmaxf(ga, a2), a3);
+            ga = fmaxf(fmaxf(ga, b0), b1);
+            GA[j] = fmaxf(fmaxf(ga, b2), b3);
+            GH[j] = fmaxf(fmaxf(GH[j], hA), hB);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float M = fmaxf(GA[j], 0.5f * GH[j]);
+            if (M > best[j]) {
+                best[j] = M;
+                bkey[j] = 16 * grp;
+            }
+        }
+    }
+
+    // ---- reduce over the 4 lanes that share a chunk, hand the winner to the owner lane ------
+    // key = 16 grp + lane/16: the first of the 4 candidates s = key + 4 t of the winning lane.
+    // Chunk 16 j + col was scored by lanes col, col + 16, col + 32, col + 48 (slot j of each) and
+    // is owned by lane 16 j + col: the (score, key) pairs go through LDS (the operand buffer is
+    // free by now), the owner reads its four and keeps the larger score, the lower key on equal ones.
+    int key_mine;
+    {
+        uint2 *red = my_ubuf;  // [4 slots][64 lanes]
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            red[j * 64 + lane] = make_uint2(__float_as_uint(best[j]), (uint32_t)(bkey[j] + (lane >> 4)));
+        wave_lds_sync();
+        const uint2 *mine = red + (lane >> 4) * 64 + (lane & 15);
+        uint2 e = mine[0];
+        float bj = __uint_as_float(e.x);
+        int kj = (int)e.y;
+#pragma unroll
+        for (int m = 1; m < 4; ++m) {
+            e = mine[16 * m];
+            const float ob = __uint_as_float(e.x);
+            const int ok = (int)e.y;
+            const bool take = (ob > bj) | ((ob == bj) & (ok < kj));
+            bj = take ? ob : bj;
+            kj = take ? ok : kj;
+        }
+        key_mine = kj;
+    }
+
+    // ---- re-score the 4 candidates of the winning group: secondary, primary -----------------
+    uint32_t code = 0;
+    if (!flagged && r2 != 0.0) {
+        float bsc = -1.f;
+        float w0 = 0.f, w1 = 0.f, w2 = 0.f, w3 = 0.f;
+        int bs = key_mine;
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) {
+            const int sc_idx = key_mine + 4 * tt;  // < 16 S16: inside the padded table
+            const float *q = secl + 4 * sc_idx;
+            const float a = q[0], bq = q[1], cq = q[2], d = q[3];
+            const float v0 = fmaf(d, u3, fmaf(cq, u2, fmaf(bq, u1, a * u0)));
+            const float v1 = fmaf(cq, u3, fmaf(-d, u2, fmaf(a, u1, -bq * u0)));
+            const float v2 = fmaf(-bq, u3, fmaf(a, u2, fmaf(d, u1, -cq * u0)));
+            const float v3 = fmaf(a, u3, fmaf(bq, u2, fmaf(-cq, u1, -d * u0)));
+            const float a0 = fabsf(v0), a1 = fabsf(v1), a2 = fabsf(v2), a3 = fabsf(v3);
+            const float sc = fmaxf(fmaxf(fmaxf(a0, a1), fmaxf(a2, a3)), 0.5f * (((a0 + a1) + a2) + a3));
+            const bool take = (sc_idx < g.S) & (sc > bsc);  // strict: the lowest s wins a tie
+            bsc = take ? sc : bsc;
+            bs = take ? sc_idx : bs;
+            w0 = take ? v0 : w0;
+            w1 = take ? v1 : w1;
+            w2 = take ? v2 : w2;
+            w3 = take ? v3 : w3;
+        }
+        float sc;
+        const int p = nearest_primary(w0, w1, w2, w3, sc);
+        code = ((uint32_t)rq << g.w_idx) | (uint32_t)(p * g.S + bs);
+    }
+    return code;
+}
+
 }  // namespace
 
 // The K = 4 contraction v = A(q_s) u runs on v_mfma_f32_16x16x32_f16, which issues in half the time
@@ -186,10 +394,9 @@ __global__ __launch_bounds__(kThreads) void k_prepare_operands(Geometry g, Works
 
 // kWaves: 4, or 8 when the A operands are so large (S > 256) that only one workgroup fits a CU: twice
 // the waves then share them and keep two waves on every SIMD.
-// kFull: D = 128, every lane of a 32-lane row slot holds a chunk.  Otherwise a row has g.n_c <= 32
-// chunks: the lanes past them carry a zero chunk (no flag, code 0, no part in the row's scale) and
-// only the row's ceil(n_c w / 32) code words are stored.
-template <int kWaves, int kRows, bool kFull>
+// This kernel is for rows of 128 elements (32 chunks: two rows per wave); k_search_flat below takes
+// every other head dimension.
+template <int kWaves, int kRows>
 __global__ __launch_bounds__(64 * kWaves) void k_search(Geometry g, WorkspaceOffsets wo, EncodeBatch batch)
 {
     constexpr int kThreadsS = 64 * kWaves;
@@ -232,8 +439,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_search(Geometry g, WorkspaceOff
     const int c = lane & 31, half_id = lane >> 5;
     uint2 *my_ubuf = ubuf + wv * 64 * 4;
     uint32_t *my_pack = pack + wv * 64;
-    const _Float16 *base = x + (int64_t)b * g.sb + (int64_t)h * g.sh;
-    const int row_words = kFull ? g.w : g.row_words;
+    const _Float16 *base = x + (int64_t)b * g.sb + (int64_t)h * g.sh + 4 * c;
 
     for (int it = 0; it < kRows / (2 * kWaves); ++it) {
         const int r_in_block = it * 2 * kWaves + wv * 2 + half_id;
@@ -246,9 +452,9 @@ __global__ __launch_bounds__(64 * kWaves) void k_search(Geometry g, WorkspaceOff
         }
 
         // ---- chunk, norm, flag, row scale --------------------------------------------------
-        half4_t xv = valid ? load_row_chunk<kFull>(base + (int64_t)t * g.st, c, g) : half4_t{0, 0, 0, 0};
+        half4_t xv = valid ? load_chunk(base + (int64_t)t * g.st) : half4_t{0, 0, 0, 0};
         const double r2 = chunk_norm2(xv);
-        const bool flagged = valid && (kFull || c < g.n_c) && (r2 > thr);
+        const bool flagged = valid && (r2 > thr);
         const unsigned long long ballot = __ballot(flagged);
         const uint32_t word = half_id ? (uint32_t)(ballot >> 32) : (uint32_t)ballot;
 
@@ -262,187 +468,12 @@ __global__ __launch_bounds__(64 * kWaves) void k_search(Geometry g, WorkspaceOff
         rbits = umax64(rbits, dpp_move64<0x140>(rbits));  // row_mirror
         rbits = umax64(rbits, (unsigned long long)__shfl_xor((long long)rbits, 16, 64));
         const double rmax = __longlong_as_double((long long)rbits);
-        // sigma = fp16(sqrt(rmax)), round to nearest even, saturating.  The fp32 square root is within
-        // 2 ulp(fp32) of the exact one, so it rounds to the same fp16 value unless it lies within a few
-        // fp32 ulp of a rounding boundary (the 13 dropped bits close to 0x1000) or the result is
-        // subnormal; only then is the fp64 recipe run.
-        uint16_t sigma16 = 0;
-        {
-            const float sf = sqrtf((float)rmax);
-            const uint32_t sb = __float_as_uint(sf);
-            const int dist = (int)(sb & 0x1fffu) - 0x1000;
-            const bool slow = rmax != 0.0 && sf < 65504.f && (sf < 0x1.0p-14f || (dist >= -8 && dist <= 8));
-            sigma16 = sf >= 65504.f ? (uint16_t)0x7bff : __builtin_bit_cast(uint16_t, (_Float16)sf);
-            if (__any(slow)) {
-                if (slow)
-                    sigma16 = double_to_half_rne_sat(sqrt(rmax));
-            }
-        }
-        const double sigma = half_bits_to_double(sigma16);
-
-        // Radius code r_q = clamp(rint(sqrt(r2) * L / sigma), 0, L), defined in fp64.  An fp32
-        // evaluation with the hardware's 1-ulp square root and reciprocal is off by at most
-        // 6e-7 * L (five roundings of <= 1.2e-7 each); it rounds the same way unless it lands within
-        // that distance of a rounding boundary, and only then is the fp64 recipe run (about one wave
-        // in two hundred at L = 63).
-        int rq = 0;
-        const float r2f = (float)r2;
-        const float r_f = __builtin_amdgcn_sqrtf(r2f);
-        const float sigma_f = (float)__builtin_bit_cast(_Float16, sigma16);
-        bool exact_needed = false;
-        if (sigma16 != 0 && r2 != 0.0) {
-            const float qf = fminf(r_f * (float)Lq * __builtin_amdgcn_rcpf(sigma_f), (float)Lq);
-            const float fr = qf - floorf(qf);
-            exact_needed = fabsf(fr - 0.5f) < 6e-7f * (float)Lq + 1e-6f;
-            rq = (int)rintf(qf);
-        }
-        if (__any(exact_needed)) {
-            if (exact_needed) {
-                double q = rint((sqrt(r2) * Lq) / sigma);
-                q = q < 0.0 ? 0.0 : (q > Lq ? Lq : q);
-                rq = (int)q;
-            }
-        }
-
-        // ---- unit direction (fp32) and its transpose into MFMA B operands --------------------
-        float u0 = 0.f, u1 = 0.f, u2 = 0.f, u3 = 0.f;
-        if (r2 != 0.0) {
-            const float inv = __builtin_amdgcn_rcpf(r_f);
-            u0 = (float)xv[0] * inv;
-            u1 = (float)xv[1] * inv;
-            u2 = (float)xv[2] * inv;
-            u3 = (float)xv[3] * inv;
-        }
-        wave_lds_sync();  // this wave's reads of ubuf / pack from the previous iteration are done
-        {
-            const Parts p0 = split3(u0 * kOperandScale), p1 = split3(u1 * kOperandScale);
-            const Parts p2 = split3(u2 * kOperandScale), p3 = split3(u3 * kOperandScale);
-            uint4 *dst = reinterpret_cast<uint4 *>(my_ubuf + 4 * lane);
-            dst[0] = make_uint4(pack2(p0.h, p0.l), pack2(p0.m, (_Float16)0.f), pack2(p1.h, p1.l), pack2(p1.m, (_Float16)0.f));
-            dst[1] = make_uint4(pack2(p2.h, p2.l), pack2(p2.m, (_Float16)0.f), pack2(p3.h, p3.l), pack2(p3.m, (_Float16)0.f));
-        }
-        my_pack[lane] = 0;
-        wave_lds_sync();
-        // B operand of chunk group j: lane (col l % 16, k l / 16) holds the parts of u_k of chunk 16 j + col
-        half8_t bop[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const uint2 e = my_ubuf[4 * (16 * j + (lane & 15)) + (lane >> 4)];  // (h, l), (m, 0)
-            const uint32_t mh = __builtin_amdgcn_perm(e.x, e.y, 0x05040100u);   // (m, h)
-            const uint32_t ml = __builtin_amdgcn_perm(e.x, e.y, 0x07060100u);   // (m, l)
-            bop[j] = __builtin_bit_cast(half8_t, make_uint4(e.x, e.x, mh, ml));
-        }
-
-        // ---- exhaustive search over the secondaries -------------------------------------------
-        // best[j] / bgrp[j]: running maximum of the closed-form score and the group of 16
-        // secondaries (4 of them on this lane: s = 16 grp + 4 t + lane/16) that reached it.
-        float best[4] = {-1.f, -1.f, -1.f, -1.f};
-        int bgrp[4] = {0, 0, 0, 0};
-        const float4_t zero4 = {0.f, 0.f, 0.f, 0.f};
-        for (int grp = 0; grp < g.S16; ++grp) {
-            // Over the group's 4 secondaries: GA = largest |v_i| (best axis element), GH = largest
-            // |v_0|+|v_1|+|v_2|+|v_3| (twice the best half-integer element); the group's score is
-            // max(GA, GH / 2), taken once per group.
-            float GA[4] = {0.f, 0.f, 0.f, 0.f}, GH[4] = {0.f, 0.f, 0.f, 0.f};
-            const uint4 *arow = amat + (size_t)grp * 4 * 64 + lane;
-            half8_t aop[4];
-#pragma unroll
-            for (int t = 0; t < 4; ++t)
-                aop[t] = __builtin_bit_cast(half8_t, arow[t * 64]);
-            // 8 pairs of products (secondaries 2 tp, 2 tp + 1 of the group x chunk group j).  The
-            // products of pair k + 1 are issued before the arithmetic on pair k: MFMA and VALU do not
-            // overlap on this SIMD, but a VALU instruction right behind the MFMA it depends on idles
-            // for the depth of the matrix pipeline.
-            float4_t vA = __builtin_amdgcn_mfma_f32_16x16x32_f16(aop[0], bop[0], zero4, 0, 0, 0);
-            float4_t vB = __builtin_amdgcn_mfma_f32_16x16x32_f16(aop[1], bop[0], zero4, 0, 0, 0);
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                const int j = k & 3;
-                const float4_t cA = vA, cB = vB;
-                if (k + 1 < 8) {
-                    const int tn = (k + 1) >> 2, jn = (k + 1) & 3;
-                    vA = __builtin_amdgcn_mfma_f32_16x16x32_f16(aop[2 * tn], bop[jn], zero4, 0, 0, 0);
-                    vB = __builtin_amdgcn_mfma_f32_16x16x32_f16(aop[2 * tn + 1], bop[jn], zero4, 0, 0, 0);
-                }
-                __builtin_amdgcn_sched_barrier(0);  // products first, then the arithmetic on the older pair
-                const float a0 = fabsf(cA[0]), a1 = fabsf(cA[1]), a2 = fabsf(cA[2]), a3 = fabsf(cA[3]);
-                const float b0 = fabsf(cB[0]), b1 = fabsf(cB[1]), b2 = fabsf(cB[2]), b3 = fabsf(cB[3]);
-                const float hA = ((a0 + a1) + a2) + a3;
-                const float hB = ((b0 + b1) + b2) + b3;
-                float ga = fmaxf(fmaxf(GA[j], a0), a1);  // v_max3 each
-                ga = fmaxf(fmaxf(ga, a2), a3);
-                ga = fmaxf(fmaxf(ga, b0), b1);
-                GA[j] = fmaxf(fmaxf(ga, b2), b3);
-                GH[j] = fmaxf(fmaxf(GH[j], hA), hB);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const float M = fmaxf(GA[j], 0.5f * GH[j]);
-                if (M > best[j]) {
-                    best[j] = M;
-                    bgrp[j] = grp;
-                }
-            }
-        }
-
-        // ---- reduce over the 4 lanes that share a chunk, hand the winner to the owner lane ------
-        // key = 16 grp + lane/16: the first of the 4 candidates s = key + 4 t of the winning lane.
-        // Chunk 16 j + col was scored by lanes col, col + 16, col + 32, col + 48 (slot j of each) and
-        // is owned by lane 16 j + col: the (score, key) pairs go through LDS (the operand buffer is
-        // free by now), the owner reads its four and keeps the larger score, the lower key on equal ones.
-        int key_mine;
-        {
-            uint2 *red = my_ubuf;  // [4 slots][64 lanes]
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                red[j * 64 + lane] = make_uint2(__float_as_uint(best[j]), (uint32_t)(16 * bgrp[j] + (lane >> 4)));
-            wave_lds_sync();
-            const uint2 *mine = red + (lane >> 4) * 64 + (lane & 15);
-            uint2 e = mine[0];
-            float bj = __uint_as_float(e.x);
-            int kj = (int)e.y;
-#pragma unroll
-            for (int m = 1; m < 4; ++m) {
-                e = mine[16 * m];
-                const float ob = __uint_as_float(e.x);
-                const int ok = (int)e.y;
-                const bool take = (ob > bj) | ((ob == bj) & (ok < kj));
-                bj = take ? ob : bj;
-                kj = take ? ok : kj;
-            }
-            key_mine = kj;
-        }
-
-        // ---- re-score the 4 candidates of the winning group: secondary, primary, code word -------
-        uint32_t code = 0;
-        if (!flagged && r2 != 0.0) {
-            float bsc = -1.f;
-            float w0 = 0.f, w1 = 0.f, w2 = 0.f, w3 = 0.f;
-            int bs = key_mine;
-#pragma unroll
-            for (int tt = 0; tt < 4; ++tt) {
-                const int sc_idx = key_mine + 4 * tt;  // < 16 S16: inside the padded table
-                const float *q = secl + 4 * sc_idx;
-                const float a = q[0], bq = q[1], cq = q[2], d = q[3];
-                const float v0 = fmaf(d, u3, fmaf(cq, u2, fmaf(bq, u1, a * u0)));
-                const float v1 = fmaf(cq, u3, fmaf(-d, u2, fmaf(a, u1, -bq * u0)));
-                const float v2 = fmaf(-bq, u3, fmaf(a, u2, fmaf(d, u1, -cq * u0)));
-                const float v3 = fmaf(a, u3, fmaf(bq, u2, fmaf(-cq, u1, -d * u0)));
-                const float a0 = fabsf(v0), a1 = fabsf(v1), a2 = fabsf(v2), a3 = fabsf(v3);
-                const float sc = fmaxf(fmaxf(fmaxf(a0, a1), fmaxf(a2, a3)), 0.5f * (((a0 + a1) + a2) + a3));
-                const bool take = (sc_idx < g.S) & (sc > bsc);  // strict: the lowest s wins a tie
-                bsc = take ? sc : bsc;
-                bs = take ? sc_idx : bs;
-                w0 = take ? v0 : w0;
-                w1 = take ? v1 : w1;
-                w2 = take ? v2 : w2;
-                w3 = take ? v3 : w3;
-            }
-            float sc;
-            const int p = nearest_primary(w0, w1, w2, w3, sc);
-            code = ((uint32_t)rq << g.w_idx) | (uint32_t)(p * g.S + bs);
-        }
+        const uint16_t sigma16 = sigma_of_row_max(rmax);
+        const float r_f = __builtin_amdgcn_sqrtf((float)r2);
+        const int rq = radius_code(r2, r_f, sigma16, Lq);
+        const Direction u = unit_direction(xv, r2, r_f);
+        my_pack[lane] = 0;  // after the previous iteration's reads of it: LDS serves a wave in order
+        const uint32_t code = search_codeword(g, lane, u, flagged, r2, rq, my_ubuf, amat, secl);
 
         // ---- pack the row: chunk c at bits [c*w, (c+1)*w) -----------------------------------------
         {
@@ -458,8 +489,8 @@ __global__ __launch_bounds__(64 * kWaves) void k_search(Geometry g, WorkspaceOff
         wave_lds_sync();
         if (valid) {
             const int64_t R = row0 + t;
-            if (c < row_words)
-                enc.codes[R * row_words + c] = my_pack[half_id * 32 + c];
+            if (c < g.w)
+                enc.codes[R * g.w + c] = my_pack[half_id * 32 + c];
             if (c == 0) {
                 enc.sigma[R] = sigma16;
                 enc.flags[R] = word;
@@ -494,29 +525,174 @@ __global__ __launch_bounds__(64 * kWaves) void k_search(Geometry g, WorkspaceOff
     }
 }
 
+// The same search for any head dimension: rows of n_c = ceil(D / 4) <= 32 chunks.  A workgroup owns
+// 64 rows of one (b, h) segment and treats their n_c * 64 chunks as one flat list, 64 consecutive
+// chunks per wave and iteration, so that every lane of every matrix product carries a chunk whatever
+// n_c is.  Rows then straddle waves, so what the row-per-half-wave kernel does with cross-lane
+// operations goes through LDS here:
+//   pass 1  every chunk's squared norm once: flagged chunks set their bit in the row's flag word,
+//           the others take part in the row's maximum (atomics on LDS); one lane per row then turns
+//           the maximum into the fp16 scale and writes scale and flag word out;
+//   pass 2  the chunks again (second read from L2): radius code against the row's scale, direction
+//           search, code word OR-ed into the row's slot of the packing area;
+//   end     the packing area goes out as one contiguous block, then the outlier offsets as above.
+// Dynamic LDS: amat | secl | ubuf as in k_search, then rowmax u64 [64] | fword u32 [64] | sig u32 [64]
+// | rcnt u32 [64] | pack u32 [64 * row_words].
+template <int kWaves>
+__global__ __launch_bounds__(64 * kWaves) void k_search_flat(Geometry g, WorkspaceOffsets wo, EncodeBatch batch)
+{
+    constexpr int kThreadsS = 64 * kWaves;
+    constexpr int kRows = kSearchRowsSmall;
+    static_assert(kRows == 64, "one lane of wave 0 per row in the scale pass and the offset scan");
+    const EncodeTensor &tn = batch.t[blockIdx.z];
+    const Workspace ws = carve_workspace(tn.ws, wo);
+    const EncodedPtrs enc = tn.enc;
+    const _Float16 *__restrict__ x = tn.x;
+    extern __shared__ float smem[];
+    uint4 *amat = reinterpret_cast<uint4 *>(smem);
+    float *secl = reinterpret_cast<float *>(amat + (size_t)g.S16 * 4 * 64);
+    uint2 *ubuf = reinterpret_cast<uint2 *>(secl + (size_t)g.S16 * 16 * 4);
+    unsigned long long *rowmax = reinterpret_cast<unsigned long long *>(ubuf + kWaves * 64 * 4);
+    uint32_t *fword = reinterpret_cast<uint32_t *>(rowmax + kRows);
+    uint32_t *sig = fword + kRows;
+    uint32_t *rcnt = sig + kRows;
+    uint32_t *pack = rcnt + kRows;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int seg = blockIdx.y, b = seg / g.H, h = seg % g.H;
+    const int t0 = blockIdx.x * kRows;
+    const int nrows = min(kRows, g.T - t0);       // >= 1 by the grid's size
+    const int nchunks = nrows * g.n_c;
+    const int row_words = g.row_words;
+    const int64_t row0 = (int64_t)seg * g.T + t0;  // linear index of the workgroup's first row
+    const float *sec_h = tn.sec + (size_t)h * g.S * 4;
+
+    // ---- setup: tables into LDS, per-row state cleared ------------------------------------------
+    for (int s = tid; s < g.S16 * 16; s += kThreadsS) {
+        float4_t q = {0.f, 0.f, 0.f, 0.f};
+        if (s < g.S)
+            q = *reinterpret_cast<const float4_t *>(sec_h + 4 * s);
+        *reinterpret_cast<float4_t *>(secl + 4 * s) = q;
+    }
+    {
+        const uint4 *src = ws.aop + (size_t)h * g.S16 * 4 * 64;
+        for (int idx = tid; idx < g.S16 * 4 * 64; idx += kThreadsS)
+            amat[idx] = src[idx];
+    }
+    for (int i = tid; i < kRows; i += kThreadsS) {
+        rowmax[i] = 0ull;
+        fword[i] = 0u;
+    }
+    for (int i = tid; i < kRows * row_words; i += kThreadsS)
+        pack[i] = 0u;
+    __syncthreads();
+
+    const double thr = ws.thr[h];
+    const double Lq = (double)((1 << g.b_r) - 1);
+    const _Float16 *base = x + (int64_t)b * g.sb + (int64_t)h * g.sh + (int64_t)t0 * g.st;
+
+    // ---- pass 1: flags and row maxima ---------------------------------------------------------------
+    for (int q = tid; q < nchunks; q += kThreadsS) {
+        const int r = q / g.n_c, c = q - r * g.n_c;
+        const double r2 = chunk_norm2(load_row_chunk<false>(base + (int64_t)r * g.st, c, g));
+        if (r2 > thr)
+            atomicOr(&fword[r], 1u << c);
+        else
+            atomicMax(&rowmax[r], key_of(r2));  // non-negative doubles order like their bit patterns
+    }
+    __syncthreads();
+    if (tid < kRows) {
+        uint32_t word = 0;
+        if (tid < nrows) {
+            word = fword[tid];
+            const uint16_t sigma16 = sigma_of_row_max(__longlong_as_double((long long)rowmax[tid]));
+            sig[tid] = sigma16;
+            enc.sigma[row0 + tid] = sigma16;
+            enc.flags[row0 + tid] = word;
+        }
+        rcnt[tid] = __popc(word);
+    }
+    __syncthreads();
+
+    // ---- pass 2: radius codes and the direction search ----------------------------------------------
+    uint2 *my_ubuf = ubuf + wv * 64 * 4;
+    for (int q0 = wv * 64; q0 < nchunks; q0 += kThreadsS) {  // wave-uniform trip count
+        const int q = q0 + lane;
+        const bool valid = q < nchunks;
+        const int r = valid ? q / g.n_c : 0, c = valid ? q - r * g.n_c : 0;
+        const half4_t xv = valid ? load_row_chunk<false>(base + (int64_t)r * g.st, c, g) : half4_t{0, 0, 0, 0};
+        const double r2 = chunk_norm2(xv);
+        const bool flagged = valid && (r2 > thr);
+        const uint16_t sigma16 = (uint16_t)sig[r];
+        const float r_f = __builtin_amdgcn_sqrtf((float)r2);
+        const int rq = radius_code(r2, r_f, sigma16, Lq);
+        const Direction u = unit_direction(xv, r2, r_f);
+        const uint32_t code = search_codeword(g, lane, u, flagged || !valid, r2, rq, my_ubuf, amat, secl);
+        if (code) {
+            const uint32_t bitpos = (uint32_t)c * g.w;
+            const uint32_t d0 = bitpos >> 5, sh = bitpos & 31;
+            uint32_t *rowp = pack + r * row_words;
+            atomicOr(&rowp[d0], code << sh);
+            if (sh + g.w > 32)
+                atomicOr(&rowp[d0 + 1], code >> (32 - sh));
+        }
+    }
+    __syncthreads();
+
+    // ---- the workgroup's code words: one contiguous block ------------------------------------------
+    {
+        uint32_t *dst = enc.codes + row0 * row_words;
+        for (int i = tid; i < nrows * row_words; i += kThreadsS)
+            dst[i] = pack[i];
+    }
+    // ---- outlier offsets local to the workgroup and its total ---------------------------------------
+    if (wv == 0) {
+        const uint32_t cnt = rcnt[lane];
+        uint32_t inc = cnt;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            uint32_t o = __shfl_up(inc, d, 64);
+            if (lane >= d)
+                inc += o;
+        }
+        if (lane < nrows)
+            enc.row_off[row0 + lane] = inc - cnt;
+        if (lane == 63)
+            ws.block_sum[(size_t)seg * g.n_search_blocks_per_seg + blockIdx.x] = inc;
+    }
+}
+
 hipError_t launch_search(const Geometry &g, const WorkspaceOffsets &wo, const EncodeBatch &batch, int n_tensors,
                          hipStream_t stream)
 {
     dim3 grid((g.T + g.search_rows - 1) / g.search_rows, g.B * g.H, (unsigned)n_tensors);
-    const int waves = g.S16 > 16 ? 8 : 4;
-    const size_t lds = (size_t)g.S16 * 4 * 64 * sizeof(uint4) + (size_t)g.S16 * 16 * 4 * sizeof(float) +
-                       (size_t)waves * 64 * 4 * sizeof(uint2) + ((size_t)waves * 2 * 32 + (size_t)g.search_rows) * sizeof(uint32_t);
-    // more than the 64 KiB a kernel gets by default once S > 208: raise the kernel's limit, once per device
+    const bool full = g.D == 4 * kChunksPerRow;
+    const size_t lds_tables = (size_t)g.S16 * 4 * 64 * sizeof(uint4) + (size_t)g.S16 * 16 * 4 * sizeof(float);
+    const size_t lds_rows = full ? (size_t)g.search_rows * sizeof(uint32_t)
+                                 : (size_t)kSearchRowsSmall * (8 + 4 + 4 + 4 + 4 * (size_t)g.row_words);
+    auto lds_for = [&](int waves) {
+        return lds_tables + (size_t)waves * 64 * 4 * sizeof(uint2) + (full ? (size_t)waves * 2 * 32 * sizeof(uint32_t) : 0) +
+               lds_rows;
+    };
+    // 4 waves when two workgroups fit a CU's 160 KiB; otherwise one workgroup of 8 keeps two waves on
+    // every SIMD and shares one copy of the tables
+    const int waves = 2 * lds_for(4) > 160 * 1024 ? 8 : 4;
+    const size_t lds = lds_for(waves);
+    // more than the 64 KiB a kernel gets by default once S > 208: raise the kernels' limit, once per device
     static bool raised[64] = {};
     int device = 0;
     hipError_t err = hipGetDevice(&device);
     if (err != hipSuccess)
         return err;
     if (device < 0 || device >= 64 || !raised[device]) {
-        const void *variants[8] = {reinterpret_cast<const void *>(k_search<4, kSearchRowsSmall, true>),
-                                   reinterpret_cast<const void *>(k_search<4, kSearchRowsLarge, true>),
-                                   reinterpret_cast<const void *>(k_search<8, kSearchRowsSmall, true>),
-                                   reinterpret_cast<const void *>(k_search<8, kSearchRowsLarge, true>),
-                                   reinterpret_cast<const void *>(k_search<4, kSearchRowsSmall, false>),
-                                   reinterpret_cast<const void *>(k_search<4, kSearchRowsLarge, false>),
-                                   reinterpret_cast<const void *>(k_search<8, kSearchRowsSmall, false>),
-                                   reinterpret_cast<const void *>(k_search<8, kSearchRowsLarge, false>)};
-        for (int i = 0; i < 8 && err == hipSuccess; ++i)
+        const void *variants[6] = {reinterpret_cast<const void *>(k_search<4, kSearchRowsSmall>),
+                                   reinterpret_cast<const void *>(k_search<4, kSearchRowsLarge>),
+                                   reinterpret_cast<const void *>(k_search<8, kSearchRowsSmall>),
+                                   reinterpret_cast<const void *>(k_search<8, kSearchRowsLarge>),
+                                   reinterpret_cast<const void *>(k_search_flat<4>),
+                                   reinterpret_cast<const void *>(k_search_flat<8>)};
+        for (int i = 0; i < 6 && err == hipSuccess; ++i)
             err = hipFuncSetAttribute(variants[i], hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (err != hipSuccess)
             return err;
@@ -526,29 +702,19 @@ hipError_t launch_search(const Geometry &g, const WorkspaceOffsets &wo, const En
     hipLaunchKernelGGL(k_prepare_operands, dim3((g.S16 * 4 * 64 + kThreads - 1) / kThreads, g.H, (unsigned)n_tensors),
                        dim3(kThreads), 0, stream, g, wo, batch);
     const bool large = g.search_rows == kSearchRowsLarge;
-    const bool full = g.D == 4 * kChunksPerRow;
-#define HQMQ_LAUNCH_SEARCH(W, R, F) \
-    hipLaunchKernelGGL((k_search<W, R, F>), grid, dim3(64 * W), lds, stream, g, wo, batch)
-    if (full) {
-        if (waves == 8 && large)
-            HQMQ_LAUNCH_SEARCH(8, kSearchRowsLarge, true);
-        else if (waves == 8)
-            HQMQ_LAUNCH_SEARCH(8, kSearchRowsSmall, true);
-        else if (large)
-            HQMQ_LAUNCH_SEARCH(4, kSearchRowsLarge, true);
+    if (!full) {
+        if (waves == 8)
+            hipLaunchKernelGGL(k_search_flat<8>, grid, dim3(512), lds, stream, g, wo, batch);
         else
-            HQMQ_LAUNCH_SEARCH(4, kSearchRowsSmall, true);
-    } else {
-        if (waves == 8 && large)
-            HQMQ_LAUNCH_SEARCH(8, kSearchRowsLarge, false);
-        else if (waves == 8)
-            HQMQ_LAUNCH_SEARCH(8, kSearchRowsSmall, false);
-        else if (large)
-            HQMQ_LAUNCH_SEARCH(4, kSearchRowsLarge, false);
-        else
-            HQMQ_LAUNCH_SEARCH(4, kSearchRowsSmall, false);
-    }
-#undef HQMQ_LAUNCH_SEARCH
+            hipLaunchKernelGGL(k_search_flat<4>, grid, dim3(256), lds, stream, g, wo, batch);
+    } else if (waves == 8 && large)
+        hipLaunchKernelGGL((k_search<8, kSearchRowsLarge>), grid, dim3(512), lds, stream, g, wo, batch);
+    else if (waves == 8)
+        hipLaunchKernelGGL((k_search<8, kSearchRowsSmall>), grid, dim3(512), lds, stream, g, wo, batch);
+    else if (large)
+        hipLaunchKernelGGL((k_search<4, kSearchRowsLarge>), grid, dim3(256), lds, stream, g, wo, batch);
+    else
+        hipLaunchKernelGGL((k_search<4, kSearchRowsSmall>), grid, dim3(256), lds, stream, g, wo, batch);
     return hipGetLastError();
 }
 
