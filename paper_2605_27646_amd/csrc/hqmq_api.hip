@@ -71,8 +71,7 @@ static Geometry make_geometry(const hqmq_params *p)
     for (int j = 0; j < 16; ++j)
         if ((1 << j) == p->S)
             g.log2_S = j;
-    // rows of other lengths than 128 elements go through the search kernel that owns 64 rows per workgroup
-    g.search_rows = (p->T >= kSearchRowsSwitch && p->D == 4 * kChunksPerRow) ? kSearchRowsLarge : kSearchRowsSmall;
+    g.search_rows = search_rows_for(p->T, g.S16, g.D, g.row_words);
     g.n_search_blocks_per_seg = (uint32_t)((p->T + g.search_rows - 1) / g.search_rows);
     return g;
 }

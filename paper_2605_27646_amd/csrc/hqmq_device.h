@@ -48,6 +48,30 @@ struct Geometry {
     uint32_t n_search_blocks_per_seg;  // ceil(T / search_rows)
 };
 
+// Dynamic LDS of one search workgroup (host side; the kernels carve the same layout): the head's
+// MFMA A operands and secondaries, the waves' operand buffers, and the per-row state, which for rows of
+// 128 elements is two rows of code words per wave and a counter per row, and for other row lengths a
+// running maximum, flag word, scale, counter and the code words of every row of the workgroup.
+inline size_t search_lds_bytes(int S16, int D, int row_words, int waves, int rows)
+{
+    const size_t tables = (size_t)S16 * 4 * 64 * 16 + (size_t)S16 * 16 * 4 * 4;
+    const size_t ubuf = (size_t)waves * 64 * 4 * 8;
+    if (D == 4 * kChunksPerRow)
+        return tables + ubuf + ((size_t)waves * 2 * 32 + (size_t)rows) * 4;
+    return tables + ubuf + (size_t)rows * (8 + 4 + 4 + 4 + 4 * (size_t)row_words);
+}
+constexpr size_t kLdsPerCu = 160 * 1024;
+
+// Rows per search workgroup: 256 for long segments (the head's operand table is copied a quarter as
+// often), as long as two such workgroups still fit a CU; 64 otherwise.
+inline int search_rows_for(int T, int S16, int D, int row_words)
+{
+    if (T >= kSearchRowsSwitch &&
+        (D == 4 * kChunksPerRow || 2 * search_lds_bytes(S16, D, row_words, 4, kSearchRowsLarge) <= kLdsPerCu))
+        return kSearchRowsLarge;
+    return kSearchRowsSmall;
+}
+
 // Workspace carve-up (device pointers into the caller's workspace).
 struct Workspace {
     SelectState *state;            // [H]

@@ -526,7 +526,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_search(Geometry g, WorkspaceOff
 }
 
 // The same search for any head dimension: rows of n_c = ceil(D / 4) <= 32 chunks.  A workgroup owns
-// 64 rows of one (b, h) segment and treats their n_c * 64 chunks as one flat list, 64 consecutive
+// 64 or 256 rows of one (b, h) segment and treats their chunks as one flat list, 64 consecutive
 // chunks per wave and iteration, so that every lane of every matrix product carries a chunk whatever
 // n_c is.  Rows then straddle waves, so what the row-per-half-wave kernel does with cross-lane
 // operations goes through LDS here:
@@ -536,14 +536,13 @@ __global__ __launch_bounds__(64 * kWaves) void k_search(Geometry g, WorkspaceOff
 //   pass 2  the chunks again (second read from L2): radius code against the row's scale, direction
 //           search, code word OR-ed into the row's slot of the packing area;
 //   end     the packing area goes out as one contiguous block, then the outlier offsets as above.
-// Dynamic LDS: amat | secl | ubuf as in k_search, then rowmax u64 [64] | fword u32 [64] | sig u32 [64]
-// | rcnt u32 [64] | pack u32 [64 * row_words].
-template <int kWaves>
+// Dynamic LDS: amat | secl | ubuf as in k_search, then rowmax u64 [kRows] | fword u32 [kRows] |
+// sig u32 [kRows] | rcnt u32 [kRows] | pack u32 [kRows * row_words].
+template <int kWaves, int kRows>
 __global__ __launch_bounds__(64 * kWaves) void k_search_flat(Geometry g, WorkspaceOffsets wo, EncodeBatch batch)
 {
     constexpr int kThreadsS = 64 * kWaves;
-    constexpr int kRows = kSearchRowsSmall;
-    static_assert(kRows == 64, "one lane of wave 0 per row in the scale pass and the offset scan");
+    static_assert(kRows % 64 == 0 && kRows <= kThreadsS, "one thread per row in the scale pass");
     const EncodeTensor &tn = batch.t[blockIdx.z];
     const Workspace ws = carve_workspace(tn.ws, wo);
     const EncodedPtrs enc = tn.enc;
@@ -648,18 +647,24 @@ __global__ __launch_bounds__(64 * kWaves) void k_search_flat(Geometry g, Workspa
     }
     // ---- outlier offsets local to the workgroup and its total ---------------------------------------
     if (wv == 0) {
-        const uint32_t cnt = rcnt[lane];
-        uint32_t inc = cnt;
+        uint32_t carry = 0;
 #pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            uint32_t o = __shfl_up(inc, d, 64);
-            if (lane >= d)
-                inc += o;
+        for (int part = 0; part < kRows / 64; ++part) {
+            const int r = 64 * part + lane;
+            const uint32_t cnt = rcnt[r];
+            uint32_t inc = cnt;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                uint32_t o = __shfl_up(inc, d, 64);
+                if (lane >= d)
+                    inc += o;
+            }
+            if (r < nrows)
+                enc.row_off[row0 + r] = carry + inc - cnt;
+            carry += __shfl(inc, 63, 64);
         }
-        if (lane < nrows)
-            enc.row_off[row0 + lane] = inc - cnt;
-        if (lane == 63)
-            ws.block_sum[(size_t)seg * g.n_search_blocks_per_seg + blockIdx.x] = inc;
+        if (lane == 0)
+            ws.block_sum[(size_t)seg * g.n_search_blocks_per_seg + blockIdx.x] = carry;
     }
 }
 
@@ -668,17 +673,10 @@ hipError_t launch_search(const Geometry &g, const WorkspaceOffsets &wo, const En
 {
     dim3 grid((g.T + g.search_rows - 1) / g.search_rows, g.B * g.H, (unsigned)n_tensors);
     const bool full = g.D == 4 * kChunksPerRow;
-    const size_t lds_tables = (size_t)g.S16 * 4 * 64 * sizeof(uint4) + (size_t)g.S16 * 16 * 4 * sizeof(float);
-    const size_t lds_rows = full ? (size_t)g.search_rows * sizeof(uint32_t)
-                                 : (size_t)kSearchRowsSmall * (8 + 4 + 4 + 4 + 4 * (size_t)g.row_words);
-    auto lds_for = [&](int waves) {
-        return lds_tables + (size_t)waves * 64 * 4 * sizeof(uint2) + (full ? (size_t)waves * 2 * 32 * sizeof(uint32_t) : 0) +
-               lds_rows;
-    };
-    // 4 waves when two workgroups fit a CU's 160 KiB; otherwise one workgroup of 8 keeps two waves on
-    // every SIMD and shares one copy of the tables
-    const int waves = 2 * lds_for(4) > 160 * 1024 ? 8 : 4;
-    const size_t lds = lds_for(waves);
+    // 4 waves when two workgroups fit a CU's LDS; otherwise one workgroup of 8 keeps two waves on every
+    // SIMD and shares one copy of the tables
+    const int waves = 2 * search_lds_bytes(g.S16, g.D, g.row_words, 4, g.search_rows) > kLdsPerCu ? 8 : 4;
+    const size_t lds = search_lds_bytes(g.S16, g.D, g.row_words, waves, g.search_rows);
     // more than the 64 KiB a kernel gets by default once S > 208: raise the kernels' limit, once per device
     static bool raised[64] = {};
     int device = 0;
@@ -686,14 +684,16 @@ hipError_t launch_search(const Geometry &g, const WorkspaceOffsets &wo, const En
     if (err != hipSuccess)
         return err;
     if (device < 0 || device >= 64 || !raised[device]) {
-        const void *variants[6] = {reinterpret_cast<const void *>(k_search<4, kSearchRowsSmall>),
+        const void *variants[8] = {reinterpret_cast<const void *>(k_search<4, kSearchRowsSmall>),
                                    reinterpret_cast<const void *>(k_search<4, kSearchRowsLarge>),
                                    reinterpret_cast<const void *>(k_search<8, kSearchRowsSmall>),
                                    reinterpret_cast<const void *>(k_search<8, kSearchRowsLarge>),
-                                   reinterpret_cast<const void *>(k_search_flat<4>),
-                                   reinterpret_cast<const void *>(k_search_flat<8>)};
-        for (int i = 0; i < 6 && err == hipSuccess; ++i)
-            err = hipFuncSetAttribute(variants[i], hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+                                   reinterpret_cast<const void *>(k_search_flat<4, kSearchRowsSmall>),
+                                   reinterpret_cast<const void *>(k_search_flat<4, kSearchRowsLarge>),
+                                   reinterpret_cast<const void *>(k_search_flat<8, kSearchRowsSmall>),
+                                   reinterpret_cast<const void *>(k_search_flat<8, kSearchRowsLarge>)};
+        for (int i = 0; i < 8 && err == hipSuccess; ++i)
+            err = hipFuncSetAttribute(variants[i], hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCu);
         if (err != hipSuccess)
             return err;
         if (device >= 0 && device < 64)
@@ -702,19 +702,27 @@ hipError_t launch_search(const Geometry &g, const WorkspaceOffsets &wo, const En
     hipLaunchKernelGGL(k_prepare_operands, dim3((g.S16 * 4 * 64 + kThreads - 1) / kThreads, g.H, (unsigned)n_tensors),
                        dim3(kThreads), 0, stream, g, wo, batch);
     const bool large = g.search_rows == kSearchRowsLarge;
-    if (!full) {
-        if (waves == 8)
-            hipLaunchKernelGGL(k_search_flat<8>, grid, dim3(512), lds, stream, g, wo, batch);
+#define HQMQ_LAUNCH(KERNEL, W, R) hipLaunchKernelGGL((KERNEL<W, R>), grid, dim3(64 * W), lds, stream, g, wo, batch)
+    if (full) {
+        if (waves == 8 && large)
+            HQMQ_LAUNCH(k_search, 8, kSearchRowsLarge);
+        else if (waves == 8)
+            HQMQ_LAUNCH(k_search, 8, kSearchRowsSmall);
+        else if (large)
+            HQMQ_LAUNCH(k_search, 4, kSearchRowsLarge);
         else
-            hipLaunchKernelGGL(k_search_flat<4>, grid, dim3(256), lds, stream, g, wo, batch);
-    } else if (waves == 8 && large)
-        hipLaunchKernelGGL((k_search<8, kSearchRowsLarge>), grid, dim3(512), lds, stream, g, wo, batch);
-    else if (waves == 8)
-        hipLaunchKernelGGL((k_search<8, kSearchRowsSmall>), grid, dim3(512), lds, stream, g, wo, batch);
-    else if (large)
-        hipLaunchKernelGGL((k_search<4, kSearchRowsLarge>), grid, dim3(256), lds, stream, g, wo, batch);
-    else
-        hipLaunchKernelGGL((k_search<4, kSearchRowsSmall>), grid, dim3(256), lds, stream, g, wo, batch);
+            HQMQ_LAUNCH(k_search, 4, kSearchRowsSmall);
+    } else {
+        if (waves == 8 && large)
+            HQMQ_LAUNCH(k_search_flat, 8, kSearchRowsLarge);
+        else if (waves == 8)
+            HQMQ_LAUNCH(k_search_flat, 8, kSearchRowsSmall);
+        else if (large)
+            HQMQ_LAUNCH(k_search_flat, 4, kSearchRowsLarge);
+        else
+            HQMQ_LAUNCH(k_search_flat, 4, kSearchRowsSmall);
+    }
+#undef HQMQ_LAUNCH
     return hipGetLastError();
 }
 
