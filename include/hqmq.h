@@ -205,6 +205,38 @@ int32_t hqmq_encode_batch_given_thresholds(const hqmq_params *params, int32_t n_
 int32_t hqmq_thresholds(const hqmq_params *params, const void *workspace_dev, int32_t slice,
                         double *thr_out_dev, void *stream);
 
+/* The median of a cache whose TOKEN axis is split over several shards (context-parallel serving:
+ * each GPU holds a slice of T of the same (layer, role) tensor).  Sec. 3 "Median-multiplier outlier
+ * extraction" takes the median per (layer, head, role) over the whole batch, so the shards must agree
+ * on it; everything else of the encode is local to a shard.  The select is a radix select that
+ * exchanges nothing but histograms:
+ *     for pass = 0 .. 5:   every shard calls hqmq_shard_median_pass(pass) on its slice; the caller then
+ *                          SUMS the region hqmq_shard_median_region(pass) names (uint32 counters inside
+ *                          the shard's workspace) over all shards and writes the sums back into every
+ *                          shard's workspace (one all-reduce of 32 KiB * H for pass 0, 4 KiB * H after)
+ *     pass = 6:            every shard calls hqmq_shard_median_pass(6): the thresholds
+ *                          fl(fl(C*C) * median) are now in its workspace, the same on every shard;
+ *                          read them with hqmq_thresholds(params, workspace, 0, ...) and encode the slice
+ *                          with hqmq_encode_given_thresholds.
+ * Pass 0 counts bits 62..50 of the squared norms' bit patterns, passes 1..5 the next 10 bits each of
+ * the keys under the prefix fixed so far; the result is the exact lower median of all shards' chunks,
+ * whatever the values (no candidate lists that could overflow).
+ *   params                 HOST; THIS shard's shape and strides (B, H, D, S, b_r equal on all shards; T may
+ *                          differ); C is used by pass 6; HQMQ_FLAG_NO_OUTLIERS is rejected (INVALID_ARG).
+ *   total_chunks_per_head  B * ceil(D/4) * (sum of T over all shards): the same number on every shard
+ *                          and in every pass; < 2^32 (else UNSUPPORTED), >= this shard's own count.
+ *   pass                   0..5 a counting pass, 6 the finish.  Passes must run in order; the summed
+ *                          histogram of pass p must be in place before pass p + 1 is enqueued.
+ *   x_dev                  DEVICE, this shard's slice, as for hqmq_encode (not read by pass 6).
+ *   workspace_dev          DEVICE, 256-byte aligned, >= hqmq_sizes(params).workspace_bytes; holds the
+ *                          select's state between the calls, so nothing else may use it meanwhile.
+ * hqmq_shard_median_region: HOST function; byte offset inside the workspace and number of uint32
+ * counters of the histogram that pass 0..5 leaves behind. */
+int32_t hqmq_shard_median_pass(const hqmq_params *params, uint64_t total_chunks_per_head, int32_t pass,
+                               const void *x_dev, void *workspace_dev, uint64_t workspace_bytes, void *stream);
+int32_t hqmq_shard_median_region(const hqmq_params *params, int32_t pass, uint64_t *offset_bytes,
+                                 uint64_t *n_counters);
+
 /* Encode n_tensors tensors of ONE shape (the same params: e.g. the K and V of every layer of the
  * current batch, Alg. 1 applied per (layer, role)) with as few launches as possible: up to 32
  * tensors share each kernel launch, which removes the launch gaps and small-kernel tails of the

@@ -27,6 +27,8 @@ from .binding import (  # noqa: F401
     hqmq_encode_given_thresholds,
     hqmq_encode_timed,
     hqmq_last_hip_error,
+    hqmq_shard_median_pass,
+    hqmq_shard_median_region,
     hqmq_sizes,
     hqmq_thresholds,
     library_path,

@@ -81,6 +81,12 @@ def _load():
                                                            C.c_uint64, C.c_void_p]
         lib.hqmq_thresholds.restype = C.c_int32
         lib.hqmq_thresholds.argtypes = [C.POINTER(HqmqParams), C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
+        lib.hqmq_shard_median_pass.restype = C.c_int32
+        lib.hqmq_shard_median_pass.argtypes = [C.POINTER(HqmqParams), C.c_uint64, C.c_int32, C.c_void_p, C.c_void_p,
+                                               C.c_uint64, C.c_void_p]
+        lib.hqmq_shard_median_region.restype = C.c_int32
+        lib.hqmq_shard_median_region.argtypes = [C.POINTER(HqmqParams), C.c_int32, C.POINTER(C.c_uint64),
+                                                 C.POINTER(C.c_uint64)]
         lib.hqmq_encode_batch.restype = C.c_int32
         lib.hqmq_encode_batch.argtypes = [C.POINTER(HqmqParams), C.c_int32, C.POINTER(C.c_void_p),
                                           C.POINTER(C.c_void_p), C.POINTER(_Encoded), C.POINTER(C.c_uint64),
@@ -247,6 +253,23 @@ def hqmq_thresholds(params: HqmqParams, workspace: torch.Tensor, slice_index: in
                                  _stream_ptr(stream))
     _check(rc, "hqmq_thresholds")
     return out
+
+
+def hqmq_shard_median_pass(params: HqmqParams, total_chunks_per_head: int, pass_index: int, x: torch.Tensor,
+                           workspace: torch.Tensor, stream=None) -> None:
+    """One pass (0..5 counting, 6 finish) of the sequence-sharded median on this shard's slice x."""
+    rc = _load().hqmq_shard_median_pass(C.byref(params), int(total_chunks_per_head), int(pass_index), x.data_ptr(),
+                                        workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                        _stream_ptr(stream))
+    _check(rc, "hqmq_shard_median_pass")
+
+
+def hqmq_shard_median_region(params: HqmqParams, pass_index: int, workspace: torch.Tensor) -> torch.Tensor:
+    """The histogram pass 0..5 left in the workspace, as an int32 view of it: what the shards sum."""
+    off, n = C.c_uint64(), C.c_uint64()
+    _check(_load().hqmq_shard_median_region(C.byref(params), int(pass_index), C.byref(off), C.byref(n)),
+           "hqmq_shard_median_region")
+    return workspace.view(torch.uint8)[off.value: off.value + 4 * n.value].view(torch.int32)
 
 
 class EncodeBatch:

@@ -352,6 +352,51 @@ extern "C" int32_t hqmq_thresholds(const hqmq_params *params, const void *worksp
     return HQMQ_OK;
 }
 
+extern "C" int32_t hqmq_shard_median_region(const hqmq_params *params, int32_t pass, uint64_t *offset_bytes,
+                                            uint64_t *n_counters)
+{
+    int32_t rc = check_params(params);
+    if (rc != HQMQ_OK)
+        return rc;
+    if (pass < 0 || pass > 5 || !offset_bytes || !n_counters)
+        return HQMQ_ERR_INVALID_ARG;
+    const WorkspaceLayout l = workspace_layout(make_geometry(params));
+    *offset_bytes = pass == 0 ? l.hist0 : l.hist1;
+    *n_counters = (uint64_t)params->H * (pass == 0 ? kBins0 : kBins1);
+    return HQMQ_OK;
+}
+
+extern "C" int32_t hqmq_shard_median_pass(const hqmq_params *params, uint64_t total_chunks_per_head, int32_t pass,
+                                          const void *x_dev, void *workspace_dev, uint64_t workspace_bytes,
+                                          void *stream)
+{
+    int32_t rc = check_params(params);
+    if (rc != HQMQ_OK)
+        return rc;
+    if (pass < 0 || pass > 6 || !x_dev || !workspace_dev || misaligned(x_dev, 16) || misaligned(workspace_dev, 256))
+        return HQMQ_ERR_INVALID_ARG;
+    if (params->flags & HQMQ_FLAG_NO_OUTLIERS)
+        return HQMQ_ERR_INVALID_ARG;
+    const Geometry g = make_geometry(params);
+    const uint64_t own = (uint64_t)g.B * g.T * g.n_c;
+    if (total_chunks_per_head < own)
+        return HQMQ_ERR_INVALID_ARG;
+    if (total_chunks_per_head >= (1ull << 32))
+        return HQMQ_ERR_UNSUPPORTED;  // 32-bit ranks and counters
+    const WorkspaceLayout l = workspace_layout(g);
+    if (workspace_bytes < l.total)
+        return HQMQ_ERR_BUFFER_TOO_SMALL;
+    EncodeBatch batch;
+    std::memset(&batch, 0, sizeof(batch));
+    batch.t[0].x = static_cast<const _Float16 *>(x_dev);
+    batch.t[0].ws = static_cast<char *>(workspace_dev);
+    hipError_t err = launch_shard_median_pass(g, workspace_offsets(l), batch, pass, total_chunks_per_head, params->C,
+                                              static_cast<hipStream_t>(stream));
+    if (err != hipSuccess)
+        return hip_failed(err);
+    return HQMQ_OK;
+}
+
 extern "C" int32_t hqmq_encode_batch(const hqmq_params *params, int32_t n_tensors, const void *const *x_dev,
                                      const float *const *sec_dev, const hqmq_encoded *enc,
                                      const uint64_t *outlier_capacity, void *workspace_dev,

@@ -227,6 +227,8 @@ __device__ __forceinline__ unsigned long long key_of(double r2)
 // Launchers implemented in the kernel translation units (host side).
 hipError_t launch_select_median(const Geometry &g, const WorkspaceOffsets &wo, const EncodeBatch &batch, int n_tensors,
                                 float C, bool skip_select, hipStream_t stream);
+hipError_t launch_shard_median_pass(const Geometry &g, const WorkspaceOffsets &wo, const EncodeBatch &batch, int pass,
+                                    unsigned long long total_per_head, float C, hipStream_t stream);
 hipError_t launch_search(const Geometry &g, const WorkspaceOffsets &wo, const EncodeBatch &batch, int n_tensors,
                          hipStream_t stream);
 hipError_t launch_outlier_list(const Geometry &g, const WorkspaceOffsets &wo, const EncodeBatch &batch, int n_tensors,

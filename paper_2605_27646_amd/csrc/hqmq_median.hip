@@ -359,6 +359,110 @@ __global__ __launch_bounds__(kThreads) void k_gather(Geometry g, WorkspaceOffset
 }
 
 // ---------------------------------------------------------------------------------------
+// The median of a head whose token axis is split over several shards (a context-parallel cache: every
+// shard holds a slice of T; paper Sec. 3 takes the median per (layer, head, role) over the whole
+// batch).  Plain most-significant-digit radix select with histograms only, so that the one thing the
+// shards have to exchange is a histogram: pass 0 counts bits 62..50 of every key, passes 1..5 the
+// next 10 bits of the keys under the prefix fixed so far; the caller sums the pass's histogram over
+// the shards before the next call, and every shard then takes the same decisions.
+//   k_shard_pick   one workgroup per head: (pass > 0) locates the wanted rank in the summed histogram
+//                  of the previous pass and extends the prefix; clears the histogram of this pass;
+//                  (finish) writes the threshold fl(fl(C C) median)
+//   k_shard_hist   sweep of this shard's rows, as k_select_sweep
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ int shard_digit_bits(int pass) { return pass == 0 ? kBits0 : kBits1; }
+__device__ __forceinline__ int shard_digit_shift(int pass) { return pass == 0 ? kShift0 : kShift1 - 10 * (pass - 1); }
+
+// pass: the pass about to run (0..5), or 6 = finish.
+__global__ __launch_bounds__(kSelectThreads) void k_shard_pick(Geometry g, WorkspaceOffsets wo, EncodeBatch batch,
+                                                               int pass, unsigned long long total_per_head, float C)
+{
+    const EncodeTensor &tn = batch.t[blockIdx.z];
+    const Workspace ws = carve_workspace(tn.ws, wo);
+    __shared__ uint32_t scratch[kSelectThreads + 2];
+    const int h = blockIdx.x;
+    unsigned long long prefix = 0;
+    uint32_t rank = (uint32_t)((total_per_head - 1) / 2);
+    if (pass > 0) {
+        prefix = ws.state[h].prefix;
+        rank = ws.state[h].rank;
+        uint32_t bin, before;
+        if (pass == 1)
+            pick_bin<kBins0, kSelectThreads>(ws.hist0 + (size_t)h * kBins0, rank, scratch, bin, before);
+        else
+            pick_bin<kBins1, kSelectThreads>(ws.hist1 + (size_t)h * kBins1, rank, scratch, bin, before);
+        prefix = (prefix << shard_digit_bits(pass - 1)) | bin;
+        rank -= before;
+    }
+    if (pass < 6) {
+        uint32_t *hist = pass == 0 ? ws.hist0 + (size_t)h * kBins0 : ws.hist1 + (size_t)h * kBins1;
+        const int bins = pass == 0 ? kBins0 : kBins1;
+        for (int i = threadIdx.x; i < bins; i += kSelectThreads)
+            hist[i] = 0;  // after pick_bin's barriers: every thread has read the previous counts
+    }
+    if (threadIdx.x == 0) {
+        ws.state[h].prefix = prefix;
+        ws.state[h].rank = rank;
+        if (pass == 6) {
+            const double c = (double)C;
+            const double c2 = c * c;
+            ws.thr[h] = c2 * __longlong_as_double((long long)prefix);  // all 63 bits fixed: the median itself
+        }
+    }
+}
+
+template <bool kFull>
+__global__ __launch_bounds__(kSelectThreads) void k_shard_hist(Geometry g, WorkspaceOffsets wo, EncodeBatch batch, int pass)
+{
+    const EncodeTensor &tn = batch.t[blockIdx.z];
+    const Workspace ws = carve_workspace(tn.ws, wo);
+    const _Float16 *__restrict__ x = tn.x;
+    __shared__ uint32_t lh[kBins0];
+    const int seg = blockIdx.y, b = seg / g.H, h = seg % g.H;
+    const int bins = pass == 0 ? kBins0 : kBins1;
+    const int shift = shard_digit_shift(pass), nbits = shard_digit_bits(pass);
+    const unsigned long long prefix = ws.state[h].prefix;  // pass 0: zero, and every key matches
+    for (int i = threadIdx.x; i < bins; i += kSelectThreads)
+        lh[i] = 0;
+    __syncthreads();
+    const int c = threadIdx.x & 31, sub = threadIdx.x >> 5;
+    const int t0 = blockIdx.x * kSelectRows;
+    const int t1 = min(g.T, t0 + kSelectRows);
+    const _Float16 *base = x + (int64_t)b * g.sb + (int64_t)h * g.sh;
+    if (kFull || c < g.n_c) {
+        for (int t = t0 + sub; t < t1; t += kSelectThreads / 32) {
+            const unsigned long long key =
+                key_of(chunk_norm2(load_row_chunk<kFull>(base + (int64_t)t * g.st, c, g))) & kKeyMask;
+            // (key >> 63) == 0 == prefix in pass 0; a shift by shift + nbits <= 63 is always defined
+            if ((key >> (shift + nbits)) == prefix)
+                atomicAdd(&lh[(uint32_t)(key >> shift) & (uint32_t)(bins - 1)], 1u);
+        }
+    }
+    __syncthreads();
+    uint32_t *gh = pass == 0 ? ws.hist0 + (size_t)h * kBins0 : ws.hist1 + (size_t)h * kBins1;
+    for (int i = threadIdx.x; i < bins; i += kSelectThreads) {
+        const uint32_t n = lh[i];
+        if (n)
+            atomicAdd(&gh[i], n);
+    }
+}
+
+hipError_t launch_shard_median_pass(const Geometry &g, const WorkspaceOffsets &wo, const EncodeBatch &batch, int pass,
+                                    unsigned long long total_per_head, float C, hipStream_t stream)
+{
+    hipLaunchKernelGGL(k_shard_pick, dim3(g.H, 1, 1), dim3(kSelectThreads), 0, stream, g, wo, batch, pass,
+                       total_per_head, C);
+    if (pass < 6) {
+        dim3 grid((g.T + kSelectRows - 1) / kSelectRows, g.B * g.H, 1);
+        if (g.D == 4 * kChunksPerRow)
+            hipLaunchKernelGGL(k_shard_hist<true>, grid, dim3(kSelectThreads), 0, stream, g, wo, batch, pass);
+        else
+            hipLaunchKernelGGL(k_shard_hist<false>, grid, dim3(kSelectThreads), 0, stream, g, wo, batch, pass);
+    }
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
 // host-side launch sequences
 // ---------------------------------------------------------------------------------------
 hipError_t launch_select_median(const Geometry &g, const WorkspaceOffsets &wo, const EncodeBatch &batch, int n_tensors,

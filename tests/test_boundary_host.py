@@ -27,7 +27,7 @@ def lib():
 def test_library_exports_every_declared_symbol(lib):
     header = open(os.path.join(ROOT, "include", "hqmq.h")).read()
     declared = set(re.findall(r"^(?:int32_t|void|uint64_t)\s+(hqmq_\w+)\s*\(", header, re.M))
-    assert declared == {"hqmq_build_codebooks", "hqmq_sizes", "hqmq_encode", "hqmq_encode_timed", "hqmq_encode_batch", "hqmq_encode_given_thresholds", "hqmq_encode_batch_given_thresholds", "hqmq_thresholds", "hqmq_decode", "hqmq_decode_batch", "hqmq_attend", "hqmq_attend_workspace_bytes", "hqmq_last_hip_error"}
+    assert declared == {"hqmq_build_codebooks", "hqmq_sizes", "hqmq_encode", "hqmq_encode_timed", "hqmq_encode_batch", "hqmq_encode_given_thresholds", "hqmq_encode_batch_given_thresholds", "hqmq_thresholds", "hqmq_shard_median_pass", "hqmq_shard_median_region", "hqmq_decode", "hqmq_decode_batch", "hqmq_attend", "hqmq_attend_workspace_bytes", "hqmq_last_hip_error"}
     for name in declared:
         assert hasattr(lib, name), name
 
@@ -153,6 +153,21 @@ def test_encode_decode_reject_bad_arguments_without_touching_the_gpu(lib):
     assert th(C.byref(p), None, 0, 0x1000, None) == -1 and th(C.byref(p), 0x1000, 0, None, None) == -1
     assert th(C.byref(p), 0x1000, 32, 0x1000, None) == -1 and th(C.byref(p), 0x1000, -1, 0x1000, None) == -1
     assert th(C.byref(_params(D=132, stride_t=136)), 0x1000, 0, 0x1000, None) == -2
+    sm = lib.hqmq_shard_median_pass
+    own = 1024 * 32
+    assert sm(C.byref(p), own, 0, None, 0x1000, ws, None) == -1 and sm(C.byref(p), own, 0, 0x1000, None, ws, None) == -1
+    assert sm(C.byref(p), own, 7, 0x1000, 0x1000, ws, None) == -1 and sm(C.byref(p), own, -1, 0x1000, 0x1000, ws, None) == -1
+    assert sm(C.byref(p), own - 1, 0, 0x1000, 0x1000, ws, None) == -1       # fewer chunks in total than this shard holds
+    assert sm(C.byref(p), 1 << 32, 0, 0x1000, 0x1000, ws, None) == -2       # ranks are 32-bit
+    assert sm(C.byref(p), own, 0, 0x1000, 0x1000, ws - 1, None) == -3
+    assert sm(C.byref(_params(flags=hq.HQMQ_FLAG_NO_OUTLIERS)), own, 0, 0x1000, 0x1000, ws, None) == -1
+    off, cnt = C.c_uint64(), C.c_uint64()
+    reg = lib.hqmq_shard_median_region
+    assert reg(C.byref(p), 0, C.byref(off), C.byref(cnt)) == 0 and cnt.value == 8 * 8192 and off.value % 256 == 0
+    first = off.value
+    assert reg(C.byref(p), 3, C.byref(off), C.byref(cnt)) == 0 and cnt.value == 8 * 1024 and off.value != first
+    assert off.value + 4 * cnt.value <= ws
+    assert reg(C.byref(p), 6, C.byref(off), C.byref(cnt)) == -1 and reg(C.byref(p), 0, None, C.byref(cnt)) == -1
     att = lib.hqmq_attend
     wsb = lib.hqmq_attend_workspace_bytes
     need = wsb(C.byref(p), 4 * p.H)

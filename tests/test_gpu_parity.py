@@ -310,6 +310,89 @@ def test_other_head_dimensions_batched_and_incremental():
 
 
 # ---------------------------------------------------------------------------------------
+# a cache whose token axis is split over shards: the median is found by exchanging histograms
+# ---------------------------------------------------------------------------------------
+
+def _sharded_thresholds(shards_dev, S, b_r, Cmul):
+    """Run the 6 counting passes and the finish on every shard; between passes sum the pass's histogram
+    over the shards and write it back to each (what an all-reduce would do).  Returns thresholds per shard."""
+    ps = [hq.params_for(x, S, b_r, Cmul) for x in shards_dev]
+    wss = [hq.alloc_workspace(p, DEV) for p in ps]
+    for ws in wss:
+        ws.fill_(0xCD)
+    total = sum(p.B * p.T * (-(-p.D // 4)) for p in ps)
+    for pas in range(6):
+        for p, x, ws in zip(ps, shards_dev, wss):
+            hq.hqmq_shard_median_pass(p, total, pas, x, ws)
+        regions = [hq.hqmq_shard_median_region(p, pas, ws) for p, ws in zip(ps, wss)]
+        summed = torch.stack(regions).sum(0, dtype=torch.int32)
+        assert int(summed.sum()) <= total * ps[0].H
+        for r in regions:
+            r.copy_(summed)
+    out = []
+    for p, x, ws in zip(ps, shards_dev, wss):
+        hq.hqmq_shard_median_pass(p, total, 6, x, ws)
+        out.append(hq.hqmq_thresholds(p, ws))
+    torch.cuda.synchronize()
+    return ps, out
+
+
+@pytest.mark.parametrize("D,splits,kind", [
+    (128, (700, 1, 323), "lognormal"),      # ragged shards, one of a single token
+    (96, (256, 300), "lognormal"),
+    (128, (128, 128, 128, 128), "equal"),   # every norm equal: all keys fall into one bin in every pass
+    (64, (50, 77), "few_values"),           # coarsely quantised data: heavy ties around the median
+])
+def test_sequence_sharded_median_and_encode(D, splits, kind):
+    B, H, S, b_r, Cmul = 2, 3, 24, 4, 3.0
+    T = sum(splits)
+    x = _lognormal_tensor(B, H, T, seed=77 + D, sigma_g=0.9, D=D)
+    if kind == "equal":
+        x = torch.full_like(x, 0.5)
+    elif kind == "few_values":
+        x = (x * 2).round().clamp(-3, 3).to(torch.float16) / 2
+    sec_t, sec = _sec(4, H, S)
+    whole = oracle.encode(_bits(x), sec, b_r=b_r, Cmul=Cmul, rows=np.zeros(B * H * T, bool))
+    want_thr = np.float64(np.float32(Cmul)) ** 2 * whole.m2
+    bounds = np.cumsum((0,) + splits)
+    shards = [x[:, :, a:b].contiguous() for a, b in zip(bounds[:-1], bounds[1:])]
+    shards_dev = [s.to(DEV) for s in shards]
+    ps, thrs = _sharded_thresholds(shards_dev, S, b_r, Cmul)
+    for t in thrs:
+        assert np.array_equal(t.cpu().numpy(), want_thr)       # bit-exact, and the same on every shard
+    # every shard encodes its slice against the common thresholds: equal to the oracle on that slice,
+    # and the flags are those of the unsharded tensor
+    fl_whole = whole.flag.reshape(B, H, T, -1)
+    sec_dev = sec_t.to(DEV)
+    from gpu_util import GpuEncoded
+    for (a, b), sh, shd, p in zip(zip(bounds[:-1], bounds[1:]), shards, shards_dev, ps):
+        e = oracle.encode(_bits(sh), sec, b_r=b_r, thresholds=want_thr)
+        assert np.array_equal(e.flag.reshape(B, H, b - a, -1), fl_whole[:, :, a:b])
+        nc = e.r2.shape[1]
+        bufs = hq.alloc_encoded(p, DEV, outlier_capacity=B * H * (b - a) * nc)
+        hq.hqmq_encode_given_thresholds(p, shd, sec_dev, thrs[0], bufs, hq.alloc_workspace(p, DEV))
+        torch.cuda.synchronize()
+        n_out = bufs.n_outliers.cpu().numpy().view(np.uint32)
+        total = int(n_out[-1])
+        g = GpuEncoded(p, bufs, bufs.codes.cpu().numpy().view(np.uint32), bufs.sigma.cpu().numpy().view(np.uint16),
+                       bufs.flags.cpu().numpy().view(np.uint32), bufs.row_off.cpu().numpy().view(np.uint32), n_out,
+                       bufs.outliers[:total].cpu().numpy().view(np.uint16).reshape(total, 4),
+                       int(bufs.status.cpu().numpy().view(np.uint32)[0]))
+        compare_encode(g, e, _bits(sh), sec)
+
+
+def test_sequence_sharded_median_equals_the_single_call_select():
+    """One shard holding everything: the histogram-only select and the encode's own select agree."""
+    x = _lognormal_tensor(1, 4, 3000, seed=91, sigma_g=0.7)
+    sec_t, _ = _sec(0, 4, 16)
+    xd = x.to(DEV)
+    ps, thrs = _sharded_thresholds([xd], 16, 6, 3.0)
+    ws = hq.alloc_workspace(ps[0], DEV)
+    hq.hqmq_encode(ps[0], xd, sec_t.to(DEV), hq.alloc_encoded(ps[0], DEV), ws)
+    assert torch.equal(hq.hqmq_thresholds(ps[0], ws), thrs[0])
+
+
+# ---------------------------------------------------------------------------------------
 # degenerate inputs and the boundary's data-dependent behaviour
 # ---------------------------------------------------------------------------------------
 
