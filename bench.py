@@ -29,7 +29,9 @@ PEAK_HBM_GBS = 8000.0        # MI355X HBM3E peak
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs, each scaled
 # by a plain copy of known size in the same run); figures and commands in profiles/hbm_traffic_*.txt
-MEASURED_TRAFFIC_BYTES = {"llama3_8b_32k": {"k_search": 90.1e6, "k_decode": 91.4e6}}
+MEASURED_TRAFFIC_BYTES = {"llama3_8b_32k": {"k_search": 94.2e6, "k_decode": 91.4e6},
+                          "mha32_d96_8k": {"k_search": 101.1e6, "k_decode": 68.5e6},
+                          "gqa8_d64_32k": {"k_search": 50.7e6, "k_decode": 47.7e6}}
 
 
 def search_flops_per_chunk(S: int) -> float:
@@ -201,7 +203,7 @@ def main() -> int:
         # metric names.  The 32 S of them that form the K = 4 contraction execute on the fp16 matrix path as
         # a 3-part split of every fp32 factor (8 exact fp16 products per fp32 product, fp32 accumulation);
         # "executed" prices those instructions against their own peak.
-        "roofline": {"kernel": "k_search", "bound": "mfma", "achieved": search_tflops, "peak": PEAK_FP32_TFLOPS,
+        "roofline": {"kernel": "k_search" if wl.D == 128 else "k_search_flat", "bound": "mfma", "achieved": search_tflops, "peak": PEAK_FP32_TFLOPS,
                      "unit": "TFLOP/s", "frac": search_tflops / PEAK_FP32_TFLOPS,
                      "traffic": (MEASURED_TRAFFIC_BYTES[wl.name]["k_search"] * tensors_per_enc_launch
                                  if wl.name in MEASURED_TRAFFIC_BYTES else None),
