@@ -294,6 +294,18 @@ int32_t hqmq_attend(const hqmq_params *params, int32_t n_q_heads, const void *q_
                     const hqmq_encoded *enc_v, uint64_t cap_v, const float *sec_v_dev, void *out_dev,
                     void *workspace_dev, uint64_t workspace_bytes, void *stream);
 
+/* hqmq_attend that also returns, per query head, the natural logarithm of the softmax denominator,
+ * lse = ln(sum_t exp(scale * <q, K_hat_t>)): what is needed to combine attention results over
+ * several token ranges exactly (a cache kept as a prefill tensor plus tensors of appended tokens, or
+ * a recent-token tail the caller holds in fp16): with parts (o_i, lse_i) the whole is
+ * o = sum_i exp(lse_i - L) o_i, L = ln(sum_i exp(lse_i)).
+ *   lse_dev    DEVICE, out, fp32 [B][n_q_heads], 4-byte aligned.
+ * Everything else, and the errors, as hqmq_attend (INVALID_ARG also for a null or misaligned lse_dev). */
+int32_t hqmq_attend_lse(const hqmq_params *params, int32_t n_q_heads, const void *q_dev, float scale,
+                        const hqmq_encoded *enc_k, uint64_t cap_k, const float *sec_k_dev,
+                        const hqmq_encoded *enc_v, uint64_t cap_v, const float *sec_v_dev, void *out_dev,
+                        float *lse_dev, void *workspace_dev, uint64_t workspace_bytes, void *stream);
+
 /* Workspace hqmq_attend needs for these params and n_q_heads, in bytes (0 if they are invalid). */
 uint64_t hqmq_attend_workspace_bytes(const hqmq_params *params, int32_t n_q_heads);
 

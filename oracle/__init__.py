@@ -117,6 +117,9 @@ def _declare(L):
     L.hqo_attend.restype = None
     L.hqo_attend.argtypes = [_u16p, _f64p, _f64p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                              C.c_double, _u16p, _f64p]
+    L.hqo_attend_lse.restype = None
+    L.hqo_attend_lse.argtypes = [_u16p, _f64p, _f64p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                 C.c_double, _u16p, _f64p, _f64p]
     L.hqo_decode.restype = None
     L.hqo_decode.argtypes = [_u32p, _u16p, _u32p, _u32p, _u16p, _f32p, C.c_int, C.c_int,
                              C.c_int, C.c_int, C.c_int, C.c_int, _u16p, C.c_void_p]
@@ -393,9 +396,10 @@ def decode64(codes, sigma, flags, row_off, outliers, sec, B, H, T, b_r, D=4 * NC
     return np.ascontiguousarray(out64.reshape(B, H, T, nc * 4)[..., :D])
 
 
-def attend(q_bits: np.ndarray, K64: np.ndarray, V64: np.ndarray, scale: float):
+def attend(q_bits: np.ndarray, K64: np.ndarray, V64: np.ndarray, scale: float, want_lse: bool = False):
     """Single-query attention (one token per sequence) over a reconstructed cache.
-    q_bits: fp16 bit patterns [B, Hq, D]; K64, V64: fp64 [B, H, T, D]; returns (fp16 bits, fp64)."""
+    q_bits: fp16 bit patterns [B, Hq, D]; K64, V64: fp64 [B, H, T, D]; returns (fp16 bits, fp64) and,
+    with want_lse, the natural log of the softmax denominator, fp64 [B, Hq]."""
     q_bits = np.ascontiguousarray(q_bits, np.uint16)
     K64 = np.ascontiguousarray(K64, np.float64)
     V64 = np.ascontiguousarray(V64, np.float64)
@@ -404,8 +408,11 @@ def attend(q_bits: np.ndarray, K64: np.ndarray, V64: np.ndarray, scale: float):
     assert Hq % H == 0 and K64.shape == V64.shape and K64.shape[0] == B and K64.shape[3] == D
     out16 = np.zeros((B, Hq, D), np.uint16)
     out64 = np.zeros((B, Hq, D))
-    lib().hqo_attend(q_bits.reshape(-1), K64.reshape(-1), V64.reshape(-1), B, Hq, H, T, D, float(scale),
-                     out16.reshape(-1), out64.reshape(-1))
+    lse = np.zeros((B, Hq))
+    lib().hqo_attend_lse(q_bits.reshape(-1), K64.reshape(-1), V64.reshape(-1), B, Hq, H, T, D, float(scale),
+                         out16.reshape(-1), out64.reshape(-1), lse.reshape(-1))
+    if want_lse:
+        return out16, out64, lse
     return out16, out64
 
 

@@ -557,10 +557,21 @@ void hqo_decode64(const uint32_t *codes, const uint16_t *sigma16, const uint32_t
  * query token per sequence, the decode step of generation).  q: fp16 [B][Hq][D]; K, V: fp64
  * [B][H][T][D] as returned by hqo_decode64 (reconstruction before fp16 rounding, outliers as
  * stored); query head hq reads kv head hq / (Hq / H) (grouped-query attention).  Plain softmax
- * with the row maximum subtracted, everything in fp64; out16 = result rounded to fp16.
+ * with the row maximum subtracted, everything in fp64; out16 = result rounded to fp16.  lse64
+ * (optional): the natural logarithm of the softmax denominator sum_t exp(scale * <q, K_t>), as
+ * maximum + log of the shifted sum.
  * ---------------------------------------------------------------------------------- */
+void hqo_attend_lse(const uint16_t *q, const double *K, const double *V, int B, int Hq, int H, int T,
+                    int D, double scale, uint16_t *out16, double *out64, double *lse64);
+
 void hqo_attend(const uint16_t *q, const double *K, const double *V, int B, int Hq, int H, int T,
                 int D, double scale, uint16_t *out16, double *out64)
+{
+    hqo_attend_lse(q, K, V, B, Hq, H, T, D, scale, out16, out64, 0);
+}
+
+void hqo_attend_lse(const uint16_t *q, const double *K, const double *V, int B, int Hq, int H, int T,
+                    int D, double scale, uint16_t *out16, double *out64, double *lse64)
 {
     int G = Hq / H;
     double *p = (double *)malloc((size_t)T * sizeof(double));
@@ -584,6 +595,8 @@ void hqo_attend(const uint16_t *q, const double *K, const double *V, int B, int 
                 p[t] = exp(p[t] - m);
                 l += p[t];
             }
+            if (lse64)
+                lse64[(int64_t)b * Hq + hq] = m + log(l);
             for (int d = 0; d < D; ++d) {
                 double o = 0.0;
                 for (int t = 0; t < T; ++t)

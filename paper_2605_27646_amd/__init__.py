@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     alloc_encoded,
     alloc_workspace,
     hqmq_attend,
+    hqmq_attend_lse,
     hqmq_attend_workspace_bytes,
     hqmq_build_codebooks,
     hqmq_decode,

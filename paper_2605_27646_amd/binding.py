@@ -103,6 +103,10 @@ def _load():
                                     C.POINTER(_Encoded), C.c_uint64, C.c_void_p,
                                     C.POINTER(_Encoded), C.c_uint64, C.c_void_p,
                                     C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]
+        lib.hqmq_attend_lse.restype = C.c_int32
+        lib.hqmq_attend_lse.argtypes = [C.POINTER(HqmqParams), C.c_int32, C.c_void_p, C.c_float, C.POINTER(_Encoded),
+                                        C.c_uint64, C.c_void_p, C.POINTER(_Encoded), C.c_uint64, C.c_void_p,
+                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]
         lib.hqmq_attend_workspace_bytes.restype = C.c_uint64
         lib.hqmq_attend_workspace_bytes.argtypes = [C.POINTER(HqmqParams), C.c_int32]
         lib.hqmq_last_hip_error.restype = C.c_int32
@@ -368,11 +372,7 @@ def hqmq_attend_workspace_bytes(params: HqmqParams, n_q_heads: int) -> int:
     return int(_load().hqmq_attend_workspace_bytes(C.byref(params), int(n_q_heads)))
 
 
-def hqmq_attend(params: HqmqParams, q: torch.Tensor, scale: float, enc_k: EncodedBuffers,
-                sec_k: torch.Tensor, enc_v: EncodedBuffers, sec_v: torch.Tensor, out: torch.Tensor,
-                workspace: torch.Tensor, stream=None) -> None:
-    """Enqueue single-query attention over the packed K and V caches: q and out are contiguous
-    device fp16 [B, n_q_heads, 128]."""
+def _check_attend_args(params, q, out, sec_k, sec_v, workspace):
     for t in (q, out):
         if t.dtype != torch.float16 or not t.is_cuda or not t.is_contiguous() or t.dim() != 3:
             raise ValueError("q and out must be contiguous device fp16 [B, n_q_heads, 128]")
@@ -384,9 +384,33 @@ def hqmq_attend(params: HqmqParams, q: torch.Tensor, scale: float, enc_k: Encode
             raise ValueError("sec must be contiguous device fp32 [H, S, 4]")
     if not workspace.is_cuda or not workspace.is_contiguous():
         raise ValueError("workspace must be a contiguous device tensor")
+
+
+def hqmq_attend(params: HqmqParams, q: torch.Tensor, scale: float, enc_k: EncodedBuffers,
+                sec_k: torch.Tensor, enc_v: EncodedBuffers, sec_v: torch.Tensor, out: torch.Tensor,
+                workspace: torch.Tensor, stream=None) -> None:
+    """Enqueue single-query attention over the packed K and V caches: q and out are contiguous
+    device fp16 [B, n_q_heads, 128]."""
+    _check_attend_args(params, q, out, sec_k, sec_v, workspace)
     rc = _load().hqmq_attend(C.byref(params), int(q.shape[1]), q.data_ptr(), float(scale),
                              C.byref(enc_k.as_struct()), enc_k.outlier_capacity, sec_k.data_ptr(),
                              C.byref(enc_v.as_struct()), enc_v.outlier_capacity, sec_v.data_ptr(),
                              out.data_ptr(), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                              _stream_ptr(stream))
     _check(rc, "hqmq_attend")
+
+
+def hqmq_attend_lse(params: HqmqParams, q: torch.Tensor, scale: float, enc_k: EncodedBuffers,
+                    sec_k: torch.Tensor, enc_v: EncodedBuffers, sec_v: torch.Tensor, out: torch.Tensor,
+                    lse: torch.Tensor, workspace: torch.Tensor, stream=None) -> None:
+    """hqmq_attend that also writes lse (contiguous device fp32 [B, n_q_heads]): the natural log of each
+    query head's softmax denominator, for combining results over several token ranges."""
+    _check_attend_args(params, q, out, sec_k, sec_v, workspace)
+    if lse.dtype != torch.float32 or not lse.is_cuda or not lse.is_contiguous() or tuple(lse.shape) != tuple(q.shape[:2]):
+        raise ValueError("lse must be contiguous device fp32 [B, n_q_heads]")
+    rc = _load().hqmq_attend_lse(C.byref(params), int(q.shape[1]), q.data_ptr(), float(scale),
+                                 C.byref(enc_k.as_struct()), enc_k.outlier_capacity, sec_k.data_ptr(),
+                                 C.byref(enc_v.as_struct()), enc_v.outlier_capacity, sec_v.data_ptr(),
+                                 out.data_ptr(), lse.data_ptr(), workspace.data_ptr(),
+                                 workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    _check(rc, "hqmq_attend_lse")

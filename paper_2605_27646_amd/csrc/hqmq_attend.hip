@@ -600,6 +600,9 @@ __global__ __launch_bounds__(kAttThreads) void k_attend_merge(AttendArgs a)
             tot += sums[jj * (kMergeDims + 1) + tid];
         a.out[head * 128 + d0 + tid] = (_Float16)(tot / lsum);
     }
+    // log-sum-exp of the head's scores (the running maximum is kept in the log2 domain)
+    if (a.lse && blockIdx.y == 0 && tid == 0)
+        a.lse[head] = (mx + __builtin_amdgcn_logf(lsum)) * 0.693147180559945309417f;
 }
 
 AttendPlan plan_attend(const Geometry &g, int G)

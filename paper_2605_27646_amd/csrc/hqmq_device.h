@@ -162,6 +162,7 @@ struct AttendArgs {
     AttendSide k, v;
     const _Float16 *q;     // [B][H * G][128]
     _Float16 *out;         // [B][H * G][128]
+    float *lse;            // [B][H * G] natural-log sum of exp(score) over the cached tokens, or null
     float *part_ml;        // [B * H * G][n_splits][2]: running maximum (log2 domain) and weight sum
     float *part_acc;       // [B * H * G][n_splits][128]: weighted value sum
     float qscale;          // softmax scale * log2(e), folded into the query

@@ -286,3 +286,72 @@ def test_attend_is_deterministic():
     a = _gpu_attend(gk.params, q, 0.09, gk.bufs, sec_k.to(DEV), gv.bufs, sec_v.to(DEV))
     b = _gpu_attend(gk.params, q, 0.09, gk.bufs, sec_k.to(DEV), gv.bufs, sec_v.to(DEV))
     assert np.array_equal(a, b)
+
+
+def test_attend_lse_combines_a_prefill_tensor_and_appended_tokens():
+    """The generation setting end to end: a prefill tensor encoded with its own medians, then two batches
+    of appended tokens encoded against the prefill's thresholds as tensors of their own.  One attention
+    call per tensor with its log-sum-exp; the lse-weighted combination must equal the oracle's attention
+    over the concatenation of the three decoded ranges, and each lse the oracle's."""
+    B, H, Hq, S, b_r = 2, 2, 8, 16, 6
+    T_parts = (700, 5, 64)
+    k_all, v_all = _tensors(B, H, sum(T_parts), seed=77)
+    sec_k, sec_v = _secs(8, H, S)
+    sec_np = (sec_k.numpy(), sec_v.numpy())
+    sec_dev = (sec_k.to(DEV), sec_v.to(DEV))
+    q = _query(B, Hq, seed=78, gain=1.5)
+    scale = 1 / math.sqrt(128)
+    bounds = np.cumsum((0,) + T_parts)
+    outs, lses, K64s, V64s = [], [], [], []
+    thr = [None, None]
+    for i, (a, b) in enumerate(zip(bounds[:-1], bounds[1:])):
+        encs = []
+        for role, x_all in enumerate((k_all, v_all)):
+            x = x_all[:, :, a:b].contiguous().to(DEV)
+            p = hq.params_for(x, S, b_r)
+            ws = hq.alloc_workspace(p, DEV)
+            if i == 0:
+                bufs = hq.alloc_encoded(p, DEV)
+                hq.hqmq_encode(p, x, sec_dev[role], bufs, ws)
+                thr[role] = hq.hqmq_thresholds(p, ws)
+            else:
+                bufs = hq.alloc_encoded(p, DEV, outlier_capacity=B * H * (b - a) * 32)
+                hq.hqmq_encode_given_thresholds(p, x, sec_dev[role], thr[role], bufs, ws)
+            torch.cuda.synchronize()
+            assert int(bufs.status.item()) == 0
+            encs.append((p, bufs))
+        p = encs[0][0]
+        q_dev = q.to(DEV)
+        out = torch.full_like(q_dev, float("nan"))
+        lse = torch.full((B, Hq), float("nan"), dtype=torch.float32, device=DEV)
+        ws = torch.empty(hq.hqmq_attend_workspace_bytes(p, Hq), dtype=torch.uint8, device=DEV)
+        hq.hqmq_attend_lse(p, q_dev, scale, encs[0][1], sec_dev[0], encs[1][1], sec_dev[1], out, lse, ws)
+        torch.cuda.synchronize()
+        outs.append(out.cpu().numpy().astype(np.float64))
+        lses.append(lse.cpu().numpy().astype(np.float64))
+        # the oracle reads the library's bytes of this range back
+        def host(bufs):
+            total = int(bufs.n_outliers[-1].item())
+            class E:
+                pass
+            e = E()
+            e.codes = bufs.codes.cpu().numpy().view(np.uint32); e.sigma = bufs.sigma.cpu().numpy().view(np.uint16)
+            e.flags = bufs.flags.cpu().numpy().view(np.uint32); e.row_off = bufs.row_off.cpu().numpy().view(np.uint32)
+            e.outliers = bufs.outliers[:total].cpu().numpy().view(np.uint16).reshape(total, 4)
+            return e
+        K64s.append(_decoded(host(encs[0][1]), sec_np[0], B, H, b - a, b_r))
+        V64s.append(_decoded(host(encs[1][1]), sec_np[1], B, H, b - a, b_r))
+        _, want_i, lse_i = oracle.attend(_bits(q), K64s[-1], V64s[-1], scale, want_lse=True)
+        _check(outs[-1], want_i, V64s[-1], Hq)
+        assert np.abs(lses[-1] - lse_i).max() < 2e-5 * max(1.0, np.abs(lse_i).max())
+    K64 = np.concatenate(K64s, axis=2)
+    V64 = np.concatenate(V64s, axis=2)
+    _, want, lse_want = oracle.attend(_bits(q), K64, V64, scale, want_lse=True)
+    L = np.logaddexp.reduce(np.stack(lses), axis=0)
+    merged = sum(np.exp(l - L)[..., None] * o for l, o in zip(lses, outs))
+    assert np.abs(L - lse_want).max() < 2e-5 * max(1.0, np.abs(lse_want).max())
+    # each part carries one fp16 rounding of its own; the weights sum to one
+    H_ = V64.shape[1]
+    vmax_q = np.repeat(np.abs(V64).max(axis=(2, 3)), Hq // H_, axis=1)[:, :, None]
+    err = np.abs(merged - want)
+    assert (err <= 2.0 ** -10 * np.abs(want) + 2 * ATT_TOL * vmax_q).all(), float(err.max())

@@ -566,6 +566,28 @@ def test_attend_matches_numpy_softmax_einsum_with_gqa():
     assert np.array_equal(o16, o64.astype(np.float16).view(np.uint16))      # numpy's RNE cast
 
 
+def test_attend_lse_against_scipy_and_the_segment_merge_identity():
+    """lse = logsumexp of the scaled scores; attention over a token range split in two equals the
+    lse-weighted combination of the two parts (the identity a caller uses to combine segments)."""
+    from scipy.special import logsumexp
+    rng = np.random.default_rng(53)
+    B, Hq, H, T, D = 2, 4, 2, 61, 128
+    q = rng.standard_normal((B, Hq, D)).astype(np.float16)
+    K = rng.standard_normal((B, H, T, D)) * 3
+    V = rng.standard_normal((B, H, T, D))
+    scale = 0.2
+    _, o, lse = oracle.attend(q.view(np.uint16), K, V, scale, want_lse=True)
+    kv = np.repeat(np.arange(H), Hq // H)
+    s = np.einsum("bqd,bqtd->bqt", q.astype(np.float64), K[:, kv]) * scale
+    assert np.allclose(lse, logsumexp(s, axis=-1), rtol=0, atol=1e-12)
+    cut = 23
+    _, o1, l1 = oracle.attend(q.view(np.uint16), K[:, :, :cut], V[:, :, :cut], scale, want_lse=True)
+    _, o2, l2 = oracle.attend(q.view(np.uint16), K[:, :, cut:], V[:, :, cut:], scale, want_lse=True)
+    L = np.logaddexp(l1, l2)
+    merged = np.exp(l1 - L)[..., None] * o1 + np.exp(l2 - L)[..., None] * o2
+    assert np.allclose(L, lse, atol=1e-12) and np.allclose(merged, o, atol=1e-12)
+
+
 def test_attend_invariants():
     rng = np.random.default_rng(51)
     B, Hq, H, T, D = 1, 4, 1, 50, 128
