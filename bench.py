@@ -216,7 +216,7 @@ def main() -> int:
                                   "peak": PEAK_F16_TFLOPS, "unit": "TFLOP/s",
                                   "frac": 256.0 * S16 * 16 * chunks_per_tensor * tensors_per_enc_launch
                                   / (search_ms * 1e-3) / 1e12 / PEAK_F16_TFLOPS}},
-        "roofline_decode": {"kernel": "k_decode" if wl.D == 128 else "k_decode_rows", "bound": "hbm", "achieved": dec_gbs, "peak": PEAK_HBM_GBS,
+        "roofline_decode": {"kernel": "k_decode" if wl.D in (64, 96, 128) else "k_decode_rows", "bound": "hbm", "achieved": dec_gbs, "peak": PEAK_HBM_GBS,
                             "unit": "GB/s", "frac": dec_gbs / PEAK_HBM_GBS,
                             "traffic": (MEASURED_TRAFFIC_BYTES[wl.name]["k_decode"] * tensors_per_dec_launch
                                         if wl.name in MEASURED_TRAFFIC_BYTES else None),
@@ -227,7 +227,7 @@ def main() -> int:
 
     # ---- extra, outside the timed step: one generation step's attention read from the packed cache
     # (one hqmq_attend per layer over that layer's encoded K and V) ------------------------------
-    if args.q_heads_per_kv > 0 and wl.D == 128:   # the attention kernel takes 128-element heads
+    if args.q_heads_per_kv > 0 and wl.D in (64, 96, 128):   # the head dimensions the attention kernel takes
         import math
         G = args.q_heads_per_kv
         gen = torch.Generator(device=dev)
@@ -250,7 +250,7 @@ def main() -> int:
         eb.record()
         torch.cuda.synchronize()
         us_layer = ea.elapsed_time(eb) * 1e3 / (reps * layers)
-        packed = 2 * info.n_rows * (4 * info.code_bits + 10) + 8.0 * n_out / layers
+        packed = 2 * info.n_rows * (4 * info.code_words_per_row + 10) + 8.0 * n_out / layers
         result["attend"] = {
             "what": "single-query attention read from the packed K and V of one layer (hqmq_attend)",
             "q_heads_per_kv_head": G, "us_per_layer": us_layer,

@@ -30,7 +30,7 @@
  *     encode and the surplus elements are not written on decode; nothing past D is touched.
  *     D = 128 is the tuned path and wants strides that are multiples of 8; other D take any
  *     strides (multiples of 4 and a D that is one keep every chunk one aligned 8-byte access).
- *     hqmq_attend is written for D = 128 only.
+ *     hqmq_attend takes D = 64, 96 and 128 (the head dimensions of the paper's models).
  */
 #ifndef HQMQ_H
 #define HQMQ_H
@@ -43,7 +43,7 @@ extern "C" {
 
 #define HQMQ_OK 0
 #define HQMQ_ERR_INVALID_ARG (-1)      /* null pointer, non-positive size, misaligned pointer or stride */
-#define HQMQ_ERR_UNSUPPORTED (-2)      /* D > 128 (hqmq_attend: D != 128), S outside 1..512, b_r outside 1..8, C not a positive finite number */
+#define HQMQ_ERR_UNSUPPORTED (-2)      /* D > 128 (hqmq_attend: D not 64, 96 or 128), S outside 1..512, b_r outside 1..8, C not a positive finite number */
 #define HQMQ_ERR_BUFFER_TOO_SMALL (-3) /* workspace smaller than hqmq_sizes() asks for */
 #define HQMQ_ERR_HIP (-4)              /* a HIP call failed; see hqmq_last_hip_error() */
 
@@ -277,18 +277,19 @@ int32_t hqmq_decode_batch(const hqmq_params *params, int32_t n_tensors, const hq
  *   params     HOST; B, H, T, D, S, b_r describe BOTH caches (strides are ignored).
  *   n_q_heads  a multiple of H, at most 16 * H.  Several query tokens that all see the whole cache
  *              (a few speculative or chunked decode positions) can ride along as extra query
- *              heads of their kv head: lay q out as [B][H][tokens * heads_per_kv][128] and pass
+ *              heads of their kv head: lay q out as [B][H][tokens * heads_per_kv][D] and pass
  *              n_q_heads = H * tokens * heads_per_kv <= 16 * H.
- *   q_dev      DEVICE, fp16 [B][n_q_heads][128] contiguous, 16-byte aligned.
- *   scale      softmax scale (usually 1/sqrt(128)); finite.
+ *   q_dev      DEVICE, fp16 [B][n_q_heads][D] contiguous, 16-byte aligned.
+ *   scale      softmax scale (usually 1/sqrt(D)); finite.
  *   enc_k, enc_v, cap_k, cap_v, sec_k_dev, sec_v_dev   as enc / outlier_capacity / sec_dev of
  *              hqmq_decode, for the key and the value cache.
- *   out_dev    DEVICE, out, fp16 [B][n_q_heads][128] contiguous, 16-byte aligned.
+ *   out_dev    DEVICE, out, fp16 [B][n_q_heads][D] contiguous, 16-byte aligned.
  *   workspace_dev  DEVICE scratch, 256-byte aligned, hqmq_attend_workspace_bytes() bytes; owned
  *              by the caller, contents undefined afterwards; concurrent calls need their own.
  *   stream     hipStream_t; two kernels are enqueued, nothing is synchronised or allocated.
  * Errors: INVALID_ARG (null / misaligned pointer, bad n_q_heads, non-finite scale), UNSUPPORTED
- * (params the decode rejects, more than 16 query heads per kv head), BUFFER_TOO_SMALL, HIP. */
+ * (params the decode rejects, D other than 64, 96, 128, more than 16 query heads per kv head),
+ * BUFFER_TOO_SMALL, HIP. */
 int32_t hqmq_attend(const hqmq_params *params, int32_t n_q_heads, const void *q_dev, float scale,
                     const hqmq_encoded *enc_k, uint64_t cap_k, const float *sec_k_dev,
                     const hqmq_encoded *enc_v, uint64_t cap_v, const float *sec_v_dev, void *out_dev,

@@ -375,7 +375,7 @@ def hqmq_attend_workspace_bytes(params: HqmqParams, n_q_heads: int) -> int:
 def _check_attend_args(params, q, out, sec_k, sec_v, workspace):
     for t in (q, out):
         if t.dtype != torch.float16 or not t.is_cuda or not t.is_contiguous() or t.dim() != 3:
-            raise ValueError("q and out must be contiguous device fp16 [B, n_q_heads, 128]")
+            raise ValueError("q and out must be contiguous device fp16 [B, n_q_heads, D]")
     if q.shape != out.shape or q.shape[0] != params.B or q.shape[2] != params.D:
         raise ValueError("q / out shape does not match params")
     for sec in (sec_k, sec_v):
@@ -390,7 +390,7 @@ def hqmq_attend(params: HqmqParams, q: torch.Tensor, scale: float, enc_k: Encode
                 sec_k: torch.Tensor, enc_v: EncodedBuffers, sec_v: torch.Tensor, out: torch.Tensor,
                 workspace: torch.Tensor, stream=None) -> None:
     """Enqueue single-query attention over the packed K and V caches: q and out are contiguous
-    device fp16 [B, n_q_heads, 128]."""
+    device fp16 [B, n_q_heads, D], D = 64, 96 or 128."""
     _check_attend_args(params, q, out, sec_k, sec_v, workspace)
     rc = _load().hqmq_attend(C.byref(params), int(q.shape[1]), q.data_ptr(), float(scale),
                              C.byref(enc_k.as_struct()), enc_k.outlier_capacity, sec_k.data_ptr(),

@@ -467,8 +467,8 @@ static int32_t check_attend(const hqmq_params *params, int32_t n_q_heads)
         return rc;
     if (n_q_heads <= 0 || n_q_heads % params->H)
         return HQMQ_ERR_INVALID_ARG;
-    if (params->D != 4 * kChunksPerRow)
-        return HQMQ_ERR_UNSUPPORTED;  // the attention kernel is written for 128-element heads
+    if (params->D != 128 && params->D != 96 && params->D != 64)
+        return HQMQ_ERR_UNSUPPORTED;  // the attention kernel takes the head dimensions of the paper's models
     if (n_q_heads / params->H > kMaxGroup)
         return HQMQ_ERR_UNSUPPORTED;
     return HQMQ_OK;
@@ -527,6 +527,7 @@ static int32_t attend_impl(const hqmq_params *params, int32_t n_q_heads, const v
     a.part_acc = reinterpret_cast<float *>(static_cast<char *>(workspace_dev) + plan.ml_bytes);
     a.qscale = scale * 1.44269504088896340736f;
     a.G = G;
+    a.D = params->D;
     a.n_splits = plan.n_splits;
     a.rows_per_split = plan.rows_per_split;
     hipError_t err = launch_attend(g, a, static_cast<hipStream_t>(stream));

@@ -23,6 +23,8 @@
 //     when a tile raises a head's running maximum;
 //   * a flagged chunk takes its stored fp16 payload from the wave's window of the outlier list.
 // The work per cached token does not depend on G (up to 16 heads ride in one product).
+// Written out for 128-element heads (32 chunks per row); heads of 96 and 64 elements run the same code
+// with 6 or 4 score products per tile and 2 (the second half empty) or 1 column groups on the value side.
 #include <type_traits>
 
 #include "hqmq_device.h"
@@ -65,15 +67,15 @@ struct TileRegs {
 };
 
 __device__ __forceinline__ void load_tile(TileRegs &t, const AttendSide &s, int64_t R0, int nrows,
-                                          uint32_t w, int lane)
+                                          uint32_t row_words, int lane)
 {
 #pragma unroll
     for (int j = 0; j < kLoadsPerLane; ++j)
         t.cw[j] = 0;
     t.fw = t.sg = t.ro = 0;
     if (nrows > 0) {
-        const uint32_t *cw = s.codes + R0 * w;
-        const int ncw = nrows * (int)w;
+        const uint32_t *cw = s.codes + R0 * row_words;
+        const int ncw = nrows * (int)row_words;
 #pragma unroll
         for (int j = 0; j < kLoadsPerLane; ++j)
             if (lane + 64 * j < ncw)
@@ -86,7 +88,7 @@ __device__ __forceinline__ void load_tile(TileRegs &t, const AttendSide &s, int6
     }
 }
 
-// LDS image of one side: code words [16 rows][w] | padding | flag words [16] | scales [16] |
+// LDS image of one side: code words [16 rows][row_words] | padding | flag words [16] | scales [16] |
 // offsets [16] | payload window [64] x 8 bytes
 __device__ __forceinline__ void stage_tile(const TileRegs &t, uint32_t *stage, int lane)
 {
@@ -122,9 +124,15 @@ __device__ __forceinline__ float4_t mfma16(uint2 a, uint2 b, float4_t c)
 // grid = (n_splits, B*H), block = 256.
 // dynamic LDS: prim [48][4] f32 | max(staging [4 waves][K, V][kSideWords] u32, merge buffer
 //              [4 waves][G][130] f32) | secondaries of K [S][4] f32 | secondaries of V [S][4] f32
-template <bool kPow2>
+// kNc: chunks per row, 32, 24 or 16 for head dimensions 128, 96, 64 (multiples of 16 elements, so that
+// the score products take whole groups of 4 chunks).  The value side always works in column groups of
+// 16 chunks; chunks past the row (the upper 8 of the second group at 24) read as code 0 = zeros.
+template <bool kPow2, int kNc>
 __global__ __launch_bounds__(kAttThreads, 2) void k_attend_partial(Geometry g, AttendArgs a, int stage_floats)
 {
+    constexpr int kM = kNc / 4;          // score products per tile (16 dimensions each)
+    constexpr int kU = (kNc + 15) / 16;  // column groups of 16 chunks on the value side
+    constexpr int kD = 4 * kNc;
     extern __shared__ float lds[];
     float *prim = lds;
     uint32_t *stage_all = reinterpret_cast<uint32_t *>(prim + 48 * 4);
@@ -139,6 +147,7 @@ __global__ __launch_bounds__(kAttThreads, 2) void k_attend_partial(Geometry g, A
     const int n16_ = n16, j4_ = j4;
     const int G = a.G;
     const uint32_t w = g.w, w_idx = g.w_idx;
+    const uint32_t row_words = kNc == 32 ? w : (uint32_t)g.row_words;
     const int row_begin = split * a.rows_per_split;
     const int row_end = min(g.T, row_begin + a.rows_per_split);
 
@@ -150,15 +159,15 @@ __global__ __launch_bounds__(kAttThreads, 2) void k_attend_partial(Geometry g, A
     int nrows = min(kStageRows, row_end - (row_begin + wv * kStageRows));
     {
         const int64_t R0 = (int64_t)seg * g.T + row_begin + wv * kStageRows;
-        load_tile(tk, a.k, R0, nrows, w, lane);
-        load_tile(tv, a.v, R0, nrows, w, lane);
+        load_tile(tk, a.k, R0, nrows, row_words, lane);
+        load_tile(tv, a.v, R0, nrows, row_words, lane);
     }
     // Q^T as the B operand of the score products: lane (head n16, j4) holds q[head][16 m + 4 j4 + 0..3]
-    uint2 qb[8];
+    uint2 qb[kM];
     {
-        const _Float16 *qh = a.q + (((size_t)b * g.H + h) * G + min(n16, G - 1)) * 128 + 4 * j4;
+        const _Float16 *qh = a.q + (((size_t)b * g.H + h) * G + min(n16, G - 1)) * kD + 4 * j4;
 #pragma unroll
-        for (int m = 0; m < 8; ++m) {
+        for (int m = 0; m < kM; ++m) {
             const uint2 v = *reinterpret_cast<const uint2 *>(qh + 16 * m);
             qb[m] = (n16 < G) ? v : make_uint2(0u, 0u);
         }
@@ -185,9 +194,9 @@ __global__ __launch_bounds__(kAttThreads, 2) void k_attend_partial(Geometry g, A
     // rows only and is summed over j4 at the end)
     float m_run = kNegBig, l_run = 0.f;
     // [upper chunk u][component e]: element i = head 4 j4 + i, output column n16 = dimension 64 u + 4 n16 + e
-    float4_t acc[2][4];
+    float4_t acc[kU][4];
 #pragma unroll
-    for (int u = 0; u < 2; ++u)
+    for (int u = 0; u < kU; ++u)
 #pragma unroll
         for (int e = 0; e < 4; ++e)
             acc[u][e] = float4_t{0.f, 0.f, 0.f, 0.f};
@@ -248,9 +257,12 @@ __global__ __launch_bounds__(kAttThreads, 2) void k_attend_partial(Geometry g, A
     // tile and side.
     auto read_code = [&](const uint32_t *stage, int row, uint32_t c) {
         const uint32_t bitpos = c * w;
-        const uint32_t *rw = stage + row * w + (bitpos >> 5);
+        const uint32_t *rw = stage + row * row_words + (bitpos >> 5);
         const uint32_t d0 = rw[0], d1 = rw[1];
-        return __builtin_amdgcn_alignbit(d1, d0, bitpos & 31u) & code_mask;
+        const uint32_t code = __builtin_amdgcn_alignbit(d1, d0, bitpos & 31u) & code_mask;
+        // a chunk slot past the row's chunks (value side, 24 chunks per row): what was read lies inside
+        // the staged words but means nothing; code 0 decodes to zeros and its flag bit is never set
+        return (kNc % 16 == 0 || c < (uint32_t)kNc) ? code : 0u;
     };
     struct Fetched {
         float4_t P, q;
@@ -335,8 +347,8 @@ __global__ __launch_bounds__(kAttThreads, 2) void k_attend_partial(Geometry g, A
         const int nn = more ? min(kStageRows, row_end - tgn) : 0;
         if (more) {
             const int64_t R0n = (int64_t)seg * g.T + tgn;
-            load_tile(tk, a.k, R0n, nn, w, lane);
-            load_tile(tv, a.v, R0n, nn, w, lane);
+            load_tile(tk, a.k, R0n, nn, row_words, lane);
+            load_tile(tv, a.v, R0n, nn, row_words, lane);
         }
 
         uint2 p_hi = make_uint2(0u, 0u), p_lo = make_uint2(0u, 0u);
@@ -356,15 +368,15 @@ __global__ __launch_bounds__(kAttThreads, 2) void k_attend_partial(Geometry g, A
                 const uint32_t roff = stage_k[kStageWords + 2 * kStageRows + n16];
                 const float sol = sigma * inv_L;
                 const bool valid = n16 < nrows;
-                uint32_t code[8];
+                uint32_t code[kM];
 #pragma unroll
-                for (int m = 0; m < 8; ++m)
+                for (int m = 0; m < kM; ++m)
                     code[m] = read_code(stage_k, n16, (uint32_t)(4 * m + j4));
                 Fetched cur = fetch(stage_k, sec_k, base_k, code[0], (uint32_t)j4, word, roff);
 #pragma unroll
-                for (int m = 0; m < 8; ++m) {
+                for (int m = 0; m < kM; ++m) {
                     Fetched nxt = cur;
-                    if (m + 1 < 8)
+                    if (m + 1 < kM)
                         nxt = fetch(stage_k, sec_k, base_k, code[m + 1], (uint32_t)(4 * (m + 1) + j4), word, roff);
                     const uint2 kh = finish(fast_tag, a.k, base_k, cur, code[m], (uint32_t)(4 * m + j4), word, sol, valid);
                     sc = mfma16(kh, qb[m], sc);
@@ -397,7 +409,7 @@ __global__ __launch_bounds__(kAttThreads, 2) void k_attend_partial(Geometry g, A
                 for (int i = 0; i < 4; ++i) {
                     const float ci = __shfl(corr, 4 * j4 + i);
 #pragma unroll
-                    for (int u = 0; u < 2; ++u)
+                    for (int u = 0; u < kU; ++u)
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
                             acc[u][e][i] *= ci;
@@ -438,23 +450,24 @@ __global__ __launch_bounds__(kAttThreads, 2) void k_attend_partial(Geometry g, A
                 const uint4v sig4 = *reinterpret_cast<const uint4v *>(stage_v + kStageWords + kStageRows + 4 * j4);
                 const uint4v roff4 =
                     *reinterpret_cast<const uint4v *>(stage_v + kStageWords + 2 * kStageRows + 4 * j4);
-                uint32_t code[8];
+                uint32_t code[4 * kU];
                 float sol[4];
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     sol[i] = (float)__builtin_bit_cast(_Float16, (uint16_t)sig4[i]) * inv_L;
-                    code[i] = read_code(stage_v, 4 * j4 + i, (uint32_t)n16);
-                    code[4 + i] = read_code(stage_v, 4 * j4 + i, (uint32_t)(n16 + 16));
+#pragma unroll
+                    for (int u = 0; u < kU; ++u)
+                        code[4 * u + i] = read_code(stage_v, 4 * j4 + i, (uint32_t)(n16 + 16 * u));
                 }
                 Fetched cur = fetch(stage_v, sec_v, base_v, code[0], (uint32_t)n16, word4[0], roff4[0]);
 #pragma unroll
-                for (int u = 0; u < 2; ++u) {
+                for (int u = 0; u < kU; ++u) {
                     uint2 vh[4];
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         const int at = 4 * u + i, nx = at + 1;
                         Fetched nxt = cur;
-                        if (nx < 8)
+                        if (nx < 4 * kU)
                             nxt = fetch(stage_v, sec_v, base_v, code[nx], (uint32_t)(n16 + 16 * (nx >> 2)),
                                         word4[nx & 3], roff4[nx & 3]);
                         vh[i] = finish(fast_tag, a.v, base_v, cur, code[at], (uint32_t)(n16 + 16 * u), word4[i],
@@ -502,7 +515,7 @@ __global__ __launch_bounds__(kAttThreads, 2) void k_attend_partial(Geometry g, A
         const int head = 4 * j4 + i;
         if (head < G) {
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
+            for (int u = 0; u < kU; ++u) {
                 float *dst = red + (wv * G + head) * kRedStride + 2 + 64 * u + 4 * n16;
                 *reinterpret_cast<float2 *>(dst) = make_float2(acc[u][0][i], acc[u][1][i]);
                 *reinterpret_cast<float2 *>(dst + 2) = make_float2(acc[u][2][i], acc[u][3][i]);
@@ -512,6 +525,8 @@ __global__ __launch_bounds__(kAttThreads, 2) void k_attend_partial(Geometry g, A
     __syncthreads();
     for (int idx = tid; idx < G * 128; idx += kAttThreads) {
         const int gq = idx >> 7, d = idx & 127;
+        if (d >= kD)
+            continue;  // dimensions past the head (the partial arrays keep a pitch of 128)
         float mm = kNegBig;
 #pragma unroll
         for (int wq = 0; wq < kAttWaves; ++wq)
@@ -533,7 +548,7 @@ __global__ __launch_bounds__(kAttThreads, 2) void k_attend_partial(Geometry g, A
     }
 }
 
-// grid = (B * H * G, 8): workgroup (head, y) produces 16 of the head's 128 output dimensions.
+// grid = (B * H * G, D / 16): workgroup (head, y) produces 16 of the head's D output dimensions.
 // First the global maximum and the weight 2^(m_s - M) of every split (kept in LDS), then plain
 // weighted sums with independent loads: thread (j, i) adds the splits j, j + 16, ... for dimension i.
 constexpr int kMergeDims = 16;
@@ -598,7 +613,7 @@ __global__ __launch_bounds__(kAttThreads) void k_attend_merge(AttendArgs a)
 #pragma unroll
         for (int jj = 0; jj < kMergeWays; ++jj)
             tot += sums[jj * (kMergeDims + 1) + tid];
-        a.out[head * 128 + d0 + tid] = (_Float16)(tot / lsum);
+        a.out[head * a.D + d0 + tid] = (_Float16)(tot / lsum);
     }
     // log-sum-exp of the head's scores (the running maximum is kept in the log2 domain)
     if (a.lse && blockIdx.y == 0 && tid == 0)
@@ -636,15 +651,28 @@ hipError_t launch_attend(const Geometry &g, const AttendArgs &a, hipStream_t str
     stage_floats = (stage_floats + 3) / 4 * 4;
     const size_t lds = (size_t)(48 * 4 + stage_floats + 8 * g.S) * sizeof(float);
     dim3 grid((unsigned)a.n_splits, (unsigned)(g.B * g.H));
-    if ((g.S & (g.S - 1)) == 0)
-        hipLaunchKernelGGL(k_attend_partial<true>, grid, dim3(kAttThreads), lds, stream, g, a, stage_floats);
+    const bool pow2 = (g.S & (g.S - 1)) == 0;
+#define HQMQ_LAUNCH_ATTEND(NC)                                                                                       \
+    do {                                                                                                             \
+        if (pow2)                                                                                                    \
+            hipLaunchKernelGGL((k_attend_partial<true, NC>), grid, dim3(kAttThreads), lds, stream, g, a, stage_floats);  \
+        else                                                                                                         \
+            hipLaunchKernelGGL((k_attend_partial<false, NC>), grid, dim3(kAttThreads), lds, stream, g, a, stage_floats); \
+    } while (0)
+    if (g.D == 128)
+        HQMQ_LAUNCH_ATTEND(32);
+    else if (g.D == 96)
+        HQMQ_LAUNCH_ATTEND(24);
+    else if (g.D == 64)
+        HQMQ_LAUNCH_ATTEND(16);
     else
-        hipLaunchKernelGGL(k_attend_partial<false>, grid, dim3(kAttThreads), lds, stream, g, a, stage_floats);
+        return hipErrorInvalidValue;
+#undef HQMQ_LAUNCH_ATTEND
     hipError_t err = hipGetLastError();
     if (err != hipSuccess)
         return err;
     const size_t merge_lds = ((size_t)a.n_splits + kMergeWays * (kMergeDims + 1)) * sizeof(float);
-    hipLaunchKernelGGL(k_attend_merge, dim3((unsigned)(g.B * g.H * a.G), 128 / kMergeDims), dim3(kAttThreads),
+    hipLaunchKernelGGL(k_attend_merge, dim3((unsigned)(g.B * g.H * a.G), (unsigned)(g.D / kMergeDims)), dim3(kAttThreads),
                        merge_lds, stream, a);
     return hipGetLastError();
 }

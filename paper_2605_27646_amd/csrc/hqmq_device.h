@@ -160,13 +160,14 @@ struct AttendSide {
 };
 struct AttendArgs {
     AttendSide k, v;
-    const _Float16 *q;     // [B][H * G][128]
-    _Float16 *out;         // [B][H * G][128]
+    const _Float16 *q;     // [B][H * G][D]
+    _Float16 *out;         // [B][H * G][D]
     float *lse;            // [B][H * G] natural-log sum of exp(score) over the cached tokens, or null
     float *part_ml;        // [B * H * G][n_splits][2]: running maximum (log2 domain) and weight sum
     float *part_acc;       // [B * H * G][n_splits][128]: weighted value sum
     float qscale;          // softmax scale * log2(e), folded into the query
     int32_t G;             // query heads per kv head
+    int32_t D;             // head dimension: 64, 96 or 128 (q and out rows; the partial sums keep a pitch of 128)
     int32_t n_splits;      // workgroups along the sequence
     int32_t rows_per_split;  // multiple of kAttendTile
 };

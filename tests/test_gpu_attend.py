@@ -36,9 +36,9 @@ def _secs(seed, H, S):
     return cb[0, 0].contiguous(), cb[0, 1].contiguous()
 
 
-def _query(B, Hq, seed, gain=1.0):
+def _query(B, Hq, seed, gain=1.0, D=128):
     gen = torch.Generator().manual_seed(seed)
-    return (torch.randn(B, Hq, 128, generator=gen) * gain).to(torch.float16)
+    return (torch.randn(B, Hq, D, generator=gen) * gain).to(torch.float16)
 
 
 def _gpu_attend(params, q, scale, bufs_k, sec_k, bufs_v, sec_v):
@@ -64,22 +64,22 @@ def _check(got, want64, V64, Hq):
     return rel
 
 
-def _decoded(e, sec_np, B, H, T, b_r):
-    """The oracle's fp16 decode of an encoded tensor, widened to fp64 [B, H, T, 128]."""
-    bits = oracle.decode(e.codes, e.sigma, e.flags, e.row_off, e.outliers, sec_np, B, H, T, b_r)
-    return bits.view(np.float16).astype(np.float64).reshape(B, H, T, 128)
+def _decoded(e, sec_np, B, H, T, b_r, D=128):
+    """The oracle's fp16 decode of an encoded tensor, widened to fp64 [B, H, T, D]."""
+    bits = oracle.decode(e.codes, e.sigma, e.flags, e.row_off, e.outliers, sec_np, B, H, T, b_r, D=D)
+    return bits.view(np.float16).astype(np.float64).reshape(B, H, T, D)
 
 
-def _oracle_attend(enc, sec_np, q, scale, B, H, T, b_r):
+def _oracle_attend(enc, sec_np, q, scale, B, H, T, b_r, D=128):
     """enc: a pair of objects with codes / sigma / flags / row_off / outliers (numpy)."""
-    K64 = _decoded(enc[0], sec_np[0], B, H, T, b_r)
-    V64 = _decoded(enc[1], sec_np[1], B, H, T, b_r)
+    K64 = _decoded(enc[0], sec_np[0], B, H, T, b_r, D)
+    V64 = _decoded(enc[1], sec_np[1], B, H, T, b_r, D)
     _, o64 = oracle.attend(_bits(q), K64, V64, scale)
     return o64, K64, V64
 
 
-def _tensors(B, H, T, seed, law_sigma=0.7):
-    wl = workloads.Workload("att", 300 + seed, 1, B, H, T, 128, 16, sigma_g=law_sigma)
+def _tensors(B, H, T, seed, law_sigma=0.7, D=128):
+    wl = workloads.Workload("att", 300 + seed, 1, B, H, T, D, 16, sigma_g=law_sigma)
     return workloads.make_tensor(wl, 0, 0, "cpu"), workloads.make_tensor(wl, 0, 1, "cpu")
 
 
@@ -106,6 +106,53 @@ def test_attend_small_oracle_encoded(B, H, T, Hq, S, b_r):
     got = _gpu_attend(params, q, scale, upload_encoded(ek, DEV), sec_k.to(DEV), upload_encoded(ev, DEV),
                       sec_v.to(DEV))
     _check(got, want, V64, Hq)
+
+
+@pytest.mark.parametrize("D,B,H,T,Hq,S,b_r", [
+    (64, 1, 2, 63, 4, 16, 6),           # 16 chunks per row: 4 score products, one column group of values
+    (64, 2, 1, 1000, 8, 192, 4),        # the paper's s192_r4, 8 query heads per kv head
+    (64, 1, 1, 1, 16, 24, 4),           # a single cached token
+    (96, 1, 2, 129, 6, 16, 6),          # 24 chunks per row: 6 score products, second column group half empty
+    (96, 2, 2, 777, 8, 192, 4),
+    (96, 1, 1, 3000, 16, 48, 3),
+])
+def test_attend_other_head_dimensions(D, B, H, T, Hq, S, b_r):
+    """Heads of 64 and 96 elements, GPU-encoded (exercises their search and packing as well); the oracle
+    reads those bytes back, decodes and attends."""
+    k, v = _tensors(B, H, T, seed=T + D, D=D)
+    sec_k, sec_v = _secs(7, H, S)
+    gk = gpu_encode(k.to(DEV), sec_k.to(DEV), b_r)
+    gv = gpu_encode(v.to(DEV), sec_v.to(DEV), b_r)
+    assert gk.status == 0 and gv.status == 0 and (gk.n_out[-1] > 0 or T < 8)
+    q = _query(B, Hq, seed=T + 2, gain=1.5, D=D)
+    scale = 1 / math.sqrt(D)
+    want, _, V64 = _oracle_attend((gk, gv), (sec_k.numpy(), sec_v.numpy()), q, scale, B, H, T, b_r, D)
+    got = _gpu_attend(gk.params, q, scale, gk.bufs, sec_k.to(DEV), gv.bufs, sec_v.to(DEV))
+    _check(got, want, V64, Hq)
+
+
+def test_attend_other_head_dimensions_full_size_with_lse():
+    """One layer of the 64-element workload at its full length, and the log-sum-exp output."""
+    wl = workloads.WORKLOADS["gqa8_d64_32k"]
+    k = workloads.make_tensor(wl, 0, 0, "cpu")
+    v = workloads.make_tensor(wl, 0, 1, "cpu")
+    sec_k, sec_v = _secs(0, wl.H, wl.S)
+    gk = gpu_encode(k.to(DEV), sec_k.to(DEV), wl.b_r)
+    gv = gpu_encode(v.to(DEV), sec_v.to(DEV), wl.b_r)
+    Hq = 4 * wl.H
+    q = _query(wl.B, Hq, seed=5, gain=2.0, D=wl.D)
+    scale = 1 / math.sqrt(wl.D)
+    K64 = _decoded(gk, sec_k.numpy(), wl.B, wl.H, wl.T, wl.b_r, wl.D)
+    V64 = _decoded(gv, sec_v.numpy(), wl.B, wl.H, wl.T, wl.b_r, wl.D)
+    _, want, lse_want = oracle.attend(_bits(q), K64, V64, scale, want_lse=True)
+    q_dev = q.to(DEV)
+    out = torch.full_like(q_dev, float("nan"))
+    lse = torch.full((wl.B, Hq), float("nan"), dtype=torch.float32, device=DEV)
+    ws = torch.empty(hq.hqmq_attend_workspace_bytes(gk.params, Hq), dtype=torch.uint8, device=DEV)
+    hq.hqmq_attend_lse(gk.params, q_dev, scale, gk.bufs, sec_k.to(DEV), gv.bufs, sec_v.to(DEV), out, lse, ws)
+    torch.cuda.synchronize()
+    _check(out.cpu().numpy().astype(np.float64), want, V64, Hq)
+    assert np.abs(lse.cpu().numpy() - lse_want).max() < 2e-5 * max(1.0, np.abs(lse_want).max())
 
 
 def test_attend_splits_with_several_tiles_each_gpu_encoded():
