@@ -684,15 +684,14 @@ hipError_t launch_search(const Geometry &g, const WorkspaceOffsets &wo, const En
     if (err != hipSuccess)
         return err;
     if (device < 0 || device >= 64 || !raised[device]) {
-        const void *variants[8] = {reinterpret_cast<const void *>(k_search<4, kSearchRowsSmall>),
+        const void *variants[7] = {reinterpret_cast<const void *>(k_search<4, kSearchRowsSmall>),
                                    reinterpret_cast<const void *>(k_search<4, kSearchRowsLarge>),
                                    reinterpret_cast<const void *>(k_search<8, kSearchRowsSmall>),
                                    reinterpret_cast<const void *>(k_search<8, kSearchRowsLarge>),
                                    reinterpret_cast<const void *>(k_search_flat<4, kSearchRowsSmall>),
                                    reinterpret_cast<const void *>(k_search_flat<4, kSearchRowsLarge>),
-                                   reinterpret_cast<const void *>(k_search_flat<8, kSearchRowsSmall>),
-                                   reinterpret_cast<const void *>(k_search_flat<8, kSearchRowsLarge>)};
-        for (int i = 0; i < 8 && err == hipSuccess; ++i)
+                                   reinterpret_cast<const void *>(k_search_flat<8, kSearchRowsSmall>)};
+        for (int i = 0; i < 7 && err == hipSuccess; ++i)
             err = hipFuncSetAttribute(variants[i], hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCu);
         if (err != hipSuccess)
             return err;
@@ -713,12 +712,11 @@ hipError_t launch_search(const Geometry &g, const WorkspaceOffsets &wo, const En
         else
             HQMQ_LAUNCH(k_search, 4, kSearchRowsSmall);
     } else {
-        if (waves == 8 && large)
-            HQMQ_LAUNCH(k_search_flat, 8, kSearchRowsLarge);
+        // 256 rows per workgroup are only chosen when two 4-wave workgroups fit a CU
+        if (large)
+            HQMQ_LAUNCH(k_search_flat, 4, kSearchRowsLarge);
         else if (waves == 8)
             HQMQ_LAUNCH(k_search_flat, 8, kSearchRowsSmall);
-        else if (large)
-            HQMQ_LAUNCH(k_search_flat, 4, kSearchRowsLarge);
         else
             HQMQ_LAUNCH(k_search_flat, 4, kSearchRowsSmall);
     }

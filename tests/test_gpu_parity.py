@@ -232,6 +232,10 @@ def test_other_workloads_full_size_sampled(name, layer, role):
     (100, 2, 2, 90, 33, 5),      # multiple of 4, strides not multiples of 8
     (126, 1, 1, 130, 256, 6),    # 32 chunks like the full row, but through the general path
     (124, 1, 3, 2100, 64, 6),    # 31 chunks; long enough for the 256-row search workgroups
+    (96, 1, 1, 2100, 256, 6),    # long, but the tables leave no room for 256-row workgroups: 8 waves, 64 rows
+    (96, 1, 1, 70, 512, 8),      # largest S and b_r at 24 chunks per row
+    (124, 1, 1, 70, 512, 8),     # the most LDS the general search can ask for
+    (64, 1, 2, 4100, 192, 4),    # 256-row workgroups at 16 chunks per row, ragged last workgroup
 ])
 def test_other_head_dimensions_small(D, B, H, T, S, b_r):
     print(f"case D={D} B={B} H={H} T={T} S={S} b_r={b_r}", flush=True)
