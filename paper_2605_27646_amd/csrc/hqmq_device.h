@@ -11,8 +11,10 @@ namespace hqmq {
 
 constexpr int kChunksPerRow = 32;    // chunks of a row of D = 128 elements, and the most a row may have
 constexpr int kSearchRowsSmall = 64;   // rows per search workgroup = granularity of the outlier scan:
-constexpr int kSearchRowsLarge = 256;  // 64 for short segments (more workgroups), 256 from 2048 rows on
+constexpr int kSearchRowsLarge = 256;  // 64 for short segments (more workgroups), 256 from 2048 rows on,
+constexpr int kSearchRowsHuge = 512;   // 512 from 4096 rows on (rows of 128 elements, 16-wave workgroups)
 constexpr int kSearchRowsSwitch = 2048;
+constexpr int kSearchRowsSwitchHuge = 4096;
 constexpr int kThreads = 256;        // default workgroup: 4 wave64
 
 // Radix select over the 63 value bits of a non-negative IEEE double: two histogram digits from
@@ -62,10 +64,25 @@ inline size_t search_lds_bytes(int S16, int D, int row_words, int waves, int row
 }
 constexpr size_t kLdsPerCu = 160 * 1024;
 
-// Rows per search workgroup: 256 for long segments (the head's operand table is copied a quarter as
-// often), as long as two such workgroups still fit a CU; 64 otherwise.
+// Waves of a search workgroup.  Rows of 128 elements, 256 or more rows per workgroup: one workgroup of 16
+// waves per CU when its LDS fits (four waves on every SIMD sharing one copy of the tables: measured 2 %
+// faster than two workgroups of 4).  Otherwise 4 waves when two workgroups fit a CU's LDS, else one
+// workgroup of 8, which keeps two waves on every SIMD.
+inline int search_waves_for(int S16, int D, int row_words, int rows)
+{
+    if (D == 4 * kChunksPerRow && rows >= kSearchRowsLarge &&
+        search_lds_bytes(S16, D, row_words, 16, rows) <= kLdsPerCu)
+        return 16;
+    return 2 * search_lds_bytes(S16, D, row_words, 4, rows) > kLdsPerCu ? 8 : 4;
+}
+
+// Rows per search workgroup: more rows for long segments (the head's operand table is copied less
+// often), as long as the workgroups that go with them fit a CU; 64 otherwise.
 inline int search_rows_for(int T, int S16, int D, int row_words)
 {
+    if (T >= kSearchRowsSwitchHuge && D == 4 * kChunksPerRow &&
+        search_lds_bytes(S16, D, row_words, 16, kSearchRowsHuge) <= kLdsPerCu)
+        return kSearchRowsHuge;
     if (T >= kSearchRowsSwitch &&
         (D == 4 * kChunksPerRow || 2 * search_lds_bytes(S16, D, row_words, 4, kSearchRowsLarge) <= kLdsPerCu))
         return kSearchRowsLarge;

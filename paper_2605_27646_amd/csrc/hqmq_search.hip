@@ -392,7 +392,8 @@ __global__ __launch_bounds__(kThreads) void k_prepare_operands(Geometry g, Works
 
 }
 
-// kWaves: 4, or 8 when the A operands are so large (S > 256) that only one workgroup fits a CU: twice
+// kWaves: 16 for workgroups of 256 or 512 rows (one per CU, four waves on every SIMD); for 64-row
+// workgroups 4, or 8 when the A operands are so large (S > 256) that only one workgroup fits a CU: twice
 // the waves then share them and keep two waves on every SIMD.
 // This kernel is for rows of 128 elements (32 chunks: two rows per wave); k_search_flat below takes
 // every other head dimension.
@@ -673,9 +674,7 @@ hipError_t launch_search(const Geometry &g, const WorkspaceOffsets &wo, const En
 {
     dim3 grid((g.T + g.search_rows - 1) / g.search_rows, g.B * g.H, (unsigned)n_tensors);
     const bool full = g.D == 4 * kChunksPerRow;
-    // 4 waves when two workgroups fit a CU's LDS; otherwise one workgroup of 8 keeps two waves on every
-    // SIMD and shares one copy of the tables
-    const int waves = 2 * search_lds_bytes(g.S16, g.D, g.row_words, 4, g.search_rows) > kLdsPerCu ? 8 : 4;
+    const int waves = search_waves_for(g.S16, g.D, g.row_words, g.search_rows);
     const size_t lds = search_lds_bytes(g.S16, g.D, g.row_words, waves, g.search_rows);
     // more than the 64 KiB a kernel gets by default once S > 208: raise the kernels' limit, once per device
     static bool raised[64] = {};
@@ -684,14 +683,15 @@ hipError_t launch_search(const Geometry &g, const WorkspaceOffsets &wo, const En
     if (err != hipSuccess)
         return err;
     if (device < 0 || device >= 64 || !raised[device]) {
-        const void *variants[7] = {reinterpret_cast<const void *>(k_search<4, kSearchRowsSmall>),
-                                   reinterpret_cast<const void *>(k_search<4, kSearchRowsLarge>),
+        const void *variants[8] = {reinterpret_cast<const void *>(k_search<4, kSearchRowsSmall>),
                                    reinterpret_cast<const void *>(k_search<8, kSearchRowsSmall>),
                                    reinterpret_cast<const void *>(k_search<8, kSearchRowsLarge>),
+                                   reinterpret_cast<const void *>(k_search<16, kSearchRowsLarge>),
+                                   reinterpret_cast<const void *>(k_search<16, kSearchRowsHuge>),
                                    reinterpret_cast<const void *>(k_search_flat<4, kSearchRowsSmall>),
                                    reinterpret_cast<const void *>(k_search_flat<4, kSearchRowsLarge>),
                                    reinterpret_cast<const void *>(k_search_flat<8, kSearchRowsSmall>)};
-        for (int i = 0; i < 7 && err == hipSuccess; ++i)
+        for (int i = 0; i < 8 && err == hipSuccess; ++i)
             err = hipFuncSetAttribute(variants[i], hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCu);
         if (err != hipSuccess)
             return err;
@@ -703,12 +703,16 @@ hipError_t launch_search(const Geometry &g, const WorkspaceOffsets &wo, const En
     const bool large = g.search_rows == kSearchRowsLarge;
 #define HQMQ_LAUNCH(KERNEL, W, R) hipLaunchKernelGGL((KERNEL<W, R>), grid, dim3(64 * W), lds, stream, g, wo, batch)
     if (full) {
-        if (waves == 8 && large)
+        // (256 rows with 4 waves cannot come up: tables that leave no room for 16 waves leave none for
+        // two workgroups of 4 either)
+        if (g.search_rows == kSearchRowsHuge)
+            HQMQ_LAUNCH(k_search, 16, kSearchRowsHuge);
+        else if (large && waves == 16)
+            HQMQ_LAUNCH(k_search, 16, kSearchRowsLarge);
+        else if (large)
             HQMQ_LAUNCH(k_search, 8, kSearchRowsLarge);
         else if (waves == 8)
             HQMQ_LAUNCH(k_search, 8, kSearchRowsSmall);
-        else if (large)
-            HQMQ_LAUNCH(k_search, 4, kSearchRowsLarge);
         else
             HQMQ_LAUNCH(k_search, 4, kSearchRowsSmall);
     } else {
