@@ -64,13 +64,15 @@ inline size_t search_lds_bytes(int S16, int D, int row_words, int waves, int row
 }
 constexpr size_t kLdsPerCu = 160 * 1024;
 
-// Waves of a search workgroup.  Rows of 128 elements, 256 or more rows per workgroup: one workgroup of 16
-// waves per CU when its LDS fits (four waves on every SIMD sharing one copy of the tables: measured 2 %
-// faster than two workgroups of 4).  Otherwise 4 waves when two workgroups fit a CU's LDS, else one
-// workgroup of 8, which keeps two waves on every SIMD.
+// Waves of a search workgroup.  256 or more rows per workgroup, and tables so large
+// that fewer than four 4-wave workgroups fit a CU's LDS: one workgroup of 16 waves per CU when its LDS
+// fits (four waves on every SIMD sharing one copy of the tables; at S = 256 measured 3 % faster than two
+// workgroups of 4, while at S = 64, where five small workgroups fit, the small ones are 13 % faster).
+// Otherwise 4 waves when two workgroups fit a CU's LDS, else one workgroup of 8, which keeps two waves
+// on every SIMD.
 inline int search_waves_for(int S16, int D, int row_words, int rows)
 {
-    if (D == 4 * kChunksPerRow && rows >= kSearchRowsLarge &&
+    if (rows >= kSearchRowsLarge && kLdsPerCu / search_lds_bytes(S16, D, row_words, 4, rows) < 4 &&
         search_lds_bytes(S16, D, row_words, 16, rows) <= kLdsPerCu)
         return 16;
     return 2 * search_lds_bytes(S16, D, row_words, 4, rows) > kLdsPerCu ? 8 : 4;
@@ -81,7 +83,7 @@ inline int search_waves_for(int S16, int D, int row_words, int rows)
 inline int search_rows_for(int T, int S16, int D, int row_words)
 {
     if (T >= kSearchRowsSwitchHuge && D == 4 * kChunksPerRow &&
-        search_lds_bytes(S16, D, row_words, 16, kSearchRowsHuge) <= kLdsPerCu)
+        search_waves_for(S16, D, row_words, kSearchRowsHuge) == 16)
         return kSearchRowsHuge;
     if (T >= kSearchRowsSwitch &&
         (D == 4 * kChunksPerRow || 2 * search_lds_bytes(S16, D, row_words, 4, kSearchRowsLarge) <= kLdsPerCu))

@@ -392,9 +392,10 @@ __global__ __launch_bounds__(kThreads) void k_prepare_operands(Geometry g, Works
 
 }
 
-// kWaves: 16 for workgroups of 256 or 512 rows (one per CU, four waves on every SIMD); for 64-row
-// workgroups 4, or 8 when the A operands are so large (S > 256) that only one workgroup fits a CU: twice
-// the waves then share them and keep two waves on every SIMD.
+// kWaves: 4 (several workgroups per CU); 16 for workgroups of 256 or 512 rows whose tables would leave
+// room for fewer than four such workgroups (one per CU, four waves on every SIMD); 8 when the A operands
+// are so large (S > 256) that only one workgroup fits a CU and 16 waves do not: twice the waves then share
+// the tables and keep two waves on every SIMD.
 // This kernel is for rows of 128 elements (32 chunks: two rows per wave); k_search_flat below takes
 // every other head dimension.
 template <int kWaves, int kRows>
@@ -683,7 +684,9 @@ hipError_t launch_search(const Geometry &g, const WorkspaceOffsets &wo, const En
     if (err != hipSuccess)
         return err;
     if (device < 0 || device >= 64 || !raised[device]) {
-        const void *variants[8] = {reinterpret_cast<const void *>(k_search<4, kSearchRowsSmall>),
+        const void *variants[10] = {reinterpret_cast<const void *>(k_search_flat<16, kSearchRowsLarge>),
+                                    reinterpret_cast<const void *>(k_search<4, kSearchRowsSmall>),
+                                   reinterpret_cast<const void *>(k_search<4, kSearchRowsLarge>),
                                    reinterpret_cast<const void *>(k_search<8, kSearchRowsSmall>),
                                    reinterpret_cast<const void *>(k_search<8, kSearchRowsLarge>),
                                    reinterpret_cast<const void *>(k_search<16, kSearchRowsLarge>),
@@ -691,7 +694,7 @@ hipError_t launch_search(const Geometry &g, const WorkspaceOffsets &wo, const En
                                    reinterpret_cast<const void *>(k_search_flat<4, kSearchRowsSmall>),
                                    reinterpret_cast<const void *>(k_search_flat<4, kSearchRowsLarge>),
                                    reinterpret_cast<const void *>(k_search_flat<8, kSearchRowsSmall>)};
-        for (int i = 0; i < 8 && err == hipSuccess; ++i)
+        for (int i = 0; i < 10 && err == hipSuccess; ++i)
             err = hipFuncSetAttribute(variants[i], hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCu);
         if (err != hipSuccess)
             return err;
@@ -703,21 +706,23 @@ hipError_t launch_search(const Geometry &g, const WorkspaceOffsets &wo, const En
     const bool large = g.search_rows == kSearchRowsLarge;
 #define HQMQ_LAUNCH(KERNEL, W, R) hipLaunchKernelGGL((KERNEL<W, R>), grid, dim3(64 * W), lds, stream, g, wo, batch)
     if (full) {
-        // (256 rows with 4 waves cannot come up: tables that leave no room for 16 waves leave none for
-        // two workgroups of 4 either)
-        if (g.search_rows == kSearchRowsHuge)
+        if (g.search_rows == kSearchRowsHuge)  // only chosen together with 16 waves
             HQMQ_LAUNCH(k_search, 16, kSearchRowsHuge);
         else if (large && waves == 16)
             HQMQ_LAUNCH(k_search, 16, kSearchRowsLarge);
-        else if (large)
+        else if (large && waves == 8)
             HQMQ_LAUNCH(k_search, 8, kSearchRowsLarge);
+        else if (large)
+            HQMQ_LAUNCH(k_search, 4, kSearchRowsLarge);
         else if (waves == 8)
             HQMQ_LAUNCH(k_search, 8, kSearchRowsSmall);
         else
             HQMQ_LAUNCH(k_search, 4, kSearchRowsSmall);
     } else {
         // 256 rows per workgroup are only chosen when two 4-wave workgroups fit a CU
-        if (large)
+        if (large && waves == 16)
+            HQMQ_LAUNCH(k_search_flat, 16, kSearchRowsLarge);
+        else if (large)
             HQMQ_LAUNCH(k_search_flat, 4, kSearchRowsLarge);
         else if (waves == 8)
             HQMQ_LAUNCH(k_search_flat, 8, kSearchRowsSmall);
