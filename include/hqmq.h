@@ -307,6 +307,21 @@ int32_t hqmq_attend_lse(const hqmq_params *params, int32_t n_q_heads, const void
                         const hqmq_encoded *enc_v, uint64_t cap_v, const float *sec_v_dev, void *out_dev,
                         float *lse_dev, void *workspace_dev, uint64_t workspace_bytes, void *stream);
 
+/* hqmq_attend with a causal limit per query head, for steps that carry several query tokens (a few
+ * speculative or chunked positions riding along as extra query heads, see n_q_heads): query head hq
+ * sees only the first visible_dev[b][hq] cached tokens, t < visible (the paper's fused kernel applies
+ * the causal mask, App. F; with one query token per sequence the mask is empty).  Values above T mean
+ * T; a head that may see nothing gets zeros and lse = -infinity.
+ *   visible_dev  DEVICE, in, int32 [B][n_q_heads], 4-byte aligned, values >= 0.
+ *   lse_dev      DEVICE, out, fp32 [B][n_q_heads] as in hqmq_attend_lse, or NULL.
+ * Everything else, and the errors, as hqmq_attend (INVALID_ARG also for a null or misaligned
+ * visible_dev). */
+int32_t hqmq_attend_masked(const hqmq_params *params, int32_t n_q_heads, const void *q_dev, float scale,
+                           const hqmq_encoded *enc_k, uint64_t cap_k, const float *sec_k_dev,
+                           const hqmq_encoded *enc_v, uint64_t cap_v, const float *sec_v_dev,
+                           const int32_t *visible_dev, void *out_dev, float *lse_dev, void *workspace_dev,
+                           uint64_t workspace_bytes, void *stream);
+
 /* Workspace hqmq_attend needs for these params and n_q_heads, in bytes (0 if they are invalid). */
 uint64_t hqmq_attend_workspace_bytes(const hqmq_params *params, int32_t n_q_heads);
 

@@ -120,6 +120,9 @@ def _declare(L):
     L.hqo_attend_lse.restype = None
     L.hqo_attend_lse.argtypes = [_u16p, _f64p, _f64p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                  C.c_double, _u16p, _f64p, _f64p]
+    L.hqo_attend_masked.restype = None
+    L.hqo_attend_masked.argtypes = [_u16p, _f64p, _f64p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                    C.c_double, C.c_void_p, _u16p, _f64p, _f64p]
     L.hqo_decode.restype = None
     L.hqo_decode.argtypes = [_u32p, _u16p, _u32p, _u32p, _u16p, _f32p, C.c_int, C.c_int,
                              C.c_int, C.c_int, C.c_int, C.c_int, _u16p, C.c_void_p]
@@ -396,10 +399,12 @@ def decode64(codes, sigma, flags, row_off, outliers, sec, B, H, T, b_r, D=4 * NC
     return np.ascontiguousarray(out64.reshape(B, H, T, nc * 4)[..., :D])
 
 
-def attend(q_bits: np.ndarray, K64: np.ndarray, V64: np.ndarray, scale: float, want_lse: bool = False):
+def attend(q_bits: np.ndarray, K64: np.ndarray, V64: np.ndarray, scale: float, want_lse: bool = False,
+           visible=None):
     """Single-query attention (one token per sequence) over a reconstructed cache.
     q_bits: fp16 bit patterns [B, Hq, D]; K64, V64: fp64 [B, H, T, D]; returns (fp16 bits, fp64) and,
-    with want_lse, the natural log of the softmax denominator, fp64 [B, Hq]."""
+    with want_lse, the natural log of the softmax denominator, fp64 [B, Hq].  visible: optional int32
+    [B, Hq], query head hq sees only the tokens t < visible[b, hq] (causal limit)."""
     q_bits = np.ascontiguousarray(q_bits, np.uint16)
     K64 = np.ascontiguousarray(K64, np.float64)
     V64 = np.ascontiguousarray(V64, np.float64)
@@ -409,8 +414,10 @@ def attend(q_bits: np.ndarray, K64: np.ndarray, V64: np.ndarray, scale: float, w
     out16 = np.zeros((B, Hq, D), np.uint16)
     out64 = np.zeros((B, Hq, D))
     lse = np.zeros((B, Hq))
-    lib().hqo_attend_lse(q_bits.reshape(-1), K64.reshape(-1), V64.reshape(-1), B, Hq, H, T, D, float(scale),
-                         out16.reshape(-1), out64.reshape(-1), lse.reshape(-1))
+    vis = None if visible is None else np.ascontiguousarray(visible, np.int32).reshape(B, Hq)
+    lib().hqo_attend_masked(q_bits.reshape(-1), K64.reshape(-1), V64.reshape(-1), B, Hq, H, T, D, float(scale),
+                            None if vis is None else vis.ctypes.data, out16.reshape(-1), out64.reshape(-1),
+                            lse.reshape(-1))
     if want_lse:
         return out16, out64, lse
     return out16, out64

@@ -563,6 +563,9 @@ void hqo_decode64(const uint32_t *codes, const uint16_t *sigma16, const uint32_t
  * ---------------------------------------------------------------------------------- */
 void hqo_attend_lse(const uint16_t *q, const double *K, const double *V, int B, int Hq, int H, int T,
                     int D, double scale, uint16_t *out16, double *out64, double *lse64);
+void hqo_attend_masked(const uint16_t *q, const double *K, const double *V, int B, int Hq, int H, int T,
+                       int D, double scale, const int32_t *visible, uint16_t *out16, double *out64,
+                       double *lse64);
 
 void hqo_attend(const uint16_t *q, const double *K, const double *V, int B, int Hq, int H, int T,
                 int D, double scale, uint16_t *out16, double *out64)
@@ -573,14 +576,38 @@ void hqo_attend(const uint16_t *q, const double *K, const double *V, int B, int 
 void hqo_attend_lse(const uint16_t *q, const double *K, const double *V, int B, int Hq, int H, int T,
                     int D, double scale, uint16_t *out16, double *out64, double *lse64)
 {
+    hqo_attend_masked(q, K, V, B, Hq, H, T, D, scale, 0, out16, out64, lse64);
+}
+
+/* The same with a causal limit: query head hq of sequence b attends to the tokens t < visible[b*Hq + hq]
+ * only (App. F: the fused kernel masks causally); visible == NULL or a value >= T: all T tokens.  A head
+ * that sees no token has an empty softmax: output 0, lse = -infinity. */
+void hqo_attend_masked(const uint16_t *q, const double *K, const double *V, int B, int Hq, int H, int T_all,
+                       int D, double scale, const int32_t *visible, uint16_t *out16, double *out64,
+                       double *lse64)
+{
     int G = Hq / H;
-    double *p = (double *)malloc((size_t)T * sizeof(double));
+    double *p = (double *)malloc((size_t)(T_all > 0 ? T_all : 1) * sizeof(double));
     for (int b = 0; b < B; ++b)
         for (int hq = 0; hq < Hq; ++hq) {
             int h = hq / G;
-            const double *Kh = K + ((int64_t)b * H + h) * T * D;
-            const double *Vh = V + ((int64_t)b * H + h) * T * D;
+            const double *Kh = K + ((int64_t)b * H + h) * T_all * D;
+            const double *Vh = V + ((int64_t)b * H + h) * T_all * D;
             const uint16_t *qv = q + ((int64_t)b * Hq + hq) * D;
+            int T = T_all; /* tokens this head sees */
+            if (visible && visible[(int64_t)b * Hq + hq] < T_all)
+                T = visible[(int64_t)b * Hq + hq] < 0 ? 0 : visible[(int64_t)b * Hq + hq];
+            if (T == 0) {
+                if (lse64)
+                    lse64[(int64_t)b * Hq + hq] = -INFINITY;
+                for (int d = 0; d < D; ++d) {
+                    int64_t at = ((int64_t)b * Hq + hq) * D + d;
+                    if (out64)
+                        out64[at] = 0.0;
+                    out16[at] = 0;
+                }
+                continue;
+            }
             double m = -INFINITY;
             for (int t = 0; t < T; ++t) {
                 double s = 0.0;

@@ -18,6 +18,7 @@ from .binding import (  # noqa: F401
     alloc_workspace,
     hqmq_attend,
     hqmq_attend_lse,
+    hqmq_attend_masked,
     hqmq_attend_workspace_bytes,
     hqmq_build_codebooks,
     hqmq_decode,

@@ -107,6 +107,11 @@ def _load():
         lib.hqmq_attend_lse.argtypes = [C.POINTER(HqmqParams), C.c_int32, C.c_void_p, C.c_float, C.POINTER(_Encoded),
                                         C.c_uint64, C.c_void_p, C.POINTER(_Encoded), C.c_uint64, C.c_void_p,
                                         C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]
+        lib.hqmq_attend_masked.restype = C.c_int32
+        lib.hqmq_attend_masked.argtypes = [C.POINTER(HqmqParams), C.c_int32, C.c_void_p, C.c_float,
+                                           C.POINTER(_Encoded), C.c_uint64, C.c_void_p, C.POINTER(_Encoded),
+                                           C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                           C.c_uint64, C.c_void_p]
         lib.hqmq_attend_workspace_bytes.restype = C.c_uint64
         lib.hqmq_attend_workspace_bytes.argtypes = [C.POINTER(HqmqParams), C.c_int32]
         lib.hqmq_last_hip_error.restype = C.c_int32
@@ -414,3 +419,24 @@ def hqmq_attend_lse(params: HqmqParams, q: torch.Tensor, scale: float, enc_k: En
                                  out.data_ptr(), lse.data_ptr(), workspace.data_ptr(),
                                  workspace.numel() * workspace.element_size(), _stream_ptr(stream))
     _check(rc, "hqmq_attend_lse")
+
+
+def hqmq_attend_masked(params: HqmqParams, q: torch.Tensor, scale: float, enc_k: EncodedBuffers,
+                       sec_k: torch.Tensor, enc_v: EncodedBuffers, sec_v: torch.Tensor, visible: torch.Tensor,
+                       out: torch.Tensor, workspace: torch.Tensor, lse: torch.Tensor | None = None, stream=None) -> None:
+    """hqmq_attend with a causal limit per query head: visible is contiguous device int32 [B, n_q_heads],
+    head hq sees the cached tokens t < visible[b, hq].  lse as in hqmq_attend_lse, optional."""
+    _check_attend_args(params, q, out, sec_k, sec_v, workspace)
+    if visible.dtype != torch.int32 or not visible.is_cuda or not visible.is_contiguous() or \
+            tuple(visible.shape) != tuple(q.shape[:2]):
+        raise ValueError("visible must be contiguous device int32 [B, n_q_heads]")
+    if lse is not None and (lse.dtype != torch.float32 or not lse.is_cuda or not lse.is_contiguous() or
+                            tuple(lse.shape) != tuple(q.shape[:2])):
+        raise ValueError("lse must be contiguous device fp32 [B, n_q_heads]")
+    rc = _load().hqmq_attend_masked(C.byref(params), int(q.shape[1]), q.data_ptr(), float(scale),
+                                    C.byref(enc_k.as_struct()), enc_k.outlier_capacity, sec_k.data_ptr(),
+                                    C.byref(enc_v.as_struct()), enc_v.outlier_capacity, sec_v.data_ptr(),
+                                    visible.data_ptr(), out.data_ptr(), None if lse is None else lse.data_ptr(),
+                                    workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                    _stream_ptr(stream))
+    _check(rc, "hqmq_attend_masked")

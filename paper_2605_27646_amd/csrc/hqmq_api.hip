@@ -484,8 +484,8 @@ extern "C" uint64_t hqmq_attend_workspace_bytes(const hqmq_params *params, int32
 static int32_t attend_impl(const hqmq_params *params, int32_t n_q_heads, const void *q_dev,
                            float scale, const hqmq_encoded *enc_k, uint64_t cap_k,
                            const float *sec_k_dev, const hqmq_encoded *enc_v, uint64_t cap_v,
-                           const float *sec_v_dev, void *out_dev, float *lse_dev, void *workspace_dev,
-                           uint64_t workspace_bytes, void *stream)
+                           const float *sec_v_dev, void *out_dev, float *lse_dev, const int32_t *visible_dev,
+                           void *workspace_dev, uint64_t workspace_bytes, void *stream)
 {
     int32_t rc = check_attend(params, n_q_heads);
     if (rc != HQMQ_OK)
@@ -523,6 +523,7 @@ static int32_t attend_impl(const hqmq_params *params, int32_t n_q_heads, const v
     a.q = static_cast<const _Float16 *>(q_dev);
     a.out = static_cast<_Float16 *>(out_dev);
     a.lse = lse_dev;
+    a.visible = visible_dev;
     a.part_ml = reinterpret_cast<float *>(workspace_dev);
     a.part_acc = reinterpret_cast<float *>(static_cast<char *>(workspace_dev) + plan.ml_bytes);
     a.qscale = scale * 1.44269504088896340736f;
@@ -543,7 +544,7 @@ extern "C" int32_t hqmq_attend(const hqmq_params *params, int32_t n_q_heads, con
                                uint64_t workspace_bytes, void *stream)
 {
     return attend_impl(params, n_q_heads, q_dev, scale, enc_k, cap_k, sec_k_dev, enc_v, cap_v, sec_v_dev, out_dev,
-                       nullptr, workspace_dev, workspace_bytes, stream);
+                       nullptr, nullptr, workspace_dev, workspace_bytes, stream);
 }
 
 extern "C" int32_t hqmq_attend_lse(const hqmq_params *params, int32_t n_q_heads, const void *q_dev,
@@ -555,5 +556,17 @@ extern "C" int32_t hqmq_attend_lse(const hqmq_params *params, int32_t n_q_heads,
     if (!lse_dev || misaligned(lse_dev, 4))
         return HQMQ_ERR_INVALID_ARG;
     return attend_impl(params, n_q_heads, q_dev, scale, enc_k, cap_k, sec_k_dev, enc_v, cap_v, sec_v_dev, out_dev,
-                       lse_dev, workspace_dev, workspace_bytes, stream);
+                       lse_dev, nullptr, workspace_dev, workspace_bytes, stream);
+}
+
+extern "C" int32_t hqmq_attend_masked(const hqmq_params *params, int32_t n_q_heads, const void *q_dev,
+                                      float scale, const hqmq_encoded *enc_k, uint64_t cap_k,
+                                      const float *sec_k_dev, const hqmq_encoded *enc_v, uint64_t cap_v,
+                                      const float *sec_v_dev, const int32_t *visible_dev, void *out_dev,
+                                      float *lse_dev, void *workspace_dev, uint64_t workspace_bytes, void *stream)
+{
+    if (!visible_dev || misaligned(visible_dev, 4) || misaligned(lse_dev, 4))
+        return HQMQ_ERR_INVALID_ARG;
+    return attend_impl(params, n_q_heads, q_dev, scale, enc_k, cap_k, sec_k_dev, enc_v, cap_v, sec_v_dev, out_dev,
+                       lse_dev, visible_dev, workspace_dev, workspace_bytes, stream);
 }

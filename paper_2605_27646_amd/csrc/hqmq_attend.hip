@@ -146,6 +146,11 @@ __global__ __launch_bounds__(kAttThreads, 2) void k_attend_partial(Geometry g, A
     const int n16 = lane & 15, j4 = lane >> 4;
     const int n16_ = n16, j4_ = j4;
     const int G = a.G;
+    // tokens this lane's query head (n16) may see: all of them unless the caller limits it (a query
+    // token of a multi-token step sees the cache only up to its own position)
+    int vis = 0x7fffffff;
+    if (a.visible)
+        vis = (n16 < G) ? a.visible[((size_t)b * g.H + h) * G + n16] : 0;
     const uint32_t w = g.w, w_idx = g.w_idx;
     const uint32_t row_words = kNc == 32 ? w : (uint32_t)g.row_words;
     const int row_begin = split * a.rows_per_split;
@@ -394,7 +399,8 @@ __global__ __launch_bounds__(kAttThreads, 2) void k_attend_partial(Geometry g, A
             float mx = kNegBig;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                s4[i] = (4 * j4 + i < nrows) ? sc[i] * a.qscale : kNegBig;
+                const bool seen = 4 * j4 + i < nrows && t0 + wv * kStageRows + 4 * j4 + i < vis;
+                s4[i] = seen ? sc[i] * a.qscale : kNegBig;
                 mx = fmaxf(mx, s4[i]);
             }
             mx = fmaxf(mx, __shfl_xor(mx, 16));
@@ -420,7 +426,8 @@ __global__ __launch_bounds__(kAttThreads, 2) void k_attend_partial(Geometry g, A
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const float e = __builtin_amdgcn_exp2f(s4[i] - m_run);
-                pw[i] = (4 * j4 + i < nrows) ? e : 0.f;
+                const bool seen = 4 * j4 + i < nrows && t0 + wv * kStageRows + 4 * j4 + i < vis;
+                pw[i] = seen ? e : 0.f;
                 l_run += pw[i];
             }
             // P^T as the A operand of the value products, split into an fp16 pair
@@ -613,11 +620,13 @@ __global__ __launch_bounds__(kAttThreads) void k_attend_merge(AttendArgs a)
 #pragma unroll
         for (int jj = 0; jj < kMergeWays; ++jj)
             tot += sums[jj * (kMergeDims + 1) + tid];
-        a.out[head * a.D + d0 + tid] = (_Float16)(tot / lsum);
+        // a head that may see no token at all has an empty softmax: zeros
+        a.out[head * a.D + d0 + tid] = lsum > 0.f ? (_Float16)(tot / lsum) : (_Float16)0.f;
     }
     // log-sum-exp of the head's scores (the running maximum is kept in the log2 domain)
     if (a.lse && blockIdx.y == 0 && tid == 0)
-        a.lse[head] = (mx + __builtin_amdgcn_logf(lsum)) * 0.693147180559945309417f;
+        a.lse[head] = lsum > 0.f ? (mx + __builtin_amdgcn_logf(lsum)) * 0.693147180559945309417f
+                                 : -__builtin_inff();
 }
 
 AttendPlan plan_attend(const Geometry &g, int G)

@@ -182,6 +182,7 @@ struct AttendArgs {
     const _Float16 *q;     // [B][H * G][D]
     _Float16 *out;         // [B][H * G][D]
     float *lse;            // [B][H * G] natural-log sum of exp(score) over the cached tokens, or null
+    const int32_t *visible;  // [B][H * G] number of leading cached tokens each query head may see, or null (all)
     float *part_ml;        // [B * H * G][n_splits][2]: running maximum (log2 domain) and weight sum
     float *part_acc;       // [B * H * G][n_splits][128]: weighted value sum
     float qscale;          // softmax scale * log2(e), folded into the query

@@ -27,7 +27,7 @@ def lib():
 def test_library_exports_every_declared_symbol(lib):
     header = open(os.path.join(ROOT, "include", "hqmq.h")).read()
     declared = set(re.findall(r"^(?:int32_t|void|uint64_t)\s+(hqmq_\w+)\s*\(", header, re.M))
-    assert declared == {"hqmq_build_codebooks", "hqmq_sizes", "hqmq_encode", "hqmq_encode_timed", "hqmq_encode_batch", "hqmq_encode_given_thresholds", "hqmq_encode_batch_given_thresholds", "hqmq_thresholds", "hqmq_shard_median_pass", "hqmq_shard_median_region", "hqmq_decode", "hqmq_decode_batch", "hqmq_attend", "hqmq_attend_lse", "hqmq_attend_workspace_bytes", "hqmq_last_hip_error"}
+    assert declared == {"hqmq_build_codebooks", "hqmq_sizes", "hqmq_encode", "hqmq_encode_timed", "hqmq_encode_batch", "hqmq_encode_given_thresholds", "hqmq_encode_batch_given_thresholds", "hqmq_thresholds", "hqmq_shard_median_pass", "hqmq_shard_median_region", "hqmq_decode", "hqmq_decode_batch", "hqmq_attend", "hqmq_attend_lse", "hqmq_attend_masked", "hqmq_attend_workspace_bytes", "hqmq_last_hip_error"}
     for name in declared:
         assert hasattr(lib, name), name
 
@@ -185,6 +185,13 @@ def test_encode_decode_reject_bad_arguments_without_touching_the_gpu(lib):
     assert call(ws_ptr=0x4010) == -1                  # workspace not 256-byte aligned
     assert call(ws_bytes=need - 1) == -3
     assert call(params=_params(D=32)) == -2          # the attention kernel takes heads of 64, 96 or 128 elements
+    am = lib.hqmq_attend_masked
+    assert am(C.byref(p), 4 * p.H, 0x1000, 0.1, C.byref(good), 0, 0x1000, C.byref(good), 0, 0x1000, None, 0x2000, None,
+              0x4000, need, None) == -1           # no visible array
+    assert am(C.byref(p), 4 * p.H, 0x1000, 0.1, C.byref(good), 0, 0x1000, C.byref(good), 0, 0x1000, 0x3002, 0x2000, None,
+              0x4000, need, None) == -1           # misaligned visible array
+    assert am(C.byref(p), 4 * p.H, 0x1000, 0.1, C.byref(good), 0, 0x1000, C.byref(good), 0, 0x1000, 0x3000, 0x2000, None,
+              0x4000, need - 1, None) == -3
     al = lib.hqmq_attend_lse
     assert al(C.byref(p), 4 * p.H, 0x1000, 0.1, C.byref(good), 0, 0x1000, C.byref(good), 0, 0x1000, 0x2000, None,
               0x4000, need, None) == -1           # no lse buffer

@@ -402,3 +402,60 @@ def test_attend_lse_combines_a_prefill_tensor_and_appended_tokens():
     vmax_q = np.repeat(np.abs(V64).max(axis=(2, 3)), Hq // H_, axis=1)[:, :, None]
     err = np.abs(merged - want)
     assert (err <= 2.0 ** -10 * np.abs(want) + 2 * ATT_TOL * vmax_q).all(), float(err.max())
+
+
+@pytest.mark.parametrize("D,T,n_tok,G", [(128, 3001, 4, 4), (64, 700, 16, 1), (96, 130, 2, 7)])
+def test_attend_causal_limit_for_several_query_tokens(D, T, n_tok, G):
+    """A step with n_tok query tokens per sequence riding as extra query heads of their kv head: token i
+    sees the cache up to its own position, T - n_tok + i + 1 tokens."""
+    B, H, S, b_r = 2, 2, 24, 4
+    k, v = _tensors(B, H, T, seed=T + n_tok, D=D)
+    sec_k, sec_v = _secs(9, H, S)
+    gk = gpu_encode(k.to(DEV), sec_k.to(DEV), b_r)
+    gv = gpu_encode(v.to(DEV), sec_v.to(DEV), b_r)
+    Hq = H * n_tok * G                                   # laid out [H][token][head of the group]
+    q = _query(B, Hq, seed=3 * T, gain=1.5, D=D)
+    vis = np.zeros((B, H, n_tok, G), np.int32)
+    vis[:] = (T - n_tok + 1 + np.arange(n_tok))[None, None, :, None]
+    vis = vis.reshape(B, Hq)
+    scale = 1 / math.sqrt(D)
+    K64 = _decoded(gk, sec_k.numpy(), B, H, T, b_r, D)
+    V64 = _decoded(gv, sec_v.numpy(), B, H, T, b_r, D)
+    _, want, lse_want = oracle.attend(_bits(q), K64, V64, scale, want_lse=True, visible=vis)
+    q_dev = q.to(DEV)
+    out = torch.full_like(q_dev, float("nan"))
+    lse = torch.full((B, Hq), float("nan"), dtype=torch.float32, device=DEV)
+    ws = torch.empty(hq.hqmq_attend_workspace_bytes(gk.params, Hq), dtype=torch.uint8, device=DEV)
+    hq.hqmq_attend_masked(gk.params, q_dev, scale, gk.bufs, sec_k.to(DEV), gv.bufs, sec_v.to(DEV),
+                          torch.from_numpy(vis).to(DEV), out, ws, lse)
+    torch.cuda.synchronize()
+    _check(out.cpu().numpy().astype(np.float64), want, V64, Hq)
+    assert np.abs(lse.cpu().numpy() - lse_want).max() < 2e-5 * max(1.0, np.abs(lse_want).max())
+
+
+def test_attend_causal_limit_edge_values():
+    """Limits of 0 (sees nothing: zeros, lse = -inf), 1, exactly T, beyond T, and limits that end inside a
+    tile or exactly on a split boundary."""
+    B, H, T, S, b_r, Hq = 1, 1, 20011, 16, 6, 16
+    k, v = _tensors(B, H, T, seed=31)
+    sec_k, sec_v = _secs(2, H, S)
+    gk = gpu_encode(k.to(DEV), sec_k.to(DEV), b_r)
+    gv = gpu_encode(v.to(DEV), sec_v.to(DEV), b_r)
+    q = _query(B, Hq, seed=32, gain=2.0)
+    vis = np.array([[0, 1, 2, 15, 16, 17, 63, 64, 65, 1024, 9999, 10048, T - 1, T, T + 5, 2 ** 31 - 1]], np.int32)
+    scale = 1 / math.sqrt(128)
+    K64 = _decoded(gk, sec_k.numpy(), B, H, T, b_r)
+    V64 = _decoded(gv, sec_v.numpy(), B, H, T, b_r)
+    _, want, lse_want = oracle.attend(_bits(q), K64, V64, scale, want_lse=True, visible=vis)
+    q_dev = q.to(DEV)
+    out = torch.full_like(q_dev, float("nan"))
+    lse = torch.full((B, Hq), float("nan"), dtype=torch.float32, device=DEV)
+    ws = torch.empty(hq.hqmq_attend_workspace_bytes(gk.params, Hq), dtype=torch.uint8, device=DEV)
+    hq.hqmq_attend_masked(gk.params, q_dev, scale, gk.bufs, sec_k.to(DEV), gv.bufs, sec_v.to(DEV),
+                          torch.from_numpy(vis).to(DEV), out, ws, lse)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    _check(got, want, V64, Hq)
+    assert not got[0, 0].any() and lse[0, 0].item() == -math.inf
+    fin = np.isfinite(lse_want)
+    assert np.abs(lse.cpu().numpy()[fin] - lse_want[fin]).max() < 2e-5 * np.abs(lse_want[fin]).max()

@@ -588,6 +588,28 @@ def test_attend_lse_against_scipy_and_the_segment_merge_identity():
     assert np.allclose(L, lse, atol=1e-12) and np.allclose(merged, o, atol=1e-12)
 
 
+def test_attend_causal_limit_equals_attention_over_the_truncated_cache():
+    """Query head hq with visible = v must equal plain attention over the first v tokens; v = 0 gives zeros
+    and lse = -inf, v >= T the unmasked result."""
+    rng = np.random.default_rng(54)
+    B, Hq, H, T, D = 2, 6, 2, 40, 64
+    q = rng.standard_normal((B, Hq, D)).astype(np.float16).view(np.uint16)
+    K = rng.standard_normal((B, H, T, D))
+    V = rng.standard_normal((B, H, T, D))
+    vis = np.array([[0, 1, 7, 39, 40, 1000], [40, 3, 0, 25, 12, 41]], np.int32)
+    _, o, lse = oracle.attend(q, K, V, 0.3, want_lse=True, visible=vis)
+    for b in range(B):
+        for hq_ in range(Hq):
+            v = min(int(vis[b, hq_]), T)
+            if v == 0:
+                assert not o[b, hq_].any() and lse[b, hq_] == -np.inf
+                continue
+            h = hq_ // (Hq // H)
+            _, o1, l1 = oracle.attend(q[b:b + 1, hq_:hq_ + 1], K[b:b + 1, h:h + 1, :v], V[b:b + 1, h:h + 1, :v], 0.3,
+                                      want_lse=True)
+            assert np.array_equal(o[b, hq_], o1[0, 0]) and lse[b, hq_] == l1[0, 0]
+
+
 def test_attend_invariants():
     rng = np.random.default_rng(51)
     B, Hq, H, T, D = 1, 4, 1, 50, 128
