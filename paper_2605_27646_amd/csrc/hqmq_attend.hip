@@ -45,6 +45,7 @@ constexpr float kNegBig = -1.0e30f;                 // "no row seen yet" (finite
 constexpr int kRedStride = 2 + 128;                 // one partial state: maximum, sum, 128 weighted values
 constexpr int kAttendTargetBlocks = 512;            // two resident workgroups per compute unit
 constexpr uint32_t kHalfOfMaxHalf = 0x77ffu;        // 32752 = 65504 / 2 as fp16 bits
+constexpr float kWeightScale = 16384.f;             // softmax weights enter the value products times 2^14
 
 static_assert(kAttendTile == kAttWaves * kStageRows, "tile = rows of all waves");
 static_assert(kStageWords % 4 == 0 && kSideWords % 4 == 0, "16-byte LDS reads of the per-row words");
@@ -430,13 +431,21 @@ __global__ __launch_bounds__(kAttThreads, 2) void k_attend_partial(Geometry g, A
                 pw[i] = seen ? e : 0.f;
                 l_run += pw[i];
             }
-            // P^T as the A operand of the value products, split into an fp16 pair
-            p_hi = make_uint2(pack_half2(pw[0], pw[1]), pack_half2(pw[2], pw[3]));
+            // P^T as the A operand of the value products, split into an fp16 pair.  The weights (<= 1)
+            // are scaled by 2^14 first: unscaled, the remainder part of every weight below 1/8 and both
+            // parts of a weight below 2^-14 would be fp16 subnormals, i.e. carry an absolute error of
+            // 2^-25 however small the weight, which adds up over a long cache.  The accumulators hold
+            // 2^14 times the weighted sums; the factor is taken out when the partial sums are written.
             {
+                float ps[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    ps[i] = pw[i] * kWeightScale;
+                p_hi = make_uint2(pack_half2(ps[0], ps[1]), pack_half2(ps[2], ps[3]));
                 const half4_t hv = __builtin_bit_cast(half4_t, p_hi);
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
-                    ph[i] = pw[i] - (float)hv[i];
+                    ph[i] = ps[i] - (float)hv[i];
                 p_lo = make_uint2(pack_half2(ph[0], ph[1]), pack_half2(ph[2], ph[3]));
             }
         }
@@ -547,7 +556,7 @@ __global__ __launch_bounds__(kAttThreads, 2) void k_attend_partial(Geometry g, A
             oo = fmaf(src[2 + d], c, oo);
         }
         const size_t head = (size_t)seg * G + gq;  // = b * (H G) + h * G + gq
-        a.part_acc[(head * a.n_splits + split) * 128 + d] = oo;
+        a.part_acc[(head * a.n_splits + split) * 128 + d] = oo * (1.0f / kWeightScale);
         if (d == 0) {
             a.part_ml[(head * a.n_splits + split) * 2 + 0] = mm;
             a.part_ml[(head * a.n_splits + split) * 2 + 1] = ll;
