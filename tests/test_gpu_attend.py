@@ -114,7 +114,7 @@ def _check(got, want64, K, V, q, scale, visible=None, lse=None, lse_want=None):
     err = np.abs(got - want64)
     assert np.isfinite(got).all()
     assert (err <= bound).all(), (float(err.max()), np.argwhere(err > bound)[:5], err[err > bound][:5], bound[err > bound][:5])
-    rel = float((err / np.maximum(A, 1e-30)).max())
+    rel = float((err / np.maximum(A, 1e-3 * A.max() + 1e-30)).max())   # reported only; tiny outputs sit on the fp16 floor
     print({"max_err_over_weighted_abs_v": rel, "k_may_flip": int((K.slack > 0).sum()), "v_may_flip": int((V.slack > 0).sum())},
           flush=True)
     if lse is not None:
