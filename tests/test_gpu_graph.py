@@ -31,24 +31,31 @@ def test_graph_replays_match_eager():
     q = torch.randn(B, H * G, 128, generator=torch.Generator().manual_seed(3)).to(torch.float16).to(DEV)
     o = torch.empty_like(q)
     aws = torch.empty(hq.hqmq_attend_workspace_bytes(params, H * G), dtype=torch.uint8, device=DEV)
+    o2 = torch.empty_like(q)
+    lse = torch.empty(B, H * G, dtype=torch.float32, device=DEV)
+    vis = torch.randint(0, T + 1, (B, H * G), generator=torch.Generator().manual_seed(4), dtype=torch.int32).to(DEV)
+    aws2 = torch.empty_like(aws)
 
     def path():
         hq.hqmq_encode_batch(batch)
         hq.hqmq_decode_batch(dec)
         hq.hqmq_attend(params, q, 0.09, ek, sec_k, ev, sec_v, o, aws)
+        hq.hqmq_attend_masked(params, q, 0.09, ek, sec_k, ev, sec_v, vis, o2, aws2, lse)
 
     def snapshot():
         torch.cuda.synchronize()
         return [t.clone() for t in (ek.codes, ek.flags, ek.row_off, ek.n_outliers, ev.codes, ok.view(torch.int16),
-                                    ov.view(torch.int16), o.view(torch.int16))]
+                                    ov.view(torch.int16), o.view(torch.int16), o2.view(torch.int16),
+                                    lse.view(torch.int32))]
 
     def scrub():
         for t in (ek.codes, ek.flags, ek.row_off, ev.codes, ek.n_outliers):
             t.fill_(-1)
-        for t in (ok, ov, o):
+        for t in (ok, ov, o, o2, lse):
             t.fill_(float("nan"))
         ws.fill_(0x77)
         aws.fill_(0x77)
+        aws2.fill_(0x77)
 
     path()
     want = snapshot()
