@@ -55,6 +55,7 @@ static Geometry make_geometry(const hqmq_params *p)
     g.T = p->T;
     g.D = p->D;
     g.n_c = (p->D + 3) / 4;
+    g.n_c_magic = g.n_c >= 2 ? (uint32_t)((1ull << 32) / (uint64_t)g.n_c + 1ull) : 0u;
     g.vec_ok = (p->D % 4 == 0 && p->stride_b % 4 == 0 && p->stride_h % 4 == 0 && p->stride_t % 4 == 0) ? 1 : 0;
     g.S = p->S;
     g.S16 = (p->S + 15) / 16;

@@ -37,6 +37,7 @@ struct Geometry {
     int32_t B, H, T;
     int32_t D;            // elements per row (head dimension), 1..128
     int32_t n_c;          // ceil(D / 4): chunks per row; a last partial chunk is zero-padded
+    uint32_t n_c_magic;   // 2^32 / n_c + 1 (n_c >= 2): __umulhi(q, n_c_magic) == q / n_c for every q < 2^27
     int32_t row_words;    // ceil(n_c * w / 32): 32-bit words of one packed row (w when D = 128)
     int32_t vec_ok;       // D and the strides are multiples of 4: every chunk is one aligned 8-byte access
     int32_t S;            // secondaries per head
@@ -239,6 +240,12 @@ __device__ __forceinline__ half4_t load_row_chunk(const _Float16 *row, int c, co
         }
     }
     return v;
+}
+
+// q / n_c for a flat chunk index q < 2^27 (one chunk per row: the multiplier would not fit 32 bits).
+__device__ __forceinline__ int row_of_chunk(int q, const Geometry &g)
+{
+    return g.n_c == 1 ? q : (int)__umulhi((uint32_t)q, g.n_c_magic);
 }
 
 __device__ __forceinline__ unsigned long long key_of(double r2)

@@ -595,7 +595,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_search_flat(Geometry g, Workspa
 
     // ---- pass 1: flags and row maxima ---------------------------------------------------------------
     for (int q = tid; q < nchunks; q += kThreadsS) {
-        const int r = q / g.n_c, c = q - r * g.n_c;
+        const int r = row_of_chunk(q, g), c = q - r * g.n_c;
         const double r2 = chunk_norm2(load_row_chunk<false>(base + (int64_t)r * g.st, c, g));
         if (r2 > thr)
             atomicOr(&fword[r], 1u << c);
@@ -621,7 +621,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_search_flat(Geometry g, Workspa
     for (int q0 = wv * 64; q0 < nchunks; q0 += kThreadsS) {  // wave-uniform trip count
         const int q = q0 + lane;
         const bool valid = q < nchunks;
-        const int r = valid ? q / g.n_c : 0, c = valid ? q - r * g.n_c : 0;
+        const int r = valid ? row_of_chunk(q, g) : 0, c = valid ? q - r * g.n_c : 0;
         const half4_t xv = valid ? load_row_chunk<false>(base + (int64_t)r * g.st, c, g) : half4_t{0, 0, 0, 0};
         const double r2 = chunk_norm2(xv);
         const bool flagged = valid && (r2 > thr);
