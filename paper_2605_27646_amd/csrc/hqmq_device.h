@@ -12,7 +12,7 @@ namespace hqmq {
 constexpr int kChunksPerRow = 32;    // chunks of a row of D = 128 elements, and the most a row may have
 constexpr int kSearchRowsSmall = 64;   // rows per search workgroup = granularity of the outlier scan:
 constexpr int kSearchRowsLarge = 256;  // 64 for short segments (more workgroups), 256 from 2048 rows on,
-constexpr int kSearchRowsHuge = 512;   // 512 from 4096 rows on (rows of 128 elements, 16-wave workgroups)
+constexpr int kSearchRowsHuge = 512;   // 512 from 4096 rows on (16-wave workgroups)
 constexpr int kSearchRowsSwitch = 2048;
 constexpr int kSearchRowsSwitchHuge = 4096;
 constexpr int kThreads = 256;        // default workgroup: 4 wave64
@@ -83,8 +83,7 @@ inline int search_waves_for(int S16, int D, int row_words, int rows)
 // often), as long as the workgroups that go with them fit a CU; 64 otherwise.
 inline int search_rows_for(int T, int S16, int D, int row_words)
 {
-    if (T >= kSearchRowsSwitchHuge && D == 4 * kChunksPerRow &&
-        search_waves_for(S16, D, row_words, kSearchRowsHuge) == 16)
+    if (T >= kSearchRowsSwitchHuge && search_waves_for(S16, D, row_words, kSearchRowsHuge) == 16)
         return kSearchRowsHuge;
     if (T >= kSearchRowsSwitch &&
         (D == 4 * kChunksPerRow || 2 * search_lds_bytes(S16, D, row_words, 4, kSearchRowsLarge) <= kLdsPerCu))

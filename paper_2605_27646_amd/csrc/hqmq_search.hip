@@ -684,7 +684,8 @@ hipError_t launch_search(const Geometry &g, const WorkspaceOffsets &wo, const En
     if (err != hipSuccess)
         return err;
     if (device < 0 || device >= 64 || !raised[device]) {
-        const void *variants[10] = {reinterpret_cast<const void *>(k_search_flat<16, kSearchRowsLarge>),
+        const void *variants[11] = {reinterpret_cast<const void *>(k_search_flat<16, kSearchRowsLarge>),
+                                    reinterpret_cast<const void *>(k_search_flat<16, kSearchRowsHuge>),
                                     reinterpret_cast<const void *>(k_search<4, kSearchRowsSmall>),
                                    reinterpret_cast<const void *>(k_search<4, kSearchRowsLarge>),
                                    reinterpret_cast<const void *>(k_search<8, kSearchRowsSmall>),
@@ -694,7 +695,7 @@ hipError_t launch_search(const Geometry &g, const WorkspaceOffsets &wo, const En
                                    reinterpret_cast<const void *>(k_search_flat<4, kSearchRowsSmall>),
                                    reinterpret_cast<const void *>(k_search_flat<4, kSearchRowsLarge>),
                                    reinterpret_cast<const void *>(k_search_flat<8, kSearchRowsSmall>)};
-        for (int i = 0; i < 10 && err == hipSuccess; ++i)
+        for (int i = 0; i < 11 && err == hipSuccess; ++i)
             err = hipFuncSetAttribute(variants[i], hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCu);
         if (err != hipSuccess)
             return err;
@@ -720,7 +721,9 @@ hipError_t launch_search(const Geometry &g, const WorkspaceOffsets &wo, const En
             HQMQ_LAUNCH(k_search, 4, kSearchRowsSmall);
     } else {
         // 256 rows per workgroup are only chosen when two 4-wave workgroups fit a CU
-        if (large && waves == 16)
+        if (g.search_rows == kSearchRowsHuge)  // only chosen together with 16 waves
+            HQMQ_LAUNCH(k_search_flat, 16, kSearchRowsHuge);
+        else if (large && waves == 16)
             HQMQ_LAUNCH(k_search_flat, 16, kSearchRowsLarge);
         else if (large)
             HQMQ_LAUNCH(k_search_flat, 4, kSearchRowsLarge);
