@@ -179,9 +179,10 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(Geometry g, DecodeBatch 
         const uint32_t rq = code >> w_idx;
         uint32_t p_off, s_off;  // byte offsets of P_p and q_s in their LDS tables
         if (kPow2) {
-            // code = r_q : p : s as bit fields; p has 5 bits (24 S <= 2^w_idx < 48 S)
-            p_off = ((code >> g.log2_S) & 31u) << 4;
-            s_off = (code << 4) & (((uint32_t)g.S - 1u) << 4);
+            // code = r_q : p : s as bit fields; p has 5 bits (24 S <= 2^w_idx < 48 S); one bit-field
+            // extract each, so that the shift by 4 fuses with the table's base address
+            p_off = __builtin_amdgcn_ubfe(code, (uint32_t)g.log2_S, 5u) << 4;
+            s_off = __builtin_amdgcn_ubfe(code, 0u, (uint32_t)g.log2_S) << 4;
         } else {
             // p = k / S by a biased reciprocal, exact for k < 48 S (see Geometry::inv_S)
             const uint32_t k = code & idx_mask;
