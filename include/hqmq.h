@@ -227,7 +227,8 @@ int32_t hqmq_thresholds(const hqmq_params *params, const void *workspace_dev, in
  *                          and in every pass; < 2^32 (else UNSUPPORTED), >= this shard's own count.
  *   pass                   0..5 a counting pass, 6 the finish.  Passes must run in order; the summed
  *                          histogram of pass p must be in place before pass p + 1 is enqueued.
- *   x_dev                  DEVICE, this shard's slice, as for hqmq_encode (not read by pass 6).
+ *   x_dev                  DEVICE, this shard's slice, as for hqmq_encode (not read by pass 6, where it
+ *                          may be NULL).
  *   workspace_dev          DEVICE, 256-byte aligned, >= hqmq_sizes(params).workspace_bytes; holds the
  *                          select's state between the calls, so nothing else may use it meanwhile.
  * hqmq_shard_median_region: HOST function; byte offset inside the workspace and number of uint32

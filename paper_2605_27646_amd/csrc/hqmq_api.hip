@@ -374,7 +374,9 @@ extern "C" int32_t hqmq_shard_median_pass(const hqmq_params *params, uint64_t to
     int32_t rc = check_params(params);
     if (rc != HQMQ_OK)
         return rc;
-    if (pass < 0 || pass > 6 || !x_dev || !workspace_dev || misaligned(x_dev, 16) || misaligned(workspace_dev, 256))
+    if (pass < 0 || pass > 6 || !workspace_dev || misaligned(workspace_dev, 256))
+        return HQMQ_ERR_INVALID_ARG;
+    if (pass < 6 && (!x_dev || misaligned(x_dev, 16)))  // the finish reads no rows
         return HQMQ_ERR_INVALID_ARG;
     if (params->flags & HQMQ_FLAG_NO_OUTLIERS)
         return HQMQ_ERR_INVALID_ARG;
