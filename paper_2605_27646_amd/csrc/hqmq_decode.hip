@@ -3,7 +3,7 @@
 //
 // HBM-bound: per chunk it reads w/8 bytes of code (+ 1/8 flag, 1/16 scale, 1/8 offset) and
 // writes 8 bytes of fp16.  The kernel is shaped like a streaming copy:
-//   * small one-shot workgroups (4 wave64, 64 rows, ~14 KiB of LDS) launched in row order: the
+//   * small one-shot workgroups (4 wave64, 64 or 128 rows, ~14 KiB of LDS) launched in row order: the
 //     hardware dispatcher hands the next rows to whichever CU frees up, so the set of rows in
 //     flight is a compact window moving front to back through the tensor (good DRAM page
 //     locality, no tail from a static partition), and 8 workgroups per CU overlap one another's
@@ -11,8 +11,9 @@
 //   * a wave takes 16 consecutive rows: their code words, flag words, scales and outlier offsets
 //     arrive with a few fully coalesced loads and are re-distributed through LDS; every lane then
 //     owns two adjacent chunks of a row, i.e. one 16-byte store per lane and 1 KiB contiguous per
-//     wave store (rows of 128 elements: 16 such pairs per row, 4 rows per wave store; rows of 96 or
-//     64 elements have 12 or 8 pairs and the wave's 16 rows take 3 or 2 stores);
+//     wave store (rows of 128 elements: 16 such pairs per row, 4 rows per wave store; rows of 96
+//     elements have 12 pairs and the wave's 16 rows take 3 stores; rows of 64 elements have 8 pairs and a
+//     wave takes 32 rows, 4 stores again);
 //   * the head's S secondaries (S*16 bytes) and the 24 primaries sit in LDS; the Hamilton product
 //     is taken per chunk (16 FMA), which keeps the workgroup small enough to be one-shot;
 //   * the outlier payloads of a wave's rows are one contiguous window of the list: requested with
@@ -25,27 +26,39 @@ namespace {
 
 constexpr int kDecThreads = 256;
 constexpr int kDecWaves = kDecThreads / 64;
-constexpr int kStageRows = 16;                      // rows per wave
-constexpr int kDecRows = kStageRows * kDecWaves;    // rows per workgroup
-constexpr int kMaxW = 24;                           // w_idx <= 14 (S <= 512), b_r <= 8  ->  w <= 22
-constexpr int kStageWords = kStageRows * kMaxW + 2; // + 2 words of padding for the 3-word window
-constexpr int kPaySlots = 64;                       // outlier payloads of a wave's 16 rows kept in LDS
-constexpr int kStagePerWave = kStageWords + 3 * kStageRows + 2 * kPaySlots;
-constexpr int kLoadsPerLane = (kStageRows * kMaxW + 63) / 64;  // 6 code words per lane
+constexpr int kPaySlots = 64;                       // outlier payloads of a wave's rows kept in LDS
+constexpr int kGeneralRows = 64;                    // rows per workgroup of the general-row kernel
+
+// Sizes of one variant of the tuned kernel: kPairs chunk pairs per row, kRowsW rows per wave.
+template <int kPairs, int kRowsW>
+struct DecodeShape {
+    static constexpr int kRows = kRowsW * kDecWaves;                 // rows per workgroup
+    // code words of a row at most: 2 kPairs chunks of w <= 22 bits (w_idx <= 14 for S <= 512, b_r <= 8)
+    static constexpr int kMaxRowWords = kPairs == 16 ? 24 : (2 * kPairs * 22 + 31) / 32;
+    static constexpr int kLoadsPerLane = (kRowsW * kMaxRowWords + 63) / 64;  // code words per lane
+    // every lane parks all its words: whole multiples of 64, + 2 words of padding for the 3-word window
+    static constexpr int kStageWords = 64 * kLoadsPerLane + 2;
+    static constexpr int kStagePerWave = kStageWords + 3 * kRowsW + 2 * kPaySlots;
+    static constexpr int kSubs = kRowsW * kPairs / 64;               // stores of 64 lanes x 16 bytes per wave
+    static_assert((kRowsW * kPairs) % 64 == 0, "a wave's rows must fill whole 64-lane stores");
+    static_assert(kRowsW <= 64, "one lane per row for the flag word, scale and offset");
+};
 
 }  // namespace
 
-// grid = (ceil(T / 64), B*H, tensors), block = 256.
+// grid = (ceil(T / rows per workgroup), B*H, tensors), block = 256.
 // dynamic LDS: prim [48][4] f32 | staging [4 waves][kStagePerWave] u32 | secl [S][4] f32
 // (the tables with compile-time sizes first, so that their LDS addresses are immediates)
 // blockIdx.z selects the tensor of a batch (all of one shape); the descriptors travel as kernel
 // arguments, so a batch needs no device-side table.
-// kPairs: chunk pairs (8 elements) per row: 16, 12 or 8 for D = 128, 96, 64.
-template <bool kPow2, int kPairs>
+// kPairs: chunk pairs (8 elements) per row: 16, 12 or 8 for D = 128, 96, 64; kStageRows: rows per wave
+// (16; 32 for the short rows, so that a wave's fixed work is spread over as many bytes).
+template <bool kPow2, int kPairs, int kStageRows>
 __global__ __launch_bounds__(kDecThreads) void k_decode(Geometry g, DecodeBatch batch)
 {
-    static_assert((kStageRows * kPairs) % 64 == 0, "a wave's rows must fill whole 64-lane stores");
-    constexpr int kSubs = kStageRows * kPairs / 64;  // stores of 64 lanes x 16 bytes per wave
+    typedef DecodeShape<kPairs, kStageRows> Shape;
+    constexpr int kSubs = Shape::kSubs, kDecRows = Shape::kRows, kStageWords = Shape::kStageWords;
+    constexpr int kStagePerWave = Shape::kStagePerWave, kLoadsPerLane = Shape::kLoadsPerLane;
     const DecodeTensor &dt = batch.t[blockIdx.z];
     EncodedPtrs enc;
     enc.codes = dt.codes;
@@ -336,8 +349,8 @@ __global__ __launch_bounds__(kDecThreads) void k_decode_rows(Geometry g, DecodeB
     const uint32_t w = g.w, w_idx = g.w_idx;
     const uint32_t bitpos = (uint32_t)c * w, i0 = bitpos >> 5, sh = bitpos & 31;
     const uint32_t code_mask = (1u << w) - 1u, idx_mask = (1u << w_idx) - 1u;
-    for (int pass = 0; pass < kDecRows / 8; ++pass) {
-        const int t = blockIdx.x * kDecRows + pass * 8 + rsub;
+    for (int pass = 0; pass < kGeneralRows / 8; ++pass) {
+        const int t = blockIdx.x * kGeneralRows + pass * 8 + rsub;
         if (t >= g.T)
             break;  // later passes lie further past the end
         const int64_t R = (int64_t)seg * g.T + t;
@@ -395,39 +408,36 @@ __global__ __launch_bounds__(kDecThreads) void k_decode_rows(Geometry g, DecodeB
     }
 }
 
+template <int kPairs, int kRowsW>
+static void launch_tuned(const Geometry &g, const DecodeBatch &batch, int n_tensors, hipStream_t stream)
+{
+    typedef DecodeShape<kPairs, kRowsW> Shape;
+    const size_t lds = ((size_t)g.S * 4 + 48 * 4) * sizeof(float) + (size_t)kDecWaves * Shape::kStagePerWave * 4;
+    dim3 grid((unsigned)((g.T + Shape::kRows - 1) / Shape::kRows), (unsigned)(g.B * g.H), (unsigned)n_tensors);
+    if ((g.S & (g.S - 1)) == 0)
+        hipLaunchKernelGGL((k_decode<true, kPairs, kRowsW>), grid, dim3(kDecThreads), lds, stream, g, batch);
+    else
+        hipLaunchKernelGGL((k_decode<false, kPairs, kRowsW>), grid, dim3(kDecThreads), lds, stream, g, batch);
+}
+
 hipError_t launch_decode(const Geometry &g, const DecodeBatch &batch, int n_tensors, hipStream_t stream)
 {
-    const size_t lds = ((size_t)g.S * 4 + 48 * 4) * sizeof(float) + (size_t)kDecWaves * kStagePerWave * 4;
-    dim3 grid((unsigned)((g.T + kDecRows - 1) / kDecRows), (unsigned)(g.B * g.H), (unsigned)n_tensors);
     // rows of 128, 96 or 64 elements whose strides keep every 16-byte store aligned take the tuned kernel
     const bool aligned16 = g.sb % 8 == 0 && g.sh % 8 == 0 && g.st % 8 == 0;
-    const bool pow2 = (g.S & (g.S - 1)) == 0;
-    if (aligned16 && (g.D == 96 || g.D == 64)) {
-        if (g.D == 96) {
-            if (pow2)
-                hipLaunchKernelGGL((k_decode<true, 12>), grid, dim3(kDecThreads), lds, stream, g, batch);
-            else
-                hipLaunchKernelGGL((k_decode<false, 12>), grid, dim3(kDecThreads), lds, stream, g, batch);
-        } else {
-            if (pow2)
-                hipLaunchKernelGGL((k_decode<true, 8>), grid, dim3(kDecThreads), lds, stream, g, batch);
-            else
-                hipLaunchKernelGGL((k_decode<false, 8>), grid, dim3(kDecThreads), lds, stream, g, batch);
-        }
-        return hipGetLastError();
-    }
-    if (g.D != 4 * kChunksPerRow) {
+    if (g.D == 4 * kChunksPerRow) {
+        launch_tuned<16, 16>(g, batch, n_tensors, stream);
+    } else if (aligned16 && g.D == 96) {
+        launch_tuned<12, 16>(g, batch, n_tensors, stream);  // (32 rows per wave: 6 stores per wave, measured slower)
+    } else if (aligned16 && g.D == 64) {
+        launch_tuned<8, 32>(g, batch, n_tensors, stream);   // 4 stores per wave as at 128: 54 -> 67 % of the HBM peak
+    } else {
         const size_t lds_rows = ((size_t)g.S * 4 + 48 * 4) * sizeof(float);
+        dim3 grid((unsigned)((g.T + kGeneralRows - 1) / kGeneralRows), (unsigned)(g.B * g.H), (unsigned)n_tensors);
         if ((g.S & (g.S - 1)) == 0)
             hipLaunchKernelGGL(k_decode_rows<true>, grid, dim3(kDecThreads), lds_rows, stream, g, batch);
         else
             hipLaunchKernelGGL(k_decode_rows<false>, grid, dim3(kDecThreads), lds_rows, stream, g, batch);
-        return hipGetLastError();
     }
-    if (pow2)
-        hipLaunchKernelGGL((k_decode<true, 16>), grid, dim3(kDecThreads), lds, stream, g, batch);
-    else
-        hipLaunchKernelGGL((k_decode<false, 16>), grid, dim3(kDecThreads), lds, stream, g, batch);
     return hipGetLastError();
 }
 
