@@ -30,8 +30,8 @@ PEAK_HBM_GBS = 8000.0        # MI355X HBM3E peak
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs, each scaled
 # by a plain copy of known size in the same run); figures and commands in profiles/hbm_traffic_*.txt
 MEASURED_TRAFFIC_BYTES = {"llama3_8b_32k": {"k_search": 94.4e6, "k_decode": 91.4e6},
-                          "mha32_d96_8k": {"k_search": 80.7e6, "k_decode": 68.5e6},
-                          "gqa8_d64_32k": {"k_search": 49.3e6, "k_decode": 47.7e6}}
+                          "mha32_d96_8k": {"k_search": 80.1e6, "k_decode": 68.5e6},
+                          "gqa8_d64_32k": {"k_search": 56.1e6, "k_decode": 47.6e6}}
 
 
 def search_flops_per_chunk(S: int) -> float:
