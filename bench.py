@@ -210,11 +210,11 @@ def main() -> int:
                      "tensors_per_launch": tensors_per_enc_launch,
                      "flops_per_chunk": search_flops_per_chunk(wl.S), "formulation": "W_min (36 S flop/chunk)",
                      "avg_launch_ms": search_ms,
-                     "executed": {"instruction": "v_mfma_f32_16x16x32_f16", "flops_per_chunk": 256.0 * S16 * 16,
-                                  "achieved": 256.0 * S16 * 16 * chunks_per_tensor * tensors_per_enc_launch
+                     "executed": {"instruction": "v_mfma_f32_32x32x16_f16", "flops_per_chunk": 128.0 * S16 * 16,
+                                  "achieved": 128.0 * S16 * 16 * chunks_per_tensor * tensors_per_enc_launch
                                   / (search_ms * 1e-3) / 1e12,
                                   "peak": PEAK_F16_TFLOPS, "unit": "TFLOP/s",
-                                  "frac": 256.0 * S16 * 16 * chunks_per_tensor * tensors_per_enc_launch
+                                  "frac": 128.0 * S16 * 16 * chunks_per_tensor * tensors_per_enc_launch
                                   / (search_ms * 1e-3) / 1e12 / PEAK_F16_TFLOPS}},
         "roofline_decode": {"kernel": "k_decode" if wl.D in (64, 96, 128) else "k_decode_rows", "bound": "hbm", "achieved": dec_gbs, "peak": PEAK_HBM_GBS,
                             "unit": "GB/s", "frac": dec_gbs / PEAK_HBM_GBS,

@@ -99,7 +99,7 @@ static WorkspaceLayout workspace_layout(const Geometry &g)
     l.cand = take((uint64_t)g.H * kCandCap * sizeof(unsigned long long));
     l.block_sum = take(n_blocks * sizeof(uint32_t));
     l.block_pre = take(n_blocks * sizeof(uint32_t));
-    l.aop = take((uint64_t)g.H * g.S16 * 4 * 64 * 16);
+    l.aop = take((uint64_t)g.H * g.S16 * kATiles * 64 * 16);
     l.total = off;
     return l;
 }

@@ -16,6 +16,7 @@ constexpr int kSearchRowsHuge = 512;   // 512 from 4096 rows on (16-wave workgro
 constexpr int kSearchRowsSwitch = 2048;
 constexpr int kSearchRowsSwitchHuge = 4096;
 constexpr int kThreads = 256;        // default workgroup: 4 wave64
+constexpr int kATiles = 2;           // 64-lane x 16-byte MFMA A operand tiles per 16 secondaries (8 secondaries each)
 
 // Radix select over the 63 value bits of a non-negative IEEE double: two histogram digits from
 // the top, then a candidate list for the keys sharing those 23 bits.
@@ -52,23 +53,22 @@ struct Geometry {
 };
 
 // Dynamic LDS of one search workgroup (host side; the kernels carve the same layout): the head's
-// MFMA A operands and secondaries, the waves' operand buffers, and the per-row state, which for rows of
+// MFMA A operands and secondaries, and the per-row state, which for rows of
 // 128 elements is two rows of code words per wave and a counter per row, and for other row lengths a
 // running maximum, flag word, scale, counter and the code words of every row of the workgroup.
 inline size_t search_lds_bytes(int S16, int D, int row_words, int waves, int rows)
 {
-    const size_t tables = (size_t)S16 * 4 * 64 * 16 + (size_t)S16 * 16 * 4 * 4;
-    const size_t ubuf = (size_t)waves * 64 * 4 * 8;
+    const size_t tables = (size_t)S16 * kATiles * 64 * 16 + (size_t)S16 * 16 * 4 * 4;
     if (D == 4 * kChunksPerRow)
-        return tables + ubuf + ((size_t)waves * 2 * 32 + (size_t)rows) * 4;
-    return tables + ubuf + (size_t)rows * (8 + 4 + 4 + 4 + 4 * (size_t)row_words);
+        return tables + ((size_t)waves * 2 * 32 + (size_t)rows) * 4;
+    return tables + (size_t)rows * (8 + 4 + 4 + 4 + 4 * (size_t)row_words);
 }
 constexpr size_t kLdsPerCu = 160 * 1024;
 
 // Waves of a search workgroup.  256 or more rows per workgroup, and tables so large
 // that fewer than four 4-wave workgroups fit a CU's LDS: one workgroup of 16 waves per CU when its LDS
-// fits (four waves on every SIMD sharing one copy of the tables; at S = 256 measured 3 % faster than two
-// workgroups of 4, while at S = 64, where five small workgroups fit, the small ones are 13 % faster).
+// fits (four waves on every SIMD sharing one copy of the tables; measured 3 % faster than two
+// workgroups of 4, while four or more small workgroups, where they fit, are 7 to 13 % faster than the large one).
 // Otherwise 4 waves when two workgroups fit a CU's LDS, else one workgroup of 8, which keeps two waves
 // on every SIMD.
 inline int search_waves_for(int S16, int D, int row_words, int rows)
@@ -101,7 +101,7 @@ struct Workspace {
     unsigned long long *cand;      // [H][kCandCap]
     uint32_t *block_sum;           // [B*H*n_search_blocks_per_seg] outliers per search workgroup
     uint32_t *block_pre;           // same shape, exclusive prefix
-    uint4 *aop;                    // [H][4 * S16][64] MFMA A operands of the search, built once per call
+    uint4 *aop;                    // [H][kATiles * S16][64] MFMA A operands of the search, built once per call
 };
 
 struct EncodedPtrs {

@@ -8,22 +8,28 @@
 //     max_p <v, P_p> = max( max_i |v_i| , (|v_0|+|v_1|+|v_2|+|v_3|)/2 )
 // (first term: the 8 axis elements +-1, +-i, +-j, +-k; second: the 16 half-integer elements).
 // The map u -> v is linear, v = A(q_s) u with a 4x4 matrix per secondary, so all S products of
-// 16 chunks are one [4S x 4] x [4 x 16] contraction with K = 4 on the matrix cores (how it is fed
+// 32 chunks are one [4S x 4] x [4 x 32] contraction with K = 4 on the matrix cores (how it is fed
 // to them is described at the kernel).  One MFMA gives every lane the four components of v for
-// one (chunk, secondary) pair; the closed form and the running argmax over s are a handful of
+// four (chunk, secondary) pairs; the closed form and the running argmax over s are a handful of
 // VALU instructions per pair.  The search stays exhaustive over all S secondaries and, through
 // the closed form, over all 24 primaries.
 //
-// On gfx950 MFMA and VALU instructions do not run concurrently on a SIMD (measured: their times
-// add), so the inner loop is costed as 17 cycles of MFMA plus 3 to 4 cycles per VALU instruction
-// for every 64 (chunk, secondary) pairs, and the VALU count per pair is what is minimised: the
-// running argmax is kept per group of 16 secondaries (4 per lane) with v_max3 chains, one
-// compare-and-select per group, and the winner inside the winning group is found afterwards by
-// re-scoring its 4 candidates once per chunk.
+// On gfx950 MFMA and VALU instructions of one SIMD largely take turns (measured: their times add up
+// to within a few per cent), so the inner loop is costed as the matrix time plus 3 to 4 cycles per VALU
+// instruction, and the VALU count per (chunk, secondary) pair is what is minimised: the running argmax
+// is kept per group of 16 secondaries (8 per lane) with v_max3 chains, one compare-and-select per
+// group, and the winner inside the winning group is found afterwards by re-scoring its candidates.
 //
-// Work split: a workgroup (4 wave64) owns 64 or 256 rows of one (b, h) segment, so the A
+// The matrix pass is a screen, not the decision.  It runs on v_mfma_f32_32x32x16_f16 with every fp32
+// factor split into two fp16 parts (24 bits), i.e. four products per term, a quarter of what a
+// three-part split costs on the matrix cores and an eighth of the fp32 shape's time.  A screened score is
+// within 7e-7 of the true one.  Next to its best group every lane keeps the runner-up score; a chunk whose
+// winning group is not ahead of every other group by 4e-6 is searched again over all S secondaries with
+// plain fp32 arithmetic.  Either way the choice between secondaries is made on fp32 closed-form scores.
+//
+// Work split: a workgroup (4, 8 or 16 wave64) owns 64, 256 or 512 rows of one (b, h) segment, so the A
 // matrices of the head sit in LDS once per workgroup.  A wave takes 64 chunks, one per lane, at a
-// time and runs them as four 16-chunk MFMA column groups: two whole rows of 128 elements in
+// time and runs them as two 32-chunk MFMA column groups: two whole rows of 128 elements in
 // k_search, 64 consecutive chunks of the workgroup's flattened rows in k_search_flat (any other
 // head dimension).  The per-chunk steps (scale, radius code, direction search) are shared.
 #include "hqmq_device.h"
@@ -68,20 +74,6 @@ __device__ __forceinline__ uint16_t double_to_half_rne_sat(double v)
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 constexpr float kOperandScale = 1024.f;
 
-// x = h + l + m to 33 bits, each part an fp16
-struct Parts {
-    _Float16 h, l, m;
-};
-__device__ __forceinline__ Parts split3(float x)
-{
-    Parts p;
-    p.h = (_Float16)x;
-    float r = x - (float)p.h;
-    p.l = (_Float16)r;
-    r -= (float)p.l;
-    p.m = (_Float16)r;
-    return p;
-}
 __device__ __forceinline__ uint32_t pack2(_Float16 lo, _Float16 hi)
 {
     typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
@@ -191,143 +183,199 @@ __device__ __forceinline__ Direction unit_direction(const half4_t xv, double r2,
     return d;
 }
 
+typedef float float16_t __attribute__((ext_vector_type(16)));
+
+// x = h + l to 24 bits (|x - h - l| <= 2^-24 |x|), each part an fp16
+struct Parts2 {
+    _Float16 h, l;
+};
+__device__ __forceinline__ Parts2 split2(float x)
+{
+    Parts2 p;
+    p.h = (_Float16)x;
+    p.l = (_Float16)(x - (float)p.h);
+    return p;
+}
+
+// v = u conj(q) in fp32 and its closed-form score max_p <v, P_p>
+__device__ __forceinline__ float score_secondary(const float *q, float u0, float u1, float u2, float u3, float &v0,
+                                                 float &v1, float &v2, float &v3)
+{
+    const float a = q[0], bq = q[1], cq = q[2], d = q[3];
+    v0 = fmaf(d, u3, fmaf(cq, u2, fmaf(bq, u1, a * u0)));
+    v1 = fmaf(cq, u3, fmaf(-d, u2, fmaf(a, u1, -bq * u0)));
+    v2 = fmaf(-bq, u3, fmaf(a, u2, fmaf(d, u1, -cq * u0)));
+    v3 = fmaf(a, u3, fmaf(bq, u2, fmaf(-cq, u1, -d * u0)));
+    const float a0 = fabsf(v0), a1 = fabsf(v1), a2 = fabsf(v2), a3 = fabsf(v3);
+    return fmaxf(fmaxf(fmaxf(a0, a1), fmaxf(a2, a3)), 0.5f * (((a0 + a1) + a2) + a3));
+}
+
+// Maximum of a 64-bit key over the wave (every lane gets it).
+__device__ __forceinline__ unsigned long long wave_umax64(unsigned long long k)
+{
+    k = umax64(k, dpp_move64<0xB1>(k));   // quad_perm [1, 0, 3, 2]
+    k = umax64(k, dpp_move64<0x4E>(k));   // quad_perm [2, 3, 0, 1]
+    k = umax64(k, dpp_move64<0x141>(k));  // row_half_mirror
+    k = umax64(k, dpp_move64<0x140>(k));  // row_mirror
+    k = umax64(k, (unsigned long long)__shfl_xor((long long)k, 16, 64));
+    k = umax64(k, (unsigned long long)__shfl_xor((long long)k, 32, 64));
+    return k;
+}
+
+// Scores of the screening pass are scaled by kOperandScale^2 = 2^20.  Two groups of secondaries whose
+// screened maxima lie closer than this are not told apart by the screen: its error is below 7e-7 per
+// score (operands carried to 2^-24 each, fp32 accumulation, three fp32 additions), the band is 4e-6.
+constexpr float kScreenBand = 4.0e-6f * kOperandScale * kOperandScale;
+
 // Exhaustive nearest-codeword search for the wave's 64 chunks (one per lane, direction u): returns
 // the chunk's code word (rq << w_idx) | k with k = p S + s of the best joint codeword; 0 for a
 // flagged chunk (also to be passed for a lane without a chunk) and for a zero chunk (r2 == 0).
-// Called by all 64 lanes.
-// my_ubuf: the wave's [64][4] x 8 B operand buffer; amat / secl: the head's A operands and
-// secondaries in LDS.
+// Called by all 64 lanes.  amat / secl: the head's A operands and secondaries in LDS.
+//
+// Three steps.  Screen: all S secondaries on the matrix cores with operands split in two fp16
+// parts; lane (col = l % 32, half = l / 32) sees, for the chunks col and 32 + col, the secondaries
+// 16 grp + 2 t + half (t = 0..7) of every group grp, and keeps per chunk slot the best group, its
+// score and the runner-up score.  Decide: the two lanes of a chunk exchange their results; a clear
+// winner (ahead of every other lane-group by more than the band) names 8 candidate secondaries, which
+// are scored again in fp32.  Otherwise (a few chunks in a thousand) the wave scores all S secondaries
+// of that chunk in fp32, 64 at a time.  The decision between secondaries is therefore always taken
+// on fp32 closed-form scores, the lowest s winning exact ties.
 __device__ __forceinline__ uint32_t search_codeword(const Geometry &g, int lane, const Direction u, bool flagged,
-                                                    double r2, int rq,
-                                                    uint2 *my_ubuf, const uint4 *amat, const float *secl)
+                                                    double r2, int rq, const uint4 *amat, const float *secl)
 {
     const float u0 = u.u0, u1 = u.u1, u2 = u.u2, u3 = u.u3;
-    wave_lds_sync();  // this wave's reads of ubuf / pack from the previous iteration are done
+    const int half = lane >> 5;
+    // B operands: lane (col, half) supplies components 2 half, 2 half + 1 of chunk 32 j + col in the
+    // slots [h l h l | h l h l]; chunk 32 half + col is its own, the other one its partner's (lane ^ 32)
+    half8_t bop[2];
     {
-        const Parts p0 = split3(u0 * kOperandScale), p1 = split3(u1 * kOperandScale);
-        const Parts p2 = split3(u2 * kOperandScale), p3 = split3(u3 * kOperandScale);
-        uint4 *dst = reinterpret_cast<uint4 *>(my_ubuf + 4 * lane);
-        dst[0] = make_uint4(pack2(p0.h, p0.l), pack2(p0.m, (_Float16)0.f), pack2(p1.h, p1.l), pack2(p1.m, (_Float16)0.f));
-        dst[1] = make_uint4(pack2(p2.h, p2.l), pack2(p2.m, (_Float16)0.f), pack2(p3.h, p3.l), pack2(p3.m, (_Float16)0.f));
-    }
-    wave_lds_sync();
-    // B operand of chunk group j: lane (col l % 16, k l / 16) holds the parts of u_k of chunk 16 j + col
-    half8_t bop[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const uint2 e = my_ubuf[4 * (16 * j + (lane & 15)) + (lane >> 4)];  // (h, l), (m, 0)
-        const uint32_t mh = __builtin_amdgcn_perm(e.x, e.y, 0x05040100u);   // (m, h)
-        const uint32_t ml = __builtin_amdgcn_perm(e.x, e.y, 0x07060100u);   // (m, l)
-        bop[j] = __builtin_bit_cast(half8_t, make_uint4(e.x, e.x, mh, ml));
+        const Parts2 p0 = split2(u0 * kOperandScale), p1 = split2(u1 * kOperandScale);
+        const Parts2 p2 = split2(u2 * kOperandScale), p3 = split2(u3 * kOperandScale);
+        const uint32_t k0 = pack2(p0.h, p0.l), k1 = pack2(p1.h, p1.l), k2 = pack2(p2.h, p2.l), k3 = pack2(p3.h, p3.l);
+        const uint32_t own_a = half ? k2 : k0, own_b = half ? k3 : k1;
+        const uint32_t snd_a = half ? k0 : k2, snd_b = half ? k1 : k3;
+        const uint32_t rcv_a = (uint32_t)__shfl_xor((int)snd_a, 32, 64), rcv_b = (uint32_t)__shfl_xor((int)snd_b, 32, 64);
+        const uint32_t j0a = half ? rcv_a : own_a, j0b = half ? rcv_b : own_b;
+        const uint32_t j1a = half ? own_a : rcv_a, j1b = half ? own_b : rcv_b;
+        bop[0] = __builtin_bit_cast(half8_t, make_uint4(j0a, j0a, j0b, j0b));
+        bop[1] = __builtin_bit_cast(half8_t, make_uint4(j1a, j1a, j1b, j1b));
     }
 
-    // ---- exhaustive search over the secondaries -------------------------------------------
-    // best[j] / bkey[j]: running maximum of the closed-form score and 16 x the group of 16
-    // secondaries (4 of them on this lane: s = 16 grp + 4 t + lane/16) that reached it.
-    float best[4] = {-1.f, -1.f, -1.f, -1.f};
-    int bkey[4] = {0, 0, 0, 0};
-    const float4_t zero4 = {0.f, 0.f, 0.f, 0.f};
+    // ---- screen ----------------------------------------------------------------------------------------
+    float best[2] = {-1.f, -1.f}, second[2] = {-1.f, -1.f};
+    int bkey[2] = {0, 0};
+    float16_t zero16;
+#pragma unroll
+    for (int e = 0; e < 16; ++e)
+        zero16[e] = 0.f;
+    const uint4 *arow = amat + lane;
+    half8_t a0 = __builtin_bit_cast(half8_t, arow[0]), a1 = __builtin_bit_cast(half8_t, arow[64]);
+    // the product of (tile 0, chunk slot 0) of the next group is issued before the arithmetic on the last
+    // product of this one: MFMA and VALU do not overlap on a SIMD, but a VALU instruction right behind
+    // the MFMA it depends on idles for the depth of the matrix pipeline
+    float16_t ahead = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, bop[0], zero16, 0, 0, 0);
     for (int grp = 0; grp < g.S16; ++grp) {
-        // Over the group's 4 secondaries: GA = largest |v_i| (best axis element), GH = largest
-        // |v_0|+|v_1|+|v_2|+|v_3| (twice the best half-integer element); the group's score is
-        // max(GA, GH / 2), taken once per group.
-        float GA[4] = {0.f, 0.f, 0.f, 0.f}, GH[4] = {0.f, 0.f, 0.f, 0.f};
-        const uint4 *arow = amat + (size_t)grp * 4 * 64 + lane;
-        half8_t aop[4];
+        const int gn = min(grp + 1, g.S16 - 1);  // the last group re-reads itself; that product is dropped
+        const half8_t n0 = __builtin_bit_cast(half8_t, arow[(2 * gn) * 64]);
+        const half8_t n1 = __builtin_bit_cast(half8_t, arow[(2 * gn + 1) * 64]);
+        // over the group's 8 secondaries on this lane: GA = largest |v_i| (best axis element), GH = largest
+        // |v_0|+|v_1|+|v_2|+|v_3| (twice the best half-integer element)
+        float GA[2] = {0.f, 0.f}, GH[2] = {0.f, 0.f};
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
-            aop[t] = __builtin_bit_cast(half8_t, arow[t * 64]);
-        // 8 pairs of products (secondaries 2 tp, 2 tp + 1 of the group x chunk group j).  The
-        // products of pair k + 1 are issued before the arithmetic on pair k: MFMA and VALU do not
-        // overlap on this SIMD, but a VALU instruction right behind the MFMA it depends on idles
-        // for the depth of the matrix pipeline.
-        float4_t vA = __builtin_amdgcn_mfma_f32_16x16x32_f16(aop[0], bop[0], zero4, 0, 0, 0);
-        float4_t vB = __builtin_amdgcn_mfma_f32_16x16x32_f16(aop[1], bop[0], zero4, 0, 0, 0);
+        for (int k = 0; k < 4; ++k) {  // (tile k / 2, chunk slot k % 2)
+            const int j = k & 1;
+            const float16_t c = ahead;
+            if (k == 0)
+                ahead = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, bop[1], zero16, 0, 0, 0);
+            else if (k == 1)
+                ahead = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1, bop[0], zero16, 0, 0, 0);
+            else if (k == 2)
+                ahead = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1, bop[1], zero16, 0, 0, 0);
+            else
+                ahead = __builtin_amdgcn_mfma_f32_32x32x16_f16(n0, bop[0], zero16, 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            float ga = GA[j], gh = GH[j];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const int j = k & 3;
-            const float4_t cA = vA, cB = vB;
-            if (k + 1 < 8) {
-                const int tn = (k + 1) >> 2, jn = (k + 1) & 3;
-                vA = __builtin_amdgcn_mfma_f32_16x16x32_f16(aop[2 * tn], bop[jn], zero4, 0, 0, 0);
-                vB = __builtin_amdgcn_mfma_f32_16x16x32_f16(aop[2 * tn + 1], bop[jn], zero4, 0, 0, 0);
+            for (int i = 0; i < 4; i += 2) {  // secondaries i, i + 1 of the tile's four
+                const float x0 = fabsf(c[4 * i]), x1 = fabsf(c[4 * i + 1]), x2 = fabsf(c[4 * i + 2]), x3 = fabsf(c[4 * i + 3]);
+                const float y0 = fabsf(c[4 * i + 4]), y1 = fabsf(c[4 * i + 5]), y2 = fabsf(c[4 * i + 6]), y3 = fabsf(c[4 * i + 7]);
+                const float hx = ((x0 + x1) + x2) + x3;
+                const float hy = ((y0 + y1) + y2) + y3;
+                ga = fmaxf(fmaxf(ga, x0), x1);  // v_max3 each
+                ga = fmaxf(fmaxf(ga, x2), x3);
+                ga = fmaxf(fmaxf(ga, y0), y1);
+                ga = fmaxf(fmaxf(ga, y2), y3);
+                gh = fmaxf(fmaxf(gh, hx), hy);
             }
-            __builtin_amdgcn_sched_barrier(0);  // products first, then the arithmetic on the older pair
-            const float a0 = fabsf(cA[0]), a1 = fabsf(cA[1]), a2 = fabsf(cA[2]), a3 = fabsf(cA[3]);
-            const float b0 = fabsf(cB[0]), b1 = fabsf(cB[1]), b2 = fabsf(cB[2]), b3 = fabsf(cB[3]);
-            const float hA = ((a0 + a1) + a2) + a3;
-            const float hB = ((b0 + b1) + b2) + b3;
-            float ga = fmaxf(fmaxf(GA[j], a0), a1);  // v_max3 each
-            ga = fmaxf(fmaxf(ga, a2), a3);
-            ga = fmaxf(fmaxf(ga, b0), b1);
-            GA[j] = fmaxf(fmaxf(ga, b2), b3);
-            GH[j] = fmaxf(fmaxf(GH[j], hA), hB);
+            GA[j] = ga;
+            GH[j] = gh;
             __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < 2; ++j) {
             const float M = fmaxf(GA[j], 0.5f * GH[j]);
+            second[j] = __builtin_amdgcn_fmed3f(M, best[j], second[j]);  // second <= best on entry
             if (M > best[j]) {
                 best[j] = M;
                 bkey[j] = 16 * grp;
             }
         }
+        a0 = n0;
+        a1 = n1;
     }
 
-    // ---- reduce over the 4 lanes that share a chunk, hand the winner to the owner lane ------
-    // key = 16 grp + lane/16: the first of the 4 candidates s = key + 4 t of the winning lane.
-    // Chunk 16 j + col was scored by lanes col, col + 16, col + 32, col + 48 (slot j of each) and
-    // is owned by lane 16 j + col: the (score, key) pairs go through LDS (the operand buffer is
-    // free by now), the owner reads its four and keeps the larger score, the lower key on equal ones.
-    int key_mine;
-    {
-        uint2 *red = my_ubuf;  // [4 slots][64 lanes]
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            red[j * 64 + lane] = make_uint2(__float_as_uint(best[j]), (uint32_t)(bkey[j] + (lane >> 4)));
-        wave_lds_sync();
-        const uint2 *mine = red + (lane >> 4) * 64 + (lane & 15);
-        uint2 e = mine[0];
-        float bj = __uint_as_float(e.x);
-        int kj = (int)e.y;
-#pragma unroll
-        for (int m = 1; m < 4; ++m) {
-            e = mine[16 * m];
-            const float ob = __uint_as_float(e.x);
-            const int ok = (int)e.y;
-            const bool take = (ob > bj) | ((ob == bj) & (ok < kj));
-            bj = take ? ob : bj;
-            kj = take ? ok : kj;
-        }
-        key_mine = kj;
-    }
+    // ---- decide: chunk 32 j + col was screened by lanes col and 32 + col (slot j of each) and is
+    // owned by lane 32 j + col, i.e. slot `half` of the owner and of its partner ------------------------
+    const float my_b = half ? best[1] : best[0], my_s = half ? second[1] : second[0];
+    const int my_k = half ? bkey[1] : bkey[0];
+    const float ot_b = __shfl_xor(half ? best[0] : best[1], 32, 64);
+    const float ot_s = __shfl_xor(half ? second[0] : second[1], 32, 64);
+    const int ot_k = __shfl_xor(half ? bkey[0] : bkey[1], 32, 64);
+    const bool other = ot_b > my_b;
+    const float top = other ? ot_b : my_b;
+    const float runner = fmaxf(fmaxf(fminf(my_b, ot_b), my_s), ot_s);
+    const int first = (other ? ot_k : my_k) + (other ? 1 - half : half);  // candidates first + 2 t
+    const bool live = !flagged && r2 != 0.0;
+    const bool unclear = live && !(top - runner >= kScreenBand);
 
-    // ---- re-score the 4 candidates of the winning group: secondary, primary -----------------
-    uint32_t code = 0;
-    if (!flagged && r2 != 0.0) {
+    int bs = first;
+    if (live) {
         float bsc = -1.f;
-        float w0 = 0.f, w1 = 0.f, w2 = 0.f, w3 = 0.f;
-        int bs = key_mine;
 #pragma unroll
-        for (int tt = 0; tt < 4; ++tt) {
-            const int sc_idx = key_mine + 4 * tt;  // < 16 S16: inside the padded table
-            const float *q = secl + 4 * sc_idx;
-            const float a = q[0], bq = q[1], cq = q[2], d = q[3];
-            const float v0 = fmaf(d, u3, fmaf(cq, u2, fmaf(bq, u1, a * u0)));
-            const float v1 = fmaf(cq, u3, fmaf(-d, u2, fmaf(a, u1, -bq * u0)));
-            const float v2 = fmaf(-bq, u3, fmaf(a, u2, fmaf(d, u1, -cq * u0)));
-            const float v3 = fmaf(a, u3, fmaf(bq, u2, fmaf(-cq, u1, -d * u0)));
-            const float a0 = fabsf(v0), a1 = fabsf(v1), a2 = fabsf(v2), a3 = fabsf(v3);
-            const float sc = fmaxf(fmaxf(fmaxf(a0, a1), fmaxf(a2, a3)), 0.5f * (((a0 + a1) + a2) + a3));
+        for (int tt = 0; tt < 8; ++tt) {
+            const int sc_idx = first + 2 * tt;  // < 16 S16: inside the padded table
+            float v0, v1, v2, v3;
+            const float sc = score_secondary(secl + 4 * sc_idx, u0, u1, u2, u3, v0, v1, v2, v3);
             const bool take = (sc_idx < g.S) & (sc > bsc);  // strict: the lowest s wins a tie
             bsc = take ? sc : bsc;
             bs = take ? sc_idx : bs;
-            w0 = take ? v0 : w0;
-            w1 = take ? v1 : w1;
-            w2 = take ? v2 : w2;
-            w3 = take ? v3 : w3;
         }
-        float sc;
+    }
+    // the unclear chunks, one at a time: every lane scores the secondaries lane, lane + 64, ...; the key
+    // orders by score, then by descending s (scores are positive, so their bit patterns order like them)
+    unsigned long long todo = __ballot(unclear);
+    while (todo) {  // wave-uniform
+        const int src = __ffsll((long long)todo) - 1;
+        todo &= todo - 1ull;
+        const float e0 = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(u0), src));
+        const float e1 = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(u1), src));
+        const float e2 = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(u2), src));
+        const float e3 = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(u3), src));
+        unsigned long long key = 0ull;
+        for (int s = lane; s < g.S; s += 64) {
+            float v0, v1, v2, v3;
+            const float sc = score_secondary(secl + 4 * s, e0, e1, e2, e3, v0, v1, v2, v3);
+            key = umax64(key, ((unsigned long long)__float_as_uint(sc) << 32) | (0xffffffffu - (uint32_t)s));
+        }
+        key = wave_umax64(key);
+        if (lane == src)
+            bs = (int)min(0xffffffffu - (uint32_t)key, (uint32_t)g.S - 1u);
+    }
+
+    uint32_t code = 0;
+    if (live) {
+        float w0, w1, w2, w3, sc;
+        (void)score_secondary(secl + 4 * bs, u0, u1, u2, u3, w0, w1, w2, w3);
         const int p = nearest_primary(w0, w1, w2, w3, sc);
         code = ((uint32_t)rq << g.w_idx) | (uint32_t)(p * g.S + bs);
     }
@@ -336,19 +384,19 @@ __device__ __forceinline__ uint32_t search_codeword(const Geometry &g, int lane,
 
 }  // namespace
 
-// The K = 4 contraction v = A(q_s) u runs on v_mfma_f32_16x16x32_f16, which issues in half the time
-// of the fp32 shape: every fp32 factor is split into three fp16 parts (h + l + m carries 33 bits; both
-// operands are scaled by 2^10 first so that the small parts stay normal), lane group k of the
-// product holds the parts of its one factor in its 8 slots, A as [h h l l h m l m], B as
-// [h l h l m h m l], and the eight fp16 x fp16 products (exact in fp32) add up to the fp32-accurate
-// a * u inside the matrix core.  The scores come out scaled by 2^20, which no comparison notices.
+// The K = 4 contraction v = A(q_s) u on v_mfma_f32_32x32x16_f16: a product covers 8 secondaries (32 rows =
+// 8 x 4 components of v) and 32 chunks (columns); its K = 16 are the 4 terms of the contraction times the
+// 4 products of a two-part split (both operands are scaled by 2^10 first so that the low parts stay
+// normal).  Lane l of an operand holds row (column) l % 32 and the terms 2 (l / 32), 2 (l / 32) + 1, each in
+// four fp16 slots: A as [h h l l], B as [h l h l].  The four fp16 x fp16 products are exact in fp32 and
+// add up inside the matrix core.  Lane l of the result holds, for column l % 32, the rows
+// 8 i + 4 (l / 32) + c (i, c = 0..3): all four components of v for the secondaries 2 i + l / 32 of the tile.
+// The scores come out scaled by 2^20, which no comparison notices.
 //
 // Dynamic LDS layout:
-//   amat  [4*S16][64] x 16 B   MFMA A operands: lane l of s-block sb holds the parts of
-//                              A[row l%16][k l/16], row 4g+i = component i of v for secondary 4 sb + g
+//   amat  [2*S16][64] x 16 B   MFMA A operands, one 64-lane tile per 8 secondaries
 //                              (copied from the table k_prepare_operands built for the head)
 //   secl  [16*S16][4] f32      the head's secondaries (zero padded to a multiple of 16)
-//   ubuf  [kWaves][64][4] x 8 B   parts (h, l, m, 0) of the unit directions of the wave's 64 chunks
 //   pack  [kWaves][2][32] u32 row code words being assembled
 //   rcnt  [search_rows] u32    outliers per row of the workgroup
 // The search's MFMA A operands of every head, built once per call into the workspace (the workgroups
@@ -359,15 +407,17 @@ __global__ __launch_bounds__(kThreads) void k_prepare_operands(Geometry g, Works
     const Workspace ws = carve_workspace(tn.ws, wo);
     const int h = blockIdx.y;
     const float *sec_h = tn.sec + (size_t)h * g.S * 4;
-    uint4 *dst = ws.aop + (size_t)h * g.S16 * 4 * 64;
+    uint4 *dst = ws.aop + (size_t)h * g.S16 * kATiles * 64;
     {
         const int idx = blockIdx.x * kThreads + threadIdx.x;
-        if (idx >= g.S16 * 4 * 64)
+        if (idx >= g.S16 * kATiles * 64)
             return;
-        int sb = idx >> 6, l = idx & 63;
-        int row = l & 15, k = l >> 4;
-        int gsub = row >> 2, i = row & 3;
-        const int sidx = 4 * sb + gsub;
+        // tile of 8 secondaries: lane l holds row l % 32 = 4 (secondary in tile) + i and the factors
+        // k = 2 (l / 32), 2 (l / 32) + 1 of that row, each in the slots [h h l l]
+        const int tile = idx >> 6, l = idx & 63;
+        const int row = l & 31, kh = l >> 5;
+        const int i = row & 3;
+        const int sidx = 8 * tile + (row >> 2);
         float a = 0.f, bq = 0.f, c = 0.f, d = 0.f;  // zero rows pad S up to a multiple of 16
         if (sidx < g.S) {
             const float *q = sec_h + 4 * sidx;
@@ -377,24 +427,25 @@ __global__ __launch_bounds__(kThreads) void k_prepare_operands(Geometry g, Works
         //                     v1 = -b u0 + a u1 - d u2 + c u3
         //                     v2 = -c u0 + d u1 + a u2 - b u3
         //                     v3 = -d u0 - c u1 + b u2 + a u3
-        float val;
+        const float r0[4] = {a, bq, c, d}, r1[4] = {-bq, a, -d, c}, r2[4] = {-c, d, a, -bq}, r3[4] = {-d, -c, bq, a};
+        float va, vb;
         if (i == 0)
-            val = (k == 0) ? a : (k == 1) ? bq : (k == 2) ? c : d;
+            va = r0[2 * kh], vb = r0[2 * kh + 1];
         else if (i == 1)
-            val = (k == 0) ? -bq : (k == 1) ? a : (k == 2) ? -d : c;
+            va = r1[2 * kh], vb = r1[2 * kh + 1];
         else if (i == 2)
-            val = (k == 0) ? -c : (k == 1) ? d : (k == 2) ? a : -bq;
+            va = r2[2 * kh], vb = r2[2 * kh + 1];
         else
-            val = (k == 0) ? -d : (k == 1) ? -c : (k == 2) ? bq : a;
-        const Parts pa = split3(val * kOperandScale);
-        dst[idx] = make_uint4(pack2(pa.h, pa.h), pack2(pa.l, pa.l), pack2(pa.h, pa.m), pack2(pa.l, pa.m));
+            va = r3[2 * kh], vb = r3[2 * kh + 1];
+        const Parts2 pa = split2(va * kOperandScale), pb = split2(vb * kOperandScale);
+        dst[idx] = make_uint4(pack2(pa.h, pa.h), pack2(pa.l, pa.l), pack2(pb.h, pb.h), pack2(pb.l, pb.l));
     }
 
 }
 
 // kWaves: 4 (several workgroups per CU); 16 for workgroups of 256 or 512 rows whose tables would leave
-// room for fewer than four such workgroups (one per CU, four waves on every SIMD); 8 when the A operands
-// are so large (S > 256) that only one workgroup fits a CU and 16 waves do not: twice the waves then share
+// room for fewer than four such workgroups (one per CU, four waves on every SIMD); 8 when tables and row
+// state are so large that only one workgroup fits a CU and 16 waves do not: twice the waves then share
 // the tables and keep two waves on every SIMD.
 // This kernel is for rows of 128 elements (32 chunks: two rows per wave); k_search_flat below takes
 // every other head dimension.
@@ -409,9 +460,8 @@ __global__ __launch_bounds__(64 * kWaves) void k_search(Geometry g, WorkspaceOff
     const float *__restrict__ sec = tn.sec;
     extern __shared__ float smem[];
     uint4 *amat = reinterpret_cast<uint4 *>(smem);
-    float *secl = reinterpret_cast<float *>(amat + (size_t)g.S16 * 4 * 64);
-    uint2 *ubuf = reinterpret_cast<uint2 *>(secl + (size_t)g.S16 * 16 * 4);
-    uint32_t *pack = reinterpret_cast<uint32_t *>(ubuf + kWaves * 64 * 4);
+    float *secl = reinterpret_cast<float *>(amat + (size_t)g.S16 * kATiles * 64);
+    uint32_t *pack = reinterpret_cast<uint32_t *>(secl + (size_t)g.S16 * 16 * 4);
     uint32_t *rcnt = pack + kWaves * 2 * 32;
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -429,8 +479,8 @@ __global__ __launch_bounds__(64 * kWaves) void k_search(Geometry g, WorkspaceOff
         *reinterpret_cast<float4_t *>(secl + 4 * s) = q;
     }
     {
-        const uint4 *src = ws.aop + (size_t)h * g.S16 * 4 * 64;
-        for (int idx = tid; idx < g.S16 * 4 * 64; idx += kThreadsS)
+        const uint4 *src = ws.aop + (size_t)h * g.S16 * kATiles * 64;
+        for (int idx = tid; idx < g.S16 * kATiles * 64; idx += kThreadsS)
             amat[idx] = src[idx];
     }
 
@@ -439,7 +489,6 @@ __global__ __launch_bounds__(64 * kWaves) void k_search(Geometry g, WorkspaceOff
     const double thr = ws.thr[h];
     const double Lq = (double)((1 << g.b_r) - 1);
     const int c = lane & 31, half_id = lane >> 5;
-    uint2 *my_ubuf = ubuf + wv * 64 * 4;
     uint32_t *my_pack = pack + wv * 64;
     const _Float16 *base = x + (int64_t)b * g.sb + (int64_t)h * g.sh + 4 * c;
 
@@ -475,7 +524,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_search(Geometry g, WorkspaceOff
         const int rq = radius_code(r2, r_f, sigma16, Lq);
         const Direction u = unit_direction(xv, r2, r_f);
         my_pack[lane] = 0;  // after the previous iteration's reads of it: LDS serves a wave in order
-        const uint32_t code = search_codeword(g, lane, u, flagged, r2, rq, my_ubuf, amat, secl);
+        const uint32_t code = search_codeword(g, lane, u, flagged, r2, rq, amat, secl);
 
         // ---- pack the row: chunk c at bits [c*w, (c+1)*w) -----------------------------------------
         {
@@ -538,7 +587,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_search(Geometry g, WorkspaceOff
 //   pass 2  the chunks again (second read from L2): radius code against the row's scale, direction
 //           search, code word OR-ed into the row's slot of the packing area;
 //   end     the packing area goes out as one contiguous block, then the outlier offsets as above.
-// Dynamic LDS: amat | secl | ubuf as in k_search, then rowmax u64 [kRows] | fword u32 [kRows] |
+// Dynamic LDS: amat | secl as in k_search, then rowmax u64 [kRows] | fword u32 [kRows] |
 // sig u32 [kRows] | rcnt u32 [kRows] | pack u32 [kRows * row_words].
 template <int kWaves, int kRows>
 __global__ __launch_bounds__(64 * kWaves) void k_search_flat(Geometry g, WorkspaceOffsets wo, EncodeBatch batch)
@@ -551,9 +600,8 @@ __global__ __launch_bounds__(64 * kWaves) void k_search_flat(Geometry g, Workspa
     const _Float16 *__restrict__ x = tn.x;
     extern __shared__ float smem[];
     uint4 *amat = reinterpret_cast<uint4 *>(smem);
-    float *secl = reinterpret_cast<float *>(amat + (size_t)g.S16 * 4 * 64);
-    uint2 *ubuf = reinterpret_cast<uint2 *>(secl + (size_t)g.S16 * 16 * 4);
-    unsigned long long *rowmax = reinterpret_cast<unsigned long long *>(ubuf + kWaves * 64 * 4);
+    float *secl = reinterpret_cast<float *>(amat + (size_t)g.S16 * kATiles * 64);
+    unsigned long long *rowmax = reinterpret_cast<unsigned long long *>(secl + (size_t)g.S16 * 16 * 4);
     uint32_t *fword = reinterpret_cast<uint32_t *>(rowmax + kRows);
     uint32_t *sig = fword + kRows;
     uint32_t *rcnt = sig + kRows;
@@ -577,8 +625,8 @@ __global__ __launch_bounds__(64 * kWaves) void k_search_flat(Geometry g, Workspa
         *reinterpret_cast<float4_t *>(secl + 4 * s) = q;
     }
     {
-        const uint4 *src = ws.aop + (size_t)h * g.S16 * 4 * 64;
-        for (int idx = tid; idx < g.S16 * 4 * 64; idx += kThreadsS)
+        const uint4 *src = ws.aop + (size_t)h * g.S16 * kATiles * 64;
+        for (int idx = tid; idx < g.S16 * kATiles * 64; idx += kThreadsS)
             amat[idx] = src[idx];
     }
     for (int i = tid; i < kRows; i += kThreadsS) {
@@ -617,7 +665,6 @@ __global__ __launch_bounds__(64 * kWaves) void k_search_flat(Geometry g, Workspa
     __syncthreads();
 
     // ---- pass 2: radius codes and the direction search ----------------------------------------------
-    uint2 *my_ubuf = ubuf + wv * 64 * 4;
     for (int q0 = wv * 64; q0 < nchunks; q0 += kThreadsS) {  // wave-uniform trip count
         const int q = q0 + lane;
         const bool valid = q < nchunks;
@@ -629,7 +676,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_search_flat(Geometry g, Workspa
         const float r_f = __builtin_amdgcn_sqrtf((float)r2);
         const int rq = radius_code(r2, r_f, sigma16, Lq);
         const Direction u = unit_direction(xv, r2, r_f);
-        const uint32_t code = search_codeword(g, lane, u, flagged || !valid, r2, rq, my_ubuf, amat, secl);
+        const uint32_t code = search_codeword(g, lane, u, flagged || !valid, r2, rq, amat, secl);
         if (code) {
             const uint32_t bitpos = (uint32_t)c * g.w;
             const uint32_t d0 = bitpos >> 5, sh = bitpos & 31;
@@ -702,7 +749,7 @@ hipError_t launch_search(const Geometry &g, const WorkspaceOffsets &wo, const En
         if (device >= 0 && device < 64)
             raised[device] = true;
     }
-    hipLaunchKernelGGL(k_prepare_operands, dim3((g.S16 * 4 * 64 + kThreads - 1) / kThreads, g.H, (unsigned)n_tensors),
+    hipLaunchKernelGGL(k_prepare_operands, dim3((g.S16 * kATiles * 64 + kThreads - 1) / kThreads, g.H, (unsigned)n_tensors),
                        dim3(kThreads), 0, stream, g, wo, batch);
     const bool large = g.search_rows == kSearchRowsLarge;
 #define HQMQ_LAUNCH(KERNEL, W, R) hipLaunchKernelGGL((KERNEL<W, R>), grid, dim3(64 * W), lds, stream, g, wo, batch)

@@ -446,6 +446,43 @@ def test_exact_tie_structured_input():
     assert stats["near_ties"] == 16 * 32
 
 
+@pytest.mark.parametrize("S,pairs", [(80, [(2, 19), (7, 40), (33, 79), (64, 65)]), (5, [(1, 4)]), (256, [(0, 255), (100, 101)])])
+def test_codebook_with_repeated_secondaries(S, pairs):
+    """Two bit-identical secondaries score identically for every chunk, whatever group of the matrix
+    pass they sit in: the library has to notice that the two groups cannot be told apart, search the
+    chunk again with plain fp32 arithmetic, and return the lower index like the oracle."""
+    x = _lognormal_tensor(1, 1, 96, seed=31 + S, sigma_g=0.7)
+    sec = _sec(3, 1, S)[1].copy()
+    for lo, hi in pairs:
+        sec[0, hi] = sec[0, lo]
+    xb = _bits(x)
+    e = oracle.encode(xb, sec, b_r=6, Cmul=3.0)
+    g = gpu_encode(x.to(DEV), torch.from_numpy(sec).to(DEV), 6, 3.0)
+    stats = compare_encode(g, e, xb, sec)
+    print(stats, flush=True)
+    assert stats["near_ties"] >= 10 * len(pairs) // 2       # the chunks nearest to a repeated secondary
+    assert stats["index_mismatch_in_near_ties"] == 0
+    k, _ = oracle.unpack_rows(g.codes, S, 6)
+    assert not np.isin(k % S, [hi for _, hi in pairs]).any()  # never the second copy
+
+
+def test_codebook_with_nearly_equal_secondaries():
+    """Secondaries that differ in their last bits only: scores closer than the matrix pass resolves.
+    Whichever codeword the library returns must score within 1e-6 of the oracle's best."""
+    S = 112
+    x = _lognormal_tensor(1, 2, 128, seed=77, sigma_g=0.7)
+    sec = _sec(5, 2, S)[1].copy()
+    rng = np.random.default_rng(5)
+    for lo, hi in [(3, 50), (20, 111), (21, 22), (64, 9)]:
+        sec[:, hi] = sec[:, lo] * (1.0 + rng.uniform(-2e-7, 2e-7, size=(2, 4))).astype(np.float32)
+    xb = _bits(x)
+    e = oracle.encode(xb, sec, b_r=4, Cmul=3.0)
+    g = gpu_encode(x.to(DEV), torch.from_numpy(sec).to(DEV), 4, 3.0)
+    stats = compare_encode(g, e, xb, sec)
+    print(stats, flush=True)
+    assert stats["near_ties"] > 100
+
+
 def test_extreme_magnitudes():
     x = _lognormal_tensor(1, 2, 64, seed=9).float()
     x[0, 0, :8] *= 6e-6                                 # subnormal fp16 territory
