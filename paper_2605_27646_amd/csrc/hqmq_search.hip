@@ -275,9 +275,9 @@ __device__ __forceinline__ uint32_t search_codeword(const Geometry &g, int lane,
     // the MFMA it depends on idles for the depth of the matrix pipeline
     float16_t ahead = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, bop[0], zero16, 0, 0, 0);
     for (int grp = 0; grp < g.S16; ++grp) {
-        const int gn = min(grp + 1, g.S16 - 1);  // the last group re-reads itself; that product is dropped
-        const half8_t n0 = __builtin_bit_cast(half8_t, arow[(2 * gn) * 64]);
-        const half8_t n1 = __builtin_bit_cast(half8_t, arow[(2 * gn + 1) * 64]);
+        // the next group's operands replace this group's as soon as their last product is issued (the
+        // last group re-reads itself; that product is dropped)
+        const uint4 *anext = arow + 2 * min(grp + 1, g.S16 - 1) * 64;
         // over the group's 8 secondaries on this lane: GA = largest |v_i| (best axis element), GH = largest
         // |v_0|+|v_1|+|v_2|+|v_3| (twice the best half-integer element)
         float GA[2] = {0.f, 0.f}, GH[2] = {0.f, 0.f};
@@ -285,14 +285,17 @@ __device__ __forceinline__ uint32_t search_codeword(const Geometry &g, int lane,
         for (int k = 0; k < 4; ++k) {  // (tile k / 2, chunk slot k % 2)
             const int j = k & 1;
             const float16_t c = ahead;
-            if (k == 0)
+            if (k == 0) {
                 ahead = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, bop[1], zero16, 0, 0, 0);
-            else if (k == 1)
+                a0 = __builtin_bit_cast(half8_t, anext[0]);
+            } else if (k == 1) {
                 ahead = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1, bop[0], zero16, 0, 0, 0);
-            else if (k == 2)
+            } else if (k == 2) {
                 ahead = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1, bop[1], zero16, 0, 0, 0);
-            else
-                ahead = __builtin_amdgcn_mfma_f32_32x32x16_f16(n0, bop[0], zero16, 0, 0, 0);
+                a1 = __builtin_bit_cast(half8_t, anext[64]);
+            } else {
+                ahead = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, bop[0], zero16, 0, 0, 0);
+            }
             __builtin_amdgcn_sched_barrier(0);
             float ga = GA[j], gh = GH[j];
 #pragma unroll
@@ -320,8 +323,6 @@ __device__ __forceinline__ uint32_t search_codeword(const Geometry &g, int lane,
                 bkey[j] = 16 * grp;
             }
         }
-        a0 = n0;
-        a1 = n1;
     }
 
     // ---- decide: chunk 32 j + col was screened by lanes col and 32 + col (slot j of each) and is
