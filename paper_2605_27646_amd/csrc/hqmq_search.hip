@@ -21,8 +21,8 @@
 // group, and the winner inside the winning group is found afterwards by re-scoring its candidates.
 //
 // The matrix pass is a screen, not the decision.  It runs on v_mfma_f32_32x32x16_f16 with every fp32
-// factor split into two fp16 parts (24 bits), i.e. four products per term, a quarter of what a
-// three-part split costs on the matrix cores and an eighth of the fp32 shape's time.  A screened score is
+// factor split into two fp16 parts (24 bits), i.e. four products per term, half of what a
+// three-part split costs on the matrix cores and a quarter of the fp32 shape's time.  A screened score is
 // within 7e-7 of the true one.  Next to its best group every lane keeps the runner-up score; a chunk whose
 // winning group is not ahead of every other group by 4e-6 is searched again over all S secondaries with
 // plain fp32 arithmetic.  Either way the choice between secondaries is made on fp32 closed-form scores.
@@ -428,16 +428,16 @@ __global__ __launch_bounds__(kThreads) void k_prepare_operands(Geometry g, Works
         //                     v1 = -b u0 + a u1 - d u2 + c u3
         //                     v2 = -c u0 + d u1 + a u2 - b u3
         //                     v3 = -d u0 - c u1 + b u2 + a u3
-        const float r0[4] = {a, bq, c, d}, r1[4] = {-bq, a, -d, c}, r2[4] = {-c, d, a, -bq}, r3[4] = {-d, -c, bq, a};
-        float va, vb;
-        if (i == 0)
-            va = r0[2 * kh], vb = r0[2 * kh + 1];
-        else if (i == 1)
-            va = r1[2 * kh], vb = r1[2 * kh + 1];
-        else if (i == 2)
-            va = r2[2 * kh], vb = r2[2 * kh + 1];
-        else
-            va = r3[2 * kh], vb = r3[2 * kh + 1];
+        auto entry = [&](int k) -> float {  // A[i][k]
+            if (i == 0)
+                return (k == 0) ? a : (k == 1) ? bq : (k == 2) ? c : d;
+            if (i == 1)
+                return (k == 0) ? -bq : (k == 1) ? a : (k == 2) ? -d : c;
+            if (i == 2)
+                return (k == 0) ? -c : (k == 1) ? d : (k == 2) ? a : -bq;
+            return (k == 0) ? -d : (k == 1) ? -c : (k == 2) ? bq : a;
+        };
+        const float va = entry(2 * kh), vb = entry(2 * kh + 1);
         const Parts2 pa = split2(va * kOperandScale), pb = split2(vb * kOperandScale);
         dst[idx] = make_uint4(pack2(pa.h, pa.h), pack2(pa.l, pa.l), pack2(pb.h, pb.h), pack2(pb.l, pb.l));
     }
