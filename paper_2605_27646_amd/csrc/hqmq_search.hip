@@ -89,6 +89,12 @@ __device__ __forceinline__ unsigned long long dpp_move64(unsigned long long v)
     return ((unsigned long long)(uint32_t)hi << 32) | (uint32_t)lo;
 }
 
+template <int kCtrl>
+__device__ __forceinline__ double dpp_move_f64(double v)
+{
+    return __longlong_as_double((long long)dpp_move64<kCtrl>((unsigned long long)__double_as_longlong(v)));
+}
+
 __device__ __forceinline__ unsigned long long umax64(unsigned long long a, unsigned long long b)
 {
     return a > b ? a : b;
@@ -127,7 +133,7 @@ __device__ __forceinline__ int nearest_primary(float v0, float v1, float v2, flo
 // subnormal; only then is the fp64 recipe run.
 __device__ __forceinline__ uint16_t sigma_of_row_max(double rmax)
 {
-    const float sf = sqrtf((float)rmax);
+    const float sf = __builtin_amdgcn_sqrtf((float)rmax);  // 1 ulp; a flushed subnormal takes the fp64 recipe below
     const uint32_t sb = __float_as_uint(sf);
     const int dist = (int)(sb & 0x1fffu) - 0x1000;
     const bool slow = rmax != 0.0 && sf < 65504.f && (sf < 0x1.0p-14f || (dist >= -8 && dist <= 8));
@@ -280,7 +286,7 @@ __device__ __forceinline__ uint32_t search_codeword(const Geometry &g, int lane,
         const uint4 *anext = arow + 2 * min(grp + 1, g.S16 - 1) * 64;
         // over the group's 8 secondaries on this lane: GA = largest |v_i| (best axis element), GH = largest
         // |v_0|+|v_1|+|v_2|+|v_3| (twice the best half-integer element)
-        float GA[2] = {0.f, 0.f}, GH[2] = {0.f, 0.f};
+        float GA[2], GH[2];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {  // (tile k / 2, chunk slot k % 2)
             const int j = k & 1;
@@ -297,18 +303,28 @@ __device__ __forceinline__ uint32_t search_codeword(const Geometry &g, int lane,
                 ahead = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, bop[0], zero16, 0, 0, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
-            float ga = GA[j], gh = GH[j];
+            float t[16], h[4];
 #pragma unroll
-            for (int i = 0; i < 4; i += 2) {  // secondaries i, i + 1 of the tile's four
-                const float x0 = fabsf(c[4 * i]), x1 = fabsf(c[4 * i + 1]), x2 = fabsf(c[4 * i + 2]), x3 = fabsf(c[4 * i + 3]);
-                const float y0 = fabsf(c[4 * i + 4]), y1 = fabsf(c[4 * i + 5]), y2 = fabsf(c[4 * i + 6]), y3 = fabsf(c[4 * i + 7]);
-                const float hx = ((x0 + x1) + x2) + x3;
-                const float hy = ((y0 + y1) + y2) + y3;
-                ga = fmaxf(fmaxf(ga, x0), x1);  // v_max3 each
-                ga = fmaxf(fmaxf(ga, x2), x3);
-                ga = fmaxf(fmaxf(ga, y0), y1);
-                ga = fmaxf(fmaxf(ga, y2), y3);
-                gh = fmaxf(fmaxf(gh, hx), hy);
+            for (int e = 0; e < 16; ++e)
+                t[e] = fabsf(c[e]);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)  // secondary i of the tile's four
+                h[i] = ((t[4 * i] + t[4 * i + 1]) + t[4 * i + 2]) + t[4 * i + 3];
+            // v_max3 chains; the group's first tile starts them from its own values (|v| >= 0: no zero needed)
+            float ga, gh;
+            if (k < 2) {
+                ga = fmaxf(fmaxf(t[0], t[1]), t[2]);
+#pragma unroll
+                for (int e = 3; e < 15; e += 2)
+                    ga = fmaxf(fmaxf(ga, t[e]), t[e + 1]);
+                ga = fmaxf(ga, t[15]);
+                gh = fmaxf(fmaxf(fmaxf(h[0], h[1]), h[2]), h[3]);
+            } else {
+                ga = GA[j];
+#pragma unroll
+                for (int e = 0; e < 16; e += 2)
+                    ga = fmaxf(fmaxf(ga, t[e]), t[e + 1]);
+                gh = fmaxf(fmaxf(fmaxf(fmaxf(GH[j], h[0]), h[1]), h[2]), h[3]);
             }
             GA[j] = ga;
             GH[j] = gh;
@@ -510,16 +526,15 @@ __global__ __launch_bounds__(64 * kWaves) void k_search(Geometry g, WorkspaceOff
         const unsigned long long ballot = __ballot(flagged);
         const uint32_t word = half_id ? (uint32_t)(ballot >> 32) : (uint32_t)ballot;
 
-        // max over the 32 lanes of the row: non-negative doubles order like their bit patterns; four
-        // DPP steps inside each 16-lane row (after each step the running maxima are uniform over a
-        // block twice as large, so the mirror patterns pair the right blocks), one swap across rows
-        unsigned long long rbits = flagged ? 0ull : key_of(r2);
-        rbits = umax64(rbits, dpp_move64<0xB1>(rbits));   // quad_perm [1, 0, 3, 2]
-        rbits = umax64(rbits, dpp_move64<0x4E>(rbits));   // quad_perm [2, 3, 0, 1]
-        rbits = umax64(rbits, dpp_move64<0x141>(rbits));  // row_half_mirror
-        rbits = umax64(rbits, dpp_move64<0x140>(rbits));  // row_mirror
-        rbits = umax64(rbits, (unsigned long long)__shfl_xor((long long)rbits, 16, 64));
-        const double rmax = __longlong_as_double((long long)rbits);
+        // max over the 32 lanes of the row: four DPP steps inside each 16-lane row (after each step the
+        // running maxima are uniform over a block twice as large, so the mirror patterns pair the right
+        // blocks), one swap across rows
+        double rmax = flagged ? 0.0 : r2;
+        rmax = fmax(rmax, dpp_move_f64<0xB1>(rmax));   // quad_perm [1, 0, 3, 2]
+        rmax = fmax(rmax, dpp_move_f64<0x4E>(rmax));   // quad_perm [2, 3, 0, 1]
+        rmax = fmax(rmax, dpp_move_f64<0x141>(rmax));  // row_half_mirror
+        rmax = fmax(rmax, dpp_move_f64<0x140>(rmax));  // row_mirror
+        rmax = fmax(rmax, __shfl_xor(rmax, 16, 64));
         const uint16_t sigma16 = sigma_of_row_max(rmax);
         const float r_f = __builtin_amdgcn_sqrtf((float)r2);
         const int rq = radius_code(r2, r_f, sigma16, Lq);
