@@ -95,7 +95,7 @@ static WorkspaceLayout workspace_layout(const Geometry &g)
     l.thr = take((uint64_t)g.H * sizeof(double));
     l.hist0 = take((uint64_t)g.H * kBins0 * sizeof(uint32_t));
     l.hist1 = take((uint64_t)g.H * kBins1 * sizeof(uint32_t));
-    l.cand_count = take((uint64_t)g.H * sizeof(uint32_t));
+    l.cand_count = take((uint64_t)g.H * 2 * sizeof(uint32_t));
     l.cand = take((uint64_t)g.H * kCandCap * sizeof(unsigned long long));
     l.block_sum = take(n_blocks * sizeof(uint32_t));
     l.block_pre = take(n_blocks * sizeof(uint32_t));

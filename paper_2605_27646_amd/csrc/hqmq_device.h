@@ -18,11 +18,16 @@ constexpr int kSearchRowsSwitchHuge = 4096;
 constexpr int kThreads = 256;        // default workgroup: 4 wave64
 constexpr int kATiles = 2;           // 64-lane x 16-byte MFMA A operand tiles per 16 secondaries (8 secondaries each)
 
-// Radix select over the 63 value bits of a non-negative IEEE double: two histogram digits from
-// the top, then a candidate list for the keys sharing those 23 bits.
+// Radix select over the 63 value bits of a non-negative IEEE double.  The sequence-sharded select takes
+// bits 62..50, then 10 bits per pass.  The single-tensor select takes exponent and 6 mantissa bits first
+// (17-bit prefix minus kFineBase, clamped to the kBins0 bins: what squares of fp16 data need), collects the
+// keys of that bin as candidates and, should they overflow their list, narrows by bits 45..36.
 constexpr int kBits0 = 13, kShift0 = 50, kBins0 = 1 << kBits0;  // bits 62..50
 constexpr int kBits1 = 10, kShift1 = 40, kBins1 = 1 << kBits1;  // bits 49..40
-constexpr int kCandCap = 16384;      // candidate keys kept per head
+constexpr int kFineShift = 46;                      // first digit of the single-tensor select: key >> 46 ...
+constexpr uint32_t kFineBase = (975u << 6) - 1u;    // ... minus this: 2^-48, the smallest square of an fp16 value, lands in bin 1
+constexpr int kSecShift = kFineShift - kBits1;      // its second digit: bits 45..36
+constexpr int kCandCap = 32768;      // candidate keys kept per head
 constexpr int kSelectThreads = 1024; // workgroup of the select sweeps
 constexpr int kSelectRows = 1024;    // rows of one (b, h) segment per select workgroup
 
@@ -104,7 +109,7 @@ struct Workspace {
     double *thr;                   // [H] outlier threshold on squared norms
     uint32_t *hist0;               // [H][kBins0]
     uint32_t *hist1;               // [H][kBins1]
-    uint32_t *cand_count;          // [H] keys in the candidate bucket (may exceed kCandCap)
+    uint32_t *cand_count;          // [2][H] keys sent to the candidate list by the second sweep, by the third (either may exceed kCandCap)
     unsigned long long *cand;      // [H][kCandCap]
     uint32_t *block_sum;           // [B*H*n_search_blocks_per_seg] outliers per search workgroup
     uint32_t *block_pre;           // same shape, exclusive prefix

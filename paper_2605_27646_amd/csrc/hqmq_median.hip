@@ -4,16 +4,19 @@
 // The median is the lower median (element (n-1)/2 of the sorted norms) of all B*T*ceil(D/4) chunks
 // of a head.  Non-negative IEEE doubles order like their bit patterns read as unsigned integers,
 // so the median is found by a most-significant-digit radix select on the 63 value bits of r^2:
-//   pass 0  histogram of bits 62..50 (sign-free exponent + 2 mantissa bits), all keys
-//   pass 1  histogram of bits 49..40 of the keys in the bucket that holds the wanted rank
-//   collect the few keys that share the 23 bits fixed so far go to a candidate list
-//   finish  one workgroup per head selects the wanted rank among the candidates (radix select on
-//           the low 40 bits) and writes the outlier threshold C^2 * median.
+//   sweep 0  histogram of a first digit made of the exponent and 6 mantissa bits (the squares of fp16
+//            data span 83 binades, which at 64 bins each fit the 8192 bins of a workgroup's LDS)
+//   sweep 1  the keys in the bin that holds the wanted rank (about one in 200 for smooth data) go to a
+//            candidate list, and are counted by their next 10 bits
+//   sweep 2  only for a head whose list overflowed: collects the keys that share both digits; returns
+//            at once otherwise
+//   finish   one workgroup per head selects the wanted rank among the candidates (radix select on
+//            their low 46 or 36 bits) and writes the outlier threshold C^2 * median.
 // Nothing is sorted and no float arithmetic is involved after r^2 itself, so the result is the
-// exact order statistic.  Each pass recomputes r^2 in registers from the fp16 tensor (8 B per
-// chunk, HBM-bound); the bucket choice of the previous pass is re-derived by every workgroup
+// exact order statistic.  Each sweep recomputes r^2 in registers from the fp16 tensor (8 B per
+// chunk, HBM-bound); the bin choice of the previous sweep is re-derived by every workgroup
 // from the (L2-resident) histogram instead of costing a kernel launch of its own.
-// If a head has more keys in the candidate bucket than the list holds (many equal norms: a
+// If a head has more keys sharing both digits than the list holds (many equal norms: a
 // constant or coarsely quantised tensor), the finishing workgroup falls back to radix-selecting
 // the low bits over the head's raw rows itself: slow, exact, and only for such inputs.
 #include "hqmq_device.h"
@@ -78,6 +81,19 @@ __device__ __forceinline__ void pick_bin(const uint32_t *hist, uint32_t rank, ui
 
 }  // namespace
 
+// First digit of the two-sweep select: exponent and 6 mantissa bits of r^2, offset so that the squares
+// that fp16 data can produce (0, and 2^-48 up to below 2^35) fill bins 0 and 1..5312.  Monotone; bins
+// 1..kBins0-2 each hold exactly the keys of one 17-bit prefix bin + kFineBase; bin 0 holds the keys
+// below 2^-48 (for fp16 data: zero only), the last bin everything from 2^(kBins0-2)/64 binades up
+// (never reached by finite fp16 data).
+__device__ __forceinline__ uint32_t fine_bin(unsigned long long key)
+{
+    const uint32_t p = (uint32_t)(key >> kFineShift);
+    const uint32_t d = p > kFineBase ? p - kFineBase : 0u;
+    return min(d, (uint32_t)kBins0 - 1u);
+}
+__device__ __forceinline__ bool fine_bin_is_prefix(uint32_t bin) { return bin >= 1u && bin <= (uint32_t)kBins0 - 2u; }
+
 // ---------------------------------------------------------------------------------------
 // reset of the per-call scratch state
 // ---------------------------------------------------------------------------------------
@@ -91,8 +107,9 @@ __global__ __launch_bounds__(kThreads) void k_init(Geometry g, WorkspaceOffsets 
         ws.hist0[i] = 0;
     if (i < (uint32_t)g.H * kBins1)
         ws.hist1[i] = 0;
-    if (i < (uint32_t)g.H) {
+    if (i < 2u * (uint32_t)g.H)
         ws.cand_count[i] = 0;
+    if (i < (uint32_t)g.H) {
         // +inf: nothing is flagged (replaced by the select, unless the caller supplies the thresholds)
         ws.thr[i] = tn.thr_given ? tn.thr_given[i] : __longlong_as_double(0x7ff0000000000000LL);
     }
@@ -105,11 +122,16 @@ __global__ __launch_bounds__(kThreads) void k_init(Geometry g, WorkspaceOffsets 
 // ---------------------------------------------------------------------------------------
 // sweeps.  grid = (ceil(T / kSelectRows), B*H), 1024 threads: one lane per chunk, 32 rows per
 // block iteration, four independent 8-byte loads in flight per lane.
-//   MODE 0: histogram of digit 0            MODE 1: pick digit 0, histogram of digit 1
-//   MODE 2: pick digits 0 and 1, append the keys of the chosen bucket to the candidate list
+//   MODE 0: histogram of the first digit (fine_bin), all keys
+//   MODE 1: picks the first digit; the keys of that bin (about one in 200) go to the head's candidate
+//           list, staged in LDS so that a workgroup costs the list's counter one update, and are
+//           counted by their next 10 bits (45..36) in case the list overflows
+//   MODE 2: returns at once unless the head's list overflowed; then picks both digits and collects the
+//           keys that share them (the list's memory is reused, with a counter of its own)
 // ---------------------------------------------------------------------------------------
 // kFull: D = 128 (every lane of a 32-lane row slot holds a chunk); otherwise lanes past the row's
 // chunks are idle and the loads go through the general path.
+constexpr int kStageKeys = 1024;  // candidate keys a workgroup of MODE 1 stages in LDS
 template <int MODE, bool kFull>
 __global__ __launch_bounds__(kSelectThreads) void k_select_sweep(Geometry g, WorkspaceOffsets wo, EncodeBatch batch)
 {
@@ -119,26 +141,28 @@ __global__ __launch_bounds__(kSelectThreads) void k_select_sweep(Geometry g, Wor
     constexpr int kLdsBins = MODE == 0 ? kBins0 : kBins1;
     __shared__ uint32_t lh[MODE == 2 ? 1 : kLdsBins];
     __shared__ uint32_t scratch[kSelectThreads + 2];
+    __shared__ unsigned long long staged[MODE == 1 ? kStageKeys : 1];
+    __shared__ uint32_t n_staged, list_base;
 
     const int seg = blockIdx.y, b = seg / g.H, h = seg % g.H;
     const uint32_t rank0 = (uint32_t)(((uint64_t)g.B * g.T * g.n_c - 1) / 2);
     uint32_t bin0 = 0, before0 = 0, bin1 = 0, before1 = 0;
-    if (MODE >= 1)
+    if (MODE == 2 && ws.cand_count[h] <= (uint32_t)kCandCap)
+        return;  // the list of MODE 1 holds every candidate (uniform over the workgroup)
+    if (MODE >= 1) {
         pick_bin<kBins0, kSelectThreads>(ws.hist0 + (size_t)h * kBins0, rank0, scratch, bin0, before0);
-    if (MODE == 2) {
-        pick_bin<kBins1, kSelectThreads>(ws.hist1 + (size_t)h * kBins1, rank0 - before0, scratch, bin1, before1);
-        if (blockIdx.x == 0 && b == 0 && threadIdx.x == 0) {
-            ws.state[h].prefix = ((unsigned long long)bin0 << kBits1) | bin1;
-            ws.state[h].rank = rank0 - before0 - before1;
-        }
+        if (!fine_bin_is_prefix(bin0))
+            return;  // the finishing kernel knows the median of such a bin without candidates
     }
+    if (MODE == 2)
+        pick_bin<kBins1, kSelectThreads>(ws.hist1 + (size_t)h * kBins1, rank0 - before0, scratch, bin1, before1);
     if (MODE != 2) {
         for (int i = threadIdx.x; i < kLdsBins; i += kSelectThreads)
             lh[i] = 0;
+        if (threadIdx.x == 0)
+            n_staged = 0;
         __syncthreads();
     }
-    const unsigned long long prefix = MODE == 1 ? (unsigned long long)bin0
-                                                : (((unsigned long long)bin0 << kBits1) | bin1);
 
     const int c = threadIdx.x & 31, sub = threadIdx.x >> 5;  // 32 rows per iteration
     const int t0 = blockIdx.x * kSelectRows;
@@ -160,19 +184,28 @@ __global__ __launch_bounds__(kSelectThreads) void k_select_sweep(Geometry g, Wor
             const unsigned long long key = key_of(chunk_norm2(v[u])) & kKeyMask;
             if (MODE == 0) {
                 if (in)
-                    atomicAdd(&lh[(uint32_t)(key >> kShift0)], 1u);
+                    atomicAdd(&lh[fine_bin(key)], 1u);
             } else if (MODE == 1) {
-                if (in && (key >> kShift0) == prefix)
-                    atomicAdd(&lh[(uint32_t)(key >> kShift1) & (kBins1 - 1)], 1u);
+                if (in && fine_bin(key) == bin0) {
+                    atomicAdd(&lh[(uint32_t)(key >> kSecShift) & (kBins1 - 1)], 1u);
+                    const uint32_t pos = atomicAdd(&n_staged, 1u);
+                    if (pos < (uint32_t)kStageKeys) {
+                        staged[pos] = key;
+                    } else {  // more than the stage holds (many equal norms): straight to the list
+                        const uint32_t gpos = atomicAdd(&ws.cand_count[h], 1u);
+                        if (gpos < (uint32_t)kCandCap)
+                            cand[gpos] = key;
+                    }
+                }
             } else {
                 // one counter update per wave: ballot, leader adds, lanes take consecutive slots
-                const bool hit = in && (key >> kShift1) == prefix;
+                const bool hit = in && fine_bin(key) == bin0 && ((uint32_t)(key >> kSecShift) & (kBins1 - 1)) == bin1;
                 const unsigned long long m = __ballot(hit);
                 if (m) {
                     uint32_t basepos = 0;
                     const int leader = __ffsll((long long)m) - 1;
                     if ((int)(threadIdx.x & 63) == leader)
-                        basepos = atomicAdd(&ws.cand_count[h], (uint32_t)__popcll(m));
+                        basepos = atomicAdd(&ws.cand_count[g.H + h], (uint32_t)__popcll(m));
                     basepos = __shfl(basepos, leader, 64);
                     if (hit) {
                         const uint32_t pos = basepos + __popcll(m & ((1ull << (threadIdx.x & 63)) - 1ull));
@@ -192,12 +225,25 @@ __global__ __launch_bounds__(kSelectThreads) void k_select_sweep(Geometry g, Wor
                 atomicAdd(&gh[i], n);
         }
     }
+    if (MODE == 1) {
+        const uint32_t n = min(n_staged, (uint32_t)kStageKeys);
+        if (threadIdx.x == 0)
+            list_base = n ? atomicAdd(&ws.cand_count[h], n) : 0u;
+        __syncthreads();
+        const uint32_t at = list_base;
+        for (uint32_t i = threadIdx.x; i < n; i += kSelectThreads)
+            if (at + i < (uint32_t)kCandCap)
+                cand[at + i] = staged[i];
+    }
 }
 
 // ---------------------------------------------------------------------------------------
-// finish: one workgroup per head.  Radix-selects the low kShift1 = 40 bits (4 digits of 10 bits)
-// among the keys whose top 23 bits equal the chosen prefix: from the candidate list when it holds
-// them all, otherwise from the head's raw rows.  Writes thr[h] = fl(fl(C*C) * median).
+// finish: one workgroup per head.  Locates the first digit again; a head whose candidate list is
+// complete has its median among the list's keys (they share the digit's 17-bit prefix): radix select on
+// their low 46 bits.  After an overflow the second digit is located too and the select runs on the low
+// 36 bits of the keys MODE 2 collected, or, if even those were too many (many equal norms: a constant or
+// coarsely quantised tensor), over the head's raw rows: slow, exact, and only for such inputs.
+// Writes thr[h] = fl(fl(C*C) * median).
 // ---------------------------------------------------------------------------------------
 template <bool kFull>
 __global__ __launch_bounds__(kSelectThreads) void k_select_finish(Geometry g, WorkspaceOffsets wo, EncodeBatch batch,
@@ -209,48 +255,70 @@ __global__ __launch_bounds__(kSelectThreads) void k_select_finish(Geometry g, Wo
     __shared__ uint32_t lh[kBins1];
     __shared__ uint32_t scratch[kSelectThreads + 2];
     const int h = blockIdx.x;
-    const unsigned long long prefix = ws.state[h].prefix;  // top 23 bits, right aligned
-    uint32_t rank = ws.state[h].rank;
-    const uint32_t n_cand = ws.cand_count[h];
-    const bool from_list = n_cand <= (uint32_t)kCandCap;
-    const unsigned long long *cand = ws.cand + (size_t)h * kCandCap;
+    uint32_t rank = (uint32_t)(((uint64_t)g.B * g.T * g.n_c - 1) / 2);
+    uint32_t bin0, before0;
+    pick_bin<kBins0, kSelectThreads>(ws.hist0 + (size_t)h * kBins0, rank, scratch, bin0, before0);
+    rank -= before0;
 
-    unsigned long long low = 0;  // low-bit digits fixed so far, right aligned
-    int fixed = 0;               // number of low-part bits fixed (from the top of the 40)
-    for (int pass = 0; pass < 4; ++pass) {
-        for (int i = threadIdx.x; i < kBins1; i += kSelectThreads)
-            lh[i] = 0;
-        __syncthreads();
-        const int shift = kShift1 - 10 * (pass + 1);  // 30, 20, 10, 0
-        const unsigned long long want = (prefix << fixed) | low;  // compare key >> (shift + 10)
-        if (from_list) {
-            for (uint32_t i = threadIdx.x; i < n_cand; i += kSelectThreads) {
-                const unsigned long long key = cand[i];
-                if ((key >> (shift + 10)) == want)
-                    atomicAdd(&lh[(uint32_t)(key >> shift) & (kBins1 - 1)], 1u);
-            }
-        } else {
-            // rare path: sweep the head's rows (every batch entry), one lane per chunk
-            const int c = threadIdx.x & 31, sub = threadIdx.x >> 5;
-            for (int b = 0; b < g.B; ++b) {
-                const _Float16 *base = x + (int64_t)b * g.sb + (int64_t)h * g.sh;
-                for (int t = sub; t < g.T; t += kSelectThreads / 32) {
-                    const unsigned long long key =
-                        key_of(chunk_norm2(load_row_chunk<kFull>(base + (int64_t)t * g.st, c, g))) & kKeyMask;
-                    if ((kFull || c < g.n_c) && (key >> (shift + 10)) == want)
-                        atomicAdd(&lh[(uint32_t)(key >> shift) & (kBins1 - 1)], 1u);
+    unsigned long long median_bits;
+    if (bin0 == 0u) {
+        median_bits = 0ull;  // fp16 data: the bin holds zeros only
+    } else if (!fine_bin_is_prefix(bin0)) {
+        median_bits = 0x7ff0000000000000ull;  // not reached by finite fp16 data: nothing is flagged
+    } else {
+        unsigned long long prefix = (unsigned long long)(bin0 + kFineBase);  // key bits fixed so far, right aligned
+        int low_bits = kFineShift;
+        uint32_t n_cand = ws.cand_count[h];
+        if (n_cand > (uint32_t)kCandCap) {
+            uint32_t bin1, before1;
+            pick_bin<kBins1, kSelectThreads>(ws.hist1 + (size_t)h * kBins1, rank, scratch, bin1, before1);
+            rank -= before1;
+            prefix = (prefix << kBits1) | bin1;
+            low_bits = kSecShift;
+            n_cand = ws.cand_count[g.H + h];
+        }
+        const bool from_list = n_cand <= (uint32_t)kCandCap;
+        const unsigned long long *cand = ws.cand + (size_t)h * kCandCap;
+
+        unsigned long long low = 0;  // low-part digits fixed so far, right aligned
+        int remaining = low_bits;    // low-part bits still open
+        while (remaining > 0) {
+            const int d = remaining < 10 ? remaining : 10;
+            const int shift = remaining - d;
+            const uint32_t dmask = (1u << d) - 1u;
+            for (int i = threadIdx.x; i < kBins1; i += kSelectThreads)
+                lh[i] = 0;
+            __syncthreads();
+            const unsigned long long want = (prefix << (low_bits - remaining)) | low;  // compare key >> remaining
+            if (from_list) {
+                for (uint32_t i = threadIdx.x; i < n_cand; i += kSelectThreads) {
+                    const unsigned long long key = cand[i];
+                    if ((key >> remaining) == want)
+                        atomicAdd(&lh[(uint32_t)(key >> shift) & dmask], 1u);
+                }
+            } else {
+                // rare path: sweep the head's rows (every batch entry), one lane per chunk
+                const int c = threadIdx.x & 31, sub = threadIdx.x >> 5;
+                for (int b = 0; b < g.B; ++b) {
+                    const _Float16 *base = x + (int64_t)b * g.sb + (int64_t)h * g.sh;
+                    for (int t = sub; t < g.T; t += kSelectThreads / 32) {
+                        const unsigned long long key =
+                            key_of(chunk_norm2(load_row_chunk<kFull>(base + (int64_t)t * g.st, c, g))) & kKeyMask;
+                        if ((kFull || c < g.n_c) && (key >> remaining) == want)
+                            atomicAdd(&lh[(uint32_t)(key >> shift) & dmask], 1u);
+                    }
                 }
             }
+            __syncthreads();
+            uint32_t bin, before;
+            pick_bin<kBins1, kSelectThreads>(lh, rank, scratch, bin, before);
+            rank -= before;
+            low = (low << d) | bin;
+            remaining -= d;
         }
-        __syncthreads();
-        uint32_t bin, before;
-        pick_bin<kBins1, kSelectThreads>(lh, rank, scratch, bin, before);
-        rank -= before;
-        low = (low << 10) | bin;
-        fixed += 10;
+        median_bits = (prefix << low_bits) | low;
     }
     if (threadIdx.x == 0) {
-        const unsigned long long median_bits = (prefix << kShift1) | low;
         // threshold on squares: fl(fl(C*C) * median), C widened from fp32
         const double c = (double)C;
         const double c2 = c * c;

@@ -24,7 +24,7 @@
 // factor split into two fp16 parts (24 bits), i.e. four products per term, half of what a
 // three-part split costs on the matrix cores and a quarter of the fp32 shape's time.  A screened score is
 // within 7e-7 of the true one.  Next to its best group every lane keeps the runner-up score; a chunk whose
-// winning group is not ahead of every other group by 4e-6 is searched again over all S secondaries with
+// winning group is not ahead of every other group by 6e-6 of its score is searched again over all S secondaries with
 // plain fp32 arithmetic.  Either way the choice between secondaries is made on fp32 closed-form scores.
 //
 // Work split: a workgroup (4, 8 or 16 wave64) owns 64, 256 or 512 rows of one (b, h) segment, so the A
@@ -228,10 +228,13 @@ __device__ __forceinline__ unsigned long long wave_umax64(unsigned long long k)
     return k;
 }
 
-// Scores of the screening pass are scaled by kOperandScale^2 = 2^20.  Two groups of secondaries whose
-// screened maxima lie closer than this are not told apart by the screen: its error is below 7e-7 per
-// score (operands carried to 2^-24 each, fp32 accumulation, three fp32 additions), the band is 4e-6.
-constexpr float kScreenBand = 4.0e-6f * kOperandScale * kOperandScale;
+// Two groups of secondaries whose screened maxima lie closer than this fraction of the larger one are
+// not told apart by the screen.  Its error is below 7e-7 |q_s| per score (operands carried to 2^-24 each,
+// fp32 accumulation, three fp32 additions; 2.9e-7 measured), the best score is at least |q_s| / sqrt(2),
+// so the band is at least three times that bound on the error of the two scores compared (seven times
+// the measured value), whatever the common scale
+// (the scores of the matrix pass carry a factor kOperandScale^2 = 2^20).
+constexpr float kScreenBand = 6.0e-6f;
 
 // Exhaustive nearest-codeword search for the wave's 64 chunks (one per lane, direction u): returns
 // the chunk's code word (rq << w_idx) | k with k = p S + s of the best joint codeword; 0 for a
@@ -353,7 +356,7 @@ __device__ __forceinline__ uint32_t search_codeword(const Geometry &g, int lane,
     const float runner = fmaxf(fmaxf(fminf(my_b, ot_b), my_s), ot_s);
     const int first = (other ? ot_k : my_k) + (other ? 1 - half : half);  // candidates first + 2 t
     const bool live = !flagged && r2 != 0.0;
-    const bool unclear = live && !(top - runner >= kScreenBand);
+    const bool unclear = live && !(top - runner >= kScreenBand * top);
 
     int bs = first;
     if (live) {

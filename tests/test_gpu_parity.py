@@ -430,6 +430,36 @@ def test_median_with_many_equal_norms():
     assert stats["outliers"] == 20 * 16 + 1
 
 
+@pytest.mark.parametrize("spread", [0.004, 0.03, 0.2])
+def test_median_of_concentrated_norms(spread):
+    """Norms packed into a narrow band: the bin of the select's first digit that holds the median then
+    holds from a few per cent to most of a head's chunks, more than a workgroup stages (0.03) and more
+    than the candidate list keeps (0.004: the third sweep has to narrow it down).  Thresholds bit for
+    bit, and with them every flag word."""
+    B, H, T, S = 1, 2, 4096, 1
+    gen = torch.Generator().manual_seed(int(spread * 1e4))
+    mag = 1.0 + spread * (2.0 * torch.rand(B, H, T, 128, generator=gen) - 1.0)
+    sign = torch.where(torch.rand(B, H, T, 128, generator=gen) < 0.5, -1.0, 1.0)
+    x = (mag * sign).half()
+    x[0, 1] *= 37.0                                        # the second head in another binade
+    x[0, :, ::7, :4] *= 6.0                                # some outliers
+    sec_t, sec = _sec(4, H, S)
+    xb = _bits(x)
+    e = oracle.encode(xb, sec, rows=np.arange(0, B * H * T, 97))
+    x_dev, sec_dev = x.to(DEV), sec_t.to(DEV)
+    g = gpu_encode(x_dev, sec_dev)
+    stats = compare_encode(g, e, xb, sec)
+    print(stats, flush=True)
+    params = hq.params_for(x_dev, S)
+    ws = hq.alloc_workspace(params, DEV)
+    hq.hqmq_encode(params, x_dev, sec_dev, hq.alloc_encoded(params, DEV), ws)
+    thr = hq.hqmq_thresholds(params, ws)
+    torch.cuda.synchronize()
+    c = float(np.float32(3.0))
+    assert np.array_equal(thr.cpu().numpy().view(np.uint64), ((c * c) * e.m2).view(np.uint64))
+    assert stats["outliers"] > 0
+
+
 def test_exact_tie_structured_input():
     """Chunks like (a, a, 0, 0) sit on the boundary between several codewords when the
     secondary is the identity; whichever the GPU picks must score as the oracle's best."""
