@@ -358,18 +358,24 @@ __device__ __forceinline__ uint32_t search_codeword(const Geometry &g, int lane,
     const bool live = !flagged && r2 != 0.0;
     const bool unclear = live && !(top - runner >= kScreenBand * top);
 
+    // The 8 candidates first + 2 t in ascending order, strict comparison: the lowest s wins a tie.  Padding
+    // secondaries (zeros, s >= S) score 0 and every real one scores at least |q_s| / sqrt(2) > 0 for a
+    // non-zero chunk, so a group that won the screen never yields a padding index; the bound below only
+    // keeps the index inside the codebook should the input break the contract (non-finite values).
     int bs = first;
     if (live) {
+        const float *cq = secl + 4 * first;  // < 16 S16 entries: inside the padded table
         float bsc = -1.f;
+        int bt = 0;
 #pragma unroll
         for (int tt = 0; tt < 8; ++tt) {
-            const int sc_idx = first + 2 * tt;  // < 16 S16: inside the padded table
             float v0, v1, v2, v3;
-            const float sc = score_secondary(secl + 4 * sc_idx, u0, u1, u2, u3, v0, v1, v2, v3);
-            const bool take = (sc_idx < g.S) & (sc > bsc);  // strict: the lowest s wins a tie
+            const float sc = score_secondary(cq + 8 * tt, u0, u1, u2, u3, v0, v1, v2, v3);
+            const bool take = sc > bsc;
             bsc = take ? sc : bsc;
-            bs = take ? sc_idx : bs;
+            bt = take ? tt : bt;
         }
+        bs = min(first + 2 * bt, g.S - 1);
     }
     // the unclear chunks, one at a time: every lane scores the secondaries lane, lane + 64, ...; the key
     // orders by score, then by descending s (scores are positive, so their bit patterns order like them)
