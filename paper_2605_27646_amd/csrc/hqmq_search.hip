@@ -172,20 +172,20 @@ __device__ __forceinline__ int radius_code(double r2, float r_f, uint16_t sigma1
     return rq;
 }
 
-// Unit direction of a chunk in fp32 (zeros for a zero chunk).
+// Direction of a chunk in fp32: kOperandScale times the unit vector (zeros for a zero chunk).
 struct Direction {
     float u0, u1, u2, u3;
 };
 __device__ __forceinline__ Direction unit_direction(const half4_t xv, double r2, float r_f)
 {
-    Direction d = {0.f, 0.f, 0.f, 0.f};
-    if (r2 != 0.0) {
-        const float inv = __builtin_amdgcn_rcpf(r_f);
-        d.u0 = (float)xv[0] * inv;
-        d.u1 = (float)xv[1] * inv;
-        d.u2 = (float)xv[2] * inv;
-        d.u3 = (float)xv[3] * inv;
-    }
+    // times kOperandScale, the factor the matrix operands carry: a power of two, so every comparison
+    // between scores comes out as for the unit vector itself
+    const float inv = r2 != 0.0 ? __builtin_amdgcn_rcpf(r_f) * kOperandScale : 0.f;
+    Direction d;
+    d.u0 = (float)xv[0] * inv;
+    d.u1 = (float)xv[1] * inv;
+    d.u2 = (float)xv[2] * inv;
+    d.u3 = (float)xv[3] * inv;
     return d;
 }
 
@@ -213,7 +213,7 @@ __device__ __forceinline__ float score_secondary(const float *q, float u0, float
     v2 = fmaf(-bq, u3, fmaf(a, u2, fmaf(d, u1, -cq * u0)));
     v3 = fmaf(a, u3, fmaf(bq, u2, fmaf(-cq, u1, -d * u0)));
     const float a0 = fabsf(v0), a1 = fabsf(v1), a2 = fabsf(v2), a3 = fabsf(v3);
-    return fmaxf(fmaxf(fmaxf(a0, a1), fmaxf(a2, a3)), 0.5f * (((a0 + a1) + a2) + a3));
+    return fmaxf(fmaxf(fmaxf(fmaxf(a0, a1), a2), a3), 0.5f * (((a0 + a1) + a2) + a3));  // two v_max3
 }
 
 // Maximum of a 64-bit key over the wave (every lane gets it).
@@ -236,7 +236,8 @@ __device__ __forceinline__ unsigned long long wave_umax64(unsigned long long k)
 // (the scores of the matrix pass carry a factor kOperandScale^2 = 2^20).
 constexpr float kScreenBand = 6.0e-6f;
 
-// Exhaustive nearest-codeword search for the wave's 64 chunks (one per lane, direction u): returns
+// Exhaustive nearest-codeword search for the wave's 64 chunks (one per lane, direction u as
+// unit_direction returns it): returns
 // the chunk's code word (rq << w_idx) | k with k = p S + s of the best joint codeword; 0 for a
 // flagged chunk (also to be passed for a lane without a chunk) and for a zero chunk (r2 == 0).
 // Called by all 64 lanes.  amat / secl: the head's A operands and secondaries in LDS.
@@ -258,8 +259,7 @@ __device__ __forceinline__ uint32_t search_codeword(const Geometry &g, int lane,
     // slots [h l h l | h l h l]; chunk 32 half + col is its own, the other one its partner's (lane ^ 32)
     half8_t bop[2];
     {
-        const Parts2 p0 = split2(u0 * kOperandScale), p1 = split2(u1 * kOperandScale);
-        const Parts2 p2 = split2(u2 * kOperandScale), p3 = split2(u3 * kOperandScale);
+        const Parts2 p0 = split2(u0), p1 = split2(u1), p2 = split2(u2), p3 = split2(u3);
         const uint32_t k0 = pack2(p0.h, p0.l), k1 = pack2(p1.h, p1.l), k2 = pack2(p2.h, p2.l), k3 = pack2(p3.h, p3.l);
         const uint32_t own_a = half ? k2 : k0, own_b = half ? k3 : k1;
         const uint32_t snd_a = half ? k0 : k2, snd_b = half ? k1 : k3;
