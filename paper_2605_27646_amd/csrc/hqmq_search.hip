@@ -195,6 +195,17 @@ typedef float float16_t __attribute__((ext_vector_type(16)));
 struct Parts2 {
     _Float16 h, l;
 };
+// Hides how an fp32 value was computed.  split2 needs it: left to itself the compiler folds the
+// multiplication that produced x into one of the two conversions (v_fma_mixlo_f16 rounds the exact product
+// once) and converts the rounded x for the other (rounded twice); where x sits on the midpoint between two
+// fp16 values the two disagree by one fp16 step and h + l misses x by 2^-11 |x|.  Seen once in 786,432
+// chunks; harmless only when the product is exact (a scaling by a power of two).
+__device__ __forceinline__ float opaque(float x)
+{
+    asm volatile("" : "+v"(x));
+    return x;
+}
+// x: a value that went through opaque(), or an exact scaling of one.
 __device__ __forceinline__ Parts2 split2(float x)
 {
     Parts2 p;
@@ -253,7 +264,7 @@ constexpr float kScreenBand = 6.0e-6f;
 __device__ __forceinline__ uint32_t search_codeword(const Geometry &g, int lane, const Direction u, bool flagged,
                                                     double r2, int rq, const uint4 *amat, const float *secl)
 {
-    const float u0 = u.u0, u1 = u.u1, u2 = u.u2, u3 = u.u3;
+    const float u0 = opaque(u.u0), u1 = opaque(u.u1), u2 = opaque(u.u2), u3 = opaque(u.u3);
     const int half = lane >> 5;
     // B operands: lane (col, half) supplies components 2 half, 2 half + 1 of chunk 32 j + col in the
     // slots [h l h l | h l h l]; chunk 32 half + col is its own, the other one its partner's (lane ^ 32)
@@ -463,7 +474,7 @@ __global__ __launch_bounds__(kThreads) void k_prepare_operands(Geometry g, Works
             return (k == 0) ? -d : (k == 1) ? -c : (k == 2) ? bq : a;
         };
         const float va = entry(2 * kh), vb = entry(2 * kh + 1);
-        const Parts2 pa = split2(va * kOperandScale), pb = split2(vb * kOperandScale);
+        const Parts2 pa = split2(opaque(va) * kOperandScale), pb = split2(opaque(vb) * kOperandScale);
         dst[idx] = make_uint4(pack2(pa.h, pa.h), pack2(pa.l, pa.l), pack2(pb.h, pb.h), pack2(pb.l, pb.l));
     }
 

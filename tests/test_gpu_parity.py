@@ -513,6 +513,16 @@ def test_codebook_with_nearly_equal_secondaries():
     assert stats["near_ties"] > 100
 
 
+def test_direction_component_on_a_half_precision_midpoint():
+    """Regression: the matrix pass splits every direction component into two fp16 parts; both must be
+    taken from the same fp32 value.  Row 630 of this tensor holds a chunk whose fourth component, scaled, is
+    exactly halfway between two fp16 values; a build whose two conversions rounded it differently ranked
+    the runner-up codeword (6e-5 behind) first."""
+    x = _lognormal_tensor(2, 3, 4096, seed=582616, sigma_g=0.7)
+    stats, e, g = _roundtrip(x, 3, b_r=4, Cmul=1.5, seed=60, check_decode=False)
+    assert stats["index_mismatch_in_near_ties"] <= stats["near_ties"]
+
+
 def test_extreme_magnitudes():
     x = _lognormal_tensor(1, 2, 64, seed=9).float()
     x[0, 0, :8] *= 6e-6                                 # subnormal fp16 territory
