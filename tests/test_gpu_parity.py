@@ -128,15 +128,13 @@ def test_outlier_heavy_laws_reduced_length(name):
 # full-size tensor in the launch configuration the bench times
 # ---------------------------------------------------------------------------------------
 
-def test_llama3_8b_32k_layer_sampled():
-    """One full [1, 8, 32768, 128] tensor with S = 256: everything that is O(n) in the oracle
-    (norms, medians, masks, offsets, payload, scales) is compared on all rows; the exhaustive
-    search on a sample of token rows (first, last, seeded random) of every head."""
+def test_llama3_8b_32k_layer_every_row():
+    """One full [1, 8, 32768, 128] tensor with S = 256, every step on every row: norms, medians, masks,
+    offsets, payload, scales, radius codes, the exhaustive search of all 8.4 M chunks, and the decode of
+    both sides' bytes (the oracle takes about 20 s on 16 threads)."""
     wl = workloads.WORKLOADS["llama3_8b_32k"]
     x = workloads.make_tensor(wl, 3, 0, "cpu")
-    rows = workloads.sample_rows(wl, 48, 48, 160, seed=1).numpy()
-    print(f"llama3 8b 32k layer 3 K: searching {int(rows.sum())} of {rows.size} rows on the CPU", flush=True)
-    stats, e, g = _roundtrip(x, wl.S, wl.b_r, rows=rows, check_decode=True)
+    stats, e, g = _roundtrip(x, wl.S, wl.b_r, check_decode=True)
     assert 0.005 < stats["outliers"] / e.flag.size < 0.03
     assert stats["near_ties"] < 1e-3 * stats["chunks"]
 
