@@ -14,9 +14,9 @@
 // VALU instructions per pair.  The search stays exhaustive over all S secondaries and, through
 // the closed form, over all 24 primaries.
 //
-// On gfx950 MFMA and VALU instructions of one SIMD largely take turns (measured: their times add up
-// to within a few per cent), so the inner loop is costed as the matrix time plus 3 to 4 cycles per VALU
-// instruction, and the VALU count per (chunk, secondary) pair is what is minimised: the running argmax
+// The kernel is bound by VALU issue: with four waves on a SIMD the matrix products run behind the other
+// waves' vector work (counters: the VALU is busy for the whole kernel, the MFMA pipe for a quarter of it),
+// so the VALU count per (chunk, secondary) pair is what is minimised: the running argmax
 // is kept per group of 16 secondaries (8 per lane) with v_max3 chains, one compare-and-select per
 // group, and the winner inside the winning group is found afterwards by re-scoring its candidates.
 //
@@ -291,8 +291,8 @@ __device__ __forceinline__ uint32_t search_codeword(const Geometry &g, int lane,
     const uint4 *arow = amat + lane;
     half8_t a0 = __builtin_bit_cast(half8_t, arow[0]), a1 = __builtin_bit_cast(half8_t, arow[64]);
     // the product of (tile 0, chunk slot 0) of the next group is issued before the arithmetic on the last
-    // product of this one: MFMA and VALU do not overlap on a SIMD, but a VALU instruction right behind
-    // the MFMA it depends on idles for the depth of the matrix pipeline
+    // product of this one: a VALU instruction right behind the MFMA it depends on idles for the depth of
+    // the matrix pipeline
     float16_t ahead = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, bop[0], zero16, 0, 0, 0);
     for (int grp = 0; grp < g.S16; ++grp) {
         // the next group's operands replace this group's as soon as their last product is issued (the
