@@ -30,8 +30,8 @@ PEAK_VALU_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12   # plain (unpacked) VALU lane-oper
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs, each scaled
 # by a plain copy of known size in the same run); figures and commands in profiles/hbm_traffic_*.txt
-MEASURED_TRAFFIC_BYTES = {"llama3_8b_32k": {"k_search": 92.1e6, "k_decode": 91.4e6},
-                          "mha32_d96_8k": {"k_search": 75.4e6, "k_decode": 68.5e6},
+MEASURED_TRAFFIC_BYTES = {"llama3_8b_32k": {"k_search": 92.2e6, "k_decode": 91.4e6},
+                          "mha32_d96_8k": {"k_search": 75.3e6, "k_decode": 68.5e6},
                           "gqa8_d64_32k": {"k_search": 48.5e6, "k_decode": 47.6e6}}
 
 
