@@ -13,7 +13,8 @@
  * Conventions common to every entry point
  *   - extern "C", plain pointers and sizes.  "HOST" / "DEVICE" says where a pointer lives.
  *   - The caller owns every buffer.  The library allocates nothing, keeps no global state
- *     besides the last HIP error code, and only enqueues work on the given HIP stream
+ *     besides the last HIP error code of each thread and a set-up flag per device (see hqmq_init),
+ *     and only enqueues work on the given HIP stream
  *     (hipStream_t passed as void*; NULL = the default stream).  Calls return as soon as the
  *     work is enqueued; results are valid once the stream has been synchronised.
  *   - Return value: HQMQ_OK or a negative HQMQ_ERR_* code.  Nothing is enqueued when an
@@ -41,6 +42,10 @@
 extern "C" {
 #endif
 
+/* Largest secondary codebook every entry point takes (the paper sweeps S = 24 .. 192; the search keeps
+ * a head's codebook and its matrix operands in a CU's LDS, which 512 entries fill). */
+#define HQMQ_MAX_S 512
+
 #define HQMQ_OK 0
 #define HQMQ_ERR_INVALID_ARG (-1)      /* null pointer, non-positive size, misaligned pointer or stride */
 #define HQMQ_ERR_UNSUPPORTED (-2)      /* D > 128 (hqmq_attend: D not 64, 96 or 128), S outside 1..512, b_r outside 1..8, C not a positive finite number */
@@ -49,9 +54,13 @@ extern "C" {
 
 /* hqmq_params.flags */
 #define HQMQ_FLAG_NO_OUTLIERS 1u /* skip the median and the extraction: no chunk is flagged */
+#define HQMQ_FLAG_CHECK_FINITE 2u /* encode: report an input that holds an infinity or a NaN in the status word \
+                                     (the encoded result of such a tensor is undefined, but every access stays  \
+                                     in bounds and every index inside the codebook) */
 
 /* bits of the device-side status word */
 #define HQMQ_STATUS_OUTLIER_OVERFLOW 1u /* more outliers than outlier_capacity: payload truncated */
+#define HQMQ_STATUS_NONFINITE 2u        /* HQMQ_FLAG_CHECK_FINITE was set and x holds an infinity or a NaN */
 
 typedef struct hqmq_params {
     int32_t B, H, T, D;                   /* X is fp16 [B, H, T, D], D contiguous                  */
@@ -108,13 +117,20 @@ typedef struct hqmq_encoded {
     uint32_t *status;
 } hqmq_encoded;
 
+/* Per-device set-up for the CURRENT device (hipSetDevice): raises the dynamic-LDS limit of the search
+ * kernels.  Thread-safe and idempotent.  Every encode entry point runs it by itself on its first call
+ * on a device, so calling it is optional - except before a stream capture: the set-up is not stream
+ * work and must not happen while a capture is open, so call hqmq_init() (or run one eager encode) on the
+ * device first.  Errors: HIP. */
+int32_t hqmq_init(void);
+
 /* Secondary codebooks (App. D "Secondary codebook initialization"): for every (layer, role,
  * head) S i.i.d. standard-normal 4-vectors, normalised to unit length, drawn from a
  * counter-based generator so that entry (layer, role, head, s) depends only on the seed and
  * its linear index ((layer*2 + role)*n_kv_heads + head)*S + s.  role 0 = K, 1 = V.
  *   sec_host  HOST, out, fp32 [n_layers][2][n_kv_heads][S][4], caller-owned.
  * Pure host function (no GPU work).  Errors: INVALID_ARG (null pointer, non-positive size),
- * UNSUPPORTED (24*S > 65536). */
+ * UNSUPPORTED (S > 512: the limit of hqmq_encode and hqmq_decode). */
 int32_t hqmq_build_codebooks(uint64_t seed, int32_t n_layers, int32_t n_kv_heads, int32_t S,
                              float *sec_host);
 
@@ -129,7 +145,9 @@ int32_t hqmq_sizes(const hqmq_params *params, hqmq_size_info *out);
  * by exhaustive search over all S secondaries (24 primaries each, lowest index on ties);
  * radius code r_q = clamp(rint(r * (2^b_r - 1) / sigma), 0, 2^b_r - 1); bit packing.
  *   params            HOST.
- *   x_dev             DEVICE, in, fp16, 16-byte aligned, addressed with params strides; finite.
+ *   x_dev             DEVICE, in, fp16, 16-byte aligned, addressed with params strides; finite (the
+ *                     paper does not define the encode of an infinity or a NaN; with HQMQ_FLAG_CHECK_FINITE
+ *                     status gets HQMQ_STATUS_NONFINITE for such an input).
  *   sec_dev           DEVICE, in, fp32 [H][S][4]: the codebooks of THIS (layer, role); unit
  *                     quaternions (what hqmq_build_codebooks makes).  Components must stay below
  *                     32 in magnitude (they pass through fp16 parts scaled by 2^10).
@@ -200,10 +218,11 @@ int32_t hqmq_encode_batch_given_thresholds(const hqmq_params *params, int32_t n_
  * applied (fl(fl(C C) median(r^2)) per head, Sec. 3; +infinity with HQMQ_FLAG_NO_OUTLIERS): a
  * stream-ordered device-to-device copy of H doubles, e.g. to seed or update a caller's running
  * estimate.  slice: 0 for hqmq_encode; for hqmq_encode_batch the index of the tensor within its
- * launch group of 32.  Errors: INVALID_ARG (null / misaligned pointer, slice outside 0..31),
- * UNSUPPORTED (params), HIP. */
-int32_t hqmq_thresholds(const hqmq_params *params, const void *workspace_dev, int32_t slice,
-                        double *thr_out_dev, void *stream);
+ * launch group of 32.  workspace_bytes: the size of the caller's workspace, as passed to the encode.
+ * Errors: INVALID_ARG (null / misaligned pointer, slice outside 0..31), UNSUPPORTED (params),
+ * BUFFER_TOO_SMALL (the slice does not lie inside workspace_bytes), HIP. */
+int32_t hqmq_thresholds(const hqmq_params *params, const void *workspace_dev, uint64_t workspace_bytes,
+                        int32_t slice, double *thr_out_dev, void *stream);
 
 /* The median of a cache whose TOKEN axis is split over several shards (context-parallel serving:
  * each GPU holds a slice of T of the same (layer, role) tensor).  Sec. 3 "Median-multiplier outlier

@@ -122,6 +122,11 @@ void hqo_hamilton(const double a[4], const double b[4], double out[4])
 void hqo_primary(int p, double q[4])
 {
     int i;
+    if (p < 0 || p >= 24) { /* the group has 24 elements: any other index names none */
+        for (i = 0; i < 4; ++i)
+            q[i] = NAN;
+        return;
+    }
     if (p < 8) {
         for (i = 0; i < 4; ++i)
             q[i] = 0.0;

@@ -5,7 +5,10 @@ The product is the C-ABI library ``libhqmq.so`` (HIP kernels for gfx950, declare
 library's names and only marshal arguments.  PyTorch provides device memory and streams.
 """
 from .binding import (  # noqa: F401
+    HQMQ_FLAG_CHECK_FINITE,
     HQMQ_FLAG_NO_OUTLIERS,
+    HQMQ_MAX_S,
+    HQMQ_STATUS_NONFINITE,
     HQMQ_STATUS_OUTLIER_OVERFLOW,
     DecodeBatch,
     EncodeBatch,
@@ -28,6 +31,7 @@ from .binding import (  # noqa: F401
     hqmq_encode_batch_given_thresholds,
     hqmq_encode_given_thresholds,
     hqmq_encode_timed,
+    hqmq_init,
     hqmq_last_hip_error,
     hqmq_shard_median_pass,
     hqmq_shard_median_region,

@@ -14,7 +14,10 @@ _LIB_PATH = os.path.join(_HERE, "libhqmq.so")
 
 HQMQ_OK = 0
 HQMQ_FLAG_NO_OUTLIERS = 1
+HQMQ_FLAG_CHECK_FINITE = 2
 HQMQ_STATUS_OUTLIER_OVERFLOW = 1
+HQMQ_STATUS_NONFINITE = 2
+HQMQ_MAX_S = 512
 _ERRORS = {-1: "HQMQ_ERR_INVALID_ARG", -2: "HQMQ_ERR_UNSUPPORTED", -3: "HQMQ_ERR_BUFFER_TOO_SMALL",
            -4: "HQMQ_ERR_HIP"}
 
@@ -80,7 +83,10 @@ def _load():
                                                            C.POINTER(_Encoded), C.POINTER(C.c_uint64), C.c_void_p,
                                                            C.c_uint64, C.c_void_p]
         lib.hqmq_thresholds.restype = C.c_int32
-        lib.hqmq_thresholds.argtypes = [C.POINTER(HqmqParams), C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
+        lib.hqmq_thresholds.argtypes = [C.POINTER(HqmqParams), C.c_void_p, C.c_uint64, C.c_int32, C.c_void_p,
+                                        C.c_void_p]
+        lib.hqmq_init.restype = C.c_int32
+        lib.hqmq_init.argtypes = []
         lib.hqmq_shard_median_pass.restype = C.c_int32
         lib.hqmq_shard_median_pass.argtypes = [C.POINTER(HqmqParams), C.c_uint64, C.c_int32, C.c_void_p, C.c_void_p,
                                                C.c_uint64, C.c_void_p]
@@ -160,6 +166,11 @@ class EncodedBuffers:
 
 def hqmq_last_hip_error() -> int:
     return int(_load().hqmq_last_hip_error())
+
+
+def hqmq_init() -> None:
+    """Per-device set-up of the library for torch's current device (optional except before a stream capture)."""
+    _check(_load().hqmq_init(), "hqmq_init")
 
 
 def hqmq_build_codebooks(seed: int, n_layers: int, n_kv_heads: int, S: int) -> torch.Tensor:
@@ -258,8 +269,8 @@ def hqmq_encode_given_thresholds(params: HqmqParams, x: torch.Tensor, sec: torch
 def hqmq_thresholds(params: HqmqParams, workspace: torch.Tensor, slice_index: int = 0, stream=None) -> torch.Tensor:
     """Device fp64 [H]: the thresholds the last encode on this workspace (slice) applied."""
     out = torch.empty(params.H, dtype=torch.float64, device=workspace.device)
-    rc = _load().hqmq_thresholds(C.byref(params), workspace.data_ptr(), int(slice_index), out.data_ptr(),
-                                 _stream_ptr(stream))
+    rc = _load().hqmq_thresholds(C.byref(params), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                 int(slice_index), out.data_ptr(), _stream_ptr(stream))
     _check(rc, "hqmq_thresholds")
     return out
 

@@ -1,13 +1,40 @@
 // C ABI of the HQMQ library (declared in include/hqmq.h): argument validation, workspace
 // carve-up and the stream-ordered kernel sequences.  No allocation, no synchronisation.
+#include <atomic>
 #include <cmath>
 #include <cstring>
+#include <mutex>
 
 #include "hqmq_device.h"
 
 namespace hqmq {
 
 static thread_local int32_t g_last_hip_error = 0;
+
+// Per-device set-up, done once: the search kernels' LDS limit.  The flag of a device is set only after its
+// set-up succeeded, so a failed attempt is retried by the next call; devices beyond the table are set up
+// on every call.
+constexpr int kMaxDevices = 64;
+static std::atomic<bool> g_device_ready[kMaxDevices];
+static std::mutex g_setup_mutex;
+
+static hipError_t ensure_device_setup()
+{
+    int device = 0;
+    hipError_t err = hipGetDevice(&device);
+    if (err != hipSuccess)
+        return err;
+    const bool tracked = device >= 0 && device < kMaxDevices;
+    if (tracked && g_device_ready[device].load(std::memory_order_acquire))
+        return hipSuccess;
+    std::lock_guard<std::mutex> lock(g_setup_mutex);
+    if (tracked && g_device_ready[device].load(std::memory_order_relaxed))
+        return hipSuccess;
+    err = prepare_search_kernels();
+    if (err == hipSuccess && tracked)
+        g_device_ready[device].store(true, std::memory_order_release);
+    return err;
+}
 
 static inline uint64_t align_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
 
@@ -20,7 +47,7 @@ static int index_bits(int S)
 }
 
 // Largest S the search kernel's LDS tables are sized for (paper sweeps S up to 192).
-constexpr int kMaxS = 512;
+constexpr int kMaxS = HQMQ_MAX_S;
 
 static int32_t check_params(const hqmq_params *p)
 {
@@ -72,6 +99,7 @@ static Geometry make_geometry(const hqmq_params *p)
     for (int j = 0; j < 16; ++j)
         if ((1 << j) == p->S)
             g.log2_S = j;
+    g.check_finite = (p->flags & HQMQ_FLAG_CHECK_FINITE) ? 1 : 0;
     g.search_rows = search_rows_for(p->T, g.S16, g.D, g.row_words);
     g.n_search_blocks_per_seg = (uint32_t)((p->T + g.search_rows - 1) / g.search_rows);
     return g;
@@ -146,6 +174,12 @@ static int32_t hip_failed(hipError_t err)
 using namespace hqmq;
 
 extern "C" int32_t hqmq_last_hip_error(void) { return g_last_hip_error; }
+
+extern "C" int32_t hqmq_init(void)
+{
+    const hipError_t err = ensure_device_setup();
+    return err == hipSuccess ? HQMQ_OK : hip_failed(err);
+}
 
 extern "C" int32_t hqmq_sizes(const hqmq_params *params, hqmq_size_info *out)
 {
@@ -226,7 +260,6 @@ static int32_t encode_impl(const hqmq_params *params, int32_t n_tensors, const v
     if (l.total >= (1ull << 32))
         return HQMQ_ERR_UNSUPPORTED;  // 32-bit offsets inside a slice
     const WorkspaceOffsets wo = workspace_offsets(l);
-
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool no_outliers = (params->flags & HQMQ_FLAG_NO_OUTLIERS) != 0;
     if (thr_given) {
@@ -235,6 +268,11 @@ static int32_t encode_impl(const hqmq_params *params, int32_t n_tensors, const v
         for (int32_t i = 0; i < n_tensors; ++i)
             if (!thr_given[i] || misaligned(thr_given[i], 8))
                 return HQMQ_ERR_INVALID_ARG;
+    }
+    {
+        const hipError_t ready = ensure_device_setup();
+        if (ready != hipSuccess)
+            return hip_failed(ready);
     }
     auto mark = [&](int i) -> hipError_t {
         if (phase_events && phase_events[i])
@@ -335,8 +373,8 @@ extern "C" int32_t hqmq_encode_batch_given_thresholds(const hqmq_params *params,
                        stream, nullptr, thr_dev);
 }
 
-extern "C" int32_t hqmq_thresholds(const hqmq_params *params, const void *workspace_dev, int32_t slice,
-                                   double *thr_out_dev, void *stream)
+extern "C" int32_t hqmq_thresholds(const hqmq_params *params, const void *workspace_dev, uint64_t workspace_bytes,
+                                   int32_t slice, double *thr_out_dev, void *stream)
 {
     int32_t rc = check_params(params);
     if (rc != HQMQ_OK)
@@ -345,6 +383,8 @@ extern "C" int32_t hqmq_thresholds(const hqmq_params *params, const void *worksp
         misaligned(workspace_dev, 256) || misaligned(thr_out_dev, 8))
         return HQMQ_ERR_INVALID_ARG;
     const WorkspaceLayout l = workspace_layout(make_geometry(params));
+    if (workspace_bytes < l.total * ((uint64_t)slice + 1))
+        return HQMQ_ERR_BUFFER_TOO_SMALL;  // the slice lies (partly) outside the caller's workspace
     const char *src = static_cast<const char *>(workspace_dev) + l.total * (uint64_t)slice + l.thr;
     hipError_t err = hipMemcpyAsync(thr_out_dev, src, (size_t)params->H * sizeof(double), hipMemcpyDeviceToDevice,
                                     static_cast<hipStream_t>(stream));

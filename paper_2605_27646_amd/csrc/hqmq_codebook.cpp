@@ -48,8 +48,8 @@ extern "C" int32_t hqmq_build_codebooks(uint64_t seed, int32_t n_layers, int32_t
 {
     if (!sec_host || n_layers <= 0 || n_kv_heads <= 0 || S <= 0)
         return HQMQ_ERR_INVALID_ARG;
-    if (24ll * S > 65536)
-        return HQMQ_ERR_UNSUPPORTED;
+    if (S > HQMQ_MAX_S)
+        return HQMQ_ERR_UNSUPPORTED;  // the same limit as hqmq_encode / hqmq_decode
     const Stream stream(seed);
     const uint64_t entries = static_cast<uint64_t>(n_layers) * 2u * n_kv_heads * S;
     for (uint64_t e = 0; e < entries; ++e) {

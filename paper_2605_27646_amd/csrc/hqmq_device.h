@@ -53,6 +53,7 @@ struct Geometry {
     float inv_L;          // 1 / (2^b_r - 1)
     int32_t log2_S;       // log2(S) when S is a power of two, else -1
     float inv_S;          // (1/S)(1 + 2^-18): uint(float(k) * inv_S) == k / S for every k < 48 S, S <= 512
+    int32_t check_finite;  // HQMQ_FLAG_CHECK_FINITE: the search reports chunks holding an infinity or a NaN in the status word
     int32_t search_rows;               // rows per search workgroup (kSearchRowsSmall or kSearchRowsLarge)
     uint32_t n_search_blocks_per_seg;  // ceil(T / search_rows)
 };
@@ -269,6 +270,7 @@ hipError_t launch_select_median(const Geometry &g, const WorkspaceOffsets &wo, c
                                 float C, bool skip_select, hipStream_t stream);
 hipError_t launch_shard_median_pass(const Geometry &g, const WorkspaceOffsets &wo, const EncodeBatch &batch, int pass,
                                     unsigned long long total_per_head, float C, hipStream_t stream);
+hipError_t prepare_search_kernels();  // once per device, before the first launch_search on it
 hipError_t launch_search(const Geometry &g, const WorkspaceOffsets &wo, const EncodeBatch &batch, int n_tensors,
                          hipStream_t stream);
 hipError_t launch_outlier_list(const Geometry &g, const WorkspaceOffsets &wo, const EncodeBatch &batch, int n_tensors,

@@ -391,7 +391,7 @@ __global__ __launch_bounds__(1024) void k_scan(Geometry g, WorkspaceOffsets wo, 
         enc.n_outliers[g.H] = total;
         enc.row_off[n_rows] = total;
         if ((uint64_t)total > outlier_capacity)
-            enc.status[0] = HQMQ_STATUS_OUTLIER_OVERFLOW;
+            atomicOr(enc.status, HQMQ_STATUS_OUTLIER_OVERFLOW);  // next to what the search may have reported
     }
 }
 

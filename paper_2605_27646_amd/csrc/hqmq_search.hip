@@ -545,6 +545,11 @@ __global__ __launch_bounds__(64 * kWaves) void k_search(Geometry g, WorkspaceOff
         const bool flagged = valid && (r2 > thr);
         const unsigned long long ballot = __ballot(flagged);
         const uint32_t word = half_id ? (uint32_t)(ballot >> 32) : (uint32_t)ballot;
+        if (g.check_finite) {  // uniform; an infinite or NaN element makes r2 one (exponent field all ones)
+            const bool bad = valid && ((uint32_t)(key_of(r2) >> 32) & 0x7fffffffu) >= 0x7ff00000u;
+            if (__ballot(bad) != 0ull && lane == 0)
+                atomicOr(enc.status, HQMQ_STATUS_NONFINITE);
+        }
 
         // max over the 32 lanes of the row: four DPP steps inside each 16-lane row (after each step the
         // running maxima are uniform over a block twice as large, so the mirror patterns pair the right
@@ -681,6 +686,8 @@ __global__ __launch_bounds__(64 * kWaves) void k_search_flat(Geometry g, Workspa
     for (int q = tid; q < nchunks; q += kThreadsS) {
         const int r = row_of_chunk(q, g), c = q - r * g.n_c;
         const double r2 = chunk_norm2(load_row_chunk<false>(base + (int64_t)r * g.st, c, g));
+        if (g.check_finite && ((uint32_t)(key_of(r2) >> 32) & 0x7fffffffu) >= 0x7ff00000u)
+            atomicOr(enc.status, HQMQ_STATUS_NONFINITE);  // an infinite or NaN element
         if (r2 > thr)
             atomicOr(&fword[r], 1u << c);
         else
@@ -753,6 +760,28 @@ __global__ __launch_bounds__(64 * kWaves) void k_search_flat(Geometry g, Workspa
     }
 }
 
+// The search kernels' dynamic LDS exceeds the 64 KiB a kernel gets by default once S > 208: raises the limit
+// of every variant on the current device.  Stateless; the caller (the library's per-device set-up) runs it
+// once per device, before any launch and outside any stream capture.
+hipError_t prepare_search_kernels()
+{
+    const void *variants[11] = {reinterpret_cast<const void *>(k_search_flat<16, kSearchRowsLarge>),
+                                reinterpret_cast<const void *>(k_search_flat<16, kSearchRowsHuge>),
+                                reinterpret_cast<const void *>(k_search<4, kSearchRowsSmall>),
+                                reinterpret_cast<const void *>(k_search<4, kSearchRowsLarge>),
+                                reinterpret_cast<const void *>(k_search<8, kSearchRowsSmall>),
+                                reinterpret_cast<const void *>(k_search<8, kSearchRowsLarge>),
+                                reinterpret_cast<const void *>(k_search<16, kSearchRowsLarge>),
+                                reinterpret_cast<const void *>(k_search<16, kSearchRowsHuge>),
+                                reinterpret_cast<const void *>(k_search_flat<4, kSearchRowsSmall>),
+                                reinterpret_cast<const void *>(k_search_flat<4, kSearchRowsLarge>),
+                                reinterpret_cast<const void *>(k_search_flat<8, kSearchRowsSmall>)};
+    hipError_t err = hipSuccess;
+    for (int i = 0; i < 11 && err == hipSuccess; ++i)
+        err = hipFuncSetAttribute(variants[i], hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCu);
+    return err;
+}
+
 hipError_t launch_search(const Geometry &g, const WorkspaceOffsets &wo, const EncodeBatch &batch, int n_tensors,
                          hipStream_t stream)
 {
@@ -760,31 +789,6 @@ hipError_t launch_search(const Geometry &g, const WorkspaceOffsets &wo, const En
     const bool full = g.D == 4 * kChunksPerRow;
     const int waves = search_waves_for(g.S16, g.D, g.row_words, g.search_rows);
     const size_t lds = search_lds_bytes(g.S16, g.D, g.row_words, waves, g.search_rows);
-    // more than the 64 KiB a kernel gets by default once S > 208: raise the kernels' limit, once per device
-    static bool raised[64] = {};
-    int device = 0;
-    hipError_t err = hipGetDevice(&device);
-    if (err != hipSuccess)
-        return err;
-    if (device < 0 || device >= 64 || !raised[device]) {
-        const void *variants[11] = {reinterpret_cast<const void *>(k_search_flat<16, kSearchRowsLarge>),
-                                    reinterpret_cast<const void *>(k_search_flat<16, kSearchRowsHuge>),
-                                    reinterpret_cast<const void *>(k_search<4, kSearchRowsSmall>),
-                                   reinterpret_cast<const void *>(k_search<4, kSearchRowsLarge>),
-                                   reinterpret_cast<const void *>(k_search<8, kSearchRowsSmall>),
-                                   reinterpret_cast<const void *>(k_search<8, kSearchRowsLarge>),
-                                   reinterpret_cast<const void *>(k_search<16, kSearchRowsLarge>),
-                                   reinterpret_cast<const void *>(k_search<16, kSearchRowsHuge>),
-                                   reinterpret_cast<const void *>(k_search_flat<4, kSearchRowsSmall>),
-                                   reinterpret_cast<const void *>(k_search_flat<4, kSearchRowsLarge>),
-                                   reinterpret_cast<const void *>(k_search_flat<8, kSearchRowsSmall>)};
-        for (int i = 0; i < 11 && err == hipSuccess; ++i)
-            err = hipFuncSetAttribute(variants[i], hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCu);
-        if (err != hipSuccess)
-            return err;
-        if (device >= 0 && device < 64)
-            raised[device] = true;
-    }
     hipLaunchKernelGGL(k_prepare_operands, dim3((g.S16 * kATiles * 64 + kThreads - 1) / kThreads, g.H, (unsigned)n_tensors),
                        dim3(kThreads), 0, stream, g, wo, batch);
     const bool large = g.search_rows == kSearchRowsLarge;

@@ -98,6 +98,8 @@ def compare_encode(g: GpuEncoded, e: oracle.Encoded, x_bits: np.ndarray, sec: np
     assert g.codes.shape == e.codes.shape
     k_gpu, rq_gpu = oracle.unpack_rows(g.codes[rows], e.S, e.b_r, nc)
     ok = e.flag[rows] == 0
+    # every index names a codeword (an index past 24 S could not be scored by the near-tie rule below)
+    assert (k_gpu < 24 * e.S).all(), "codeword index outside the joint codebook"
     # flagged chunks carry code 0
     assert (k_gpu[~ok] == 0).all() and (rq_gpu[~ok] == 0).all()
     assert np.array_equal(rq_gpu[ok], e.rq[rows][ok]), "radius codes differ"

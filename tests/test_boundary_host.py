@@ -27,7 +27,7 @@ def lib():
 def test_library_exports_every_declared_symbol(lib):
     header = open(os.path.join(ROOT, "include", "hqmq.h")).read()
     declared = set(re.findall(r"^(?:int32_t|void|uint64_t)\s+(hqmq_\w+)\s*\(", header, re.M))
-    assert declared == {"hqmq_build_codebooks", "hqmq_sizes", "hqmq_encode", "hqmq_encode_timed", "hqmq_encode_batch", "hqmq_encode_given_thresholds", "hqmq_encode_batch_given_thresholds", "hqmq_thresholds", "hqmq_shard_median_pass", "hqmq_shard_median_region", "hqmq_decode", "hqmq_decode_batch", "hqmq_attend", "hqmq_attend_lse", "hqmq_attend_masked", "hqmq_attend_workspace_bytes", "hqmq_last_hip_error"}
+    assert declared == {"hqmq_build_codebooks", "hqmq_sizes", "hqmq_encode", "hqmq_encode_timed", "hqmq_encode_batch", "hqmq_encode_given_thresholds", "hqmq_encode_batch_given_thresholds", "hqmq_thresholds", "hqmq_shard_median_pass", "hqmq_shard_median_region", "hqmq_decode", "hqmq_decode_batch", "hqmq_attend", "hqmq_attend_lse", "hqmq_attend_masked", "hqmq_attend_workspace_bytes", "hqmq_last_hip_error", "hqmq_init"}
     for name in declared:
         assert hasattr(lib, name), name
 
@@ -150,9 +150,11 @@ def test_encode_decode_reject_bad_arguments_without_touching_the_gpu(lib):
     assert ebg(C.byref(p), 2, ptrs, ptrs, (C.c_void_p * 2)(0x1000, None), encs, caps, 0x1000, ws2, None) == -1
     assert ebg(C.byref(p), 2, ptrs, ptrs, ptrs, encs, caps, 0x1000, ws2 - 1, None) == -3
     th = lib.hqmq_thresholds
-    assert th(C.byref(p), None, 0, 0x1000, None) == -1 and th(C.byref(p), 0x1000, 0, None, None) == -1
-    assert th(C.byref(p), 0x1000, 32, 0x1000, None) == -1 and th(C.byref(p), 0x1000, -1, 0x1000, None) == -1
-    assert th(C.byref(_params(D=132, stride_t=136)), 0x1000, 0, 0x1000, None) == -2
+    assert th(C.byref(p), None, ws, 0, 0x1000, None) == -1 and th(C.byref(p), 0x1000, ws, 0, None, None) == -1
+    assert th(C.byref(p), 0x1000, 32 * ws, 32, 0x1000, None) == -1 and th(C.byref(p), 0x1000, ws, -1, 0x1000, None) == -1
+    assert th(C.byref(_params(D=132, stride_t=136)), 0x1000, ws, 0, 0x1000, None) == -2
+    assert th(C.byref(p), 0x1000, ws - 1, 0, 0x1000, None) == -3     # slice 0 does not fit the workspace
+    assert th(C.byref(p), 0x1000, 3 * ws, 3, 0x1000, None) == -3     # slice 3 needs four slices
     sm = lib.hqmq_shard_median_pass
     own = 1024 * 32
     assert sm(C.byref(p), own, 0, None, 0x1000, ws, None) == -1 and sm(C.byref(p), own, 0, 0x1000, None, ws, None) == -1
@@ -219,6 +221,45 @@ def test_build_codebooks_matches_the_oracles_generator(lib):
     assert lib.hqmq_build_codebooks(0, 1, 1, 4, None) == -1
     buf = (C.c_float * 16)()
     assert lib.hqmq_build_codebooks(0, 1, 1, 3000, buf) == -2
+    # one limit on S in every entry point: what the codebook call accepts, the encode takes
+    big = (C.c_float * (2 * 4 * (hq.HQMQ_MAX_S + 1)))()   # [1 layer][2 roles][1 head][S][4]
+    assert lib.hqmq_build_codebooks(0, 1, 1, hq.HQMQ_MAX_S, big) == 0
+    assert lib.hqmq_build_codebooks(0, 1, 1, hq.HQMQ_MAX_S + 1, big) == -2
+    hq.hqmq_sizes(_params(S=hq.HQMQ_MAX_S))
+    with pytest.raises(hq.HqmqError):
+        hq.hqmq_sizes(_params(S=hq.HQMQ_MAX_S + 1))
+    header = open(os.path.join(ROOT, "include", "hqmq.h")).read()
+    assert int(re.search(r"#define HQMQ_MAX_S (\d+)", header).group(1)) == hq.HQMQ_MAX_S
+
+
+def test_host_entry_points_from_several_threads(lib):
+    """The library keeps no state that distinct callers share (besides a per-device set-up flag): the
+    host-side calls give every thread the same answers as a single thread, and the last-HIP-error word is
+    per thread."""
+    import threading
+    want_info = hq.hqmq_sizes(_params())
+    want_sec = hq.hqmq_build_codebooks(3, 1, 2, 24)
+    errors = []
+
+    def worker(seed):
+        try:
+            for i in range(200):
+                info = hq.hqmq_sizes(_params())
+                assert bytes(info) == bytes(want_info)
+                good = binding._Encoded(0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000)
+                assert lib.hqmq_encode(C.byref(_params()), 0x1008, 0x1000, C.byref(good), 0, 0x1000,
+                                       int(info.workspace_bytes), None) == -1
+                if i % 50 == 0:
+                    assert torch.equal(hq.hqmq_build_codebooks(3, 1, 2, 24), want_sec)
+                assert lib.hqmq_last_hip_error() == 0
+        except Exception as exc:       # noqa: BLE001 - reported by the main thread
+            errors.append(exc)
+    threads = [threading.Thread(target=worker, args=(k,)) for k in range(8)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
 
 
 def test_binding_refuses_host_tensors(lib):

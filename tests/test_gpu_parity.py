@@ -67,6 +67,8 @@ def _lognormal_tensor(B, H, T, seed, sigma_g=0.5, D=128):
     (1, 1, 130, 5, 6),         # S not a multiple of 4 (padded MFMA rows)
     (1, 1, 64, 1, 6),          # S = 1: the codebook is a rotated 24-cell
     (1, 1, 96, 192, 6),        # paper's s192_r6
+    (1, 2, 150, 96, 4),        # paper's s96_r4
+    (2, 1, 90, 48, 4),         # paper's s48_r4
     (1, 1, 70, 256, 6),        # S of the headline workload
     (1, 1, 40, 512, 8),        # largest supported S and b_r
 ])
@@ -198,7 +200,7 @@ def test_llama3_8b_32k_in_the_bench_launch_configuration():
 def test_other_workloads_full_size(name, layer, role):
     """One full-size tensor of each remaining workload, as the library is launched on it: every step on
     every row (about 10 s of oracle time each), except for the 128k-token tensor, whose search is compared
-    on a sample of token rows of every head (all its O(n) results still on every row)."""
+    on a sample of token rows of every head (all its O(n) results, and its decode, still on every row)."""
     wl = workloads.WORKLOADS[name]
     x = workloads.make_tensor(wl, layer, role, "cpu")
     rows = None if name != "llama3_70b_128k" else workloads.sample_rows(wl, 16, 16, 64, seed=2).numpy()
@@ -207,13 +209,12 @@ def test_other_workloads_full_size(name, layer, role):
     stats, e, g = _roundtrip(x, wl.S, wl.b_r, rows=rows, check_decode=(name != "llama3_70b_128k"))
     assert stats["near_ties"] < 1e-3 * stats["chunks"]
     if name == "llama3_70b_128k":
-        # decode parity on the sampled rows only (the full 33.5 M-chunk comparison is done for the
-        # smaller shapes): both decoders on the GPU-encoded bytes
+        # decode parity on every row: both decoders on the GPU-encoded bytes (the oracle's own encoding has
+        # codes on the sampled rows only)
         want, r_hat = oracle.decode(g.codes, g.sigma, g.flags, g.row_off, g.outliers, _sec(0, wl.H, wl.S)[1],
                                     wl.B, wl.H, wl.T, wl.b_r, True)
         got = gpu_decode(g.params, g.bufs, _sec(0, wl.H, wl.S)[0].to(DEV), x.to(DEV))
-        sel = np.flatnonzero(rows)
-        compare_decode(got.reshape(-1, 128)[sel], want.reshape(-1, 128)[sel], r_hat[sel], e.flag[sel])
+        compare_decode(got, want, r_hat, e.flag)
 
 
 # ---------------------------------------------------------------------------------------
@@ -520,7 +521,12 @@ def test_direction_component_on_a_half_precision_midpoint():
     the runner-up codeword (6e-5 behind) first."""
     x = _lognormal_tensor(2, 3, 4096, seed=582616, sigma_g=0.7)
     stats, e, g = _roundtrip(x, 3, b_r=4, Cmul=1.5, seed=60, check_decode=False)
-    assert stats["index_mismatch_in_near_ties"] <= stats["near_ties"]
+    # the chunk in question has a gap of 6e-5, far from a near-tie: the comparison inside _roundtrip
+    # rejects any index that differs at such a gap; what is left may only differ inside near-ties
+    k_gpu, _ = oracle.unpack_rows(g.codes, 3, 4, 32)
+    differs = (e.flag == 0) & (k_gpu != e.k)
+    assert not (differs & ((e.best - e.second) >= 1e-6)).any()
+    assert int(differs.sum()) == stats["index_mismatch_in_near_ties"] <= stats["near_ties"]
 
 
 def test_extreme_magnitudes():
@@ -730,6 +736,90 @@ def test_batched_incremental_encode_equals_single_calls():
         assert torch.equal(a.n_outliers, b.n_outliers)
         assert torch.equal(a.sigma.view(torch.int16), b.sigma.view(torch.int16))
         assert torch.equal(a.outliers[:total].view(torch.int16), b.outliers[:total].view(torch.int16))
+
+
+@pytest.mark.parametrize("D", [128, 96])
+def test_check_finite_flag_reports_infinities_and_nans(D):
+    """The paper does not define the encode of a non-finite value; the library's contract is a status bit
+    when HQMQ_FLAG_CHECK_FINITE is set, in every mode of the encode (own median, extraction off, supplied
+    thresholds), and code words that stay inside the codebook so that a decode of the result is safe."""
+    B, H, T, S = 1, 3, 700, 48
+    clean = _lognormal_tensor(B, H, T, seed=31, D=D)
+    sec_t, sec = _sec(2, H, S)
+    sec_dev = sec_t.to(DEV)
+    CF, NF = hq.HQMQ_FLAG_CHECK_FINITE, hq.HQMQ_STATUS_NONFINITE
+    # finite input: the flag changes nothing, and the result is the oracle's
+    stats, e, g = _roundtrip(clean, S, seed=2, flags=CF)
+    plain = gpu_encode(clean.to(DEV), sec_dev, flags=0)
+    assert g.status == 0 and plain.status == 0
+    for f in ("codes", "sigma", "flags", "row_off", "n_out", "outliers"):
+        assert np.array_equal(getattr(g, f), getattr(plain, f)), f
+    nc = -(-D // 4)
+    for what in ("inf", "nan", "both"):
+        x = clean.clone()
+        if what in ("inf", "both"):
+            x[0, 1, 333, 5] = float("-inf")
+        if what in ("nan", "both"):
+            x[0, 2, 699, D - 1] = float("nan")
+        xd = x.to(DEV)
+        for flags in (CF, CF | hq.HQMQ_FLAG_NO_OUTLIERS):
+            g = gpu_encode(xd, sec_dev, flags=flags)
+            assert g.status & NF, (what, flags)
+            k, _ = oracle.unpack_rows(g.codes, S, 6, nc)
+            assert (k < 24 * S).all()
+            gpu_decode(g.params, g.bufs, sec_dev, xd)          # stays in bounds, whatever it returns
+        for flags in (0, hq.HQMQ_FLAG_NO_OUTLIERS):
+            assert not (gpu_encode(xd, sec_dev, flags=flags).status & NF)   # only reported on request
+        # supplied thresholds
+        params = hq.params_for(xd, S, 6, 3.0, CF)
+        bufs = hq.alloc_encoded(params, DEV, B * H * T * nc)
+        thr = torch.full((H,), 50.0, dtype=torch.float64, device=DEV)
+        hq.hqmq_encode_given_thresholds(params, xd, sec_dev, thr, bufs, hq.alloc_workspace(params, DEV))
+        torch.cuda.synchronize()
+        assert int(bufs.status.item()) & NF
+
+
+def test_concurrent_encodes_from_two_threads():
+    """Calls on distinct buffers and streams may come from different host threads: every thread's results
+    equal those of the same calls made one after the other."""
+    import threading
+    S = 64
+    xs = [_lognormal_tensor(1, 4, 900 + 50 * i, seed=40 + i).to(DEV) for i in range(2)]
+    sec_dev = _sec(3, 4, S)[0].to(DEV)
+    want = [gpu_encode(x, sec_dev) for x in xs]
+    got = [None, None]
+    errors = []
+
+    def worker(i):
+        try:
+            stream = torch.cuda.Stream()
+            with torch.cuda.stream(stream):
+                params = hq.params_for(xs[i], S)
+                ws = hq.alloc_workspace(params, DEV)
+                for _ in range(20):
+                    bufs = hq.alloc_encoded(params, DEV)
+                    hq.hqmq_encode(params, xs[i], sec_dev, bufs, ws, stream=stream)
+                    out = torch.empty_like(xs[i])
+                    hq.hqmq_decode(params, bufs, sec_dev, out, stream=stream)
+                stream.synchronize()
+                got[i] = (bufs, out)
+        except Exception as exc:       # noqa: BLE001 - reported by the main thread
+            errors.append(exc)
+    torch.cuda.synchronize()
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    for i in range(2):
+        bufs, out = got[i]
+        assert np.array_equal(bufs.codes.cpu().numpy().view(np.uint32), want[i].codes)
+        assert np.array_equal(bufs.flags.cpu().numpy().view(np.uint32), want[i].flags)
+        assert np.array_equal(bufs.row_off.cpu().numpy().view(np.uint32), want[i].row_off)
+        assert np.array_equal(bufs.sigma.cpu().numpy().view(np.uint16), want[i].sigma)
+        ref = gpu_decode(want[i].params, want[i].bufs, sec_dev, xs[i])
+        assert np.array_equal(out.cpu().numpy().view(np.uint16), ref)
 
 
 def test_deterministic_bytes():

@@ -108,6 +108,17 @@ def test_sign_convention_ij_k():
     assert np.array_equal(oracle.hamilton(k, i), j)
 
 
+
+def test_primary_index_outside_the_group_names_no_element():
+    """2T has exactly 24 elements (App. D "The Hurwitz primary codebook"): any other index yields NaNs,
+    so a codeword index k >= 24 S can never score as a valid pick."""
+    for p in (-1, 24, 25, 39, 47):
+        assert np.isnan(oracle.primary(p)).all()
+    sec = oracle.build_codebooks(0, 1, 1, 4)[0, 0, 0]
+    x = np.array([1.0, 0.5, -0.25, 2.0], np.float16).view(np.uint16)
+    assert np.isnan(oracle.score(x, sec, 24 * 4 + 1))
+    assert np.isfinite(oracle.score(x, sec, 24 * 4 - 1))
+
 def test_2T_elements_and_order():
     P = oracle.primaries()
     assert P.shape == (24, 4)
