@@ -225,6 +225,17 @@ __device__ __forceinline__ double chunk_norm2(const half4_t v)
     return ((x0 * x0 + x1 * x1) + x2 * x2) + x3 * x3;
 }
 
+// True when one of the chunk's four fp16 values is an infinity or a NaN (exponent field all ones).  Taken
+// on the bit patterns: the build tells the compiler that no arithmetic sees a NaN, so a test on a computed
+// value could be folded away.  Adding 0x0400 to a masked exponent field carries into bit 15 exactly when the
+// field is 0x7c00.
+__device__ __forceinline__ bool chunk_nonfinite(const half4_t v)
+{
+    const uint2 raw = __builtin_bit_cast(uint2, v);
+    const uint32_t a = ((raw.x & 0x7c007c00u) + 0x04000400u) | ((raw.y & 0x7c007c00u) + 0x04000400u);
+    return (a & 0x80008000u) != 0u;
+}
+
 __device__ __forceinline__ half4_t load_chunk(const _Float16 *p)
 {
     uint2 raw = *reinterpret_cast<const uint2 *>(p);

@@ -545,8 +545,8 @@ __global__ __launch_bounds__(64 * kWaves) void k_search(Geometry g, WorkspaceOff
         const bool flagged = valid && (r2 > thr);
         const unsigned long long ballot = __ballot(flagged);
         const uint32_t word = half_id ? (uint32_t)(ballot >> 32) : (uint32_t)ballot;
-        if (g.check_finite) {  // uniform; an infinite or NaN element makes r2 one (exponent field all ones)
-            const bool bad = valid && ((uint32_t)(key_of(r2) >> 32) & 0x7fffffffu) >= 0x7ff00000u;
+        if (g.check_finite) {  // uniform
+            const bool bad = valid && chunk_nonfinite(xv);
             if (__ballot(bad) != 0ull && lane == 0)
                 atomicOr(enc.status, HQMQ_STATUS_NONFINITE);
         }
@@ -685,9 +685,10 @@ __global__ __launch_bounds__(64 * kWaves) void k_search_flat(Geometry g, Workspa
     // ---- pass 1: flags and row maxima ---------------------------------------------------------------
     for (int q = tid; q < nchunks; q += kThreadsS) {
         const int r = row_of_chunk(q, g), c = q - r * g.n_c;
-        const double r2 = chunk_norm2(load_row_chunk<false>(base + (int64_t)r * g.st, c, g));
-        if (g.check_finite && ((uint32_t)(key_of(r2) >> 32) & 0x7fffffffu) >= 0x7ff00000u)
-            atomicOr(enc.status, HQMQ_STATUS_NONFINITE);  // an infinite or NaN element
+        const half4_t xv = load_row_chunk<false>(base + (int64_t)r * g.st, c, g);
+        const double r2 = chunk_norm2(xv);
+        if (g.check_finite && chunk_nonfinite(xv))
+            atomicOr(enc.status, HQMQ_STATUS_NONFINITE);
         if (r2 > thr)
             atomicOr(&fword[r], 1u << c);
         else
