@@ -118,7 +118,7 @@ typedef struct hqmq_encoded {
 } hqmq_encoded;
 
 /* Per-device set-up for the CURRENT device (hipSetDevice): raises the dynamic-LDS limit of the search
- * kernels.  Thread-safe and idempotent.  Every encode entry point runs it by itself on its first call
+ * kernels and looks up the device address of the workspace of hqmq_encode_static.  Thread-safe and idempotent.  Every encode entry point runs it by itself on its first call
  * on a device, so calling it is optional - except before a stream capture: the set-up is not stream
  * work and must not happen while a capture is open, so call hqmq_init() (or run one eager encode) on the
  * device first.  Errors: HIP. */
@@ -163,6 +163,24 @@ int32_t hqmq_sizes(const hqmq_params *params, hqmq_size_info *out);
 int32_t hqmq_encode(const hqmq_params *params, const void *x_dev, const float *sec_dev,
                     const hqmq_encoded *enc, uint64_t outlier_capacity, void *workspace_dev,
                     uint64_t workspace_bytes, void *stream);
+
+/* hqmq_encode for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid allocation.  Identical to hqmq_encode in arguments,
+ * results and errors, except that the workspace is an array of HQMQ_STATIC_SCRATCH_BYTES inside the
+ * library's own device image (every GPU the library runs on holds one copy of it until the process ends);
+ * the call allocates and frees nothing.
+ *   - Shapes whose hqmq_sizes().workspace_bytes exceeds HQMQ_STATIC_SCRATCH_BYTES are rejected with
+ *     HQMQ_ERR_BUFFER_TOO_SMALL and nothing is enqueued (16 MiB covers H <= 48 kv heads at S = 256; the
+ *     need grows with H, S and the number of row blocks B*H*T/64).
+ *   - Every call on a GPU uses that GPU's one array: calls that overlap on one GPU (different streams or
+ *     threads) race on it and give undefined results; calls ordered on one stream are fine.  What must
+ *     start at zero is cleared by the call's first kernel, so the previous call's contents do not matter.
+ *   - hqmq_thresholds cannot read this workspace; use hqmq_encode when the thresholds are wanted.
+ *   - The array's address is looked up by the per-device set-up (hqmq_init): before a stream capture,
+ *     call hqmq_init() on the device once. */
+#define HQMQ_STATIC_SCRATCH_BYTES (16u << 20)
+int32_t hqmq_encode_static(const hqmq_params *params, const void *x_dev, const float *sec_dev,
+                           const hqmq_encoded *enc, uint64_t outlier_capacity, void *stream);
 
 /* hqmq_encode with measurement marks (the per-kernel figures of the paper's latency tables,
  * App. E / Sec. 4.10, are quoted per call; this gives the same split for the encode phases).

@@ -8,6 +8,7 @@ from .binding import (  # noqa: F401
     HQMQ_FLAG_CHECK_FINITE,
     HQMQ_FLAG_NO_OUTLIERS,
     HQMQ_MAX_S,
+    HQMQ_STATIC_SCRATCH_BYTES,
     HQMQ_STATUS_NONFINITE,
     HQMQ_STATUS_OUTLIER_OVERFLOW,
     DecodeBatch,
@@ -30,6 +31,7 @@ from .binding import (  # noqa: F401
     hqmq_encode_batch,
     hqmq_encode_batch_given_thresholds,
     hqmq_encode_given_thresholds,
+    hqmq_encode_static,
     hqmq_encode_timed,
     hqmq_init,
     hqmq_last_hip_error,

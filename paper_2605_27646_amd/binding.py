@@ -18,6 +18,7 @@ HQMQ_FLAG_CHECK_FINITE = 2
 HQMQ_STATUS_OUTLIER_OVERFLOW = 1
 HQMQ_STATUS_NONFINITE = 2
 HQMQ_MAX_S = 512
+HQMQ_STATIC_SCRATCH_BYTES = 16 << 20
 _ERRORS = {-1: "HQMQ_ERR_INVALID_ARG", -2: "HQMQ_ERR_UNSUPPORTED", -3: "HQMQ_ERR_BUFFER_TOO_SMALL",
            -4: "HQMQ_ERR_HIP"}
 
@@ -71,6 +72,9 @@ def _load():
         lib.hqmq_encode.restype = C.c_int32
         lib.hqmq_encode.argtypes = [C.POINTER(HqmqParams), C.c_void_p, C.c_void_p, C.POINTER(_Encoded),
                                     C.c_uint64, C.c_void_p, C.c_uint64, C.c_void_p]
+        lib.hqmq_encode_static.restype = C.c_int32
+        lib.hqmq_encode_static.argtypes = [C.POINTER(HqmqParams), C.c_void_p, C.c_void_p, C.POINTER(_Encoded),
+                                           C.c_uint64, C.c_void_p]
         lib.hqmq_encode_timed.restype = C.c_int32
         lib.hqmq_encode_timed.argtypes = lib.hqmq_encode.argtypes + [C.POINTER(C.c_void_p)]
         lib.hqmq_encode_given_thresholds.restype = C.c_int32
@@ -227,6 +231,19 @@ def hqmq_encode(params: HqmqParams, x: torch.Tensor, sec: torch.Tensor, enc: Enc
                              enc.outlier_capacity, workspace.data_ptr(), workspace.numel(),
                              _stream_ptr(stream))
     _check(rc, "hqmq_encode")
+
+
+def hqmq_encode_static(params: HqmqParams, x: torch.Tensor, sec: torch.Tensor, enc: EncodedBuffers,
+                       stream=None) -> None:
+    """hqmq_encode on the library's own static workspace: nothing is allocated by the call.  Shapes whose
+    workspace exceeds HQMQ_STATIC_SCRATCH_BYTES are refused; calls that overlap on one GPU race."""
+    if x.dtype != torch.float16 or not x.is_cuda or not sec.is_cuda or sec.dtype != torch.float32:
+        raise ValueError("x must be a device fp16 tensor and sec a device fp32 tensor")
+    if not sec.is_contiguous() or tuple(sec.shape) != (params.H, params.S, 4):
+        raise ValueError("sec must be contiguous [H, S, 4]")
+    rc = _load().hqmq_encode_static(C.byref(params), x.data_ptr(), sec.data_ptr(), C.byref(enc.as_struct()),
+                                    enc.outlier_capacity, _stream_ptr(stream))
+    _check(rc, "hqmq_encode_static")
 
 
 def hqmq_encode_timed(params: HqmqParams, x: torch.Tensor, sec: torch.Tensor, enc: EncodedBuffers,

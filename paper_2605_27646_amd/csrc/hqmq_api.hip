@@ -11,29 +11,55 @@ namespace hqmq {
 
 static thread_local int32_t g_last_hip_error = 0;
 
-// Per-device set-up, done once: the search kernels' LDS limit.  The flag of a device is set only after its
-// set-up succeeded, so a failed attempt is retried by the next call; devices beyond the table are set up
-// on every call.
+}  // namespace hqmq
+
+// Workspace of hqmq_encode_static, for callers that cannot allocate: every GPU the library runs on holds
+// its own copy of this array, at its own address, until the process ends.  Host code never uses the
+// array's name as an address: the per-device set-up below asks the runtime for it.
+static __device__ __align__(256) unsigned char scratch[HQMQ_STATIC_SCRATCH_BYTES];
+
+namespace hqmq {
+
+// Per-device set-up, done once: the search kernels' LDS limit and the device address of `scratch`.  The flag
+// of a device is set only after its set-up succeeded, so a failed attempt is retried by the next call;
+// devices beyond the table are set up on every call.
 constexpr int kMaxDevices = 64;
 static std::atomic<bool> g_device_ready[kMaxDevices];
+static void *g_scratch_ptr[kMaxDevices];  // written before the device's flag is set, read after it is seen
 static std::mutex g_setup_mutex;
 
-static hipError_t ensure_device_setup()
+// scratch_out: null, or receives the current device's address of the static scratch array.
+static hipError_t ensure_device_setup(void **scratch_out = nullptr)
 {
     int device = 0;
     hipError_t err = hipGetDevice(&device);
     if (err != hipSuccess)
         return err;
     const bool tracked = device >= 0 && device < kMaxDevices;
-    if (tracked && g_device_ready[device].load(std::memory_order_acquire))
-        return hipSuccess;
-    std::lock_guard<std::mutex> lock(g_setup_mutex);
-    if (tracked && g_device_ready[device].load(std::memory_order_relaxed))
-        return hipSuccess;
-    err = prepare_search_kernels();
-    if (err == hipSuccess && tracked)
-        g_device_ready[device].store(true, std::memory_order_release);
-    return err;
+    if (!(tracked && g_device_ready[device].load(std::memory_order_acquire))) {
+        std::lock_guard<std::mutex> lock(g_setup_mutex);
+        if (!(tracked && g_device_ready[device].load(std::memory_order_relaxed))) {
+            err = prepare_search_kernels();
+            if (err != hipSuccess)
+                return err;
+            void *ptr = nullptr;
+            err = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+            if (err != hipSuccess)
+                return err;
+            if (!ptr)
+                return hipErrorInvalidSymbol;
+            if (!tracked) {  // nowhere to keep it: hand it out and set up again next time
+                if (scratch_out)
+                    *scratch_out = ptr;
+                return hipSuccess;
+            }
+            g_scratch_ptr[device] = ptr;
+            g_device_ready[device].store(true, std::memory_order_release);
+        }
+    }
+    if (scratch_out)
+        *scratch_out = g_scratch_ptr[device];
+    return hipSuccess;
 }
 
 static inline uint64_t align_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
@@ -236,14 +262,17 @@ static WorkspaceOffsets workspace_offsets(const WorkspaceLayout &l)
 static int32_t encode_impl(const hqmq_params *params, int32_t n_tensors, const void *const *x_dev,
                            const float *const *sec_dev, const hqmq_encoded *enc,
                            const uint64_t *outlier_capacity, void *workspace_dev, uint64_t workspace_bytes,
-                           void *stream, void *const *phase_events, const double *const *thr_given = nullptr)
+                           void *stream, void *const *phase_events, const double *const *thr_given = nullptr,
+                           bool static_scratch = false)
 {
     int32_t rc = check_params(params);
     if (rc != HQMQ_OK)
         return rc;
-    if (n_tensors <= 0 || !x_dev || !sec_dev || !enc || !outlier_capacity || !workspace_dev)
+    if (n_tensors <= 0 || !x_dev || !sec_dev || !enc || !outlier_capacity)
         return HQMQ_ERR_INVALID_ARG;
-    if (misaligned(workspace_dev, 256))
+    if (static_scratch)  // the library's own array stands in for the caller's workspace
+        workspace_bytes = HQMQ_STATIC_SCRATCH_BYTES;
+    else if (!workspace_dev || misaligned(workspace_dev, 256))
         return HQMQ_ERR_INVALID_ARG;
     for (int32_t i = 0; i < n_tensors; ++i) {
         if (!x_dev[i] || !sec_dev[i] || misaligned(x_dev[i], 16) || misaligned(sec_dev[i], 16))
@@ -270,9 +299,12 @@ static int32_t encode_impl(const hqmq_params *params, int32_t n_tensors, const v
                 return HQMQ_ERR_INVALID_ARG;
     }
     {
-        const hipError_t ready = ensure_device_setup();
+        void *own = nullptr;
+        const hipError_t ready = ensure_device_setup(&own);
         if (ready != hipSuccess)
             return hip_failed(ready);
+        if (static_scratch)
+            workspace_dev = own;
     }
     auto mark = [&](int i) -> hipError_t {
         if (phase_events && phase_events[i])
@@ -320,6 +352,13 @@ extern "C" int32_t hqmq_encode(const hqmq_params *params, const void *x_dev, con
 {
     return encode_impl(params, 1, &x_dev, &sec_dev, enc, &outlier_capacity, workspace_dev, workspace_bytes,
                        stream, nullptr);
+}
+
+extern "C" int32_t hqmq_encode_static(const hqmq_params *params, const void *x_dev, const float *sec_dev,
+                                      const hqmq_encoded *enc, uint64_t outlier_capacity, void *stream)
+{
+    return encode_impl(params, 1, &x_dev, &sec_dev, enc, &outlier_capacity, nullptr, 0, stream, nullptr, nullptr,
+                       true);
 }
 
 extern "C" int32_t hqmq_encode_timed(const hqmq_params *params, const void *x_dev,

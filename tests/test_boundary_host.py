@@ -27,7 +27,7 @@ def lib():
 def test_library_exports_every_declared_symbol(lib):
     header = open(os.path.join(ROOT, "include", "hqmq.h")).read()
     declared = set(re.findall(r"^(?:int32_t|void|uint64_t)\s+(hqmq_\w+)\s*\(", header, re.M))
-    assert declared == {"hqmq_build_codebooks", "hqmq_sizes", "hqmq_encode", "hqmq_encode_timed", "hqmq_encode_batch", "hqmq_encode_given_thresholds", "hqmq_encode_batch_given_thresholds", "hqmq_thresholds", "hqmq_shard_median_pass", "hqmq_shard_median_region", "hqmq_decode", "hqmq_decode_batch", "hqmq_attend", "hqmq_attend_lse", "hqmq_attend_masked", "hqmq_attend_workspace_bytes", "hqmq_last_hip_error", "hqmq_init"}
+    assert declared == {"hqmq_build_codebooks", "hqmq_sizes", "hqmq_encode", "hqmq_encode_timed", "hqmq_encode_batch", "hqmq_encode_given_thresholds", "hqmq_encode_batch_given_thresholds", "hqmq_thresholds", "hqmq_shard_median_pass", "hqmq_shard_median_region", "hqmq_decode", "hqmq_decode_batch", "hqmq_attend", "hqmq_attend_lse", "hqmq_attend_masked", "hqmq_attend_workspace_bytes", "hqmq_last_hip_error", "hqmq_init", "hqmq_encode_static"}
     for name in declared:
         assert hasattr(lib, name), name
 
@@ -117,6 +117,13 @@ def test_encode_decode_reject_bad_arguments_without_touching_the_gpu(lib):
     bad = binding._Encoded(0x1002, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000)
     assert enc(C.byref(p), 0x1000, 0x1000, C.byref(bad), 0, 0x1000, ws, None) == -1         # misaligned member
     assert enc(C.byref(_params(D=132, stride_t=136)), 0x1000, 0x1000, C.byref(good), 0, 0x1000, ws, None) == -2
+    es = lib.hqmq_encode_static
+    assert es(C.byref(p), None, 0x1000, C.byref(good), 0, None) == -1                          # null x
+    assert es(C.byref(p), 0x1000, 0x1000, C.byref(bad), 0, None) == -1                         # misaligned member
+    wide = _params(H=64, stride_b=64 * 1024 * 128)                                             # 64 heads: 21 MiB of workspace
+    assert hq.hqmq_sizes(wide).workspace_bytes > hq.HQMQ_STATIC_SCRATCH_BYTES
+    assert es(C.byref(wide), 0x1000, 0x1000, C.byref(good), 0, None) == -3                     # beyond the static array
+    assert hq.hqmq_sizes(_params(H=48, stride_b=48 * 1024 * 128)).workspace_bytes <= hq.HQMQ_STATIC_SCRATCH_BYTES
     dec = lib.hqmq_decode
     assert dec(C.byref(p), C.byref(good), 0, None, 0x1000, None) == -1
     assert dec(C.byref(p), C.byref(good), 0, 0x1000, 0x1008, None) == -1
@@ -230,6 +237,7 @@ def test_build_codebooks_matches_the_oracles_generator(lib):
         hq.hqmq_sizes(_params(S=hq.HQMQ_MAX_S + 1))
     header = open(os.path.join(ROOT, "include", "hqmq.h")).read()
     assert int(re.search(r"#define HQMQ_MAX_S (\d+)", header).group(1)) == hq.HQMQ_MAX_S
+    assert "#define HQMQ_STATIC_SCRATCH_BYTES (16u << 20)" in header and hq.HQMQ_STATIC_SCRATCH_BYTES == 16 << 20
 
 
 def test_host_entry_points_from_several_threads(lib):
