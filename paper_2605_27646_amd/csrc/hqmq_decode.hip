@@ -3,17 +3,20 @@
 //
 // HBM-bound: per chunk it reads w/8 bytes of code (+ 1/8 flag, 1/16 scale, 1/8 offset) and
 // writes 8 bytes of fp16.  The kernel is shaped like a streaming copy:
-//   * small one-shot workgroups (4 wave64, 64 or 128 rows, ~14 KiB of LDS) launched in row order: the
+//   * small one-shot workgroups (4 wave64, 128 rows, ~21 KiB of LDS) launched in row order: the
 //     hardware dispatcher hands the next rows to whichever CU frees up, so the set of rows in
 //     flight is a compact window moving front to back through the tensor (good DRAM page
-//     locality, no tail from a static partition), and 8 workgroups per CU overlap one another's
+//     locality, no tail from a static partition), and 7 workgroups per CU overlap one another's
 //     load latency;
-//   * a wave takes 16 consecutive rows: their code words, flag words, scales and outlier offsets
+//   * a wave takes 32 consecutive rows: their code words, flag words, scales and outlier offsets
 //     arrive with a few fully coalesced loads and are re-distributed through LDS; every lane then
 //     owns two adjacent chunks of a row, i.e. one 16-byte store per lane and 1 KiB contiguous per
-//     wave store (rows of 128 elements: 16 such pairs per row, 4 rows per wave store; rows of 96
-//     elements have 12 pairs and the wave's 16 rows take 3 stores; rows of 64 elements have 8 pairs and a
-//     wave takes 32 rows, 4 stores again);
+//     wave store (rows of 128 elements: 16 such pairs per row, 4 rows per wave store, 8 stores in two
+//     rounds of 4; rows of 96 elements have 12 pairs and the wave's 32 rows take two rounds of 3 stores;
+//     rows of 64 elements have 8 pairs and 4 stores in one round).  The kernel is close to VALU-bound as
+//     well as HBM-bound (counters: the vector ALUs are busy for 85 % of it), so the wave's fixed work -
+//     address set-up, staging, barrier, payload window - is spread over as many rows as the register
+//     budget of one round allows;
 //   * the head's S secondaries (S*16 bytes) and the 24 primaries sit in LDS; the Hamilton product
 //     is taken per chunk (16 FMA), which keeps the workgroup small enough to be one-shot;
 //   * the outlier payloads of a wave's rows are one contiguous window of the list: requested with
@@ -51,9 +54,9 @@ struct DecodeShape {
 // (the tables with compile-time sizes first, so that their LDS addresses are immediates)
 // blockIdx.z selects the tensor of a batch (all of one shape); the descriptors travel as kernel
 // arguments, so a batch needs no device-side table.
-// kPairs: chunk pairs (8 elements) per row: 16, 12 or 8 for D = 128, 96, 64; kStageRows: rows per wave
-// (16; 32 for the short rows, so that a wave's fixed work is spread over as many bytes).
-template <bool kPow2, int kPairs, int kStageRows>
+// kPairs: chunk pairs (8 elements) per row: 16, 12 or 8 for D = 128, 96, 64; kStageRows: rows per wave (32);
+// kGroup: stores of 64 lanes x 16 bytes per round.
+template <bool kPow2, int kPairs, int kStageRows, int kGroup>
 __global__ __launch_bounds__(kDecThreads) void k_decode(Geometry g, DecodeBatch batch)
 {
     typedef DecodeShape<kPairs, kStageRows> Shape;
@@ -291,22 +294,34 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(Geometry g, DecodeBatch 
             __builtin_nontemporal_store(ov, reinterpret_cast<u32x4 *>(obase + (int64_t)r * g.st + 8 * cp));
         }
     };
-    Sub sv[kSubs];
-    uint4 ov[kSubs];
+    // Rounds of kGroup stores each, kept apart (the scheduling barrier) so that the registers of one round
+    // serve the next: the wave's fixed work - loads, staging, barrier, payload window - is spread over
+    // twice the rows of a single round at the register count of one.
 #pragma unroll
-    for (int i = 0; i < kSubs; ++i)
-        sv[i] = phase1(i);
+    for (int g0 = 0; g0 < kSubs; g0 += kGroup) {
+        Sub sv[kGroup];
+        uint4 ov[kGroup];
 #pragma unroll
-    for (int i = 0; i < kSubs; ++i)
-        ov[i] = phase2(sv[i]);
-    // the window lands in LDS only now, after all the arithmetic that does not need it
-    st_pay[lane] = pay_mine;
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        for (int i = 0; i < kGroup; ++i)
+            if (g0 + i < kSubs)
+                sv[i] = phase1(g0 + i);
 #pragma unroll
-    for (int i = 0; i < kSubs; ++i)
-        phase3(i, sv[i], ov[i]);
+        for (int i = 0; i < kGroup; ++i)
+            if (g0 + i < kSubs)
+                ov[i] = phase2(sv[i]);
+        if (g0 == 0) {
+            // the window lands in LDS only now, after the first round's arithmetic, which does not need it
+            st_pay[lane] = pay_mine;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+#pragma unroll
+        for (int i = 0; i < kGroup; ++i)
+            if (g0 + i < kSubs)
+                phase3(g0 + i, sv[i], ov[i]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
 }
 
 // Decode for head dimensions other than 128 (rows of n_c = ceil(D / 4) <= 32 chunks, ceil(n_c w / 32)
@@ -408,16 +423,16 @@ __global__ __launch_bounds__(kDecThreads) void k_decode_rows(Geometry g, DecodeB
     }
 }
 
-template <int kPairs, int kRowsW>
+template <int kPairs, int kRowsW, int kGroup>
 static void launch_tuned(const Geometry &g, const DecodeBatch &batch, int n_tensors, hipStream_t stream)
 {
     typedef DecodeShape<kPairs, kRowsW> Shape;
     const size_t lds = ((size_t)g.S * 4 + 48 * 4) * sizeof(float) + (size_t)kDecWaves * Shape::kStagePerWave * 4;
     dim3 grid((unsigned)((g.T + Shape::kRows - 1) / Shape::kRows), (unsigned)(g.B * g.H), (unsigned)n_tensors);
     if ((g.S & (g.S - 1)) == 0)
-        hipLaunchKernelGGL((k_decode<true, kPairs, kRowsW>), grid, dim3(kDecThreads), lds, stream, g, batch);
+        hipLaunchKernelGGL((k_decode<true, kPairs, kRowsW, kGroup>), grid, dim3(kDecThreads), lds, stream, g, batch);
     else
-        hipLaunchKernelGGL((k_decode<false, kPairs, kRowsW>), grid, dim3(kDecThreads), lds, stream, g, batch);
+        hipLaunchKernelGGL((k_decode<false, kPairs, kRowsW, kGroup>), grid, dim3(kDecThreads), lds, stream, g, batch);
 }
 
 hipError_t launch_decode(const Geometry &g, const DecodeBatch &batch, int n_tensors, hipStream_t stream)
@@ -425,11 +440,11 @@ hipError_t launch_decode(const Geometry &g, const DecodeBatch &batch, int n_tens
     // rows of 128, 96 or 64 elements whose strides keep every 16-byte store aligned take the tuned kernel
     const bool aligned16 = g.sb % 8 == 0 && g.sh % 8 == 0 && g.st % 8 == 0;
     if (g.D == 4 * kChunksPerRow) {
-        launch_tuned<16, 16>(g, batch, n_tensors, stream);
+        launch_tuned<16, 32, 4>(g, batch, n_tensors, stream);  // two rounds of 4 stores (one: 6-10 % slower; three, four: slower)
     } else if (aligned16 && g.D == 96) {
-        launch_tuned<12, 16>(g, batch, n_tensors, stream);  // (32 rows per wave: 6 stores per wave, measured slower)
+        launch_tuned<12, 32, 3>(g, batch, n_tensors, stream);  // two rounds of 3 stores (one round of 16 rows: 13 % slower)
     } else if (aligned16 && g.D == 64) {
-        launch_tuned<8, 32>(g, batch, n_tensors, stream);   // 4 stores per wave as at 128: 54 -> 67 % of the HBM peak
+        launch_tuned<8, 32, 4>(g, batch, n_tensors, stream);   // one round of 4 stores (64 rows in two rounds: 9 % slower)
     } else {
         const size_t lds_rows = ((size_t)g.S * 4 + 48 * 4) * sizeof(float);
         dim3 grid((unsigned)((g.T + kGeneralRows - 1) / kGeneralRows), (unsigned)(g.B * g.H), (unsigned)n_tensors);

@@ -487,7 +487,7 @@ __global__ __launch_bounds__(kThreads) void k_prepare_operands(Geometry g, Works
 // This kernel is for rows of 128 elements (32 chunks: two rows per wave); k_search_flat below takes
 // every other head dimension.
 template <int kWaves, int kRows>
-__global__ __launch_bounds__(64 * kWaves) void k_search(Geometry g, WorkspaceOffsets wo, EncodeBatch batch)
+__global__ __launch_bounds__(64 * kWaves, 4) void k_search(Geometry g, WorkspaceOffsets wo, EncodeBatch batch)
 {
     constexpr int kThreadsS = 64 * kWaves;
     const EncodeTensor &tn = batch.t[blockIdx.z];
