@@ -143,6 +143,12 @@ def max_threads() -> int:
     return int(omp.omp_get_max_threads())
 
 
+def set_threads(n: int) -> None:
+    """Number of host threads the oracle's parallel-for over rows uses from now on."""
+    omp = C.CDLL("libgomp.so.1")
+    omp.omp_set_num_threads(int(n))
+
+
 def primary(p: int) -> np.ndarray:
     q = np.zeros(4)
     lib().hqo_primary(int(p), q)
