@@ -338,14 +338,29 @@ class EncodeBatch:
         self.workspace = workspace
 
 
+class ThresholdBatch:
+    """Marshalled threshold pointers of hqmq_encode_batch_given_thresholds for one EncodeBatch, built once and
+    reusable across calls (a generation loop appends with the same buffers every step)."""
+
+    def __init__(self, batch: "EncodeBatch", thrs):
+        if len(thrs) != batch.n:
+            raise ValueError("one threshold tensor per batch entry")
+        for t in thrs:
+            if not t.is_cuda or t.dtype != torch.float64 or not t.is_contiguous() or t.numel() != batch.params.H:
+                raise ValueError("thresholds must be contiguous device fp64 tensors of H entries")
+        self.keep = list(thrs)
+        self.n = batch.n
+        self.ptrs = (C.c_void_p * batch.n)(*[t.data_ptr() for t in thrs])
+
+
 def hqmq_encode_batch_given_thresholds(batch: "EncodeBatch", thrs, stream=None) -> None:
-    """hqmq_encode_batch with one caller-supplied threshold vector (device fp64 [H]) per tensor."""
-    if len(thrs) != batch.n:
+    """hqmq_encode_batch with one caller-supplied threshold vector (device fp64 [H]) per tensor: a list of
+    tensors, or a ThresholdBatch built from one."""
+    if not isinstance(thrs, ThresholdBatch):
+        thrs = ThresholdBatch(batch, thrs)
+    if thrs.n != batch.n:
         raise ValueError("one threshold tensor per batch entry")
-    for t in thrs:
-        if not t.is_cuda or t.dtype != torch.float64 or not t.is_contiguous() or t.numel() != batch.params.H:
-            raise ValueError("thresholds must be contiguous device fp64 tensors of H entries")
-    ptrs = (C.c_void_p * batch.n)(*[t.data_ptr() for t in thrs])
+    ptrs = thrs.ptrs
     ws = batch.workspace
     rc = _load().hqmq_encode_batch_given_thresholds(C.byref(batch.params), batch.n, batch.x, batch.sec, ptrs,
                                                     batch.enc, batch.cap, ws.data_ptr(),

@@ -327,6 +327,26 @@ static int32_t encode_impl(const hqmq_params *params, int32_t n_tensors, const v
         hipError_t err = first == 0 ? mark(0) : hipSuccess;
         if (err != hipSuccess)
             return hip_failed(err);
+        // A tensor of a few rows whose thresholds are known beforehand (appended tokens, extraction off)
+        // takes two launches: the fused search, then one workgroup per tensor for the outlier list.
+        const uint64_t n_rows_t = (uint64_t)g.B * g.H * g.T;
+        const uint64_t n_blocks_t = (uint64_t)g.B * g.H * g.n_search_blocks_per_seg;
+        const bool fused = (no_outliers || thr_given != nullptr) && n_rows_t <= (uint64_t)kSmallListRows &&
+                           n_blocks_t <= (uint64_t)kSmallListBlocks && search_fused_available(g);
+        if (fused) {
+            err = mark(1);
+            if (err == hipSuccess)
+                err = launch_search_fused(g, wo, batch, n, st);
+            if (err == hipSuccess)
+                err = mark(2);
+            if (err == hipSuccess)
+                err = launch_outlier_list_small(g, wo, batch, n, st);
+            if (err == hipSuccess)
+                err = mark(3);
+            if (err != hipSuccess)
+                return hip_failed(err);
+            continue;
+        }
         err = launch_select_median(g, wo, batch, n, params->C, no_outliers || thr_given != nullptr, st);
         if (err == hipSuccess)
             err = mark(1);

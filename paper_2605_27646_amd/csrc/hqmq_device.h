@@ -30,6 +30,8 @@ constexpr int kSecShift = kFineShift - kBits1;      // its second digit: bits 45
 constexpr int kCandCap = 32768;      // candidate keys kept per head
 constexpr int kSelectThreads = 1024; // workgroup of the select sweeps
 constexpr int kSelectRows = 1024;    // rows of one (b, h) segment per select workgroup
+constexpr int kSmallListRows = 4096;   // a tensor of at most this many rows and kSmallListBlocks search workgroups,
+constexpr int kSmallListBlocks = 1024; // with thresholds known beforehand, is encoded by two launches
 
 // Per-head state of the running radix select.
 struct SelectState {
@@ -284,6 +286,11 @@ hipError_t launch_shard_median_pass(const Geometry &g, const WorkspaceOffsets &w
 hipError_t prepare_search_kernels();  // once per device, before the first launch_search on it
 hipError_t launch_search(const Geometry &g, const WorkspaceOffsets &wo, const EncodeBatch &batch, int n_tensors,
                          hipStream_t stream);
+bool search_fused_available(const Geometry &g);  // launch_search_fused has a kernel for this shape
+hipError_t launch_search_fused(const Geometry &g, const WorkspaceOffsets &wo, const EncodeBatch &batch, int n_tensors,
+                               hipStream_t stream);
+hipError_t launch_outlier_list_small(const Geometry &g, const WorkspaceOffsets &wo, const EncodeBatch &batch,
+                                     int n_tensors, hipStream_t stream);
 hipError_t launch_outlier_list(const Geometry &g, const WorkspaceOffsets &wo, const EncodeBatch &batch, int n_tensors,
                                hipStream_t stream);
 hipError_t launch_decode(const Geometry &g, const DecodeBatch &batch, int n_tensors, hipStream_t stream);

@@ -426,6 +426,85 @@ __global__ __launch_bounds__(kThreads) void k_gather(Geometry g, WorkspaceOffset
     }
 }
 
+// The outlier list of a small tensor whose search ran in its fused form (no kernel before it): one
+// workgroup per tensor does what k_scan and k_gather do, and what k_init would have done for them:
+//   scan    exclusive scan of the search workgroups' totals (at most kSmallListBlocks of them, one per
+//           thread), per-head totals, grand total, status word (overflow; non-finite input, which the search
+//           workgroups report in bit 31 of their totals)
+//   gather  every row adds its workgroup's prefix to its offset and copies its flagged chunks
+// grid = (1, 1, tensors), 1024 threads.
+template <bool kFull>
+__global__ __launch_bounds__(1024) void k_list_small(Geometry g, WorkspaceOffsets wo, EncodeBatch batch)
+{
+    const EncodeTensor &tn = batch.t[blockIdx.z];
+    const Workspace ws = carve_workspace(tn.ws, wo);
+    const EncodedPtrs enc = tn.enc;
+    const uint64_t outlier_capacity = tn.outlier_capacity;
+    const _Float16 *__restrict__ x = tn.x;
+    __shared__ uint32_t pre[kSmallListBlocks + 1];  // exclusive prefix of the workgroup totals, then the grand total
+    __shared__ uint32_t wave_tot[16];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const uint32_t blocks_per_seg = g.n_search_blocks_per_seg;
+    const uint32_t n_blocks = (uint32_t)g.B * g.H * blocks_per_seg;  // <= kSmallListBlocks (checked by the host)
+    const uint32_t raw = (uint32_t)tid < n_blocks ? ws.block_sum[tid] : 0u;
+    const uint32_t v = raw & 0x7fffffffu;
+    const int bad = __syncthreads_or((int)(raw >> 31));
+    uint32_t inc = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        uint32_t o = __shfl_up(inc, d, 64);
+        if (lane >= d)
+            inc += o;
+    }
+    if (lane == 63)
+        wave_tot[wv] = inc;
+    __syncthreads();
+    uint32_t wave_before = 0, total = 0;
+    for (int k = 0; k < 16; ++k) {
+        const uint32_t wt = wave_tot[k];
+        if (k < wv)
+            wave_before += wt;
+        total += wt;
+    }
+    if ((uint32_t)tid < n_blocks)
+        pre[tid] = wave_before + inc - v;
+    if (tid == 0)
+        pre[n_blocks] = total;
+    __syncthreads();
+    for (uint32_t h = tid; h < (uint32_t)g.H; h += 1024) {
+        uint32_t sum = 0;
+        for (uint32_t b = 0; b < (uint32_t)g.B; ++b) {
+            const uint32_t first = (b * (uint32_t)g.H + h) * blocks_per_seg;
+            sum += pre[first + blocks_per_seg] - pre[first];
+        }
+        enc.n_outliers[h] = sum;
+    }
+    const uint32_t n_rows = (uint32_t)g.B * g.H * g.T;
+    if (tid == 0) {
+        enc.n_outliers[g.H] = total;
+        enc.row_off[n_rows] = total;
+        enc.status[0] = ((uint64_t)total > outlier_capacity ? HQMQ_STATUS_OUTLIER_OVERFLOW : 0u) |
+                        (bad ? HQMQ_STATUS_NONFINITE : 0u);
+    }
+    for (uint32_t R = tid; R < n_rows; R += 1024) {
+        const uint32_t seg = R / (uint32_t)g.T, t = R - seg * (uint32_t)g.T;
+        const uint32_t b = seg / (uint32_t)g.H, h = seg - b * (uint32_t)g.H;
+        uint32_t word = enc.flags[R];
+        const uint32_t off = enc.row_off[R] + pre[seg * blocks_per_seg + t / (uint32_t)g.search_rows];
+        enc.row_off[R] = off;
+        const _Float16 *row = x + (int64_t)b * g.sb + (int64_t)h * g.sh + (int64_t)t * g.st;
+        uint64_t pos = off;
+        while (word) {
+            const int c = __ffs((int)word) - 1;
+            word &= word - 1;
+            if (pos < outlier_capacity)
+                *reinterpret_cast<uint2 *>(enc.outliers + 4 * pos) =
+                    __builtin_bit_cast(uint2, load_row_chunk<kFull>(row, c, g));
+            ++pos;
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------------------
 // The median of a head whose token axis is split over several shards (a context-parallel cache: every
 // shard holds a slice of T; paper Sec. 3 takes the median per (layer, head, role) over the whole
@@ -553,6 +632,17 @@ hipError_t launch_select_median(const Geometry &g, const WorkspaceOffsets &wo, c
             hipLaunchKernelGGL(k_select_finish<false>, dim3(g.H, 1, n), dim3(kSelectThreads), 0, stream, g, wo, batch, C);
         }
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_outlier_list_small(const Geometry &g, const WorkspaceOffsets &wo, const EncodeBatch &batch,
+                                     int n_tensors, hipStream_t stream)
+{
+    const dim3 grid(1, 1, (unsigned)n_tensors);
+    if (g.D == 4 * kChunksPerRow)
+        hipLaunchKernelGGL(k_list_small<true>, grid, dim3(1024), 0, stream, g, wo, batch);
+    else
+        hipLaunchKernelGGL(k_list_small<false>, grid, dim3(1024), 0, stream, g, wo, batch);
     return hipGetLastError();
 }
 

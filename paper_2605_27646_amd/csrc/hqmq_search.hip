@@ -438,46 +438,46 @@ __device__ __forceinline__ uint32_t search_codeword(const Geometry &g, int lane,
 //   rcnt  [search_rows] u32    outliers per row of the workgroup
 // The search's MFMA A operands of every head, built once per call into the workspace (the workgroups
 // of the search then only copy their head's table into LDS).  grid = (ceil(4 S16 64 / 256), H, tensors).
+// Entry idx of a head's operand table: tile idx / 64 of 8 secondaries, lane l = idx % 64 holding row
+// l % 32 = 4 (secondary in tile) + i and the factors k = 2 (l / 32), 2 (l / 32) + 1 of that row, each in the
+// slots [h h l l].
+__device__ __forceinline__ uint4 operand_entry(const float *sec_h, int S, int idx)
+{
+    const int tile = idx >> 6, l = idx & 63;
+    const int row = l & 31, kh = l >> 5;
+    const int i = row & 3;
+    const int sidx = 8 * tile + (row >> 2);
+    float a = 0.f, bq = 0.f, c = 0.f, d = 0.f;  // zero rows pad S up to a multiple of 16
+    if (sidx < S) {
+        const float *q = sec_h + 4 * sidx;
+        a = q[0], bq = q[1], c = q[2], d = q[3];
+    }
+    // v = u (x) conj(q):  v0 =  a u0 + b u1 + c u2 + d u3
+    //                     v1 = -b u0 + a u1 - d u2 + c u3
+    //                     v2 = -c u0 + d u1 + a u2 - b u3
+    //                     v3 = -d u0 - c u1 + b u2 + a u3
+    auto entry = [&](int k) -> float {  // A[i][k]
+        if (i == 0)
+            return (k == 0) ? a : (k == 1) ? bq : (k == 2) ? c : d;
+        if (i == 1)
+            return (k == 0) ? -bq : (k == 1) ? a : (k == 2) ? -d : c;
+        if (i == 2)
+            return (k == 0) ? -c : (k == 1) ? d : (k == 2) ? a : -bq;
+        return (k == 0) ? -d : (k == 1) ? -c : (k == 2) ? bq : a;
+    };
+    const float va = entry(2 * kh), vb = entry(2 * kh + 1);
+    const Parts2 pa = split2(opaque(va) * kOperandScale), pb = split2(opaque(vb) * kOperandScale);
+    return make_uint4(pack2(pa.h, pa.h), pack2(pa.l, pa.l), pack2(pb.h, pb.h), pack2(pb.l, pb.l));
+}
+
 __global__ __launch_bounds__(kThreads) void k_prepare_operands(Geometry g, WorkspaceOffsets wo, EncodeBatch batch)
 {
     const EncodeTensor &tn = batch.t[blockIdx.z];
     const Workspace ws = carve_workspace(tn.ws, wo);
     const int h = blockIdx.y;
-    const float *sec_h = tn.sec + (size_t)h * g.S * 4;
-    uint4 *dst = ws.aop + (size_t)h * g.S16 * kATiles * 64;
-    {
-        const int idx = blockIdx.x * kThreads + threadIdx.x;
-        if (idx >= g.S16 * kATiles * 64)
-            return;
-        // tile of 8 secondaries: lane l holds row l % 32 = 4 (secondary in tile) + i and the factors
-        // k = 2 (l / 32), 2 (l / 32) + 1 of that row, each in the slots [h h l l]
-        const int tile = idx >> 6, l = idx & 63;
-        const int row = l & 31, kh = l >> 5;
-        const int i = row & 3;
-        const int sidx = 8 * tile + (row >> 2);
-        float a = 0.f, bq = 0.f, c = 0.f, d = 0.f;  // zero rows pad S up to a multiple of 16
-        if (sidx < g.S) {
-            const float *q = sec_h + 4 * sidx;
-            a = q[0], bq = q[1], c = q[2], d = q[3];
-        }
-        // v = u (x) conj(q):  v0 =  a u0 + b u1 + c u2 + d u3
-        //                     v1 = -b u0 + a u1 - d u2 + c u3
-        //                     v2 = -c u0 + d u1 + a u2 - b u3
-        //                     v3 = -d u0 - c u1 + b u2 + a u3
-        auto entry = [&](int k) -> float {  // A[i][k]
-            if (i == 0)
-                return (k == 0) ? a : (k == 1) ? bq : (k == 2) ? c : d;
-            if (i == 1)
-                return (k == 0) ? -bq : (k == 1) ? a : (k == 2) ? -d : c;
-            if (i == 2)
-                return (k == 0) ? -c : (k == 1) ? d : (k == 2) ? a : -bq;
-            return (k == 0) ? -d : (k == 1) ? -c : (k == 2) ? bq : a;
-        };
-        const float va = entry(2 * kh), vb = entry(2 * kh + 1);
-        const Parts2 pa = split2(opaque(va) * kOperandScale), pb = split2(opaque(vb) * kOperandScale);
-        dst[idx] = make_uint4(pack2(pa.h, pa.h), pack2(pa.l, pa.l), pack2(pb.h, pb.h), pack2(pb.l, pb.l));
-    }
-
+    const int idx = blockIdx.x * kThreads + threadIdx.x;
+    if (idx < g.S16 * kATiles * 64)
+        ws.aop[(size_t)h * g.S16 * kATiles * 64 + idx] = operand_entry(tn.sec + (size_t)h * g.S * 4, g.S, idx);
 }
 
 // kWaves: 4 (several workgroups per CU); 16 for workgroups of 256 or 512 rows whose tables would leave
@@ -486,8 +486,12 @@ __global__ __launch_bounds__(kThreads) void k_prepare_operands(Geometry g, Works
 // the tables and keep two waves on every SIMD.
 // This kernel is for rows of 128 elements (32 chunks: two rows per wave); k_search_flat below takes
 // every other head dimension.
-template <int kWaves, int kRows>
-__global__ __launch_bounds__(64 * kWaves, 4) void k_search(Geometry g, WorkspaceOffsets wo, EncodeBatch batch)
+// kFused: the form for tensors of a few rows whose thresholds are known beforehand (appended tokens with
+// supplied thresholds, extraction switched off): no kernel runs before this one, so it takes its thresholds
+// from the caller's array (+infinity without one), builds the head's operand table itself, and reports a
+// non-finite input through bit 31 of its workgroup total, which the list kernel turns into the status word.
+template <int kWaves, int kRows, bool kFused = false>
+__global__ __launch_bounds__(64 * kWaves, kFused ? 1 : 4) void k_search(Geometry g, WorkspaceOffsets wo, EncodeBatch batch)
 {
     constexpr int kThreadsS = 64 * kWaves;
     const EncodeTensor &tn = batch.t[blockIdx.z];
@@ -515,7 +519,10 @@ __global__ __launch_bounds__(64 * kWaves, 4) void k_search(Geometry g, Workspace
             q = *reinterpret_cast<const float4_t *>(sec_h + 4 * s);
         *reinterpret_cast<float4_t *>(secl + 4 * s) = q;
     }
-    {
+    if (kFused) {
+        for (int idx = tid; idx < g.S16 * kATiles * 64; idx += kThreadsS)
+            amat[idx] = operand_entry(sec_h, g.S, idx);
+    } else {
         const uint4 *src = ws.aop + (size_t)h * g.S16 * kATiles * 64;
         for (int idx = tid; idx < g.S16 * kATiles * 64; idx += kThreadsS)
             amat[idx] = src[idx];
@@ -523,7 +530,10 @@ __global__ __launch_bounds__(64 * kWaves, 4) void k_search(Geometry g, Workspace
 
     __syncthreads();
 
-    const double thr = ws.thr[h];
+    const double thr = !kFused ? ws.thr[h] : tn.thr_given ? tn.thr_given[h] : __longlong_as_double(0x7ff0000000000000LL);
+    if (kFused && blockIdx.x == 0 && b == 0 && tid == 0)
+        ws.thr[h] = thr;  // what hqmq_thresholds reads back
+    uint32_t bad_seen = 0;  // kFused: this lane saw a ballot with a non-finite chunk in it
     const double Lq = (double)((1 << g.b_r) - 1);
     const int c = lane & 31, half_id = lane >> 5;
     uint32_t *my_pack = pack + wv * 64;
@@ -547,8 +557,12 @@ __global__ __launch_bounds__(64 * kWaves, 4) void k_search(Geometry g, Workspace
         const uint32_t word = half_id ? (uint32_t)(ballot >> 32) : (uint32_t)ballot;
         if (g.check_finite) {  // uniform
             const bool bad = valid && chunk_nonfinite(xv);
-            if (__ballot(bad) != 0ull && lane == 0)
-                atomicOr(enc.status, HQMQ_STATUS_NONFINITE);
+            if (__ballot(bad) != 0ull) {
+                if (kFused)
+                    bad_seen = 1u;
+                else if (lane == 0)
+                    atomicOr(enc.status, HQMQ_STATUS_NONFINITE);
+            }
         }
 
         // max over the 32 lanes of the row: four DPP steps inside each 16-lane row (after each step the
@@ -594,7 +608,7 @@ __global__ __launch_bounds__(64 * kWaves, 4) void k_search(Geometry g, Workspace
 
     // ---- outlier offsets local to the workgroup and its total; the global prefix is added by the
     // scan / gather kernels that follow --------------------------------------------------------------
-    __syncthreads();
+    const uint32_t bad_any = kFused ? (uint32_t)__syncthreads_or((int)bad_seen) : (__syncthreads(), 0u);
     if (wv == 0) {
         uint32_t carry = 0;
 #pragma unroll
@@ -612,8 +626,8 @@ __global__ __launch_bounds__(64 * kWaves, 4) void k_search(Geometry g, Workspace
                 enc.row_off[row0 + t0 + r] = carry + inc - cnt;
             carry += __shfl(inc, 63, 64);
         }
-        if (lane == 0)
-            ws.block_sum[(size_t)seg * g.n_search_blocks_per_seg + blockIdx.x] = carry;
+        if (lane == 0)  // a workgroup holds at most 512 x 32 outliers: bit 31 is free for the flag
+            ws.block_sum[(size_t)seg * g.n_search_blocks_per_seg + blockIdx.x] = carry | (bad_any ? 0x80000000u : 0u);
     }
 }
 
@@ -630,7 +644,8 @@ __global__ __launch_bounds__(64 * kWaves, 4) void k_search(Geometry g, Workspace
 //   end     the packing area goes out as one contiguous block, then the outlier offsets as above.
 // Dynamic LDS: amat | secl as in k_search, then rowmax u64 [kRows] | fword u32 [kRows] |
 // sig u32 [kRows] | rcnt u32 [kRows] | pack u32 [kRows * row_words].
-template <int kWaves, int kRows>
+// kFused: as in k_search.
+template <int kWaves, int kRows, bool kFused = false>
 __global__ __launch_bounds__(64 * kWaves) void k_search_flat(Geometry g, WorkspaceOffsets wo, EncodeBatch batch)
 {
     constexpr int kThreadsS = 64 * kWaves;
@@ -665,7 +680,10 @@ __global__ __launch_bounds__(64 * kWaves) void k_search_flat(Geometry g, Workspa
             q = *reinterpret_cast<const float4_t *>(sec_h + 4 * s);
         *reinterpret_cast<float4_t *>(secl + 4 * s) = q;
     }
-    {
+    if (kFused) {
+        for (int idx = tid; idx < g.S16 * kATiles * 64; idx += kThreadsS)
+            amat[idx] = operand_entry(sec_h, g.S, idx);
+    } else {
         const uint4 *src = ws.aop + (size_t)h * g.S16 * kATiles * 64;
         for (int idx = tid; idx < g.S16 * kATiles * 64; idx += kThreadsS)
             amat[idx] = src[idx];
@@ -678,7 +696,10 @@ __global__ __launch_bounds__(64 * kWaves) void k_search_flat(Geometry g, Workspa
         pack[i] = 0u;
     __syncthreads();
 
-    const double thr = ws.thr[h];
+    const double thr = !kFused ? ws.thr[h] : tn.thr_given ? tn.thr_given[h] : __longlong_as_double(0x7ff0000000000000LL);
+    if (kFused && blockIdx.x == 0 && b == 0 && tid == 0)
+        ws.thr[h] = thr;  // what hqmq_thresholds reads back
+    uint32_t bad_seen = 0;
     const double Lq = (double)((1 << g.b_r) - 1);
     const _Float16 *base = x + (int64_t)b * g.sb + (int64_t)h * g.sh + (int64_t)t0 * g.st;
 
@@ -687,14 +708,18 @@ __global__ __launch_bounds__(64 * kWaves) void k_search_flat(Geometry g, Workspa
         const int r = row_of_chunk(q, g), c = q - r * g.n_c;
         const half4_t xv = load_row_chunk<false>(base + (int64_t)r * g.st, c, g);
         const double r2 = chunk_norm2(xv);
-        if (g.check_finite && chunk_nonfinite(xv))
-            atomicOr(enc.status, HQMQ_STATUS_NONFINITE);
+        if (g.check_finite && chunk_nonfinite(xv)) {
+            if (kFused)
+                bad_seen = 1u;
+            else
+                atomicOr(enc.status, HQMQ_STATUS_NONFINITE);
+        }
         if (r2 > thr)
             atomicOr(&fword[r], 1u << c);
         else
             atomicMax(&rowmax[r], key_of(r2));  // non-negative doubles order like their bit patterns
     }
-    __syncthreads();
+    const uint32_t bad_any = kFused ? (uint32_t)__syncthreads_or((int)bad_seen) : (__syncthreads(), 0u);
     if (tid < kRows) {
         uint32_t word = 0;
         if (tid < nrows) {
@@ -757,7 +782,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_search_flat(Geometry g, Workspa
             carry += __shfl(inc, 63, 64);
         }
         if (lane == 0)
-            ws.block_sum[(size_t)seg * g.n_search_blocks_per_seg + blockIdx.x] = carry;
+            ws.block_sum[(size_t)seg * g.n_search_blocks_per_seg + blockIdx.x] = carry | (bad_any ? 0x80000000u : 0u);
     }
 }
 
@@ -766,7 +791,11 @@ __global__ __launch_bounds__(64 * kWaves) void k_search_flat(Geometry g, Workspa
 // once per device, before any launch and outside any stream capture.
 hipError_t prepare_search_kernels()
 {
-    const void *variants[11] = {reinterpret_cast<const void *>(k_search_flat<16, kSearchRowsLarge>),
+    const void *variants[15] = {reinterpret_cast<const void *>(k_search<4, kSearchRowsSmall, true>),
+                                reinterpret_cast<const void *>(k_search<8, kSearchRowsSmall, true>),
+                                reinterpret_cast<const void *>(k_search_flat<4, kSearchRowsSmall, true>),
+                                reinterpret_cast<const void *>(k_search_flat<8, kSearchRowsSmall, true>),
+                                reinterpret_cast<const void *>(k_search_flat<16, kSearchRowsLarge>),
                                 reinterpret_cast<const void *>(k_search_flat<16, kSearchRowsHuge>),
                                 reinterpret_cast<const void *>(k_search<4, kSearchRowsSmall>),
                                 reinterpret_cast<const void *>(k_search<4, kSearchRowsLarge>),
@@ -778,9 +807,39 @@ hipError_t prepare_search_kernels()
                                 reinterpret_cast<const void *>(k_search_flat<4, kSearchRowsLarge>),
                                 reinterpret_cast<const void *>(k_search_flat<8, kSearchRowsSmall>)};
     hipError_t err = hipSuccess;
-    for (int i = 0; i < 11 && err == hipSuccess; ++i)
-        err = hipFuncSetAttribute(variants[i], hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCu);
+    // the first four (the fused forms, only ever launched with 64 rows per workgroup) also hold a few bytes of
+    // static LDS (the workgroup-wide OR), which count against the same 160 KiB
+    for (int i = 0; i < 15 && err == hipSuccess; ++i)
+        err = hipFuncSetAttribute(variants[i], hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)kLdsPerCu - (i < 4 ? 1024 : 0));
     return err;
+}
+
+// The fused form exists for the workgroup shapes that short segments get: 64 rows, 4 or 8 waves.
+bool search_fused_available(const Geometry &g)
+{
+    const int waves = search_waves_for(g.S16, g.D, g.row_words, g.search_rows);
+    return g.search_rows == kSearchRowsSmall && (waves == 4 || waves == 8);
+}
+
+hipError_t launch_search_fused(const Geometry &g, const WorkspaceOffsets &wo, const EncodeBatch &batch, int n_tensors,
+                               hipStream_t stream)
+{
+    dim3 grid((g.T + g.search_rows - 1) / g.search_rows, g.B * g.H, (unsigned)n_tensors);
+    const int waves = search_waves_for(g.S16, g.D, g.row_words, g.search_rows);
+    const size_t lds = search_lds_bytes(g.S16, g.D, g.row_words, waves, g.search_rows);
+    if (g.D == 4 * kChunksPerRow) {
+        if (waves == 8)
+            hipLaunchKernelGGL((k_search<8, kSearchRowsSmall, true>), grid, dim3(512), lds, stream, g, wo, batch);
+        else
+            hipLaunchKernelGGL((k_search<4, kSearchRowsSmall, true>), grid, dim3(256), lds, stream, g, wo, batch);
+    } else {
+        if (waves == 8)
+            hipLaunchKernelGGL((k_search_flat<8, kSearchRowsSmall, true>), grid, dim3(512), lds, stream, g, wo, batch);
+        else
+            hipLaunchKernelGGL((k_search_flat<4, kSearchRowsSmall, true>), grid, dim3(256), lds, stream, g, wo, batch);
+    }
+    return hipGetLastError();
 }
 
 hipError_t launch_search(const Geometry &g, const WorkspaceOffsets &wo, const EncodeBatch &batch, int n_tensors,
