@@ -521,3 +521,51 @@ def test_attend_causal_limit_edge_values():
     got = out.cpu().numpy().astype(np.float64)
     _check(got, want, Kd, Vd, q, scale, visible=vis, lse=lse.cpu().numpy().astype(np.float64), lse_want=lse_want)
     assert not got[0, 0].any() and lse[0, 0].item() == -math.inf
+
+
+def _attend_sweep_cases(n, seed):
+    """Seeded random attention cases: head dimension, codebook size, radius width, group size, lengths on and off
+    the tile and split edges, query gain, and the three entry points (plain, log-sum-exp, causal limits)."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n):
+        D = int(rng.choice([128, 96, 64]))
+        S = int(rng.choice([1, 3, 16, 24, 64, 100, 192, 256, 512]))
+        b_r = int(rng.integers(1, 9))
+        B, H, G = int(rng.integers(1, 3)), int(rng.integers(1, 4)), int(rng.integers(1, 17))
+        T = int(rng.choice([1, 2, 15, 16, 17, 63, 64, 65, 129, int(rng.integers(1, 6000)), int(rng.integers(1, 40000))]))
+        if B * H * T * (D // 4) * 24 * S > 2e8:    # the GPU encodes; the oracle decodes and attends
+            T = max(1, int(2e8 / (B * H * (D // 4) * 24 * S)))
+        cases.append((D, S, b_r, B, H, G, T, float(rng.choice([0.5, 1.5, 3.0])), int(rng.integers(0, 3)),
+                      float(rng.choice([0.4, 0.9])), int(rng.integers(1, 10 ** 6))))
+    return cases
+
+
+@pytest.mark.parametrize("D,S,b_r,B,H,G,T,gain,mode,law,seed", _attend_sweep_cases(24, seed=20261128))
+def test_attend_randomized_sweep(D, S, b_r, B, H, G, T, gain, mode, law, seed):
+    print(f"case D={D} S={S} b_r={b_r} B={B} H={H} G={G} T={T} gain={gain} mode={mode} law={law} seed={seed}", flush=True)
+    rng = np.random.default_rng(seed)
+    k, v = _tensors(B, H, T, seed=seed, D=D, law_sigma=law)
+    sec_k, sec_v = _secs(seed % 50, H, S)
+    gk, gv = gpu_encode(k.to(DEV), sec_k.to(DEV), b_r), gpu_encode(v.to(DEV), sec_v.to(DEV), b_r)
+    Hq = H * G
+    q = _query(B, Hq, seed=seed + 1, gain=gain, D=D)
+    scale = 1 / math.sqrt(D)
+    Kd, Vd = _decoded(gk, sec_k.numpy(), B, H, T, b_r, D), _decoded(gv, sec_v.numpy(), B, H, T, b_r, D)
+    vis = rng.integers(0, T + 3, (B, Hq)).astype(np.int32) if mode == 2 else None
+    _, want, lse_want = oracle.attend(_bits(q), Kd.hat, Vd.hat, scale, want_lse=True, visible=vis)
+    q_dev = q.to(DEV)
+    out = torch.full_like(q_dev, float("nan"))
+    lse = torch.full((B, Hq), float("nan"), dtype=torch.float32, device=DEV)
+    ws = torch.empty(hq.hqmq_attend_workspace_bytes(gk.params, Hq), dtype=torch.uint8, device=DEV)
+    ws.fill_(0xCD)
+    args = (gk.params, q_dev, scale, gk.bufs, sec_k.to(DEV), gv.bufs, sec_v.to(DEV))
+    if mode == 0:
+        hq.hqmq_attend(*args, out, ws)
+    elif mode == 1:
+        hq.hqmq_attend_lse(*args, out, lse, ws)
+    else:
+        hq.hqmq_attend_masked(*args, torch.from_numpy(vis).to(DEV), out, ws, lse)
+    torch.cuda.synchronize()
+    _check(out.cpu().numpy().astype(np.float64), want, Kd, Vd, q, scale, visible=vis,
+           lse=lse.cpu().numpy().astype(np.float64) if mode else None, lse_want=lse_want if mode else None)

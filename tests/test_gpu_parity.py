@@ -822,6 +822,46 @@ def test_concurrent_encodes_from_two_threads():
         assert np.array_equal(out.cpu().numpy().view(np.uint16), ref)
 
 
+def _sweep_cases(n, seed):
+    """Seeded random encode / decode cases over head dimensions, codebook sizes, radius widths, shapes (ragged
+    tails, workgroup and tile edges), multipliers and flags, a quarter of them with the chunk norms packed into
+    a narrow band (the median select's overflow paths); sized so that the oracle takes about a second each."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    while len(cases) < n:
+        D = int(rng.choice([128, 128, 96, 64, int(rng.integers(1, 129))]))
+        S = int(rng.choice([1, 2, 3, 5, 16, 24, 48, 64, 96, 100, 192, 255, 256, 257, 384, 512]))
+        b_r = int(rng.integers(1, 9))
+        B, H = int(rng.integers(1, 4)), int(rng.integers(1, 5))
+        nc = -(-D // 4)
+        budget = 1.5e7
+        max_t = max(1, int(budget / (B * H * nc * 24 * S)))
+        T = int(rng.integers(1, min(max_t, 5000) + 1))
+        if rng.random() < 0.2:
+            T = int(rng.choice([1, 2, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257, 2047, 2048, 2049]))
+            if B * H * T * nc * 24 * S > 4 * budget:
+                continue
+        C = float(rng.choice([3.0, 3.0, 1.5, 10.0, 0.7]))
+        flags = int(rng.choice([0, 0, 0, 0, 0, 0, 0, 1, 2, 3]))
+        sg = float(rng.choice([0.3, 0.7, 1.2]))
+        spread = float(rng.choice([0.001, 0.004, 0.03, 0.2])) if rng.random() < 0.25 else 0.0
+        cases.append((D, S, b_r, B, H, T, C, flags, sg, spread, int(rng.integers(1, 10 ** 6))))
+    return cases
+
+
+@pytest.mark.parametrize("D,S,b_r,B,H,T,C,flags,sg,spread,seed", _sweep_cases(40, seed=20261128))
+def test_randomized_sweep(D, S, b_r, B, H, T, C, flags, sg, spread, seed):
+    print(f"case D={D} S={S} b_r={b_r} B={B} H={H} T={T} C={C} flags={flags} sg={sg} spread={spread} seed={seed}",
+          flush=True)
+    x = _lognormal_tensor(B, H, T, seed=seed, sigma_g=sg, D=D)
+    if spread:
+        gen = torch.Generator().manual_seed(seed + 1)
+        mag = (1.0 + spread * (2.0 * torch.rand(x.shape, generator=gen) - 1.0)) * [1e-3, 1.0, 50.0][seed % 3]
+        x = (mag * torch.where(torch.rand(x.shape, generator=gen) < 0.5, -1.0, 1.0)).half()
+        x[..., ::5, :4] *= 5.0
+    _roundtrip(x, S, b_r=b_r, Cmul=C, seed=seed % 100, flags=flags)
+
+
 def test_deterministic_bytes():
     x = _lognormal_tensor(1, 4, 300, seed=15).to(DEV)
     sec_t, _ = _sec(0, 4, 64)
