@@ -446,6 +446,13 @@ __global__ __launch_bounds__(1024) void k_list_small(Geometry g, WorkspaceOffset
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const uint32_t blocks_per_seg = g.n_search_blocks_per_seg;
     const uint32_t n_blocks = (uint32_t)g.B * g.H * blocks_per_seg;  // <= kSmallListBlocks (checked by the host)
+    const uint32_t n_rows = (uint32_t)g.B * g.H * g.T;
+    // the first round of rows: flag word and local offset requested together with the workgroup totals
+    uint32_t word0 = 0, off0 = 0;
+    if ((uint32_t)tid < n_rows) {
+        word0 = enc.flags[tid];
+        off0 = enc.row_off[tid];
+    }
     const uint32_t raw = (uint32_t)tid < n_blocks ? ws.block_sum[tid] : 0u;
     const uint32_t v = raw & 0x7fffffffu;
     const int bad = __syncthreads_or((int)(raw >> 31));
@@ -479,7 +486,6 @@ __global__ __launch_bounds__(1024) void k_list_small(Geometry g, WorkspaceOffset
         }
         enc.n_outliers[h] = sum;
     }
-    const uint32_t n_rows = (uint32_t)g.B * g.H * g.T;
     if (tid == 0) {
         enc.n_outliers[g.H] = total;
         enc.row_off[n_rows] = total;
@@ -489,8 +495,9 @@ __global__ __launch_bounds__(1024) void k_list_small(Geometry g, WorkspaceOffset
     for (uint32_t R = tid; R < n_rows; R += 1024) {
         const uint32_t seg = R / (uint32_t)g.T, t = R - seg * (uint32_t)g.T;
         const uint32_t b = seg / (uint32_t)g.H, h = seg - b * (uint32_t)g.H;
-        uint32_t word = enc.flags[R];
-        const uint32_t off = enc.row_off[R] + pre[seg * blocks_per_seg + t / (uint32_t)g.search_rows];
+        uint32_t word = R == (uint32_t)tid ? word0 : enc.flags[R];
+        const uint32_t off = (R == (uint32_t)tid ? off0 : enc.row_off[R]) +
+                             pre[seg * blocks_per_seg + t / (uint32_t)g.search_rows];
         enc.row_off[R] = off;
         const _Float16 *row = x + (int64_t)b * g.sb + (int64_t)h * g.sh + (int64_t)t * g.st;
         uint64_t pos = off;

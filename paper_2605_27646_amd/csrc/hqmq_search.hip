@@ -261,8 +261,17 @@ constexpr float kScreenBand = 6.0e-6f;
 // are scored again in fp32.  Otherwise (a few chunks in a thousand) the wave scores all S secondaries
 // of that chunk in fp32, 64 at a time.  The decision between secondaries is therefore always taken
 // on fp32 closed-form scores, the lowest s winning exact ties.
+//
+// kCoop (a workgroup whose rows fill a single pass): all kWaves waves of the workgroup hold the same 64
+// chunks, each screens its share of the groups, the per-chunk results (best lane-group, its score, the
+// runner-up) meet in `merge` [kWaves][64][3], and wave 0 alone decides and returns the code words (the other
+// waves return 0).  The merged triple is what one wave screening every group would have found, except when two
+// waves tie for the best score exactly; the runner-up then equals the best and the chunk takes the fp32 search,
+// as any tie between groups does.
+template <bool kCoop = false, int kWaves = 1>
 __device__ __forceinline__ uint32_t search_codeword(const Geometry &g, int lane, const Direction u, bool flagged,
-                                                    double r2, int rq, const uint4 *amat, const float *secl)
+                                                    double r2, int rq, const uint4 *amat, const float *secl,
+                                                    int wv = 0, float *merge = nullptr)
 {
     const float u0 = opaque(u.u0), u1 = opaque(u.u1), u2 = opaque(u.u2), u3 = opaque(u.u3);
     const int half = lane >> 5;
@@ -288,13 +297,18 @@ __device__ __forceinline__ uint32_t search_codeword(const Geometry &g, int lane,
 #pragma unroll
     for (int e = 0; e < 16; ++e)
         zero16[e] = 0.f;
+    // groups this wave screens
+    const int per_wave = kCoop ? (g.S16 + kWaves - 1) / kWaves : g.S16;
+    const int grp_begin = kCoop ? min(wv * per_wave, g.S16) : 0;
+    const int grp_end = kCoop ? min(grp_begin + per_wave, g.S16) : g.S16;
     const uint4 *arow = amat + lane;
-    half8_t a0 = __builtin_bit_cast(half8_t, arow[0]), a1 = __builtin_bit_cast(half8_t, arow[64]);
+    half8_t a0 = __builtin_bit_cast(half8_t, arow[2 * min(grp_begin, g.S16 - 1) * 64]),
+            a1 = __builtin_bit_cast(half8_t, arow[2 * min(grp_begin, g.S16 - 1) * 64 + 64]);
     // the product of (tile 0, chunk slot 0) of the next group is issued before the arithmetic on the last
     // product of this one: a VALU instruction right behind the MFMA it depends on idles for the depth of
     // the matrix pipeline
     float16_t ahead = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, bop[0], zero16, 0, 0, 0);
-    for (int grp = 0; grp < g.S16; ++grp) {
+    for (int grp = grp_begin; grp < grp_end; ++grp) {
         // the next group's operands replace this group's as soon as their last product is issued (the
         // last group re-reads itself; that product is dropped)
         const uint4 *anext = arow + 2 * min(grp + 1, g.S16 - 1) * 64;
@@ -363,9 +377,28 @@ __device__ __forceinline__ uint32_t search_codeword(const Geometry &g, int lane,
     const float ot_s = __shfl_xor(half ? second[0] : second[1], 32, 64);
     const int ot_k = __shfl_xor(half ? bkey[0] : bkey[1], 32, 64);
     const bool other = ot_b > my_b;
-    const float top = other ? ot_b : my_b;
-    const float runner = fmaxf(fmaxf(fminf(my_b, ot_b), my_s), ot_s);
-    const int first = (other ? ot_k : my_k) + (other ? 1 - half : half);  // candidates first + 2 t
+    float top = other ? ot_b : my_b;
+    float runner = fmaxf(fmaxf(fminf(my_b, ot_b), my_s), ot_s);
+    int first = (other ? ot_k : my_k) + (other ? 1 - half : half);  // candidates first + 2 t
+    if (kCoop) {
+        float *mine = merge + (wv * 64 + lane) * 3;
+        mine[0] = top;
+        mine[1] = runner;
+        mine[2] = __int_as_float(first);
+        __syncthreads();
+        if (wv != 0)
+            return 0u;
+#pragma unroll
+        for (int k = 1; k < kWaves; ++k) {  // a wave without groups left its initial -1: never the best
+            const float *theirs = merge + (k * 64 + lane) * 3;
+            const float tb = theirs[0], tr = theirs[1];
+            const int tf = __float_as_int(theirs[2]);
+            const bool better = tb > top;
+            runner = fmaxf(fmaxf(fminf(top, tb), runner), tr);
+            first = better ? tf : first;
+            top = better ? tb : top;
+        }
+    }
     const bool live = !flagged && r2 != 0.0;
     const bool unclear = live && !(top - runner >= kScreenBand * top);
 
@@ -511,6 +544,17 @@ __global__ __launch_bounds__(64 * kWaves, kFused ? 1 : 4) void k_search(Geometry
     const int t0 = blockIdx.x * kRows;
     const int64_t row0 = (int64_t)seg * g.T;  // linear index of the segment's first row
     const float *sec_h = sec + (size_t)h * g.S * 4;
+    // kFused (a launch of a few rows, bound by latency): a workgroup with one or two rows (one appended token)
+    // runs its single pass on all its waves together (search_codeword's cooperative form), and the first
+    // chunk is requested before the tables
+    const bool coop = kFused && g.T - t0 <= 2;  // uniform over the workgroup
+    __shared__ float merge[kFused ? kWaves * 64 * 3 : 1];
+    half4_t first_chunk = {0, 0, 0, 0};
+    if (kFused) {
+        const int t = t0 + (coop ? 0 : wv * 2) + (lane >> 5);
+        if (t < g.T)
+            first_chunk = load_chunk(x + (int64_t)b * g.sb + (int64_t)h * g.sh + 4 * (lane & 31) + (int64_t)t * g.st);
+    }
 
     // ---- setup: secondaries and A operands into LDS ---------------------------------------
     for (int s = tid; s < g.S16 * 16; s += kThreadsS) {
@@ -522,6 +566,9 @@ __global__ __launch_bounds__(64 * kWaves, kFused ? 1 : 4) void k_search(Geometry
     if (kFused) {
         for (int idx = tid; idx < g.S16 * kATiles * 64; idx += kThreadsS)
             amat[idx] = operand_entry(sec_h, g.S, idx);
+        if (coop)  // the one pass writes the counters of rows 0 and 1 only
+            for (int r = tid; r < kRows; r += kThreadsS)
+                rcnt[r] = 0;
     } else {
         const uint4 *src = ws.aop + (size_t)h * g.S16 * kATiles * 64;
         for (int idx = tid; idx < g.S16 * kATiles * 64; idx += kThreadsS)
@@ -539,18 +586,19 @@ __global__ __launch_bounds__(64 * kWaves, kFused ? 1 : 4) void k_search(Geometry
     uint32_t *my_pack = pack + wv * 64;
     const _Float16 *base = x + (int64_t)b * g.sb + (int64_t)h * g.sh + 4 * c;
 
-    for (int it = 0; it < kRows / (2 * kWaves); ++it) {
-        const int r_in_block = it * 2 * kWaves + wv * 2 + half_id;
+    const int n_it = coop ? 1 : kRows / (2 * kWaves);
+    for (int it = 0; it < n_it; ++it) {
+        const int r_in_block = coop ? half_id : it * 2 * kWaves + wv * 2 + half_id;
         const int t = t0 + r_in_block;
         const bool valid = t < g.T;
-        if (t0 + it * 2 * kWaves + wv * 2 >= g.T) {  // wave-uniform: both rows of this iteration lie past the end
+        if (!coop && t0 + it * 2 * kWaves + wv * 2 >= g.T) {  // wave-uniform: both rows of this iteration lie past the end
             if (c == 0)
                 rcnt[r_in_block] = 0;
             continue;
         }
 
         // ---- chunk, norm, flag, row scale --------------------------------------------------
-        half4_t xv = valid ? load_chunk(base + (int64_t)t * g.st) : half4_t{0, 0, 0, 0};
+        half4_t xv = (kFused && it == 0) ? first_chunk : valid ? load_chunk(base + (int64_t)t * g.st) : half4_t{0, 0, 0, 0};
         const double r2 = chunk_norm2(xv);
         const bool flagged = valid && (r2 > thr);
         const unsigned long long ballot = __ballot(flagged);
@@ -579,7 +627,14 @@ __global__ __launch_bounds__(64 * kWaves, kFused ? 1 : 4) void k_search(Geometry
         const int rq = radius_code(r2, r_f, sigma16, Lq);
         const Direction u = unit_direction(xv, r2, r_f);
         my_pack[lane] = 0;  // after the previous iteration's reads of it: LDS serves a wave in order
-        const uint32_t code = search_codeword(g, lane, u, flagged, r2, rq, amat, secl);
+        uint32_t code;
+        if (coop) {
+            code = search_codeword<true, kWaves>(g, lane, u, flagged, r2, rq, amat, secl, wv, merge);
+            if (wv != 0)
+                continue;  // wave 0 holds the result and writes the two rows
+        } else {
+            code = search_codeword(g, lane, u, flagged, r2, rq, amat, secl);
+        }
 
         // ---- pack the row: chunk c at bits [c*w, (c+1)*w) -----------------------------------------
         {
@@ -807,11 +862,11 @@ hipError_t prepare_search_kernels()
                                 reinterpret_cast<const void *>(k_search_flat<4, kSearchRowsLarge>),
                                 reinterpret_cast<const void *>(k_search_flat<8, kSearchRowsSmall>)};
     hipError_t err = hipSuccess;
-    // the first four (the fused forms, only ever launched with 64 rows per workgroup) also hold a few bytes of
-    // static LDS (the workgroup-wide OR), which count against the same 160 KiB
+    // the first four (the fused forms, only ever launched with 64 rows per workgroup) also hold static LDS (the
+    // workgroup-wide OR, the merge buffer of the cooperative pass: up to 6 KiB), which counts against the same 160 KiB
     for (int i = 0; i < 15 && err == hipSuccess; ++i)
         err = hipFuncSetAttribute(variants[i], hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  (int)kLdsPerCu - (i < 4 ? 1024 : 0));
+                                  (int)kLdsPerCu - (i < 4 ? 8192 : 0));
     return err;
 }
 

@@ -713,6 +713,68 @@ def test_incremental_encode_of_appended_tokens(T_new):
     assert 0 < stats["outliers"] < n_chunks
 
 
+@pytest.mark.parametrize("D,B,H,T,S,b_r", [
+    (128, 1, 8, 1, 256, 6),     # one appended token of the headline shape: one row per workgroup, all waves on one pass
+    (128, 3, 2, 2, 512, 8),     # two rows per workgroup; 8-wave workgroups (S = 512)
+    (128, 1, 2, 1, 1, 3),       # fewer groups of secondaries than waves
+    (128, 2, 3, 1, 40, 4),      # 3 groups over 4 waves
+    (128, 1, 2, 65, 96, 4),     # a full workgroup and one of a single row
+    (128, 2, 2, 66, 24, 6),     # ... and one of two rows
+    (128, 1, 3, 130, 16, 6),    # three workgroups per segment, the last with two rows
+    (128, 4, 8, 128, 64, 6),    # 4096 rows, 64 workgroups: the largest tensor the short form takes
+    (96, 2, 4, 1, 192, 4),      # other head dimensions: the flat kernel's short form
+    (64, 1, 8, 3, 192, 4),
+    (45, 2, 2, 5, 48, 4),
+])
+def test_short_tensors_with_known_thresholds(D, B, H, T, S, b_r):
+    """Tensors of a few rows whose thresholds are known beforehand (supplied, or extraction off) take the
+    two-launch form of the encode: parity with the oracle in both modes, and bytes equal to those of the
+    same rows encoded as part of a tensor long enough to take the general form (thresholds supplied)."""
+    print(f"case D={D} B={B} H={H} T={T} S={S} b_r={b_r}", flush=True)
+    x = _lognormal_tensor(B, H, T, seed=7 * T + S + D, sigma_g=1.0, D=D)
+    sec_t, sec = _sec(S % 17, H, S)
+    sec_dev, x_dev, xb = sec_t.to(DEV), x.to(DEV), _bits(x)
+    nc = -(-D // 4)
+    # extraction off
+    stats, e0, g0 = _roundtrip(x, S, b_r, seed=S % 17, flags=hq.HQMQ_FLAG_NO_OUTLIERS | hq.HQMQ_FLAG_CHECK_FINITE)
+    assert g0.status == 0
+    # supplied thresholds that flag a fair share of the chunks
+    r2 = e0.r2
+    thr_np = np.array([np.quantile(r2.reshape(B, H, T * nc)[:, h], 0.8) for h in range(H)])
+    thr = torch.from_numpy(thr_np).to(DEV)
+    e = oracle.encode(xb, sec, b_r=b_r, thresholds=thr_np)
+    params = hq.params_for(x_dev, S, b_r)
+    bufs = hq.alloc_encoded(params, DEV, outlier_capacity=B * H * T * nc)
+    ws = hq.alloc_workspace(params, DEV)
+    ws.fill_(0x5A)
+    for t in (bufs.codes, bufs.flags, bufs.row_off, bufs.n_outliers, bufs.status):
+        t.fill_(-1)
+    hq.hqmq_encode_given_thresholds(params, x_dev, sec_dev, thr, bufs, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(hq.hqmq_thresholds(params, ws), thr)
+    from gpu_util import GpuEncoded
+    total = int(bufs.n_outliers[-1])
+    g = GpuEncoded(params, bufs, bufs.codes.cpu().numpy().view(np.uint32), bufs.sigma.cpu().numpy().view(np.uint16),
+                   bufs.flags.cpu().numpy().view(np.uint32), bufs.row_off.cpu().numpy().view(np.uint32),
+                   bufs.n_outliers.cpu().numpy().view(np.uint32),
+                   bufs.outliers[:total].cpu().numpy().view(np.uint16).reshape(total, 4), int(bufs.status.item()))
+    stats = compare_encode(g, e, xb, sec)
+    assert stats["outliers"] > 0 or T * nc < 8
+    # the same rows at the front of a long tensor (general form: separate operand table, scan and gather
+    # kernels): code words, scales and flag words of those rows must be the same bytes
+    T_long = 5000 if B * H * 5000 > 4096 else 9000
+    long = torch.zeros(B, H, T_long, D, dtype=torch.float16)
+    long[:, :, :T] = x
+    pl = hq.params_for(long.to(DEV), S, b_r)
+    bl = hq.alloc_encoded(pl, DEV, outlier_capacity=B * H * T_long * nc)
+    hq.hqmq_encode_given_thresholds(pl, long.to(DEV), sec_dev, thr, bl, hq.alloc_workspace(pl, DEV))
+    torch.cuda.synchronize()
+    rows_long = (torch.arange(B * H).view(-1, 1) * T_long + torch.arange(T).view(1, -1)).reshape(-1).to(DEV)
+    assert torch.equal(bl.codes[rows_long], bufs.codes)
+    assert torch.equal(bl.flags[rows_long], bufs.flags)
+    assert torch.equal(bl.sigma[rows_long].view(torch.int16), bufs.sigma.view(torch.int16))
+
+
 def test_batched_incremental_encode_equals_single_calls():
     B, H, S, T_new, n = 2, 4, 16, 2, 5
     cb = hq.hqmq_build_codebooks(6, n, H, S)
