@@ -29,7 +29,7 @@ namespace {
 
 constexpr int kDecThreads = 256;
 constexpr int kDecWaves = kDecThreads / 64;
-constexpr int kPaySlots = 64;                       // outlier payloads of a wave's rows kept in LDS
+constexpr int kPaySlots = 128;                      // outlier payloads of a wave's rows kept in LDS (two per lane)
 constexpr int kGeneralRows = 64;                    // rows per workgroup of the general-row kernel
 
 // Sizes of one variant of the tuned kernel: kPairs chunk pairs per row, kRowsW rows per wave.
@@ -154,6 +154,7 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(Geometry g, DecodeBatch 
     const uint2 *pay_src = has_pay ? reinterpret_cast<const uint2 *>(enc.outliers) + pay_base
                                    : reinterpret_cast<const uint2 *>(enc.row_off);
     const uint2 pay_mine = pay_src[min((uint64_t)lane, pay_last)];
+    const uint2 pay_mine2 = pay_src[min((uint64_t)lane + 64u, pay_last)];
     // wave-uniform: the whole window fits the LDS slots and the list's capacity
     const bool window_ok = pay_n <= (uint32_t)kPaySlots && (uint64_t)pay_base + pay_n <= outlier_capacity;
 
@@ -312,6 +313,7 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(Geometry g, DecodeBatch 
         if (g0 == 0) {
             // the window lands in LDS only now, after the first round's arithmetic, which does not need it
             st_pay[lane] = pay_mine;
+            st_pay[lane + 64] = pay_mine2;
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
