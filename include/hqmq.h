@@ -182,8 +182,9 @@ int32_t hqmq_encode(const hqmq_params *params, const void *x_dev, const float *s
 int32_t hqmq_encode_static(const hqmq_params *params, const void *x_dev, const float *sec_dev,
                            const hqmq_encoded *enc, uint64_t outlier_capacity, void *stream);
 
-/* hqmq_encode with measurement marks (the per-kernel figures of the paper's latency tables,
- * App. E / Sec. 4.10, are quoted per call; this gives the same split for the encode phases).
+/* hqmq_encode with measurement marks: an entry point of this library's own, for callers who want the
+ * encode's time split by phase (the paper reports no encode timing at all; its latency tables, App. E /
+ * Sec. 4.10, are per call of a whole kernel).
  * phase_events: HOST array of 4 caller-created hipEvent_t (any entry, or the array, may be
  * NULL), recorded on `stream`: [0] before the first kernel, [1] after the median select,
  * [2] after the search kernel (flags, scales, codes), [3] after the outlier list (scan and
