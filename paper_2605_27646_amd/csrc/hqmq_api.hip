@@ -126,6 +126,7 @@ static Geometry make_geometry(const hqmq_params *p)
         if ((1 << j) == p->S)
             g.log2_S = j;
     g.check_finite = (p->flags & HQMQ_FLAG_CHECK_FINITE) ? 1 : 0;
+    g.fused_by_head = 0;
     g.search_rows = search_rows_for(p->T, g.S16, g.D, g.row_words);
     g.n_search_blocks_per_seg = (uint32_t)((p->T + g.search_rows - 1) / g.search_rows);
     return g;
@@ -334,9 +335,15 @@ static int32_t encode_impl(const hqmq_params *params, int32_t n_tensors, const v
         const bool fused = (no_outliers || thr_given != nullptr) && n_rows_t <= (uint64_t)kSmallListRows &&
                            n_blocks_t <= (uint64_t)kSmallListBlocks && search_fused_available(g);
         if (fused) {
+            // several batch entries whose rows together fill no more than one pass of the workgroup's waves (rows
+            // of 128 elements): a workgroup per head takes them all, and builds the head's tables once instead
+            // of once per batch entry; more rows than that are faster on workgroups of their own
+            Geometry gf = g;
+            const int waves = search_waves_for(g.S16, g.D, g.row_words, g.search_rows);
+            gf.fused_by_head = (g.B > 1 && (int64_t)g.B * g.T <= 2 * waves && g.D == 4 * kChunksPerRow) ? 1 : 0;
             err = mark(1);
             if (err == hipSuccess)
-                err = launch_search_fused(g, wo, batch, n, st);
+                err = launch_search_fused(gf, wo, batch, n, st);
             if (err == hipSuccess)
                 err = mark(2);
             if (err == hipSuccess)

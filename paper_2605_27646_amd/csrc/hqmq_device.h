@@ -56,6 +56,7 @@ struct Geometry {
     int32_t log2_S;       // log2(S) when S is a power of two, else -1
     float inv_S;          // (1/S)(1 + 2^-18): uint(float(k) * inv_S) == k / S for every k < 48 S, S <= 512
     int32_t check_finite;  // HQMQ_FLAG_CHECK_FINITE: the search reports chunks holding an infinity or a NaN in the status word
+    int32_t fused_by_head;  // fused search only: one workgroup per head takes the rows of all batch entries (B T <= 64)
     int32_t search_rows;               // rows per search workgroup (kSearchRowsSmall or kSearchRowsLarge)
     uint32_t n_search_blocks_per_seg;  // ceil(T / search_rows)
 };

@@ -540,20 +540,36 @@ __global__ __launch_bounds__(64 * kWaves, kFused ? 1 : 4) void k_search(Geometry
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, and known to be
-    const int seg = blockIdx.y, b = seg / g.H, h = seg % g.H;
+    // by_head (kFused, several batch entries of a few rows each): one workgroup per head takes the rows of all
+    // batch entries, so that the head's tables are built once; its rows are the pairs (b, t), b-major
+    const bool by_head = kFused && g.fused_by_head != 0;
+    const int seg = blockIdx.y, b = by_head ? 0 : seg / g.H, h = by_head ? seg : seg % g.H;
     const int t0 = blockIdx.x * kRows;
-    const int64_t row0 = (int64_t)seg * g.T;  // linear index of the segment's first row
+    const int n_here = by_head ? g.B * g.T : g.T;  // rows this workgroup column addresses
     const float *sec_h = sec + (size_t)h * g.S * 4;
+    // row v of the column: its batch entry and token, the address of its chunk c, its linear row index
+    struct RowAt {
+        const _Float16 *chunk;
+        int64_t R;
+    };
+    auto row_at = [&](int v, int c) {
+        const int bb = by_head ? v / g.T : b;
+        const int tt = by_head ? v - bb * g.T : v;
+        RowAt r;
+        r.chunk = x + (int64_t)bb * g.sb + (int64_t)h * g.sh + (int64_t)tt * g.st + 4 * c;
+        r.R = ((int64_t)bb * g.H + h) * g.T + tt;
+        return r;
+    };
     // kFused (a launch of a few rows, bound by latency): a workgroup with one or two rows (one appended token)
     // runs its single pass on all its waves together (search_codeword's cooperative form), and the first
     // chunk is requested before the tables
-    const bool coop = kFused && g.T - t0 <= 2;  // uniform over the workgroup
+    const bool coop = kFused && n_here - t0 <= 2;  // uniform over the workgroup
     __shared__ float merge[kFused ? kWaves * 64 * 3 : 1];
     half4_t first_chunk = {0, 0, 0, 0};
     if (kFused) {
-        const int t = t0 + (coop ? 0 : wv * 2) + (lane >> 5);
-        if (t < g.T)
-            first_chunk = load_chunk(x + (int64_t)b * g.sb + (int64_t)h * g.sh + 4 * (lane & 31) + (int64_t)t * g.st);
+        const int v = t0 + (coop ? 0 : wv * 2) + (lane >> 5);
+        if (v < n_here)
+            first_chunk = load_chunk(row_at(v, lane & 31).chunk);
     }
 
     // ---- setup: secondaries and A operands into LDS ---------------------------------------
@@ -584,21 +600,21 @@ __global__ __launch_bounds__(64 * kWaves, kFused ? 1 : 4) void k_search(Geometry
     const double Lq = (double)((1 << g.b_r) - 1);
     const int c = lane & 31, half_id = lane >> 5;
     uint32_t *my_pack = pack + wv * 64;
-    const _Float16 *base = x + (int64_t)b * g.sb + (int64_t)h * g.sh + 4 * c;
 
     const int n_it = coop ? 1 : kRows / (2 * kWaves);
     for (int it = 0; it < n_it; ++it) {
         const int r_in_block = coop ? half_id : it * 2 * kWaves + wv * 2 + half_id;
         const int t = t0 + r_in_block;
-        const bool valid = t < g.T;
-        if (!coop && t0 + it * 2 * kWaves + wv * 2 >= g.T) {  // wave-uniform: both rows of this iteration lie past the end
+        const bool valid = t < n_here;
+        if (!coop && t0 + it * 2 * kWaves + wv * 2 >= n_here) {  // wave-uniform: both rows of this iteration lie past the end
             if (c == 0)
                 rcnt[r_in_block] = 0;
             continue;
         }
 
         // ---- chunk, norm, flag, row scale --------------------------------------------------
-        half4_t xv = (kFused && it == 0) ? first_chunk : valid ? load_chunk(base + (int64_t)t * g.st) : half4_t{0, 0, 0, 0};
+        const RowAt here = row_at(valid ? t : t0, c);
+        half4_t xv = (kFused && it == 0) ? first_chunk : valid ? load_chunk(here.chunk) : half4_t{0, 0, 0, 0};
         const double r2 = chunk_norm2(xv);
         const bool flagged = valid && (r2 > thr);
         const unsigned long long ballot = __ballot(flagged);
@@ -649,7 +665,7 @@ __global__ __launch_bounds__(64 * kWaves, kFused ? 1 : 4) void k_search(Geometry
         }
         wave_lds_sync();
         if (valid) {
-            const int64_t R = row0 + t;
+            const int64_t R = here.R;
             if (c < g.w)
                 enc.codes[R * g.w + c] = my_pack[half_id * 32 + c];
             if (c == 0) {
@@ -677,14 +693,26 @@ __global__ __launch_bounds__(64 * kWaves, kFused ? 1 : 4) void k_search(Geometry
                 if (lane >= d)
                     inc += o;
             }
-            if (t0 + r < g.T)
-                enc.row_off[row0 + t0 + r] = carry + inc - cnt;
+            if (by_head) {
+                // (64 rows at most, one part) every batch entry's rows are a run of their own in the list's
+                // order: offsets restart at each run, and each run reports its total as a workgroup would
+                const int run = r / g.T, start = run * g.T;
+                const uint32_t before_run = __shfl(inc - cnt, min(start, 63), 64);
+                if (r < n_here) {
+                    enc.row_off[row_at(r, 0).R] = inc - cnt - before_run;
+                    if (r - start == g.T - 1)
+                        ws.block_sum[(size_t)run * g.H + h] = (inc - before_run) | (bad_any ? 0x80000000u : 0u);
+                }
+            } else if (t0 + r < g.T) {
+                enc.row_off[row_at(t0 + r, 0).R] = carry + inc - cnt;
+            }
             carry += __shfl(inc, 63, 64);
         }
-        if (lane == 0)  // a workgroup holds at most 512 x 32 outliers: bit 31 is free for the flag
+        if (lane == 0 && !by_head)  // a workgroup holds at most 512 x 32 outliers: bit 31 is free for the flag
             ws.block_sum[(size_t)seg * g.n_search_blocks_per_seg + blockIdx.x] = carry | (bad_any ? 0x80000000u : 0u);
     }
 }
+
 
 // The same search for any head dimension: rows of n_c = ceil(D / 4) <= 32 chunks.  A workgroup owns
 // 64 or 256 rows of one (b, h) segment and treats their chunks as one flat list, 64 consecutive
@@ -880,7 +908,7 @@ bool search_fused_available(const Geometry &g)
 hipError_t launch_search_fused(const Geometry &g, const WorkspaceOffsets &wo, const EncodeBatch &batch, int n_tensors,
                                hipStream_t stream)
 {
-    dim3 grid((g.T + g.search_rows - 1) / g.search_rows, g.B * g.H, (unsigned)n_tensors);
+    dim3 grid((g.T + g.search_rows - 1) / g.search_rows, g.fused_by_head ? g.H : g.B * g.H, (unsigned)n_tensors);
     const int waves = search_waves_for(g.S16, g.D, g.row_words, g.search_rows);
     const size_t lds = search_lds_bytes(g.S16, g.D, g.row_words, waves, g.search_rows);
     if (g.D == 4 * kChunksPerRow) {

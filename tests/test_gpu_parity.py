@@ -722,6 +722,11 @@ def test_incremental_encode_of_appended_tokens(T_new):
     (128, 2, 2, 66, 24, 6),     # ... and one of two rows
     (128, 1, 3, 130, 16, 6),    # three workgroups per segment, the last with two rows
     (128, 4, 8, 128, 64, 6),    # 4096 rows, 64 workgroups: the largest tensor the short form takes
+    (128, 8, 8, 1, 256, 6),     # a generation step of 8 sequences: one workgroup per head takes all batch entries
+    (128, 4, 2, 2, 64, 6),      # ... 8 rows per head: one pass of the four waves exactly
+    (128, 3, 3, 3, 24, 4),      # 9 rows per head: back to one workgroup per (batch entry, head)
+    (128, 5, 2, 3, 512, 6),     # 15 rows per head on 8-wave workgroups
+    (128, 2, 2, 1, 16, 6),      # two batch entries of one row: one cooperative pass for both
     (96, 2, 4, 1, 192, 4),      # other head dimensions: the flat kernel's short form
     (64, 1, 8, 3, 192, 4),
     (45, 2, 2, 5, 48, 4),
