@@ -36,7 +36,10 @@ def test_graph_replays_match_eager():
     vis = torch.randint(0, T + 1, (B, H * G), generator=torch.Generator().manual_seed(4), dtype=torch.int32).to(DEV)
     aws2 = torch.empty_like(aws)
 
+    es = hq.alloc_encoded(params, DEV)          # K once more through the entry point that takes no workspace
+
     def path():
+        hq.hqmq_encode_static(params, k, sec_k, es)
         hq.hqmq_encode_batch(batch)
         hq.hqmq_decode_batch(dec)
         hq.hqmq_attend(params, q, 0.09, ek, sec_k, ev, sec_v, o, aws)
@@ -44,12 +47,13 @@ def test_graph_replays_match_eager():
 
     def snapshot():
         torch.cuda.synchronize()
-        return [t.clone() for t in (ek.codes, ek.flags, ek.row_off, ek.n_outliers, ev.codes, ok.view(torch.int16),
+        return [t.clone() for t in (es.codes, es.row_off, es.n_outliers, es.status,
+                                    ek.codes, ek.flags, ek.row_off, ek.n_outliers, ev.codes, ok.view(torch.int16),
                                     ov.view(torch.int16), o.view(torch.int16), o2.view(torch.int16),
                                     lse.view(torch.int32))]
 
     def scrub():
-        for t in (ek.codes, ek.flags, ek.row_off, ev.codes, ek.n_outliers):
+        for t in (ek.codes, ek.flags, ek.row_off, ev.codes, ek.n_outliers, es.codes, es.row_off, es.n_outliers, es.status):
             t.fill_(-1)
         for t in (ok, ov, o, o2, lse):
             t.fill_(float("nan"))
@@ -57,9 +61,11 @@ def test_graph_replays_match_eager():
         aws.fill_(0x77)
         aws2.fill_(0x77)
 
+    hq.hqmq_init()                              # per-device set-up outside any capture
     path()
     want = snapshot()
     assert int(ek.n_outliers[-1]) > 0
+    assert torch.equal(es.codes, ek.codes) and torch.equal(es.row_off, ek.row_off)
 
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
