@@ -116,6 +116,7 @@ def main() -> int:
 
     elems_per_step = wl.elems_per_tensor * n_t
     chunks_per_tensor = wl.B * wl.H * wl.T * ((wl.D + 3) // 4)
+    select_reads = 1.0 + 1.0 / 16.0 if chunks_per_tensor // wl.H >= 2 ** 17 else 2.0
 
     def new_events(n):
         evs = [torch.cuda.Event(enable_timing=True) for _ in range(n)]
@@ -243,7 +244,9 @@ def main() -> int:
         "encode_phase_ms_per_tensor": {"median_select": t_sel / launches / tensors_per_enc_launch,
                                        "search_quantise_pack": search_ms / tensors_per_enc_launch,
                                        "outlier_scan_gather": t_list / launches / tensors_per_enc_launch},
-        "median_select_GBs": 2 * 8.0 * chunks_per_tensor * tensors_per_enc_launch / (t_sel / launches * 1e-3) / 1e9,
+        # the select reads every row once and every 16th row before that (heads of at least 2^17 chunks), else twice
+        "median_select_reads": select_reads,
+        "median_select_GBs": select_reads * 8.0 * chunks_per_tensor * tensors_per_enc_launch / (t_sel / launches * 1e-3) / 1e9,
         "codeword_scores_per_s": 24.0 * wl.S * chunks_per_tensor * tensors_per_enc_launch / (search_ms * 1e-3),
         "outlier_fraction": p_out,
         "status_bits": status,

@@ -127,13 +127,14 @@ static Geometry make_geometry(const hqmq_params *p)
             g.log2_S = j;
     g.check_finite = (p->flags & HQMQ_FLAG_CHECK_FINITE) ? 1 : 0;
     g.fused_by_head = 0;
+    g.select_sampled = 0;
     g.search_rows = search_rows_for(p->T, g.S16, g.D, g.row_words);
     g.n_search_blocks_per_seg = (uint32_t)((p->T + g.search_rows - 1) / g.search_rows);
     return g;
 }
 
 struct WorkspaceLayout {
-    uint64_t state, thr, hist0, hist1, cand_count, cand, block_sum, block_pre, aop, total;
+    uint64_t state, thr, hist0, hist1, plan, cand_count, cand, block_sum, block_pre, aop, total;
 };
 
 static WorkspaceLayout workspace_layout(const Geometry &g)
@@ -150,7 +151,8 @@ static WorkspaceLayout workspace_layout(const Geometry &g)
     l.thr = take((uint64_t)g.H * sizeof(double));
     l.hist0 = take((uint64_t)g.H * kBins0 * sizeof(uint32_t));
     l.hist1 = take((uint64_t)g.H * kBins1 * sizeof(uint32_t));
-    l.cand_count = take((uint64_t)g.H * 2 * sizeof(uint32_t));
+    l.plan = take((uint64_t)g.H * sizeof(SelectPlan));
+    l.cand_count = take((uint64_t)g.H * 3 * sizeof(uint32_t));
     l.cand = take((uint64_t)g.H * kCandCap * sizeof(unsigned long long));
     l.block_sum = take(n_blocks * sizeof(uint32_t));
     l.block_pre = take(n_blocks * sizeof(uint32_t));
@@ -250,6 +252,7 @@ static WorkspaceOffsets workspace_offsets(const WorkspaceLayout &l)
     o.thr = (uint32_t)l.thr;
     o.hist0 = (uint32_t)l.hist0;
     o.hist1 = (uint32_t)l.hist1;
+    o.plan = (uint32_t)l.plan;
     o.cand_count = (uint32_t)l.cand_count;
     o.cand = (uint32_t)l.cand;
     o.block_sum = (uint32_t)l.block_sum;

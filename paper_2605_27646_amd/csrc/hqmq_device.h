@@ -28,8 +28,12 @@ constexpr int kFineShift = 46;                      // first digit of the single
 constexpr uint32_t kFineBase = (975u << 6) - 1u;    // ... minus this: 2^-48, the smallest square of an fp16 value, lands in bin 1
 constexpr int kSecShift = kFineShift - kBits1;      // its second digit: bits 45..36
 constexpr int kCandCap = 32768;      // candidate keys kept per head
+static_assert(kBins0 * sizeof(uint32_t) <= kCandCap * sizeof(unsigned long long),
+              "the sample histogram borrows the candidate list's memory");
 constexpr int kSelectThreads = 1024; // workgroup of the select sweeps
 constexpr int kSelectRows = 1024;    // rows of one (b, h) segment per select workgroup
+constexpr int kSampleStride = 16;     // the sampled select reads every 16th row of a head first ...
+constexpr int kSampleMinChunks = 1 << 17;  // ... when the head has at least this many chunks
 constexpr int kSmallListRows = 4096;   // a tensor of at most this many rows and kSmallListBlocks search workgroups,
 constexpr int kSmallListBlocks = 1024; // with thresholds known beforehand, is encoded by two launches
 
@@ -38,6 +42,16 @@ struct SelectState {
     unsigned long long prefix;  // key bits fixed so far (right aligned)
     uint32_t rank;              // rank still to be located inside the prefix bucket
     uint32_t pad;
+};
+
+// Per-head plan of the sampled select: the bins of the first digit whose keys the full sweep keeps as
+// candidates (predicted from a sample of the rows), and what the full histogram then says.
+struct SelectPlan {
+    uint32_t lo, span;   // candidate bins lo .. lo + span (lo = kBins0: none)
+    uint32_t bin0;       // the bin that holds the median, from the full histogram
+    uint32_t before0;    // keys in the bins below it
+    uint32_t need;       // 1: the prediction missed the bin or the list overflowed; a sweep of its own collects the bin
+    uint32_t pad[3];
 };
 
 // Shape and addressing of one tensor, passed by value to every kernel.
@@ -56,6 +70,7 @@ struct Geometry {
     int32_t log2_S;       // log2(S) when S is a power of two, else -1
     float inv_S;          // (1/S)(1 + 2^-18): uint(float(k) * inv_S) == k / S for every k < 48 S, S <= 512
     int32_t check_finite;  // HQMQ_FLAG_CHECK_FINITE: the search reports chunks holding an infinity or a NaN in the status word
+    int32_t select_sampled;  // the median select predicts the median's bin from a sample of the rows (large heads only)
     int32_t fused_by_head;  // fused search only: one workgroup per head takes the rows of all batch entries (B T <= 64)
     int32_t search_rows;               // rows per search workgroup (kSearchRowsSmall or kSearchRowsLarge)
     uint32_t n_search_blocks_per_seg;  // ceil(T / search_rows)
@@ -113,7 +128,12 @@ struct Workspace {
     double *thr;                   // [H] outlier threshold on squared norms
     uint32_t *hist0;               // [H][kBins0]
     uint32_t *hist1;               // [H][kBins1]
-    uint32_t *cand_count;          // [2][H] keys sent to the candidate list by the second sweep, by the third (either may exceed kCandCap)
+    uint32_t *hist_s;              // [H][kBins0] first digit of the sampled rows; shares the candidate list's memory (read
+                                   // before the first candidate is written)
+    SelectPlan *plan;              // [H]
+    uint32_t *cand_count;          // [3][H] keys sent to the candidate list (any may exceed kCandCap): by the sweep that
+                                   // collects one bin (or, in the sampled select, the predicted bins), by the sweep after
+                                   // an overflow, by the sampled select's fallback sweep of one bin
     unsigned long long *cand;      // [H][kCandCap]
     uint32_t *block_sum;           // [B*H*n_search_blocks_per_seg] outliers per search workgroup
     uint32_t *block_pre;           // same shape, exclusive prefix
@@ -132,7 +152,7 @@ struct EncodedPtrs {
 
 // Byte offsets of the workspace parts inside one tensor's slice (same for every tensor of a shape).
 struct WorkspaceOffsets {
-    uint32_t state, thr, hist0, hist1, cand_count, cand, block_sum, block_pre, aop;
+    uint32_t state, thr, hist0, hist1, plan, cand_count, cand, block_sum, block_pre, aop;
 };
 
 // One tensor of an encode batch and the batch itself (passed by value as kernel arguments; every
@@ -157,6 +177,8 @@ __device__ __forceinline__ Workspace carve_workspace(char *base, const Workspace
     ws.thr = reinterpret_cast<double *>(base + o.thr);
     ws.hist0 = reinterpret_cast<uint32_t *>(base + o.hist0);
     ws.hist1 = reinterpret_cast<uint32_t *>(base + o.hist1);
+    ws.hist_s = reinterpret_cast<uint32_t *>(base + o.cand);
+    ws.plan = reinterpret_cast<SelectPlan *>(base + o.plan);
     ws.cand_count = reinterpret_cast<uint32_t *>(base + o.cand_count);
     ws.cand = reinterpret_cast<unsigned long long *>(base + o.cand);
     ws.block_sum = reinterpret_cast<uint32_t *>(base + o.block_sum);

@@ -16,6 +16,11 @@
 // exact order statistic.  Each sweep recomputes r^2 in registers from the fp16 tensor (8 B per
 // chunk, HBM-bound); the bin choice of the previous sweep is re-derived by every workgroup
 // from the (L2-resident) histogram instead of costing a kernel launch of its own.
+// A head of at least kSampleMinChunks chunks skips sweep 1 (the sampled select): a histogram of every
+// kSampleStride-th row predicts a few bins around the median's, sweep 0 keeps the keys of those bins as
+// candidates while it counts all keys, and only a head whose prediction missed the bin that the full
+// histogram names (or whose list overflowed) goes through sweep 1 after all.  The prediction decides which
+// keys are kept, never the result.
 // If a head has more keys sharing both digits than the list holds (many equal norms: a
 // constant or coarsely quantised tensor), the finishing workgroup falls back to radix-selecting
 // the low bits over the head's raw rows itself: slow, exact, and only for such inputs.
@@ -103,11 +108,13 @@ __global__ __launch_bounds__(kThreads) void k_init(Geometry g, WorkspaceOffsets 
     const Workspace ws = carve_workspace(tn.ws, wo);
     const EncodedPtrs enc = tn.enc;
     const uint32_t i = blockIdx.x * kThreads + threadIdx.x;
-    if (i < (uint32_t)g.H * kBins0)
+    if (i < (uint32_t)g.H * kBins0) {
         ws.hist0[i] = 0;
+        ws.hist_s[i] = 0;
+    }
     if (i < (uint32_t)g.H * kBins1)
         ws.hist1[i] = 0;
-    if (i < 2u * (uint32_t)g.H)
+    if (i < 3u * (uint32_t)g.H)
         ws.cand_count[i] = 0;
     if (i < (uint32_t)g.H) {
         // +inf: nothing is flagged (replaced by the select, unless the caller supplies the thresholds)
@@ -122,8 +129,10 @@ __global__ __launch_bounds__(kThreads) void k_init(Geometry g, WorkspaceOffsets 
 // ---------------------------------------------------------------------------------------
 // sweeps.  grid = (ceil(T / kSelectRows), B*H), 1024 threads: one lane per chunk, 32 rows per
 // block iteration, four independent 8-byte loads in flight per lane.
-//   MODE 0: histogram of the first digit (fine_bin), all keys
-//   MODE 1: picks the first digit; the keys of that bin (about one in 200) go to the head's candidate
+//   MODE 0: histogram of the first digit (fine_bin), all keys; in the sampled select it also keeps the keys of
+//           the predicted bins as candidates (staged like MODE 1's)
+//   MODE 3: histogram of the first digit over every kSampleStride-th row (sampled select only)
+//   MODE 1: picks the first digit (sampled select: returns at once unless the head needs it); the keys of that bin (about one in 200) go to the head's candidate
 //           list, staged in LDS so that a workgroup costs the list's counter one update, and are
 //           counted by their next 10 bits (45..36) in case the list overflows
 //   MODE 2: returns at once unless the head's list overflowed; then picks both digits and collects the
@@ -131,25 +140,41 @@ __global__ __launch_bounds__(kThreads) void k_init(Geometry g, WorkspaceOffsets 
 // ---------------------------------------------------------------------------------------
 // kFull: D = 128 (every lane of a 32-lane row slot holds a chunk); otherwise lanes past the row's
 // chunks are idle and the loads go through the general path.
-constexpr int kStageKeys = 1024;  // candidate keys a workgroup of MODE 1 stages in LDS
-template <int MODE, bool kFull>
+constexpr int kStageKeys = 1024;  // candidate keys a workgroup stages in LDS
+constexpr int kFallbackSpan = 8;  // sampled select: a workgroup of MODE 1 or 2 covers this many times kSelectRows rows
+// The counter of the list that holds the keys of the median's bin alone: MODE 1's.
+__device__ __forceinline__ uint32_t *bin_list_counter(const Geometry &g, const Workspace &ws, int h)
+{
+    return ws.cand_count + (g.select_sampled ? 2 * g.H + h : h);
+}
+template <int MODE, bool kFull, bool kCollect = false>
 __global__ __launch_bounds__(kSelectThreads) void k_select_sweep(Geometry g, WorkspaceOffsets wo, EncodeBatch batch)
 {
     const EncodeTensor &tn = batch.t[blockIdx.z];
     const Workspace ws = carve_workspace(tn.ws, wo);
     const _Float16 *__restrict__ x = tn.x;
-    constexpr int kLdsBins = MODE == 0 ? kBins0 : kBins1;
+    constexpr bool kHist0 = MODE == 0 || MODE == 3;
+    constexpr bool kStages = MODE == 1 || (MODE == 0 && kCollect);
+    constexpr int kLdsBins = kHist0 ? kBins0 : kBins1;
     __shared__ uint32_t lh[MODE == 2 ? 1 : kLdsBins];
     __shared__ uint32_t scratch[kSelectThreads + 2];
-    __shared__ unsigned long long staged[MODE == 1 ? kStageKeys : 1];
+    __shared__ unsigned long long staged[kStages ? kStageKeys : 1];
     __shared__ uint32_t n_staged, list_base;
 
     const int seg = blockIdx.y, b = seg / g.H, h = seg % g.H;
     const uint32_t rank0 = (uint32_t)(((uint64_t)g.B * g.T * g.n_c - 1) / 2);
     uint32_t bin0 = 0, before0 = 0, bin1 = 0, before1 = 0;
-    if (MODE == 2 && ws.cand_count[h] <= (uint32_t)kCandCap)
+    uint32_t keep_lo = 0, keep_span = 0;
+    if (MODE == 0 && kCollect) {
+        keep_lo = ws.plan[h].lo;
+        keep_span = ws.plan[h].span;
+    }
+    if ((MODE == 1 || MODE == 2) && g.select_sampled && !ws.plan[h].need)
+        return;  // the candidates kept by MODE 0 hold the median's bin (uniform over the workgroup)
+    uint32_t *const bin_count = bin_list_counter(g, ws, h);
+    if (MODE == 2 && *bin_count <= (uint32_t)kCandCap)
         return;  // the list of MODE 1 holds every candidate (uniform over the workgroup)
-    if (MODE >= 1) {
+    if (MODE == 1 || MODE == 2) {
         pick_bin<kBins0, kSelectThreads>(ws.hist0 + (size_t)h * kBins0, rank0, scratch, bin0, before0);
         if (!fine_bin_is_prefix(bin0))
             return;  // the finishing kernel knows the median of such a bin without candidates
@@ -165,9 +190,15 @@ __global__ __launch_bounds__(kSelectThreads) void k_select_sweep(Geometry g, Wor
     }
 
     const int c = threadIdx.x & 31, sub = threadIdx.x >> 5;  // 32 rows per iteration
-    const int t0 = blockIdx.x * kSelectRows;
-    const int t1 = min(g.T, t0 + kSelectRows);
+    // MODE 3 walks the sampled rows: row j of its grid is token kSampleStride * j
+    constexpr int kStep = MODE == 3 ? kSampleStride : 1;
+    const int n_t = MODE == 3 ? (g.T + kSampleStride - 1) / kSampleStride : g.T;
+    // the sweeps that a sampled select seldom needs are launched with fewer, longer workgroups
+    const int rows = ((MODE == 1 || MODE == 2) && g.select_sampled) ? kSelectRows * kFallbackSpan : kSelectRows;
+    const int t0 = blockIdx.x * rows;
+    const int t1 = min(n_t, t0 + rows);
     const _Float16 *base = x + (int64_t)b * g.sb + (int64_t)h * g.sh;
+    const int64_t row_stride = (int64_t)kStep * g.st;
     const bool active = kFull || c < g.n_c;
     unsigned long long *cand = ws.cand + (size_t)h * kCandCap;
 
@@ -176,15 +207,27 @@ __global__ __launch_bounds__(kSelectThreads) void k_select_sweep(Geometry g, Wor
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int tt = tb + sub + 32 * u;
-            v[u] = (tt < t1) ? load_row_chunk<kFull>(base + (int64_t)tt * g.st, c, g) : half4_t{0, 0, 0, 0};
+            v[u] = (tt < t1) ? load_row_chunk<kFull>(base + (int64_t)tt * row_stride, c, g) : half4_t{0, 0, 0, 0};
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const bool in = active && (tb + sub + 32 * u) < t1;
             const unsigned long long key = key_of(chunk_norm2(v[u])) & kKeyMask;
-            if (MODE == 0) {
-                if (in)
-                    atomicAdd(&lh[fine_bin(key)], 1u);
+            if (kHist0) {
+                if (in) {
+                    const uint32_t bin = fine_bin(key);
+                    atomicAdd(&lh[bin], 1u);
+                    if (kCollect && bin - keep_lo <= keep_span) {
+                        const uint32_t pos = atomicAdd(&n_staged, 1u);
+                        if (pos < (uint32_t)kStageKeys) {
+                            staged[pos] = key;
+                        } else {
+                            const uint32_t gpos = atomicAdd(&ws.cand_count[h], 1u);
+                            if (gpos < (uint32_t)kCandCap)
+                                cand[gpos] = key;
+                        }
+                    }
+                }
             } else if (MODE == 1) {
                 if (in && fine_bin(key) == bin0) {
                     atomicAdd(&lh[(uint32_t)(key >> kSecShift) & (kBins1 - 1)], 1u);
@@ -192,7 +235,7 @@ __global__ __launch_bounds__(kSelectThreads) void k_select_sweep(Geometry g, Wor
                     if (pos < (uint32_t)kStageKeys) {
                         staged[pos] = key;
                     } else {  // more than the stage holds (many equal norms): straight to the list
-                        const uint32_t gpos = atomicAdd(&ws.cand_count[h], 1u);
+                        const uint32_t gpos = atomicAdd(bin_count, 1u);
                         if (gpos < (uint32_t)kCandCap)
                             cand[gpos] = key;
                     }
@@ -218,22 +261,71 @@ __global__ __launch_bounds__(kSelectThreads) void k_select_sweep(Geometry g, Wor
     }
     if (MODE != 2) {
         __syncthreads();
-        uint32_t *gh = MODE == 0 ? ws.hist0 + (size_t)h * kBins0 : ws.hist1 + (size_t)h * kBins1;
+        uint32_t *gh = MODE == 0   ? ws.hist0 + (size_t)h * kBins0
+                       : MODE == 3 ? ws.hist_s + (size_t)h * kBins0
+                                   : ws.hist1 + (size_t)h * kBins1;
         for (int i = threadIdx.x; i < kLdsBins; i += kSelectThreads) {
             const uint32_t n = lh[i];
             if (n)
                 atomicAdd(&gh[i], n);
         }
     }
-    if (MODE == 1) {
+    if (kStages) {
         const uint32_t n = min(n_staged, (uint32_t)kStageKeys);
+        uint32_t *const counter = MODE == 1 ? bin_count : ws.cand_count + h;
         if (threadIdx.x == 0)
-            list_base = n ? atomicAdd(&ws.cand_count[h], n) : 0u;
+            list_base = n ? atomicAdd(counter, n) : 0u;
         __syncthreads();
         const uint32_t at = list_base;
         for (uint32_t i = threadIdx.x; i < n; i += kSelectThreads)
             if (at + i < (uint32_t)kCandCap)
                 cand[at + i] = staged[i];
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// The two small steps of the sampled select, one workgroup per head.
+//   k_select_range   after MODE 3: the bins of the first digit that hold the sample's ranks within four
+//                    standard deviations of its median rank (a binomial count: sqrt(n)/2 ranks each): for
+//                    rows drawn from one distribution the full data's median falls outside them about once
+//                    in 16000 heads
+//   k_select_decide  after MODE 0: the median's bin from the full histogram, and whether the kept keys
+//                    cover it (inside the predicted bins, list not overflowed)
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kSelectThreads) void k_select_range(Geometry g, WorkspaceOffsets wo, EncodeBatch batch)
+{
+    const EncodeTensor &tn = batch.t[blockIdx.z];
+    const Workspace ws = carve_workspace(tn.ws, wo);
+    __shared__ uint32_t scratch[kSelectThreads + 2];
+    const int h = blockIdx.x;
+    const uint32_t n_s = (uint32_t)((uint64_t)g.B * ((g.T + kSampleStride - 1) / kSampleStride) * g.n_c);
+    const uint32_t mid = (n_s - 1) / 2;
+    const uint32_t margin = (uint32_t)(2.0f * sqrtf((float)n_s)) + 2u;
+    uint32_t lo, hi, before;
+    pick_bin<kBins0, kSelectThreads>(ws.hist_s + (size_t)h * kBins0, mid > margin ? mid - margin : 0u, scratch, lo, before);
+    pick_bin<kBins0, kSelectThreads>(ws.hist_s + (size_t)h * kBins0, min(n_s - 1, mid + margin), scratch, hi, before);
+    lo = max(lo, 1u);                      // only bins that are one 17-bit prefix each hold candidates
+    hi = min(hi, (uint32_t)kBins0 - 2u);
+    if (threadIdx.x == 0) {
+        ws.plan[h].lo = lo <= hi ? lo : (uint32_t)kBins0;
+        ws.plan[h].span = lo <= hi ? hi - lo : 0u;
+    }
+}
+
+__global__ __launch_bounds__(kSelectThreads) void k_select_decide(Geometry g, WorkspaceOffsets wo, EncodeBatch batch)
+{
+    const EncodeTensor &tn = batch.t[blockIdx.z];
+    const Workspace ws = carve_workspace(tn.ws, wo);
+    __shared__ uint32_t scratch[kSelectThreads + 2];
+    const int h = blockIdx.x;
+    const uint32_t rank0 = (uint32_t)(((uint64_t)g.B * g.T * g.n_c - 1) / 2);
+    uint32_t bin0, before0;
+    pick_bin<kBins0, kSelectThreads>(ws.hist0 + (size_t)h * kBins0, rank0, scratch, bin0, before0);
+    if (threadIdx.x == 0) {
+        const bool covered = bin0 - ws.plan[h].lo <= ws.plan[h].span && ws.cand_count[h] <= (uint32_t)kCandCap;
+        ws.plan[h].bin0 = bin0;
+        ws.plan[h].before0 = before0;
+        ws.plan[h].need = fine_bin_is_prefix(bin0) && !covered ? 1u : 0u;
     }
 }
 
@@ -268,7 +360,10 @@ __global__ __launch_bounds__(kSelectThreads) void k_select_finish(Geometry g, Wo
     } else {
         unsigned long long prefix = (unsigned long long)(bin0 + kFineBase);  // key bits fixed so far, right aligned
         int low_bits = kFineShift;
-        uint32_t n_cand = ws.cand_count[h];
+        // sampled select whose kept keys cover the bin: the list also holds keys of the neighbouring bins,
+        // which the comparisons against the prefix below pass over
+        const bool kept = g.select_sampled && !ws.plan[h].need;
+        uint32_t n_cand = kept ? ws.cand_count[h] : *bin_list_counter(g, ws, h);
         if (n_cand > (uint32_t)kCandCap) {
             uint32_t bin1, before1;
             pick_bin<kBins1, kSelectThreads>(ws.hist1 + (size_t)h * kBins1, rank, scratch, bin1, before1);
@@ -291,10 +386,19 @@ __global__ __launch_bounds__(kSelectThreads) void k_select_finish(Geometry g, Wo
             __syncthreads();
             const unsigned long long want = (prefix << (low_bits - remaining)) | low;  // compare key >> remaining
             if (from_list) {
-                for (uint32_t i = threadIdx.x; i < n_cand; i += kSelectThreads) {
-                    const unsigned long long key = cand[i];
-                    if ((key >> remaining) == want)
-                        atomicAdd(&lh[(uint32_t)(key >> shift) & dmask], 1u);
+                // four keys requested before the first is used; a slot past the list reads as a key with
+                // bit 63 set, which no prefix matches
+                for (uint32_t i0 = 0; i0 < n_cand; i0 += 4 * kSelectThreads) {
+                    unsigned long long key[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const uint32_t i = i0 + u * kSelectThreads + threadIdx.x;
+                        key[u] = i < n_cand ? cand[i] : ~0ull;
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        if ((key[u] >> remaining) == want)
+                            atomicAdd(&lh[(uint32_t)(key[u] >> shift) & dmask], 1u);
                 }
             } else {
                 // rare path: sweep the head's rows (every batch entry), one lane per chunk
@@ -619,6 +723,37 @@ hipError_t launch_shard_median_pass(const Geometry &g, const WorkspaceOffsets &w
 // ---------------------------------------------------------------------------------------
 // host-side launch sequences
 // ---------------------------------------------------------------------------------------
+template <bool kFull>
+static void select_sweeps_for(Geometry g, const WorkspaceOffsets &wo, const EncodeBatch &batch, unsigned n, float C,
+                              hipStream_t stream)
+{
+    const dim3 grid((g.T + kSelectRows - 1) / kSelectRows, g.B * g.H, n), heads(g.H, 1, n), block(kSelectThreads);
+    g.select_sampled = (uint64_t)g.B * g.T * g.n_c >= (uint64_t)kSampleMinChunks ? 1 : 0;
+    if (g.select_sampled) {
+        const int n_t = (g.T + kSampleStride - 1) / kSampleStride;
+        const dim3 grid_s((n_t + kSelectRows - 1) / kSelectRows, g.B * g.H, n);
+        hipLaunchKernelGGL((k_select_sweep<3, kFull>), grid_s, block, 0, stream, g, wo, batch);
+        hipLaunchKernelGGL(k_select_range, heads, block, 0, stream, g, wo, batch);
+        hipLaunchKernelGGL((k_select_sweep<0, kFull, true>), grid, block, 0, stream, g, wo, batch);
+        hipLaunchKernelGGL(k_select_decide, heads, block, 0, stream, g, wo, batch);
+    } else {
+        hipLaunchKernelGGL((k_select_sweep<0, kFull>), grid, block, 0, stream, g, wo, batch);
+    }
+    const int rows_late = g.select_sampled ? kSelectRows * kFallbackSpan : kSelectRows;
+    const dim3 grid_late((g.T + rows_late - 1) / rows_late, g.B * g.H, n);
+    hipLaunchKernelGGL((k_select_sweep<1, kFull>), grid_late, block, 0, stream, g, wo, batch);
+    hipLaunchKernelGGL((k_select_sweep<2, kFull>), grid_late, block, 0, stream, g, wo, batch);
+    hipLaunchKernelGGL(k_select_finish<kFull>, heads, block, 0, stream, g, wo, batch, C);
+}
+static void select_sweeps(const Geometry &g, const WorkspaceOffsets &wo, const EncodeBatch &batch, unsigned n, float C,
+                          bool full, hipStream_t stream)
+{
+    if (full)
+        select_sweeps_for<true>(g, wo, batch, n, C, stream);
+    else
+        select_sweeps_for<false>(g, wo, batch, n, C, stream);
+}
+
 hipError_t launch_select_median(const Geometry &g, const WorkspaceOffsets &wo, const EncodeBatch &batch, int n_tensors,
                                 float C, bool skip_select, hipStream_t stream)
 {
@@ -626,18 +761,7 @@ hipError_t launch_select_median(const Geometry &g, const WorkspaceOffsets &wo, c
     uint32_t n_init = (uint32_t)g.H * kBins0;
     hipLaunchKernelGGL(k_init, dim3((n_init + kThreads - 1) / kThreads, 1, n), dim3(kThreads), 0, stream, g, wo, batch);
     if (!skip_select) {
-        dim3 grid((g.T + kSelectRows - 1) / kSelectRows, g.B * g.H, n);
-        if (g.D == 4 * kChunksPerRow) {
-            hipLaunchKernelGGL((k_select_sweep<0, true>), grid, dim3(kSelectThreads), 0, stream, g, wo, batch);
-            hipLaunchKernelGGL((k_select_sweep<1, true>), grid, dim3(kSelectThreads), 0, stream, g, wo, batch);
-            hipLaunchKernelGGL((k_select_sweep<2, true>), grid, dim3(kSelectThreads), 0, stream, g, wo, batch);
-            hipLaunchKernelGGL(k_select_finish<true>, dim3(g.H, 1, n), dim3(kSelectThreads), 0, stream, g, wo, batch, C);
-        } else {
-            hipLaunchKernelGGL((k_select_sweep<0, false>), grid, dim3(kSelectThreads), 0, stream, g, wo, batch);
-            hipLaunchKernelGGL((k_select_sweep<1, false>), grid, dim3(kSelectThreads), 0, stream, g, wo, batch);
-            hipLaunchKernelGGL((k_select_sweep<2, false>), grid, dim3(kSelectThreads), 0, stream, g, wo, batch);
-            hipLaunchKernelGGL(k_select_finish<false>, dim3(g.H, 1, n), dim3(kSelectThreads), 0, stream, g, wo, batch, C);
-        }
+        select_sweeps(g, wo, batch, n, C, g.D == 4 * kChunksPerRow, stream);
     }
     return hipGetLastError();
 }

@@ -91,7 +91,7 @@ bench.py line of the same build (python bench.py --workload {wl}; {d['warmup']} 
       executed on the matrix cores: {ex['instruction']}, {ex['achieved']:.0f} TFLOP/s of 2500 = {ex['frac'] * 100:.1f} %
   decode kernel: avg launch {rd['avg_launch_ms'] * 1e3:.1f} us for {rd['tensors_per_launch']:g} tensors (median {rd['median_launch_ms'] * 1e3:.1f}, min {rd['min_launch_ms'] * 1e3:.1f}; {rd['avg_launch_ms'] * 1e3 / rd['tensors_per_launch']:.1f} us per tensor)  ->  {rd['achieved']:.0f} GB/s of 8000 = {rd['frac'] * 100:.1f} % ({rd['bytes_per_chunk']:.2f} B per chunk)
   encode {d['encode_elems_per_s']:.3e} elems/s, decode {d['decode_elems_per_s']:.3e} elems/s, encode+decode {d['value']:.3e} elems/s ({d['ms_per_step']:.1f} ms per step)
-  encode phases per tensor: median select {d['encode_phase_ms_per_tensor']['median_select'] * 1e3:.1f} us ({d['median_select_GBs']:.0f} GB/s over its two sweeps), search + quantise + pack {d['encode_phase_ms_per_tensor']['search_quantise_pack'] * 1e3:.1f} us, outlier scan + gather {d['encode_phase_ms_per_tensor']['outlier_scan_gather'] * 1e3:.1f} us
+  encode phases per tensor: median select {d['encode_phase_ms_per_tensor']['median_select'] * 1e3:.1f} us ({d['median_select_GBs']:.0f} GB/s over the {d['median_select_reads']:.4g} reads of the tensor it makes), search + quantise + pack {d['encode_phase_ms_per_tensor']['search_quantise_pack'] * 1e3:.1f} us, outlier scan + gather {d['encode_phase_ms_per_tensor']['outlier_scan_gather'] * 1e3:.1f} us
   outlier fraction {d['outlier_fraction']:.4f}, stored bits per element {d['bits_per_element_stored']:.3f}""")
     if has_att:
         at = d["attend"]

@@ -461,6 +461,37 @@ def test_median_of_concentrated_norms(spread):
     assert stats["outliers"] > 0
 
 
+def test_sampled_select_and_its_fallbacks():
+    """Heads of at least 2^17 chunks: the select predicts the median's bin from every 16th row.  One head
+    whose sample is representative, one whose sampled rows are eight times smaller than the rest (the
+    prediction misses and the bin is collected by a sweep of its own), one of equal norms (every list
+    overflows: the slow exact path), one of zeros, and one whose sampled rows alone are zero.
+    Thresholds bit for bit."""
+    B, H, T, S = 1, 5, 8192, 1
+    gen = torch.Generator().manual_seed(77)
+    x = torch.randn(B, H, T, 128, generator=gen) * torch.exp(0.5 * torch.randn(B, H, T, 1, generator=gen))
+    x[0, 1, ::16] *= 0.125
+    x[0, 2] = 0.75
+    x[0, 3] = 0.0
+    x[0, 4, ::16] = 0.0
+    x = x.half()
+    sec_t, sec = _sec(4, H, S)
+    xb = _bits(x)
+    e = oracle.encode(xb, sec, rows=np.arange(0, B * H * T, 211))
+    x_dev, sec_dev = x.to(DEV), sec_t.to(DEV)
+    g = gpu_encode(x_dev, sec_dev)
+    stats = compare_encode(g, e, xb, sec)
+    print(stats, flush=True)
+    params = hq.params_for(x_dev, S)
+    ws = hq.alloc_workspace(params, DEV)
+    hq.hqmq_encode(params, x_dev, sec_dev, hq.alloc_encoded(params, DEV), ws)
+    thr = hq.hqmq_thresholds(params, ws)
+    torch.cuda.synchronize()
+    c = float(np.float32(3.0))
+    assert np.array_equal(thr.cpu().numpy().view(np.uint64), ((c * c) * e.m2).view(np.uint64))
+    assert e.m2[3] == 0.0 and e.m2[2] == 4 * 0.75 ** 2
+
+
 def test_exact_tie_structured_input():
     """Chunks like (a, a, 0, 0) sit on the boundary between several codewords when the
     secondary is the identity; whichever the GPU picks must score as the oracle's best."""
