@@ -618,6 +618,31 @@ def test_strided_input_and_output():
     compare_decode(out.contiguous().cpu().numpy().view(np.uint16), want, r_hat, e.flag)
 
 
+@pytest.mark.parametrize("D", [128, 96])
+def test_strided_input_long_enough_for_the_sampled_select(D):
+    """[B, T, H, D] memory order with heads of more than 2^17 chunks (the select reads every 16th row first)
+    and a pitch above D: thresholds bit for bit, encode on sampled rows."""
+    B, H, T, S = 2, 2, 3000 if D == 128 else 4000, 8
+    x = _lognormal_tensor(B, H, T, seed=31, D=D)
+    sec_t, sec = _sec(2, H, S)
+    xb = _bits(x)
+    e = oracle.encode(xb, sec, rows=np.arange(0, B * H * T, 53))
+    store = torch.zeros(B, T, H, D + 8, dtype=torch.float16)
+    store[..., :D] = x.permute(0, 2, 1, 3)
+    view = store.to(DEV).permute(0, 2, 1, 3)[..., :D]              # logical [B, H, T, D], pitch D + 8
+    assert not view.is_contiguous()
+    g = gpu_encode(view, sec_t.to(DEV))
+    stats = compare_encode(g, e, xb, sec)
+    print(stats, flush=True)
+    params = hq.params_for(view, S)
+    ws = hq.alloc_workspace(params, DEV)
+    hq.hqmq_encode(params, view, sec_t.to(DEV), hq.alloc_encoded(params, DEV), ws)
+    thr = hq.hqmq_thresholds(params, ws)
+    torch.cuda.synchronize()
+    c = float(np.float32(3.0))
+    assert np.array_equal(thr.cpu().numpy().view(np.uint64), ((c * c) * e.m2).view(np.uint64))
+
+
 def test_decode_batch_equals_single_decodes():
     """One launch for many tensors of a shape must give each tensor exactly hqmq_decode's bytes
     (40 tensors: more than one launch's worth of descriptors)."""
