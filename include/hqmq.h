@@ -42,13 +42,15 @@
 extern "C" {
 #endif
 
-/* Largest secondary codebook every entry point takes (the paper sweeps S = 24 .. 192; the search keeps
- * a head's codebook and its matrix operands in a CU's LDS, which 512 entries fill). */
-#define HQMQ_MAX_S 512
+/* Largest secondary codebook every entry point takes: a joint index k = p S + s < 24 S has to fit 16 bits.
+ * The paper sweeps S = 24 .. 192.  Up to 512 entries the search keeps a head's codebook and its matrix operands
+ * in a CU's LDS; beyond that every chunk scores all S secondaries in fp32 on the vector ALUs: the same result
+ * (the decision is taken on fp32 scores either way), several times slower per codeword. */
+#define HQMQ_MAX_S 2730
 
 #define HQMQ_OK 0
 #define HQMQ_ERR_INVALID_ARG (-1)      /* null pointer, non-positive size, misaligned pointer or stride */
-#define HQMQ_ERR_UNSUPPORTED (-2)      /* D > 128 (hqmq_attend: D not 64, 96 or 128), S outside 1..512, b_r outside 1..8, C not a positive finite number */
+#define HQMQ_ERR_UNSUPPORTED (-2)      /* D > 128 (hqmq_attend: D not 64, 96 or 128), S outside 1..2730, b_r outside 1..8, C not a positive finite number */
 #define HQMQ_ERR_BUFFER_TOO_SMALL (-3) /* workspace smaller than hqmq_sizes() asks for */
 #define HQMQ_ERR_HIP (-4)              /* a HIP call failed; see hqmq_last_hip_error() */
 
@@ -130,7 +132,7 @@ int32_t hqmq_init(void);
  * its linear index ((layer*2 + role)*n_kv_heads + head)*S + s.  role 0 = K, 1 = V.
  *   sec_host  HOST, out, fp32 [n_layers][2][n_kv_heads][S][4], caller-owned.
  * Pure host function (no GPU work).  Errors: INVALID_ARG (null pointer, non-positive size),
- * UNSUPPORTED (S > 512: the limit of hqmq_encode and hqmq_decode). */
+ * UNSUPPORTED (S > HQMQ_MAX_S: the limit of hqmq_encode and hqmq_decode). */
 int32_t hqmq_build_codebooks(uint64_t seed, int32_t n_layers, int32_t n_kv_heads, int32_t S,
                              float *sec_host);
 

@@ -17,7 +17,7 @@ HQMQ_FLAG_NO_OUTLIERS = 1
 HQMQ_FLAG_CHECK_FINITE = 2
 HQMQ_STATUS_OUTLIER_OVERFLOW = 1
 HQMQ_STATUS_NONFINITE = 2
-HQMQ_MAX_S = 512
+HQMQ_MAX_S = 2730
 HQMQ_STATIC_SCRATCH_BYTES = 16 << 20
 _ERRORS = {-1: "HQMQ_ERR_INVALID_ARG", -2: "HQMQ_ERR_UNSUPPORTED", -3: "HQMQ_ERR_BUFFER_TOO_SMALL",
            -4: "HQMQ_ERR_HIP"}

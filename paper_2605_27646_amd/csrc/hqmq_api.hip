@@ -40,6 +40,8 @@ static hipError_t ensure_device_setup(void **scratch_out = nullptr)
         std::lock_guard<std::mutex> lock(g_setup_mutex);
         if (!(tracked && g_device_ready[device].load(std::memory_order_relaxed))) {
             err = prepare_search_kernels();
+            if (err == hipSuccess)
+                err = prepare_attend_kernels();
             if (err != hipSuccess)
                 return err;
             void *ptr = nullptr;
@@ -112,6 +114,7 @@ static Geometry make_geometry(const hqmq_params *p)
     g.vec_ok = (p->D % 4 == 0 && p->stride_b % 4 == 0 && p->stride_h % 4 == 0 && p->stride_t % 4 == 0) ? 1 : 0;
     g.S = p->S;
     g.S16 = (p->S + 15) / 16;
+    g.A16 = p->S <= kScreenMaxS ? g.S16 : 0;
     g.b_r = p->b_r;
     g.w_idx = index_bits(p->S);
     g.w = g.w_idx + p->b_r;
@@ -128,7 +131,7 @@ static Geometry make_geometry(const hqmq_params *p)
     g.check_finite = (p->flags & HQMQ_FLAG_CHECK_FINITE) ? 1 : 0;
     g.fused_by_head = 0;
     g.select_sampled = 0;
-    g.search_rows = search_rows_for(p->T, g.S16, g.D, g.row_words);
+    g.search_rows = search_rows_for(p->T, g.S16, g.A16, g.D, g.row_words);
     g.n_search_blocks_per_seg = (uint32_t)((p->T + g.search_rows - 1) / g.search_rows);
     return g;
 }
@@ -156,7 +159,7 @@ static WorkspaceLayout workspace_layout(const Geometry &g)
     l.cand = take((uint64_t)g.H * kCandCap * sizeof(unsigned long long));
     l.block_sum = take(n_blocks * sizeof(uint32_t));
     l.block_pre = take(n_blocks * sizeof(uint32_t));
-    l.aop = take((uint64_t)g.H * g.S16 * kATiles * 64 * 16);
+    l.aop = take((uint64_t)g.H * g.A16 * kATiles * 64 * 16);
     l.total = off;
     return l;
 }
@@ -342,7 +345,7 @@ static int32_t encode_impl(const hqmq_params *params, int32_t n_tensors, const v
             // of 128 elements): a workgroup per head takes them all, and builds the head's tables once instead
             // of once per batch entry; more rows than that are faster on workgroups of their own
             Geometry gf = g;
-            const int waves = search_waves_for(g.S16, g.D, g.row_words, g.search_rows);
+            const int waves = search_waves_for(g.S16, g.A16, g.D, g.row_words, g.search_rows);
             gf.fused_by_head = (g.B > 1 && (int64_t)g.B * g.T <= 2 * waves && g.D == 4 * kChunksPerRow) ? 1 : 0;
             err = mark(1);
             if (err == hipSuccess)
@@ -617,6 +620,11 @@ static int32_t attend_impl(const hqmq_params *params, int32_t n_q_heads, const v
     const AttendPlan plan = plan_attend(g, G);
     if (workspace_bytes < plan.total_bytes)
         return HQMQ_ERR_BUFFER_TOO_SMALL;
+    {  // the kernels may ask for more LDS than a launch gets by default (large S)
+        const hipError_t ready = ensure_device_setup();
+        if (ready != hipSuccess)
+            return hip_failed(ready);
+    }
 
     auto side = [](const hqmq_encoded *e, const float *sec, uint64_t cap) {
         AttendSide s;

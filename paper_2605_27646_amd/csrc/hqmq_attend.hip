@@ -36,7 +36,7 @@ namespace {
 constexpr int kAttThreads = 256;
 constexpr int kAttWaves = kAttThreads / 64;
 constexpr int kStageRows = 16;                      // rows per wave and tile
-constexpr int kMaxW = 24;                           // w <= 22
+constexpr int kMaxW = 24;                           // w = w_idx + b_r <= 16 + 8
 constexpr int kStageWords = kStageRows * kMaxW + 4; // + padding: a 2-word window may start at the last word
 constexpr int kPaySlots = 128;                      // outlier payloads of a wave's 16 rows kept in LDS
 constexpr int kSideWords = kStageWords + 3 * kStageRows + 2 * kPaySlots;  // one side (K or V) of one wave
@@ -656,6 +656,21 @@ AttendPlan plan_attend(const Geometry &g, int G)
     p.acc_bytes = (heads * p.n_splits * 128 * sizeof(float) + 255) / 256 * 256;
     p.total_bytes = p.ml_bytes + p.acc_bytes;
     return p;
+}
+
+// Codebooks of more than about 1300 secondaries put the two tables of a head past the 64 KiB of LDS that a
+// launch gets without asking.
+hipError_t prepare_attend_kernels()
+{
+    const void *variants[] = {
+        reinterpret_cast<const void *>(&k_attend_partial<true, 32>), reinterpret_cast<const void *>(&k_attend_partial<false, 32>),
+        reinterpret_cast<const void *>(&k_attend_partial<true, 24>), reinterpret_cast<const void *>(&k_attend_partial<false, 24>),
+        reinterpret_cast<const void *>(&k_attend_partial<true, 16>), reinterpret_cast<const void *>(&k_attend_partial<false, 16>),
+    };
+    hipError_t err = hipSuccess;
+    for (size_t i = 0; i < sizeof(variants) / sizeof(variants[0]) && err == hipSuccess; ++i)
+        err = hipFuncSetAttribute(variants[i], hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCu);
+    return err;
 }
 
 hipError_t launch_attend(const Geometry &g, const AttendArgs &a, hipStream_t stream)

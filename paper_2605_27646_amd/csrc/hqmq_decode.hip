@@ -36,8 +36,8 @@ constexpr int kGeneralRows = 64;                    // rows per workgroup of the
 template <int kPairs, int kRowsW>
 struct DecodeShape {
     static constexpr int kRows = kRowsW * kDecWaves;                 // rows per workgroup
-    // code words of a row at most: 2 kPairs chunks of w <= 22 bits (w_idx <= 14 for S <= 512, b_r <= 8)
-    static constexpr int kMaxRowWords = kPairs == 16 ? 24 : (2 * kPairs * 22 + 31) / 32;
+    // code words of a row at most: 2 kPairs chunks of w <= 24 bits (w_idx <= 16, b_r <= 8)
+    static constexpr int kMaxRowWords = (2 * kPairs * 24 + 31) / 32;
     static constexpr int kLoadsPerLane = (kRowsW * kMaxRowWords + 63) / 64;  // code words per lane
     // every lane parks all its words: whole multiples of 64, + 2 words of padding for the 3-word window
     static constexpr int kStageWords = 64 * kLoadsPerLane + 2;

@@ -32,6 +32,7 @@ static_assert(kBins0 * sizeof(uint32_t) <= kCandCap * sizeof(unsigned long long)
               "the sample histogram borrows the candidate list's memory");
 constexpr int kSelectThreads = 1024; // workgroup of the select sweeps
 constexpr int kSelectRows = 1024;    // rows of one (b, h) segment per select workgroup
+constexpr int kScreenMaxS = 512;      // largest S whose search is screened on the matrix cores (operand tables in LDS)
 constexpr int kSampleStride = 16;     // the sampled select reads every 16th row of a head first ...
 constexpr int kSampleMinChunks = 1 << 17;  // ... when the head has at least this many chunks
 constexpr int kSmallListRows = 4096;   // a tensor of at most this many rows and kSmallListBlocks search workgroups,
@@ -64,11 +65,13 @@ struct Geometry {
     int32_t vec_ok;       // D and the strides are multiples of 4: every chunk is one aligned 8-byte access
     int32_t S;            // secondaries per head
     int32_t S16;          // ceil(S / 16): groups of 16 secondaries (4 MFMA s-blocks) of the search loop
+    int32_t A16;          // groups held as matrix operands and screened on the matrix cores: S16, or 0 for S > kScreenMaxS
+                          // (every chunk then scores all S secondaries in fp32 on the vector ALUs: exact, slow)
     int32_t b_r, w_idx, w;
     int64_t sb, sh, st;   // element strides
     float inv_L;          // 1 / (2^b_r - 1)
     int32_t log2_S;       // log2(S) when S is a power of two, else -1
-    float inv_S;          // (1/S)(1 + 2^-18): uint(float(k) * inv_S) == k / S for every k < 48 S, S <= 512
+    float inv_S;          // (1/S)(1 + 2^-18): uint(float(k) * inv_S) == k / S for every k < 2^16, S <= 2730
     int32_t check_finite;  // HQMQ_FLAG_CHECK_FINITE: the search reports chunks holding an infinity or a NaN in the status word
     int32_t select_sampled;  // the median select predicts the median's bin from a sample of the rows (large heads only)
     int32_t fused_by_head;  // fused search only: one workgroup per head takes the rows of all batch entries (B T <= 64)
@@ -80,9 +83,9 @@ struct Geometry {
 // MFMA A operands and secondaries, and the per-row state, which for rows of
 // 128 elements is two rows of code words per wave and a counter per row, and for other row lengths a
 // running maximum, flag word, scale, counter and the code words of every row of the workgroup.
-inline size_t search_lds_bytes(int S16, int D, int row_words, int waves, int rows)
+inline size_t search_lds_bytes(int S16, int A16, int D, int row_words, int waves, int rows)
 {
-    const size_t tables = (size_t)S16 * kATiles * 64 * 16 + (size_t)S16 * 16 * 4 * 4;
+    const size_t tables = (size_t)A16 * kATiles * 64 * 16 + (size_t)S16 * 16 * 4 * 4;
     if (D == 4 * kChunksPerRow)
         return tables + ((size_t)waves * 2 * 32 + (size_t)rows) * 4;
     return tables + (size_t)rows * (8 + 4 + 4 + 4 + 4 * (size_t)row_words);
@@ -95,29 +98,29 @@ constexpr size_t kLdsPerCu = 160 * 1024;
 // workgroups of 4, while four or more small workgroups, where they fit, are 7 to 13 % faster than the large one).
 // Otherwise 4 waves when two workgroups fit a CU's LDS, else one workgroup of 8, which keeps two waves
 // on every SIMD.
-inline int search_waves_for(int S16, int D, int row_words, int rows)
+inline int search_waves_for(int S16, int A16, int D, int row_words, int rows)
 {
-    if (rows >= kSearchRowsLarge && kLdsPerCu / search_lds_bytes(S16, D, row_words, 4, rows) < 4 &&
-        search_lds_bytes(S16, D, row_words, 16, rows) <= kLdsPerCu)
+    if (rows >= kSearchRowsLarge && kLdsPerCu / search_lds_bytes(S16, A16, D, row_words, 4, rows) < 4 &&
+        search_lds_bytes(S16, A16, D, row_words, 16, rows) <= kLdsPerCu)
         return 16;
-    return 2 * search_lds_bytes(S16, D, row_words, 4, rows) > kLdsPerCu ? 8 : 4;
+    return 2 * search_lds_bytes(S16, A16, D, row_words, 4, rows) > kLdsPerCu ? 8 : 4;
 }
 
 // Rows per search workgroup.  Four or more 4-wave workgroups per CU are the fastest shape (measured 3 to
 // 7 % ahead of one 16-wave workgroup): the most rows with which they fit, 256 for long segments (the head's
 // operand table is copied less often) or 64.  With tables too large for that: one 16-wave workgroup of 512
 // or 256 rows per CU, else 64 rows.
-inline int search_rows_for(int T, int S16, int D, int row_words)
+inline int search_rows_for(int T, int S16, int A16, int D, int row_words)
 {
-    const auto four_fit = [&](int rows) { return kLdsPerCu / search_lds_bytes(S16, D, row_words, 4, rows) >= 4; };
+    const auto four_fit = [&](int rows) { return kLdsPerCu / search_lds_bytes(S16, A16, D, row_words, 4, rows) >= 4; };
     if (T >= kSearchRowsSwitch && four_fit(kSearchRowsLarge))
         return kSearchRowsLarge;
     if (four_fit(kSearchRowsSmall))
         return kSearchRowsSmall;
-    if (T >= kSearchRowsSwitchHuge && search_waves_for(S16, D, row_words, kSearchRowsHuge) == 16)
+    if (T >= kSearchRowsSwitchHuge && search_waves_for(S16, A16, D, row_words, kSearchRowsHuge) == 16)
         return kSearchRowsHuge;
     if (T >= kSearchRowsSwitch &&
-        (D == 4 * kChunksPerRow || 2 * search_lds_bytes(S16, D, row_words, 4, kSearchRowsLarge) <= kLdsPerCu))
+        (D == 4 * kChunksPerRow || 2 * search_lds_bytes(S16, A16, D, row_words, 4, kSearchRowsLarge) <= kLdsPerCu))
         return kSearchRowsLarge;
     return kSearchRowsSmall;
 }
@@ -317,6 +320,7 @@ hipError_t launch_outlier_list_small(const Geometry &g, const WorkspaceOffsets &
 hipError_t launch_outlier_list(const Geometry &g, const WorkspaceOffsets &wo, const EncodeBatch &batch, int n_tensors,
                                hipStream_t stream);
 hipError_t launch_decode(const Geometry &g, const DecodeBatch &batch, int n_tensors, hipStream_t stream);
+hipError_t prepare_attend_kernels();  // once per device, before the first launch_attend on it
 hipError_t launch_attend(const Geometry &g, const AttendArgs &args, hipStream_t stream);
 
 }  // namespace hqmq

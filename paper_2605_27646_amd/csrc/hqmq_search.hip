@@ -297,21 +297,27 @@ __device__ __forceinline__ uint32_t search_codeword(const Geometry &g, int lane,
 #pragma unroll
     for (int e = 0; e < 16; ++e)
         zero16[e] = 0.f;
-    // groups this wave screens
-    const int per_wave = kCoop ? (g.S16 + kWaves - 1) / kWaves : g.S16;
-    const int grp_begin = kCoop ? min(wv * per_wave, g.S16) : 0;
-    const int grp_end = kCoop ? min(grp_begin + per_wave, g.S16) : g.S16;
+    // groups this wave screens: those held as matrix operands (none beyond kScreenMaxS secondaries: the
+    // screen is then skipped and every chunk takes the fp32 search below)
+    const int n_grp = g.A16;
+    const int per_wave = kCoop ? (n_grp + kWaves - 1) / kWaves : n_grp;
+    const int grp_begin = kCoop ? min(wv * per_wave, n_grp) : 0;
+    const int grp_end = kCoop ? min(grp_begin + per_wave, n_grp) : n_grp;
     const uint4 *arow = amat + lane;
-    half8_t a0 = __builtin_bit_cast(half8_t, arow[2 * min(grp_begin, g.S16 - 1) * 64]),
-            a1 = __builtin_bit_cast(half8_t, arow[2 * min(grp_begin, g.S16 - 1) * 64 + 64]);
-    // the product of (tile 0, chunk slot 0) of the next group is issued before the arithmetic on the last
-    // product of this one: a VALU instruction right behind the MFMA it depends on idles for the depth of
-    // the matrix pipeline
-    float16_t ahead = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, bop[0], zero16, 0, 0, 0);
+    half8_t a0 = __builtin_bit_cast(half8_t, make_uint4(0u, 0u, 0u, 0u)), a1 = a0;
+    float16_t ahead = zero16;
+    if (n_grp > 0) {  // uniform
+        a0 = __builtin_bit_cast(half8_t, arow[2 * min(grp_begin, n_grp - 1) * 64]);
+        a1 = __builtin_bit_cast(half8_t, arow[2 * min(grp_begin, n_grp - 1) * 64 + 64]);
+        // the product of (tile 0, chunk slot 0) of the next group is issued before the arithmetic on the last
+        // product of this one: a VALU instruction right behind the MFMA it depends on idles for the depth of
+        // the matrix pipeline
+        ahead = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, bop[0], zero16, 0, 0, 0);
+    }
     for (int grp = grp_begin; grp < grp_end; ++grp) {
         // the next group's operands replace this group's as soon as their last product is issued (the
         // last group re-reads itself; that product is dropped)
-        const uint4 *anext = arow + 2 * min(grp + 1, g.S16 - 1) * 64;
+        const uint4 *anext = arow + 2 * min(grp + 1, n_grp - 1) * 64;
         // over the group's 8 secondaries on this lane: GA = largest |v_i| (best axis element), GH = largest
         // |v_0|+|v_1|+|v_2|+|v_3| (twice the best half-integer element)
         float GA[2], GH[2];
@@ -400,14 +406,14 @@ __device__ __forceinline__ uint32_t search_codeword(const Geometry &g, int lane,
         }
     }
     const bool live = !flagged && r2 != 0.0;
-    const bool unclear = live && !(top - runner >= kScreenBand * top);
+    const bool unclear = live && (n_grp == 0 || !(top - runner >= kScreenBand * top));
 
     // The 8 candidates first + 2 t in ascending order, strict comparison: the lowest s wins a tie.  Padding
     // secondaries (zeros, s >= S) score 0 and every real one scores at least |q_s| / sqrt(2) > 0 for a
     // non-zero chunk, so a group that won the screen never yields a padding index; the bound below only
     // keeps the index inside the codebook should the input break the contract (non-finite values).
     int bs = first;
-    if (live) {
+    if (live && n_grp > 0) {
         const float *cq = secl + 4 * first;  // < 16 S16 entries: inside the padded table
         float bsc = -1.f;
         int bt = 0;
@@ -509,8 +515,8 @@ __global__ __launch_bounds__(kThreads) void k_prepare_operands(Geometry g, Works
     const Workspace ws = carve_workspace(tn.ws, wo);
     const int h = blockIdx.y;
     const int idx = blockIdx.x * kThreads + threadIdx.x;
-    if (idx < g.S16 * kATiles * 64)
-        ws.aop[(size_t)h * g.S16 * kATiles * 64 + idx] = operand_entry(tn.sec + (size_t)h * g.S * 4, g.S, idx);
+    if (idx < g.A16 * kATiles * 64)
+        ws.aop[(size_t)h * g.A16 * kATiles * 64 + idx] = operand_entry(tn.sec + (size_t)h * g.S * 4, g.S, idx);
 }
 
 // kWaves: 4 (several workgroups per CU); 16 for workgroups of 256 or 512 rows whose tables would leave
@@ -534,7 +540,7 @@ __global__ __launch_bounds__(64 * kWaves, kFused ? 1 : 4) void k_search(Geometry
     const float *__restrict__ sec = tn.sec;
     extern __shared__ float smem[];
     uint4 *amat = reinterpret_cast<uint4 *>(smem);
-    float *secl = reinterpret_cast<float *>(amat + (size_t)g.S16 * kATiles * 64);
+    float *secl = reinterpret_cast<float *>(amat + (size_t)g.A16 * kATiles * 64);
     uint32_t *pack = reinterpret_cast<uint32_t *>(secl + (size_t)g.S16 * 16 * 4);
     uint32_t *rcnt = pack + kWaves * 2 * 32;
 
@@ -580,14 +586,14 @@ __global__ __launch_bounds__(64 * kWaves, kFused ? 1 : 4) void k_search(Geometry
         *reinterpret_cast<float4_t *>(secl + 4 * s) = q;
     }
     if (kFused) {
-        for (int idx = tid; idx < g.S16 * kATiles * 64; idx += kThreadsS)
+        for (int idx = tid; idx < g.A16 * kATiles * 64; idx += kThreadsS)
             amat[idx] = operand_entry(sec_h, g.S, idx);
         if (coop)  // the one pass writes the counters of rows 0 and 1 only
             for (int r = tid; r < kRows; r += kThreadsS)
                 rcnt[r] = 0;
     } else {
-        const uint4 *src = ws.aop + (size_t)h * g.S16 * kATiles * 64;
-        for (int idx = tid; idx < g.S16 * kATiles * 64; idx += kThreadsS)
+        const uint4 *src = ws.aop + (size_t)h * g.A16 * kATiles * 64;
+        for (int idx = tid; idx < g.A16 * kATiles * 64; idx += kThreadsS)
             amat[idx] = src[idx];
     }
 
@@ -739,7 +745,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_search_flat(Geometry g, Workspa
     const _Float16 *__restrict__ x = tn.x;
     extern __shared__ float smem[];
     uint4 *amat = reinterpret_cast<uint4 *>(smem);
-    float *secl = reinterpret_cast<float *>(amat + (size_t)g.S16 * kATiles * 64);
+    float *secl = reinterpret_cast<float *>(amat + (size_t)g.A16 * kATiles * 64);
     unsigned long long *rowmax = reinterpret_cast<unsigned long long *>(secl + (size_t)g.S16 * 16 * 4);
     uint32_t *fword = reinterpret_cast<uint32_t *>(rowmax + kRows);
     uint32_t *sig = fword + kRows;
@@ -764,11 +770,11 @@ __global__ __launch_bounds__(64 * kWaves) void k_search_flat(Geometry g, Workspa
         *reinterpret_cast<float4_t *>(secl + 4 * s) = q;
     }
     if (kFused) {
-        for (int idx = tid; idx < g.S16 * kATiles * 64; idx += kThreadsS)
+        for (int idx = tid; idx < g.A16 * kATiles * 64; idx += kThreadsS)
             amat[idx] = operand_entry(sec_h, g.S, idx);
     } else {
-        const uint4 *src = ws.aop + (size_t)h * g.S16 * kATiles * 64;
-        for (int idx = tid; idx < g.S16 * kATiles * 64; idx += kThreadsS)
+        const uint4 *src = ws.aop + (size_t)h * g.A16 * kATiles * 64;
+        for (int idx = tid; idx < g.A16 * kATiles * 64; idx += kThreadsS)
             amat[idx] = src[idx];
     }
     for (int i = tid; i < kRows; i += kThreadsS) {
@@ -901,7 +907,9 @@ hipError_t prepare_search_kernels()
 // The fused form exists for the workgroup shapes that short segments get: 64 rows, 4 or 8 waves.
 bool search_fused_available(const Geometry &g)
 {
-    const int waves = search_waves_for(g.S16, g.D, g.row_words, g.search_rows);
+    if (g.A16 == 0)
+        return false;  // no screen: the general form
+    const int waves = search_waves_for(g.S16, g.A16, g.D, g.row_words, g.search_rows);
     return g.search_rows == kSearchRowsSmall && (waves == 4 || waves == 8);
 }
 
@@ -909,8 +917,8 @@ hipError_t launch_search_fused(const Geometry &g, const WorkspaceOffsets &wo, co
                                hipStream_t stream)
 {
     dim3 grid((g.T + g.search_rows - 1) / g.search_rows, g.fused_by_head ? g.H : g.B * g.H, (unsigned)n_tensors);
-    const int waves = search_waves_for(g.S16, g.D, g.row_words, g.search_rows);
-    const size_t lds = search_lds_bytes(g.S16, g.D, g.row_words, waves, g.search_rows);
+    const int waves = search_waves_for(g.S16, g.A16, g.D, g.row_words, g.search_rows);
+    const size_t lds = search_lds_bytes(g.S16, g.A16, g.D, g.row_words, waves, g.search_rows);
     if (g.D == 4 * kChunksPerRow) {
         if (waves == 8)
             hipLaunchKernelGGL((k_search<8, kSearchRowsSmall, true>), grid, dim3(512), lds, stream, g, wo, batch);
@@ -930,10 +938,11 @@ hipError_t launch_search(const Geometry &g, const WorkspaceOffsets &wo, const En
 {
     dim3 grid((g.T + g.search_rows - 1) / g.search_rows, g.B * g.H, (unsigned)n_tensors);
     const bool full = g.D == 4 * kChunksPerRow;
-    const int waves = search_waves_for(g.S16, g.D, g.row_words, g.search_rows);
-    const size_t lds = search_lds_bytes(g.S16, g.D, g.row_words, waves, g.search_rows);
-    hipLaunchKernelGGL(k_prepare_operands, dim3((g.S16 * kATiles * 64 + kThreads - 1) / kThreads, g.H, (unsigned)n_tensors),
-                       dim3(kThreads), 0, stream, g, wo, batch);
+    const int waves = search_waves_for(g.S16, g.A16, g.D, g.row_words, g.search_rows);
+    const size_t lds = search_lds_bytes(g.S16, g.A16, g.D, g.row_words, waves, g.search_rows);
+    if (g.A16 > 0)
+        hipLaunchKernelGGL(k_prepare_operands, dim3((g.A16 * kATiles * 64 + kThreads - 1) / kThreads, g.H, (unsigned)n_tensors),
+                           dim3(kThreads), 0, stream, g, wo, batch);
     const bool large = g.search_rows == kSearchRowsLarge;
 #define HQMQ_LAUNCH(KERNEL, W, R) hipLaunchKernelGGL((KERNEL<W, R>), grid, dim3(64 * W), lds, stream, g, wo, batch)
     if (full) {

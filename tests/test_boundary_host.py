@@ -86,7 +86,7 @@ def test_sizes_of_other_head_dimensions(lib, D, S, b_r):
 
 @pytest.mark.parametrize("kw,code", [
     (dict(B=0), -1), (dict(T=-3), -1), (dict(stride_t=132), -1), (dict(stride_t=64), -1), (dict(stride_h=-8), -1),
-    (dict(D=132, stride_t=136), -2), (dict(D=130), -2), (dict(D=0), -1), (dict(D=96, stride_t=64), -1), (dict(S=0), -2), (dict(S=513), -2), (dict(b_r=0), -2), (dict(b_r=9), -2),
+    (dict(D=132, stride_t=136), -2), (dict(D=130), -2), (dict(D=0), -1), (dict(D=96, stride_t=64), -1), (dict(S=0), -2), (dict(S=2731), -2), (dict(b_r=0), -2), (dict(b_r=9), -2),
     (dict(C=0.0), -2), (dict(C=float("nan")), -2), (dict(C=float("inf")), -2), (dict(B=70000, H=1), -2),
     (dict(T=1 << 27), -2),
 ])
@@ -128,7 +128,7 @@ def test_encode_decode_reject_bad_arguments_without_touching_the_gpu(lib):
     assert dec(C.byref(p), C.byref(good), 0, None, 0x1000, None) == -1
     assert dec(C.byref(p), C.byref(good), 0, 0x1000, 0x1008, None) == -1
     assert dec(C.byref(p), None, 0, 0x1000, 0x1000, None) == -1
-    assert dec(C.byref(_params(S=600)), C.byref(good), 0, 0x1000, 0x1000, None) == -2
+    assert dec(C.byref(_params(S=2731)), C.byref(good), 0, 0x1000, 0x1000, None) == -2
     db = lib.hqmq_decode_batch
     encs = (binding._Encoded * 2)(good, good)
     caps = (C.c_uint64 * 2)(0, 0)
@@ -289,3 +289,14 @@ def test_bench_refuses_more_than_one_gpu():
                        text=True, timeout=120)
     assert r.returncode != 0
     assert "single-GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_division_by_the_biased_reciprocal_is_exact():
+    """Decode and attention split a joint index into k / S and k mod S with uint(float(k) * inv_S),
+    inv_S = fl(fl(1 / S) * (1 + 2^-18)) as the library's host code forms it: exact for every 16-bit k and
+    every supported S (fp32 products as the GPU rounds them, conversion by truncation)."""
+    k = np.arange(0, 65536, dtype=np.uint32)
+    kf = k.astype(np.float32)
+    for S in range(1, hq.HQMQ_MAX_S + 1):
+        inv = np.float32(np.float32(1.0) / np.float32(S)) * np.float32(1.0 + 2.0 ** -18)
+        assert np.array_equal((kf * np.float32(inv)).astype(np.uint32), k // S), S

@@ -147,6 +147,9 @@ def _tensors(B, H, T, seed, law_sigma=0.7, D=128):
     (1, 1, 90, 16, 16, 6),        # 16 per kv head: every column of the product in use
     (1, 3, 129, 9, 256, 4),       # 3 per kv head, one row past a tile
     (1, 2, 777, 14, 48, 8),       # 7 per kv head (the Qwen-2.5-7B grouping)
+    (1, 1, 150, 4, 700, 6),       # S past the matrix-core screen of the encode, not a power of two
+    (1, 1, 100, 2, 2048, 6),      # the two tables of a head past 64 KiB of LDS
+    (1, 1, 70, 16, 2730, 8),      # largest S with the largest merge buffer (16 query heads per kv head)
 ])
 def test_attend_small_oracle_encoded(B, H, T, Hq, S, b_r):
     """Identical bytes on both sides: encoded by the oracle, uploaded."""

@@ -70,7 +70,10 @@ def _lognormal_tensor(B, H, T, seed, sigma_g=0.5, D=128):
     (1, 2, 150, 96, 4),        # paper's s96_r4
     (2, 1, 90, 48, 4),         # paper's s48_r4
     (1, 1, 70, 256, 6),        # S of the headline workload
-    (1, 1, 40, 512, 8),        # largest supported S and b_r
+    (1, 1, 40, 512, 8),        # largest S that is screened on the matrix cores, largest b_r
+    (1, 2, 70, 600, 6),        # past it: every chunk scores all secondaries in fp32
+    (2, 1, 20, 2730, 8),       # largest supported S (24 S = 65520) and b_r: 24-bit code words
+    (1, 1, 300, 1024, 4),      # power of two above the screen's limit; 256-row workgroups
 ])
 def test_encode_decode_parity_small(B, H, T, S, b_r):
     print(f"case B={B} H={H} T={T} S={S} b_r={b_r}", flush=True)
@@ -236,6 +239,8 @@ def test_other_workloads_full_size(name, layer, role):
     (96, 1, 1, 2100, 256, 6),    # long, but the tables leave no room for 256-row workgroups: 8 waves, 64 rows
     (96, 1, 1, 70, 512, 8),      # largest S and b_r at 24 chunks per row
     (124, 1, 1, 70, 512, 8),     # the most LDS the general search can ask for
+    (96, 1, 2, 40, 700, 6),      # unscreened search at 24 chunks per row
+    (64, 1, 1, 30, 2730, 8),     # largest S at 16 chunks per row
     (64, 1, 2, 4100, 192, 4),    # 256-row workgroups at 16 chunks per row, ragged last workgroup
 ])
 def test_other_head_dimensions_small(D, B, H, T, S, b_r):
