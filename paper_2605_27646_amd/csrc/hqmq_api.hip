@@ -131,6 +131,12 @@ static Geometry make_geometry(const hqmq_params *p)
     g.check_finite = (p->flags & HQMQ_FLAG_CHECK_FINITE) ? 1 : 0;
     g.fused_by_head = 0;
     g.select_sampled = 0;
+    {
+        // the sampled select keeps the keys of a few bins around the median: about 2 % of a head's chunks
+        const uint64_t n_h = (uint64_t)p->B * p->T * g.n_c;
+        const uint64_t want = (n_h / 32 + 1023) / 1024 * 1024;
+        g.cand_cap = (int32_t)(want > (uint64_t)kCandCap ? want : (uint64_t)kCandCap);
+    }
     g.search_rows = search_rows_for(p->T, g.S16, g.A16, g.D, g.row_words);
     g.n_search_blocks_per_seg = (uint32_t)((p->T + g.search_rows - 1) / g.search_rows);
     return g;
@@ -156,7 +162,7 @@ static WorkspaceLayout workspace_layout(const Geometry &g)
     l.hist1 = take((uint64_t)g.H * kBins1 * sizeof(uint32_t));
     l.plan = take((uint64_t)g.H * sizeof(SelectPlan));
     l.cand_count = take((uint64_t)g.H * 3 * sizeof(uint32_t));
-    l.cand = take((uint64_t)g.H * kCandCap * sizeof(unsigned long long));
+    l.cand = take((uint64_t)g.H * g.cand_cap * sizeof(unsigned long long));
     l.block_sum = take(n_blocks * sizeof(uint32_t));
     l.block_pre = take(n_blocks * sizeof(uint32_t));
     l.aop = take((uint64_t)g.H * g.A16 * kATiles * 64 * 16);

@@ -27,7 +27,7 @@ constexpr int kBits1 = 10, kShift1 = 40, kBins1 = 1 << kBits1;  // bits 49..40
 constexpr int kFineShift = 46;                      // first digit of the single-tensor select: key >> 46 ...
 constexpr uint32_t kFineBase = (975u << 6) - 1u;    // ... minus this: 2^-48, the smallest square of an fp16 value, lands in bin 1
 constexpr int kSecShift = kFineShift - kBits1;      // its second digit: bits 45..36
-constexpr int kCandCap = 32768;      // candidate keys kept per head
+constexpr int kCandCap = 32768;      // candidate keys kept per head, at least (Geometry::cand_cap: more for very long heads)
 static_assert(kBins0 * sizeof(uint32_t) <= kCandCap * sizeof(unsigned long long),
               "the sample histogram borrows the candidate list's memory");
 constexpr int kSelectThreads = 1024; // workgroup of the select sweeps
@@ -73,6 +73,7 @@ struct Geometry {
     int32_t log2_S;       // log2(S) when S is a power of two, else -1
     float inv_S;          // (1/S)(1 + 2^-18): uint(float(k) * inv_S) == k / S for every k < 2^16, S <= 2730
     int32_t check_finite;  // HQMQ_FLAG_CHECK_FINITE: the search reports chunks holding an infinity or a NaN in the status word
+    int32_t cand_cap;     // candidate keys kept per head: kCandCap, or 1/32 of the head's chunks if that is more
     int32_t select_sampled;  // the median select predicts the median's bin from a sample of the rows (large heads only)
     int32_t fused_by_head;  // fused search only: one workgroup per head takes the rows of all batch entries (B T <= 64)
     int32_t search_rows;               // rows per search workgroup (kSearchRowsSmall or kSearchRowsLarge)
@@ -134,10 +135,10 @@ struct Workspace {
     uint32_t *hist_s;              // [H][kBins0] first digit of the sampled rows; shares the candidate list's memory (read
                                    // before the first candidate is written)
     SelectPlan *plan;              // [H]
-    uint32_t *cand_count;          // [3][H] keys sent to the candidate list (any may exceed kCandCap): by the sweep that
+    uint32_t *cand_count;          // [3][H] keys sent to the candidate list (any may exceed cand_cap): by the sweep that
                                    // collects one bin (or, in the sampled select, the predicted bins), by the sweep after
                                    // an overflow, by the sampled select's fallback sweep of one bin
-    unsigned long long *cand;      // [H][kCandCap]
+    unsigned long long *cand;      // [H][cand_cap]
     uint32_t *block_sum;           // [B*H*n_search_blocks_per_seg] outliers per search workgroup
     uint32_t *block_pre;           // same shape, exclusive prefix
     uint4 *aop;                    // [H][kATiles * S16][64] MFMA A operands of the search, built once per call

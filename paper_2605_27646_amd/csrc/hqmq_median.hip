@@ -172,7 +172,7 @@ __global__ __launch_bounds__(kSelectThreads) void k_select_sweep(Geometry g, Wor
     if ((MODE == 1 || MODE == 2) && g.select_sampled && !ws.plan[h].need)
         return;  // the candidates kept by MODE 0 hold the median's bin (uniform over the workgroup)
     uint32_t *const bin_count = bin_list_counter(g, ws, h);
-    if (MODE == 2 && *bin_count <= (uint32_t)kCandCap)
+    if (MODE == 2 && *bin_count <= (uint32_t)g.cand_cap)
         return;  // the list of MODE 1 holds every candidate (uniform over the workgroup)
     if (MODE == 1 || MODE == 2) {
         pick_bin<kBins0, kSelectThreads>(ws.hist0 + (size_t)h * kBins0, rank0, scratch, bin0, before0);
@@ -200,7 +200,7 @@ __global__ __launch_bounds__(kSelectThreads) void k_select_sweep(Geometry g, Wor
     const _Float16 *base = x + (int64_t)b * g.sb + (int64_t)h * g.sh;
     const int64_t row_stride = (int64_t)kStep * g.st;
     const bool active = kFull || c < g.n_c;
-    unsigned long long *cand = ws.cand + (size_t)h * kCandCap;
+    unsigned long long *cand = ws.cand + (size_t)h * g.cand_cap;
 
     for (int tb = t0; tb < t1; tb += 128) {  // uniform over the block
         half4_t v[4];
@@ -223,7 +223,7 @@ __global__ __launch_bounds__(kSelectThreads) void k_select_sweep(Geometry g, Wor
                             staged[pos] = key;
                         } else {
                             const uint32_t gpos = atomicAdd(&ws.cand_count[h], 1u);
-                            if (gpos < (uint32_t)kCandCap)
+                            if (gpos < (uint32_t)g.cand_cap)
                                 cand[gpos] = key;
                         }
                     }
@@ -236,7 +236,7 @@ __global__ __launch_bounds__(kSelectThreads) void k_select_sweep(Geometry g, Wor
                         staged[pos] = key;
                     } else {  // more than the stage holds (many equal norms): straight to the list
                         const uint32_t gpos = atomicAdd(bin_count, 1u);
-                        if (gpos < (uint32_t)kCandCap)
+                        if (gpos < (uint32_t)g.cand_cap)
                             cand[gpos] = key;
                     }
                 }
@@ -252,7 +252,7 @@ __global__ __launch_bounds__(kSelectThreads) void k_select_sweep(Geometry g, Wor
                     basepos = __shfl(basepos, leader, 64);
                     if (hit) {
                         const uint32_t pos = basepos + __popcll(m & ((1ull << (threadIdx.x & 63)) - 1ull));
-                        if (pos < (uint32_t)kCandCap)
+                        if (pos < (uint32_t)g.cand_cap)
                             cand[pos] = key;
                     }
                 }
@@ -278,7 +278,7 @@ __global__ __launch_bounds__(kSelectThreads) void k_select_sweep(Geometry g, Wor
         __syncthreads();
         const uint32_t at = list_base;
         for (uint32_t i = threadIdx.x; i < n; i += kSelectThreads)
-            if (at + i < (uint32_t)kCandCap)
+            if (at + i < (uint32_t)g.cand_cap)
                 cand[at + i] = staged[i];
     }
 }
@@ -322,7 +322,7 @@ __global__ __launch_bounds__(kSelectThreads) void k_select_decide(Geometry g, Wo
     uint32_t bin0, before0;
     pick_bin<kBins0, kSelectThreads>(ws.hist0 + (size_t)h * kBins0, rank0, scratch, bin0, before0);
     if (threadIdx.x == 0) {
-        const bool covered = bin0 - ws.plan[h].lo <= ws.plan[h].span && ws.cand_count[h] <= (uint32_t)kCandCap;
+        const bool covered = bin0 - ws.plan[h].lo <= ws.plan[h].span && ws.cand_count[h] <= (uint32_t)g.cand_cap;
         ws.plan[h].bin0 = bin0;
         ws.plan[h].before0 = before0;
         ws.plan[h].need = fine_bin_is_prefix(bin0) && !covered ? 1u : 0u;
@@ -364,7 +364,7 @@ __global__ __launch_bounds__(kSelectThreads) void k_select_finish(Geometry g, Wo
         // which the comparisons against the prefix below pass over
         const bool kept = g.select_sampled && !ws.plan[h].need;
         uint32_t n_cand = kept ? ws.cand_count[h] : *bin_list_counter(g, ws, h);
-        if (n_cand > (uint32_t)kCandCap) {
+        if (n_cand > (uint32_t)g.cand_cap) {
             uint32_t bin1, before1;
             pick_bin<kBins1, kSelectThreads>(ws.hist1 + (size_t)h * kBins1, rank, scratch, bin1, before1);
             rank -= before1;
@@ -372,8 +372,8 @@ __global__ __launch_bounds__(kSelectThreads) void k_select_finish(Geometry g, Wo
             low_bits = kSecShift;
             n_cand = ws.cand_count[g.H + h];
         }
-        const bool from_list = n_cand <= (uint32_t)kCandCap;
-        const unsigned long long *cand = ws.cand + (size_t)h * kCandCap;
+        const bool from_list = n_cand <= (uint32_t)g.cand_cap;
+        const unsigned long long *cand = ws.cand + (size_t)h * g.cand_cap;
 
         unsigned long long low = 0;  // low-part digits fixed so far, right aligned
         int remaining = low_bits;    // low-part bits still open
