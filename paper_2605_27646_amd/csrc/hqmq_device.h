@@ -101,6 +101,8 @@ constexpr size_t kLdsPerCu = 160 * 1024;
 // on every SIMD.
 inline int search_waves_for(int S16, int A16, int D, int row_words, int rows)
 {
+    if (A16 == 0)
+        return 4;  // the unscreened search has one shape
     if (rows >= kSearchRowsLarge && kLdsPerCu / search_lds_bytes(S16, A16, D, row_words, 4, rows) < 4 &&
         search_lds_bytes(S16, A16, D, row_words, 16, rows) <= kLdsPerCu)
         return 16;
@@ -113,6 +115,8 @@ inline int search_waves_for(int S16, int A16, int D, int row_words, int rows)
 // or 256 rows per CU, else 64 rows.
 inline int search_rows_for(int T, int S16, int A16, int D, int row_words)
 {
+    if (A16 == 0)
+        return kSearchRowsSmall;  // the unscreened search has one shape
     const auto four_fit = [&](int rows) { return kLdsPerCu / search_lds_bytes(S16, A16, D, row_words, 4, rows) >= 4; };
     if (T >= kSearchRowsSwitch && four_fit(kSearchRowsLarge))
         return kSearchRowsLarge;

@@ -268,7 +268,7 @@ constexpr float kScreenBand = 6.0e-6f;
 // waves return 0).  The merged triple is what one wave screening every group would have found, except when two
 // waves tie for the best score exactly; the runner-up then equals the best and the chunk takes the fp32 search,
 // as any tie between groups does.
-template <bool kCoop = false, int kWaves = 1>
+template <bool kCoop = false, int kWaves = 1, bool kScreen = true>
 __device__ __forceinline__ uint32_t search_codeword(const Geometry &g, int lane, const Direction u, bool flagged,
                                                     double r2, int rq, const uint4 *amat, const float *secl,
                                                     int wv = 0, float *merge = nullptr)
@@ -299,14 +299,14 @@ __device__ __forceinline__ uint32_t search_codeword(const Geometry &g, int lane,
         zero16[e] = 0.f;
     // groups this wave screens: those held as matrix operands (none beyond kScreenMaxS secondaries: the
     // screen is then skipped and every chunk takes the fp32 search below)
-    const int n_grp = g.A16;
+    const int n_grp = kScreen ? g.S16 : 0;
     const int per_wave = kCoop ? (n_grp + kWaves - 1) / kWaves : n_grp;
     const int grp_begin = kCoop ? min(wv * per_wave, n_grp) : 0;
     const int grp_end = kCoop ? min(grp_begin + per_wave, n_grp) : n_grp;
     const uint4 *arow = amat + lane;
     half8_t a0 = __builtin_bit_cast(half8_t, make_uint4(0u, 0u, 0u, 0u)), a1 = a0;
     float16_t ahead = zero16;
-    if (n_grp > 0) {  // uniform
+    if (kScreen) {
         a0 = __builtin_bit_cast(half8_t, arow[2 * min(grp_begin, n_grp - 1) * 64]);
         a1 = __builtin_bit_cast(half8_t, arow[2 * min(grp_begin, n_grp - 1) * 64 + 64]);
         // the product of (tile 0, chunk slot 0) of the next group is issued before the arithmetic on the last
@@ -406,14 +406,14 @@ __device__ __forceinline__ uint32_t search_codeword(const Geometry &g, int lane,
         }
     }
     const bool live = !flagged && r2 != 0.0;
-    const bool unclear = live && (n_grp == 0 || !(top - runner >= kScreenBand * top));
+    const bool unclear = live && (!kScreen || !(top - runner >= kScreenBand * top));
 
     // The 8 candidates first + 2 t in ascending order, strict comparison: the lowest s wins a tie.  Padding
     // secondaries (zeros, s >= S) score 0 and every real one scores at least |q_s| / sqrt(2) > 0 for a
     // non-zero chunk, so a group that won the screen never yields a padding index; the bound below only
     // keeps the index inside the codebook should the input break the contract (non-finite values).
     int bs = first;
-    if (live && n_grp > 0) {
+    if (live && kScreen) {
         const float *cq = secl + 4 * first;  // < 16 S16 entries: inside the padded table
         float bsc = -1.f;
         int bt = 0;
@@ -529,7 +529,7 @@ __global__ __launch_bounds__(kThreads) void k_prepare_operands(Geometry g, Works
 // supplied thresholds, extraction switched off): no kernel runs before this one, so it takes its thresholds
 // from the caller's array (+infinity without one), builds the head's operand table itself, and reports a
 // non-finite input through bit 31 of its workgroup total, which the list kernel turns into the status word.
-template <int kWaves, int kRows, bool kFused = false>
+template <int kWaves, int kRows, bool kFused = false, bool kScreen = true>
 __global__ __launch_bounds__(64 * kWaves, kFused ? 1 : 4) void k_search(Geometry g, WorkspaceOffsets wo, EncodeBatch batch)
 {
     constexpr int kThreadsS = 64 * kWaves;
@@ -540,7 +540,7 @@ __global__ __launch_bounds__(64 * kWaves, kFused ? 1 : 4) void k_search(Geometry
     const float *__restrict__ sec = tn.sec;
     extern __shared__ float smem[];
     uint4 *amat = reinterpret_cast<uint4 *>(smem);
-    float *secl = reinterpret_cast<float *>(amat + (size_t)g.A16 * kATiles * 64);
+    float *secl = reinterpret_cast<float *>(amat + (size_t)(kScreen ? g.S16 : 0) * kATiles * 64);
     uint32_t *pack = reinterpret_cast<uint32_t *>(secl + (size_t)g.S16 * 16 * 4);
     uint32_t *rcnt = pack + kWaves * 2 * 32;
 
@@ -586,14 +586,14 @@ __global__ __launch_bounds__(64 * kWaves, kFused ? 1 : 4) void k_search(Geometry
         *reinterpret_cast<float4_t *>(secl + 4 * s) = q;
     }
     if (kFused) {
-        for (int idx = tid; idx < g.A16 * kATiles * 64; idx += kThreadsS)
+        for (int idx = tid; idx < (kScreen ? g.S16 : 0) * kATiles * 64; idx += kThreadsS)
             amat[idx] = operand_entry(sec_h, g.S, idx);
         if (coop)  // the one pass writes the counters of rows 0 and 1 only
             for (int r = tid; r < kRows; r += kThreadsS)
                 rcnt[r] = 0;
     } else {
-        const uint4 *src = ws.aop + (size_t)h * g.A16 * kATiles * 64;
-        for (int idx = tid; idx < g.A16 * kATiles * 64; idx += kThreadsS)
+        const uint4 *src = ws.aop + (size_t)h * (kScreen ? g.S16 : 0) * kATiles * 64;
+        for (int idx = tid; idx < (kScreen ? g.S16 : 0) * kATiles * 64; idx += kThreadsS)
             amat[idx] = src[idx];
     }
 
@@ -655,7 +655,7 @@ __global__ __launch_bounds__(64 * kWaves, kFused ? 1 : 4) void k_search(Geometry
             if (wv != 0)
                 continue;  // wave 0 holds the result and writes the two rows
         } else {
-            code = search_codeword(g, lane, u, flagged, r2, rq, amat, secl);
+            code = search_codeword<false, 1, kScreen>(g, lane, u, flagged, r2, rq, amat, secl);
         }
 
         // ---- pack the row: chunk c at bits [c*w, (c+1)*w) -----------------------------------------
@@ -734,7 +734,7 @@ __global__ __launch_bounds__(64 * kWaves, kFused ? 1 : 4) void k_search(Geometry
 // Dynamic LDS: amat | secl as in k_search, then rowmax u64 [kRows] | fword u32 [kRows] |
 // sig u32 [kRows] | rcnt u32 [kRows] | pack u32 [kRows * row_words].
 // kFused: as in k_search.
-template <int kWaves, int kRows, bool kFused = false>
+template <int kWaves, int kRows, bool kFused = false, bool kScreen = true>
 __global__ __launch_bounds__(64 * kWaves) void k_search_flat(Geometry g, WorkspaceOffsets wo, EncodeBatch batch)
 {
     constexpr int kThreadsS = 64 * kWaves;
@@ -745,7 +745,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_search_flat(Geometry g, Workspa
     const _Float16 *__restrict__ x = tn.x;
     extern __shared__ float smem[];
     uint4 *amat = reinterpret_cast<uint4 *>(smem);
-    float *secl = reinterpret_cast<float *>(amat + (size_t)g.A16 * kATiles * 64);
+    float *secl = reinterpret_cast<float *>(amat + (size_t)(kScreen ? g.S16 : 0) * kATiles * 64);
     unsigned long long *rowmax = reinterpret_cast<unsigned long long *>(secl + (size_t)g.S16 * 16 * 4);
     uint32_t *fword = reinterpret_cast<uint32_t *>(rowmax + kRows);
     uint32_t *sig = fword + kRows;
@@ -770,11 +770,11 @@ __global__ __launch_bounds__(64 * kWaves) void k_search_flat(Geometry g, Workspa
         *reinterpret_cast<float4_t *>(secl + 4 * s) = q;
     }
     if (kFused) {
-        for (int idx = tid; idx < g.A16 * kATiles * 64; idx += kThreadsS)
+        for (int idx = tid; idx < (kScreen ? g.S16 : 0) * kATiles * 64; idx += kThreadsS)
             amat[idx] = operand_entry(sec_h, g.S, idx);
     } else {
-        const uint4 *src = ws.aop + (size_t)h * g.A16 * kATiles * 64;
-        for (int idx = tid; idx < g.A16 * kATiles * 64; idx += kThreadsS)
+        const uint4 *src = ws.aop + (size_t)h * (kScreen ? g.S16 : 0) * kATiles * 64;
+        for (int idx = tid; idx < (kScreen ? g.S16 : 0) * kATiles * 64; idx += kThreadsS)
             amat[idx] = src[idx];
     }
     for (int i = tid; i < kRows; i += kThreadsS) {
@@ -834,7 +834,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_search_flat(Geometry g, Workspa
         const float r_f = __builtin_amdgcn_sqrtf((float)r2);
         const int rq = radius_code(r2, r_f, sigma16, Lq);
         const Direction u = unit_direction(xv, r2, r_f);
-        const uint32_t code = search_codeword(g, lane, u, flagged || !valid, r2, rq, amat, secl);
+        const uint32_t code = search_codeword<false, 1, kScreen>(g, lane, u, flagged || !valid, r2, rq, amat, secl);
         if (code) {
             const uint32_t bitpos = (uint32_t)c * g.w;
             const uint32_t d0 = bitpos >> 5, sh = bitpos & 31;
@@ -880,7 +880,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_search_flat(Geometry g, Workspa
 // once per device, before any launch and outside any stream capture.
 hipError_t prepare_search_kernels()
 {
-    const void *variants[15] = {reinterpret_cast<const void *>(k_search<4, kSearchRowsSmall, true>),
+    const void *variants[17] = {reinterpret_cast<const void *>(k_search<4, kSearchRowsSmall, true>),
                                 reinterpret_cast<const void *>(k_search<8, kSearchRowsSmall, true>),
                                 reinterpret_cast<const void *>(k_search_flat<4, kSearchRowsSmall, true>),
                                 reinterpret_cast<const void *>(k_search_flat<8, kSearchRowsSmall, true>),
@@ -894,11 +894,13 @@ hipError_t prepare_search_kernels()
                                 reinterpret_cast<const void *>(k_search<16, kSearchRowsHuge>),
                                 reinterpret_cast<const void *>(k_search_flat<4, kSearchRowsSmall>),
                                 reinterpret_cast<const void *>(k_search_flat<4, kSearchRowsLarge>),
-                                reinterpret_cast<const void *>(k_search_flat<8, kSearchRowsSmall>)};
+                                reinterpret_cast<const void *>(k_search_flat<8, kSearchRowsSmall>),
+                                reinterpret_cast<const void *>(k_search<4, kSearchRowsSmall, false, false>),
+                                reinterpret_cast<const void *>(k_search_flat<4, kSearchRowsSmall, false, false>)};
     hipError_t err = hipSuccess;
     // the first four (the fused forms, only ever launched with 64 rows per workgroup) also hold static LDS (the
     // workgroup-wide OR, the merge buffer of the cooperative pass: up to 6 KiB), which counts against the same 160 KiB
-    for (int i = 0; i < 15 && err == hipSuccess; ++i)
+    for (int i = 0; i < 17 && err == hipSuccess; ++i)
         err = hipFuncSetAttribute(variants[i], hipFuncAttributeMaxDynamicSharedMemorySize,
                                   (int)kLdsPerCu - (i < 4 ? 8192 : 0));
     return err;
@@ -945,7 +947,13 @@ hipError_t launch_search(const Geometry &g, const WorkspaceOffsets &wo, const En
                            dim3(kThreads), 0, stream, g, wo, batch);
     const bool large = g.search_rows == kSearchRowsLarge;
 #define HQMQ_LAUNCH(KERNEL, W, R) hipLaunchKernelGGL((KERNEL<W, R>), grid, dim3(64 * W), lds, stream, g, wo, batch)
-    if (full) {
+    if (g.A16 == 0) {
+        // more secondaries than the matrix-core screen holds: 64 rows on 4 waves, every chunk scored in fp32
+        if (full)
+            hipLaunchKernelGGL((k_search<4, kSearchRowsSmall, false, false>), grid, dim3(256), lds, stream, g, wo, batch);
+        else
+            hipLaunchKernelGGL((k_search_flat<4, kSearchRowsSmall, false, false>), grid, dim3(256), lds, stream, g, wo, batch);
+    } else if (full) {
         if (g.search_rows == kSearchRowsHuge)  // only chosen together with 16 waves
             HQMQ_LAUNCH(k_search, 16, kSearchRowsHuge);
         else if (large && waves == 16)
