@@ -188,7 +188,7 @@ kernel                              waves   VALU/wave   MFMA/wave   SALU/wave   
             lines.append(f"{short(k):32s} {wv:8.0f} {c['SQ_INSTS_VALU'] / wv:11.1f} {c['SQ_INSTS_MFMA'] / wv:11.2f} "
                          f"{c['SQ_INSTS_SALU'] / wv:11.1f} {c['SQ_INSTS_LDS'] / wv:11.1f} {busy_us:16.1f} "
                          + (f"{t:24.1f} {busy_us / t:15.2f}" if t else ""))
-            m = re.search(r"(k_search(?:_flat)?)<(\d+), (\d+)(?:, \w+)?>", k)
+            m = re.search(r"(k_search(?:_flat)?)<(\d+), (\d+)(?:, \w+)*>", k)
             if m:
                 waves_wg, rows_wg = int(m.group(2)), int(m.group(3))
                 # passes of 64 chunks per wave: two rows of 32 chunks per pass in k_search; in k_search_flat the
