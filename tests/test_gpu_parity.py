@@ -497,6 +497,47 @@ def test_sampled_select_and_its_fallbacks():
     assert e.m2[3] == 0.0 and e.m2[2] == 4 * 0.75 ** 2
 
 
+@pytest.mark.parametrize("kind,D,B,H,T", [
+    ("plain", 128, 1, 2, 9000), ("ramp", 96, 2, 2, 4000), ("sampled rows small", 64, 1, 3, 12000),
+    ("sampled rows large", 128, 2, 1, 5000), ("narrow band", 96, 1, 2, 6000), ("half the rows zero", 128, 1, 2, 8200),
+    ("coarse values", 64, 2, 2, 7000),
+])
+def test_sampled_select_row_structures(kind, D, B, H, T):
+    """Heads of 2^17 chunks and more whose rows are not drawn from one distribution, in ways that mislead the
+    every-16th-row sample or overflow the candidate list: thresholds bit for bit, encode on sampled rows."""
+    gen = torch.Generator().manual_seed(len(kind) * 1000 + T)
+    x = torch.randn(B, H, T, D, generator=gen) * torch.exp(0.6 * torch.randn(B, H, T, 1, generator=gen))
+    t = torch.arange(T).view(1, 1, T, 1)
+    if kind == "ramp":
+        x = x * (0.2 + 3.0 * t / T)
+    elif kind == "sampled rows small":
+        x = x * torch.where(t % 16 == 0, 0.05, 1.0)
+    elif kind == "sampled rows large":
+        x = x * torch.where(t % 16 == 0, 30.0, 1.0)
+    elif kind == "narrow band":
+        x = (1.0 + 0.003 * torch.randn(B, H, T, D, generator=gen)) * torch.where(
+            torch.rand(B, H, T, D, generator=gen) < 0.5, -1.0, 1.0)
+    elif kind == "half the rows zero":
+        x = x * torch.where(t < T // 2, 0.0, 1.0)
+    elif kind == "coarse values":
+        x = torch.round(x * 2) / 2
+    x = x.half()
+    S = 1
+    sec_t, sec = _sec(4, H, S)
+    xb = _bits(x)
+    e = oracle.encode(xb, sec, rows=np.arange(0, B * H * T, 499))
+    x_dev, sec_dev = x.to(DEV), sec_t.to(DEV)
+    g = gpu_encode(x_dev, sec_dev)
+    print(compare_encode(g, e, xb, sec), flush=True)
+    params = hq.params_for(x_dev, S)
+    ws = hq.alloc_workspace(params, DEV)
+    hq.hqmq_encode(params, x_dev, sec_dev, hq.alloc_encoded(params, DEV), ws)
+    thr = hq.hqmq_thresholds(params, ws)
+    torch.cuda.synchronize()
+    c = float(np.float32(3.0))
+    assert np.array_equal(thr.cpu().numpy().view(np.uint64), ((c * c) * e.m2).view(np.uint64))
+
+
 def test_exact_tie_structured_input():
     """Chunks like (a, a, 0, 0) sit on the boundary between several codewords when the
     secondary is the identity; whichever the GPU picks must score as the oracle's best."""
