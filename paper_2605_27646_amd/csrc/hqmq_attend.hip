@@ -580,6 +580,14 @@ __global__ __launch_bounds__(kAttThreads) void k_attend_merge(AttendArgs a)
     const float2 *ml = reinterpret_cast<const float2 *>(a.part_ml) + head * n;
     const float *pa = a.part_acc + head * n * 128;
 
+    // the first four partial sums of this thread's dimension are requested before anything waits on the maxima
+    const int i = tid % kMergeDims, j = tid / kMergeDims;
+    float early[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int sp = j + u * kMergeWays;
+        early[u] = sp < n ? pa[(size_t)sp * 128 + d0 + i] : 0.f;
+    }
     float mx = kNegBig;
     for (int s = tid; s < n; s += kAttThreads)
         mx = fmaxf(mx, ml[s].x);
@@ -606,9 +614,14 @@ __global__ __launch_bounds__(kAttThreads) void k_attend_merge(AttendArgs a)
     __syncthreads();
     lsum = (red[0] + red[1]) + (red[2] + red[3]);
 
-    const int i = tid % kMergeDims, j = tid / kMergeDims;
     float o = 0.f;
-    int s = j;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int sp = j + u * kMergeWays;
+        if (sp < n)
+            o = fmaf(early[u], wts[sp], o);
+    }
+    int s = j + 4 * kMergeWays;
     for (; s + 3 * kMergeWays < n; s += 4 * kMergeWays) {  // four loads in flight
         const float v0 = pa[(size_t)s * 128 + d0 + i];
         const float v1 = pa[(size_t)(s + kMergeWays) * 128 + d0 + i];
