@@ -119,11 +119,12 @@ typedef struct hqmq_encoded {
     uint32_t *status;
 } hqmq_encoded;
 
-/* Per-device set-up for the CURRENT device (hipSetDevice): raises the dynamic-LDS limit of the search
- * kernels and looks up the device address of the workspace of hqmq_encode_static.  Thread-safe and idempotent.  Every encode entry point runs it by itself on its first call
- * on a device, so calling it is optional - except before a stream capture: the set-up is not stream
- * work and must not happen while a capture is open, so call hqmq_init() (or run one eager encode) on the
- * device first.  Errors: HIP. */
+/* Per-device set-up for the CURRENT device (hipSetDevice): raises the dynamic-LDS limit of the search and
+ * attention kernels and looks up the device address of the workspace of hqmq_encode_static.  Thread-safe
+ * and idempotent.  Every encode and attention entry point runs it by itself on its first call on a device,
+ * so calling it is optional - except before a stream capture: the set-up is not stream work and must not
+ * happen while a capture is open, so call hqmq_init() (or run one eager encode) on the device first.
+ * Errors: HIP. */
 int32_t hqmq_init(void);
 
 /* Secondary codebooks (App. D "Secondary codebook initialization"): for every (layer, role,
