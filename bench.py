@@ -72,6 +72,7 @@ def main() -> int:
     ap.add_argument("--workload", default="llama3_8b_32k")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-append", action="store_true", help="skip the appended-token extra")
     ap.add_argument("--q-heads-per-kv", type=int, default=4,
                     help="query heads per kv head of the fused-attention extra (0 = skip it)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096,
@@ -328,6 +329,34 @@ def main() -> int:
             "cached_tokens_per_s": wl.B * wl.T / (us_layer * 1e-6),
             "packed_bytes_per_layer": packed, "packed_GBs": packed / (us_layer * 1e-6) / 1e9,
             "fp16_cache_bytes_per_layer": 2 * info.n_rows * wl.D * 2}
+
+    # ---- extra, outside the timed step: the encode of one generation step's appended tokens (one new token
+    # per sequence: a [B, H, 1, D] tensor per layer and role, thresholds as the long tensors' encode left them)
+    if not args.no_append:
+        T_new = 1
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(4321)
+        ax = [torch.randn(wl.B, wl.H, T_new, wl.D, device=dev, generator=gen).to(torch.float16) for _ in range(n_t)]
+        ap_ = hq.params_for(ax[0], wl.S, wl.b_r, wl.C)
+        aenc = [hq.alloc_encoded(ap_, dev, outlier_capacity=wl.B * wl.H * T_new * ((wl.D + 3) // 4)) for _ in range(n_t)]
+        athr = [torch.full((wl.H,), 30.0, dtype=torch.float64, device=dev) for _ in range(n_t)]   # 9 x the median of a chi-square with 4 degrees of freedom
+        abatch = hq.EncodeBatch(ap_, ax, [sec_all[i // 2, i % 2] for i in range(n_t)], aenc,
+                                hq.alloc_batch_workspace(ap_, n_t, dev))
+        athr = hq.ThresholdBatch(abatch, athr)
+        for _ in range(3):
+            hq.hqmq_encode_batch_given_thresholds(abatch, athr)
+        torch.cuda.synchronize()
+        ea, eb = new_events(2)
+        reps = 50
+        ea.record()
+        for _ in range(reps):
+            hq.hqmq_encode_batch_given_thresholds(abatch, athr)
+        eb.record()
+        torch.cuda.synchronize()
+        result["append"] = {
+            "what": "hqmq_encode_batch with supplied thresholds of one new token per sequence for every layer and role",
+            "tensors": n_t, "shape": [wl.B, wl.H, T_new, wl.D], "us_per_step": ea.elapsed_time(eb) * 1e3 / reps,
+            "outliers": int(sum(int(e.n_outliers[-1]) for e in aenc))}
 
     if args.stream_ceiling:
         n = 1 << 30                                     # 2 GiB of fp16: the bytes one 32-tensor decode launch writes

@@ -8,11 +8,11 @@
     rocprofv3 --kernel-trace --stats --output-format csv -d <raw_dir> -o trace -- \
         python3 <repo>/bench.py --workload W --steps 3 --warmup 1 --no-cpu-baseline
     rocprofv3 --pmc FETCH_SIZE --output-format csv -d <raw_dir> -o fetch -- \
-        python3 <repo>/bench.py --workload W --steps 1 --warmup 0 --layers 2 --no-cpu-baseline --calibrate-copy
+        python3 <repo>/bench.py --workload W --steps 1 --warmup 0 --layers 2 --no-cpu-baseline --no-append --calibrate-copy
     rocprofv3 --pmc WRITE_SIZE --output-format csv -d <raw_dir> -o write -- (the same bench.py arguments)
     rocprofv3 --pmc SQ_WAVES SQ_INSTS_VALU SQ_INSTS_MFMA SQ_ACTIVE_INST_VALU SQ_BUSY_CYCLES SQ_WAVE_CYCLES \
         SQ_INSTS_SALU SQ_INSTS_LDS --output-format csv -d <raw_dir> -o insts -- \
-        python3 <repo>/bench.py --workload W --steps 1 --warmup 0 --layers 1 --no-cpu-baseline --q-heads-per-kv 0
+        python3 <repo>/bench.py --workload W --steps 1 --warmup 0 --layers 1 --no-cpu-baseline --no-append --q-heads-per-kv 0
 
 Writes profiles/hot_path_kernels_W.txt, profiles/hbm_traffic_W.txt and profiles/instruction_counters_W.txt.  The
 lines `figure <kernel> <name> <value>` at the end of the last two are what bench.py reads back for the
@@ -67,7 +67,9 @@ def main(raw: str, wl: str) -> None:
 {shape} fp16 each, S = {cfg['S']}, b_r = {cfg['b_r']}, C = {cfg['C']:g}), MI355X, 4 steps (1 warm-up + 3 timed) of {nt} tensors.
 A step is {groups} hqmq_encode_batch call(s) and one hqmq_decode_batch call; every kernel launch covers {per_launch:g} tensors
 (blockIdx.z = tensor).""" + ("""  After the timed steps bench.py runs its fused-attention extra (6 passes of one
-hqmq_attend per layer, 4 query heads per kv head).""" if has_att else "") + f"""
+hqmq_attend per layer, 4 query heads per kv head).""" if has_att else "") + ("""  Then its appended-token extra: 53 encodes of the
+one-token tensors of a generation step with supplied thresholds (the fused search kernel `k_search<.., true, ..>` or
+`k_search_flat<.., true, ..>` and `k_list_small`, two launches of 32 tensors each per encode).""" if "append" in d else "") + f"""
 
 command (run from /tmp with TMPDIR=/tmp):
   rocprofv3 --kernel-trace --stats --output-format csv -d <out> -o trace -- python3 bench.py --workload {wl} --steps 3 --warmup 1 --no-cpu-baseline
@@ -98,6 +100,10 @@ bench.py line of the same build (python bench.py --workload {wl}; {d['warmup']} 
         out.append(f"  fused attention extra: {at['us_per_layer']:.1f} us per layer (k_attend_partial + k_attend_merge) for {cfg['T']} cached "
                    f"tokens x {cfg['kv_heads'] * at['q_heads_per_kv_head']} query heads, reading {at['packed_bytes_per_layer'] / 1e6:.1f} MB of "
                    f"packed K and V (fp16 cache: {at['fp16_cache_bytes_per_layer'] / 1e6:.1f} MB)")
+    if "append" in d:
+        apd = d["append"]
+        out.append(f"  appended-token extra: {apd['us_per_step']:.1f} us for the {apd['tensors']} tensors {apd['shape']} of one generation step "
+                   f"(hqmq_encode_batch with supplied thresholds: the fused search kernel and k_list_small, one launch each per 32 tensors)")
     if "cpu_baseline" in d:
         cb = d["cpu_baseline"]
         out.append(f"  cpu_baseline (the oracle, {cb['cores']} threads, {cb['sample']}): {cb['value']:.3e} elems/s; "
@@ -128,8 +134,8 @@ its own and scaled by what the same counter reads for a plain copy of known size
 every encode / decode kernel is ONE launch over the 4 tensors""" + ("; the attention kernels run once per layer." if has_att else ".") + f"""
 
 commands (run from /tmp with TMPDIR=/tmp):
-  rocprofv3 --pmc FETCH_SIZE --output-format csv -d <out> -o fetch -- python3 bench.py --workload {wl} --steps 1 --warmup 0 --layers 2 --no-cpu-baseline --calibrate-copy
-  rocprofv3 --pmc WRITE_SIZE --output-format csv -d <out> -o write -- python3 bench.py --workload {wl} --steps 1 --warmup 0 --layers 2 --no-cpu-baseline --calibrate-copy
+  rocprofv3 --pmc FETCH_SIZE --output-format csv -d <out> -o fetch -- python3 bench.py --workload {wl} --steps 1 --warmup 0 --layers 2 --no-cpu-baseline --no-append --calibrate-copy
+  rocprofv3 --pmc WRITE_SIZE --output-format csv -d <out> -o write -- python3 bench.py --workload {wl} --steps 1 --warmup 0 --layers 2 --no-cpu-baseline --no-append --calibrate-copy
 
 calibration copy: FETCH_SIZE reads {cal_f:.1f} KiB for {tensor_kib:g} KiB  -> factor {ff:.3f};  WRITE_SIZE reads {cal_w:.1f} KiB -> factor {fw:.3f}
 
@@ -174,7 +180,7 @@ were spread evenly; "launch" is the kernel's average duration in the kernel trac
 scaled to the 2 tensors of this run.
 
 command (run from /tmp with TMPDIR=/tmp):
-  rocprofv3 --pmc SQ_WAVES SQ_INSTS_VALU SQ_INSTS_MFMA SQ_ACTIVE_INST_VALU SQ_BUSY_CYCLES SQ_WAVE_CYCLES SQ_INSTS_SALU SQ_INSTS_LDS --output-format csv -d <out> -o insts -- python3 bench.py --workload {wl} --steps 1 --warmup 0 --layers 1 --no-cpu-baseline --q-heads-per-kv 0
+  rocprofv3 --pmc SQ_WAVES SQ_INSTS_VALU SQ_INSTS_MFMA SQ_ACTIVE_INST_VALU SQ_BUSY_CYCLES SQ_WAVE_CYCLES SQ_INSTS_SALU SQ_INSTS_LDS --output-format csv -d <out> -o insts -- python3 bench.py --workload {wl} --steps 1 --warmup 0 --layers 1 --no-cpu-baseline --no-append --q-heads-per-kv 0
 
 kernel                              waves   VALU/wave   MFMA/wave   SALU/wave    LDS/wave   VALU busy (us)   launch (us, 2 tensors)   busy / launch"""]
         trace_us = {short(r["Name"]): float(r["AverageNs"]) / 1e3 / per_launch * 2 for r in rows}
