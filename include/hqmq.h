@@ -60,6 +60,12 @@ extern "C" {
                                      (the encoded result of such a tensor is undefined, but every access stays  \
                                      in bounds and every index inside the codebook) */
 
+#define HQMQ_FLAG_ATTEND_TABLES 4u /* hqmq_attend*: read the reconstruction from per-head tables of codeword      \
+                                      directions in LDS whenever they fit (S <= 256 or so), not only for long     \
+                                      caches, where the library does so by itself; same results up to the last     \
+                                      fp32 bit before the fp16 rounding of an element; the other entry points      \
+                                      ignore it */
+
 /* bits of the device-side status word */
 #define HQMQ_STATUS_OUTLIER_OVERFLOW 1u /* more outliers than outlier_capacity: payload truncated */
 #define HQMQ_STATUS_NONFINITE 2u        /* HQMQ_FLAG_CHECK_FINITE was set and x holds an infinity or a NaN */

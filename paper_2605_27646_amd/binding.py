@@ -15,6 +15,7 @@ _LIB_PATH = os.path.join(_HERE, "libhqmq.so")
 HQMQ_OK = 0
 HQMQ_FLAG_NO_OUTLIERS = 1
 HQMQ_FLAG_CHECK_FINITE = 2
+HQMQ_FLAG_ATTEND_TABLES = 4
 HQMQ_STATUS_OUTLIER_OVERFLOW = 1
 HQMQ_STATUS_NONFINITE = 2
 HQMQ_MAX_S = 2730

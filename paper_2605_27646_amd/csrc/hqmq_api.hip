@@ -599,7 +599,8 @@ extern "C" uint64_t hqmq_attend_workspace_bytes(const hqmq_params *params, int32
 {
     if (check_attend(params, n_q_heads) != HQMQ_OK)
         return 0;
-    return plan_attend(make_geometry(params), n_q_heads / params->H).total_bytes;
+    return plan_attend(make_geometry(params), n_q_heads / params->H, (params->flags & HQMQ_FLAG_ATTEND_TABLES) != 0)
+        .total_bytes;
 }
 
 static int32_t attend_impl(const hqmq_params *params, int32_t n_q_heads, const void *q_dev,
@@ -623,7 +624,7 @@ static int32_t attend_impl(const hqmq_params *params, int32_t n_q_heads, const v
         return rc;
     const Geometry g = make_geometry(params);
     const int G = n_q_heads / params->H;
-    const AttendPlan plan = plan_attend(g, G);
+    const AttendPlan plan = plan_attend(g, G, (params->flags & HQMQ_FLAG_ATTEND_TABLES) != 0);
     if (workspace_bytes < plan.total_bytes)
         return HQMQ_ERR_BUFFER_TOO_SMALL;
     {  // the kernels may ask for more LDS than a launch gets by default (large S)
@@ -657,6 +658,7 @@ static int32_t attend_impl(const hqmq_params *params, int32_t n_q_heads, const v
     a.D = params->D;
     a.n_splits = plan.n_splits;
     a.rows_per_split = plan.rows_per_split;
+    a.joint = plan.joint;
     hipError_t err = launch_attend(g, a, static_cast<hipStream_t>(stream));
     if (err != hipSuccess)
         return hip_failed(err);

@@ -235,14 +235,17 @@ struct AttendArgs {
     int32_t G;             // query heads per kv head
     int32_t D;             // head dimension: 64, 96 or 128 (q and out rows; the partial sums keep a pitch of 128)
     int32_t n_splits;      // workgroups along the sequence
-    int32_t rows_per_split;  // multiple of kAttendTile
+    int32_t rows_per_split;  // multiple of kAttendTile (of the table form's tile of 128 rows when joint)
+    int32_t joint;           // the form that reads the reconstruction from half tables in LDS
 };
 // Split of the sequence over workgroups: enough of them to fill the chip, at least one tile each.
 struct AttendPlan {
     int32_t n_splits, rows_per_split;
+    int32_t joint;
     uint64_t ml_bytes, acc_bytes, total_bytes;
 };
-AttendPlan plan_attend(const Geometry &g, int G);
+// tables_always: take the table form whenever its tables fit, whatever the size of the cache.
+AttendPlan plan_attend(const Geometry &g, int G, bool tables_always);
 
 // ---- device helpers --------------------------------------------------------------------
 

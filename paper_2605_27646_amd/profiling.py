@@ -97,7 +97,7 @@ bench.py line of the same build (python bench.py --workload {wl}; {d['warmup']} 
   outlier fraction {d['outlier_fraction']:.4f}, stored bits per element {d['bits_per_element_stored']:.3f}""")
     if has_att:
         at = d["attend"]
-        out.append(f"  fused attention extra: {at['us_per_layer']:.1f} us per layer (k_attend_partial + k_attend_merge) for {cfg['T']} cached "
+        out.append(f"  fused attention extra: {at['us_per_layer']:.1f} us per layer (k_attend_joint or k_attend_partial, then k_attend_merge) for {cfg['T']} cached "
                    f"tokens x {cfg['kv_heads'] * at['q_heads_per_kv_head']} query heads, reading {at['packed_bytes_per_layer'] / 1e6:.1f} MB of "
                    f"packed K and V (fp16 cache: {at['fp16_cache_bytes_per_layer'] / 1e6:.1f} MB)")
     if "append" in d:
@@ -160,9 +160,10 @@ algorithmic bytes for comparison, per tensor: the search kernel reads the tensor
 head dimensions other than 128 reads it twice, the second time from L2) and writes codes, flags, scales and offsets,
 {chunks * (info_w - 8 * d['outlier_fraction']) / 1e6:.1f} MB; the decode kernel reads {chunks * info_w / 1e6:.1f} MB (codes, flags, scales, offsets, payload) and writes {x_mb:.1f} MB.
 measured per tensor: search {s[0] + s[1]:.1f} MB ({s[0]:.1f} read + {s[1]:.1f} written); decode {dk[0] + dk[1]:.1f} MB ({dk[0]:.1f} read + {dk[1]:.1f} written).""")
-        if has_att and "k_attend_partial" in per:
-            ak = per["k_attend_partial"]
-            lines.append(f"k_attend_partial {ak[0]:.1f} MB read + {ak[1]:.1f} MB written per layer (algorithmic: the packed K and V of a layer, "
+        akey = "k_attend_joint" if "k_attend_joint" in per else "k_attend_partial"
+        if has_att and akey in per:
+            ak = per[akey]
+            lines.append(f"{akey} {ak[0]:.1f} MB read + {ak[1]:.1f} MB written per layer (algorithmic: the packed K and V of a layer, "
                          f"{d['attend']['packed_bytes_per_layer'] / 1e6:.1f} MB).")
         lines.append("\nfigures read back by bench.py (bytes per tensor, read + written):")
         lines.append(f"figure {skey} traffic_bytes_per_tensor {(s[0] + s[1]) * 1e6:.0f}")

@@ -26,6 +26,23 @@ DEV = "cuda:0"
 ATT_TOL = 1e-4
 
 
+@pytest.fixture(params=["form_by_size", "form_with_tables"], autouse=True)
+def attend_form(request, monkeypatch):
+    """Every test of this file runs twice: with the form of the attention that the library picks by the size
+    of the cache, and with the form that reads the reconstruction from per-head tables in LDS asked for through
+    HQMQ_FLAG_ATTEND_TABLES (taken whenever the tables fit).  Same bound for both."""
+    if request.param == "form_with_tables":
+        def flagged(fn):
+            def call(params, *args, **kwargs):
+                p = hq.HqmqParams.from_buffer_copy(params)
+                p.flags |= hq.HQMQ_FLAG_ATTEND_TABLES
+                return fn(p, *args, **kwargs)
+            return call
+        for name in ("hqmq_attend", "hqmq_attend_lse", "hqmq_attend_masked", "hqmq_attend_workspace_bytes"):
+            monkeypatch.setattr(hq, name, flagged(getattr(hq, name)))
+    return request.param
+
+
 def _bits(x: torch.Tensor) -> np.ndarray:
     return x.contiguous().cpu().numpy().view(np.uint16)
 
