@@ -63,7 +63,8 @@ extern "C" {
 #define HQMQ_FLAG_ATTEND_TABLES 4u /* hqmq_attend*: read the reconstruction from per-head tables of codeword      \
                                       directions in LDS whenever they fit (S <= 256 or so), not only for long     \
                                       caches, where the library does so by itself; same results up to the last     \
-                                      fp32 bit before the fp16 rounding of an element; the other entry points      \
+                                      fp32 bit before the fp16 rounding of an element; ask                         \
+                                      hqmq_attend_workspace_bytes with the same flags; the other entry points      \
                                       ignore it */
 
 /* bits of the device-side status word */
